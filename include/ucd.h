@@ -1,0 +1,191 @@
+/*
+ * ucd -- micro-batched convolution for MI355X (gfx950).
+ *
+ * C-ABI boundary of the library.  The method is the one of arXiv 1804.04806
+ * ("mu-cuDNN"): a convolution layer's Forward, BackwardData and BackwardFilter
+ * are executed as a sequence of micro-batches (Section 2), each micro-batch
+ * running one of several equivalent algorithms with different workspace needs,
+ * and a planner picks the division and the per-micro-batch algorithm that
+ * minimise measured time under a workspace limit (Section 3).
+ *
+ * Conventions for every entry point
+ *   - Tensors are dense fp32 in DEVICE memory: X (N,C,H,W), filter W (K,C,R,S)
+ *     with R the filter height and S its width, Y (N,K,P,Q) with
+ *     P = floor((H + 2*pad_h - R)/stride_h) + 1 and Q likewise (Section 2 gives
+ *     the NCHW / KCVU shapes; stride and zero padding are this library's
+ *     reading, the operation is cross-correlation: no filter flip).
+ *   - The caller owns every device buffer (tensors and workspace) and the
+ *     stream.  The library allocates no device memory.  `stream` is a
+ *     hipStream_t passed as void* (NULL = the default stream).
+ *   - ucd_conv_* only enqueue work on `stream`; they never synchronise it.
+ *     ucd_plan / ucd_plan_wd synchronise it to read event timings.
+ *   - Return value: UCD_OK (0) or a negative ucd_status_t.  On failure no
+ *     kernel has been launched by that call and *out arguments are untouched.
+ *     Nothing throws or aborts across this boundary.
+ *   - Host arrays (descriptors, tables, micro-configuration lists) are read
+ *     during the call only.
+ */
+#ifndef UCD_H
+#define UCD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    UCD_OK = 0,
+    UCD_E_INVALID = -1,      /* bad descriptor, enum value, size or micro-batch list */
+    UCD_E_NULLPTR = -2,      /* a required pointer is NULL */
+    UCD_E_UNSUPPORTED = -3,  /* algorithm does not apply to this layer / dtype not built */
+    UCD_E_WS_TOO_SMALL = -4, /* workspace given is smaller than the plan needs */
+    UCD_E_HIP = -5,          /* a HIP runtime call failed */
+    UCD_E_NOMEM = -6,        /* host allocation failed */
+    UCD_E_INFEASIBLE = -7    /* no configuration satisfies the limits */
+} ucd_status_t;
+
+/* dtype: 0 = fp32 (the only one built).  Layout NCHW / KCRS, dense, groups = 1, dilation = 1. */
+typedef struct {
+    int32_t N, C, H, W, K, R, S, stride_h, stride_w, pad_h, pad_w, dtype;
+} ucd_layer_t;
+
+/* The three operations of Section 2. */
+enum { UCD_FWD = 0, UCD_BWD_DATA = 1, UCD_BWD_FILTER = 2, UCD_N_OP = 3 };
+
+/* Equivalent algorithms, differing in workspace need (the role cuDNN's algorithm list plays
+ * in Section 1): implicit GEMM (no workspace), im2col into workspace + GEMM, Winograd F(2x2,3x3)
+ * with transform buffers in workspace (3x3 stride-1 Forward/BackwardData only). */
+enum { UCD_ALGO_IMPLICIT = 0, UCD_ALGO_IM2COL = 1, UCD_ALGO_WINOGRAD = 2, UCD_N_ALGO = 3 };
+
+/* Batch-size policies of Section 3.4: which micro-batch sizes get benchmarked. */
+enum { UCD_POLICY_UNDIVIDED = 0, UCD_POLICY_POW2 = 1, UCD_POLICY_ALL = 2 };
+
+/* A micro-configuration (Section 3.1): algorithm and micro-batch size. */
+typedef struct { int32_t algo, batch; } ucd_micro_t;
+
+/* A configuration: ordered list of micro-configurations, plus the layer and operation it is
+ * for.  Opaque, host memory owned by the library, freed by ucd_plan_destroy. */
+typedef struct ucd_plan ucd_plan_t;
+
+#define UCD_TIME_INF UINT64_MAX  /* "not benchmarked / does not apply" in timing tables */
+#define UCD_WS_NA SIZE_MAX       /* "algorithm does not apply" in workspace tables */
+
+const char *ucd_strerror(int status);
+int ucd_version(void);
+
+/* Bytes of workspace algorithm `algo` needs for operation `op` at micro-batch size b (the
+ * quantity compared with the limit M in step 1 of the WR algorithm, Section 3.2).
+ * Returns UCD_WS_NA if the algorithm does not apply or an argument is invalid.  Host only. */
+size_t ucd_workspace_size(const ucd_layer_t *layer, int op, int algo, int b);
+
+/* ---- planners on a given timing table (pure host, no GPU needed) ------------------------- */
+
+/* WR planner (Section 3.2, steps 2-3): T(b) = min over b_mu of T_mu(b_mu) + T(b - b_mu), T(0)=0,
+ * where T_mu(b) is the least t_ns[a][b] over algorithms a with ws[a][b] <= ws_limit, restricted
+ * to the micro-batch sizes the policy allows.
+ *   t_ns, ws : row-major [n_algo][B+1], column 0 unused; UCD_TIME_INF / UCD_WS_NA mark holes.
+ * On success *out is a plan with no layer attached (query only, cannot be executed).
+ * Ties: the largest first micro-batch, then the lowest algorithm id.  UCD_E_INFEASIBLE if no
+ * division of B is feasible. */
+int ucd_plan_from_table(int B, size_t ws_limit, int policy, int n_algo,
+                        const uint64_t *t_ns, const size_t *ws, ucd_plan_t **out);
+
+/* Desirable configuration set C(B) of Section 3.3: the set-valued variant of the WR programme,
+ * pruned at every b to the Pareto front in (time, workspace), where a configuration's time is
+ * the sum and its workspace the maximum over its micro-configurations.  Writes up to `cap`
+ * points, sorted by increasing workspace (hence decreasing time), to front_t / front_ws and
+ * the number found to *n (which may exceed cap: call again with a bigger cap). */
+int ucd_desirable_from_table(int B, size_t ws_limit, int policy, int n_algo,
+                             const uint64_t *t_ns, const size_t *ws,
+                             uint64_t *front_t, size_t *front_ws, int cap, int *n);
+
+/* WD 0-1 programme (Section 3.3, Eq. 1-4) over given desirable sets: choose one point per
+ * kernel, sum of workspaces <= budget, least sum of times.  Points of kernel k are
+ * front_t/front_ws[offset_k .. offset_k + front_n[k]), offsets being the running sum of front_n.
+ * Exact.  choice[k] receives the chosen index within kernel k, *total_t the optimum. */
+int ucd_wd_solve(int n_kernels, const int *front_n, const uint64_t *front_t,
+                 const size_t *front_ws, size_t budget, int *choice, uint64_t *total_t);
+
+/* WD planner on given tables: kernel k has mini-batch B[k] and tables at t_ns/ws + tab_off[k]
+ * (each [n_algo][B[k]+1]).  Builds every desirable set, solves the programme, and returns one
+ * layer-less plan per kernel in plans[k] and its segment offset (bytes, 256-aligned running
+ * sum in kernel order) in ws_offsets[k].  Segment sizes are rounded up to 256 bytes before
+ * they are summed against total_ws. */
+int ucd_plan_wd_from_tables(int n_kernels, const int *B, int n_algo, const size_t *tab_off,
+                            const uint64_t *t_ns, const size_t *ws, size_t total_ws, int policy,
+                            ucd_plan_t **plans, size_t *ws_offsets);
+
+/* ---- plans ------------------------------------------------------------------------------ */
+
+/* A forced configuration (for tests and for undivided baselines): micro[0..n) must have positive
+ * sizes summing to layer->N and algorithms that apply to (layer, op). */
+int ucd_plan_fixed(const ucd_layer_t *layer, int op, const ucd_micro_t *micro, int n,
+                   ucd_plan_t **out);
+
+/* Reads a plan: copies up to cap micro-configurations to `micro` (may be NULL if cap == 0),
+ * their count to *n, the planner's predicted cost (sum of table times; 0 for fixed plans) to
+ * *cost_ns and the workspace the plan needs (largest over its parts) to *ws_bytes.
+ * Any out pointer may be NULL. */
+int ucd_plan_query(const ucd_plan_t *plan, ucd_micro_t *micro, int cap, int *n,
+                   uint64_t *cost_ns, size_t *ws_bytes);
+
+void ucd_plan_destroy(ucd_plan_t *plan);
+
+/* ---- on-device benchmark + WR plan (Section 3.2, steps 1-3) --------------------------------
+ * Times every algorithm that applies and fits ws_limit at every micro-batch size the policy
+ * allows, on the caller's buffers, keeps the timings in a process-wide cache keyed by
+ * (layer shape without N, op, algo, b) so that identical layers are timed once (Section 3.4),
+ * then runs the WR programme on that table.
+ *   x  : device, N*C*H*W floats      y : device, N*K*P*Q floats      w : device, K*C*R*S floats
+ *   ws : device, at least ws_limit bytes (may be NULL when ws_limit == 0)
+ * The operation's output buffer is clobbered (FWD: y, BWD_DATA: x, BWD_FILTER: w); the other
+ * two are only read.  Each timing is the minimum of `3` runs after one warm-up, in integer ns. */
+int ucd_plan(const ucd_layer_t *layer, int op, size_t ws_limit, int policy,
+             void *x, void *w, void *y, void *ws, void *stream, ucd_plan_t **out);
+
+/* WD planner on the device (Section 3.3): benchmarks like ucd_plan (limit = total_ws) for each
+ * of the n_kernels (layers[k], ops[k]) kernels, using the same scratch tensors for all of them
+ * (each must be large enough for the largest layer; capacities in bytes are checked), then
+ * builds desirable sets and solves the 0-1 programme.  plans[k] are executable; kernel k must
+ * be run with workspace pointer ws_base + ws_offsets[k]. */
+int ucd_plan_wd(const ucd_layer_t *layers, const int *ops, int n_kernels, size_t total_ws,
+                int policy, void *x, size_t x_cap, void *w, size_t w_cap, void *y, size_t y_cap,
+                void *ws, void *stream, ucd_plan_t **plans, size_t *ws_offsets);
+
+/* Copies the cached timings of (layer, op) into t_ns[algo*(cap_b+1) + b] and the workspace
+ * formula into ws[...] for b = 1..cap_b; entries never timed are UCD_TIME_INF.  Host only. */
+int ucd_bench_table(const ucd_layer_t *layer, int op, uint64_t *t_ns, size_t *ws, int cap_b);
+
+/* Forgets every cached timing. */
+void ucd_bench_clear(void);
+
+/* ---- execution (Section 2: micro-batches run one after another on one stream, sharing one
+ * workspace; sample n of a micro-batch starting at offset o is sample o+n of the tensors) --- */
+
+/* y = conv(x, w).  Overwrites y. */
+int ucd_conv_fwd(const ucd_plan_t *plan, const void *x, const void *w, void *y,
+                 void *ws, size_t ws_bytes, void *stream);
+
+/* dx = adjoint of Forward with respect to x, applied to dy.  Overwrites all of dx (input pixels
+ * no filter tap reaches become 0). */
+int ucd_conv_bwd_data(const ucd_plan_t *plan, const void *dy, const void *w, void *dx,
+                      void *ws, size_t ws_bytes, void *stream);
+
+/* dw = beta * dw + sum over samples, beta in {0, 1}; beta = 0 ignores dw's old contents.
+ * The first micro-batch uses the caller's beta, later ones accumulate with output scale 1. */
+int ucd_conv_bwd_filter(const ucd_plan_t *plan, const void *x, const void *dy, void *dw,
+                        float beta, void *ws, size_t ws_bytes, void *stream);
+
+/* Runs a single algorithm on one micro-batch of b samples starting at the given pointers
+ * (already offset), bypassing plans: the unit the benchmark step times.  `a`, `bsrc`, `out`
+ * are (x, w, y) for FWD, (dy, w, dx) for BWD_DATA, (x, dy, dw) for BWD_FILTER. */
+int ucd_run_micro(const ucd_layer_t *layer, int op, int algo, int b, const void *a,
+                  const void *bsrc, void *out, float beta, void *ws, size_t ws_bytes,
+                  void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* UCD_H */

@@ -89,10 +89,12 @@ def micro_best(t, ws, b, M):
 def wr_optimum(B, M, policy, t, ws):
     """Least total time over every division of B (WR problem). INF if none is feasible."""
     best = INF
-    for parts in partitions(B, policy_sizes(B, policy)):
+    sizes = policy_sizes(B, policy)
+    t_mu = {b: micro_best(t, ws, b, M) for b in sizes}
+    for parts in partitions(B, sizes):
         total = 0
         for b in parts:
-            c = micro_best(t, ws, b, M)
+            c = t_mu[b]
             if c == INF:
                 total = INF
                 break

@@ -1,0 +1,534 @@
+// C-ABI of the library: validation, plan objects, the micro-batch executor, the on-device
+// benchmark cache and the glue to the host planners.  See include/ucd.h for the contract.
+#include "ucd.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <map>
+#include <mutex>
+#include <new>
+#include <tuple>
+#include <vector>
+
+#include "kernels.h"
+#include "planner.h"
+
+using namespace ucd;
+
+struct ucd_plan {
+    bool has_layer = false;
+    ucd_layer_t layer{};
+    int op = 0;
+    std::vector<Micro> micro;
+    uint64_t cost_ns = 0;
+    size_t ws_bytes = 0;
+};
+
+namespace {
+
+constexpr int kTimedRuns = 3;
+
+bool layer_ok(const ucd_layer_t *L)
+{
+    if (L->N < 1 || L->C < 1 || L->H < 1 || L->W < 1 || L->K < 1 || L->R < 1 || L->S < 1) return false;
+    if (L->stride_h < 1 || L->stride_w < 1 || L->pad_h < 0 || L->pad_w < 0) return false;
+    if (L->H + 2 * L->pad_h < L->R || L->W + 2 * L->pad_w < L->S) return false;
+    return true;
+}
+
+Dims dims_of(const ucd_layer_t *L)
+{
+    Dims d;
+    d.C = L->C; d.H = L->H; d.W = L->W; d.K = L->K; d.R = L->R; d.S = L->S;
+    d.sh = L->stride_h; d.sw = L->stride_w; d.ph = L->pad_h; d.pw = L->pad_w;
+    d.P = (L->H + 2 * L->pad_h - L->R) / L->stride_h + 1;
+    d.Q = (L->W + 2 * L->pad_w - L->S) / L->stride_w + 1;
+    return d;
+}
+
+// kernels index tensors with 32-bit element offsets relative to the micro-batch pointer
+bool fits_32bit(const ucd_layer_t *L, int b)
+{
+    const Dims d = dims_of(L);
+    const long long lim = (1ll << 31) - 1;
+    return (long long)b * d.C * d.H * d.W <= lim && (long long)b * d.K * d.P * d.Q <= lim &&
+           (long long)d.K * d.crs() <= lim && (long long)d.crs() * ((long long)b * d.P * d.Q + 4) <= lim;
+}
+
+size_t ws_size(const ucd_layer_t *L, int op, int algo, int b)
+{
+    if (!L || !layer_ok(L) || L->dtype != 0 || op < 0 || op >= UCD_N_OP || b < 1 || b > L->N) return UCD_WS_NA;
+    if (!fits_32bit(L, b)) return UCD_WS_NA;
+    const Dims d = dims_of(L);
+    switch (algo) {
+    case UCD_ALGO_IMPLICIT:
+        return 0;
+    case UCD_ALGO_IM2COL:
+        // a 1x1 stride-1 unpadded layer's column matrix is x itself: nothing to gain
+        if (d.R == 1 && d.S == 1 && d.sh == 1 && d.sw == 1 && d.ph == 0 && d.pw == 0) return UCD_WS_NA;
+        return im2col_ws_bytes(d, b);
+    case UCD_ALGO_WINOGRAD:
+        if (!winograd_applies(d, op)) return UCD_WS_NA;
+        return winograd_ws_bytes(d, op, b);
+    default:
+        return UCD_WS_NA;
+    }
+}
+
+int hip_status(hipError_t e) { return e == hipSuccess ? UCD_OK : UCD_E_HIP; }
+
+// One algorithm on one micro-batch.  (a, bsrc, out) = (x, w, y) | (dy, w, dx) | (x, dy, dw).
+int run_micro(const ucd_layer_t *L, int op, int algo, int b, const float *a, const float *bsrc, float *out,
+              float beta, float *ws, hipStream_t s)
+{
+    const Dims d = dims_of(L);
+    hipError_t e = hipErrorInvalidValue;
+    switch (algo) {
+    case UCD_ALGO_IMPLICIT:
+        if (op == UCD_FWD) e = implicit_fwd(d, b, a, bsrc, out, s);
+        else if (op == UCD_BWD_DATA) e = implicit_bwd_data(d, b, a, bsrc, out, s);
+        else e = implicit_bwd_filter(d, b, a, bsrc, out, beta, s);
+        break;
+    case UCD_ALGO_IM2COL:
+        if (op == UCD_FWD) e = im2col_fwd(d, b, a, bsrc, out, ws, s);
+        else if (op == UCD_BWD_DATA) e = im2col_bwd_data(d, b, a, bsrc, out, ws, s);
+        else e = im2col_bwd_filter(d, b, a, bsrc, out, beta, ws, s);
+        break;
+    case UCD_ALGO_WINOGRAD:
+        if (op == UCD_FWD) e = winograd_fwd(d, b, a, bsrc, out, ws, s);
+        else if (op == UCD_BWD_DATA) e = winograd_bwd_data(d, b, a, bsrc, out, ws, s);
+        break;
+    }
+    return hip_status(e);
+}
+
+int run_plan(const ucd_plan_t *plan, int op, const float *a, const float *bsrc, float *out, float beta,
+             void *ws, size_t ws_bytes, void *stream)
+{
+    if (!plan) return UCD_E_NULLPTR;
+    if (!plan->has_layer || plan->op != op) return UCD_E_INVALID;
+    if (!a || !bsrc || !out) return UCD_E_NULLPTR;
+    if (plan->ws_bytes > 0 && (!ws || ws_bytes < plan->ws_bytes)) return ws ? UCD_E_WS_TOO_SMALL : UCD_E_NULLPTR;
+    if (op == UCD_BWD_FILTER && beta != 0.f && beta != 1.f) return UCD_E_INVALID;
+    const ucd_layer_t *L = &plan->layer;
+    const Dims d = dims_of(L);
+    const size_t x_img = (size_t)d.C * d.H * d.W, y_img = (size_t)d.K * d.P * d.Q;
+    size_t o = 0;
+    bool first = true;
+    for (const Micro &m : plan->micro) {
+        int rc;
+        if (op == UCD_FWD)
+            rc = run_micro(L, op, m.algo, m.batch, a + o * x_img, bsrc, out + o * y_img, 0.f, (float *)ws,
+                           (hipStream_t)stream);
+        else if (op == UCD_BWD_DATA)
+            rc = run_micro(L, op, m.algo, m.batch, a + o * y_img, bsrc, out + o * x_img, 0.f, (float *)ws,
+                           (hipStream_t)stream);
+        else  // the caller's beta for the first micro-batch, output scale 1 afterwards
+            rc = run_micro(L, op, m.algo, m.batch, a + o * x_img, bsrc + o * y_img, out, first ? beta : 1.f,
+                           (float *)ws, (hipStream_t)stream);
+        if (rc != UCD_OK) return rc;
+        o += (size_t)m.batch;
+        first = false;
+    }
+    return UCD_OK;
+}
+
+// ---- benchmark cache ------------------------------------------------------------------------
+typedef std::tuple<int, int, int, int, int, int, int, int, int, int, int, int, int, int> BenchKey;
+std::map<BenchKey, uint64_t> g_cache;
+std::mutex g_cache_mu;
+
+BenchKey key_of(const ucd_layer_t *L, int op, int algo, int b)
+{
+    return BenchKey(L->C, L->H, L->W, L->K, L->R, L->S, L->stride_h, L->stride_w, L->pad_h, L->pad_w, L->dtype,
+                    op, algo, b);
+}
+
+bool cache_get(const BenchKey &k, uint64_t &t)
+{
+    std::lock_guard<std::mutex> g(g_cache_mu);
+    auto it = g_cache.find(k);
+    if (it == g_cache.end()) return false;
+    t = it->second;
+    return true;
+}
+
+void cache_put(const BenchKey &k, uint64_t t)
+{
+    std::lock_guard<std::mutex> g(g_cache_mu);
+    g_cache[k] = t;
+}
+
+struct Events {
+    hipEvent_t a = nullptr, b = nullptr;
+    ~Events()
+    {
+        if (a) (void)hipEventDestroy(a);
+        if (b) (void)hipEventDestroy(b);
+    }
+};
+
+// Device time of one (algo, b): one warm-up, then the minimum of kTimedRuns, in integer ns.
+int time_micro(const ucd_layer_t *L, int op, int algo, int b, float *x, float *w, float *y, float *ws,
+               hipStream_t s, Events &ev, uint64_t &ns)
+{
+    const float *a = op == UCD_BWD_DATA ? y : x;
+    const float *bs = op == UCD_BWD_FILTER ? y : w;
+    float *out = op == UCD_FWD ? y : (op == UCD_BWD_DATA ? x : w);
+    // BackwardFilter is timed as the accumulating call it is for every micro-batch but the first
+    const float beta = op == UCD_BWD_FILTER ? 1.f : 0.f;
+    if (op == UCD_BWD_FILTER) {
+        const Dims d = dims_of(L);
+        if (fill_zero(w, (size_t)d.K * d.crs(), s) != hipSuccess) return UCD_E_HIP;
+    }
+    float best = INFINITY;
+    for (int it = 0; it <= kTimedRuns; ++it) {
+        if (hipEventRecord(ev.a, s) != hipSuccess) return UCD_E_HIP;
+        int rc = run_micro(L, op, algo, b, a, bs, out, beta, ws, s);
+        if (rc != UCD_OK) return rc;
+        if (hipEventRecord(ev.b, s) != hipSuccess) return UCD_E_HIP;
+        if (hipEventSynchronize(ev.b) != hipSuccess) return UCD_E_HIP;
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, ev.a, ev.b) != hipSuccess) return UCD_E_HIP;
+        if (it > 0) best = std::min(best, ms);
+    }
+    ns = (uint64_t)std::llround((double)best * 1e6);
+    if (ns == 0) ns = 1;
+    return UCD_OK;
+}
+
+// Step 1 of the WR algorithm for one kernel: fill the table for every policy size and every
+// algorithm that applies and fits `limit`, timing what the cache does not hold yet.
+int bench_kernel(const ucd_layer_t *L, int op, size_t limit, int policy, float *x, float *w, float *y, float *ws,
+                 hipStream_t s, std::vector<uint64_t> &t, std::vector<size_t> &m)
+{
+    const int B = L->N;
+    t.assign((size_t)UCD_N_ALGO * (B + 1), kTimeInf);
+    m.assign((size_t)UCD_N_ALGO * (B + 1), kWsNa);
+    Events ev;
+    if (hipEventCreate(&ev.a) != hipSuccess || hipEventCreate(&ev.b) != hipSuccess) return UCD_E_HIP;
+    for (int b : policy_sizes(policy, B))
+        for (int a = 0; a < UCD_N_ALGO; ++a) {
+            const size_t need = ws_size(L, op, a, b);
+            if (need == UCD_WS_NA) continue;
+            m[(size_t)a * (B + 1) + b] = need;
+            if (need > limit) continue;
+            const BenchKey k = key_of(L, op, a, b);
+            uint64_t ns;
+            if (!cache_get(k, ns)) {
+                int rc = time_micro(L, op, a, b, x, w, y, ws, s, ev, ns);
+                if (rc != UCD_OK) return rc;
+                cache_put(k, ns);
+            }
+            t[(size_t)a * (B + 1) + b] = ns;
+        }
+    return UCD_OK;
+}
+
+ucd_plan_t *make_plan(const Config &cfg, const ucd_layer_t *L, int op)
+{
+    ucd_plan_t *p = new (std::nothrow) ucd_plan_t();
+    if (!p) return nullptr;
+    p->micro = cfg.micro;
+    p->cost_ns = cfg.cost;
+    p->ws_bytes = cfg.ws;
+    p->op = op;
+    if (L) {
+        p->has_layer = true;
+        p->layer = *L;
+    }
+    return p;
+}
+
+bool policy_ok(int policy) { return policy >= UCD_POLICY_UNDIVIDED && policy <= UCD_POLICY_ALL; }
+
+size_t round256(size_t v) { return (v + 255) / 256 * 256; }
+
+// Desirable sets -> 0-1 programme -> per-kernel configurations and segment offsets.
+int solve_wd(const std::vector<std::vector<Config>> &fronts, size_t total_ws, std::vector<int> &choice)
+{
+    std::vector<std::vector<FrontPoint>> pts(fronts.size());
+    for (size_t k = 0; k < fronts.size(); ++k)
+        for (const Config &c : fronts[k]) pts[k].push_back({c.cost, round256(c.ws)});
+    uint64_t total;
+    if (!wd_solve(pts, total_ws, choice, total)) return UCD_E_INFEASIBLE;
+    return UCD_OK;
+}
+
+}  // namespace
+
+// ---- exported ------------------------------------------------------------------------------
+extern "C" {
+
+const char *ucd_strerror(int status)
+{
+    switch (status) {
+    case UCD_OK: return "ok";
+    case UCD_E_INVALID: return "invalid argument";
+    case UCD_E_NULLPTR: return "null pointer";
+    case UCD_E_UNSUPPORTED: return "algorithm or dtype not supported for this layer";
+    case UCD_E_WS_TOO_SMALL: return "workspace smaller than the plan needs";
+    case UCD_E_HIP: return "HIP runtime error";
+    case UCD_E_NOMEM: return "out of host memory";
+    case UCD_E_INFEASIBLE: return "no feasible configuration";
+    default: return "unknown status";
+    }
+}
+
+int ucd_version(void) { return 100; }
+
+size_t ucd_workspace_size(const ucd_layer_t *layer, int op, int algo, int b) { return ws_size(layer, op, algo, b); }
+
+int ucd_plan_from_table(int B, size_t ws_limit, int policy, int n_algo, const uint64_t *t_ns, const size_t *ws,
+                        ucd_plan_t **out)
+{
+    if (!t_ns || !ws || !out) return UCD_E_NULLPTR;
+    if (B < 1 || n_algo < 1 || !policy_ok(policy)) return UCD_E_INVALID;
+    Table tab{B, n_algo, t_ns, ws};
+    Config cfg;
+    if (!wr_plan(tab, ws_limit, policy, cfg)) return UCD_E_INFEASIBLE;
+    ucd_plan_t *p = make_plan(cfg, nullptr, 0);
+    if (!p) return UCD_E_NOMEM;
+    *out = p;
+    return UCD_OK;
+}
+
+int ucd_desirable_from_table(int B, size_t ws_limit, int policy, int n_algo, const uint64_t *t_ns,
+                             const size_t *ws, uint64_t *front_t, size_t *front_ws, int cap, int *n)
+{
+    if (!t_ns || !ws || !n || (cap > 0 && (!front_t || !front_ws))) return UCD_E_NULLPTR;
+    if (B < 1 || n_algo < 1 || !policy_ok(policy) || cap < 0) return UCD_E_INVALID;
+    Table tab{B, n_algo, t_ns, ws};
+    std::vector<Config> front;
+    if (!desirable_set(tab, ws_limit, policy, front)) return UCD_E_INFEASIBLE;
+    for (int i = 0; i < (int)front.size() && i < cap; ++i) {
+        front_t[i] = front[i].cost;
+        front_ws[i] = front[i].ws;
+    }
+    *n = (int)front.size();
+    return UCD_OK;
+}
+
+int ucd_wd_solve(int n_kernels, const int *front_n, const uint64_t *front_t, const size_t *front_ws,
+                 size_t budget, int *choice, uint64_t *total_t)
+{
+    if (!front_n || !front_t || !front_ws || !choice || !total_t) return UCD_E_NULLPTR;
+    if (n_kernels < 1) return UCD_E_INVALID;
+    std::vector<std::vector<FrontPoint>> pts(n_kernels);
+    size_t o = 0;
+    for (int k = 0; k < n_kernels; ++k) {
+        if (front_n[k] < 1) return UCD_E_INVALID;
+        for (int i = 0; i < front_n[k]; ++i, ++o) pts[k].push_back({front_t[o], front_ws[o]});
+    }
+    std::vector<int> ch;
+    uint64_t total;
+    if (!wd_solve(pts, budget, ch, total)) return UCD_E_INFEASIBLE;
+    std::copy(ch.begin(), ch.end(), choice);
+    *total_t = total;
+    return UCD_OK;
+}
+
+int ucd_plan_wd_from_tables(int n_kernels, const int *B, int n_algo, const size_t *tab_off, const uint64_t *t_ns,
+                            const size_t *ws, size_t total_ws, int policy, ucd_plan_t **plans, size_t *ws_offsets)
+{
+    if (!B || !tab_off || !t_ns || !ws || !plans || !ws_offsets) return UCD_E_NULLPTR;
+    if (n_kernels < 1 || n_algo < 1 || !policy_ok(policy)) return UCD_E_INVALID;
+    std::vector<std::vector<Config>> fronts(n_kernels);
+    for (int k = 0; k < n_kernels; ++k) {
+        if (B[k] < 1) return UCD_E_INVALID;
+        Table tab{B[k], n_algo, t_ns + tab_off[k], ws + tab_off[k]};
+        if (!desirable_set(tab, total_ws, policy, fronts[k])) return UCD_E_INFEASIBLE;
+    }
+    std::vector<int> choice;
+    int rc = solve_wd(fronts, total_ws, choice);
+    if (rc != UCD_OK) return rc;
+    std::vector<ucd_plan_t *> made;
+    for (int k = 0; k < n_kernels; ++k) {
+        ucd_plan_t *p = make_plan(fronts[k][choice[k]], nullptr, 0);
+        if (!p) {
+            for (ucd_plan_t *q : made) delete q;
+            return UCD_E_NOMEM;
+        }
+        made.push_back(p);
+    }
+    size_t off = 0;
+    for (int k = 0; k < n_kernels; ++k) {
+        plans[k] = made[k];
+        ws_offsets[k] = off;
+        off += round256(made[k]->ws_bytes);
+    }
+    return UCD_OK;
+}
+
+int ucd_plan_fixed(const ucd_layer_t *layer, int op, const ucd_micro_t *micro, int n, ucd_plan_t **out)
+{
+    if (!layer || !micro || !out) return UCD_E_NULLPTR;
+    if (!layer_ok(layer) || op < 0 || op >= UCD_N_OP || n < 1) return UCD_E_INVALID;
+    if (layer->dtype != 0) return UCD_E_UNSUPPORTED;
+    Config cfg;
+    long sum = 0;
+    for (int i = 0; i < n; ++i) {
+        if (micro[i].batch < 1 || micro[i].batch > layer->N) return UCD_E_INVALID;
+        if (micro[i].algo < 0 || micro[i].algo >= UCD_N_ALGO) return UCD_E_INVALID;
+        const size_t need = ws_size(layer, op, micro[i].algo, micro[i].batch);
+        if (need == UCD_WS_NA) return UCD_E_UNSUPPORTED;
+        cfg.ws = std::max(cfg.ws, need);
+        cfg.micro.push_back({micro[i].algo, micro[i].batch});
+        sum += micro[i].batch;
+    }
+    if (sum != layer->N) return UCD_E_INVALID;
+    ucd_plan_t *p = make_plan(cfg, layer, op);
+    if (!p) return UCD_E_NOMEM;
+    *out = p;
+    return UCD_OK;
+}
+
+int ucd_plan_query(const ucd_plan_t *plan, ucd_micro_t *micro, int cap, int *n, uint64_t *cost_ns, size_t *ws_bytes)
+{
+    if (!plan) return UCD_E_NULLPTR;
+    if (cap < 0 || (cap > 0 && !micro)) return UCD_E_INVALID;
+    for (int i = 0; i < cap && i < (int)plan->micro.size(); ++i) {
+        micro[i].algo = plan->micro[i].algo;
+        micro[i].batch = plan->micro[i].batch;
+    }
+    if (n) *n = (int)plan->micro.size();
+    if (cost_ns) *cost_ns = plan->cost_ns;
+    if (ws_bytes) *ws_bytes = plan->ws_bytes;
+    return UCD_OK;
+}
+
+void ucd_plan_destroy(ucd_plan_t *plan) { delete plan; }
+
+int ucd_plan(const ucd_layer_t *layer, int op, size_t ws_limit, int policy, void *x, void *w, void *y, void *ws,
+             void *stream, ucd_plan_t **out)
+{
+    if (!layer || !x || !w || !y || !out) return UCD_E_NULLPTR;
+    if (!layer_ok(layer) || op < 0 || op >= UCD_N_OP || !policy_ok(policy)) return UCD_E_INVALID;
+    if (layer->dtype != 0 || !fits_32bit(layer, layer->N)) return UCD_E_UNSUPPORTED;
+    if (ws_limit > 0 && !ws) return UCD_E_NULLPTR;
+    std::vector<uint64_t> t;
+    std::vector<size_t> m;
+    int rc = bench_kernel(layer, op, ws_limit, policy, (float *)x, (float *)w, (float *)y, (float *)ws,
+                          (hipStream_t)stream, t, m);
+    if (rc != UCD_OK) return rc;
+    Table tab{layer->N, UCD_N_ALGO, t.data(), m.data()};
+    Config cfg;
+    if (!wr_plan(tab, ws_limit, policy, cfg)) return UCD_E_INFEASIBLE;
+    ucd_plan_t *p = make_plan(cfg, layer, op);
+    if (!p) return UCD_E_NOMEM;
+    *out = p;
+    return UCD_OK;
+}
+
+int ucd_plan_wd(const ucd_layer_t *layers, const int *ops, int n_kernels, size_t total_ws, int policy, void *x,
+                size_t x_cap, void *w, size_t w_cap, void *y, size_t y_cap, void *ws, void *stream,
+                ucd_plan_t **plans, size_t *ws_offsets)
+{
+    if (!layers || !ops || !x || !w || !y || !plans || !ws_offsets) return UCD_E_NULLPTR;
+    if (n_kernels < 1 || !policy_ok(policy)) return UCD_E_INVALID;
+    if (total_ws > 0 && !ws) return UCD_E_NULLPTR;
+    for (int k = 0; k < n_kernels; ++k) {
+        const ucd_layer_t *L = &layers[k];
+        if (!layer_ok(L) || ops[k] < 0 || ops[k] >= UCD_N_OP) return UCD_E_INVALID;
+        if (L->dtype != 0 || !fits_32bit(L, L->N)) return UCD_E_UNSUPPORTED;
+        const Dims d = dims_of(L);
+        if ((size_t)L->N * d.C * d.H * d.W * 4 > x_cap || (size_t)d.K * d.crs() * 4 > w_cap ||
+            (size_t)L->N * d.K * d.P * d.Q * 4 > y_cap)
+            return UCD_E_INVALID;
+    }
+    std::vector<std::vector<Config>> fronts(n_kernels);
+    for (int k = 0; k < n_kernels; ++k) {
+        std::vector<uint64_t> t;
+        std::vector<size_t> m;
+        int rc = bench_kernel(&layers[k], ops[k], total_ws, policy, (float *)x, (float *)w, (float *)y, (float *)ws,
+                              (hipStream_t)stream, t, m);
+        if (rc != UCD_OK) return rc;
+        Table tab{layers[k].N, UCD_N_ALGO, t.data(), m.data()};
+        if (!desirable_set(tab, total_ws, policy, fronts[k])) return UCD_E_INFEASIBLE;
+    }
+    std::vector<int> choice;
+    int rc = solve_wd(fronts, total_ws, choice);
+    if (rc != UCD_OK) return rc;
+    std::vector<ucd_plan_t *> made;
+    for (int k = 0; k < n_kernels; ++k) {
+        ucd_plan_t *p = make_plan(fronts[k][choice[k]], &layers[k], ops[k]);
+        if (!p) {
+            for (ucd_plan_t *q : made) delete q;
+            return UCD_E_NOMEM;
+        }
+        made.push_back(p);
+    }
+    size_t off = 0;
+    for (int k = 0; k < n_kernels; ++k) {
+        plans[k] = made[k];
+        ws_offsets[k] = off;
+        off += round256(made[k]->ws_bytes);
+    }
+    return UCD_OK;
+}
+
+int ucd_bench_table(const ucd_layer_t *layer, int op, uint64_t *t_ns, size_t *ws, int cap_b)
+{
+    if (!layer || !t_ns || !ws) return UCD_E_NULLPTR;
+    if (!layer_ok(layer) || op < 0 || op >= UCD_N_OP || cap_b < 1) return UCD_E_INVALID;
+    ucd_layer_t L = *layer;
+    for (int a = 0; a < UCD_N_ALGO; ++a)
+        for (int b = 0; b <= cap_b; ++b) {
+            const size_t i = (size_t)a * (cap_b + 1) + b;
+            t_ns[i] = UCD_TIME_INF;
+            ws[i] = UCD_WS_NA;
+            if (b < 1) continue;
+            L.N = std::max(L.N, b);
+            ws[i] = ws_size(&L, op, a, b);
+            uint64_t ns;
+            if (cache_get(key_of(&L, op, a, b), ns)) t_ns[i] = ns;
+        }
+    return UCD_OK;
+}
+
+void ucd_bench_clear(void)
+{
+    std::lock_guard<std::mutex> g(g_cache_mu);
+    g_cache.clear();
+}
+
+int ucd_conv_fwd(const ucd_plan_t *plan, const void *x, const void *w, void *y, void *ws, size_t ws_bytes,
+                 void *stream)
+{
+    return run_plan(plan, UCD_FWD, (const float *)x, (const float *)w, (float *)y, 0.f, ws, ws_bytes, stream);
+}
+
+int ucd_conv_bwd_data(const ucd_plan_t *plan, const void *dy, const void *w, void *dx, void *ws, size_t ws_bytes,
+                      void *stream)
+{
+    return run_plan(plan, UCD_BWD_DATA, (const float *)dy, (const float *)w, (float *)dx, 0.f, ws, ws_bytes, stream);
+}
+
+int ucd_conv_bwd_filter(const ucd_plan_t *plan, const void *x, const void *dy, void *dw, float beta, void *ws,
+                        size_t ws_bytes, void *stream)
+{
+    return run_plan(plan, UCD_BWD_FILTER, (const float *)x, (const float *)dy, (float *)dw, beta, ws, ws_bytes,
+                    stream);
+}
+
+int ucd_run_micro(const ucd_layer_t *layer, int op, int algo, int b, const void *a, const void *bsrc, void *out,
+                  float beta, void *ws, size_t ws_bytes, void *stream)
+{
+    if (!layer || !a || !bsrc || !out) return UCD_E_NULLPTR;
+    if (!layer_ok(layer) || op < 0 || op >= UCD_N_OP || b < 1) return UCD_E_INVALID;
+    if (layer->dtype != 0) return UCD_E_UNSUPPORTED;
+    ucd_layer_t L = *layer;
+    L.N = std::max(L.N, b);
+    const size_t need = ws_size(&L, op, algo, b);
+    if (need == UCD_WS_NA) return UCD_E_UNSUPPORTED;
+    if (need > 0 && !ws) return UCD_E_NULLPTR;
+    if (need > ws_bytes) return UCD_E_WS_TOO_SMALL;
+    if (op == UCD_BWD_FILTER && beta != 0.f && beta != 1.f) return UCD_E_INVALID;
+    return run_micro(&L, op, algo, b, (const float *)a, (const float *)bsrc, (float *)out, beta, (float *)ws,
+                     (hipStream_t)stream);
+}
+
+}  // extern "C"

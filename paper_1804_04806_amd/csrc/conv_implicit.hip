@@ -1,0 +1,114 @@
+// Zero-workspace implicit-GEMM convolution: Forward, BackwardData, BackwardFilter as tile GEMMs
+// whose operand loaders gather straight from the NCHW tensors.
+//   Forward        Y[K x bPQ]   = W[K x CRS]      * im2col(X)[CRS x bPQ]
+//   BackwardData   dX[C x bHW]  = W^T[C x KRS]    * gather(dY)[KRS x bHW]   (one GEMM per stride phase)
+//   BackwardFilter dW[K x CRS] += dY[K x bPQ]     * im2col(X)^T[bPQ x CRS]  (split over bPQ, fp32 atomics)
+#include "gemm_launch.hpp"
+#include "kernels.h"
+
+namespace ucd {
+
+__global__ void fill_zero_kernel(float *p, size_t n)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t step = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += step) p[i] = 0.f;
+}
+
+hipError_t fill_zero(float *p, size_t n, hipStream_t s)
+{
+    if (n == 0) return hipSuccess;
+    size_t blocks = (n + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    fill_zero_kernel<<<(unsigned)blocks, 256, 0, s>>>(p, n);
+    return hipGetLastError();
+}
+
+hipError_t implicit_fwd(const Dims &d, int b, const float *x, const float *w, float *y, hipStream_t s)
+{
+    GemmShape g{d.K, b * d.P * d.Q, d.crs()};
+    KLaneParams pa{};
+    pa.t = w; pa.mode = 0; pa.row_stride = 1; pa.col_stride = d.crs();
+    GatherParams pb{};
+    pb.t = x; pb.Ct = d.C; pb.Ht = d.H; pb.Wt = d.W;
+    pb.grid_hw = FastDiv(d.P * d.Q); pb.grid_w = FastDiv(d.Q);
+    pb.mul_h = d.sh; pb.add_h = -d.ph; pb.mul_w = d.sw; pb.add_w = -d.pw; pb.dir = 1;
+    pb.taps = FastDiv(d.R * d.S); pb.taps_w = FastDiv(d.S);
+    EpiNCHWParams pe{};
+    pe.out = y; pe.grid_hw = pb.grid_hw; pe.grid_w = pb.grid_w;
+    pe.M = d.K; pe.HWo = d.P * d.Q; pe.Wo = d.Q; pe.h0 = 0; pe.hs = 1; pe.w0 = 0; pe.ws = 1;
+    return launch_gemm<KLane, GatherNLane, EpiNCHW>(pa, pb, pe, g, s);
+}
+
+// Stride phases: input pixels h with (h + ph) % sh == a are reached only by filter rows
+// r = a, a + sh, ...; within a phase the gather is a dense stride-1 correlation with the
+// sub-sampled, index-reversed filter.  Pixels of a phase with no tap get zeros (Kd = 0).
+hipError_t implicit_bwd_data(const Dims &d, int b, const float *dy, const float *w, float *dx, hipStream_t s)
+{
+    for (int a = 0; a < d.sh; ++a)
+        for (int c = 0; c < d.sw; ++c) {
+            const int h0 = ((a - d.ph) % d.sh + d.sh) % d.sh, w0 = ((c - d.pw) % d.sw + d.sw) % d.sw;
+            const int Hh = h0 < d.H ? (d.H - h0 + d.sh - 1) / d.sh : 0;
+            const int Ww = w0 < d.W ? (d.W - w0 + d.sw - 1) / d.sw : 0;
+            if (Hh == 0 || Ww == 0) continue;
+            const int Ra = a < d.R ? (d.R - a + d.sh - 1) / d.sh : 0;
+            const int Sc = c < d.S ? (d.S - c + d.sw - 1) / d.sw : 0;
+            GemmShape g{d.C, b * Hh * Ww, d.K * Ra * Sc};
+            KLaneParams pa{};
+            pa.t = w; pa.mode = 1; pa.col_stride = d.R * d.S;
+            pa.taps = FastDiv(Ra * Sc); pa.taps_w = FastDiv(Sc);
+            pa.k_stride = d.crs(); pa.s_mem = d.S;
+            pa.tap_add_h = a; pa.tap_mul_h = d.sh; pa.tap_add_w = c; pa.tap_mul_w = d.sw;
+            GatherParams pb{};
+            pb.t = dy; pb.Ct = d.K; pb.Ht = d.P; pb.Wt = d.Q;
+            pb.grid_hw = FastDiv(Hh * Ww); pb.grid_w = FastDiv(Ww);
+            pb.mul_h = 1; pb.add_h = (h0 + d.ph - a) / d.sh; pb.mul_w = 1; pb.add_w = (w0 + d.pw - c) / d.sw;
+            pb.dir = -1;
+            pb.taps = pa.taps; pb.taps_w = pa.taps_w;
+            EpiNCHWParams pe{};
+            pe.out = dx; pe.grid_hw = pb.grid_hw; pe.grid_w = pb.grid_w;
+            pe.M = d.C; pe.HWo = d.H * d.W; pe.Wo = d.W; pe.h0 = h0; pe.hs = d.sh; pe.w0 = w0; pe.ws = d.sw;
+            hipError_t e = launch_gemm<KLane, GatherNLane, EpiNCHW>(pa, pb, pe, g, s);
+            if (e != hipSuccess) return e;
+        }
+    return hipSuccess;
+}
+
+// Number of reduction splits so that tiles * splits covers the chip a few times over, with
+// chunks of at least 256 reduction rows.
+int filter_splits(int M, int N, int Kd)
+{
+    const int bm = M <= 32 ? 32 : (M <= 64 ? 64 : 128), bn = N <= 64 ? 64 : 128;
+    const long tiles = (long)((M + bm - 1) / bm) * ((N + bn - 1) / bn);
+    long want = (1024 + tiles - 1) / tiles;
+    long cap = Kd / 256;
+    if (cap < 1) cap = 1;
+    if (want > cap) want = cap;
+    if (want < 1) want = 1;
+    return (int)want;
+}
+
+hipError_t implicit_bwd_filter(const Dims &d, int b, const float *x, const float *dy, float *dw, float beta,
+                               hipStream_t s)
+{
+    hipError_t e;
+    if (beta == 0.f && (e = fill_zero(dw, (size_t)d.K * d.crs(), s)) != hipSuccess) return e;
+    GemmShape g{d.K, d.crs(), b * d.P * d.Q};
+    g.splits = filter_splits(g.M, g.N, g.Kd);
+    KLaneParams pa{};
+    pa.t = dy; pa.mode = 2;
+    pa.grid_hw = FastDiv(d.P * d.Q); pa.grid_w = FastDiv(d.Q);
+    pa.col_taps = FastDiv(1); pa.col_taps_w = FastDiv(1);
+    pa.n_stride = d.K * d.P * d.Q; pa.Ht = d.P; pa.Wt = d.Q;
+    pa.mul_h = 1; pa.add_h = 0; pa.mul_w = 1; pa.add_w = 0;
+    KLaneParams pb{};
+    pb.t = x; pb.mode = 2;
+    pb.grid_hw = pa.grid_hw; pb.grid_w = pa.grid_w;
+    pb.col_taps = FastDiv(d.R * d.S); pb.col_taps_w = FastDiv(d.S);
+    pb.n_stride = d.C * d.H * d.W; pb.Ht = d.H; pb.Wt = d.W;
+    pb.mul_h = d.sh; pb.add_h = -d.ph; pb.mul_w = d.sw; pb.add_w = -d.pw;
+    EpiDenseParams pe{dw, d.crs()};
+    return launch_gemm<KLane, KLane, EpiAtomic>(pa, pb, pe, g, s);
+}
+
+}  // namespace ucd

@@ -1,0 +1,473 @@
+// LDS-staged fp32 MFMA tile GEMM for gfx950, with pluggable operand loaders and epilogues.
+//
+// C[M x N] (+)= A[M x Kd] * B[Kd x N].  One 256-thread workgroup (4 wavefronts of 64) owns a
+// BM x BN tile of C and walks Kd in steps of BK = 16.  Each step both operand tiles are fetched
+// from global memory into registers (overlapping the MFMAs of the previous step), written to
+// one of two LDS buffers laid out [BK][tile + pad] and consumed by v_mfma_f32_32x32x2_f32.
+//
+// How an operand element (row kk of the reduction, position m in the tile) maps to memory is
+// the loader's business: dense matrices, an im2col-style gather from an NCHW tensor, a filter
+// gather.  Loaders come in two lane arrangements:
+//   * "N-lane": consecutive lanes take consecutive tile positions (coalesced when memory is
+//     contiguous along the tile dimension), one reduction row per pass, row index wave-uniform;
+//   * "K-lane": consecutive lanes take consecutive reduction indices (coalesced when memory is
+//     contiguous along the reduction dimension).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ucd {
+
+constexpr int kThreads = 256;
+constexpr int kBK = 16;
+constexpr int kPad = 4;
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// Exact n / d for 0 <= n < 2^31 by multiply-high: m = ceil(2^(31+l) / d), l = ceil(log2 d).
+struct FastDiv {
+    uint32_t d, m, sh;
+    __host__ __device__ FastDiv() : d(1), m(0), sh(0) {}
+    __host__ explicit FastDiv(uint32_t div) : d(div), m(0), sh(0)
+    {
+        if (div <= 1) { d = 1; return; }
+        uint32_t l = 0;
+        while ((1ull << l) < div) ++l;
+        const uint64_t p = 1ull << (31 + l);
+        m = (uint32_t)((p + div - 1) / div);
+        sh = l - 1;
+    }
+    __device__ __forceinline__ uint32_t div(uint32_t n) const { return d == 1 ? n : (__umulhi(n, m) >> sh); }
+    __device__ __forceinline__ void divmod(uint32_t n, uint32_t &q, uint32_t &r) const
+    {
+        q = div(n);
+        r = n - q * d;
+    }
+};
+
+template <int BM_, int BN_, int WAVES_M_, int WAVES_N_>
+struct Tile {
+    static constexpr int BM = BM_, BN = BN_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
+    static constexpr int WM = BM / (32 * WAVES_M);  // 32x32 MFMA tiles per wave along M
+    static constexpr int WN = BN / (32 * WAVES_N);
+    static constexpr int LDA = BM + kPad, LDB = BN + kPad;
+    static constexpr int LDS_FLOATS = kBK * (LDA + LDB);
+    static_assert(WAVES_M * WAVES_N == 4, "four wavefronts per workgroup");
+    static_assert(WM >= 1 && WN >= 1, "tile too small for the wave layout");
+};
+
+// Block id -> tile coordinates.  Workgroups are dealt round-robin to the 8 XCDs by linear id;
+// this remaps ids so that each XCD (own L2) walks a contiguous range of tiles in which the M
+// index runs fastest, i.e. the tiles that re-read the same B (activation) columns share an L2.
+__device__ __forceinline__ void xcd_tile(int tiles_m, int tiles_n, int &tile_m, int &tile_n)
+{
+    const uint32_t total = (uint32_t)tiles_m * (uint32_t)tiles_n;
+    const uint32_t id = blockIdx.x;
+    const uint32_t xcd = id & 7u, slot = id >> 3;
+    const uint32_t q = total >> 3, rem = total & 7u;
+    const uint32_t v = xcd * q + (xcd < rem ? xcd : rem) + slot;
+    tile_m = (int)(v % (uint32_t)tiles_m);
+    tile_n = (int)(v / (uint32_t)tiles_m);
+}
+
+// ---- operand loaders ---------------------------------------------------------------------------
+// Common interface:  init(params, tile_origin, extent)  once per workgroup;
+//                    fetch(k0, k_end, regs)  global -> registers for reduction rows [k0, k0+BK);
+//                    commit(lds_tile, regs)  registers -> LDS tile laid out [BK][LD].
+// Elements outside [0, extent) x [0, k_end) read as 0.
+
+// Gather from an NCHW tensor, lanes along the tile dimension.  Tile position j decodes to
+// (n, a, b) over a (CH x CW) grid; reduction row kk decodes to (c, r, s) over (.. x RR x RS_);
+// the element is T[n, c, a*mul_h + add_h + dir*r, b*mul_w + add_w + dir*s] when in range.
+// Forward's B operand: grid = output pixels, mul = stride, add = -pad, dir = +1, T = x.
+// BackwardData's B operand (per stride phase): grid = phase pixels, mul = 1, dir = -1, T = dy.
+struct GatherParams {
+    const float *t;
+    int Ct, Ht, Wt;          // tensor channel count and plane size
+    FastDiv grid_hw, grid_w; // tile-position decode
+    int mul_h, add_h, mul_w, add_w, dir;
+    FastDiv taps, taps_w;    // reduction-row decode: kk -> (c, kk % taps), then (r, s)
+};
+
+template <int TD>
+struct GatherNLane {
+    static constexpr int RP = kThreads / TD;  // reduction rows per pass
+    static constexpr int NE = kBK / RP;       // elements per thread per step
+    static constexpr int LD = TD + kPad;
+    struct Regs { float r[NE]; };
+    const GatherParams *p;
+    int base, hb, wb, col, row0;
+
+    __device__ __forceinline__ void init(const GatherParams &prm, int origin, int extent)
+    {
+        p = &prm;
+        const int tid = threadIdx.x;
+        col = tid % TD;
+        row0 = __builtin_amdgcn_readfirstlane(tid / TD);
+        const int j = origin + col;
+        if (j < extent) {
+            uint32_t n, rest, a, b;
+            prm.grid_hw.divmod((uint32_t)j, n, rest);
+            prm.grid_w.divmod(rest, a, b);
+            hb = (int)a * prm.mul_h + prm.add_h;
+            wb = (int)b * prm.mul_w + prm.add_w;
+            base = (int)n * prm.Ct * prm.Ht * prm.Wt + hb * prm.Wt + wb;
+        } else {
+            hb = wb = -(1 << 28);  // every tap out of range
+            base = 0;
+        }
+    }
+    __device__ __forceinline__ void fetch(int k0, int k_end, float (&r)[NE]) const
+    {
+#pragma unroll
+        for (int i = 0; i < NE; ++i) {
+            const int kk = k0 + row0 + RP * i;  // wave-uniform
+            float v = 0.f;
+            if (kk < k_end) {
+                uint32_t c, tap, tr, ts;
+                p->taps.divmod((uint32_t)kk, c, tap);
+                p->taps_w.divmod(tap, tr, ts);
+                const int dr = p->dir * (int)tr, ds = p->dir * (int)ts;
+                const int ih = hb + dr, iw = wb + ds;
+                if ((unsigned)ih < (unsigned)p->Ht && (unsigned)iw < (unsigned)p->Wt)
+                    v = p->t[base + ((int)c * p->Ht + dr) * p->Wt + ds];
+            }
+            r[i] = v;
+        }
+    }
+    __device__ __forceinline__ void commit(float *lds, const float (&r)[NE]) const
+    {
+#pragma unroll
+        for (int i = 0; i < NE; ++i) lds[(row0 + RP * i) * LD + col] = r[i];
+    }
+};
+
+// Lanes along the reduction dimension.  Element (kk, j) lives at  t[rowoff(kk) + coloff(j)]  and
+// is present when  rowok(kk) && colok(j) && window(kk, j).  The decode of kk happens once per
+// step per thread (16 consecutive lanes share a tile position), that of the thread's NE tile
+// positions once per workgroup.
+//   mode 0 (plain):   rowoff = kk * row_stride,  coloff = j * col_stride          (dense matrices)
+//   mode 1 (filter):  kk -> (k, r, s):  rowoff = k*k_stride + (tap_add_h + tap_mul_h*r)*S_mem + tap_add_w + tap_mul_w*s,
+//                     coloff = j * col_stride                         (BackwardData's A operand)
+//   mode 2 (pixels):  kk -> (n, a, b) over a grid:  rowoff = n*n_stride + (a*mul_h+add_h)*Wt + b*mul_w+add_w,
+//                     j -> (c, r, s): coloff = (c*Ht + r)*Wt + s, window = tap inside the plane
+//                     (BackwardFilter's operands: x with real taps, dy with a 1x1 "tap")
+struct KLaneParams {
+    const float *t;
+    int mode;
+    int row_stride, col_stride;
+    // mode 1
+    FastDiv taps, taps_w;
+    int k_stride, s_mem, tap_mul_h, tap_add_h, tap_mul_w, tap_add_w;
+    // mode 2
+    FastDiv grid_hw, grid_w, col_taps, col_taps_w;
+    int n_stride, Ht, Wt, mul_h, add_h, mul_w, add_w;
+};
+
+template <int TD>
+struct KLane {
+    static constexpr int CP = kThreads / kBK;  // tile positions per pass (16)
+    static constexpr int NE = TD / CP;
+    static constexpr int LD = TD + kPad;
+    struct Regs { float r[NE]; };
+    const KLaneParams *p;
+    int kl, c0;
+    int coff[NE];
+    int cr[NE], cs[NE];  // mode 2 taps; cr < 0 marks an out-of-extent tile position (all modes)
+
+    __device__ __forceinline__ void init(const KLaneParams &prm, int origin, int extent)
+    {
+        p = &prm;
+        const int tid = threadIdx.x;
+        kl = tid % kBK;
+        c0 = tid / kBK;
+#pragma unroll
+        for (int i = 0; i < NE; ++i) {
+            const int j = origin + c0 + CP * i;
+            cr[i] = cs[i] = 0;
+            coff[i] = 0;
+            if (j >= extent) {
+                cr[i] = -(1 << 28);
+            } else if (prm.mode == 2) {
+                uint32_t c, tap, r, s;
+                prm.col_taps.divmod((uint32_t)j, c, tap);
+                prm.col_taps_w.divmod(tap, r, s);
+                cr[i] = (int)r;
+                cs[i] = (int)s;
+                coff[i] = ((int)c * prm.Ht + (int)r) * prm.Wt + (int)s;
+            } else {
+                coff[i] = j * prm.col_stride;
+            }
+        }
+    }
+    __device__ __forceinline__ void fetch(int k0, int k_end, float (&r)[NE]) const
+    {
+        const int kk = k0 + kl;
+        const bool rowok = kk < k_end;
+        int roff = 0, hb = 0, wb = 0;
+        if (rowok) {
+            if (p->mode == 0) {
+                roff = kk * p->row_stride;
+            } else if (p->mode == 1) {
+                uint32_t k, tap, tr, ts;
+                p->taps.divmod((uint32_t)kk, k, tap);
+                p->taps_w.divmod(tap, tr, ts);
+                roff = (int)k * p->k_stride + (p->tap_add_h + p->tap_mul_h * (int)tr) * p->s_mem +
+                       p->tap_add_w + p->tap_mul_w * (int)ts;
+            } else {
+                uint32_t n, rest, a, b;
+                p->grid_hw.divmod((uint32_t)kk, n, rest);
+                p->grid_w.divmod(rest, a, b);
+                hb = (int)a * p->mul_h + p->add_h;
+                wb = (int)b * p->mul_w + p->add_w;
+                roff = (int)n * p->n_stride + hb * p->Wt + wb;
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < NE; ++i) {
+            float v = 0.f;
+            bool ok = rowok && cr[i] >= 0;
+            if (p->mode == 2)
+                ok = ok && (unsigned)(hb + cr[i]) < (unsigned)p->Ht && (unsigned)(wb + cs[i]) < (unsigned)p->Wt;
+            if (ok) v = p->t[roff + coff[i]];
+            r[i] = v;
+        }
+    }
+    __device__ __forceinline__ void commit(float *lds, const float (&r)[NE]) const
+    {
+#pragma unroll
+        for (int i = 0; i < NE; ++i) lds[kl * LD + c0 + CP * i] = r[i];
+    }
+};
+
+// Dense matrix contiguous along the tile dimension:  element (kk, j) = t[kk*ld + j], float4 loads.
+// Requires ld % 4 == 0, a 16-byte aligned base and extent % 4 == 0 handled by the caller's padding.
+struct DenseParams {
+    const float *t;
+    int ld;
+};
+
+template <int TD>
+struct DenseNLane {
+    static constexpr int CQ = TD / 4;          // float4 columns per row
+    static constexpr int RP = kThreads / CQ;   // rows per pass
+    static constexpr int NE = (kBK + RP - 1) / RP;
+    static constexpr int LD = TD + kPad;
+    struct Regs { f32x4 r[NE]; };
+    const DenseParams *p;
+    int col, row0, origin_, extent_;
+
+    __device__ __forceinline__ void init(const DenseParams &prm, int origin, int extent)
+    {
+        p = &prm;
+        const int tid = threadIdx.x;
+        col = (tid % CQ) * 4;
+        row0 = tid / CQ;
+        origin_ = origin;
+        extent_ = extent;
+    }
+    __device__ __forceinline__ void fetch(int k0, int k_end, f32x4 (&r)[NE]) const
+    {
+#pragma unroll
+        for (int i = 0; i < NE; ++i) {
+            const int row = row0 + RP * i;
+            const int kk = k0 + row;
+            f32x4 v = {0.f, 0.f, 0.f, 0.f};
+            if (row < kBK && kk < k_end && origin_ + col < extent_)
+                v = *reinterpret_cast<const f32x4 *>(p->t + (size_t)kk * p->ld + origin_ + col);
+            r[i] = v;
+        }
+    }
+    __device__ __forceinline__ void commit(float *lds, const f32x4 (&r)[NE]) const
+    {
+#pragma unroll
+        for (int i = 0; i < NE; ++i) {
+            const int row = row0 + RP * i;
+            if (row < kBK) *reinterpret_cast<f32x4 *>(lds + row * LD + col) = r[i];
+        }
+    }
+};
+
+// Same matrix, any ld / alignment: scalar loads, one reduction row per pass.
+template <int TD>
+struct DenseNLaneS {
+    static constexpr int RP = kThreads / TD;
+    static constexpr int NE = kBK / RP;
+    static constexpr int LD = TD + kPad;
+    struct Regs { float r[NE]; };
+    const DenseParams *p;
+    int col, row0, j_;
+    bool ok_;
+
+    __device__ __forceinline__ void init(const DenseParams &prm, int origin, int extent)
+    {
+        p = &prm;
+        const int tid = threadIdx.x;
+        col = tid % TD;
+        row0 = __builtin_amdgcn_readfirstlane(tid / TD);
+        j_ = origin + col;
+        ok_ = j_ < extent;
+    }
+    __device__ __forceinline__ void fetch(int k0, int k_end, float (&r)[NE]) const
+    {
+#pragma unroll
+        for (int i = 0; i < NE; ++i) {
+            const int kk = k0 + row0 + RP * i;
+            r[i] = (kk < k_end && ok_) ? p->t[(size_t)kk * p->ld + j_] : 0.f;
+        }
+    }
+    __device__ __forceinline__ void commit(float *lds, const float (&r)[NE]) const
+    {
+#pragma unroll
+        for (int i = 0; i < NE; ++i) lds[(row0 + RP * i) * LD + col] = r[i];
+    }
+};
+
+// ---- epilogues ---------------------------------------------------------------------------------
+// store(m, j, v) for one accumulator element; `prep(j)` decodes a column once for 16 rows.
+
+// Scatter into an NCHW tensor: column j -> (n, a, b) over a (CH x CW) grid, element
+// out[n, m, h0 + hs*a, w0 + ws*b].  Forward writes y with the trivial grid; BackwardData writes
+// one stride phase of dx.
+struct EpiNCHWParams {
+    float *out;
+    FastDiv grid_hw, grid_w;
+    int M, HWo, Wo, h0, hs, w0, ws;
+};
+struct EpiNCHW {
+    typedef EpiNCHWParams Params;
+    int off;
+    __device__ __forceinline__ void prep(const Params &p, int j)
+    {
+        uint32_t n, rest, a, b;
+        p.grid_hw.divmod((uint32_t)j, n, rest);
+        p.grid_w.divmod(rest, a, b);
+        off = (int)n * p.M * p.HWo + (p.h0 + p.hs * (int)a) * p.Wo + p.w0 + p.ws * (int)b;
+    }
+    __device__ __forceinline__ void store(const Params &p, int m, float v) const { p.out[off + m * p.HWo] = v; }
+};
+
+// Dense row-major store out[m*ld + j].
+struct EpiDenseParams {
+    float *out;
+    int ld;
+};
+struct EpiDense {
+    typedef EpiDenseParams Params;
+    int j_;
+    __device__ __forceinline__ void prep(const Params &, int j) { j_ = j; }
+    __device__ __forceinline__ void store(const Params &p, int m, float v) const { p.out[(size_t)m * p.ld + j_] = v; }
+};
+
+// Dense row-major accumulate with hardware fp32 atomics (split-K partial sums of BackwardFilter).
+struct EpiAtomic {
+    typedef EpiDenseParams Params;
+    int j_;
+    __device__ __forceinline__ void prep(const Params &, int j) { j_ = j; }
+    __device__ __forceinline__ void store(const Params &p, int m, float v) const
+    {
+        unsafeAtomicAdd(p.out + (size_t)m * p.ld + j_, v);
+    }
+};
+
+// ---- the kernel --------------------------------------------------------------------------------
+// grid.x = tiles_m * tiles_n (XCD-remapped), grid.y = reduction splits (chunk `k_chunk`, a multiple
+// of BK), grid.z = batch of independent GEMMs (loaders/epilogue see pointers advanced by the
+// given element strides).
+template <class T, class ALoader, class BLoader, class Epi, class AParams, class BParams>
+__global__ __launch_bounds__(kThreads) void gemm_kernel(AParams pa, BParams pb, typename Epi::Params pe,
+                                                         int M, int N, int Kd, int k_chunk, int tiles_m,
+                                                         int tiles_n, long a_batch, long b_batch, long c_batch)
+{
+    __shared__ __attribute__((aligned(16))) float lds[2][T::LDS_FLOATS];
+
+    if (blockIdx.z) {
+        pa.t += a_batch * blockIdx.z;
+        pb.t += b_batch * blockIdx.z;
+        pe.out += c_batch * blockIdx.z;
+    }
+    int tile_m, tile_n;
+    xcd_tile(tiles_m, tiles_n, tile_m, tile_n);
+    const int m0 = tile_m * T::BM, n0 = tile_n * T::BN;
+    const int k_begin = blockIdx.y * k_chunk;
+    const int k_end = min(Kd, k_begin + k_chunk);
+
+    ALoader la;
+    BLoader lb;
+    la.init(pa, m0, M);
+    lb.init(pb, n0, N);
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm0 = (wave % T::WAVES_M) * (T::WM * 32);
+    const int wn0 = (wave / T::WAVES_M) * (T::WN * 32);
+    const int l32 = lane & 31, lhi = lane >> 5;
+
+    f32x16 acc[T::WM][T::WN];
+#pragma unroll
+    for (int i = 0; i < T::WM; ++i)
+#pragma unroll
+        for (int j = 0; j < T::WN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    typename ALoader::Regs ra;
+    typename BLoader::Regs rb;
+
+    if (k_begin < k_end) {
+        la.fetch(k_begin, k_end, ra.r);
+        lb.fetch(k_begin, k_end, rb.r);
+        la.commit(lds[0], ra.r);
+        lb.commit(lds[0] + kBK * T::LDA, rb.r);
+    }
+    __syncthreads();
+
+    int buf = 0;
+    for (int k0 = k_begin; k0 < k_end; k0 += kBK) {
+        const bool more = k0 + kBK < k_end;
+        if (more) {
+            la.fetch(k0 + kBK, k_end, ra.r);
+            lb.fetch(k0 + kBK, k_end, rb.r);
+        }
+        const float *As = lds[buf];
+        const float *Bs = lds[buf] + kBK * T::LDA;
+#pragma unroll
+        for (int kk = 0; kk < kBK; kk += 2) {
+            float a[T::WM], b[T::WN];
+#pragma unroll
+            for (int i = 0; i < T::WM; ++i) a[i] = As[(kk + lhi) * T::LDA + wm0 + i * 32 + l32];
+#pragma unroll
+            for (int j = 0; j < T::WN; ++j) b[j] = Bs[(kk + lhi) * T::LDB + wn0 + j * 32 + l32];
+#pragma unroll
+            for (int i = 0; i < T::WM; ++i)
+#pragma unroll
+                for (int j = 0; j < T::WN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+        if (more) {
+            la.commit(lds[buf ^ 1], ra.r);
+            lb.commit(lds[buf ^ 1] + kBK * T::LDA, rb.r);
+        }
+        __syncthreads();
+        buf ^= 1;
+    }
+
+    // accumulator element v of a 32x32 tile: row 8*(v/4) + 4*(lane/32) + v%4, column lane%32
+    Epi epi;
+#pragma unroll
+    for (int j = 0; j < T::WN; ++j) {
+        const int col = n0 + wn0 + j * 32 + l32;
+        if (col >= N) continue;
+        epi.prep(pe, col);
+#pragma unroll
+        for (int i = 0; i < T::WM; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = m0 + wm0 + i * 32 + 8 * (v / 4) + 4 * lhi + (v % 4);
+                if (row < M) epi.store(pe, row, acc[i][j][v]);
+            }
+    }
+}
+
+}  // namespace ucd

@@ -1,0 +1,37 @@
+// Host-side launchers of the HIP kernels.  Every launcher only enqueues on `stream` and returns
+// the launch status; pointers are device pointers already offset to the micro-batch.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <cstddef>
+
+namespace ucd {
+
+struct Dims {
+    int C, H, W, K, R, S, sh, sw, ph, pw, P, Q;
+    int crs() const { return C * R * S; }
+};
+
+// zero-workspace implicit GEMM
+hipError_t implicit_fwd(const Dims &d, int b, const float *x, const float *w, float *y, hipStream_t s);
+hipError_t implicit_bwd_data(const Dims &d, int b, const float *dy, const float *w, float *dx, hipStream_t s);
+hipError_t implicit_bwd_filter(const Dims &d, int b, const float *x, const float *dy, float *dw, float beta,
+                               hipStream_t s);
+
+// im2col into workspace + GEMM
+size_t im2col_ws_bytes(const Dims &d, int b);
+hipError_t im2col_fwd(const Dims &d, int b, const float *x, const float *w, float *y, float *ws, hipStream_t s);
+hipError_t im2col_bwd_data(const Dims &d, int b, const float *dy, const float *w, float *dx, float *ws,
+                           hipStream_t s);
+hipError_t im2col_bwd_filter(const Dims &d, int b, const float *x, const float *dy, float *dw, float beta,
+                             float *ws, hipStream_t s);
+
+// Winograd F(2x2,3x3), 3x3 stride-1 layers, Forward and BackwardData
+bool winograd_applies(const Dims &d, int op);
+size_t winograd_ws_bytes(const Dims &d, int op, int b);
+hipError_t winograd_fwd(const Dims &d, int b, const float *x, const float *w, float *y, float *ws, hipStream_t s);
+hipError_t winograd_bwd_data(const Dims &d, int b, const float *dy, const float *w, float *dx, float *ws,
+                             hipStream_t s);
+
+hipError_t fill_zero(float *p, size_t n, hipStream_t s);
+
+}  // namespace ucd

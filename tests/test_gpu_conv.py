@@ -1,0 +1,79 @@
+"""GPU parity: every algorithm x operation x forced micro-batch division against the fp64
+oracle, element by element (relative L2 over the whole tensor), through the C-ABI."""
+import numpy as np
+import pytest
+
+from paper_1804_04806_amd import ucd
+from paper_1804_04806_amd.synth import Shape
+from hip_helpers import inputs, rel_l2, run_hip, run_oracle
+
+pytestmark = pytest.mark.gpu
+
+TOL = {ucd.ALGO_IMPLICIT: 1e-5, ucd.ALGO_IM2COL: 1e-5, ucd.ALGO_WINOGRAD: 1e-3}
+
+# sizes span several tiles (128-wide) with ragged tails in M, N and the reduction
+SHAPES = [
+    Shape(8, 16, 16, 16, 32, 3, 3, 1, 1, "small3x3"),          # the small configuration
+    Shape(5, 3, 37, 35, 20, 11, 11, 4, 0, "conv1-like"),       # stride 4, C=3, ragged everything
+    Shape(3, 24, 13, 13, 40, 5, 5, 1, 2, "conv2-like"),
+    Shape(4, 70, 13, 13, 136, 3, 3, 1, 1, "conv3-like"),       # M > 128 with a tail
+    Shape(3, 8, 30, 30, 16, 7, 7, 2, 3, "stem-like"),          # (H+2p-R) % s != 0
+    Shape(3, 20, 14, 14, 36, 3, 3, 2, 1, "down3x3"),           # 3x3 stride 2 at even H
+    Shape(3, 20, 14, 14, 36, 1, 1, 2, 0, "proj1x1"),           # 1x1 stride 2
+    Shape(2, 40, 9, 9, 130, 1, 1, 1, 0, "1x1"),                # plain GEMM
+    Shape(2, 6, 9, 12, 7, 2, 4, 1, 1, "evenfilter"),           # R != S, even sizes
+    Shape(1, 1, 5, 5, 1, 3, 3, 1, 1, "tiny"),
+    Shape(2, 130, 8, 8, 260, 3, 3, 1, 1, "wide"),
+]
+
+DIVISIONS = {8: [[8], [1] * 8, [3, 5]], 5: [[5], [2, 3]], 4: [[4], [1, 3]], 3: [[3], [1, 2]],
+             2: [[2], [1, 1]], 1: [[1]]}
+
+
+def algos_for(desc, op, b):
+    return [a for a in range(ucd.N_ALGO) if ucd.ucd_workspace_size(desc, op, a, b) != ucd.WS_NA]
+
+
+@pytest.mark.parametrize("s", SHAPES, ids=lambda s: s.name)
+@pytest.mark.parametrize("op", [ucd.FWD, ucd.BWD_DATA, ucd.BWD_FILTER], ids=["fwd", "bwd_data", "bwd_filter"])
+def test_parity_all_algorithms_and_divisions(s, op):
+    x, w, dy = inputs(s, seed=11)
+    ref = run_oracle(s, op, x=x, w=w, dy=dy)
+    desc = ucd.layer(s)
+    for algo in algos_for(desc, op, 1):
+        for parts in DIVISIONS[s.N]:
+            if any(ucd.ucd_workspace_size(desc, op, algo, b) == ucd.WS_NA for b in parts):
+                continue
+            got = run_hip(s, op, [(algo, b) for b in parts], x=x, w=w, dy=dy)
+            assert np.isfinite(got).all(), (s.name, op, algo, parts)
+            err = rel_l2(got, ref)
+            assert err <= TOL[algo], (s.name, ucd.OP_NAMES[op], ucd.ALGO_NAMES[algo], parts, err)
+
+
+def test_mixed_algorithms_in_one_configuration():
+    s = SHAPES[0]
+    x, w, dy = inputs(s, seed=5)
+    desc = ucd.layer(s)
+    for op in (ucd.FWD, ucd.BWD_DATA, ucd.BWD_FILTER):
+        ref = run_oracle(s, op, x=x, w=w, dy=dy)
+        al = algos_for(desc, op, 2)
+        micro = [(al[i % len(al)], b) for i, b in enumerate([2, 1, 3, 2])]
+        assert rel_l2(run_hip(s, op, micro, x=x, w=w, dy=dy), ref) <= 1e-3
+
+
+@pytest.mark.parametrize("algo", [ucd.ALGO_IMPLICIT, ucd.ALGO_IM2COL])
+def test_bwd_filter_beta_one_accumulates(algo):
+    s = SHAPES[3]
+    x, w, dy = inputs(s, seed=3)
+    dw0 = (np.random.default_rng(0).standard_normal(s.w_shape)).astype(np.float32)
+    ref = run_oracle(s, ucd.BWD_FILTER, x=x, dy=dy, beta=1.0, dw0=dw0)
+    got = run_hip(s, ucd.BWD_FILTER, [(algo, 1), (algo, 3)], x=x, dy=dy, beta=1.0, dw0=dw0)
+    assert rel_l2(got, ref) <= 1e-5
+
+
+def test_unreached_pixels_are_written_as_zero():
+    s = Shape(2, 4, 6, 6, 5, 1, 1, 2, 0, "1x1s2")
+    x, w, dy = inputs(s)
+    got = run_hip(s, ucd.BWD_DATA, [(ucd.ALGO_IMPLICIT, 2)], w=w, dy=dy)
+    assert np.all(got[:, :, 1::2, :] == 0) and np.all(got[:, :, :, 1::2] == 0)
+    assert rel_l2(got, run_oracle(s, ucd.BWD_DATA, w=w, dy=dy)) <= 1e-5
