@@ -1,0 +1,228 @@
+#!/usr/bin/env python3
+"""Benchmark of the micro-batched convolution hot path on one MI355X.
+
+Workload: the AlexNet-shaped five-layer convolution stack at mini-batch 256, fp32 NCHW, a
+64 MiB workspace limit per layer (WR policy).  One step = Forward + BackwardData +
+BackwardFilter of every layer, each executed as the micro-batch configuration the WR planner
+chose from on-device benchmarks (planning happens once, before the timed region, as in the
+paper where it is amortised over training).  Inputs are seeded synthetic tensors already
+resident in HBM.
+
+Prints ONE JSON line: throughput in TFLOP/s of algorithmic convolution flops
+(3 * sum 2*N*K*P*Q*C*R*S per step), ms per step, the same for the best undivided
+single-algorithm plan, a roofline object for the dominant kernel and a CPU-oracle baseline.
+
+    python bench.py [--gpus 1] [--steps 50] [--warmup 3] [--policy all|pow2|undivided]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+METRIC = "conv ms/iter (fwd+bwdData+bwdFilter) @64MB workspace; TFLOP/s, % MFMA peak"
+FP32_MFMA_PEAK_TFLOPS = 157.3   # MI355X dense fp32 matrix peak: 256 CU x 2.4 GHz x 256 flop/clk/CU
+WS_LIMIT = 64 << 20
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--policy", default="all", choices=["all", "pow2", "undivided"])
+    ap.add_argument("--batch", type=int, default=256)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-samples", type=int, default=4)
+    return ap.parse_args()
+
+
+class LayerState:
+    """Device tensors and plans of one layer."""
+
+    def __init__(self, s, idx, torch, ucd, synth, dev):
+        self.s = s
+        self.desc = ucd.layer(s)
+        self.x = torch.from_numpy(synth.make_x(s, 0, idx)).to(dev)
+        self.w = torch.from_numpy(synth.make_w(s, 0, idx)).to(dev)
+        self.dy = torch.from_numpy(synth.make_dy(s, 0, idx)).to(dev)
+        self.y = torch.empty(s.y_shape, dtype=torch.float32, device=dev)
+        self.dx = torch.empty(s.x_shape, dtype=torch.float32, device=dev)
+        self.dw = torch.empty(s.w_shape, dtype=torch.float32, device=dev)
+        self.plans = {}
+
+    def plan(self, ucd, policy, ws, limit):
+        """WR planning for the three operations; each benchmark clobbers only output buffers."""
+        p = {}
+        p[ucd.FWD] = ucd.ucd_plan(self.desc, ucd.FWD, limit, policy, self.x, self.w, self.y, ws)
+        p[ucd.BWD_DATA] = ucd.ucd_plan(self.desc, ucd.BWD_DATA, limit, policy, self.dx, self.w, self.dy, ws)
+        p[ucd.BWD_FILTER] = ucd.ucd_plan(self.desc, ucd.BWD_FILTER, limit, policy, self.x, self.dw, self.dy, ws)
+        return p
+
+    def run(self, ucd, plans, ws):
+        ucd.ucd_conv_fwd(plans[ucd.FWD], self.x, self.w, self.y, ws)
+        ucd.ucd_conv_bwd_data(plans[ucd.BWD_DATA], self.dy, self.w, self.dx, ws)
+        ucd.ucd_conv_bwd_filter(plans[ucd.BWD_FILTER], self.x, self.dy, self.dw, 0.0, ws)
+
+
+def time_steps(torch, fn, steps, warmup):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def kernel_class(ucd, s, op, algo, beta_one):
+    """Name of the single kernel a micro-batch run launches, or None if it launches several."""
+    if algo != ucd.ALGO_IMPLICIT:
+        return None
+    if op == ucd.FWD:
+        return "implicit_gemm_nchw"
+    if op == ucd.BWD_DATA:
+        return "implicit_gemm_nchw" if s.stride == 1 else None
+    return "implicit_gemm_filter_atomic" if beta_one else None
+
+
+def dominant_kernel_roofline(torch, ucd, states, plans, ws, reps):
+    """HIP-event timing of every single-kernel micro-batch launch of the planned step, grouped
+    by kernel; returns the roofline object of the group with the largest total time."""
+    groups = {}
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for st, pl in zip(states, plans):
+        s = st.s
+        x_img, y_img = s.C * s.H * s.W, s.K * s.P * s.Q
+        for op in (ucd.FWD, ucd.BWD_DATA, ucd.BWD_FILTER):
+            o = 0
+            for i, (algo, b) in enumerate(pl[op].micro):
+                beta = 1.0 if (op == ucd.BWD_FILTER and i > 0) else 0.0
+                cls = kernel_class(ucd, s, op, algo, beta == 1.0)
+                if cls is not None:
+                    xo = st.x.view(-1)[o * x_img:]
+                    yo = st.y.view(-1)[o * y_img:]
+                    dyo = st.dy.view(-1)[o * y_img:]
+                    dxo = st.dx.view(-1)[o * x_img:]
+                    args = {ucd.FWD: (xo, st.w, yo), ucd.BWD_DATA: (dyo, st.w, dxo),
+                            ucd.BWD_FILTER: (xo, dyo, st.dw)}[op]
+                    tot = 0.0
+                    for _ in range(reps):
+                        e0.record()
+                        ucd.ucd_run_micro(st.desc, op, algo, b, *args, beta, ws)
+                        e1.record()
+                        e1.synchronize()
+                        tot += e0.elapsed_time(e1)
+                    g = groups.setdefault(cls, {"ms": 0.0, "flops": 0.0, "launches": 0})
+                    g["ms"] += tot / reps
+                    g["flops"] += s.with_batch(b).flops
+                    g["launches"] += 1
+                o += b
+    if not groups:
+        return None
+    name, g = max(groups.items(), key=lambda kv: kv[1]["ms"])
+    achieved = g["flops"] / (g["ms"] * 1e-3) / 1e12
+    return {"bound": "mfma", "kernel": name, "achieved": round(achieved, 2), "peak": FP32_MFMA_PEAK_TFLOPS,
+            "unit": "TFLOP/s", "frac": round(achieved / FP32_MFMA_PEAK_TFLOPS, 4), "traffic": None,
+            "launches_per_step": g["launches"], "avg_launch_ms": round(g["ms"] / g["launches"], 4),
+            "flops_per_launch": g["flops"] / g["launches"]}
+
+
+def cpu_baseline(layers, n_samples):
+    """The fp64 oracle, as it stands, on the first n_samples samples of every layer."""
+    from oracle import conv as oc
+    from paper_1804_04806_amd import synth
+    flops, secs = 0.0, 0.0
+    for idx, s in enumerate(layers):
+        sb = s.with_batch(n_samples)
+        L = oc.Layer(sb.N, sb.C, sb.H, sb.W, sb.K, sb.R, sb.S, sb.stride, sb.stride, sb.pad, sb.pad)
+        x, w, dy = synth.make_x(sb, 0, idx), synth.make_w(sb, 0, idx), synth.make_dy(sb, 0, idx)
+        t0 = time.perf_counter()
+        oc.conv_fwd(L, x, w)
+        oc.conv_bwd_data(L, dy, w)
+        oc.conv_bwd_filter(L, x, dy)
+        secs += time.perf_counter() - t0
+        flops += 3 * sb.flops
+    return {"value": round(flops / secs / 1e12, 6), "unit": "TFLOP/s", "cores": oc.threads(), "kind": "oracle",
+            "sample": f"first {n_samples} samples of each of the {len(layers)} layers, fwd+bwdData+bwdFilter, "
+                      f"fp64 direct loops, {secs:.1f} s",
+            "ms_per_iter_scaled": round(secs * 1e3 * layers[0].N / n_samples, 1)}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_1804_04806_amd import synth, ucd
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(3)
+    ucd.lib()  # fails loudly if the HIP library is missing
+    dev = torch.device("cuda:0")
+    policy = {"all": ucd.POLICY_ALL, "pow2": ucd.POLICY_POW2, "undivided": ucd.POLICY_UNDIVIDED}[args.policy]
+
+    layers = synth.config_alexnet(args.batch)
+    states = [LayerState(s, i, torch, ucd, synth, dev) for i, s in enumerate(layers)]
+    ws = torch.empty(WS_LIMIT // 4, dtype=torch.float32, device=dev)
+    flops_per_step = 3 * sum(s.flops for s in layers)
+
+    t0 = time.perf_counter()
+    undiv = [st.plan(ucd, ucd.POLICY_UNDIVIDED, ws, WS_LIMIT) for st in states]
+    t_plan_undiv = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    plans = [st.plan(ucd, policy, ws, WS_LIMIT) for st in states]
+    t_plan = time.perf_counter() - t0
+
+    def step(pl):
+        for st, p in zip(states, pl):
+            st.run(ucd, p, ws)
+
+    ms_undiv = time_steps(torch, lambda: step(undiv), args.steps, args.warmup)
+    ms = time_steps(torch, lambda: step(plans), args.steps, args.warmup)
+
+    tflops = flops_per_step / (ms * 1e-3) / 1e12
+    roof = dominant_kernel_roofline(torch, ucd, states, plans, ws, reps=5)
+
+    plan_report = []
+    for st, p, u in zip(states, plans, undiv):
+        for op in (ucd.FWD, ucd.BWD_DATA, ucd.BWD_FILTER):
+            micro, cost, need = p[op].query()
+            umicro, ucost, _ = u[op].query()
+            runs, last = [], None
+            for a, b in micro:   # run-length encode the configuration
+                if last == (a, b):
+                    runs[-1][2] += 1
+                else:
+                    runs.append([ucd.ALGO_NAMES[a], b, 1])
+                last = (a, b)
+            plan_report.append({"layer": st.s.name, "op": ucd.OP_NAMES[op], "config": runs,
+                                "predicted_ms": round(cost / 1e6, 4), "ws_MiB": round(need / 2 ** 20, 2),
+                                "undivided": [ucd.ALGO_NAMES[umicro[0][0]], umicro[0][1]],
+                                "undivided_predicted_ms": round(ucost / 1e6, 4)})
+
+    out = {
+        "metric": METRIC, "value": round(tflops, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"AlexNet-shaped 5-layer conv stack, batch {args.batch}, fp32 NCHW, "
+                               "64 MiB workspace per layer (WR)", "policy": args.policy,
+                   "global_batch": args.batch, "ws_limit_bytes": WS_LIMIT},
+        "ms_per_iter": round(ms, 4), "pct_fp32_mfma_peak": round(100 * tflops / FP32_MFMA_PEAK_TFLOPS, 2),
+        "undivided_ms_per_iter": round(ms_undiv, 4), "speedup_vs_undivided": round(ms_undiv / ms, 4),
+        "plan_seconds": round(t_plan, 2), "plan_seconds_undivided": round(t_plan_undiv, 2),
+        "gflop_per_step": round(flops_per_step / 1e9, 1),
+        "roofline": roof,
+        "cpu_baseline": None if args.no_cpu_baseline else cpu_baseline(layers, args.cpu_samples),
+        "plans": plan_report,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,73 @@
+"""The C-ABI library loads without a GPU and exports every symbol include/ucd.h declares."""
+import ctypes
+import os
+import re
+
+from paper_1804_04806_amd import ucd
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "ucd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ucd_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = declared_symbols()
+    assert len(names) >= 18 and "ucd_plan" in names and "ucd_conv_bwd_filter" in names
+    lib = ctypes.CDLL(ucd.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(ucd.EXPORTS) == names
+
+
+def test_version_and_strerror():
+    assert ucd.ucd_version() >= 100
+    assert ucd.strerror(0) == "ok" and "workspace" in ucd.strerror(ucd.E_WS_TOO_SMALL)
+
+
+def test_workspace_formulas():
+    L = ucd.layer(N=8, C=16, H=16, W=16, K=32, R=3, S=3, pad_h=1, pad_w=1)
+    assert ucd.ucd_workspace_size(L, ucd.FWD, ucd.ALGO_IMPLICIT, 8) == 0
+    # im2col: 4 bytes x C*R*S x (b*P*Q rounded up to 4): 144 KiB per image here
+    assert ucd.ucd_workspace_size(L, ucd.FWD, ucd.ALGO_IM2COL, 1) == 4 * 144 * 256 == 147456
+    assert ucd.ucd_workspace_size(L, ucd.BWD_FILTER, ucd.ALGO_IM2COL, 3) == 3 * 147456
+    assert ucd.ucd_workspace_size(L, ucd.FWD, ucd.ALGO_IM2COL, 9) == ucd.WS_NA      # b > N
+    L11 = ucd.layer(N=4, C=8, H=7, W=7, K=8, R=1, S=1)
+    assert ucd.ucd_workspace_size(L11, ucd.FWD, ucd.ALGO_IM2COL, 1) == ucd.WS_NA    # col == x
+    assert ucd.ucd_workspace_size(L11, ucd.FWD, ucd.ALGO_WINOGRAD, 1) == ucd.WS_NA  # not 3x3
+    bad = ucd.layer(N=4, C=8, H=2, W=2, K=8, R=5, S=5)
+    assert ucd.ucd_workspace_size(bad, ucd.FWD, ucd.ALGO_IMPLICIT, 1) == ucd.WS_NA
+
+
+def test_plan_fixed_validation_and_query():
+    import pytest
+    L = ucd.layer(N=8, C=16, H=16, W=16, K=32, R=3, S=3, pad_h=1, pad_w=1)
+    p = ucd.ucd_plan_fixed(L, ucd.FWD, [(0, 3), (1, 5)])
+    assert p.query() == ([(0, 3), (1, 5)], 0, 5 * 147456)
+    for micro, status in (([(0, 3), (0, 4)], ucd.E_INVALID), ([(0, 0), (0, 8)], ucd.E_INVALID),
+                          ([(5, 8)], ucd.E_INVALID)):
+        with pytest.raises(ucd.UcdError) as e:
+            ucd.ucd_plan_fixed(L, ucd.FWD, micro)
+        assert e.value.status == status
+
+
+def test_execution_rejects_bad_calls_before_any_launch():
+    import pytest
+    L = ucd.layer(N=8, C=16, H=16, W=16, K=32, R=3, S=3, pad_h=1, pad_w=1)
+    p = ucd.ucd_plan_fixed(L, ucd.FWD, [(1, 8)])
+    lib = ucd.lib()
+    # null tensors
+    assert lib.ucd_conv_fwd(p.handle, None, None, None, None, 0, None) == ucd.E_NULLPTR
+    # workspace one byte short (fake non-null addresses are never dereferenced on this path)
+    assert lib.ucd_conv_fwd(p.handle, 4096, 4096, 4096, 4096, 8 * 147456 - 1, None) == ucd.E_WS_TOO_SMALL
+    # wrong operation for this plan
+    assert lib.ucd_conv_bwd_data(p.handle, 4096, 4096, 4096, 4096, 1 << 30, None) == ucd.E_INVALID
+    pf = ucd.ucd_plan_fixed(L, ucd.BWD_FILTER, [(0, 8)])
+    assert lib.ucd_conv_bwd_filter(pf.handle, 4096, 4096, 4096, 0.5, None, 0, None) == ucd.E_INVALID
+    # a table plan has no layer attached
+    t = [[ucd.TIME_INF, 5, 9]]
+    pt = ucd.ucd_plan_from_table(2, 0, ucd.POLICY_ALL, t, [[ucd.WS_NA, 0, 0]])
+    assert lib.ucd_conv_fwd(pt.handle, 4096, 4096, 4096, None, 0, None) == ucd.E_INVALID
