@@ -35,6 +35,10 @@ def test_workspace_formulas():
     assert ucd.ucd_workspace_size(L, ucd.FWD, ucd.ALGO_IM2COL, 1) == 4 * 144 * 256 == 147456
     assert ucd.ucd_workspace_size(L, ucd.BWD_FILTER, ucd.ALGO_IM2COL, 3) == 3 * 147456
     assert ucd.ucd_workspace_size(L, ucd.FWD, ucd.ALGO_IM2COL, 9) == ucd.WS_NA      # b > N
+    # Winograd: 64 bytes x (C*K + b*T*(C+K)), T = 8*8 tiles: 32 + 64 + 128 KiB at b = 1
+    assert ucd.ucd_workspace_size(L, ucd.FWD, ucd.ALGO_WINOGRAD, 1) == 64 * (16 * 32 + 64 * 48) == 224 * 1024
+    assert ucd.ucd_workspace_size(L, ucd.BWD_DATA, ucd.ALGO_WINOGRAD, 2) == 64 * (16 * 32 + 128 * 48)
+    assert ucd.ucd_workspace_size(L, ucd.BWD_FILTER, ucd.ALGO_WINOGRAD, 1) == ucd.WS_NA
     L11 = ucd.layer(N=4, C=8, H=7, W=7, K=8, R=1, S=1)
     assert ucd.ucd_workspace_size(L11, ucd.FWD, ucd.ALGO_IM2COL, 1) == ucd.WS_NA    # col == x
     assert ucd.ucd_workspace_size(L11, ucd.FWD, ucd.ALGO_WINOGRAD, 1) == ucd.WS_NA  # not 3x3
