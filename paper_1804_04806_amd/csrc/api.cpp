@@ -49,13 +49,14 @@ Dims dims_of(const ucd_layer_t *L)
     return d;
 }
 
-// kernels index tensors with 32-bit element offsets relative to the micro-batch pointer
+// kernels address every operand of a micro-batch through a buffer resource of at most 2 GiB
+constexpr long long kMaxOperandFloats = 1ll << 29;
+
 bool fits_32bit(const ucd_layer_t *L, int b)
 {
     const Dims d = dims_of(L);
-    const long long lim = (1ll << 31) - 1;
-    return (long long)b * d.C * d.H * d.W <= lim && (long long)b * d.K * d.P * d.Q <= lim &&
-           (long long)d.K * d.crs() <= lim && (long long)d.crs() * ((long long)b * d.P * d.Q + 4) <= lim;
+    return (long long)b * d.C * d.H * d.W <= kMaxOperandFloats && (long long)b * d.K * d.P * d.Q <= kMaxOperandFloats &&
+           (long long)d.K * d.crs() <= kMaxOperandFloats;
 }
 
 size_t ws_size(const ucd_layer_t *L, int op, int algo, int b)
@@ -69,9 +70,11 @@ size_t ws_size(const ucd_layer_t *L, int op, int algo, int b)
     case UCD_ALGO_IM2COL:
         // a 1x1 stride-1 unpadded layer's column matrix is x itself: nothing to gain
         if (d.R == 1 && d.S == 1 && d.sh == 1 && d.sw == 1 && d.ph == 0 && d.pw == 0) return UCD_WS_NA;
+        if ((long long)d.crs() * ((long long)b * d.P * d.Q + 4) > kMaxOperandFloats) return UCD_WS_NA;
         return im2col_ws_bytes(d, b);
     case UCD_ALGO_WINOGRAD:
         if (!winograd_applies(d, op)) return UCD_WS_NA;
+        if (winograd_ws_bytes(d, op, b) / 64 > (size_t)kMaxOperandFloats) return UCD_WS_NA;
         return winograd_ws_bytes(d, op, b);
     default:
         return UCD_WS_NA;

@@ -99,21 +99,21 @@ hipError_t im2col_fwd(const Dims &d, int b, const float *x, const float *w, floa
     if (e != hipSuccess) return e;
     GemmShape g{d.K, b * d.P * d.Q, d.crs()};
     KLaneParams pa{};
-    pa.t = w; pa.mode = 0; pa.row_stride = 1; pa.col_stride = d.crs();
-    DenseParams pb{ws, col_ld(d, b)};
+    pa.t = w; pa.bytes = wbytes(d); pa.row_stride = 1; pa.col_stride = d.crs();
+    DenseParams pb{ws, (uint32_t)im2col_ws_bytes(d, b), col_ld(d, b)};
     EpiNCHWParams pe{};
     pe.out = y; pe.grid_hw = FastDiv(d.P * d.Q); pe.grid_w = FastDiv(d.Q);
     pe.M = d.K; pe.HWo = d.P * d.Q; pe.Wo = d.Q; pe.h0 = 0; pe.hs = 1; pe.w0 = 0; pe.ws = 1;
-    return launch_gemm<KLane, DenseNLane, EpiNCHW>(pa, pb, pe, g, s);
+    return launch_gemm<KLane0, DenseNLane, EpiNCHW>(pa, pb, pe, g, s);
 }
 
 hipError_t im2col_bwd_data(const Dims &d, int b, const float *dy, const float *w, float *dx, float *ws,
                            hipStream_t s)
 {
     GemmShape g{d.crs(), b * d.P * d.Q, d.K};
-    DenseParams pa{w, d.crs()};
+    DenseParams pa{w, wbytes(d), d.crs()};
     GatherParams pb{};
-    pb.t = dy; pb.Ct = d.K; pb.Ht = d.P; pb.Wt = d.Q;
+    pb.t = dy; pb.bytes = ybytes(d, b); pb.Ct = d.K; pb.Ht = d.P; pb.Wt = d.Q;
     pb.grid_hw = FastDiv(d.P * d.Q); pb.grid_w = FastDiv(d.Q);
     pb.mul_h = 1; pb.add_h = 0; pb.mul_w = 1; pb.add_w = 0; pb.dir = 1;
     pb.taps = FastDiv(1); pb.taps_w = FastDiv(1);
@@ -141,15 +141,15 @@ hipError_t im2col_bwd_filter(const Dims &d, int b, const float *x, const float *
     GemmShape g{d.K, d.crs(), b * d.P * d.Q};
     g.splits = filter_splits(g.M, g.N, g.Kd);
     KLaneParams pa{};
-    pa.t = dy; pa.mode = 2;
+    pa.t = dy; pa.bytes = ybytes(d, b);
     pa.grid_hw = FastDiv(d.P * d.Q); pa.grid_w = FastDiv(d.Q);
     pa.col_taps = FastDiv(1); pa.col_taps_w = FastDiv(1);
     pa.n_stride = d.K * d.P * d.Q; pa.Ht = d.P; pa.Wt = d.Q;
     pa.mul_h = 1; pa.add_h = 0; pa.mul_w = 1; pa.add_w = 0;
     KLaneParams pb{};
-    pb.t = ws; pb.mode = 0; pb.row_stride = 1; pb.col_stride = col_ld(d, b);
+    pb.t = ws; pb.bytes = (uint32_t)im2col_ws_bytes(d, b); pb.row_stride = 1; pb.col_stride = col_ld(d, b);
     EpiDenseParams pe{dw, d.crs()};
-    return launch_gemm<KLane, KLane, EpiAtomic>(pa, pb, pe, g, s);
+    return launch_gemm<KLane2, KLane0, EpiAtomic>(pa, pb, pe, g, s);
 }
 
 }  // namespace ucd

@@ -28,16 +28,16 @@ hipError_t implicit_fwd(const Dims &d, int b, const float *x, const float *w, fl
 {
     GemmShape g{d.K, b * d.P * d.Q, d.crs()};
     KLaneParams pa{};
-    pa.t = w; pa.mode = 0; pa.row_stride = 1; pa.col_stride = d.crs();
+    pa.t = w; pa.bytes = wbytes(d); pa.row_stride = 1; pa.col_stride = d.crs();
     GatherParams pb{};
-    pb.t = x; pb.Ct = d.C; pb.Ht = d.H; pb.Wt = d.W;
+    pb.t = x; pb.bytes = xbytes(d, b); pb.Ct = d.C; pb.Ht = d.H; pb.Wt = d.W;
     pb.grid_hw = FastDiv(d.P * d.Q); pb.grid_w = FastDiv(d.Q);
     pb.mul_h = d.sh; pb.add_h = -d.ph; pb.mul_w = d.sw; pb.add_w = -d.pw; pb.dir = 1;
     pb.taps = FastDiv(d.R * d.S); pb.taps_w = FastDiv(d.S);
     EpiNCHWParams pe{};
     pe.out = y; pe.grid_hw = pb.grid_hw; pe.grid_w = pb.grid_w;
     pe.M = d.K; pe.HWo = d.P * d.Q; pe.Wo = d.Q; pe.h0 = 0; pe.hs = 1; pe.w0 = 0; pe.ws = 1;
-    return launch_gemm<KLane, GatherNLane, EpiNCHW>(pa, pb, pe, g, s);
+    return launch_gemm<KLane0, GatherNLane, EpiNCHW>(pa, pb, pe, g, s);
 }
 
 // Stride phases: input pixels h with (h + ph) % sh == a are reached only by filter rows
@@ -55,12 +55,12 @@ hipError_t implicit_bwd_data(const Dims &d, int b, const float *dy, const float 
             const int Sc = c < d.S ? (d.S - c + d.sw - 1) / d.sw : 0;
             GemmShape g{d.C, b * Hh * Ww, d.K * Ra * Sc};
             KLaneParams pa{};
-            pa.t = w; pa.mode = 1; pa.col_stride = d.R * d.S;
+            pa.t = w; pa.bytes = wbytes(d); pa.col_stride = d.R * d.S;
             pa.taps = FastDiv(Ra * Sc); pa.taps_w = FastDiv(Sc);
             pa.k_stride = d.crs(); pa.s_mem = d.S;
             pa.tap_add_h = a; pa.tap_mul_h = d.sh; pa.tap_add_w = c; pa.tap_mul_w = d.sw;
             GatherParams pb{};
-            pb.t = dy; pb.Ct = d.K; pb.Ht = d.P; pb.Wt = d.Q;
+            pb.t = dy; pb.bytes = ybytes(d, b); pb.Ct = d.K; pb.Ht = d.P; pb.Wt = d.Q;
             pb.grid_hw = FastDiv(Hh * Ww); pb.grid_w = FastDiv(Ww);
             pb.mul_h = 1; pb.add_h = (h0 + d.ph - a) / d.sh; pb.mul_w = 1; pb.add_w = (w0 + d.pw - c) / d.sw;
             pb.dir = -1;
@@ -68,7 +68,7 @@ hipError_t implicit_bwd_data(const Dims &d, int b, const float *dy, const float 
             EpiNCHWParams pe{};
             pe.out = dx; pe.grid_hw = pb.grid_hw; pe.grid_w = pb.grid_w;
             pe.M = d.C; pe.HWo = d.H * d.W; pe.Wo = d.W; pe.h0 = h0; pe.hs = d.sh; pe.w0 = w0; pe.ws = d.sw;
-            hipError_t e = launch_gemm<KLane, GatherNLane, EpiNCHW>(pa, pb, pe, g, s);
+            hipError_t e = launch_gemm<KLane1, GatherNLane, EpiNCHW>(pa, pb, pe, g, s);
             if (e != hipSuccess) return e;
         }
     return hipSuccess;
@@ -96,19 +96,19 @@ hipError_t implicit_bwd_filter(const Dims &d, int b, const float *x, const float
     GemmShape g{d.K, d.crs(), b * d.P * d.Q};
     g.splits = filter_splits(g.M, g.N, g.Kd);
     KLaneParams pa{};
-    pa.t = dy; pa.mode = 2;
+    pa.t = dy; pa.bytes = ybytes(d, b);
     pa.grid_hw = FastDiv(d.P * d.Q); pa.grid_w = FastDiv(d.Q);
     pa.col_taps = FastDiv(1); pa.col_taps_w = FastDiv(1);
     pa.n_stride = d.K * d.P * d.Q; pa.Ht = d.P; pa.Wt = d.Q;
     pa.mul_h = 1; pa.add_h = 0; pa.mul_w = 1; pa.add_w = 0;
     KLaneParams pb{};
-    pb.t = x; pb.mode = 2;
+    pb.t = x; pb.bytes = xbytes(d, b);
     pb.grid_hw = pa.grid_hw; pb.grid_w = pa.grid_w;
     pb.col_taps = FastDiv(d.R * d.S); pb.col_taps_w = FastDiv(d.S);
     pb.n_stride = d.C * d.H * d.W; pb.Ht = d.H; pb.Wt = d.W;
     pb.mul_h = d.sh; pb.add_h = -d.ph; pb.mul_w = d.sw; pb.add_w = -d.pw;
     EpiDenseParams pe{dw, d.crs()};
-    return launch_gemm<KLane, KLane, EpiAtomic>(pa, pb, pe, g, s);
+    return launch_gemm<KLane2, KLane2, EpiAtomic>(pa, pb, pe, g, s);
 }
 
 }  // namespace ucd

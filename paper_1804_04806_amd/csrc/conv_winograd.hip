@@ -192,8 +192,8 @@ static hipError_t winograd_run(const Dims &d, int op, int b, const float *in, co
     gs.a_batch = (long)g.Ci * g.Mo4;
     gs.b_batch = (long)g.Ci * g.ld;
     gs.c_batch = (long)g.Co * g.ld;
-    DenseParams pa{U, g.Mo4};
-    DenseParams pb{V, g.ld};
+    DenseParams pa{U, (uint32_t)(gs.a_batch * 4), g.Mo4};
+    DenseParams pb{V, (uint32_t)(gs.b_batch * 4), g.ld};
     EpiDenseParams pe{Z, g.ld};
     if ((e = launch_gemm<DenseNLane, DenseNLane, EpiDense>(pa, pb, pe, gs, s)) != hipSuccess) return e;
 

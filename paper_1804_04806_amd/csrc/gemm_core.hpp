@@ -21,24 +21,29 @@ namespace ucd {
 constexpr int kThreads = 256;
 constexpr int kBK = 16;
 constexpr int kPad = 4;
+#ifndef UCD_MFMA_PRIO
+#define UCD_MFMA_PRIO 2
+#endif
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-// Exact n / d for 0 <= n < 2^31 by multiply-high: m = ceil(2^(31+l) / d), l = ceil(log2 d).
+// Exact n / d for 0 <= n < 2^31 by multiply-high: m = ceil(2^(31+l) / d), l = ceil(log2 d),
+// q = mulhi(n, m) >> (l-1).  d = 1 is encoded as m = 0 plus a pass-through mask, so that the
+// device code has no branch.
 struct FastDiv {
-    uint32_t d, m, sh;
-    __host__ __device__ FastDiv() : d(1), m(0), sh(0) {}
-    __host__ explicit FastDiv(uint32_t div) : d(div), m(0), sh(0)
+    uint32_t d, m, sh, pass;
+    __host__ __device__ FastDiv() : d(1), m(0), sh(0), pass(0xFFFFFFFFu) {}
+    __host__ explicit FastDiv(uint32_t div) : d(div), m(0), sh(0), pass(0)
     {
-        if (div <= 1) { d = 1; return; }
+        if (div <= 1) { d = 1; pass = 0xFFFFFFFFu; return; }
         uint32_t l = 0;
         while ((1ull << l) < div) ++l;
         const uint64_t p = 1ull << (31 + l);
         m = (uint32_t)((p + div - 1) / div);
         sh = l - 1;
     }
-    __device__ __forceinline__ uint32_t div(uint32_t n) const { return d == 1 ? n : (__umulhi(n, m) >> sh); }
+    __device__ __forceinline__ uint32_t div(uint32_t n) const { return (__umulhi(n, m) >> sh) + (n & pass); }
     __device__ __forceinline__ void divmod(uint32_t n, uint32_t &q, uint32_t &r) const
     {
         q = div(n);
@@ -75,15 +80,39 @@ __device__ __forceinline__ void xcd_tile(int tiles_m, int tiles_n, int &tile_m, 
 // Common interface:  init(params, tile_origin, extent)  once per workgroup;
 //                    fetch(k0, k_end, regs)  global -> registers for reduction rows [k0, k0+BK);
 //                    commit(lds_tile, regs)  registers -> LDS tile laid out [BK][LD].
-// Elements outside [0, extent) x [0, k_end) read as 0.
+// Elements outside [0, extent) x [0, k_end) read as 0.  All global reads are raw buffer loads
+// through a resource that spans exactly the operand (`bytes`): an element that must read as 0
+// gets the byte offset kOob, which the hardware range check turns into 0 without touching
+// memory.  That keeps the loads branch-free so that they can be issued back to back.  Operands
+// are therefore limited to 2 GiB each (checked on the host).
+
+constexpr uint32_t kOob = 0x80000000u;
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const float *p, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc((void *)p, 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ float buf_load(__amdgpu_buffer_rsrc_t r, uint32_t byte_off)
+{
+    return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, (int)byte_off, 0, 0));
+}
+__device__ __forceinline__ f32x4 buf_load4(__amdgpu_buffer_rsrc_t r, uint32_t byte_off)
+{
+    typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 q = __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, 0);
+    f32x4 v;
+    v.x = __uint_as_float(q.x); v.y = __uint_as_float(q.y); v.z = __uint_as_float(q.z); v.w = __uint_as_float(q.w);
+    return v;
+}
 
 // Gather from an NCHW tensor, lanes along the tile dimension.  Tile position j decodes to
-// (n, a, b) over a (CH x CW) grid; reduction row kk decodes to (c, r, s) over (.. x RR x RS_);
-// the element is T[n, c, a*mul_h + add_h + dir*r, b*mul_w + add_w + dir*s] when in range.
+// (n, a, b) over a grid; reduction row kk decodes to (c, r, s); the element is
+// T[n, c, a*mul_h + add_h + dir*r, b*mul_w + add_w + dir*s] when in range.
 // Forward's B operand: grid = output pixels, mul = stride, add = -pad, dir = +1, T = x.
 // BackwardData's B operand (per stride phase): grid = phase pixels, mul = 1, dir = -1, T = dy.
 struct GatherParams {
     const float *t;
+    uint32_t bytes;
     int Ct, Ht, Wt;          // tensor channel count and plane size
     FastDiv grid_hw, grid_w; // tile-position decode
     int mul_h, add_h, mul_w, add_w, dir;
@@ -97,11 +126,13 @@ struct GatherNLane {
     static constexpr int LD = TD + kPad;
     struct Regs { float r[NE]; };
     const GatherParams *p;
+    __amdgpu_buffer_rsrc_t rsrc;
     int base, hb, wb, col, row0;
 
     __device__ __forceinline__ void init(const GatherParams &prm, int origin, int extent)
     {
         p = &prm;
+        rsrc = make_rsrc(prm.t, prm.bytes);
         const int tid = threadIdx.x;
         col = tid % TD;
         row0 = __builtin_amdgcn_readfirstlane(tid / TD);
@@ -120,21 +151,21 @@ struct GatherNLane {
     }
     __device__ __forceinline__ void fetch(int k0, int k_end, float (&r)[NE]) const
     {
+        uint32_t off[NE];
 #pragma unroll
         for (int i = 0; i < NE; ++i) {
             const int kk = k0 + row0 + RP * i;  // wave-uniform
-            float v = 0.f;
-            if (kk < k_end) {
-                uint32_t c, tap, tr, ts;
-                p->taps.divmod((uint32_t)kk, c, tap);
-                p->taps_w.divmod(tap, tr, ts);
-                const int dr = p->dir * (int)tr, ds = p->dir * (int)ts;
-                const int ih = hb + dr, iw = wb + ds;
-                if ((unsigned)ih < (unsigned)p->Ht && (unsigned)iw < (unsigned)p->Wt)
-                    v = p->t[base + ((int)c * p->Ht + dr) * p->Wt + ds];
-            }
-            r[i] = v;
+            uint32_t c, tap, tr, ts;
+            p->taps.divmod((uint32_t)kk, c, tap);
+            p->taps_w.divmod(tap, tr, ts);
+            const int dr = p->dir * (int)tr, ds = p->dir * (int)ts;
+            const int rowoff = ((int)c * p->Ht + dr) * p->Wt + ds;                       // scalar
+            const int hlim = kk < k_end ? p->Ht : 0;                                     // scalar: row off -> no tap fits
+            const bool ok = (unsigned)(hb + dr) < (unsigned)hlim && (unsigned)(wb + ds) < (unsigned)p->Wt;
+            off[i] = ok ? (uint32_t)(base + rowoff) * 4u : kOob;
         }
+#pragma unroll
+        for (int i = 0; i < NE; ++i) r[i] = buf_load(rsrc, off[i]);
     }
     __device__ __forceinline__ void commit(float *lds, const float (&r)[NE]) const
     {
@@ -147,54 +178,54 @@ struct GatherNLane {
 // is present when  rowok(kk) && colok(j) && window(kk, j).  The decode of kk happens once per
 // step per thread (16 consecutive lanes share a tile position), that of the thread's NE tile
 // positions once per workgroup.
-//   mode 0 (plain):   rowoff = kk * row_stride,  coloff = j * col_stride          (dense matrices)
-//   mode 1 (filter):  kk -> (k, r, s):  rowoff = k*k_stride + (tap_add_h + tap_mul_h*r)*S_mem + tap_add_w + tap_mul_w*s,
+//   MODE 0 (plain):   rowoff = kk * row_stride,  coloff = j * col_stride          (dense matrices)
+//   MODE 1 (filter):  kk -> (k, r, s):  rowoff = k*k_stride + (tap_add_h + tap_mul_h*r)*s_mem + tap_add_w + tap_mul_w*s,
 //                     coloff = j * col_stride                         (BackwardData's A operand)
-//   mode 2 (pixels):  kk -> (n, a, b) over a grid:  rowoff = n*n_stride + (a*mul_h+add_h)*Wt + b*mul_w+add_w,
+//   MODE 2 (pixels):  kk -> (n, a, b) over a grid:  rowoff = n*n_stride + (a*mul_h+add_h)*Wt + b*mul_w+add_w,
 //                     j -> (c, r, s): coloff = (c*Ht + r)*Wt + s, window = tap inside the plane
 //                     (BackwardFilter's operands: x with real taps, dy with a 1x1 "tap")
 struct KLaneParams {
     const float *t;
-    int mode;
+    uint32_t bytes;
     int row_stride, col_stride;
-    // mode 1
+    // MODE 1
     FastDiv taps, taps_w;
     int k_stride, s_mem, tap_mul_h, tap_add_h, tap_mul_w, tap_add_w;
-    // mode 2
+    // MODE 2
     FastDiv grid_hw, grid_w, col_taps, col_taps_w;
     int n_stride, Ht, Wt, mul_h, add_h, mul_w, add_w;
 };
 
-template <int TD>
-struct KLane {
+template <int TD, int MODE>
+struct KLaneT {
     static constexpr int CP = kThreads / kBK;  // tile positions per pass (16)
     static constexpr int NE = TD / CP;
     static constexpr int LD = TD + kPad;
     struct Regs { float r[NE]; };
     const KLaneParams *p;
+    __amdgpu_buffer_rsrc_t rsrc;
     int kl, c0;
-    int coff[NE];
-    int cr[NE], cs[NE];  // mode 2 taps; cr < 0 marks an out-of-extent tile position (all modes)
+    int coff[NE];        // < 0 marks an out-of-extent tile position
+    int crs[NE];         // MODE 2: tap (r << 16 | s)
 
     __device__ __forceinline__ void init(const KLaneParams &prm, int origin, int extent)
     {
         p = &prm;
+        rsrc = make_rsrc(prm.t, prm.bytes);
         const int tid = threadIdx.x;
         kl = tid % kBK;
         c0 = tid / kBK;
 #pragma unroll
         for (int i = 0; i < NE; ++i) {
             const int j = origin + c0 + CP * i;
-            cr[i] = cs[i] = 0;
-            coff[i] = 0;
+            crs[i] = 0;
             if (j >= extent) {
-                cr[i] = -(1 << 28);
-            } else if (prm.mode == 2) {
+                coff[i] = -1;
+            } else if (MODE == 2) {
                 uint32_t c, tap, r, s;
                 prm.col_taps.divmod((uint32_t)j, c, tap);
                 prm.col_taps_w.divmod(tap, r, s);
-                cr[i] = (int)r;
-                cs[i] = (int)s;
+                crs[i] = (int)((r << 16) | s);
                 coff[i] = ((int)c * prm.Ht + (int)r) * prm.Wt + (int)s;
             } else {
                 coff[i] = j * prm.col_stride;
@@ -206,33 +237,33 @@ struct KLane {
         const int kk = k0 + kl;
         const bool rowok = kk < k_end;
         int roff = 0, hb = 0, wb = 0;
-        if (rowok) {
-            if (p->mode == 0) {
-                roff = kk * p->row_stride;
-            } else if (p->mode == 1) {
-                uint32_t k, tap, tr, ts;
-                p->taps.divmod((uint32_t)kk, k, tap);
-                p->taps_w.divmod(tap, tr, ts);
-                roff = (int)k * p->k_stride + (p->tap_add_h + p->tap_mul_h * (int)tr) * p->s_mem +
-                       p->tap_add_w + p->tap_mul_w * (int)ts;
-            } else {
-                uint32_t n, rest, a, b;
-                p->grid_hw.divmod((uint32_t)kk, n, rest);
-                p->grid_w.divmod(rest, a, b);
-                hb = (int)a * p->mul_h + p->add_h;
-                wb = (int)b * p->mul_w + p->add_w;
-                roff = (int)n * p->n_stride + hb * p->Wt + wb;
-            }
+        if (MODE == 0) {
+            roff = kk * p->row_stride;
+        } else if (MODE == 1) {
+            uint32_t k, tap, tr, ts;
+            p->taps.divmod((uint32_t)kk, k, tap);
+            p->taps_w.divmod(tap, tr, ts);
+            roff = (int)k * p->k_stride + (p->tap_add_h + p->tap_mul_h * (int)tr) * p->s_mem + p->tap_add_w +
+                   p->tap_mul_w * (int)ts;
+        } else {
+            uint32_t n, rest, a, b;
+            p->grid_hw.divmod((uint32_t)kk, n, rest);
+            p->grid_w.divmod(rest, a, b);
+            hb = (int)a * p->mul_h + p->add_h;
+            wb = (int)b * p->mul_w + p->add_w;
+            roff = (int)n * p->n_stride + hb * p->Wt + wb;
         }
+        uint32_t off[NE];
 #pragma unroll
         for (int i = 0; i < NE; ++i) {
-            float v = 0.f;
-            bool ok = rowok && cr[i] >= 0;
-            if (p->mode == 2)
-                ok = ok && (unsigned)(hb + cr[i]) < (unsigned)p->Ht && (unsigned)(wb + cs[i]) < (unsigned)p->Wt;
-            if (ok) v = p->t[roff + coff[i]];
-            r[i] = v;
+            bool ok = rowok && coff[i] >= 0;
+            if (MODE == 2)
+                ok = ok && (unsigned)(hb + (crs[i] >> 16)) < (unsigned)p->Ht &&
+                     (unsigned)(wb + (crs[i] & 0xffff)) < (unsigned)p->Wt;
+            off[i] = ok ? (uint32_t)(roff + coff[i]) * 4u : kOob;
         }
+#pragma unroll
+        for (int i = 0; i < NE; ++i) r[i] = buf_load(rsrc, off[i]);
     }
     __device__ __forceinline__ void commit(float *lds, const float (&r)[NE]) const
     {
@@ -240,11 +271,15 @@ struct KLane {
         for (int i = 0; i < NE; ++i) lds[kl * LD + c0 + CP * i] = r[i];
     }
 };
+template <int TD> using KLane0 = KLaneT<TD, 0>;
+template <int TD> using KLane1 = KLaneT<TD, 1>;
+template <int TD> using KLane2 = KLaneT<TD, 2>;
 
 // Dense matrix contiguous along the tile dimension:  element (kk, j) = t[kk*ld + j], float4 loads.
-// Requires ld % 4 == 0, a 16-byte aligned base and extent % 4 == 0 handled by the caller's padding.
+// Requires ld % 4 == 0 and a 16-byte aligned base; columns in [extent, ld) may hold anything.
 struct DenseParams {
     const float *t;
+    uint32_t bytes;
     int ld;
 };
 
@@ -256,16 +291,19 @@ struct DenseNLane {
     static constexpr int LD = TD + kPad;
     struct Regs { f32x4 r[NE]; };
     const DenseParams *p;
-    int col, row0, origin_, extent_;
+    __amdgpu_buffer_rsrc_t rsrc;
+    int col, row0, j_;
+    bool ok_;
 
     __device__ __forceinline__ void init(const DenseParams &prm, int origin, int extent)
     {
         p = &prm;
+        rsrc = make_rsrc(prm.t, prm.bytes);
         const int tid = threadIdx.x;
         col = (tid % CQ) * 4;
         row0 = tid / CQ;
-        origin_ = origin;
-        extent_ = extent;
+        j_ = origin + col;
+        ok_ = j_ < extent;
     }
     __device__ __forceinline__ void fetch(int k0, int k_end, f32x4 (&r)[NE]) const
     {
@@ -273,10 +311,8 @@ struct DenseNLane {
         for (int i = 0; i < NE; ++i) {
             const int row = row0 + RP * i;
             const int kk = k0 + row;
-            f32x4 v = {0.f, 0.f, 0.f, 0.f};
-            if (row < kBK && kk < k_end && origin_ + col < extent_)
-                v = *reinterpret_cast<const f32x4 *>(p->t + (size_t)kk * p->ld + origin_ + col);
-            r[i] = v;
+            const bool ok = ok_ && row < kBK && kk < k_end;
+            r[i] = buf_load4(rsrc, ok ? (uint32_t)(kk * p->ld + j_) * 4u : kOob);
         }
     }
     __device__ __forceinline__ void commit(float *lds, const f32x4 (&r)[NE]) const
@@ -297,12 +333,14 @@ struct DenseNLaneS {
     static constexpr int LD = TD + kPad;
     struct Regs { float r[NE]; };
     const DenseParams *p;
+    __amdgpu_buffer_rsrc_t rsrc;
     int col, row0, j_;
     bool ok_;
 
     __device__ __forceinline__ void init(const DenseParams &prm, int origin, int extent)
     {
         p = &prm;
+        rsrc = make_rsrc(prm.t, prm.bytes);
         const int tid = threadIdx.x;
         col = tid % TD;
         row0 = __builtin_amdgcn_readfirstlane(tid / TD);
@@ -314,7 +352,7 @@ struct DenseNLaneS {
 #pragma unroll
         for (int i = 0; i < NE; ++i) {
             const int kk = k0 + row0 + RP * i;
-            r[i] = (kk < k_end && ok_) ? p->t[(size_t)kk * p->ld + j_] : 0.f;
+            r[i] = buf_load(rsrc, (kk < k_end && ok_) ? (uint32_t)(kk * p->ld + j_) * 4u : kOob);
         }
     }
     __device__ __forceinline__ void commit(float *lds, const float (&r)[NE]) const
@@ -432,19 +470,31 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(AParams pa, BParams pb, 
         }
         const float *As = lds[buf];
         const float *Bs = lds[buf] + kBK * T::LDA;
+        // operands of the next k-pair are read from LDS before the MFMAs of the current one issue
+        float a[2][T::WM], b[2][T::WN];
+#pragma unroll
+        for (int i = 0; i < T::WM; ++i) a[0][i] = As[lhi * T::LDA + wm0 + i * 32 + l32];
+#pragma unroll
+        for (int j = 0; j < T::WN; ++j) b[0][j] = Bs[lhi * T::LDB + wn0 + j * 32 + l32];
 #pragma unroll
         for (int kk = 0; kk < kBK; kk += 2) {
-            float a[T::WM], b[T::WN];
+            const int cur = (kk >> 1) & 1, nxt = cur ^ 1;
+            if (kk + 2 < kBK) {
 #pragma unroll
-            for (int i = 0; i < T::WM; ++i) a[i] = As[(kk + lhi) * T::LDA + wm0 + i * 32 + l32];
+                for (int i = 0; i < T::WM; ++i) a[nxt][i] = As[(kk + 2 + lhi) * T::LDA + wm0 + i * 32 + l32];
 #pragma unroll
-            for (int j = 0; j < T::WN; ++j) b[j] = Bs[(kk + lhi) * T::LDB + wn0 + j * 32 + l32];
+                for (int j = 0; j < T::WN; ++j) b[nxt][j] = Bs[(kk + 2 + lhi) * T::LDB + wn0 + j * 32 + l32];
+            }
+            __builtin_amdgcn_sched_barrier(0);  // keep the LDS reads above ahead of these MFMAs
+            if (kk == 0) __builtin_amdgcn_s_setprio(UCD_MFMA_PRIO);  // a wave inside its MFMA run keeps the pipe
 #pragma unroll
             for (int i = 0; i < T::WM; ++i)
 #pragma unroll
                 for (int j = 0; j < T::WN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[cur][i], b[cur][j], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
+        __builtin_amdgcn_s_setprio(0);
         if (more) {
             la.commit(lds[buf ^ 1], ra.r);
             lb.commit(lds[buf ^ 1] + kBK * T::LDA, rb.r);

@@ -3,6 +3,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <cstddef>
+#include <cstdint>
 
 namespace ucd {
 
@@ -10,6 +11,11 @@ struct Dims {
     int C, H, W, K, R, S, sh, sw, ph, pw, P, Q;
     int crs() const { return C * R * S; }
 };
+
+// operand sizes in bytes (each at most 2 GiB, checked before any launch)
+inline uint32_t wbytes(const Dims &d) { return (uint32_t)((size_t)4 * d.K * d.crs()); }
+inline uint32_t xbytes(const Dims &d, int b) { return (uint32_t)((size_t)4 * b * d.C * d.H * d.W); }
+inline uint32_t ybytes(const Dims &d, int b) { return (uint32_t)((size_t)4 * b * d.K * d.P * d.Q); }
 
 // zero-workspace implicit GEMM
 hipError_t implicit_fwd(const Dims &d, int b, const float *x, const float *w, float *y, hipStream_t s);

@@ -1,0 +1,57 @@
+"""Time one (layer, operation, algorithm, micro-batch size) through the C-ABI.
+
+    python3 -m paper_1804_04806_amd.microbench --net alexnet --layer conv4 --op fwd --algo implicit --b 256
+
+Prints ms, algorithmic TFLOP/s and workspace bytes.  Meant to be run alone or under
+``rocprofv3 --kernel-trace --stats`` / ``--pmc`` to look at a single kernel.
+"""
+import argparse
+import json
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--net", default="alexnet", choices=["small", "alexnet", "resnet18", "densenet", "resnet50"])
+    ap.add_argument("--layer", default="conv4")
+    ap.add_argument("--op", default="fwd", choices=["fwd", "bwd_data", "bwd_filter"])
+    ap.add_argument("--algo", default="implicit", choices=["implicit", "im2col", "winograd"])
+    ap.add_argument("--b", type=int, default=256)
+    ap.add_argument("--reps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    args = ap.parse_args()
+
+    import torch
+    from . import synth, ucd
+    nets = {"small": synth.config_small, "alexnet": synth.config_alexnet, "resnet18": synth.config_resnet18,
+            "densenet": synth.config_densenet_block, "resnet50": synth.config_resnet50}
+    s = next(l for l in nets[args.net]() if l.name == args.layer).with_batch(args.b)
+    op = {"fwd": ucd.FWD, "bwd_data": ucd.BWD_DATA, "bwd_filter": ucd.BWD_FILTER}[args.op]
+    algo = {"implicit": ucd.ALGO_IMPLICIT, "im2col": ucd.ALGO_IM2COL, "winograd": ucd.ALGO_WINOGRAD}[args.algo]
+    dev = torch.device("cuda:0")
+    desc = ucd.layer(s)
+    need = ucd.ucd_workspace_size(desc, op, algo, args.b)
+    if need == ucd.WS_NA:
+        raise SystemExit("algorithm does not apply to this layer/operation")
+    x = torch.from_numpy(synth.make_x(s)).to(dev)
+    w = torch.from_numpy(synth.make_w(s)).to(dev)
+    y = torch.from_numpy(synth.make_dy(s)).to(dev)
+    ws = torch.empty(max(need, 4) // 4, dtype=torch.float32, device=dev)
+    a, bsrc, out = {ucd.FWD: (x, w, y), ucd.BWD_DATA: (y, w, x), ucd.BWD_FILTER: (x, y, w)}[op]
+    beta = 1.0 if op == ucd.BWD_FILTER else 0.0
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    times = []
+    for it in range(args.warmup + args.reps):
+        e0.record()
+        ucd.ucd_run_micro(desc, op, algo, args.b, a, bsrc, out, beta, ws)
+        e1.record()
+        e1.synchronize()
+        if it >= args.warmup:
+            times.append(e0.elapsed_time(e1))
+    ms = min(times)
+    print(json.dumps({"layer": s.name, "op": args.op, "algo": args.algo, "b": args.b, "ms_min": round(ms, 4),
+                      "ms_avg": round(sum(times) / len(times), 4), "tflops": round(s.flops / ms / 1e9, 2),
+                      "ws_bytes": need}))
+
+
+if __name__ == "__main__":
+    main()
