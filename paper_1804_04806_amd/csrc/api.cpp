@@ -36,6 +36,7 @@ bool layer_ok(const ucd_layer_t *L)
     if (L->N < 1 || L->C < 1 || L->H < 1 || L->W < 1 || L->K < 1 || L->R < 1 || L->S < 1) return false;
     if (L->stride_h < 1 || L->stride_w < 1 || L->pad_h < 0 || L->pad_w < 0) return false;
     if (L->H + 2 * L->pad_h < L->R || L->W + 2 * L->pad_w < L->S) return false;
+    if (L->R > 31 || L->S > 31) return false;  // the gather kernels keep one validity bit per filter row / column
     return true;
 }
 
@@ -50,7 +51,7 @@ Dims dims_of(const ucd_layer_t *L)
 }
 
 // kernels address every operand of a micro-batch through a buffer resource of at most 2 GiB
-constexpr long long kMaxOperandFloats = 1ll << 29;
+constexpr long long kMaxOperandFloats = (1ll << 29) - (1ll << 16);
 
 bool fits_32bit(const ucd_layer_t *L, int b)
 {

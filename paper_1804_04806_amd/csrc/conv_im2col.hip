@@ -117,6 +117,7 @@ hipError_t im2col_bwd_data(const Dims &d, int b, const float *dy, const float *w
     pb.grid_hw = FastDiv(d.P * d.Q); pb.grid_w = FastDiv(d.Q);
     pb.mul_h = 1; pb.add_h = 0; pb.mul_w = 1; pb.add_w = 0; pb.dir = 1;
     pb.taps = FastDiv(1); pb.taps_w = FastDiv(1);
+    pb.n_tap_h = 1; pb.n_tap_w = 1; pb.shift_thread = 0; pb.shift_row = 0;
     EpiDenseParams pe{ws, col_ld(d, b)};
     hipError_t e;
     if (d.crs() % 4 == 0)

@@ -34,10 +34,13 @@ hipError_t implicit_fwd(const Dims &d, int b, const float *x, const float *w, fl
     pb.grid_hw = FastDiv(d.P * d.Q); pb.grid_w = FastDiv(d.Q);
     pb.mul_h = d.sh; pb.add_h = -d.ph; pb.mul_w = d.sw; pb.add_w = -d.pw; pb.dir = 1;
     pb.taps = FastDiv(d.R * d.S); pb.taps_w = FastDiv(d.S);
+    pb.n_tap_h = d.R; pb.n_tap_w = d.S;
+    pb.shift_thread = d.ph * d.W + d.pw; pb.shift_row = 0;
     EpiNCHWParams pe{};
     pe.out = y; pe.grid_hw = pb.grid_hw; pe.grid_w = pb.grid_w;
     pe.M = d.K; pe.HWo = d.P * d.Q; pe.Wo = d.Q; pe.h0 = 0; pe.hs = 1; pe.w0 = 0; pe.ws = 1;
-    return launch_gemm<KLane0, GatherNLane, EpiNCHW>(pa, pb, pe, g, s);
+    if (d.R * d.S <= 31) return launch_gemm<KLane0, GatherNLane, EpiNCHW>(pa, pb, pe, g, s);
+    return launch_gemm<KLane0, GatherNLaneBig, EpiNCHW>(pa, pb, pe, g, s);
 }
 
 // Stride phases: input pixels h with (h + ph) % sh == a are reached only by filter rows
@@ -65,10 +68,13 @@ hipError_t implicit_bwd_data(const Dims &d, int b, const float *dy, const float 
             pb.mul_h = 1; pb.add_h = (h0 + d.ph - a) / d.sh; pb.mul_w = 1; pb.add_w = (w0 + d.pw - c) / d.sw;
             pb.dir = -1;
             pb.taps = pa.taps; pb.taps_w = pa.taps_w;
+            pb.n_tap_h = Ra; pb.n_tap_w = Sc;
+            pb.shift_thread = 0; pb.shift_row = (Ra > 0 ? Ra - 1 : 0) * d.Q + (Sc > 0 ? Sc - 1 : 0);
             EpiNCHWParams pe{};
             pe.out = dx; pe.grid_hw = pb.grid_hw; pe.grid_w = pb.grid_w;
             pe.M = d.C; pe.HWo = d.H * d.W; pe.Wo = d.W; pe.h0 = h0; pe.hs = d.sh; pe.w0 = w0; pe.ws = d.sw;
-            hipError_t e = launch_gemm<KLane1, GatherNLane, EpiNCHW>(pa, pb, pe, g, s);
+            hipError_t e = Ra * Sc <= 31 ? launch_gemm<KLane1, GatherNLane, EpiNCHW>(pa, pb, pe, g, s)
+                                         : launch_gemm<KLane1, GatherNLaneBig, EpiNCHW>(pa, pb, pe, g, s);
             if (e != hipSuccess) return e;
         }
     return hipSuccess;

@@ -110,6 +110,14 @@ __device__ __forceinline__ f32x4 buf_load4(__amdgpu_buffer_rsrc_t r, uint32_t by
 // T[n, c, a*mul_h + add_h + dir*r, b*mul_w + add_w + dir*s] when in range.
 // Forward's B operand: grid = output pixels, mul = stride, add = -pad, dir = +1, T = x.
 // BackwardData's B operand (per stride phase): grid = phase pixels, mul = 1, dir = -1, T = dy.
+//
+// fp32 MFMA and ordinary vector instructions share the SIMD's issue time on this chip, so the
+// per-element work in the main loop is kept to two vector instructions: the address splits into
+// a per-thread part (fixed for the whole kernel, in a VGPR), and a per-row part (wave-uniform,
+// computed on the scalar unit and passed as the load's scalar offset), and "is this tap inside
+// the image for my pixel" is one bit of a per-thread mask computed once per workgroup.
+// Both address parts are kept non-negative by pointing the buffer resource `shift` elements
+// before the tensor (never dereferenced there: every in-range element lies inside the tensor).
 struct GatherParams {
     const float *t;
     uint32_t bytes;
@@ -117,55 +125,78 @@ struct GatherParams {
     FastDiv grid_hw, grid_w; // tile-position decode
     int mul_h, add_h, mul_w, add_w, dir;
     FastDiv taps, taps_w;    // reduction-row decode: kk -> (c, kk % taps), then (r, s)
+    int n_tap_h, n_tap_w;    // taps per axis (R, S of this launch)
+    int shift_thread, shift_row;  // elements added to the per-thread / per-row offset parts
 };
 
-template <int TD>
-struct GatherNLane {
+// SMALL: at most 31 taps, one mask bit per (r, s); otherwise one mask per axis (R, S <= 31).
+template <int TD, bool SMALL>
+struct GatherNLaneT {
     static constexpr int RP = kThreads / TD;  // reduction rows per pass
     static constexpr int NE = kBK / RP;       // elements per thread per step
     static constexpr int LD = TD + kPad;
     struct Regs { float r[NE]; };
     const GatherParams *p;
     __amdgpu_buffer_rsrc_t rsrc;
-    int base, hb, wb, col, row0;
+    uint32_t voff;        // per-thread byte offset
+    uint32_t nmask, nmask_w;  // bit set = tap outside the image (bit 31 always set)
+    int col, row0;
 
     __device__ __forceinline__ void init(const GatherParams &prm, int origin, int extent)
     {
         p = &prm;
-        rsrc = make_rsrc(prm.t, prm.bytes);
+        const int shift = prm.shift_thread + prm.shift_row;
+        rsrc = make_rsrc(prm.t - shift, prm.bytes + 4u * (uint32_t)shift);
         const int tid = threadIdx.x;
         col = tid % TD;
         row0 = __builtin_amdgcn_readfirstlane(tid / TD);
         const int j = origin + col;
+        nmask = nmask_w = 0xFFFFFFFFu;
+        voff = 0;
         if (j < extent) {
             uint32_t n, rest, a, b;
             prm.grid_hw.divmod((uint32_t)j, n, rest);
             prm.grid_w.divmod(rest, a, b);
-            hb = (int)a * prm.mul_h + prm.add_h;
-            wb = (int)b * prm.mul_w + prm.add_w;
-            base = (int)n * prm.Ct * prm.Ht * prm.Wt + hb * prm.Wt + wb;
-        } else {
-            hb = wb = -(1 << 28);  // every tap out of range
-            base = 0;
+            const int hb = (int)a * prm.mul_h + prm.add_h, wb = (int)b * prm.mul_w + prm.add_w;
+            voff = 4u * (uint32_t)((int)n * prm.Ct * prm.Ht * prm.Wt + hb * prm.Wt + wb + prm.shift_thread);
+            uint32_t okh = 0, okw = 0;
+            for (int r = 0; r < prm.n_tap_h; ++r)
+                if ((unsigned)(hb + prm.dir * r) < (unsigned)prm.Ht) okh |= 1u << r;
+            for (int q = 0; q < prm.n_tap_w; ++q)
+                if ((unsigned)(wb + prm.dir * q) < (unsigned)prm.Wt) okw |= 1u << q;
+            if (SMALL) {
+                uint32_t ok = 0;
+                for (int r = 0; r < prm.n_tap_h; ++r)
+                    if ((okh >> r) & 1u) ok |= okw << (r * prm.n_tap_w);
+                nmask = ~ok | 0x80000000u;
+            } else {
+                nmask = ~okh | 0x80000000u;
+                nmask_w = ~okw;
+            }
         }
     }
     __device__ __forceinline__ void fetch(int k0, int k_end, float (&r)[NE]) const
     {
-        uint32_t off[NE];
+        uint32_t vo[NE], so[NE];
 #pragma unroll
         for (int i = 0; i < NE; ++i) {
-            const int kk = k0 + row0 + RP * i;  // wave-uniform
+            const int kk = k0 + row0 + RP * i;  // wave-uniform: everything up to `so` is scalar
             uint32_t c, tap, tr, ts;
             p->taps.divmod((uint32_t)kk, c, tap);
             p->taps_w.divmod(tap, tr, ts);
-            const int dr = p->dir * (int)tr, ds = p->dir * (int)ts;
-            const int rowoff = ((int)c * p->Ht + dr) * p->Wt + ds;                       // scalar
-            const int hlim = kk < k_end ? p->Ht : 0;                                     // scalar: row off -> no tap fits
-            const bool ok = (unsigned)(hb + dr) < (unsigned)hlim && (unsigned)(wb + ds) < (unsigned)p->Wt;
-            off[i] = ok ? (uint32_t)(base + rowoff) * 4u : kOob;
+            const uint32_t dead = (uint32_t)((k_end - 1 - kk) >> 31);  // all ones for rows past the end
+            so[i] = ~dead & (4u * (uint32_t)(((int)c * p->Ht + p->dir * (int)tr) * p->Wt + p->dir * (int)ts + p->shift_row));
+            if (SMALL) {
+                const uint32_t bit = tap | (dead & 31u);
+                vo[i] = ((nmask >> bit) << 31) | voff;
+            } else {
+                const uint32_t bit = tr | (dead & 31u);
+                vo[i] = (((nmask >> bit) | (nmask_w >> ts)) << 31) | voff;
+            }
         }
 #pragma unroll
-        for (int i = 0; i < NE; ++i) r[i] = buf_load(rsrc, off[i]);
+        for (int i = 0; i < NE; ++i)
+            r[i] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc, (int)vo[i], (int)so[i], 0));
     }
     __device__ __forceinline__ void commit(float *lds, const float (&r)[NE]) const
     {
@@ -173,6 +204,8 @@ struct GatherNLane {
         for (int i = 0; i < NE; ++i) lds[(row0 + RP * i) * LD + col] = r[i];
     }
 };
+template <int TD> using GatherNLane = GatherNLaneT<TD, true>;
+template <int TD> using GatherNLaneBig = GatherNLaneT<TD, false>;
 
 // Lanes along the reduction dimension.  Element (kk, j) lives at  t[rowoff(kk) + coloff(j)]  and
 // is present when  rowok(kk) && colok(j) && window(kk, j).  The decode of kk happens once per
@@ -207,6 +240,7 @@ struct KLaneT {
     int kl, c0;
     int coff[NE];        // < 0 marks an out-of-extent tile position
     int crs[NE];         // MODE 2: tap (r << 16 | s)
+    uint32_t voff0[NE];  // MODE 0: byte offset of (row kl, this tile position), kOob if out of extent
 
     __device__ __forceinline__ void init(const KLaneParams &prm, int origin, int extent)
     {
@@ -230,10 +264,19 @@ struct KLaneT {
             } else {
                 coff[i] = j * prm.col_stride;
             }
+            voff0[i] = coff[i] < 0 ? kOob : 4u * (uint32_t)(kl * prm.row_stride + coff[i]);
         }
     }
     __device__ __forceinline__ void fetch(int k0, int k_end, float (&r)[NE]) const
     {
+        if (MODE == 0 && k0 + kBK <= k_end) {
+            // full step of a dense matrix: per-thread offsets are fixed, the step is a scalar offset
+            const uint32_t so = 4u * (uint32_t)(k0 * p->row_stride);
+#pragma unroll
+            for (int i = 0; i < NE; ++i)
+                r[i] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc, (int)voff0[i], (int)so, 0));
+            return;
+        }
         const int kk = k0 + kl;
         const bool rowok = kk < k_end;
         int roff = 0, hb = 0, wb = 0;
