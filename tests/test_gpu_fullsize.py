@@ -1,0 +1,94 @@
+"""GPU parity at full workload sizes: the configuration the WR planner picks under the
+benchmark's limits (so the launch shapes bench.py times), checked on sampled output elements
+whose exact fp64 reduction the oracle computes one by one."""
+import numpy as np
+import pytest
+
+from oracle import conv as oc
+from paper_1804_04806_amd import synth, ucd
+from hip_helpers import oracle_layer, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+MIB = 1 << 20
+
+
+def unique(layers):
+    seen, out = set(), []
+    for i, s in enumerate(layers):
+        key = (s.N, s.C, s.H, s.W, s.K, s.R, s.S, s.stride, s.pad)
+        if key not in seen:
+            seen.add(key)
+            out.append((i, s))
+    return out
+
+
+ALEXNET = [(i, s, 64 * MIB, ucd.POLICY_ALL) for i, s in unique(synth.config_alexnet(256))]
+RESNET18 = [(i, s, 64 * MIB, ucd.POLICY_POW2) for i, s in unique(synth.config_resnet18(256))]
+DENSENET = [(i, s, 8 * MIB, ucd.POLICY_POW2) for i, s in unique(synth.config_densenet_block(64))
+            if s.name in ("l0.1x1", "l0.3x3", "l11.1x1")]
+RESNET50 = [(i, s, 64 * MIB, ucd.POLICY_POW2) for i, s in unique(synth.config_resnet50(256))
+            if s.name in ("s1b0.expand", "s4b0.reduce", "s4b0.conv3x3", "s4b0.proj")]
+SMALL = [(0, synth.config_small()[0], 64 * 1024, ucd.POLICY_ALL), (0, synth.config_small()[0], 256 * 1024, ucd.POLICY_ALL),
+         (0, synth.config_small()[0], MIB, ucd.POLICY_ALL)]
+
+
+def check_layer(idx, s, limit, policy, n_samples=1500, n_filter_samples=150):
+    import torch
+    dev = torch.device("cuda:0")
+    desc = ucd.layer(s)
+    L = oracle_layer(s)
+    x, w, dy = synth.make_x(s, 1, idx), synth.make_w(s, 1, idx), synth.make_dy(s, 1, idx)
+    xd, wd, dyd = (torch.from_numpy(a).to(dev) for a in (x, w, dy))
+    ws = torch.empty(max(limit, 4) // 4, dtype=torch.float32, device=dev)
+    out_y = torch.empty(s.y_shape, dtype=torch.float32, device=dev)
+    out_dx = torch.empty(s.x_shape, dtype=torch.float32, device=dev)
+    out_dw = torch.empty(s.w_shape, dtype=torch.float32, device=dev)
+    pf = ucd.ucd_plan(desc, ucd.FWD, limit, policy, xd, wd, out_y, ws)
+    pd = ucd.ucd_plan(desc, ucd.BWD_DATA, limit, policy, out_dx, wd, dyd, ws)
+    pw = ucd.ucd_plan(desc, ucd.BWD_FILTER, limit, policy, xd, out_dw, dyd, ws)
+    for p in (pf, pd, pw):
+        micro, _, need = p.query()
+        assert sum(b for _, b in micro) == s.N and need <= limit
+    out_y.fill_(float("nan")); out_dx.fill_(float("nan")); out_dw.fill_(float("nan")); ws.fill_(float("nan"))
+    ucd.ucd_conv_fwd(pf, xd, wd, out_y, ws)
+    ucd.ucd_conv_bwd_data(pd, dyd, wd, out_dx, ws)
+    ucd.ucd_conv_bwd_filter(pw, xd, dyd, out_dw, 0.0, ws)
+    torch.cuda.synchronize()
+    y, dx, dw = out_y.cpu().numpy(), out_dx.cpu().numpy(), out_dw.cpu().numpy()
+    del xd, dyd, out_y, out_dx, ws
+    assert np.isfinite(y).all() and np.isfinite(dx).all() and np.isfinite(dw).all()
+    x64, w64, dy64 = x.astype(np.float64), w.astype(np.float64), dy.astype(np.float64)
+
+    def tol(p):
+        return 1e-3 if any(a == ucd.ALGO_WINOGRAD for a, _ in p.micro) else 1e-5
+
+    iy = synth.sample_indices(y.size, n_samples, seed=1)
+    e = rel_l2(y.ravel()[iy], oc.conv_fwd_at(L, x64, w64, iy))
+    assert e <= tol(pf), ("fwd", s.name, pf.micro[:4], e)
+    ix = synth.sample_indices(dx.size, n_samples, seed=2)
+    e = rel_l2(dx.ravel()[ix], oc.conv_bwd_data_at(L, dy64, w64, ix))
+    assert e <= tol(pd), ("bwd_data", s.name, pd.micro[:4], e)
+    iw = synth.sample_indices(dw.size, n_filter_samples, seed=3)
+    e = rel_l2(dw.ravel()[iw], oc.conv_bwd_filter_at(L, x64, dy64, iw))
+    assert e <= tol(pw), ("bwd_filter", s.name, pw.micro[:4], e)
+
+
+@pytest.mark.parametrize("idx,s,limit,policy", SMALL, ids=lambda v: str(v) if isinstance(v, int) else getattr(v, "name", None))
+def test_small_config_planned(idx, s, limit, policy):
+    check_layer(idx, s, limit, policy, n_samples=10 ** 9, n_filter_samples=10 ** 9)
+
+
+@pytest.mark.parametrize("idx,s,limit,policy", ALEXNET, ids=lambda v: getattr(v, "name", None))
+def test_alexnet_full_batch_planned(idx, s, limit, policy):
+    check_layer(idx, s, limit, policy)
+
+
+@pytest.mark.parametrize("idx,s,limit,policy", RESNET18, ids=lambda v: getattr(v, "name", None))
+def test_resnet18_full_batch_planned(idx, s, limit, policy):
+    check_layer(idx, s, limit, policy, n_samples=800, n_filter_samples=60)
+
+
+@pytest.mark.parametrize("idx,s,limit,policy", DENSENET + RESNET50, ids=lambda v: getattr(v, "name", None))
+def test_densenet_resnet50_layers_planned(idx, s, limit, policy):
+    check_layer(idx, s, limit, policy, n_samples=800, n_filter_samples=60)

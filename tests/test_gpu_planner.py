@@ -1,0 +1,148 @@
+"""On-device benchmark + WR / WD planning: the plan's cost must equal, exactly, the exhaustive
+optimum over the very table the library measured (dumped from its cache), and the plan must
+execute to the oracle's result."""
+import numpy as np
+import pytest
+
+from oracle import planner as P
+from paper_1804_04806_amd import synth, ucd
+from paper_1804_04806_amd.synth import Shape
+from hip_helpers import inputs, rel_l2, run_oracle
+
+pytestmark = pytest.mark.gpu
+
+
+def device_buffers(s, seed=0):
+    import torch
+    dev = torch.device("cuda:0")
+    x, w, dy = inputs(s, seed)
+    return (x, w, dy), tuple(torch.from_numpy(a).to(dev) for a in (x, w, dy))
+
+
+def measured_table(desc, op, B):
+    t, ws = ucd.ucd_bench_table(desc, op, B)
+    return t, ws
+
+
+@pytest.mark.parametrize("limit", [64 * 1024, 160 * 1024, 256 * 1024, 1 << 20])
+def test_small_config_plan_equals_brute_force_on_measured_table(limit):
+    """N=8 under limits that admit nothing but implicit GEMM (64 KiB), im2col at b=1 (160 KiB),
+    Winograd at b=1 (256 KiB), several sizes (1 MiB)."""
+    import torch
+    s = synth.config_small()[0]
+    desc = ucd.layer(s)
+    (x, w, dy), (xd, wd, dyd) = device_buffers(s)
+    ws = torch.empty(max(limit, 4) // 4, dtype=torch.float32, device=xd.device)
+    ucd.ucd_bench_clear()
+    for op in (ucd.FWD, ucd.BWD_DATA, ucd.BWD_FILTER):
+        out = {ucd.FWD: torch.empty(s.y_shape, device=xd.device), ucd.BWD_DATA: torch.empty(s.x_shape, device=xd.device),
+               ucd.BWD_FILTER: torch.empty(s.w_shape, device=xd.device)}[op]
+        bufs = {ucd.FWD: (xd, wd, out), ucd.BWD_DATA: (out, wd, dyd), ucd.BWD_FILTER: (xd, out, dyd)}[op]
+        plans = {pol: ucd.ucd_plan(desc, op, limit, pol, *bufs, ws) for pol in (ucd.POLICY_ALL, ucd.POLICY_POW2, ucd.POLICY_UNDIVIDED)}
+        t, m = measured_table(desc, op, s.N)
+        for pol, plan in plans.items():
+            micro, cost, need = plan.query()
+            assert cost == P.wr_optimum(s.N, limit, pol, t, m) == P.wr_optimum_explicit(s.N, limit, pol, t, m)
+            assert need <= limit and sum(b for _, b in micro) == s.N
+            for a, b in micro:
+                assert m[a][b] <= limit and t[a][b] != ucd.TIME_INF
+        assert plans[ucd.POLICY_ALL].cost_ns <= plans[ucd.POLICY_POW2].cost_ns <= plans[ucd.POLICY_UNDIVIDED].cost_ns
+        # feasibility of each algorithm at b=1 follows the workspace formulas
+        assert (t[ucd.ALGO_IM2COL][1] != ucd.TIME_INF) == (limit >= 147456)
+        if op != ucd.BWD_FILTER:
+            assert (t[ucd.ALGO_WINOGRAD][1] != ucd.TIME_INF) == (limit >= 229376)
+        # and the planned configuration computes the right thing
+        plan = plans[ucd.POLICY_ALL]
+        if op == ucd.FWD:
+            ucd.ucd_conv_fwd(plan, xd, wd, out, ws)
+        elif op == ucd.BWD_DATA:
+            ucd.ucd_conv_bwd_data(plan, dyd, wd, out, ws)
+        else:
+            ucd.ucd_conv_bwd_filter(plan, xd, dyd, out, 0.0, ws)
+        torch.cuda.synchronize()
+        assert rel_l2(out.cpu().numpy(), run_oracle(s, op, x=x, w=w, dy=dy)) <= 1e-3
+
+
+def test_b32_all_policy_equals_brute_force():
+    import torch
+    s = Shape(32, 64, 14, 14, 96, 3, 3, 1, 1, "b32")
+    desc = ucd.layer(s)
+    _, (xd, wd, dyd) = device_buffers(s)
+    limit = 4 << 20
+    ws = torch.empty(limit // 4, dtype=torch.float32, device=xd.device)
+    y = torch.empty(s.y_shape, device=xd.device)
+    ucd.ucd_bench_clear()
+    plan = ucd.ucd_plan(desc, ucd.FWD, limit, ucd.POLICY_ALL, xd, wd, y, ws)
+    t, m = measured_table(desc, ucd.FWD, 32)
+    assert plan.cost_ns == P.wr_optimum(32, limit, P.ALL, t, m)     # 8,349 divisions
+    # a second identical layer is planned from the cache: same table, same cost, no new timings
+    plan2 = ucd.ucd_plan(desc, ucd.FWD, limit, ucd.POLICY_ALL, xd, wd, y, ws)
+    assert measured_table(desc, ucd.FWD, 32) == (t, m) and plan2.cost_ns == plan.cost_ns
+    # a tighter limit can only cost more; zero limit leaves implicit GEMM alone
+    tight = ucd.ucd_plan(desc, ucd.FWD, 0, ucd.POLICY_ALL, xd, wd, y, None)
+    assert tight.cost_ns >= plan.cost_ns and all(a == ucd.ALGO_IMPLICIT for a, _ in tight.micro)
+
+
+def test_b256_pow2_equals_brute_force_on_measured_table():
+    import torch
+    s = synth.config_alexnet(256)[4]
+    desc = ucd.layer(s)
+    _, (xd, wd, dyd) = device_buffers(s)
+    limit = 64 << 20
+    ws = torch.empty(limit // 4, dtype=torch.float32, device=xd.device)
+    dx = torch.empty(s.x_shape, device=xd.device)
+    plan = ucd.ucd_plan(desc, ucd.BWD_DATA, limit, ucd.POLICY_POW2, dx, wd, dyd, ws)
+    t, m = measured_table(desc, ucd.BWD_DATA, 256)
+    assert plan.cost_ns == P.wr_optimum(256, limit, P.POW2, t, m)   # 692,004 binary partitions
+
+
+def test_wd_plan_on_device_matches_enumeration_and_executes():
+    """Three kernels of the small layer sharing one budget: the library's WD choice equals the
+    exhaustive optimum over unpruned configurations of the measured tables, segments are
+    disjoint, and each plan runs in its own segment."""
+    import torch
+    s = Shape(4, 16, 16, 16, 32, 3, 3, 1, 1, "wd-small")
+    desc = ucd.layer(s)
+    (x, w, dy), (xd, wd, dyd) = device_buffers(s)
+    budget = 700 * 1024
+    ws = torch.empty(budget // 4, dtype=torch.float32, device=xd.device)
+    sx, sw, sy = torch.empty_like(xd), torch.empty_like(wd), torch.empty_like(dyd)
+    ops = [ucd.FWD, ucd.BWD_DATA, ucd.BWD_FILTER]
+    ucd.ucd_bench_clear()
+    plans, offs = ucd.ucd_plan_wd([desc] * 3, ops, budget, ucd.POLICY_ALL, sx, sw, sy, ws)
+    cfgs = []
+    for op in ops:
+        t, m = measured_table(desc, op, s.N)
+        m256 = [[v if v == ucd.WS_NA else (v + 255) // 256 * 256 for v in row] for row in m]
+        cfgs.append([(c[0], c[1]) for c in P.all_configurations(s.N, budget, P.ALL, t, m256)])
+    best, _ = P.wd_optimum(cfgs, budget)
+    assert sum(p.cost_ns for p in plans) == best
+    end = 0
+    for p, off in zip(plans, offs):
+        assert off % 256 == 0 and off >= end
+        end = off + p.ws_bytes
+    assert end <= budget
+    outs = [torch.empty(s.y_shape, device=xd.device), torch.empty(s.x_shape, device=xd.device),
+            torch.empty(s.w_shape, device=xd.device)]
+    base = ws.data_ptr()
+    ucd.ucd_conv_fwd(plans[0], xd, wd, outs[0], base + offs[0], plans[0].ws_bytes)
+    ucd.ucd_conv_bwd_data(plans[1], dyd, wd, outs[1], base + offs[1], plans[1].ws_bytes)
+    ucd.ucd_conv_bwd_filter(plans[2], xd, dyd, outs[2], 0.0, base + offs[2], plans[2].ws_bytes)
+    torch.cuda.synchronize()
+    for op, out in zip(ops, outs):
+        assert rel_l2(out.cpu().numpy(), run_oracle(s, op, x=x, w=w, dy=dy)) <= 1e-3
+
+
+def test_workspace_one_byte_short_is_refused():
+    import torch
+    s = synth.config_small()[0]
+    desc = ucd.layer(s)
+    _, (xd, wd, dyd) = device_buffers(s)
+    plan = ucd.ucd_plan_fixed(desc, ucd.FWD, [(ucd.ALGO_IM2COL, 8)])
+    ws = torch.empty(plan.ws_bytes // 4, dtype=torch.float32, device=xd.device)
+    y = torch.zeros(s.y_shape, device=xd.device)
+    with pytest.raises(ucd.UcdError) as e:
+        ucd.ucd_conv_fwd(plan, xd, wd, y, ws, ws_bytes=plan.ws_bytes - 1)
+    assert e.value.status == ucd.E_WS_TOO_SMALL
+    torch.cuda.synchronize()
+    assert float(y.abs().sum()) == 0.0      # nothing was launched
