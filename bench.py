@@ -79,20 +79,40 @@ def time_steps(torch, fn, steps, warmup):
     return (time.perf_counter() - t0) * 1e3 / steps
 
 
-def kernel_class(ucd, s, op, algo, beta_one):
-    """Name of the single kernel a micro-batch run launches, or None if it launches several."""
+def _tile(M, N):
+    """The block tile the library's launcher picks for a GEMM of M rows and N columns."""
+    narrow = N <= 64
+    if M <= 32:
+        return "32x128"
+    if M <= 64 or (M % 128 != 0 and M % 128 <= 64 and M < 256):
+        return "64x64" if narrow else "64x128"
+    return "128x64" if narrow else "128x128"
+
+
+def kernel_class(ucd, s, op, algo, b):
+    """Name of the single GEMM kernel instantiation an implicit-GEMM micro-batch launches (the
+    names rocprofv3 shows are the C++ template instantiations; this mirrors them), or None if the
+    run launches several kernels (im2col, Winograd, strided BackwardData's phases)."""
     if algo != ucd.ALGO_IMPLICIT:
         return None
+    crs = s.C * s.R * s.S
     if op == ucd.FWD:
-        return "implicit_gemm_nchw"
+        gather = "GatherNLane" if s.R * s.S <= 31 else "GatherNLaneBig"
+        return f"gemm_kernel<Tile<{_tile(s.K, b * s.P * s.Q)}>,KLane0,{gather},EpiNCHW> (implicit fwd)"
     if op == ucd.BWD_DATA:
-        return "implicit_gemm_nchw" if s.stride == 1 else None
-    return "implicit_gemm_filter_atomic" if beta_one else None
+        if s.stride != 1:
+            return None
+        gather = "GatherNLane" if s.R * s.S <= 31 else "GatherNLaneBig"
+        return f"gemm_kernel<Tile<{_tile(s.C, b * s.H * s.W)}>,KLane1,{gather},EpiNCHW> (implicit bwdData)"
+    return f"gemm_kernel<Tile<{_tile(s.K, crs)}>,KLane2,KLane2,EpiAtomic> (implicit bwdFilter)"
 
 
 def dominant_kernel_roofline(torch, ucd, states, plans, ws, reps):
-    """HIP-event timing of every single-kernel micro-batch launch of the planned step, grouped
-    by kernel; returns the roofline object of the group with the largest total time."""
+    """HIP-event timing (events recorded on the launch stream) of every single-kernel micro-batch
+    launch of the planned step, grouped by kernel instantiation; returns the roofline object of
+    the instantiation with the largest total time, and the per-instantiation table.
+    BackwardFilter launches are timed as the accumulating (beta = 1) call, which is the GEMM
+    kernel alone; with beta = 0 a small fill kernel precedes it."""
     groups = {}
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     for st, pl in zip(states, plans):
@@ -100,9 +120,8 @@ def dominant_kernel_roofline(torch, ucd, states, plans, ws, reps):
         x_img, y_img = s.C * s.H * s.W, s.K * s.P * s.Q
         for op in (ucd.FWD, ucd.BWD_DATA, ucd.BWD_FILTER):
             o = 0
-            for i, (algo, b) in enumerate(pl[op].micro):
-                beta = 1.0 if (op == ucd.BWD_FILTER and i > 0) else 0.0
-                cls = kernel_class(ucd, s, op, algo, beta == 1.0)
+            for algo, b in pl[op].micro:
+                cls = kernel_class(ucd, s, op, algo, b)
                 if cls is not None:
                     xo = st.x.view(-1)[o * x_img:]
                     yo = st.y.view(-1)[o * y_img:]
@@ -110,6 +129,7 @@ def dominant_kernel_roofline(torch, ucd, states, plans, ws, reps):
                     dxo = st.dx.view(-1)[o * x_img:]
                     args = {ucd.FWD: (xo, st.w, yo), ucd.BWD_DATA: (dyo, st.w, dxo),
                             ucd.BWD_FILTER: (xo, dyo, st.dw)}[op]
+                    beta = 1.0 if op == ucd.BWD_FILTER else 0.0
                     tot = 0.0
                     for _ in range(reps):
                         e0.record()
@@ -123,13 +143,18 @@ def dominant_kernel_roofline(torch, ucd, states, plans, ws, reps):
                     g["launches"] += 1
                 o += b
     if not groups:
-        return None
+        return None, []
+    table = [{"kernel": k, "launches_per_step": g["launches"], "ms_per_step": round(g["ms"], 4),
+              "avg_launch_ms": round(g["ms"] / g["launches"], 4),
+              "tflops": round(g["flops"] / (g["ms"] * 1e-3) / 1e12, 2)}
+             for k, g in sorted(groups.items(), key=lambda kv: -kv[1]["ms"])]
     name, g = max(groups.items(), key=lambda kv: kv[1]["ms"])
     achieved = g["flops"] / (g["ms"] * 1e-3) / 1e12
-    return {"bound": "mfma", "kernel": name, "achieved": round(achieved, 2), "peak": FP32_MFMA_PEAK_TFLOPS,
+    roof = {"bound": "mfma", "kernel": name, "achieved": round(achieved, 2), "peak": FP32_MFMA_PEAK_TFLOPS,
             "unit": "TFLOP/s", "frac": round(achieved / FP32_MFMA_PEAK_TFLOPS, 4), "traffic": None,
             "launches_per_step": g["launches"], "avg_launch_ms": round(g["ms"] / g["launches"], 4),
             "flops_per_launch": g["flops"] / g["launches"]}
+    return roof, table
 
 
 def cpu_baseline(layers, n_samples):
@@ -187,7 +212,7 @@ def main():
     ms = time_steps(torch, lambda: step(plans), args.steps, args.warmup)
 
     tflops = flops_per_step / (ms * 1e-3) / 1e12
-    roof = dominant_kernel_roofline(torch, ucd, states, plans, ws, reps=5)
+    roof, kernel_table = dominant_kernel_roofline(torch, ucd, states, plans, ws, reps=5)
 
     plan_report = []
     for st, p, u in zip(states, plans, undiv):
@@ -218,6 +243,7 @@ def main():
         "plan_seconds": round(t_plan, 2), "plan_seconds_undivided": round(t_plan_undiv, 2),
         "gflop_per_step": round(flops_per_step / 1e9, 1),
         "roofline": roof,
+        "kernels": kernel_table,
         "cpu_baseline": None if args.no_cpu_baseline else cpu_baseline(layers, args.cpu_samples),
         "plans": plan_report,
     }
