@@ -150,7 +150,7 @@ hipError_t im2col_bwd_filter(const Dims &d, int b, const float *x, const float *
     KLaneParams pb{};
     pb.t = ws; pb.bytes = (uint32_t)im2col_ws_bytes(d, b); pb.row_stride = 1; pb.col_stride = col_ld(d, b);
     EpiDenseParams pe{dw, d.crs()};
-    return launch_gemm<KLane2, KLane0, EpiAtomic>(pa, pb, pe, g, s);
+    return launch_gemm<DyKLane, KLane0, EpiAtomic>(pa, pb, pe, g, s);
 }
 
 }  // namespace ucd

@@ -62,6 +62,7 @@ hipError_t implicit_bwd_data(const Dims &d, int b, const float *dy, const float 
             pa.taps = FastDiv(Ra * Sc); pa.taps_w = FastDiv(Sc);
             pa.k_stride = d.crs(); pa.s_mem = d.S;
             pa.tap_add_h = a; pa.tap_mul_h = d.sh; pa.tap_add_w = c; pa.tap_mul_w = d.sw;
+            pa.unit_taps = (d.sh == 1 && d.sw == 1) ? 1 : 0;
             GatherParams pb{};
             pb.t = dy; pb.bytes = ybytes(d, b); pb.Ct = d.K; pb.Ht = d.P; pb.Wt = d.Q;
             pb.grid_hw = FastDiv(Hh * Ww); pb.grid_w = FastDiv(Ww);
@@ -73,8 +74,8 @@ hipError_t implicit_bwd_data(const Dims &d, int b, const float *dy, const float 
             EpiNCHWParams pe{};
             pe.out = dx; pe.grid_hw = pb.grid_hw; pe.grid_w = pb.grid_w;
             pe.M = d.C; pe.HWo = d.H * d.W; pe.Wo = d.W; pe.h0 = h0; pe.hs = d.sh; pe.w0 = w0; pe.ws = d.sw;
-            hipError_t e = Ra * Sc <= 31 ? launch_gemm<KLane1, GatherNLane, EpiNCHW>(pa, pb, pe, g, s)
-                                         : launch_gemm<KLane1, GatherNLaneBig, EpiNCHW>(pa, pb, pe, g, s);
+            hipError_t e = Ra * Sc <= 31 ? launch_gemm<FilterKLane, GatherNLane, EpiNCHW>(pa, pb, pe, g, s)
+                                         : launch_gemm<FilterKLane, GatherNLaneBig, EpiNCHW>(pa, pb, pe, g, s);
             if (e != hipSuccess) return e;
         }
     return hipSuccess;
@@ -113,8 +114,9 @@ hipError_t implicit_bwd_filter(const Dims &d, int b, const float *x, const float
     pb.col_taps = FastDiv(d.R * d.S); pb.col_taps_w = FastDiv(d.S);
     pb.n_stride = d.C * d.H * d.W; pb.Ht = d.H; pb.Wt = d.W;
     pb.mul_h = d.sh; pb.add_h = -d.ph; pb.mul_w = d.sw; pb.add_w = -d.pw;
+    pb.shift = d.ph * d.W + d.pw;
     EpiDenseParams pe{dw, d.crs()};
-    return launch_gemm<KLane2, KLane2, EpiAtomic>(pa, pb, pe, g, s);
+    return launch_gemm<DyKLane, XKLane, EpiAtomic>(pa, pb, pe, g, s);
 }
 
 }  // namespace ucd

@@ -175,7 +175,8 @@ struct GatherNLaneT {
             }
         }
     }
-    __device__ __forceinline__ void fetch(int k0, int k_end, float (&r)[NE]) const
+    template <class Peer>
+    __device__ __forceinline__ void fetch(int k0, int k_end, float (&r)[NE], const Peer &) const
     {
         uint32_t vo[NE], so[NE];
 #pragma unroll
@@ -207,30 +208,31 @@ struct GatherNLaneT {
 template <int TD> using GatherNLane = GatherNLaneT<TD, true>;
 template <int TD> using GatherNLaneBig = GatherNLaneT<TD, false>;
 
-// Lanes along the reduction dimension.  Element (kk, j) lives at  t[rowoff(kk) + coloff(j)]  and
-// is present when  rowok(kk) && colok(j) && window(kk, j).  The decode of kk happens once per
-// step per thread (16 consecutive lanes share a tile position), that of the thread's NE tile
-// positions once per workgroup.
-//   MODE 0 (plain):   rowoff = kk * row_stride,  coloff = j * col_stride          (dense matrices)
-//   MODE 1 (filter):  kk -> (k, r, s):  rowoff = k*k_stride + (tap_add_h + tap_mul_h*r)*s_mem + tap_add_w + tap_mul_w*s,
-//                     coloff = j * col_stride                         (BackwardData's A operand)
-//   MODE 2 (pixels):  kk -> (n, a, b) over a grid:  rowoff = n*n_stride + (a*mul_h+add_h)*Wt + b*mul_w+add_w,
-//                     j -> (c, r, s): coloff = (c*Ht + r)*Wt + s, window = tap inside the plane
-//                     (BackwardFilter's operands: x with real taps, dy with a 1x1 "tap")
+// ---- loaders with lanes along the reduction dimension -------------------------------------------
+// 16 consecutive lanes take the 16 reduction rows of a step for one tile position; a thread owns
+// NE = TD/16 tile positions.  Used where memory is contiguous along the reduction index: filter
+// matrices, and BackwardFilter's dy / x (contiguous along the pixel index).  The address of
+// element (kk, j) is split into a row part computed once per step per thread and a column part
+// fixed per thread, so that the per-element work is one add (plus the window test for x).
+// "Reads as zero" is signalled either by an additive flag at bit 30 (both parts are below 1 GiB,
+// so any flagged sum lands in [1 GiB, 4 GiB) and outside a resource of at most 1 GiB) or, for the
+// windowed loader, by a mask bit moved to bit 31.
+
+constexpr uint32_t kFlag = 0x40000000u;
+
 struct KLaneParams {
     const float *t;
     uint32_t bytes;
-    int row_stride, col_stride;
-    // MODE 1
-    FastDiv taps, taps_w;
-    int k_stride, s_mem, tap_mul_h, tap_add_h, tap_mul_w, tap_add_w;
-    // MODE 2
-    FastDiv grid_hw, grid_w, col_taps, col_taps_w;
-    int n_stride, Ht, Wt, mul_h, add_h, mul_w, add_w;
+    int row_stride, col_stride;                        // dense: element (kk, j) = t[kk*row_stride + j*col_stride]
+    FastDiv taps, taps_w;                              // filter gather: kk -> (k, tap) -> (r, s)
+    int k_stride, s_mem, tap_mul_h, tap_add_h, tap_mul_w, tap_add_w, unit_taps;
+    FastDiv grid_hw, grid_w, col_taps, col_taps_w;     // pixel rows: kk -> (n, a, b); columns j -> (c, r, s)
+    int n_stride, Ht, Wt, mul_h, add_h, mul_w, add_w, shift;
 };
 
-template <int TD, int MODE>
-struct KLaneT {
+// Dense matrix, element (kk, j) = t[kk*row_stride + j*col_stride]  (operand limit 2 GiB).
+template <int TD>
+struct KLane0 {
     static constexpr int CP = kThreads / kBK;  // tile positions per pass (16)
     static constexpr int NE = TD / CP;
     static constexpr int LD = TD + kPad;
@@ -238,75 +240,34 @@ struct KLaneT {
     const KLaneParams *p;
     __amdgpu_buffer_rsrc_t rsrc;
     int kl, c0;
-    int coff[NE];        // < 0 marks an out-of-extent tile position
-    int crs[NE];         // MODE 2: tap (r << 16 | s)
-    uint32_t voff0[NE];  // MODE 0: byte offset of (row kl, this tile position), kOob if out of extent
+    uint32_t voff0[NE];  // byte offset of (row kl, this tile position), kOob if out of extent
 
     __device__ __forceinline__ void init(const KLaneParams &prm, int origin, int extent)
     {
         p = &prm;
         rsrc = make_rsrc(prm.t, prm.bytes);
-        const int tid = threadIdx.x;
-        kl = tid % kBK;
-        c0 = tid / kBK;
+        kl = threadIdx.x % kBK;
+        c0 = threadIdx.x / kBK;
 #pragma unroll
         for (int i = 0; i < NE; ++i) {
             const int j = origin + c0 + CP * i;
-            crs[i] = 0;
-            if (j >= extent) {
-                coff[i] = -1;
-            } else if (MODE == 2) {
-                uint32_t c, tap, r, s;
-                prm.col_taps.divmod((uint32_t)j, c, tap);
-                prm.col_taps_w.divmod(tap, r, s);
-                crs[i] = (int)((r << 16) | s);
-                coff[i] = ((int)c * prm.Ht + (int)r) * prm.Wt + (int)s;
-            } else {
-                coff[i] = j * prm.col_stride;
-            }
-            voff0[i] = coff[i] < 0 ? kOob : 4u * (uint32_t)(kl * prm.row_stride + coff[i]);
+            voff0[i] = j >= extent ? kOob : 4u * (uint32_t)(kl * prm.row_stride + j * prm.col_stride);
         }
     }
-    __device__ __forceinline__ void fetch(int k0, int k_end, float (&r)[NE]) const
+    template <class Peer>
+    __device__ __forceinline__ void fetch(int k0, int k_end, float (&r)[NE], const Peer &) const
     {
-        if (MODE == 0 && k0 + kBK <= k_end) {
-            // full step of a dense matrix: per-thread offsets are fixed, the step is a scalar offset
-            const uint32_t so = 4u * (uint32_t)(k0 * p->row_stride);
+        const uint32_t so = 4u * (uint32_t)(k0 * p->row_stride);  // scalar step offset
+        if (k0 + kBK <= k_end) {
 #pragma unroll
             for (int i = 0; i < NE; ++i)
                 r[i] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc, (int)voff0[i], (int)so, 0));
-            return;
-        }
-        const int kk = k0 + kl;
-        const bool rowok = kk < k_end;
-        int roff = 0, hb = 0, wb = 0;
-        if (MODE == 0) {
-            roff = kk * p->row_stride;
-        } else if (MODE == 1) {
-            uint32_t k, tap, tr, ts;
-            p->taps.divmod((uint32_t)kk, k, tap);
-            p->taps_w.divmod(tap, tr, ts);
-            roff = (int)k * p->k_stride + (p->tap_add_h + p->tap_mul_h * (int)tr) * p->s_mem + p->tap_add_w +
-                   p->tap_mul_w * (int)ts;
-        } else {
-            uint32_t n, rest, a, b;
-            p->grid_hw.divmod((uint32_t)kk, n, rest);
-            p->grid_w.divmod(rest, a, b);
-            hb = (int)a * p->mul_h + p->add_h;
-            wb = (int)b * p->mul_w + p->add_w;
-            roff = (int)n * p->n_stride + hb * p->Wt + wb;
-        }
-        uint32_t off[NE];
+        } else {  // last, partial step: rows past the end read as zero
+            const bool rowok = k0 + kl < k_end;
 #pragma unroll
-        for (int i = 0; i < NE; ++i) {
-            bool ok = rowok && coff[i] >= 0;
-            if (MODE == 2)
-                ok = ok && (unsigned)(hb + (crs[i] >> 16)) < (unsigned)p->Ht &&
-                     (unsigned)(wb + (crs[i] & 0xffff)) < (unsigned)p->Wt;
-            off[i] = ok ? (uint32_t)(roff + coff[i]) * 4u : kOob;
+            for (int i = 0; i < NE; ++i)
+                r[i] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc, (int)(rowok ? voff0[i] : kOob), (int)so, 0));
         }
-#pragma unroll
-        for (int i = 0; i < NE; ++i) r[i] = buf_load(rsrc, off[i]);
     }
     __device__ __forceinline__ void commit(float *lds, const float (&r)[NE]) const
     {
@@ -314,9 +275,137 @@ struct KLaneT {
         for (int i = 0; i < NE; ++i) lds[kl * LD + c0 + CP * i] = r[i];
     }
 };
-template <int TD> using KLane0 = KLaneT<TD, 0>;
-template <int TD> using KLane1 = KLaneT<TD, 1>;
-template <int TD> using KLane2 = KLaneT<TD, 2>;
+
+// BackwardData's A operand: element (kk -> (k, r, s), j = c) = w[k, c, tap_add_h + tap_mul_h*r, tap_add_w + tap_mul_w*s]
+// (the filter taps of one stride phase).  Operand limit 1 GiB.
+template <int TD>
+struct FilterKLane {
+    static constexpr int CP = kThreads / kBK;
+    static constexpr int NE = TD / CP;
+    static constexpr int LD = TD + kPad;
+    struct Regs { float r[NE]; };
+    const KLaneParams *p;
+    __amdgpu_buffer_rsrc_t rsrc;
+    int kl, c0;
+    uint32_t coffb[NE];
+
+    __device__ __forceinline__ void init(const KLaneParams &prm, int origin, int extent)
+    {
+        p = &prm;
+        rsrc = make_rsrc(prm.t, prm.bytes);
+        kl = threadIdx.x % kBK;
+        c0 = threadIdx.x / kBK;
+#pragma unroll
+        for (int i = 0; i < NE; ++i) {
+            const int j = origin + c0 + CP * i;
+            coffb[i] = j >= extent ? kFlag : 4u * (uint32_t)(j * prm.col_stride);
+        }
+    }
+    template <class Peer>
+    __device__ __forceinline__ void fetch(int k0, int k_end, float (&r)[NE], const Peer &) const
+    {
+        const int kk = k0 + kl;
+        uint32_t k, tap;
+        p->taps.divmod((uint32_t)kk, k, tap);
+        int roff;
+        if (p->unit_taps) {
+            roff = (int)k * p->k_stride + (int)tap;
+        } else {
+            uint32_t tr, ts;
+            p->taps_w.divmod(tap, tr, ts);
+            roff = (int)k * p->k_stride + (p->tap_add_h + p->tap_mul_h * (int)tr) * p->s_mem + p->tap_add_w +
+                   p->tap_mul_w * (int)ts;
+        }
+        const uint32_t rterm = kk < k_end ? 4u * (uint32_t)roff : kFlag;
+#pragma unroll
+        for (int i = 0; i < NE; ++i) r[i] = buf_load(rsrc, rterm + coffb[i]);
+    }
+    __device__ __forceinline__ void commit(float *lds, const float (&r)[NE]) const
+    {
+#pragma unroll
+        for (int i = 0; i < NE; ++i) lds[kl * LD + c0 + CP * i] = r[i];
+    }
+};
+
+// BackwardFilter's operands: reduction row kk -> (n, a, b) over the output-pixel grid, tile
+// position j -> (c, r, s); element = T[n, c, a*mul_h + add_h + r, b*mul_w + add_w + s].
+//   WINDOW = false: dy (a 1x1 "tap", always inside): flags are additive, operand limit 1 GiB.
+//   WINDOW = true : x; per step the thread builds, from its pixel, one mask per axis of the taps
+//                   that fall outside the image; bit 31 of the row mask is always set and serves
+//                   out-of-extent tile positions (r = 31) and rows past the end (mask = all ones).
+// The x loader reuses the pixel decode its peer (the dy loader of the same step) has just done.
+template <int TD, bool WINDOW>
+struct PixelKLane {
+    static constexpr int CP = kThreads / kBK;
+    static constexpr int NE = TD / CP;
+    static constexpr int LD = TD + kPad;
+    struct Regs { float r[NE]; };
+    const KLaneParams *p;
+    __amdgpu_buffer_rsrc_t rsrc;
+    int kl, c0;
+    uint32_t coffb[NE];
+    uint32_t rs[NE];          // WINDOW: r | s << 8
+    mutable uint32_t n_, rest_;  // decode of this step's reduction row, for the peer
+
+    __device__ __forceinline__ void init(const KLaneParams &prm, int origin, int extent)
+    {
+        p = &prm;
+        rsrc = make_rsrc(prm.t - prm.shift, prm.bytes + 4u * (uint32_t)prm.shift);
+        kl = threadIdx.x % kBK;
+        c0 = threadIdx.x / kBK;
+        n_ = rest_ = 0;
+#pragma unroll
+        for (int i = 0; i < NE; ++i) {
+            const int j = origin + c0 + CP * i;
+            if (j < extent) {
+                uint32_t c, tap, r, s;
+                prm.col_taps.divmod((uint32_t)j, c, tap);
+                prm.col_taps_w.divmod(tap, r, s);
+                rs[i] = r | (s << 8);
+                coffb[i] = 4u * (uint32_t)(((int)c * prm.Ht + (int)r) * prm.Wt + (int)s);
+            } else {
+                rs[i] = 31u;                     // WINDOW: bit 31 of the row mask is always set
+                coffb[i] = WINDOW ? 0u : kFlag;  // otherwise: additive flag
+            }
+        }
+    }
+    template <class Peer>
+    __device__ __forceinline__ void fetch(int k0, int k_end, float (&r)[NE], const Peer &peer) const
+    {
+        const int kk = k0 + kl;
+        const bool rowok = kk < k_end;
+        if constexpr (!WINDOW) {
+            p->grid_hw.divmod((uint32_t)kk, n_, rest_);
+            // grid is the tensor's own plane here: (a, b) -> a*Wt + b == rest
+            const uint32_t rterm = rowok ? 4u * (uint32_t)((int)n_ * p->n_stride + (int)rest_) : kFlag;
+#pragma unroll
+            for (int i = 0; i < NE; ++i) r[i] = buf_load(rsrc, rterm + coffb[i]);
+        } else {
+            uint32_t a, b;
+            p->grid_w.divmod(peer.rest_, a, b);
+            const int hb = (int)a * p->mul_h + p->add_h, wb = (int)b * p->mul_w + p->add_w;
+            const uint32_t rterm = 4u * (uint32_t)((int)peer.n_ * p->n_stride + hb * p->Wt + wb + p->shift);
+            // taps r in [lo, hi) are inside the image; everything else (and bit 31) is masked
+            const int lo_h = min(max(-hb, 0), 31), hi_h = max(min(p->Ht - hb, 31), lo_h);
+            const int lo_w = min(max(-wb, 0), 31), hi_w = max(min(p->Wt - wb, 31), lo_w);
+            uint32_t nrow = ~(((1u << (hi_h - lo_h)) - 1u) << lo_h);
+            const uint32_t ncol = ~(((1u << (hi_w - lo_w)) - 1u) << lo_w);
+            nrow = rowok ? nrow : 0xFFFFFFFFu;
+#pragma unroll
+            for (int i = 0; i < NE; ++i) {
+                const uint32_t t = (nrow >> (rs[i] & 0xffu)) | (ncol >> (rs[i] >> 8));
+                r[i] = buf_load(rsrc, (t << 31) | (rterm + coffb[i]));
+            }
+        }
+    }
+    __device__ __forceinline__ void commit(float *lds, const float (&r)[NE]) const
+    {
+#pragma unroll
+        for (int i = 0; i < NE; ++i) lds[kl * LD + c0 + CP * i] = r[i];
+    }
+};
+template <int TD> using DyKLane = PixelKLane<TD, false>;
+template <int TD> using XKLane = PixelKLane<TD, true>;
 
 // Dense matrix contiguous along the tile dimension:  element (kk, j) = t[kk*ld + j], float4 loads.
 // Requires ld % 4 == 0 and a 16-byte aligned base; columns in [extent, ld) may hold anything.
@@ -348,7 +437,8 @@ struct DenseNLane {
         j_ = origin + col;
         ok_ = j_ < extent;
     }
-    __device__ __forceinline__ void fetch(int k0, int k_end, f32x4 (&r)[NE]) const
+    template <class Peer>
+    __device__ __forceinline__ void fetch(int k0, int k_end, f32x4 (&r)[NE], const Peer &) const
     {
 #pragma unroll
         for (int i = 0; i < NE; ++i) {
@@ -390,7 +480,8 @@ struct DenseNLaneS {
         j_ = origin + col;
         ok_ = j_ < extent;
     }
-    __device__ __forceinline__ void fetch(int k0, int k_end, float (&r)[NE]) const
+    template <class Peer>
+    __device__ __forceinline__ void fetch(int k0, int k_end, float (&r)[NE], const Peer &) const
     {
 #pragma unroll
         for (int i = 0; i < NE; ++i) {
@@ -497,8 +588,8 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(AParams pa, BParams pb, 
     typename BLoader::Regs rb;
 
     if (k_begin < k_end) {
-        la.fetch(k_begin, k_end, ra.r);
-        lb.fetch(k_begin, k_end, rb.r);
+        la.fetch(k_begin, k_end, ra.r, lb);
+        lb.fetch(k_begin, k_end, rb.r, la);
         la.commit(lds[0], ra.r);
         lb.commit(lds[0] + kBK * T::LDA, rb.r);
     }
@@ -508,8 +599,8 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(AParams pa, BParams pb, 
     for (int k0 = k_begin; k0 < k_end; k0 += kBK) {
         const bool more = k0 + kBK < k_end;
         if (more) {
-            la.fetch(k0 + kBK, k_end, ra.r);
-            lb.fetch(k0 + kBK, k_end, rb.r);
+            la.fetch(k0 + kBK, k_end, ra.r, lb);
+            lb.fetch(k0 + kBK, k_end, rb.r, la);
         }
         const float *As = lds[buf];
         const float *Bs = lds[buf] + kBK * T::LDA;
