@@ -80,13 +80,16 @@ def time_steps(torch, fn, steps, warmup):
 
 
 def _tile(M, N):
-    """The block tile the library's launcher picks for a GEMM of M rows and N columns."""
-    narrow = N <= 64
+    """The block tile the library's launcher picks for an implicit GEMM of M rows, N columns."""
     if M <= 32:
         return "32x128"
-    if M <= 64 or (M % 128 != 0 and M % 128 <= 64 and M < 256):
-        return "64x64" if narrow else "64x128"
-    return "128x64" if narrow else "128x128"
+    best, cost = 128, -(-M // 128) * 128
+    for bm, charge in ((96, 1.04), (64, 1.10)):
+        c = -(-M // bm) * bm * charge
+        if c < cost:
+            best, cost = bm, c
+    bn = 64 if (N <= 64 and best != 96) else 128
+    return f"{best}x{bn}"
 
 
 def kernel_class(ucd, s, op, algo, b):

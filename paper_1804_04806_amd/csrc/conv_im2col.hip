@@ -104,7 +104,7 @@ hipError_t im2col_fwd(const Dims &d, int b, const float *x, const float *w, floa
     EpiNCHWParams pe{};
     pe.out = y; pe.grid_hw = FastDiv(d.P * d.Q); pe.grid_w = FastDiv(d.Q);
     pe.M = d.K; pe.HWo = d.P * d.Q; pe.Wo = d.Q; pe.h0 = 0; pe.hs = 1; pe.w0 = 0; pe.ws = 1;
-    return launch_gemm<KLane0, DenseNLane, EpiNCHW>(pa, pb, pe, g, s);
+    return launch_gemm<KLane0, DenseNLane, EpiNCHW, true>(pa, pb, pe, g, s);
 }
 
 hipError_t im2col_bwd_data(const Dims &d, int b, const float *dy, const float *w, float *dx, float *ws,
@@ -150,7 +150,7 @@ hipError_t im2col_bwd_filter(const Dims &d, int b, const float *x, const float *
     KLaneParams pb{};
     pb.t = ws; pb.bytes = (uint32_t)im2col_ws_bytes(d, b); pb.row_stride = 1; pb.col_stride = col_ld(d, b);
     EpiDenseParams pe{dw, d.crs()};
-    return launch_gemm<DyKLane, KLane0, EpiAtomic>(pa, pb, pe, g, s);
+    return launch_gemm<DyKLane, KLane0, EpiAtomic, true>(pa, pb, pe, g, s);
 }
 
 }  // namespace ucd

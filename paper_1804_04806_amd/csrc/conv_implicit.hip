@@ -39,8 +39,8 @@ hipError_t implicit_fwd(const Dims &d, int b, const float *x, const float *w, fl
     EpiNCHWParams pe{};
     pe.out = y; pe.grid_hw = pb.grid_hw; pe.grid_w = pb.grid_w;
     pe.M = d.K; pe.HWo = d.P * d.Q; pe.Wo = d.Q; pe.h0 = 0; pe.hs = 1; pe.w0 = 0; pe.ws = 1;
-    if (d.R * d.S <= 31) return launch_gemm<KLane0, GatherNLane, EpiNCHW>(pa, pb, pe, g, s);
-    return launch_gemm<KLane0, GatherNLaneBig, EpiNCHW>(pa, pb, pe, g, s);
+    if (d.R * d.S <= 31) return launch_gemm<KLane0, GatherNLane, EpiNCHW, true>(pa, pb, pe, g, s);
+    return launch_gemm<KLane0, GatherNLaneBig, EpiNCHW, true>(pa, pb, pe, g, s);
 }
 
 // Stride phases: input pixels h with (h + ph) % sh == a are reached only by filter rows
@@ -74,8 +74,8 @@ hipError_t implicit_bwd_data(const Dims &d, int b, const float *dy, const float 
             EpiNCHWParams pe{};
             pe.out = dx; pe.grid_hw = pb.grid_hw; pe.grid_w = pb.grid_w;
             pe.M = d.C; pe.HWo = d.H * d.W; pe.Wo = d.W; pe.h0 = h0; pe.hs = d.sh; pe.w0 = w0; pe.ws = d.sw;
-            hipError_t e = Ra * Sc <= 31 ? launch_gemm<FilterKLane, GatherNLane, EpiNCHW>(pa, pb, pe, g, s)
-                                         : launch_gemm<FilterKLane, GatherNLaneBig, EpiNCHW>(pa, pb, pe, g, s);
+            hipError_t e = Ra * Sc <= 31 ? launch_gemm<FilterKLane, GatherNLane, EpiNCHW, true>(pa, pb, pe, g, s)
+                                         : launch_gemm<FilterKLane, GatherNLaneBig, EpiNCHW, true>(pa, pb, pe, g, s);
             if (e != hipSuccess) return e;
         }
     return hipSuccess;
@@ -85,7 +85,7 @@ hipError_t implicit_bwd_data(const Dims &d, int b, const float *dy, const float 
 // chunks of at least 256 reduction rows.
 int filter_splits(int M, int N, int Kd)
 {
-    const int bm = M <= 32 ? 32 : (M <= 64 ? 64 : 128), bn = N <= 64 ? 64 : 128;
+    const int bm = pick_rows(M, true), bn = N <= 64 ? 64 : 128;
     const long tiles = (long)((M + bm - 1) / bm) * ((N + bn - 1) / bn);
     long want = (1024 + tiles - 1) / tiles;
     long cap = Kd / 256;
@@ -116,7 +116,7 @@ hipError_t implicit_bwd_filter(const Dims &d, int b, const float *x, const float
     pb.mul_h = d.sh; pb.add_h = -d.ph; pb.mul_w = d.sw; pb.add_w = -d.pw;
     pb.shift = d.ph * d.W + d.pw;
     EpiDenseParams pe{dw, d.crs()};
-    return launch_gemm<DyKLane, XKLane, EpiAtomic>(pa, pb, pe, g, s);
+    return launch_gemm<DyKLane, XKLane, EpiAtomic, true>(pa, pb, pe, g, s);
 }
 
 }  // namespace ucd

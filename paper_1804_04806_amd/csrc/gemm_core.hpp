@@ -132,6 +132,7 @@ struct GatherParams {
 // SMALL: at most 31 taps, one mask bit per (r, s); otherwise one mask per axis (R, S <= 31).
 template <int TD, bool SMALL>
 struct GatherNLaneT {
+    static_assert(TD >= 64, "a wave must cover one reduction row");
     static constexpr int RP = kThreads / TD;  // reduction rows per pass
     static constexpr int NE = kBK / RP;       // elements per thread per step
     static constexpr int LD = TD + kPad;
@@ -476,7 +477,7 @@ struct DenseNLaneS {
         rsrc = make_rsrc(prm.t, prm.bytes);
         const int tid = threadIdx.x;
         col = tid % TD;
-        row0 = __builtin_amdgcn_readfirstlane(tid / TD);
+        row0 = TD >= 64 ? __builtin_amdgcn_readfirstlane(tid / TD) : tid / TD;  // wave-uniform only if TD >= 64
         j_ = origin + col;
         ok_ = j_ < extent;
     }

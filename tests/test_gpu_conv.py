@@ -24,6 +24,10 @@ SHAPES = [
     Shape(2, 6, 9, 12, 7, 2, 4, 1, 1, "evenfilter"),           # R != S, even sizes
     Shape(1, 1, 5, 5, 1, 3, 3, 1, 1, "tiny"),
     Shape(2, 130, 8, 8, 260, 3, 3, 1, 1, "wide"),
+    Shape(3, 2, 10, 10, 96, 3, 3, 1, 1, "c2k96"),              # 96-row tile; C*R*S = 18 rows in BackwardData's im2col GEMM
+    Shape(2, 96, 9, 9, 192, 3, 3, 1, 1, "c96k192"),            # two 96-row tiles; BackwardData M = 96
+    Shape(2, 2, 11, 11, 10, 4, 4, 1, 1, "crs32"),              # C*R*S = 32, 16-byte aligned filter rows
+    Shape(2, 160, 6, 6, 160, 3, 3, 1, 1, "k160"),              # 96-row tiles with a ragged second tile
 ]
 
 DIVISIONS = {8: [[8], [1] * 8, [3, 5]], 5: [[5], [2, 3]], 4: [[4], [1, 3]], 3: [[3], [1, 2]],
