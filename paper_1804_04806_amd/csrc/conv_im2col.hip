@@ -56,16 +56,14 @@ __global__ __launch_bounds__(256) void col2im_kernel(const float *__restrict__ c
     p.w.divmod(pix, h, w);
     n = nc / (uint32_t)p.C;
     c = nc - n * (uint32_t)p.C;
+    // only the taps of this pixel's stride phase can land: r = (h+ph) mod sh, then steps of sh
     float acc = 0.f;
-    for (int r = 0; r < p.R; ++r) {
-        const int hp = (int)h + p.ph - r;
-        if (hp < 0 || hp % p.sh != 0) continue;
-        const int op = hp / p.sh;
+    const int hp0 = (int)h + p.ph, wq0 = (int)w + p.pw;
+    for (int r = hp0 % p.sh; r < p.R && r <= hp0; r += p.sh) {
+        const int op = (hp0 - r) / p.sh;
         if (op >= p.P) continue;
-        for (int s = 0; s < p.S; ++s) {
-            const int wq = (int)w + p.pw - s;
-            if (wq < 0 || wq % p.sw != 0) continue;
-            const int oq = wq / p.sw;
+        for (int s = wq0 % p.sw; s < p.S && s <= wq0; s += p.sw) {
+            const int oq = (wq0 - s) / p.sw;
             if (oq >= p.Q) continue;
             acc += col[(size_t)((c * p.R + r) * p.S + s) * p.ld + (n * p.P + op) * p.Q + oq];
         }
