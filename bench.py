@@ -100,14 +100,14 @@ def kernel_class(ucd, s, op, algo, b):
         return None
     crs = s.C * s.R * s.S
     if op == ucd.FWD:
-        gather = "GatherNLane" if s.R * s.S <= 31 else "GatherNLaneBig"
+        gather = "GatherNLaneT<small>" if s.R * s.S <= 31 else "GatherNLaneT<big>"
         return f"gemm_kernel<Tile<{_tile(s.K, b * s.P * s.Q)}>,KLane0,{gather},EpiNCHW> (implicit fwd)"
     if op == ucd.BWD_DATA:
         if s.stride != 1:
             return None
-        gather = "GatherNLane" if s.R * s.S <= 31 else "GatherNLaneBig"
-        return f"gemm_kernel<Tile<{_tile(s.C, b * s.H * s.W)}>,KLane1,{gather},EpiNCHW> (implicit bwdData)"
-    return f"gemm_kernel<Tile<{_tile(s.K, crs)}>,KLane2,KLane2,EpiAtomic> (implicit bwdFilter)"
+        gather = "GatherNLaneT<small>" if s.R * s.S <= 31 else "GatherNLaneT<big>"
+        return f"gemm_kernel<Tile<{_tile(s.C, b * s.H * s.W)}>,FilterKLane,{gather},EpiNCHW> (implicit bwdData)"
+    return f"gemm_kernel<Tile<{_tile(s.K, crs)}>,PixelKLane<dy>,PixelKLane<x>,EpiAtomic> (implicit bwdFilter)"
 
 
 def dominant_kernel_roofline(torch, ucd, states, plans, ws, reps):

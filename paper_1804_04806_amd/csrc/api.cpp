@@ -523,6 +523,18 @@ int ucd_conv_bwd_filter(const ucd_plan_t *plan, const void *x, const void *dy, v
                     stream);
 }
 
+int ucd_mfma_probe(int valu_per_mfma, int blocks, int iters, void *scratch, size_t scratch_bytes, void *stream,
+                   double *flops)
+{
+    if (!scratch || !flops) return UCD_E_NULLPTR;
+    if (blocks < 1 || blocks > 65536 || iters < 1 || scratch_bytes < (size_t)blocks * 256 * 4) return UCD_E_INVALID;
+    hipError_t e = mfma_probe(valu_per_mfma, blocks, iters, (float *)scratch, (hipStream_t)stream);
+    if (e == hipErrorInvalidValue) return UCD_E_INVALID;
+    if (e != hipSuccess) return UCD_E_HIP;
+    *flops = (double)blocks * 4.0 * iters * 16.0 * 4096.0;
+    return UCD_OK;
+}
+
 int ucd_run_micro(const ucd_layer_t *layer, int op, int algo, int b, const void *a, const void *bsrc, void *out,
                   float beta, void *ws, size_t ws_bytes, void *stream)
 {

@@ -40,4 +40,7 @@ hipError_t winograd_bwd_data(const Dims &d, int b, const float *dy, const float 
 
 hipError_t fill_zero(float *p, size_t n, hipStream_t s);
 
+// register-only MFMA loop (valu_per_mfma in {0, 2, 4, 8}); out holds blocks * 256 floats
+hipError_t mfma_probe(int valu_per_mfma, int blocks, int iters, float *out, hipStream_t s);
+
 }  // namespace ucd

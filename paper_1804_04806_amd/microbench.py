@@ -18,10 +18,50 @@ def main():
     ap.add_argument("--b", type=int, default=256)
     ap.add_argument("--reps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--copy-mib", type=int, default=0,
+                    help="instead of a convolution, run a plain device copy of this many MiB "
+                         "(a kernel of known traffic, to calibrate FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--mfma-peak", action="store_true",
+                    help="instead of a convolution, time the register-only MFMA loop with 0/2/4/8 "
+                         "vector FMAs per MFMA (on-box fp32 matrix ceiling)")
     args = ap.parse_args()
 
     import torch
     from . import synth, ucd
+    if args.mfma_peak:
+        blocks, iters = 512, 2000
+        scratch = torch.empty(blocks * 256, dtype=torch.float32, device="cuda:0")
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        out = {}
+        for valu in (0, 2, 4, 8):
+            best = 1e9
+            for it in range(args.warmup + args.reps):
+                e0.record()
+                flops = ucd.ucd_mfma_probe(valu, blocks, iters, scratch)
+                e1.record()
+                e1.synchronize()
+                if it >= args.warmup:
+                    best = min(best, e0.elapsed_time(e1))
+            out[f"tflops_with_{valu}_valu_per_mfma"] = round(flops / best / 1e9, 1)
+        print(json.dumps(out))
+        return
+    if args.copy_mib:
+        n = args.copy_mib * (1 << 20) // 4
+        src = torch.rand(n, device="cuda:0")
+        dst = torch.empty_like(src)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        times = []
+        for it in range(args.warmup + args.reps):
+            e0.record()
+            dst.copy_(src)
+            e1.record()
+            e1.synchronize()
+            if it >= args.warmup:
+                times.append(e0.elapsed_time(e1))
+        ms = min(times)
+        print(json.dumps({"copy_mib": args.copy_mib, "ms_min": round(ms, 4),
+                          "GBps_read_plus_write": round(2 * n * 4 / ms / 1e6, 1)}))
+        return
     nets = {"small": synth.config_small, "alexnet": synth.config_alexnet, "resnet18": synth.config_resnet18,
             "densenet": synth.config_densenet_block, "resnet50": synth.config_resnet50}
     s = next(l for l in nets[args.net]() if l.name == args.layer).with_batch(args.b)

@@ -26,7 +26,7 @@ EXPORTS = [
     "ucd_strerror", "ucd_version", "ucd_workspace_size", "ucd_plan_from_table", "ucd_desirable_from_table",
     "ucd_wd_solve", "ucd_plan_wd_from_tables", "ucd_plan_fixed", "ucd_plan_query", "ucd_plan_destroy",
     "ucd_plan", "ucd_plan_wd", "ucd_bench_table", "ucd_bench_clear", "ucd_conv_fwd", "ucd_conv_bwd_data",
-    "ucd_conv_bwd_filter", "ucd_run_micro",
+    "ucd_conv_bwd_filter", "ucd_run_micro", "ucd_mfma_probe",
 ]
 
 
@@ -81,6 +81,7 @@ def lib():
         L.ucd_conv_bwd_data.argtypes = [vp, vp, vp, vp, vp, sz, vp]
         L.ucd_conv_bwd_filter.argtypes = [vp, vp, vp, vp, ctypes.c_float, vp, sz, vp]
         L.ucd_run_micro.argtypes = [lp, i, i, i, vp, vp, vp, ctypes.c_float, vp, sz, vp]
+        L.ucd_mfma_probe.argtypes = [i, i, i, vp, sz, vp, ctypes.POINTER(ctypes.c_double)]
         _lib = L
     return _lib
 
@@ -299,3 +300,11 @@ def ucd_run_micro(desc, op, algo, b, a, bsrc, out, beta=0.0, ws=None, ws_bytes=N
     _check(lib().ucd_run_micro(ctypes.byref(desc), op, algo, b, _ptr(a), _ptr(bsrc), _ptr(out), float(beta),
                                _ptr(ws), _nbytes(ws) if ws_bytes is None else ws_bytes, _stream(stream)),
            "ucd_run_micro")
+
+
+def ucd_mfma_probe(valu_per_mfma, blocks, iters, scratch, stream=None):
+    """Enqueues the MFMA calibration loop; returns the MFMA flops one launch executes."""
+    flops = ctypes.c_double(0.0)
+    _check(lib().ucd_mfma_probe(valu_per_mfma, blocks, iters, _ptr(scratch), _nbytes(scratch), _stream(stream),
+                                ctypes.byref(flops)), "ucd_mfma_probe")
+    return flops.value
