@@ -65,11 +65,6 @@ size_t ws_size(const ucd_layer_t *L, int op, int algo, int b)
     if (!L || !layer_ok(L) || L->dtype != 0 || op < 0 || op >= UCD_N_OP || b < 1 || b > L->N) return UCD_WS_NA;
     if (!fits_32bit(L, b)) return UCD_WS_NA;
     const Dims d = dims_of(L);
-    // operands read through the reduction-lane loaders (dy in BackwardFilter, the filter in
-    // BackwardData) are limited to 1 GiB per micro-batch
-    const long long half = kMaxOperandFloats / 2;
-    if (op == UCD_BWD_FILTER && algo != UCD_ALGO_WINOGRAD && (long long)b * d.K * d.P * d.Q > half) return UCD_WS_NA;
-    if (op == UCD_BWD_DATA && algo == UCD_ALGO_IMPLICIT && (long long)d.K * d.crs() > half) return UCD_WS_NA;
     switch (algo) {
     case UCD_ALGO_IMPLICIT:
         return 0;

@@ -214,12 +214,10 @@ template <int TD> using GatherNLaneBig = GatherNLaneT<TD, false>;
 // NE = TD/16 tile positions.  Used where memory is contiguous along the reduction index: filter
 // matrices, and BackwardFilter's dy / x (contiguous along the pixel index).  The address of
 // element (kk, j) is split into a row part computed once per step per thread and a column part
-// fixed per thread, so that the per-element work is one add (plus the window test for x).
-// "Reads as zero" is signalled either by an additive flag at bit 30 (both parts are below 1 GiB,
-// so any flagged sum lands in [1 GiB, 4 GiB) and outside a resource of at most 1 GiB) or, for the
-// windowed loader, by a mask bit moved to bit 31.
-
-constexpr uint32_t kFlag = 0x40000000u;
+// fixed per thread; wherever the per-element part is the same for the whole wave it is passed as
+// the load's scalar offset instead, leaving no per-element vector work (only x in BackwardFilter,
+// whose positions decode to irregular (c, r, s), keeps per-element offsets and a window test).
+// Rows past k_end get voffset 0x80000000.
 
 struct KLaneParams {
     const float *t;
@@ -231,7 +229,18 @@ struct KLaneParams {
     int n_stride, Ht, Wt, mul_h, add_h, mul_w, add_w, shift;
 };
 
+// A note on tile positions outside the operand's extent (the ragged last tile): they only feed
+// output rows / columns that the epilogue never stores, so the loaders below do not zero them;
+// a buffer load cannot fault, whatever it reads there.  Only the reduction dimension (rows past
+// k_end) and genuine padding taps must read as zero.
+//
+// The hardware range check covers voffset + soffset (probed on the box: a load whose scalar
+// offset pushes the sum past num_records returns 0), so the per-element part of an address can
+// be a scalar offset whenever it is the same for the whole wave.
+
 // Dense matrix, element (kk, j) = t[kk*row_stride + j*col_stride]  (operand limit 2 GiB).
+// One VGPR of address state: the thread's (kl, c0) offset; the step and the position index i enter
+// as scalar offsets.
 template <int TD>
 struct KLane0 {
     static constexpr int CP = kThreads / kBK;  // tile positions per pass (16)
@@ -241,34 +250,24 @@ struct KLane0 {
     const KLaneParams *p;
     __amdgpu_buffer_rsrc_t rsrc;
     int kl, c0;
-    uint32_t voff0[NE];  // byte offset of (row kl, this tile position), kOob if out of extent
+    uint32_t voff;  // byte offset of (row kl, position origin + c0)
 
-    __device__ __forceinline__ void init(const KLaneParams &prm, int origin, int extent)
+    __device__ __forceinline__ void init(const KLaneParams &prm, int origin, int)
     {
         p = &prm;
         rsrc = make_rsrc(prm.t, prm.bytes);
         kl = threadIdx.x % kBK;
         c0 = threadIdx.x / kBK;
-#pragma unroll
-        for (int i = 0; i < NE; ++i) {
-            const int j = origin + c0 + CP * i;
-            voff0[i] = j >= extent ? kOob : 4u * (uint32_t)(kl * prm.row_stride + j * prm.col_stride);
-        }
+        voff = 4u * (uint32_t)(kl * prm.row_stride + (origin + c0) * prm.col_stride);
     }
     template <class Peer>
     __device__ __forceinline__ void fetch(int k0, int k_end, float (&r)[NE], const Peer &) const
     {
-        const uint32_t so = 4u * (uint32_t)(k0 * p->row_stride);  // scalar step offset
-        if (k0 + kBK <= k_end) {
+        const uint32_t vo = k0 + kl < k_end ? voff : kOob;  // rows past the end read as zero
 #pragma unroll
-            for (int i = 0; i < NE; ++i)
-                r[i] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc, (int)voff0[i], (int)so, 0));
-        } else {  // last, partial step: rows past the end read as zero
-            const bool rowok = k0 + kl < k_end;
-#pragma unroll
-            for (int i = 0; i < NE; ++i)
-                r[i] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc, (int)(rowok ? voff0[i] : kOob), (int)so, 0));
-        }
+        for (int i = 0; i < NE; ++i)
+            r[i] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(
+                rsrc, (int)vo, (int)(4u * (uint32_t)(k0 * p->row_stride + CP * i * p->col_stride)), 0));
     }
     __device__ __forceinline__ void commit(float *lds, const float (&r)[NE]) const
     {
@@ -278,7 +277,7 @@ struct KLane0 {
 };
 
 // BackwardData's A operand: element (kk -> (k, r, s), j = c) = w[k, c, tap_add_h + tap_mul_h*r, tap_add_w + tap_mul_w*s]
-// (the filter taps of one stride phase).  Operand limit 1 GiB.
+// (the filter taps of one stride phase).
 template <int TD>
 struct FilterKLane {
     static constexpr int CP = kThreads / kBK;
@@ -288,19 +287,15 @@ struct FilterKLane {
     const KLaneParams *p;
     __amdgpu_buffer_rsrc_t rsrc;
     int kl, c0;
-    uint32_t coffb[NE];
+    uint32_t coff0;  // byte offset of position origin + c0
 
-    __device__ __forceinline__ void init(const KLaneParams &prm, int origin, int extent)
+    __device__ __forceinline__ void init(const KLaneParams &prm, int origin, int)
     {
         p = &prm;
         rsrc = make_rsrc(prm.t, prm.bytes);
         kl = threadIdx.x % kBK;
         c0 = threadIdx.x / kBK;
-#pragma unroll
-        for (int i = 0; i < NE; ++i) {
-            const int j = origin + c0 + CP * i;
-            coffb[i] = j >= extent ? kFlag : 4u * (uint32_t)(j * prm.col_stride);
-        }
+        coff0 = 4u * (uint32_t)((origin + c0) * prm.col_stride);
     }
     template <class Peer>
     __device__ __forceinline__ void fetch(int k0, int k_end, float (&r)[NE], const Peer &) const
@@ -317,9 +312,11 @@ struct FilterKLane {
             roff = (int)k * p->k_stride + (p->tap_add_h + p->tap_mul_h * (int)tr) * p->s_mem + p->tap_add_w +
                    p->tap_mul_w * (int)ts;
         }
-        const uint32_t rterm = kk < k_end ? 4u * (uint32_t)roff : kFlag;
+        const uint32_t vo = kk < k_end ? 4u * (uint32_t)roff + coff0 : kOob;
 #pragma unroll
-        for (int i = 0; i < NE; ++i) r[i] = buf_load(rsrc, rterm + coffb[i]);
+        for (int i = 0; i < NE; ++i)
+            r[i] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(
+                rsrc, (int)vo, (int)(4u * (uint32_t)(CP * i * p->col_stride)), 0));
     }
     __device__ __forceinline__ void commit(float *lds, const float (&r)[NE]) const
     {
@@ -340,12 +337,13 @@ struct PixelKLane {
     static constexpr int CP = kThreads / kBK;
     static constexpr int NE = TD / CP;
     static constexpr int LD = TD + kPad;
+    static constexpr int NV = WINDOW ? NE : 1;
     struct Regs { float r[NE]; };
     const KLaneParams *p;
     __amdgpu_buffer_rsrc_t rsrc;
     int kl, c0;
-    uint32_t coffb[NE];
-    uint32_t rs[NE];          // WINDOW: r | s << 8
+    uint32_t coffb[NV];       // x: byte offset of each position's (c, r, s); dy: of position origin + c0
+    uint32_t rs[NV];          // x: r | s << 8
     mutable uint32_t n_, rest_;  // decode of this step's reduction row, for the peer
 
     __device__ __forceinline__ void init(const KLaneParams &prm, int origin, int extent)
@@ -355,18 +353,23 @@ struct PixelKLane {
         kl = threadIdx.x % kBK;
         c0 = threadIdx.x / kBK;
         n_ = rest_ = 0;
+        if constexpr (!WINDOW) {
+            coffb[0] = 4u * (uint32_t)((origin + c0) * prm.Ht * prm.Wt);
+            rs[0] = 0;
+        } else {
 #pragma unroll
-        for (int i = 0; i < NE; ++i) {
-            const int j = origin + c0 + CP * i;
-            if (j < extent) {
-                uint32_t c, tap, r, s;
-                prm.col_taps.divmod((uint32_t)j, c, tap);
-                prm.col_taps_w.divmod(tap, r, s);
-                rs[i] = r | (s << 8);
-                coffb[i] = 4u * (uint32_t)(((int)c * prm.Ht + (int)r) * prm.Wt + (int)s);
-            } else {
-                rs[i] = 31u;                     // WINDOW: bit 31 of the row mask is always set
-                coffb[i] = WINDOW ? 0u : kFlag;  // otherwise: additive flag
+            for (int i = 0; i < NE; ++i) {
+                const int j = origin + c0 + CP * i;
+                if (j < extent) {
+                    uint32_t c, tap, r, s;
+                    prm.col_taps.divmod((uint32_t)j, c, tap);
+                    prm.col_taps_w.divmod(tap, r, s);
+                    rs[i] = r | (s << 8);
+                    coffb[i] = 4u * (uint32_t)(((int)c * prm.Ht + (int)r) * prm.Wt + (int)s);
+                } else {
+                    rs[i] = 31u;  // bit 31 of the row mask is always set
+                    coffb[i] = 0u;
+                }
             }
         }
     }
@@ -378,9 +381,11 @@ struct PixelKLane {
         if constexpr (!WINDOW) {
             p->grid_hw.divmod((uint32_t)kk, n_, rest_);
             // grid is the tensor's own plane here: (a, b) -> a*Wt + b == rest
-            const uint32_t rterm = rowok ? 4u * (uint32_t)((int)n_ * p->n_stride + (int)rest_) : kFlag;
+            const uint32_t vo = rowok ? 4u * (uint32_t)((int)n_ * p->n_stride + (int)rest_) + coffb[0] : kOob;
+            const uint32_t step = 4u * (uint32_t)(CP * p->Ht * p->Wt);  // scalar: 16 channels further
 #pragma unroll
-            for (int i = 0; i < NE; ++i) r[i] = buf_load(rsrc, rterm + coffb[i]);
+            for (int i = 0; i < NE; ++i)
+                r[i] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc, (int)vo, (int)(step * (uint32_t)i), 0));
         } else {
             uint32_t a, b;
             p->grid_w.divmod(peer.rest_, a, b);
