@@ -79,35 +79,19 @@ def time_steps(torch, fn, steps, warmup):
     return (time.perf_counter() - t0) * 1e3 / steps
 
 
-def _tile(M, N):
-    """The block tile the library's launcher picks for an implicit GEMM of M rows, N columns."""
-    if M <= 32:
-        return "32x128"
-    best, cost = 128, -(-M // 128) * 128
-    for bm, charge in ((96, 1.04), (64, 1.10)):
-        c = -(-M // bm) * bm * charge
-        if c < cost:
-            best, cost = bm, c
-    bn = 64 if (N <= 64 and best != 96) else 128
-    return f"{best}x{bn}"
-
-
-def kernel_class(ucd, s, op, algo, b):
-    """Name of the single GEMM kernel instantiation an implicit-GEMM micro-batch launches (the
-    names rocprofv3 shows are the C++ template instantiations; this mirrors them), or None if the
-    run launches several kernels (im2col, Winograd, strided BackwardData's phases)."""
-    if algo != ucd.ALGO_IMPLICIT:
+def kernel_class(ucd, desc, op, algo, b):
+    """The GEMM kernel instantiation a micro-batch run launches, as the library describes it
+    (the names rocprofv3 shows are these template instantiations), if the run is that one kernel
+    (a zero-fill kernel in front of it is tolerated: a few microseconds); otherwise None
+    (im2col, Winograd and strided BackwardData launch several kernels)."""
+    text, n = ucd.ucd_describe_micro(desc, op, algo, b)
+    parts = [p.strip() for p in text.split(";")]
+    gemms = [p for p in parts if p.startswith("gemm_kernel<")]
+    others = [p for p in parts if not p.startswith("gemm_kernel<") and p != "fill_zero_kernel"]
+    if len(gemms) != 1 or others:
         return None
-    crs = s.C * s.R * s.S
-    if op == ucd.FWD:
-        gather = "GatherNLaneT<small>" if s.R * s.S <= 31 else "GatherNLaneT<big>"
-        return f"gemm_kernel<Tile<{_tile(s.K, b * s.P * s.Q)}>,KLane0,{gather},EpiNCHW> (implicit fwd)"
-    if op == ucd.BWD_DATA:
-        if s.stride != 1:
-            return None
-        gather = "GatherNLaneT<small>" if s.R * s.S <= 31 else "GatherNLaneT<big>"
-        return f"gemm_kernel<Tile<{_tile(s.C, b * s.H * s.W)}>,FilterKLane,{gather},EpiNCHW> (implicit bwdData)"
-    return f"gemm_kernel<Tile<{_tile(s.K, crs)}>,PixelKLane<dy>,PixelKLane<x>,EpiAtomic> (implicit bwdFilter)"
+    name = gemms[0].split("> tiles=")[0] + ">"
+    return name + (" (after fill_zero_kernel)" if len(parts) > 1 else "")
 
 
 def dominant_kernel_roofline(torch, ucd, states, plans, ws, reps):
@@ -124,7 +108,7 @@ def dominant_kernel_roofline(torch, ucd, states, plans, ws, reps):
         for op in (ucd.FWD, ucd.BWD_DATA, ucd.BWD_FILTER):
             o = 0
             for algo, b in pl[op].micro:
-                cls = kernel_class(ucd, s, op, algo, b)
+                cls = kernel_class(ucd, st.desc, op, algo, b)
                 if cls is not None:
                     xo = st.x.view(-1)[o * x_img:]
                     yo = st.y.view(-1)[o * y_img:]

@@ -185,6 +185,14 @@ int ucd_run_micro(const ucd_layer_t *layer, int op, int algo, int b, const void 
                   const void *bsrc, void *out, float beta, void *ws, size_t ws_bytes,
                   void *stream);
 
+/* Introspection: writes to buf (NUL-terminated, at most cap bytes) the kernels that
+ * ucd_run_micro(layer, op, algo, b, ...) would launch, in order, separated by "; " (GEMM kernels
+ * with their tile, loaders, epilogue, tile count, reduction splits and batch; BackwardFilter as
+ * the accumulating beta = 1 call), and their number to *n_launches (may be NULL).  Launches
+ * nothing.  Host only. */
+int ucd_describe_micro(const ucd_layer_t *layer, int op, int algo, int b, char *buf, size_t cap,
+                       int *n_launches);
+
 /* Calibration of the roofline the GEMM kernels are held against (not part of the method):
  * enqueues a register-only loop of independent v_mfma_f32_32x32x2_f32 with `valu_per_mfma`
  * (0, 2, 4 or 8) ordinary vector FMAs interleaved per MFMA, on `blocks` workgroups of 256

@@ -518,6 +518,27 @@ int ucd_conv_bwd_filter(const ucd_plan_t *plan, const void *x, const void *dy, v
                     stream);
 }
 
+int ucd_describe_micro(const ucd_layer_t *layer, int op, int algo, int b, char *buf, size_t cap, int *n_launches)
+{
+    if (!layer || !buf) return UCD_E_NULLPTR;
+    if (!layer_ok(layer) || op < 0 || op >= UCD_N_OP || b < 1 || cap < 1) return UCD_E_INVALID;
+    if (layer->dtype != 0) return UCD_E_UNSUPPORTED;
+    ucd_layer_t L = *layer;
+    L.N = std::max(L.N, b);
+    if (ws_size(&L, op, algo, b) == UCD_WS_NA) return UCD_E_UNSUPPORTED;
+    LaunchLog log;
+    launch_log() = &log;
+    // pointers are only passed through to the (suppressed) launches, never dereferenced on the host
+    int rc = run_micro(&L, op, algo, b, nullptr, nullptr, nullptr, op == UCD_BWD_FILTER ? 1.f : 0.f, nullptr, nullptr);
+    launch_log() = nullptr;
+    if (rc != UCD_OK) return rc;
+    const size_t n = std::min(cap - 1, log.text.size());
+    std::memcpy(buf, log.text.data(), n);
+    buf[n] = 0;
+    if (n_launches) *n_launches = log.launches;
+    return UCD_OK;
+}
+
 int ucd_mfma_probe(int valu_per_mfma, int blocks, int iters, void *scratch, size_t scratch_bytes, void *stream,
                    double *flops)
 {

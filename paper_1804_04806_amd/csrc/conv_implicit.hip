@@ -15,18 +15,43 @@ __global__ void fill_zero_kernel(float *p, size_t n)
     for (; i < n; i += step) p[i] = 0.f;
 }
 
+LaunchLog *&launch_log()
+{
+    static thread_local LaunchLog *log = nullptr;
+    return log;
+}
+
 hipError_t fill_zero(float *p, size_t n, hipStream_t s)
 {
     if (n == 0) return hipSuccess;
+    if (LaunchLog *log = launch_log()) {
+        log->add("fill_zero_kernel");
+        return hipSuccess;
+    }
     size_t blocks = (n + 255) / 256;
     if (blocks > 4096) blocks = 4096;
     fill_zero_kernel<<<(unsigned)blocks, 256, 0, s>>>(p, n);
     return hipGetLastError();
 }
 
+// Forward / BackwardData write each output once, so normally one workgroup owns a whole
+// reduction.  When the output has too few tiles to give every CU several workgroups (deep
+// layers: many channels, few pixels), the reduction is split as well and the partial results meet
+// through atomics in a zero-filled output.  Chunks keep at least 1024 reduction rows.
+static int output_splits(int M, int N, int Kd)
+{
+    const long tiles = pick_tile(M, N, true, 1 << 20).blocks(M, N, 1);  // tiles at the default shape
+    if (tiles >= 768) return 1;  // three workgroups per CU already
+    long want = (1536 + tiles - 1) / tiles;
+    const long cap = Kd / 1024;
+    if (want > cap) want = cap;
+    return want < 2 ? 1 : (int)want;
+}
+
 hipError_t implicit_fwd(const Dims &d, int b, const float *x, const float *w, float *y, hipStream_t s)
 {
     GemmShape g{d.K, b * d.P * d.Q, d.crs()};
+    g.splits = output_splits(g.M, g.N, g.Kd);
     KLaneParams pa{};
     pa.t = w; pa.bytes = wbytes(d); pa.row_stride = 1; pa.col_stride = d.crs();
     GatherParams pb{};
@@ -39,6 +64,12 @@ hipError_t implicit_fwd(const Dims &d, int b, const float *x, const float *w, fl
     EpiNCHWParams pe{};
     pe.out = y; pe.grid_hw = pb.grid_hw; pe.grid_w = pb.grid_w;
     pe.M = d.K; pe.HWo = d.P * d.Q; pe.Wo = d.Q; pe.h0 = 0; pe.hs = 1; pe.w0 = 0; pe.ws = 1;
+    if (g.splits > 1) {
+        hipError_t e = fill_zero(y, (size_t)b * d.K * d.P * d.Q, s);
+        if (e != hipSuccess) return e;
+        if (d.R * d.S <= 31) return launch_gemm<KLane0, GatherNLane, EpiNCHWAtomic, true>(pa, pb, pe, g, s);
+        return launch_gemm<KLane0, GatherNLaneBig, EpiNCHWAtomic, true>(pa, pb, pe, g, s);
+    }
     if (d.R * d.S <= 31) return launch_gemm<KLane0, GatherNLane, EpiNCHW, true>(pa, pb, pe, g, s);
     return launch_gemm<KLane0, GatherNLaneBig, EpiNCHW, true>(pa, pb, pe, g, s);
 }
@@ -48,15 +79,36 @@ hipError_t implicit_fwd(const Dims &d, int b, const float *x, const float *w, fl
 // sub-sampled, index-reversed filter.  Pixels of a phase with no tap get zeros (Kd = 0).
 hipError_t implicit_bwd_data(const Dims &d, int b, const float *dy, const float *w, float *dx, hipStream_t s)
 {
+    // phases whose GEMM has too few tiles split their reduction (atomics); dx is zero-filled once
+    // if any phase does
+    auto phase_shape = [&](int a, int c, int &h0, int &w0, int &Hh, int &Ww, int &Ra, int &Sc) {
+        h0 = ((a - d.ph) % d.sh + d.sh) % d.sh;
+        w0 = ((c - d.pw) % d.sw + d.sw) % d.sw;
+        Hh = h0 < d.H ? (d.H - h0 + d.sh - 1) / d.sh : 0;
+        Ww = w0 < d.W ? (d.W - w0 + d.sw - 1) / d.sw : 0;
+        Ra = a < d.R ? (d.R - a + d.sh - 1) / d.sh : 0;
+        Sc = c < d.S ? (d.S - c + d.sw - 1) / d.sw : 0;
+    };
+    bool any_split = false;
     for (int a = 0; a < d.sh; ++a)
         for (int c = 0; c < d.sw; ++c) {
-            const int h0 = ((a - d.ph) % d.sh + d.sh) % d.sh, w0 = ((c - d.pw) % d.sw + d.sw) % d.sw;
-            const int Hh = h0 < d.H ? (d.H - h0 + d.sh - 1) / d.sh : 0;
-            const int Ww = w0 < d.W ? (d.W - w0 + d.sw - 1) / d.sw : 0;
+            int h0, w0, Hh, Ww, Ra, Sc;
+            phase_shape(a, c, h0, w0, Hh, Ww, Ra, Sc);
+            if (Hh && Ww && Ra && Sc && output_splits(d.C, b * Hh * Ww, d.K * Ra * Sc) > 1) any_split = true;
+        }
+    if (any_split) {
+        hipError_t e = fill_zero(dx, (size_t)b * d.C * d.H * d.W, s);
+        if (e != hipSuccess) return e;
+    }
+    for (int a = 0; a < d.sh; ++a)
+        for (int c = 0; c < d.sw; ++c) {
+            int h0, w0, Hh, Ww, Ra, Sc;
+            phase_shape(a, c, h0, w0, Hh, Ww, Ra, Sc);
             if (Hh == 0 || Ww == 0) continue;
-            const int Ra = a < d.R ? (d.R - a + d.sh - 1) / d.sh : 0;
-            const int Sc = c < d.S ? (d.S - c + d.sw - 1) / d.sw : 0;
             GemmShape g{d.C, b * Hh * Ww, d.K * Ra * Sc};
+            if (any_split && g.Kd == 0) continue;  // dx is already zero there
+            g.splits = output_splits(g.M, g.N, g.Kd);
+            const bool split = g.splits > 1;
             KLaneParams pa{};
             pa.t = w; pa.bytes = wbytes(d); pa.col_stride = d.R * d.S;
             pa.taps = FastDiv(Ra * Sc); pa.taps_w = FastDiv(Sc);
@@ -74,8 +126,13 @@ hipError_t implicit_bwd_data(const Dims &d, int b, const float *dy, const float 
             EpiNCHWParams pe{};
             pe.out = dx; pe.grid_hw = pb.grid_hw; pe.grid_w = pb.grid_w;
             pe.M = d.C; pe.HWo = d.H * d.W; pe.Wo = d.W; pe.h0 = h0; pe.hs = d.sh; pe.w0 = w0; pe.ws = d.sw;
-            hipError_t e = Ra * Sc <= 31 ? launch_gemm<FilterKLane, GatherNLane, EpiNCHW, true>(pa, pb, pe, g, s)
-                                         : launch_gemm<FilterKLane, GatherNLaneBig, EpiNCHW, true>(pa, pb, pe, g, s);
+            hipError_t e;
+            if (split)
+                e = Ra * Sc <= 31 ? launch_gemm<FilterKLane, GatherNLane, EpiNCHWAtomic, true>(pa, pb, pe, g, s)
+                                  : launch_gemm<FilterKLane, GatherNLaneBig, EpiNCHWAtomic, true>(pa, pb, pe, g, s);
+            else
+                e = Ra * Sc <= 31 ? launch_gemm<FilterKLane, GatherNLane, EpiNCHW, true>(pa, pb, pe, g, s)
+                                  : launch_gemm<FilterKLane, GatherNLaneBig, EpiNCHW, true>(pa, pb, pe, g, s);
             if (e != hipSuccess) return e;
         }
     return hipSuccess;
@@ -85,8 +142,7 @@ hipError_t implicit_bwd_data(const Dims &d, int b, const float *dy, const float 
 // chunks of at least 256 reduction rows.
 int filter_splits(int M, int N, int Kd)
 {
-    const int bm = pick_rows(M, true), bn = N <= 64 ? 64 : 128;
-    const long tiles = (long)((M + bm - 1) / bm) * ((N + bn - 1) / bn);
+    const long tiles = pick_tile(M, N, true, 1 << 20).blocks(M, N, 1);  // tiles at the default shape
     long want = (1024 + tiles - 1) / tiles;
     long cap = Kd / 256;
     if (cap < 1) cap = 1;

@@ -178,14 +178,19 @@ static hipError_t winograd_run(const Dims &d, int op, int b, const float *in, co
     float *Z = V + (size_t)16 * g.Ci * g.ld;
     const FastDiv divT(g.T), divTW(g.TW);
 
-    wino_filter_kernel<<<(unsigned)((g.Ci * g.Mo4 + 255) / 256), 256, 0, s>>>(w, U, g.Ci, g.Co, g.Mo4,
-                                                                           g.transposed ? 1 : 0);
-    hipError_t e = hipGetLastError();
+    LaunchLog *log = launch_log();
+    if (log) log->add("wino_filter_kernel");
+    else
+        wino_filter_kernel<<<(unsigned)((g.Ci * g.Mo4 + 255) / 256), 256, 0, s>>>(w, U, g.Ci, g.Co, g.Mo4,
+                                                                               g.transposed ? 1 : 0);
+    hipError_t e = log ? hipSuccess : hipGetLastError();
     if (e != hipSuccess) return e;
 
     dim3 gi((unsigned)((g.ld + 255) / 256), (unsigned)(g.Ci < 4096 ? g.Ci : 4096));
-    wino_input_kernel<<<gi, 256, 0, s>>>(in, V, g, divT, divTW, n_tiles);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (log) log->add("wino_input_kernel");
+    else
+        wino_input_kernel<<<gi, 256, 0, s>>>(in, V, g, divT, divTW, n_tiles);
+    if (!log && (e = hipGetLastError()) != hipSuccess) return e;
 
     GemmShape gs{g.Co, n_tiles, g.Ci};
     gs.batch = 16;
@@ -198,6 +203,10 @@ static hipError_t winograd_run(const Dims &d, int op, int b, const float *in, co
     if ((e = launch_gemm<DenseNLane, DenseNLane, EpiDense>(pa, pb, pe, gs, s)) != hipSuccess) return e;
 
     dim3 go((unsigned)((n_tiles + 255) / 256), (unsigned)(g.Co < 4096 ? g.Co : 4096));
+    if (log) {
+        log->add("wino_output_kernel");
+        return hipSuccess;
+    }
     wino_output_kernel<<<go, 256, 0, s>>>(Z, out, g, divT, divTW, n_tiles);
     return hipGetLastError();
 }

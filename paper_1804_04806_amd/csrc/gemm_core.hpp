@@ -132,6 +132,7 @@ struct GatherParams {
 // SMALL: at most 31 taps, one mask bit per (r, s); otherwise one mask per axis (R, S <= 31).
 template <int TD, bool SMALL>
 struct GatherNLaneT {
+    static const char *name() { return SMALL ? "GatherNLane<taps<=31>" : "GatherNLane<taps>31>"; }
     static_assert(TD >= 64, "a wave must cover one reduction row");
     static constexpr int RP = kThreads / TD;  // reduction rows per pass
     static constexpr int NE = kBK / RP;       // elements per thread per step
@@ -243,6 +244,7 @@ struct KLaneParams {
 // as scalar offsets.
 template <int TD>
 struct KLane0 {
+    static const char *name() { return "KLane0"; }
     static constexpr int CP = kThreads / kBK;  // tile positions per pass (16)
     static constexpr int NE = TD / CP;
     static constexpr int LD = TD + kPad;
@@ -280,6 +282,7 @@ struct KLane0 {
 // (the filter taps of one stride phase).
 template <int TD>
 struct FilterKLane {
+    static const char *name() { return "FilterKLane"; }
     static constexpr int CP = kThreads / kBK;
     static constexpr int NE = TD / CP;
     static constexpr int LD = TD + kPad;
@@ -334,6 +337,7 @@ struct FilterKLane {
 // The x loader reuses the pixel decode its peer (the dy loader of the same step) has just done.
 template <int TD, bool WINDOW>
 struct PixelKLane {
+    static const char *name() { return WINDOW ? "PixelKLane<x>" : "PixelKLane<dy>"; }
     static constexpr int CP = kThreads / kBK;
     static constexpr int NE = TD / CP;
     static constexpr int LD = TD + kPad;
@@ -423,6 +427,7 @@ struct DenseParams {
 
 template <int TD>
 struct DenseNLane {
+    static const char *name() { return "DenseNLane"; }
     static constexpr int CQ = TD / 4;          // float4 columns per row
     static constexpr int RP = kThreads / CQ;   // rows per pass
     static constexpr int NE = (kBK + RP - 1) / RP;
@@ -467,6 +472,7 @@ struct DenseNLane {
 // Same matrix, any ld / alignment: scalar loads, one reduction row per pass.
 template <int TD>
 struct DenseNLaneS {
+    static const char *name() { return "DenseNLaneS"; }
     static constexpr int RP = kThreads / TD;
     static constexpr int NE = kBK / RP;
     static constexpr int LD = TD + kPad;
@@ -514,6 +520,7 @@ struct EpiNCHWParams {
     int M, HWo, Wo, h0, hs, w0, ws;
 };
 struct EpiNCHW {
+    static const char *name() { return "EpiNCHW"; }
     typedef EpiNCHWParams Params;
     int off;
     __device__ __forceinline__ void prep(const Params &p, int j)
@@ -525,6 +532,15 @@ struct EpiNCHW {
     }
     __device__ __forceinline__ void store(const Params &p, int m, float v) const { p.out[off + m * p.HWo] = v; }
 };
+// The same scatter as an fp32 atomic add into a zero-filled tensor, for GEMMs whose reduction is
+// split over several workgroups because the output has too few tiles to fill the chip.
+struct EpiNCHWAtomic : EpiNCHW {
+    static const char *name() { return "EpiNCHWAtomic"; }
+    __device__ __forceinline__ void store(const Params &p, int m, float v) const
+    {
+        unsafeAtomicAdd(p.out + off + m * p.HWo, v);
+    }
+};
 
 // Dense row-major store out[m*ld + j].
 struct EpiDenseParams {
@@ -532,6 +548,7 @@ struct EpiDenseParams {
     int ld;
 };
 struct EpiDense {
+    static const char *name() { return "EpiDense"; }
     typedef EpiDenseParams Params;
     int j_;
     __device__ __forceinline__ void prep(const Params &, int j) { j_ = j; }
@@ -540,6 +557,7 @@ struct EpiDense {
 
 // Dense row-major accumulate with hardware fp32 atomics (split-K partial sums of BackwardFilter).
 struct EpiAtomic {
+    static const char *name() { return "EpiAtomic"; }
     typedef EpiDenseParams Params;
     int j_;
     __device__ __forceinline__ void prep(const Params &, int j) { j_ = j; }

@@ -1,6 +1,9 @@
 // Host-side tile choice and launch of gemm_kernel.
 #pragma once
+#include <string>
+
 #include "gemm_core.hpp"
+#include "kernels.h"
 
 namespace ucd {
 
@@ -22,6 +25,13 @@ hipError_t launch_tile(const AP &pa, const BP &pb, const typename Epi::Params &p
     if (k_chunk < kBK) k_chunk = kBK;
     splits = g.Kd > 0 ? (g.Kd + k_chunk - 1) / k_chunk : 1;
     dim3 grid((unsigned)(tiles_m * tiles_n), (unsigned)splits, (unsigned)g.batch);
+    if (LaunchLog *log = launch_log()) {
+        log->add(std::string("gemm_kernel<Tile<") + std::to_string(T::BM) + "x" + std::to_string(T::BN) + ">," +
+                 AL<T::BM>::name() + "," + BL<T::BN>::name() + "," + Epi::name() + "> tiles=" +
+                 std::to_string(tiles_m * tiles_n) + " splits=" + std::to_string(splits) + " batch=" +
+                 std::to_string(g.batch));
+        return hipSuccess;
+    }
     gemm_kernel<T, AL<T::BM>, BL<T::BN>, Epi, AP, BP><<<grid, kThreads, 0, s>>>(
         pa, pb, pe, g.M, g.N, g.Kd, k_chunk, tiles_m, tiles_n, g.a_batch, g.b_batch, g.c_batch);
     return hipGetLastError();
@@ -46,21 +56,36 @@ inline int pick_rows(int M, bool rows96)
     return best;
 }
 
+// Tile for a GEMM that will run `mult` times in one launch (reduction splits x batch): rows as
+// above, 128 columns unless N is tiny; when that leaves the launch with fewer workgroups than CUs,
+// narrower and then shorter tiles are taken to put more workgroups on the chip.
+struct TilePick {
+    int bm, bn;
+    long blocks(int M, int N, long mult) const { return (long)((M + bm - 1) / bm) * ((N + bn - 1) / bn) * mult; }
+};
+inline TilePick pick_tile(int M, int N, bool rows96, long mult)
+{
+    TilePick t{pick_rows(M, rows96), N <= 64 ? 64 : 128};
+    if (t.bm == 32 || t.bm == 96) return t;  // single shapes
+    if (t.blocks(M, N, mult) < 256 && t.bn == 128) t.bn = 64;
+    if (t.blocks(M, N, mult) < 256 && t.bm == 128) t.bm = 64;
+    return t;
+}
+
 template <template <int> class AL, template <int> class BL, class Epi, bool ROWS96 = false, class AP, class BP>
 hipError_t launch_gemm(const AP &pa, const BP &pb, const typename Epi::Params &pe, const GemmShape &g,
                        hipStream_t s)
 {
-    const bool narrow = g.N <= 64;
-    const int best = pick_rows(g.M, ROWS96);
-    if (best == 32) return launch_tile<Tile<32, 128, 1, 4>, AL, BL, Epi>(pa, pb, pe, g, s);
-    if (best == 64) {
-        if (narrow) return launch_tile<Tile<64, 64, 2, 2>, AL, BL, Epi>(pa, pb, pe, g, s);
+    const TilePick t = pick_tile(g.M, g.N, ROWS96, (long)(g.splits < 1 ? 1 : g.splits) * g.batch);
+    if (t.bm == 32) return launch_tile<Tile<32, 128, 1, 4>, AL, BL, Epi>(pa, pb, pe, g, s);
+    if (t.bm == 64) {
+        if (t.bn == 64) return launch_tile<Tile<64, 64, 2, 2>, AL, BL, Epi>(pa, pb, pe, g, s);
         return launch_tile<Tile<64, 128, 2, 2>, AL, BL, Epi>(pa, pb, pe, g, s);
     }
     if constexpr (ROWS96) {
-        if (best == 96) return launch_tile<Tile<96, 128, 1, 4>, AL, BL, Epi>(pa, pb, pe, g, s);
+        if (t.bm == 96) return launch_tile<Tile<96, 128, 1, 4>, AL, BL, Epi>(pa, pb, pe, g, s);
     }
-    if (narrow) return launch_tile<Tile<128, 64, 2, 2>, AL, BL, Epi>(pa, pb, pe, g, s);
+    if (t.bn == 64) return launch_tile<Tile<128, 64, 2, 2>, AL, BL, Epi>(pa, pb, pe, g, s);
     return launch_tile<Tile<128, 128, 2, 2>, AL, BL, Epi>(pa, pb, pe, g, s);
 }
 

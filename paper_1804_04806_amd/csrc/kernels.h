@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 #include <cstddef>
 #include <cstdint>
+#include <string>
 
 namespace ucd {
 
@@ -39,6 +40,20 @@ hipError_t winograd_bwd_data(const Dims &d, int b, const float *dy, const float 
                              hipStream_t s);
 
 hipError_t fill_zero(float *p, size_t n, hipStream_t s);
+
+// Dry-run support: while a log is installed (per host thread) every launcher appends a one-line
+// description of the kernel it would launch and launches nothing.
+struct LaunchLog {
+    std::string text;
+    int launches = 0;
+    void add(const std::string &line)
+    {
+        if (!text.empty()) text += "; ";
+        text += line;
+        ++launches;
+    }
+};
+LaunchLog *&launch_log();
 
 // register-only MFMA loop (valu_per_mfma in {0, 2, 4, 8}); out holds blocks * 256 floats
 hipError_t mfma_probe(int valu_per_mfma, int blocks, int iters, float *out, hipStream_t s);

@@ -26,7 +26,7 @@ EXPORTS = [
     "ucd_strerror", "ucd_version", "ucd_workspace_size", "ucd_plan_from_table", "ucd_desirable_from_table",
     "ucd_wd_solve", "ucd_plan_wd_from_tables", "ucd_plan_fixed", "ucd_plan_query", "ucd_plan_destroy",
     "ucd_plan", "ucd_plan_wd", "ucd_bench_table", "ucd_bench_clear", "ucd_conv_fwd", "ucd_conv_bwd_data",
-    "ucd_conv_bwd_filter", "ucd_run_micro", "ucd_mfma_probe",
+    "ucd_conv_bwd_filter", "ucd_run_micro", "ucd_mfma_probe", "ucd_describe_micro",
 ]
 
 
@@ -81,6 +81,7 @@ def lib():
         L.ucd_conv_bwd_data.argtypes = [vp, vp, vp, vp, vp, sz, vp]
         L.ucd_conv_bwd_filter.argtypes = [vp, vp, vp, vp, ctypes.c_float, vp, sz, vp]
         L.ucd_run_micro.argtypes = [lp, i, i, i, vp, vp, vp, ctypes.c_float, vp, sz, vp]
+        L.ucd_describe_micro.argtypes = [lp, i, i, i, ctypes.c_char_p, sz, ip]
         L.ucd_mfma_probe.argtypes = [i, i, i, vp, sz, vp, ctypes.POINTER(ctypes.c_double)]
         _lib = L
     return _lib
@@ -308,3 +309,12 @@ def ucd_mfma_probe(valu_per_mfma, blocks, iters, scratch, stream=None):
     _check(lib().ucd_mfma_probe(valu_per_mfma, blocks, iters, _ptr(scratch), _nbytes(scratch), _stream(stream),
                                 ctypes.byref(flops)), "ucd_mfma_probe")
     return flops.value
+
+
+def ucd_describe_micro(desc, op, algo, b):
+    """(description string, number of kernel launches) of one algorithm on one micro-batch."""
+    buf = ctypes.create_string_buffer(2048)
+    n = ctypes.c_int(0)
+    _check(lib().ucd_describe_micro(ctypes.byref(desc), op, algo, b, buf, len(buf), ctypes.byref(n)),
+           "ucd_describe_micro")
+    return buf.value.decode(), n.value

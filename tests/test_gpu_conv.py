@@ -28,6 +28,8 @@ SHAPES = [
     Shape(2, 96, 9, 9, 192, 3, 3, 1, 1, "c96k192"),            # two 96-row tiles; BackwardData M = 96
     Shape(2, 2, 11, 11, 10, 4, 4, 1, 1, "crs32"),              # C*R*S = 32, 16-byte aligned filter rows
     Shape(2, 160, 6, 6, 160, 3, 3, 1, 1, "k160"),              # 96-row tiles with a ragged second tile
+    Shape(3, 120, 7, 7, 136, 3, 3, 1, 1, "deep"),              # few output tiles, long reduction: split + atomics
+    Shape(3, 130, 10, 10, 72, 3, 3, 2, 1, "deep-s2"),          # the same through BackwardData's stride phases
 ]
 
 DIVISIONS = {8: [[8], [1] * 8, [3, 5]], 5: [[5], [2, 3]], 4: [[4], [1, 3]], 3: [[3], [1, 2]],
