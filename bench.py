@@ -37,6 +37,8 @@ def parse():
     ap.add_argument("--batch", type=int, default=256)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-samples", type=int, default=4)
+    ap.add_argument("--bench-db", default=None,
+                    help="benchmark database file: loaded before planning if it exists, saved afterwards")
     return ap.parse_args()
 
 
@@ -184,12 +186,17 @@ def main():
     ws = torch.empty(WS_LIMIT // 4, dtype=torch.float32, device=dev)
     flops_per_step = 3 * sum(s.flops for s in layers)
 
+    if args.bench_db and os.path.exists(args.bench_db):
+        ucd.ucd_bench_load(args.bench_db)
     t0 = time.perf_counter()
     undiv = [st.plan(ucd, ucd.POLICY_UNDIVIDED, ws, WS_LIMIT) for st in states]
     t_plan_undiv = time.perf_counter() - t0
     t0 = time.perf_counter()
     plans = [st.plan(ucd, policy, ws, WS_LIMIT) for st in states]
     t_plan = time.perf_counter() - t0
+
+    if args.bench_db:
+        ucd.ucd_bench_save(args.bench_db)
 
     def step(pl):
         for st, p in zip(states, pl):

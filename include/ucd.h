@@ -161,6 +161,20 @@ int ucd_bench_table(const ucd_layer_t *layer, int op, uint64_t *t_ns, size_t *ws
 /* Forgets every cached timing. */
 void ucd_bench_clear(void);
 
+/* File-backed benchmark database (Section 3.4: timings are kept in a file so that benchmarking
+ * can happen offline and be shared between identical GPUs).
+ * ucd_bench_save writes every cached timing to a text file; ucd_bench_load merges a file into
+ * the cache (*n_loaded, may be NULL, receives the number of timings read) and refuses, with
+ * UCD_E_UNSUPPORTED, a file taken on a different device than the current one (a process without
+ * a GPU accepts any file).  ucd_bench_put injects one timing by hand.  Host only. */
+int ucd_bench_save(const char *path);
+int ucd_bench_load(const char *path, int *n_loaded);
+int ucd_bench_put(const ucd_layer_t *layer, int op, int algo, int b, uint64_t t_ns);
+
+/* WR plan from the cache alone (offline planning, no GPU work): like ucd_plan, but (algorithm, b)
+ * pairs without a cached timing count as not benchmarked.  The plan is executable. */
+int ucd_plan_cached(const ucd_layer_t *layer, int op, size_t ws_limit, int policy, ucd_plan_t **out);
+
 /* ---- execution (Section 2: micro-batches run one after another on one stream, sharing one
  * workspace; sample n of a micro-batch starting at offset o is sample o+n of the tensors) --- */
 

@@ -6,10 +6,12 @@
 
 #include <algorithm>
 #include <cmath>
+#include <cstdio>
 #include <cstring>
 #include <map>
 #include <mutex>
 #include <new>
+#include <string>
 #include <tuple>
 #include <vector>
 
@@ -497,6 +499,113 @@ void ucd_bench_clear(void)
 {
     std::lock_guard<std::mutex> g(g_cache_mu);
     g_cache.clear();
+}
+
+int ucd_bench_put(const ucd_layer_t *layer, int op, int algo, int b, uint64_t t_ns)
+{
+    if (!layer) return UCD_E_NULLPTR;
+    if (!layer_ok(layer) || op < 0 || op >= UCD_N_OP || algo < 0 || algo >= UCD_N_ALGO || b < 1 || t_ns == 0 ||
+        t_ns == UCD_TIME_INF)
+        return UCD_E_INVALID;
+    cache_put(key_of(layer, op, algo, b), t_ns);
+    return UCD_OK;
+}
+
+// File format: one header line "ucd-bench 1 <device>", then one line of 15 integers per timing:
+// C H W K R S stride_h stride_w pad_h pad_w dtype op algo b ns.
+static std::string device_tag()
+{
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return "none";
+    }
+    std::string tag = std::string(prop.gcnArchName) + "/" + std::to_string(prop.multiProcessorCount) + "cu";
+    for (char &ch : tag)
+        if (ch == ' ') ch = '_';
+    return tag;
+}
+
+int ucd_bench_save(const char *path)
+{
+    if (!path) return UCD_E_NULLPTR;
+    FILE *f = std::fopen(path, "w");
+    if (!f) return UCD_E_INVALID;
+    std::fprintf(f, "ucd-bench 1 %s\n", device_tag().c_str());
+    std::lock_guard<std::mutex> g(g_cache_mu);
+    for (const auto &kv : g_cache) {
+        const BenchKey &k = kv.first;
+        std::fprintf(f, "%d %d %d %d %d %d %d %d %d %d %d %d %d %d %llu\n", std::get<0>(k), std::get<1>(k),
+                     std::get<2>(k), std::get<3>(k), std::get<4>(k), std::get<5>(k), std::get<6>(k), std::get<7>(k),
+                     std::get<8>(k), std::get<9>(k), std::get<10>(k), std::get<11>(k), std::get<12>(k), std::get<13>(k),
+                     (unsigned long long)kv.second);
+    }
+    const bool ok = std::fclose(f) == 0;
+    return ok ? UCD_OK : UCD_E_INVALID;
+}
+
+int ucd_bench_load(const char *path, int *n_loaded)
+{
+    if (!path) return UCD_E_NULLPTR;
+    FILE *f = std::fopen(path, "r");
+    if (!f) return UCD_E_INVALID;
+    char magic[32] = {0}, dev[128] = {0};
+    int ver = 0;
+    if (std::fscanf(f, "%31s %d %127s", magic, &ver, dev) != 3 || std::strcmp(magic, "ucd-bench") != 0 || ver != 1) {
+        std::fclose(f);
+        return UCD_E_INVALID;
+    }
+    // timings are only meaningful on the device they were taken on; a process without a GPU
+    // (offline planning) accepts any file
+    const std::string here = device_tag();
+    if (here != "none" && std::strcmp(dev, "none") != 0 && here != dev) {
+        std::fclose(f);
+        return UCD_E_UNSUPPORTED;
+    }
+    std::vector<std::pair<BenchKey, uint64_t>> rows;
+    int v[14];
+    unsigned long long ns;
+    for (;;) {
+        int got = 0;
+        for (int i = 0; i < 14; ++i) got += std::fscanf(f, "%d", &v[i]) == 1;
+        if (got == 0) break;
+        if (got != 14 || std::fscanf(f, "%llu", &ns) != 1 || ns == 0) {
+            std::fclose(f);
+            return UCD_E_INVALID;
+        }
+        rows.push_back({BenchKey(v[0], v[1], v[2], v[3], v[4], v[5], v[6], v[7], v[8], v[9], v[10], v[11], v[12], v[13]),
+                        (uint64_t)ns});
+    }
+    std::fclose(f);
+    for (const auto &r : rows) cache_put(r.first, r.second);
+    if (n_loaded) *n_loaded = (int)rows.size();
+    return UCD_OK;
+}
+
+int ucd_plan_cached(const ucd_layer_t *layer, int op, size_t ws_limit, int policy, ucd_plan_t **out)
+{
+    if (!layer || !out) return UCD_E_NULLPTR;
+    if (!layer_ok(layer) || op < 0 || op >= UCD_N_OP || !policy_ok(policy)) return UCD_E_INVALID;
+    if (layer->dtype != 0 || !fits_32bit(layer, layer->N)) return UCD_E_UNSUPPORTED;
+    const int B = layer->N;
+    std::vector<uint64_t> t((size_t)UCD_N_ALGO * (B + 1), kTimeInf);
+    std::vector<size_t> m((size_t)UCD_N_ALGO * (B + 1), kWsNa);
+    for (int b : policy_sizes(policy, B))
+        for (int a = 0; a < UCD_N_ALGO; ++a) {
+            const size_t need = ws_size(layer, op, a, b);
+            if (need == UCD_WS_NA) continue;
+            m[(size_t)a * (B + 1) + b] = need;
+            uint64_t ns;
+            if (need <= ws_limit && cache_get(key_of(layer, op, a, b), ns)) t[(size_t)a * (B + 1) + b] = ns;
+        }
+    Table tab{B, UCD_N_ALGO, t.data(), m.data()};
+    Config cfg;
+    if (!wr_plan(tab, ws_limit, policy, cfg)) return UCD_E_INFEASIBLE;
+    ucd_plan_t *p = make_plan(cfg, layer, op);
+    if (!p) return UCD_E_NOMEM;
+    *out = p;
+    return UCD_OK;
 }
 
 int ucd_conv_fwd(const ucd_plan_t *plan, const void *x, const void *w, void *y, void *ws, size_t ws_bytes,

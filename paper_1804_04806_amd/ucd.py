@@ -27,6 +27,7 @@ EXPORTS = [
     "ucd_wd_solve", "ucd_plan_wd_from_tables", "ucd_plan_fixed", "ucd_plan_query", "ucd_plan_destroy",
     "ucd_plan", "ucd_plan_wd", "ucd_bench_table", "ucd_bench_clear", "ucd_conv_fwd", "ucd_conv_bwd_data",
     "ucd_conv_bwd_filter", "ucd_run_micro", "ucd_mfma_probe", "ucd_describe_micro",
+    "ucd_bench_save", "ucd_bench_load", "ucd_bench_put", "ucd_plan_cached",
 ]
 
 
@@ -81,6 +82,10 @@ def lib():
         L.ucd_conv_bwd_data.argtypes = [vp, vp, vp, vp, vp, sz, vp]
         L.ucd_conv_bwd_filter.argtypes = [vp, vp, vp, vp, ctypes.c_float, vp, sz, vp]
         L.ucd_run_micro.argtypes = [lp, i, i, i, vp, vp, vp, ctypes.c_float, vp, sz, vp]
+        L.ucd_bench_save.argtypes = [ctypes.c_char_p]
+        L.ucd_bench_load.argtypes = [ctypes.c_char_p, ip]
+        L.ucd_bench_put.argtypes = [lp, i, i, i, ctypes.c_uint64]
+        L.ucd_plan_cached.argtypes = [lp, i, sz, i, pp]
         L.ucd_describe_micro.argtypes = [lp, i, i, i, ctypes.c_char_p, sz, ip]
         L.ucd_mfma_probe.argtypes = [i, i, i, vp, sz, vp, ctypes.POINTER(ctypes.c_double)]
         _lib = L
@@ -318,3 +323,24 @@ def ucd_describe_micro(desc, op, algo, b):
     _check(lib().ucd_describe_micro(ctypes.byref(desc), op, algo, b, buf, len(buf), ctypes.byref(n)),
            "ucd_describe_micro")
     return buf.value.decode(), n.value
+
+
+def ucd_bench_save(path):
+    _check(lib().ucd_bench_save(str(path).encode()), "ucd_bench_save")
+
+
+def ucd_bench_load(path):
+    """Merges a benchmark file into the cache; returns the number of timings read."""
+    n = ctypes.c_int(0)
+    _check(lib().ucd_bench_load(str(path).encode(), ctypes.byref(n)), "ucd_bench_load")
+    return n.value
+
+
+def ucd_bench_put(desc, op, algo, b, t_ns):
+    _check(lib().ucd_bench_put(ctypes.byref(desc), op, algo, b, int(t_ns)), "ucd_bench_put")
+
+
+def ucd_plan_cached(desc, op, ws_limit, policy):
+    out = ctypes.c_void_p()
+    _check(lib().ucd_plan_cached(ctypes.byref(desc), op, ws_limit, policy, ctypes.byref(out)), "ucd_plan_cached")
+    return Plan(out)

@@ -146,3 +146,27 @@ def test_workspace_one_byte_short_is_refused():
     assert e.value.status == ucd.E_WS_TOO_SMALL
     torch.cuda.synchronize()
     assert float(y.abs().sum()) == 0.0      # nothing was launched
+
+
+def test_benchmark_db_roundtrip_on_device(tmp_path):
+    """Timings measured on the device survive save / clear / load, and planning from the loaded
+    cache (no GPU work) reproduces the plan."""
+    import torch
+    s = Shape(16, 32, 12, 12, 48, 3, 3, 1, 1, "db")
+    desc = ucd.layer(s)
+    _, (xd, wd, dyd) = device_buffers(s)
+    limit = 2 << 20
+    ws = torch.empty(limit // 4, dtype=torch.float32, device=xd.device)
+    y = torch.empty(s.y_shape, device=xd.device)
+    ucd.ucd_bench_clear()
+    plan = ucd.ucd_plan(desc, ucd.FWD, limit, ucd.POLICY_ALL, xd, wd, y, ws)
+    table = ucd.ucd_bench_table(desc, ucd.FWD, 16)
+    path = tmp_path / "bench.txt"
+    ucd.ucd_bench_save(path)
+    ucd.ucd_bench_clear()
+    assert ucd.ucd_bench_load(path) > 0
+    assert ucd.ucd_bench_table(desc, ucd.FWD, 16) == table
+    again = ucd.ucd_plan_cached(desc, ucd.FWD, limit, ucd.POLICY_ALL)
+    assert again.query() == plan.query()
+    ucd.ucd_conv_fwd(again, xd, wd, y, ws)
+    torch.cuda.synchronize()
