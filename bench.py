@@ -13,6 +13,10 @@ Prints ONE JSON line: throughput in TFLOP/s of algorithmic convolution flops
 single-algorithm plan, a roofline object for the dominant kernel and a CPU-oracle baseline.
 
     python bench.py [--gpus 1] [--steps 50] [--warmup 3] [--policy all|pow2|undivided]
+
+Other workloads of the same shape family can be timed with --workload (not the contract line):
+small (N=8, 64 KiB), resnet18 (64 MiB/layer, WR), densenet (B=64, 8 MiB/layer, WR),
+resnet50-wr (64 MiB/layer) and resnet50-wd (one 512 MiB budget over all 159 kernels, WD).
 """
 import argparse
 import json
@@ -27,14 +31,26 @@ METRIC = "conv ms/iter (fwd+bwdData+bwdFilter) @64MB workspace; TFLOP/s, % MFMA 
 FP32_MFMA_PEAK_TFLOPS = 157.3   # MI355X dense fp32 matrix peak: 256 CU x 2.4 GHz x 256 flop/clk/CU
 WS_LIMIT = 64 << 20
 
+# name -> (description, layer table, batch, per-layer limit or total budget, "wr" | "wd", default policy)
+WORKLOADS = {
+    "alexnet": ("AlexNet-shaped 5-layer conv stack", "config_alexnet", 256, 64 << 20, "wr", "all"),
+    "small": ("single small 3x3 layer", "config_small", 8, 64 << 10, "wr", "all"),
+    "resnet18": ("ResNet-18-shaped conv layers (20 layers)", "config_resnet18", 256, 64 << 20, "wr", "pow2"),
+    "densenet": ("DenseNet-BC-style block (24 layers)", "config_densenet_block", 64, 8 << 20, "wr", "pow2"),
+    "resnet50-wr": ("ResNet-50-shaped conv layers (53 layers)", "config_resnet50", 256, 64 << 20, "wr", "pow2"),
+    "resnet50-wd": ("ResNet-50-shaped conv layers (53 layers, 159 kernels)", "config_resnet50", 256, 512 << 20,
+                    "wd", "pow2"),
+}
+
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--policy", default="all", choices=["all", "pow2", "undivided"])
-    ap.add_argument("--batch", type=int, default=256)
+    ap.add_argument("--workload", default="alexnet", choices=sorted(WORKLOADS))
+    ap.add_argument("--policy", default=None, choices=["all", "pow2", "undivided"])
+    ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-samples", type=int, default=4)
     ap.add_argument("--bench-db", default=None,
@@ -42,19 +58,42 @@ def parse():
     return ap.parse_args()
 
 
+class Pool:
+    """One set of device buffers, sized for the largest layer, that every layer of a big
+    workload takes views of (a resident ResNet-50 at batch 256 would need hundreds of GB)."""
+
+    def __init__(self, layers, torch, dev):
+        nx = max(s.N * s.C * s.H * s.W for s in layers)
+        ny = max(s.N * s.K * s.P * s.Q for s in layers)
+        nw = max(s.K * s.C * s.R * s.S for s in layers)
+        g = torch.Generator(device=dev)
+        g.manual_seed(1234)
+        self.x = torch.rand(nx, device=dev, generator=g) * 2 - 1
+        self.dy = torch.rand(ny, device=dev, generator=g) * 2 - 1
+        self.w = torch.randn(nw, device=dev, generator=g) * 0.03
+        self.y = torch.empty(ny, dtype=torch.float32, device=dev)
+        self.dx = torch.empty(nx, dtype=torch.float32, device=dev)
+        self.dw = torch.empty(nw, dtype=torch.float32, device=dev)
+
+
 class LayerState:
     """Device tensors and plans of one layer."""
 
-    def __init__(self, s, idx, torch, ucd, synth, dev):
+    def __init__(self, s, idx, torch, ucd, synth, dev, pool=None):
         self.s = s
         self.desc = ucd.layer(s)
-        self.x = torch.from_numpy(synth.make_x(s, 0, idx)).to(dev)
-        self.w = torch.from_numpy(synth.make_w(s, 0, idx)).to(dev)
-        self.dy = torch.from_numpy(synth.make_dy(s, 0, idx)).to(dev)
-        self.y = torch.empty(s.y_shape, dtype=torch.float32, device=dev)
-        self.dx = torch.empty(s.x_shape, dtype=torch.float32, device=dev)
-        self.dw = torch.empty(s.w_shape, dtype=torch.float32, device=dev)
-        self.plans = {}
+        if pool is None:
+            self.x = torch.from_numpy(synth.make_x(s, 0, idx)).to(dev)
+            self.w = torch.from_numpy(synth.make_w(s, 0, idx)).to(dev)
+            self.dy = torch.from_numpy(synth.make_dy(s, 0, idx)).to(dev)
+            self.y = torch.empty(s.y_shape, dtype=torch.float32, device=dev)
+            self.dx = torch.empty(s.x_shape, dtype=torch.float32, device=dev)
+            self.dw = torch.empty(s.w_shape, dtype=torch.float32, device=dev)
+        else:
+            nx, ny, nw = s.N * s.C * s.H * s.W, s.N * s.K * s.P * s.Q, s.K * s.C * s.R * s.S
+            self.x, self.dx = pool.x[:nx], pool.dx[:nx]
+            self.dy, self.y = pool.dy[:ny], pool.y[:ny]
+            self.w, self.dw = pool.w[:nw], pool.dw[:nw]
 
     def plan(self, ucd, policy, ws, limit):
         """WR planning for the three operations; each benchmark clobbers only output buffers."""
@@ -64,10 +103,37 @@ class LayerState:
         p[ucd.BWD_FILTER] = ucd.ucd_plan(self.desc, ucd.BWD_FILTER, limit, policy, self.x, self.dw, self.dy, ws)
         return p
 
-    def run(self, ucd, plans, ws):
-        ucd.ucd_conv_fwd(plans[ucd.FWD], self.x, self.w, self.y, ws)
-        ucd.ucd_conv_bwd_data(plans[ucd.BWD_DATA], self.dy, self.w, self.dx, ws)
-        ucd.ucd_conv_bwd_filter(plans[ucd.BWD_FILTER], self.x, self.dy, self.dw, 0.0, ws)
+    def run(self, ucd, plans, ws, offsets=None):
+        """offsets: byte offsets of the three kernels' workspace segments (WD), else one shared workspace."""
+        if offsets is None:
+            ucd.ucd_conv_fwd(plans[ucd.FWD], self.x, self.w, self.y, ws)
+            ucd.ucd_conv_bwd_data(plans[ucd.BWD_DATA], self.dy, self.w, self.dx, ws)
+            ucd.ucd_conv_bwd_filter(plans[ucd.BWD_FILTER], self.x, self.dy, self.dw, 0.0, ws)
+        else:
+            base, total = ws.data_ptr(), ws.numel() * 4
+            f, d, g = offsets
+            ucd.ucd_conv_fwd(plans[ucd.FWD], self.x, self.w, self.y, base + f, total - f)
+            ucd.ucd_conv_bwd_data(plans[ucd.BWD_DATA], self.dy, self.w, self.dx, base + d, total - d)
+            ucd.ucd_conv_bwd_filter(plans[ucd.BWD_FILTER], self.x, self.dy, self.dw, 0.0, base + g, total - g)
+
+
+def plan_wd(ucd, states, pool, policy, ws, budget):
+    """One global budget over all kernels (layers x {fwd, bwdData, bwdFilter}): desirable sets +
+    0-1 programme.  Returns per-layer plan dicts and per-layer segment offsets."""
+    descs, ops = [], []
+    for st in states:
+        for op in (ucd.FWD, ucd.BWD_DATA, ucd.BWD_FILTER):
+            descs.append(st.desc)
+            ops.append(op)
+    # scratch tensors for the benchmarks: outputs are clobbered, so hand over the output buffers
+    # for the roles that get written and the input buffers otherwise is not possible in one call;
+    # the pool's x / w / dy are re-randomised afterwards
+    plans, offs = ucd.ucd_plan_wd(descs, ops, budget, policy, pool.x, pool.w, pool.dy, ws)
+    per_layer, per_off = [], []
+    for i in range(len(states)):
+        per_layer.append({ucd.FWD: plans[3 * i], ucd.BWD_DATA: plans[3 * i + 1], ucd.BWD_FILTER: plans[3 * i + 2]})
+        per_off.append(tuple(offs[3 * i:3 * i + 3]))
+    return per_layer, per_off
 
 
 def time_steps(torch, fn, steps, warmup):
@@ -179,31 +245,44 @@ def main():
         sys.exit(3)
     ucd.lib()  # fails loudly if the HIP library is missing
     dev = torch.device("cuda:0")
-    policy = {"all": ucd.POLICY_ALL, "pow2": ucd.POLICY_POW2, "undivided": ucd.POLICY_UNDIVIDED}[args.policy]
-
-    layers = synth.config_alexnet(args.batch)
-    states = [LayerState(s, i, torch, ucd, synth, dev) for i, s in enumerate(layers)]
-    ws = torch.empty(WS_LIMIT // 4, dtype=torch.float32, device=dev)
+    title, table, batch0, limit, mode, policy0 = WORKLOADS[args.workload]
+    batch = args.batch or batch0
+    policy_name = args.policy or policy0
+    policy = {"all": ucd.POLICY_ALL, "pow2": ucd.POLICY_POW2, "undivided": ucd.POLICY_UNDIVIDED}[policy_name]
+    layers = getattr(synth, table)() if args.workload == "small" else getattr(synth, table)(batch)
+    pool = None if args.workload in ("alexnet", "small") else Pool(layers, torch, dev)
+    states = [LayerState(s, i, torch, ucd, synth, dev, pool) for i, s in enumerate(layers)]
+    ws = torch.empty(max(limit, 4) // 4, dtype=torch.float32, device=dev)
     flops_per_step = 3 * sum(s.flops for s in layers)
 
     if args.bench_db and os.path.exists(args.bench_db):
         ucd.ucd_bench_load(args.bench_db)
+    offsets = None
     t0 = time.perf_counter()
-    undiv = [st.plan(ucd, ucd.POLICY_UNDIVIDED, ws, WS_LIMIT) for st in states]
+    # baseline: the best single algorithm per kernel with no workspace beyond its own layer limit
+    # (WR undivided); for the WD workload the same per-kernel share of the budget
+    base_limit = limit if mode == "wr" else limit // (3 * len(layers))
+    undiv = [st.plan(ucd, ucd.POLICY_UNDIVIDED, ws, base_limit) for st in states]
     t_plan_undiv = time.perf_counter() - t0
     t0 = time.perf_counter()
-    plans = [st.plan(ucd, policy, ws, WS_LIMIT) for st in states]
+    if mode == "wr":
+        plans = [st.plan(ucd, policy, ws, limit) for st in states]
+    else:
+        plans, offsets = plan_wd(ucd, states, pool, policy, ws, limit)
+        pool.x.uniform_(-1, 1)
+        pool.dy.uniform_(-1, 1)
+        pool.w.normal_(0, 0.03)
     t_plan = time.perf_counter() - t0
 
     if args.bench_db:
         ucd.ucd_bench_save(args.bench_db)
 
-    def step(pl):
-        for st, p in zip(states, pl):
-            st.run(ucd, p, ws)
+    def step(pl, offs=None):
+        for i, (st, p) in enumerate(zip(states, pl)):
+            st.run(ucd, p, ws, None if offs is None else offs[i])
 
     ms_undiv = time_steps(torch, lambda: step(undiv), args.steps, args.warmup)
-    ms = time_steps(torch, lambda: step(plans), args.steps, args.warmup)
+    ms = time_steps(torch, lambda: step(plans, offsets), args.steps, args.warmup)
 
     tflops = flops_per_step / (ms * 1e-3) / 1e12
     roof, kernel_table = dominant_kernel_roofline(torch, ucd, states, plans, ws, reps=5)
@@ -229,16 +308,20 @@ def main():
         "metric": METRIC, "value": round(tflops, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"AlexNet-shaped 5-layer conv stack, batch {args.batch}, fp32 NCHW, "
-                               "64 MiB workspace per layer (WR)", "policy": args.policy,
-                   "global_batch": args.batch, "ws_limit_bytes": WS_LIMIT},
+        "config": {"workload": f"{title}, batch {batch}, fp32 NCHW, "
+                               + (f"{limit >> 20} MiB workspace per layer (WR)" if mode == "wr" and limit >= 1 << 20
+                                  else f"{limit >> 10} KiB workspace per layer (WR)" if mode == "wr"
+                                  else f"one {limit >> 20} MiB workspace budget over {3 * len(layers)} kernels (WD)"),
+                   "policy": policy_name, "global_batch": batch, "ws_limit_bytes": limit, "mode": mode},
         "ms_per_iter": round(ms, 4), "pct_fp32_mfma_peak": round(100 * tflops / FP32_MFMA_PEAK_TFLOPS, 2),
         "undivided_ms_per_iter": round(ms_undiv, 4), "speedup_vs_undivided": round(ms_undiv / ms, 4),
         "plan_seconds": round(t_plan, 2), "plan_seconds_undivided": round(t_plan_undiv, 2),
         "gflop_per_step": round(flops_per_step / 1e9, 1),
         "roofline": roof,
         "kernels": kernel_table,
-        "cpu_baseline": None if args.no_cpu_baseline else cpu_baseline(layers, args.cpu_samples),
+        "cpu_baseline": None if args.no_cpu_baseline else cpu_baseline(layers, min(args.cpu_samples, batch)),
+        "peak_ws_MiB": round(max(max(p[op].ws_bytes for op in p) for p in plans) / 2 ** 20, 2),
+        "total_ws_MiB": round(sum(p[op].ws_bytes for p in plans for op in p) / 2 ** 20, 2),
         "plans": plan_report,
     }
     print(json.dumps(out))
