@@ -62,18 +62,23 @@ struct Tile {
     static_assert(WM >= 1 && WN >= 1, "tile too small for the wave layout");
 };
 
-// Block id -> tile coordinates.  Workgroups are dealt round-robin to the 8 XCDs by linear id;
-// this remaps ids so that each XCD (own L2) walks a contiguous range of tiles in which the M
-// index runs fastest, i.e. the tiles that re-read the same B (activation) columns share an L2.
-__device__ __forceinline__ void xcd_tile(int tiles_m, int tiles_n, int &tile_m, int &tile_n)
+// Block id -> (reduction split, tile).  Workgroups are dealt round-robin to the 8 XCDs by linear
+// id (x fastest, then y); this remaps ids so that each XCD (own L2) walks a contiguous range of
+// work items ordered split-major, then tile column, then tile row.  Tiles that re-read the same
+// B (activation) columns, and all tiles of one reduction chunk (which re-read the same slices of
+// both operands), therefore share an L2 instead of pulling the data into all eight.
+__device__ __forceinline__ void xcd_tile(int tiles_m, int tiles_n, int &tile_m, int &tile_n, int &split)
 {
-    const uint32_t total = (uint32_t)tiles_m * (uint32_t)tiles_n;
-    const uint32_t id = blockIdx.x;
+    const uint32_t tiles = (uint32_t)tiles_m * (uint32_t)tiles_n;
+    const uint32_t total = tiles * gridDim.y;
+    const uint32_t id = blockIdx.x + gridDim.x * blockIdx.y;
     const uint32_t xcd = id & 7u, slot = id >> 3;
     const uint32_t q = total >> 3, rem = total & 7u;
     const uint32_t v = xcd * q + (xcd < rem ? xcd : rem) + slot;
-    tile_m = (int)(v % (uint32_t)tiles_m);
-    tile_n = (int)(v / (uint32_t)tiles_m);
+    split = (int)(v / tiles);
+    const uint32_t t = v - (uint32_t)split * tiles;
+    tile_m = (int)(t % (uint32_t)tiles_m);
+    tile_n = (int)(t / (uint32_t)tiles_m);
 }
 
 // ---- operand loaders ---------------------------------------------------------------------------
@@ -583,10 +588,10 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(AParams pa, BParams pb, 
         pb.t += b_batch * blockIdx.z;
         pe.out += c_batch * blockIdx.z;
     }
-    int tile_m, tile_n;
-    xcd_tile(tiles_m, tiles_n, tile_m, tile_n);
+    int tile_m, tile_n, split;
+    xcd_tile(tiles_m, tiles_n, tile_m, tile_n, split);
     const int m0 = tile_m * T::BM, n0 = tile_n * T::BN;
-    const int k_begin = blockIdx.y * k_chunk;
+    const int k_begin = split * k_chunk;
     const int k_end = min(Kd, k_begin + k_chunk);
 
     ALoader la;
