@@ -31,6 +31,21 @@ METRIC = "conv ms/iter (fwd+bwdData+bwdFilter) @64MB workspace; TFLOP/s, % MFMA 
 FP32_MFMA_PEAK_TFLOPS = 157.3   # MI355X dense fp32 matrix peak: 256 CU x 2.4 GHz x 256 flop/clk/CU
 WS_LIMIT = 64 << 20
 
+# HBM bytes per launch (fetched + written) of the GEMM instantiations of the default workload's
+# planned step, from two rocprofv3 --pmc passes over this script (FETCH_SIZE, then WRITE_SIZE, each
+# scaled by what the counter reads for a plain device copy of known size: x2.00 and x1.00), mean
+# over the dispatches of a run whose benchmark cache came from a file, so that every dispatch has
+# a shape of the step.  Summary: profiles/bench_alexnet_b256_ws64MiB_kernel_stats.md.
+# A profiler cannot run inside the timed script, so these are recorded figures; they apply to
+# the AlexNet workload at batch 256 only and `traffic` is null for anything else.
+MEASURED_TRAFFIC_BYTES = {
+    "gemm_kernel<Tile<128x128>,PixelKLane<dy>,PixelKLane<x>,EpiAtomic>": 274.6e6,
+    "gemm_kernel<Tile<96x128>,PixelKLane<dy>,PixelKLane<x>,EpiAtomic>": 569.8e6,
+    "gemm_kernel<Tile<128x128>,KLane0,GatherNLane<taps<=31>,EpiNCHW>": 233.7e6,
+    "gemm_kernel<Tile<96x128>,FilterKLane,GatherNLane<taps<=31>,EpiNCHW>": 279.4e6,
+    "gemm_kernel<Tile<128x128>,FilterKLane,GatherNLane<taps<=31>,EpiNCHW>": 182.1e6,
+}
+
 # name -> (description, layer table, batch, per-layer limit or total budget, "wr" | "wd", default policy)
 WORKLOADS = {
     "alexnet": ("AlexNet-shaped 5-layer conv stack", "config_alexnet", 256, 64 << 20, "wr", "all"),
@@ -162,7 +177,7 @@ def kernel_class(ucd, desc, op, algo, b):
     return name + (" (after fill_zero_kernel)" if len(parts) > 1 else "")
 
 
-def dominant_kernel_roofline(torch, ucd, states, plans, ws, reps):
+def dominant_kernel_roofline(torch, ucd, states, plans, ws, reps, traffic_table=None):
     """HIP-event timing (events recorded on the launch stream) of every single-kernel micro-batch
     launch of the planned step, grouped by kernel instantiation; returns the roofline object of
     the instantiation with the largest total time, and the per-instantiation table.
@@ -206,7 +221,8 @@ def dominant_kernel_roofline(torch, ucd, states, plans, ws, reps):
     name, g = max(groups.items(), key=lambda kv: kv[1]["ms"])
     achieved = g["flops"] / (g["ms"] * 1e-3) / 1e12
     roof = {"bound": "mfma", "kernel": name, "achieved": round(achieved, 2), "peak": FP32_MFMA_PEAK_TFLOPS,
-            "unit": "TFLOP/s", "frac": round(achieved / FP32_MFMA_PEAK_TFLOPS, 4), "traffic": None,
+            "unit": "TFLOP/s", "frac": round(achieved / FP32_MFMA_PEAK_TFLOPS, 4),
+            "traffic": (traffic_table or {}).get(name.split(" (after")[0]),
             "launches_per_step": g["launches"], "avg_launch_ms": round(g["ms"] / g["launches"], 4),
             "flops_per_launch": g["flops"] / g["launches"]}
     return roof, table
@@ -285,7 +301,9 @@ def main():
     ms = time_steps(torch, lambda: step(plans, offsets), args.steps, args.warmup)
 
     tflops = flops_per_step / (ms * 1e-3) / 1e12
-    roof, kernel_table = dominant_kernel_roofline(torch, ucd, states, plans, ws, reps=5)
+    roof, kernel_table = dominant_kernel_roofline(
+        torch, ucd, states, plans, ws, reps=5,
+        traffic_table=MEASURED_TRAFFIC_BYTES if args.workload == "alexnet" and batch == 256 else None)
 
     plan_report = []
     for st, p, u in zip(states, plans, undiv):
