@@ -83,8 +83,11 @@ __device__ __forceinline__ void xcd_tile(int tiles_m, int tiles_n, int &tile_m, 
 
 // ---- operand loaders ---------------------------------------------------------------------------
 // Common interface:  init(params, tile_origin, extent)  once per workgroup;
-//                    fetch(k0, k_end, regs)  global -> registers for reduction rows [k0, k0+BK);
-//                    commit(lds_tile, regs)  registers -> LDS tile laid out [BK][LD].
+//                    prep(k0, k_end, peer)   per-step state for reduction rows [k0, k0+BK);
+//                    load(i, regs)           global -> register, element i of the thread's NE;
+//                    store(lds_tile, i, regs) register -> LDS tile laid out [BK][LD].
+// Any k0 is legal: rows at or past k_end read as 0 (the main loop prefetches two tiles ahead and
+// does not special-case the end of the reduction).
 // Elements outside [0, extent) x [0, k_end) read as 0.  All global reads are raw buffer loads
 // through a resource that spans exactly the operand (`bytes`): an element that must read as 0
 // gets the byte offset kOob, which the hardware range check turns into 0 without touching
@@ -148,6 +151,7 @@ struct GatherNLaneT {
     uint32_t voff;        // per-thread byte offset
     uint32_t nmask, nmask_w;  // bit set = tap outside the image (bit 31 always set)
     int col, row0;
+    int k0_, k_end_;
 
     __device__ __forceinline__ void init(const GatherParams &prm, int origin, int extent)
     {
@@ -183,33 +187,33 @@ struct GatherNLaneT {
         }
     }
     template <class Peer>
-    __device__ __forceinline__ void fetch(int k0, int k_end, float (&r)[NE], const Peer &) const
+    __device__ __forceinline__ void prep(int k0, int k_end, const Peer &)
     {
-        uint32_t vo[NE], so[NE];
-#pragma unroll
-        for (int i = 0; i < NE; ++i) {
-            const int kk = k0 + row0 + RP * i;  // wave-uniform: everything up to `so` is scalar
-            uint32_t c, tap, tr, ts;
-            p->taps.divmod((uint32_t)kk, c, tap);
-            p->taps_w.divmod(tap, tr, ts);
-            const uint32_t dead = (uint32_t)((k_end - 1 - kk) >> 31);  // all ones for rows past the end
-            so[i] = ~dead & (4u * (uint32_t)(((int)c * p->Ht + p->dir * (int)tr) * p->Wt + p->dir * (int)ts + p->shift_row));
-            if (SMALL) {
-                const uint32_t bit = tap | (dead & 31u);
-                vo[i] = ((nmask >> bit) << 31) | voff;
-            } else {
-                const uint32_t bit = tr | (dead & 31u);
-                vo[i] = (((nmask >> bit) | (nmask_w >> ts)) << 31) | voff;
-            }
-        }
-#pragma unroll
-        for (int i = 0; i < NE; ++i)
-            r[i] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc, (int)vo[i], (int)so[i], 0));
+        k0_ = k0;
+        k_end_ = k_end;
     }
-    __device__ __forceinline__ void commit(float *lds, const float (&r)[NE]) const
+    __device__ __forceinline__ void load(int i, float (&r)[NE]) const
     {
-#pragma unroll
-        for (int i = 0; i < NE; ++i) lds[(row0 + RP * i) * LD + col] = r[i];
+        const int kk = k0_ + row0 + RP * i;  // wave-uniform: everything up to `so` is scalar
+        uint32_t c, tap, tr, ts;
+        p->taps.divmod((uint32_t)kk, c, tap);
+        p->taps_w.divmod(tap, tr, ts);
+        const uint32_t dead = (uint32_t)((k_end_ - 1 - kk) >> 31);  // all ones for rows past the end
+        const uint32_t so =
+            ~dead & (4u * (uint32_t)(((int)c * p->Ht + p->dir * (int)tr) * p->Wt + p->dir * (int)ts + p->shift_row));
+        uint32_t vo;
+        if (SMALL) {
+            const uint32_t bit = tap | (dead & 31u);
+            vo = ((nmask >> bit) << 31) | voff;
+        } else {
+            const uint32_t bit = tr | (dead & 31u);
+            vo = (((nmask >> bit) | (nmask_w >> ts)) << 31) | voff;
+        }
+        r[i] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc, (int)vo, (int)so, 0));
+    }
+    __device__ __forceinline__ void store(float *lds, int i, const float (&r)[NE]) const
+    {
+        lds[(row0 + RP * i) * LD + col] = r[i];
     }
 };
 template <int TD> using GatherNLane = GatherNLaneT<TD, true>;
@@ -258,6 +262,8 @@ struct KLane0 {
     __amdgpu_buffer_rsrc_t rsrc;
     int kl, c0;
     uint32_t voff;  // byte offset of (row kl, position origin + c0)
+    uint32_t vo_;
+    int k0_;
 
     __device__ __forceinline__ void init(const KLaneParams &prm, int origin, int)
     {
@@ -268,18 +274,19 @@ struct KLane0 {
         voff = 4u * (uint32_t)(kl * prm.row_stride + (origin + c0) * prm.col_stride);
     }
     template <class Peer>
-    __device__ __forceinline__ void fetch(int k0, int k_end, float (&r)[NE], const Peer &) const
+    __device__ __forceinline__ void prep(int k0, int k_end, const Peer &)
     {
-        const uint32_t vo = k0 + kl < k_end ? voff : kOob;  // rows past the end read as zero
-#pragma unroll
-        for (int i = 0; i < NE; ++i)
-            r[i] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(
-                rsrc, (int)vo, (int)(4u * (uint32_t)(k0 * p->row_stride + CP * i * p->col_stride)), 0));
+        vo_ = k0 + kl < k_end ? voff : kOob;  // rows past the end read as zero
+        k0_ = k0;
     }
-    __device__ __forceinline__ void commit(float *lds, const float (&r)[NE]) const
+    __device__ __forceinline__ void load(int i, float (&r)[NE]) const
     {
-#pragma unroll
-        for (int i = 0; i < NE; ++i) lds[kl * LD + c0 + CP * i] = r[i];
+        r[i] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(
+            rsrc, (int)vo_, (int)(4u * (uint32_t)(k0_ * p->row_stride + CP * i * p->col_stride)), 0));
+    }
+    __device__ __forceinline__ void store(float *lds, int i, const float (&r)[NE]) const
+    {
+        lds[kl * LD + c0 + CP * i] = r[i];
     }
 };
 
@@ -296,6 +303,7 @@ struct FilterKLane {
     __amdgpu_buffer_rsrc_t rsrc;
     int kl, c0;
     uint32_t coff0;  // byte offset of position origin + c0
+    uint32_t vo_;
 
     __device__ __forceinline__ void init(const KLaneParams &prm, int origin, int)
     {
@@ -306,7 +314,7 @@ struct FilterKLane {
         coff0 = 4u * (uint32_t)((origin + c0) * prm.col_stride);
     }
     template <class Peer>
-    __device__ __forceinline__ void fetch(int k0, int k_end, float (&r)[NE], const Peer &) const
+    __device__ __forceinline__ void prep(int k0, int k_end, const Peer &)
     {
         const int kk = k0 + kl;
         uint32_t k, tap;
@@ -320,16 +328,16 @@ struct FilterKLane {
             roff = (int)k * p->k_stride + (p->tap_add_h + p->tap_mul_h * (int)tr) * p->s_mem + p->tap_add_w +
                    p->tap_mul_w * (int)ts;
         }
-        const uint32_t vo = kk < k_end ? 4u * (uint32_t)roff + coff0 : kOob;
-#pragma unroll
-        for (int i = 0; i < NE; ++i)
-            r[i] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(
-                rsrc, (int)vo, (int)(4u * (uint32_t)(CP * i * p->col_stride)), 0));
+        vo_ = kk < k_end ? 4u * (uint32_t)roff + coff0 : kOob;
     }
-    __device__ __forceinline__ void commit(float *lds, const float (&r)[NE]) const
+    __device__ __forceinline__ void load(int i, float (&r)[NE]) const
     {
-#pragma unroll
-        for (int i = 0; i < NE; ++i) lds[kl * LD + c0 + CP * i] = r[i];
+        r[i] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(
+            rsrc, (int)vo_, (int)(4u * (uint32_t)(CP * i * p->col_stride)), 0));
+    }
+    __device__ __forceinline__ void store(float *lds, int i, const float (&r)[NE]) const
+    {
+        lds[kl * LD + c0 + CP * i] = r[i];
     }
 };
 
@@ -353,7 +361,8 @@ struct PixelKLane {
     int kl, c0;
     uint32_t coffb[NV];       // x: byte offset of each position's (c, r, s); dy: of position origin + c0
     uint32_t rs[NV];          // x: r | s << 8
-    mutable uint32_t n_, rest_;  // decode of this step's reduction row, for the peer
+    uint32_t n_, rest_;       // decode of this step's reduction row, for the peer
+    uint32_t vo_, nrow_, ncol_;  // this step's row offset and window masks
 
     __device__ __forceinline__ void init(const KLaneParams &prm, int origin, int extent)
     {
@@ -383,40 +392,40 @@ struct PixelKLane {
         }
     }
     template <class Peer>
-    __device__ __forceinline__ void fetch(int k0, int k_end, float (&r)[NE], const Peer &peer) const
+    __device__ __forceinline__ void prep(int k0, int k_end, const Peer &peer)
     {
         const int kk = k0 + kl;
         const bool rowok = kk < k_end;
         if constexpr (!WINDOW) {
             p->grid_hw.divmod((uint32_t)kk, n_, rest_);
             // grid is the tensor's own plane here: (a, b) -> a*Wt + b == rest
-            const uint32_t vo = rowok ? 4u * (uint32_t)((int)n_ * p->n_stride + (int)rest_) + coffb[0] : kOob;
-            const uint32_t step = 4u * (uint32_t)(CP * p->Ht * p->Wt);  // scalar: 16 channels further
-#pragma unroll
-            for (int i = 0; i < NE; ++i)
-                r[i] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc, (int)vo, (int)(step * (uint32_t)i), 0));
+            vo_ = rowok ? 4u * (uint32_t)((int)n_ * p->n_stride + (int)rest_) + coffb[0] : kOob;
         } else {
             uint32_t a, b;
             p->grid_w.divmod(peer.rest_, a, b);
             const int hb = (int)a * p->mul_h + p->add_h, wb = (int)b * p->mul_w + p->add_w;
-            const uint32_t rterm = 4u * (uint32_t)((int)peer.n_ * p->n_stride + hb * p->Wt + wb + p->shift);
+            vo_ = 4u * (uint32_t)((int)peer.n_ * p->n_stride + hb * p->Wt + wb + p->shift);
             // taps r in [lo, hi) are inside the image; everything else (and bit 31) is masked
             const int lo_h = min(max(-hb, 0), 31), hi_h = max(min(p->Ht - hb, 31), lo_h);
             const int lo_w = min(max(-wb, 0), 31), hi_w = max(min(p->Wt - wb, 31), lo_w);
-            uint32_t nrow = ~(((1u << (hi_h - lo_h)) - 1u) << lo_h);
-            const uint32_t ncol = ~(((1u << (hi_w - lo_w)) - 1u) << lo_w);
-            nrow = rowok ? nrow : 0xFFFFFFFFu;
-#pragma unroll
-            for (int i = 0; i < NE; ++i) {
-                const uint32_t t = (nrow >> (rs[i] & 0xffu)) | (ncol >> (rs[i] >> 8));
-                r[i] = buf_load(rsrc, (t << 31) | (rterm + coffb[i]));
-            }
+            const uint32_t nrow = ~(((1u << (hi_h - lo_h)) - 1u) << lo_h);
+            ncol_ = ~(((1u << (hi_w - lo_w)) - 1u) << lo_w);
+            nrow_ = rowok ? nrow : 0xFFFFFFFFu;
         }
     }
-    __device__ __forceinline__ void commit(float *lds, const float (&r)[NE]) const
+    __device__ __forceinline__ void load(int i, float (&r)[NE]) const
     {
-#pragma unroll
-        for (int i = 0; i < NE; ++i) lds[kl * LD + c0 + CP * i] = r[i];
+        if constexpr (!WINDOW) {
+            const uint32_t step = 4u * (uint32_t)(CP * p->Ht * p->Wt);  // scalar: 16 channels further
+            r[i] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc, (int)vo_, (int)(step * (uint32_t)i), 0));
+        } else {
+            const uint32_t t = (nrow_ >> (rs[i] & 0xffu)) | (ncol_ >> (rs[i] >> 8));
+            r[i] = buf_load(rsrc, (t << 31) | (vo_ + coffb[i]));
+        }
+    }
+    __device__ __forceinline__ void store(float *lds, int i, const float (&r)[NE]) const
+    {
+        lds[kl * LD + c0 + CP * i] = r[i];
     }
 };
 template <int TD> using DyKLane = PixelKLane<TD, false>;
@@ -442,6 +451,7 @@ struct DenseNLane {
     __amdgpu_buffer_rsrc_t rsrc;
     int col, row0, j_;
     bool ok_;
+    int k0_, k_end_;
 
     __device__ __forceinline__ void init(const DenseParams &prm, int origin, int extent)
     {
@@ -454,23 +464,22 @@ struct DenseNLane {
         ok_ = j_ < extent;
     }
     template <class Peer>
-    __device__ __forceinline__ void fetch(int k0, int k_end, f32x4 (&r)[NE], const Peer &) const
+    __device__ __forceinline__ void prep(int k0, int k_end, const Peer &)
     {
-#pragma unroll
-        for (int i = 0; i < NE; ++i) {
-            const int row = row0 + RP * i;
-            const int kk = k0 + row;
-            const bool ok = ok_ && row < kBK && kk < k_end;
-            r[i] = buf_load4(rsrc, ok ? (uint32_t)(kk * p->ld + j_) * 4u : kOob);
-        }
+        k0_ = k0;
+        k_end_ = k_end;
     }
-    __device__ __forceinline__ void commit(float *lds, const f32x4 (&r)[NE]) const
+    __device__ __forceinline__ void load(int i, f32x4 (&r)[NE]) const
     {
-#pragma unroll
-        for (int i = 0; i < NE; ++i) {
-            const int row = row0 + RP * i;
-            if (row < kBK) *reinterpret_cast<f32x4 *>(lds + row * LD + col) = r[i];
-        }
+        const int row = row0 + RP * i;
+        const int kk = k0_ + row;
+        const bool ok = ok_ && row < kBK && kk < k_end_;
+        r[i] = buf_load4(rsrc, ok ? (uint32_t)(kk * p->ld + j_) * 4u : kOob);
+    }
+    __device__ __forceinline__ void store(float *lds, int i, const f32x4 (&r)[NE]) const
+    {
+        const int row = row0 + RP * i;
+        if (row < kBK) *reinterpret_cast<f32x4 *>(lds + row * LD + col) = r[i];
     }
 };
 
@@ -486,6 +495,7 @@ struct DenseNLaneS {
     __amdgpu_buffer_rsrc_t rsrc;
     int col, row0, j_;
     bool ok_;
+    int k0_, k_end_;
 
     __device__ __forceinline__ void init(const DenseParams &prm, int origin, int extent)
     {
@@ -498,18 +508,19 @@ struct DenseNLaneS {
         ok_ = j_ < extent;
     }
     template <class Peer>
-    __device__ __forceinline__ void fetch(int k0, int k_end, float (&r)[NE], const Peer &) const
+    __device__ __forceinline__ void prep(int k0, int k_end, const Peer &)
     {
-#pragma unroll
-        for (int i = 0; i < NE; ++i) {
-            const int kk = k0 + row0 + RP * i;
-            r[i] = buf_load(rsrc, (kk < k_end && ok_) ? (uint32_t)(kk * p->ld + j_) * 4u : kOob);
-        }
+        k0_ = k0;
+        k_end_ = k_end;
     }
-    __device__ __forceinline__ void commit(float *lds, const float (&r)[NE]) const
+    __device__ __forceinline__ void load(int i, float (&r)[NE]) const
     {
-#pragma unroll
-        for (int i = 0; i < NE; ++i) lds[(row0 + RP * i) * LD + col] = r[i];
+        const int kk = k0_ + row0 + RP * i;
+        r[i] = buf_load(rsrc, (kk < k_end_ && ok_) ? (uint32_t)(kk * p->ld + j_) * 4u : kOob);
+    }
+    __device__ __forceinline__ void store(float *lds, int i, const float (&r)[NE]) const
+    {
+        lds[(row0 + RP * i) * LD + col] = r[i];
     }
 };
 
@@ -616,52 +627,83 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(AParams pa, BParams pb, 
     typename ALoader::Regs ra;
     typename BLoader::Regs rb;
 
-    if (k_begin < k_end) {
-        la.fetch(k_begin, k_end, ra.r, lb);
-        lb.fetch(k_begin, k_end, rb.r, la);
-        la.commit(lds[0], ra.r);
-        lb.commit(lds[0] + kBK * T::LDA, rb.r);
-    }
+    // Software pipeline, two tiles deep with one register set: during step s (MFMAs on tile s from
+    // one LDS buffer) the registers holding tile s+1, loaded during step s-1, are written to the
+    // other LDS buffer and immediately reloaded with tile s+2.  That work is dealt out over the 8
+    // k-pairs of the step, so that each wave always has MFMAs in flight while it issues its loads
+    // and LDS writes (a wave that issued them in one block would leave the matrix pipe idle unless
+    // another wave happened to be in its MFMA phase).
+    constexpr int NA = ALoader::NE, NB = BLoader::NE, kGroups = kBK / 2;
+    la.prep(k_begin, k_end, lb);
+    lb.prep(k_begin, k_end, la);
+#pragma unroll
+    for (int i = 0; i < NA; ++i) la.load(i, ra.r);
+#pragma unroll
+    for (int i = 0; i < NB; ++i) lb.load(i, rb.r);
+#pragma unroll
+    for (int i = 0; i < NA; ++i) la.store(lds[0], i, ra.r);
+#pragma unroll
+    for (int i = 0; i < NB; ++i) lb.store(lds[0] + kBK * T::LDA, i, rb.r);
+    la.prep(k_begin + kBK, k_end, lb);
+    lb.prep(k_begin + kBK, k_end, la);
+#pragma unroll
+    for (int i = 0; i < NA; ++i) la.load(i, ra.r);
+#pragma unroll
+    for (int i = 0; i < NB; ++i) lb.load(i, rb.r);
     __syncthreads();
 
     int buf = 0;
     for (int k0 = k_begin; k0 < k_end; k0 += kBK) {
-        const bool more = k0 + kBK < k_end;
-        if (more) {
-            la.fetch(k0 + kBK, k_end, ra.r, lb);
-            lb.fetch(k0 + kBK, k_end, rb.r, la);
-        }
+        la.prep(k0 + 2 * kBK, k_end, lb);
+        lb.prep(k0 + 2 * kBK, k_end, la);
         const float *As = lds[buf];
         const float *Bs = lds[buf] + kBK * T::LDA;
+        float *An = lds[buf ^ 1];
+        float *Bn = lds[buf ^ 1] + kBK * T::LDA;
         // operands of the next k-pair are read from LDS before the MFMAs of the current one issue
         float a[2][T::WM], b[2][T::WN];
 #pragma unroll
         for (int i = 0; i < T::WM; ++i) a[0][i] = As[lhi * T::LDA + wm0 + i * 32 + l32];
 #pragma unroll
         for (int j = 0; j < T::WN; ++j) b[0][j] = Bs[lhi * T::LDB + wn0 + j * 32 + l32];
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_setprio(UCD_MFMA_PRIO);  // a wave inside its MFMA run keeps the pipe
 #pragma unroll
         for (int kk = 0; kk < kBK; kk += 2) {
-            const int cur = (kk >> 1) & 1, nxt = cur ^ 1;
-            if (kk + 2 < kBK) {
+            const int g = kk >> 1, cur = g & 1, nxt = cur ^ 1;
+            constexpr int NM = T::WM * T::WN;
+            // each piece of memory work issues behind one MFMA, in the shadow of its 16 passes
 #pragma unroll
-                for (int i = 0; i < T::WM; ++i) a[nxt][i] = As[(kk + 2 + lhi) * T::LDA + wm0 + i * 32 + l32];
+            for (int m = 0; m < NM; ++m) {
+                const int mi = m / T::WN, mj = m % T::WN;
+                acc[mi][mj] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[cur][mi], b[cur][mj], acc[mi][mj], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (m == 0 && kk + 2 < kBK) {
 #pragma unroll
-                for (int j = 0; j < T::WN; ++j) b[nxt][j] = Bs[(kk + 2 + lhi) * T::LDB + wn0 + j * 32 + l32];
+                    for (int i = 0; i < T::WM; ++i) a[nxt][i] = As[(kk + 2 + lhi) * T::LDA + wm0 + i * 32 + l32];
+#pragma unroll
+                    for (int j = 0; j < T::WN; ++j) b[nxt][j] = Bs[(kk + 2 + lhi) * T::LDB + wn0 + j * 32 + l32];
+                }
+                if (m == 1 % NM) {
+#pragma unroll
+                    for (int i = 0; i < NA; ++i)
+                        if (i * kGroups / NA == g) {
+                            la.store(An, i, ra.r);
+                            la.load(i, ra.r);
+                        }
+                }
+                if (m == 2 % NM) {
+#pragma unroll
+                    for (int i = 0; i < NB; ++i)
+                        if (i * kGroups / NB == g) {
+                            lb.store(Bn, i, rb.r);
+                            lb.load(i, rb.r);
+                        }
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
-            __builtin_amdgcn_sched_barrier(0);  // keep the LDS reads above ahead of these MFMAs
-            if (kk == 0) __builtin_amdgcn_s_setprio(UCD_MFMA_PRIO);  // a wave inside its MFMA run keeps the pipe
-#pragma unroll
-            for (int i = 0; i < T::WM; ++i)
-#pragma unroll
-                for (int j = 0; j < T::WN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[cur][i], b[cur][j], acc[i][j], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
         }
         __builtin_amdgcn_s_setprio(0);
-        if (more) {
-            la.commit(lds[buf ^ 1], ra.r);
-            lb.commit(lds[buf ^ 1] + kBK * T::LDA, rb.r);
-        }
         __syncthreads();
         buf ^= 1;
     }
