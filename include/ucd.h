@@ -24,6 +24,12 @@
  *     Nothing throws or aborts across this boundary.
  *   - Host arrays (descriptors, tables, micro-configuration lists) are read
  *     during the call only.
+ *   - Limits (checked on the host; UCD_E_INVALID / UCD_E_UNSUPPORTED, or
+ *     UCD_WS_NA from ucd_workspace_size): filter extents R, S <= 31; every
+ *     tensor slice one micro-batch touches (b*C*H*W, b*K*P*Q, K*C*R*S floats)
+ *     and every workspace matrix below 2 GiB - 256 KiB, because the kernels
+ *     address operands with 32-bit byte offsets; tensor pointers 4-byte
+ *     aligned, workspace pointers 16-byte aligned (UCD_E_INVALID otherwise).
  */
 #ifndef UCD_H
 #define UCD_H

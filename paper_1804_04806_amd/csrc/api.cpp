@@ -91,6 +91,9 @@ int run_micro(const ucd_layer_t *L, int op, int algo, int b, const float *a, con
               float beta, float *ws, hipStream_t s)
 {
     const Dims d = dims_of(L);
+    // tensors are read with 4-byte loads; the workspace matrices with 16-byte loads
+    if ((((uintptr_t)a | (uintptr_t)bsrc | (uintptr_t)out) & 3u) != 0) return UCD_E_INVALID;
+    if (algo != UCD_ALGO_IMPLICIT && ((uintptr_t)ws & 15u) != 0) return UCD_E_INVALID;
     hipError_t e = hipErrorInvalidValue;
     switch (algo) {
     case UCD_ALGO_IMPLICIT:

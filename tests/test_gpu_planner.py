@@ -148,6 +148,26 @@ def test_workspace_one_byte_short_is_refused():
     assert float(y.abs().sum()) == 0.0      # nothing was launched
 
 
+def test_misaligned_workspace_is_refused():
+    """The workspace matrices are read with 16-byte loads: a workspace pointer that is not 16-byte
+    aligned is an error before any launch."""
+    import torch
+    s = synth.config_small()[0]
+    desc = ucd.layer(s)
+    _, (xd, wd, dyd) = device_buffers(s)
+    plan = ucd.ucd_plan_fixed(desc, ucd.FWD, [(ucd.ALGO_IM2COL, 8)])
+    ws = torch.empty(plan.ws_bytes // 4 + 4, dtype=torch.float32, device=xd.device)
+    y = torch.zeros(s.y_shape, device=xd.device)
+    with pytest.raises(ucd.UcdError) as e:
+        ucd.ucd_conv_fwd(plan, xd, wd, y, ws[1:], ws_bytes=plan.ws_bytes)
+    assert e.value.status == ucd.E_INVALID
+    torch.cuda.synchronize()
+    assert float(y.abs().sum()) == 0.0
+    ucd.ucd_conv_fwd(plan, xd, wd, y, ws[4:], ws_bytes=plan.ws_bytes)   # 16-byte offset is fine
+    torch.cuda.synchronize()
+    assert float(y.abs().sum()) > 0.0
+
+
 def test_benchmark_db_roundtrip_on_device(tmp_path):
     """Timings measured on the device survive save / clear / load, and planning from the loaded
     cache (no GPU work) reproduces the plan."""
