@@ -9,7 +9,7 @@
  * minimise measured time under a workspace limit (Section 3).
  *
  * Conventions for every entry point
- *   - Tensors are dense fp32 in DEVICE memory: X (N,C,H,W), filter W (K,C,R,S)
+ *   - Tensors are dense, in DEVICE memory: X (N,C,H,W), filter W (K,C,R,S)
  *     with R the filter height and S its width, Y (N,K,P,Q) with
  *     P = floor((H + 2*pad_h - R)/stride_h) + 1 and Q likewise (Section 2 gives
  *     the NCHW / KCVU shapes; stride and zero padding are this library's
@@ -26,10 +26,10 @@
  *     during the call only.
  *   - Limits (checked on the host; UCD_E_INVALID / UCD_E_UNSUPPORTED, or
  *     UCD_WS_NA from ucd_workspace_size): filter extents R, S <= 31; every
- *     tensor slice one micro-batch touches (b*C*H*W, b*K*P*Q, K*C*R*S floats)
- *     and every workspace matrix below 2 GiB - 256 KiB, because the kernels
- *     address operands with 32-bit byte offsets; tensor pointers 4-byte
- *     aligned, workspace pointers 16-byte aligned (UCD_E_INVALID otherwise).
+ *     tensor slice one micro-batch touches (b*C*H*W, b*K*P*Q, K*C*R*S elements)
+ *     and every workspace matrix below 2^29 - 2^16 elements, because the kernels
+ *     address operands with 32-bit byte offsets; tensor pointers aligned to
+ *     their element size, workspace pointers to 16 bytes (UCD_E_INVALID otherwise).
  */
 #ifndef UCD_H
 #define UCD_H
@@ -52,7 +52,12 @@ typedef enum {
     UCD_E_INFEASIBLE = -7    /* no configuration satisfies the limits */
 } ucd_status_t;
 
-/* dtype: 0 = fp32 (the only one built).  Layout NCHW / KCRS, dense, groups = 1, dilation = 1. */
+/* dtype 0: every tensor fp32.
+ * dtype 1: x, w, dy, y, dx hold bfloat16 (16-bit storage; outputs rounded to nearest-even), dw is
+ *          fp32 (it accumulates over micro-batches with beta = 1) and so is every workspace
+ *          matrix; the arithmetic is the fp32 path's (bf16 operands widen exactly), so only the
+ *          memory traffic and the output rounding differ from dtype 0.
+ * Layout NCHW / KCRS, dense, groups = 1, dilation = 1. */
 typedef struct {
     int32_t N, C, H, W, K, R, S, stride_h, stride_w, pad_h, pad_w, dtype;
 } ucd_layer_t;
@@ -147,13 +152,15 @@ void ucd_plan_destroy(ucd_plan_t *plan);
  *   x  : device, N*C*H*W floats      y : device, N*K*P*Q floats      w : device, K*C*R*S floats
  *   ws : device, at least ws_limit bytes (may be NULL when ws_limit == 0)
  * The operation's output buffer is clobbered (FWD: y, BWD_DATA: x, BWD_FILTER: w); the other
- * two are only read.  Each timing is the minimum of `3` runs after one warm-up, in integer ns. */
+ * two are only read.  For BWD_FILTER `w` stands in for dw and must hold K*C*R*S fp32 values
+ * whatever the dtype.  Each timing is the minimum of `3` runs after one warm-up, in integer ns. */
 int ucd_plan(const ucd_layer_t *layer, int op, size_t ws_limit, int policy,
              void *x, void *w, void *y, void *ws, void *stream, ucd_plan_t **out);
 
 /* WD planner on the device (Section 3.3): benchmarks like ucd_plan (limit = total_ws) for each
  * of the n_kernels (layers[k], ops[k]) kernels, using the same scratch tensors for all of them
- * (each must be large enough for the largest layer; capacities in bytes are checked), then
+ * (each must be large enough for the largest layer; capacities in bytes are checked; the w
+ * scratch is sized as K*C*R*S fp32 values for every dtype, since BackwardFilter writes dw there), then
  * builds desirable sets and solves the 0-1 programme.  plans[k] are executable; kernel k must
  * be run with workspace pointer ws_base + ws_offsets[k]. */
 int ucd_plan_wd(const ucd_layer_t *layers, const int *ops, int n_kernels, size_t total_ws,

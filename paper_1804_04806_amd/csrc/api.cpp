@@ -39,6 +39,7 @@ bool layer_ok(const ucd_layer_t *L)
     if (L->stride_h < 1 || L->stride_w < 1 || L->pad_h < 0 || L->pad_w < 0) return false;
     if (L->H + 2 * L->pad_h < L->R || L->W + 2 * L->pad_w < L->S) return false;
     if (L->R > 31 || L->S > 31) return false;  // the gather kernels keep one validity bit per filter row / column
+    if (L->dtype != 0 && L->dtype != 1) return false;
     return true;
 }
 
@@ -49,6 +50,7 @@ Dims dims_of(const ucd_layer_t *L)
     d.sh = L->stride_h; d.sw = L->stride_w; d.ph = L->pad_h; d.pw = L->pad_w;
     d.P = (L->H + 2 * L->pad_h - L->R) / L->stride_h + 1;
     d.Q = (L->W + 2 * L->pad_w - L->S) / L->stride_w + 1;
+    d.dtype = L->dtype;
     return d;
 }
 
@@ -64,7 +66,7 @@ bool fits_32bit(const ucd_layer_t *L, int b)
 
 size_t ws_size(const ucd_layer_t *L, int op, int algo, int b)
 {
-    if (!L || !layer_ok(L) || L->dtype != 0 || op < 0 || op >= UCD_N_OP || b < 1 || b > L->N) return UCD_WS_NA;
+    if (!L || !layer_ok(L) || op < 0 || op >= UCD_N_OP || b < 1 || b > L->N) return UCD_WS_NA;
     if (!fits_32bit(L, b)) return UCD_WS_NA;
     const Dims d = dims_of(L);
     switch (algo) {
@@ -87,24 +89,25 @@ size_t ws_size(const ucd_layer_t *L, int op, int algo, int b)
 int hip_status(hipError_t e) { return e == hipSuccess ? UCD_OK : UCD_E_HIP; }
 
 // One algorithm on one micro-batch.  (a, bsrc, out) = (x, w, y) | (dy, w, dx) | (x, dy, dw).
-int run_micro(const ucd_layer_t *L, int op, int algo, int b, const float *a, const float *bsrc, float *out,
+int run_micro(const ucd_layer_t *L, int op, int algo, int b, const void *a, const void *bsrc, void *out,
               float beta, float *ws, hipStream_t s)
 {
     const Dims d = dims_of(L);
-    // tensors are read with 4-byte loads; the workspace matrices with 16-byte loads
-    if ((((uintptr_t)a | (uintptr_t)bsrc | (uintptr_t)out) & 3u) != 0) return UCD_E_INVALID;
+    // tensors are read element by element (dw is always fp32); the workspace matrices with 16-byte loads
+    const uintptr_t emask = d.esize() - 1, omask = op == UCD_BWD_FILTER ? 3u : emask;
+    if ((((uintptr_t)a | (uintptr_t)bsrc) & emask) != 0 || ((uintptr_t)out & omask) != 0) return UCD_E_INVALID;
     if (algo != UCD_ALGO_IMPLICIT && ((uintptr_t)ws & 15u) != 0) return UCD_E_INVALID;
     hipError_t e = hipErrorInvalidValue;
     switch (algo) {
     case UCD_ALGO_IMPLICIT:
         if (op == UCD_FWD) e = implicit_fwd(d, b, a, bsrc, out, s);
         else if (op == UCD_BWD_DATA) e = implicit_bwd_data(d, b, a, bsrc, out, s);
-        else e = implicit_bwd_filter(d, b, a, bsrc, out, beta, s);
+        else e = implicit_bwd_filter(d, b, a, bsrc, (float *)out, beta, s);
         break;
     case UCD_ALGO_IM2COL:
         if (op == UCD_FWD) e = im2col_fwd(d, b, a, bsrc, out, ws, s);
         else if (op == UCD_BWD_DATA) e = im2col_bwd_data(d, b, a, bsrc, out, ws, s);
-        else e = im2col_bwd_filter(d, b, a, bsrc, out, beta, ws, s);
+        else e = im2col_bwd_filter(d, b, a, bsrc, (float *)out, beta, ws, s);
         break;
     case UCD_ALGO_WINOGRAD:
         if (op == UCD_FWD) e = winograd_fwd(d, b, a, bsrc, out, ws, s);
@@ -114,17 +117,20 @@ int run_micro(const ucd_layer_t *L, int op, int algo, int b, const float *a, con
     return hip_status(e);
 }
 
-int run_plan(const ucd_plan_t *plan, int op, const float *a, const float *bsrc, float *out, float beta,
+int run_plan(const ucd_plan_t *plan, int op, const void *a_, const void *bsrc_, void *out_, float beta,
              void *ws, size_t ws_bytes, void *stream)
 {
     if (!plan) return UCD_E_NULLPTR;
     if (!plan->has_layer || plan->op != op) return UCD_E_INVALID;
+    const char *a = (const char *)a_, *bsrc = (const char *)bsrc_;
+    char *out = (char *)out_;
     if (!a || !bsrc || !out) return UCD_E_NULLPTR;
     if (plan->ws_bytes > 0 && (!ws || ws_bytes < plan->ws_bytes)) return ws ? UCD_E_WS_TOO_SMALL : UCD_E_NULLPTR;
     if (op == UCD_BWD_FILTER && beta != 0.f && beta != 1.f) return UCD_E_INVALID;
     const ucd_layer_t *L = &plan->layer;
     const Dims d = dims_of(L);
-    const size_t x_img = (size_t)d.C * d.H * d.W, y_img = (size_t)d.K * d.P * d.Q;
+    // bytes per sample of the two activation tensors
+    const size_t x_img = d.esize() * d.C * d.H * d.W, y_img = d.esize() * d.K * d.P * d.Q;
     size_t o = 0;
     bool first = true;
     for (const Micro &m : plan->micro) {
@@ -181,17 +187,17 @@ struct Events {
 };
 
 // Device time of one (algo, b): one warm-up, then the minimum of kTimedRuns, in integer ns.
-int time_micro(const ucd_layer_t *L, int op, int algo, int b, float *x, float *w, float *y, float *ws,
+int time_micro(const ucd_layer_t *L, int op, int algo, int b, void *x, void *w, void *y, float *ws,
                hipStream_t s, Events &ev, uint64_t &ns)
 {
-    const float *a = op == UCD_BWD_DATA ? y : x;
-    const float *bs = op == UCD_BWD_FILTER ? y : w;
-    float *out = op == UCD_FWD ? y : (op == UCD_BWD_DATA ? x : w);
+    const void *a = op == UCD_BWD_DATA ? y : x;
+    const void *bs = op == UCD_BWD_FILTER ? y : w;
+    void *out = op == UCD_FWD ? y : (op == UCD_BWD_DATA ? x : w);
     // BackwardFilter is timed as the accumulating call it is for every micro-batch but the first
     const float beta = op == UCD_BWD_FILTER ? 1.f : 0.f;
     if (op == UCD_BWD_FILTER) {
         const Dims d = dims_of(L);
-        if (fill_zero(w, (size_t)d.K * d.crs(), s) != hipSuccess) return UCD_E_HIP;
+        if (fill_zero((float *)w, (size_t)d.K * d.crs(), s) != hipSuccess) return UCD_E_HIP;
     }
     float best = INFINITY;
     for (int it = 0; it <= kTimedRuns; ++it) {
@@ -211,7 +217,7 @@ int time_micro(const ucd_layer_t *L, int op, int algo, int b, float *x, float *w
 
 // Step 1 of the WR algorithm for one kernel: fill the table for every policy size and every
 // algorithm that applies and fits `limit`, timing what the cache does not hold yet.
-int bench_kernel(const ucd_layer_t *L, int op, size_t limit, int policy, float *x, float *w, float *y, float *ws,
+int bench_kernel(const ucd_layer_t *L, int op, size_t limit, int policy, void *x, void *w, void *y, float *ws,
                  hipStream_t s, std::vector<uint64_t> &t, std::vector<size_t> &m)
 {
     const int B = L->N;
@@ -376,7 +382,6 @@ int ucd_plan_fixed(const ucd_layer_t *layer, int op, const ucd_micro_t *micro, i
 {
     if (!layer || !micro || !out) return UCD_E_NULLPTR;
     if (!layer_ok(layer) || op < 0 || op >= UCD_N_OP || n < 1) return UCD_E_INVALID;
-    if (layer->dtype != 0) return UCD_E_UNSUPPORTED;
     Config cfg;
     long sum = 0;
     for (int i = 0; i < n; ++i) {
@@ -416,11 +421,11 @@ int ucd_plan(const ucd_layer_t *layer, int op, size_t ws_limit, int policy, void
 {
     if (!layer || !x || !w || !y || !out) return UCD_E_NULLPTR;
     if (!layer_ok(layer) || op < 0 || op >= UCD_N_OP || !policy_ok(policy)) return UCD_E_INVALID;
-    if (layer->dtype != 0 || !fits_32bit(layer, layer->N)) return UCD_E_UNSUPPORTED;
+    if (!fits_32bit(layer, layer->N)) return UCD_E_UNSUPPORTED;
     if (ws_limit > 0 && !ws) return UCD_E_NULLPTR;
     std::vector<uint64_t> t;
     std::vector<size_t> m;
-    int rc = bench_kernel(layer, op, ws_limit, policy, (float *)x, (float *)w, (float *)y, (float *)ws,
+    int rc = bench_kernel(layer, op, ws_limit, policy, x, w, y, (float *)ws,
                           (hipStream_t)stream, t, m);
     if (rc != UCD_OK) return rc;
     Table tab{layer->N, UCD_N_ALGO, t.data(), m.data()};
@@ -442,17 +447,18 @@ int ucd_plan_wd(const ucd_layer_t *layers, const int *ops, int n_kernels, size_t
     for (int k = 0; k < n_kernels; ++k) {
         const ucd_layer_t *L = &layers[k];
         if (!layer_ok(L) || ops[k] < 0 || ops[k] >= UCD_N_OP) return UCD_E_INVALID;
-        if (L->dtype != 0 || !fits_32bit(L, L->N)) return UCD_E_UNSUPPORTED;
+        if (!fits_32bit(L, L->N)) return UCD_E_UNSUPPORTED;
         const Dims d = dims_of(L);
-        if ((size_t)L->N * d.C * d.H * d.W * 4 > x_cap || (size_t)d.K * d.crs() * 4 > w_cap ||
-            (size_t)L->N * d.K * d.P * d.Q * 4 > y_cap)
+        // the w scratch doubles as the fp32 dw of BackwardFilter kernels
+        if ((size_t)L->N * d.C * d.H * d.W * d.esize() > x_cap || (size_t)d.K * d.crs() * 4 > w_cap ||
+            (size_t)L->N * d.K * d.P * d.Q * d.esize() > y_cap)
             return UCD_E_INVALID;
     }
     std::vector<std::vector<Config>> fronts(n_kernels);
     for (int k = 0; k < n_kernels; ++k) {
         std::vector<uint64_t> t;
         std::vector<size_t> m;
-        int rc = bench_kernel(&layers[k], ops[k], total_ws, policy, (float *)x, (float *)w, (float *)y, (float *)ws,
+        int rc = bench_kernel(&layers[k], ops[k], total_ws, policy, x, w, y, (float *)ws,
                               (hipStream_t)stream, t, m);
         if (rc != UCD_OK) return rc;
         Table tab{layers[k].N, UCD_N_ALGO, t.data(), m.data()};
@@ -590,7 +596,7 @@ int ucd_plan_cached(const ucd_layer_t *layer, int op, size_t ws_limit, int polic
 {
     if (!layer || !out) return UCD_E_NULLPTR;
     if (!layer_ok(layer) || op < 0 || op >= UCD_N_OP || !policy_ok(policy)) return UCD_E_INVALID;
-    if (layer->dtype != 0 || !fits_32bit(layer, layer->N)) return UCD_E_UNSUPPORTED;
+    if (!fits_32bit(layer, layer->N)) return UCD_E_UNSUPPORTED;
     const int B = layer->N;
     std::vector<uint64_t> t((size_t)UCD_N_ALGO * (B + 1), kTimeInf);
     std::vector<size_t> m((size_t)UCD_N_ALGO * (B + 1), kWsNa);
@@ -614,19 +620,19 @@ int ucd_plan_cached(const ucd_layer_t *layer, int op, size_t ws_limit, int polic
 int ucd_conv_fwd(const ucd_plan_t *plan, const void *x, const void *w, void *y, void *ws, size_t ws_bytes,
                  void *stream)
 {
-    return run_plan(plan, UCD_FWD, (const float *)x, (const float *)w, (float *)y, 0.f, ws, ws_bytes, stream);
+    return run_plan(plan, UCD_FWD, x, w, y, 0.f, ws, ws_bytes, stream);
 }
 
 int ucd_conv_bwd_data(const ucd_plan_t *plan, const void *dy, const void *w, void *dx, void *ws, size_t ws_bytes,
                       void *stream)
 {
-    return run_plan(plan, UCD_BWD_DATA, (const float *)dy, (const float *)w, (float *)dx, 0.f, ws, ws_bytes, stream);
+    return run_plan(plan, UCD_BWD_DATA, dy, w, dx, 0.f, ws, ws_bytes, stream);
 }
 
 int ucd_conv_bwd_filter(const ucd_plan_t *plan, const void *x, const void *dy, void *dw, float beta, void *ws,
                         size_t ws_bytes, void *stream)
 {
-    return run_plan(plan, UCD_BWD_FILTER, (const float *)x, (const float *)dy, (float *)dw, beta, ws, ws_bytes,
+    return run_plan(plan, UCD_BWD_FILTER, x, dy, dw, beta, ws, ws_bytes,
                     stream);
 }
 
@@ -634,7 +640,6 @@ int ucd_describe_micro(const ucd_layer_t *layer, int op, int algo, int b, char *
 {
     if (!layer || !buf) return UCD_E_NULLPTR;
     if (!layer_ok(layer) || op < 0 || op >= UCD_N_OP || b < 1 || cap < 1) return UCD_E_INVALID;
-    if (layer->dtype != 0) return UCD_E_UNSUPPORTED;
     ucd_layer_t L = *layer;
     L.N = std::max(L.N, b);
     if (ws_size(&L, op, algo, b) == UCD_WS_NA) return UCD_E_UNSUPPORTED;
@@ -668,7 +673,6 @@ int ucd_run_micro(const ucd_layer_t *layer, int op, int algo, int b, const void 
 {
     if (!layer || !a || !bsrc || !out) return UCD_E_NULLPTR;
     if (!layer_ok(layer) || op < 0 || op >= UCD_N_OP || b < 1) return UCD_E_INVALID;
-    if (layer->dtype != 0) return UCD_E_UNSUPPORTED;
     ucd_layer_t L = *layer;
     L.N = std::max(L.N, b);
     const size_t need = ws_size(&L, op, algo, b);
@@ -676,7 +680,7 @@ int ucd_run_micro(const ucd_layer_t *layer, int op, int algo, int b, const void 
     if (need > 0 && !ws) return UCD_E_NULLPTR;
     if (need > ws_bytes) return UCD_E_WS_TOO_SMALL;
     if (op == UCD_BWD_FILTER && beta != 0.f && beta != 1.f) return UCD_E_INVALID;
-    return run_micro(&L, op, algo, b, (const float *)a, (const float *)bsrc, (float *)out, beta, (float *)ws,
+    return run_micro(&L, op, algo, b, a, bsrc, out, beta, (float *)ws,
                      (hipStream_t)stream);
 }
 

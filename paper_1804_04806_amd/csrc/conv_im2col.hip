@@ -5,6 +5,8 @@
 //   Forward        Y  = W[K x CRS] * col                     (epilogue scatters to NCHW)
 //   BackwardData   col = W^T[CRS x K] * dY[K x bPQ], then dx = col2im(col) in gather form
 //   BackwardFilter dW += dY[K x bPQ] * col^T                  (split over bPQ, fp32 atomics)
+#include <type_traits>
+
 #include "gemm_launch.hpp"
 #include "kernels.h"
 
@@ -21,7 +23,8 @@ struct ColParams {
 };
 
 // one thread per column-matrix element, lanes along (n,p,q): coalesced writes, cached reads
-__global__ __launch_bounds__(256) void im2col_kernel(const float *__restrict__ x, float *__restrict__ col,
+template <class E>
+__global__ __launch_bounds__(256) void im2col_kernel(const void *__restrict__ x, float *__restrict__ col,
                                                      ColParams p, int rows)
 {
     const int j = blockIdx.x * 256 + threadIdx.x;
@@ -39,14 +42,15 @@ __global__ __launch_bounds__(256) void im2col_kernel(const float *__restrict__ x
             p.s.divmod(tap, r, s);
             const int ih = (int)op * p.sh - p.ph + (int)r, iw = (int)oq * p.sw - p.pw + (int)s;
             if ((unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W)
-                v = x[(((size_t)n * p.C + c) * p.H + ih) * p.W + iw];
+                v = Elem<E>::get(x, (((size_t)n * p.C + c) * p.H + ih) * p.W + iw);
         }
         col[(size_t)row * p.ld + j] = v;
     }
 }
 
 // dx[n,c,h,w] = sum over the taps (r,s) that reach it of col[(c,r,s)][(n,p,q)]
-__global__ __launch_bounds__(256) void col2im_kernel(const float *__restrict__ col, float *__restrict__ dx,
+template <class E>
+__global__ __launch_bounds__(256) void col2im_kernel(const float *__restrict__ col, void *__restrict__ dx,
                                                      ColParams p, int total)
 {
     const int i = blockIdx.x * 256 + threadIdx.x;
@@ -68,7 +72,7 @@ __global__ __launch_bounds__(256) void col2im_kernel(const float *__restrict__ c
             acc += col[(size_t)((c * p.R + r) * p.S + s) * p.ld + (n * p.P + op) * p.Q + oq];
         }
     }
-    dx[i] = acc;
+    Elem<E>::store(dx, i, acc);
 }
 
 static ColParams col_params(const Dims &d, int b)
@@ -83,7 +87,8 @@ static ColParams col_params(const Dims &d, int b)
     return p;
 }
 
-static hipError_t run_im2col(const Dims &d, int b, const float *x, float *col, hipStream_t s)
+template <class E>
+static hipError_t run_im2col(const Dims &d, int b, const void *x, float *col, hipStream_t s)
 {
     const ColParams p = col_params(d, b);
     dim3 grid((unsigned)((p.ld + 255) / 256), (unsigned)(d.crs() < 32768 ? d.crs() : 32768));
@@ -91,13 +96,15 @@ static hipError_t run_im2col(const Dims &d, int b, const float *x, float *col, h
         log->add("im2col_kernel");
         return hipSuccess;
     }
-    im2col_kernel<<<grid, 256, 0, s>>>(x, col, p, d.crs());
+    im2col_kernel<E><<<grid, 256, 0, s>>>(x, col, p, d.crs());
     return hipGetLastError();
 }
 
-hipError_t im2col_fwd(const Dims &d, int b, const float *x, const float *w, float *y, float *ws, hipStream_t s)
+template <class E>
+static hipError_t im2col_fwd_t(const Dims &d, int b, const void *x, const void *w, void *y, float *ws, hipStream_t s)
 {
-    hipError_t e = run_im2col(d, b, x, ws, s);
+    typedef Loaders<E> L;
+    hipError_t e = run_im2col<E>(d, b, x, ws, s);
     if (e != hipSuccess) return e;
     GemmShape g{d.K, b * d.P * d.Q, d.crs()};
     KLaneParams pa{};
@@ -106,12 +113,19 @@ hipError_t im2col_fwd(const Dims &d, int b, const float *x, const float *w, floa
     EpiNCHWParams pe{};
     pe.out = y; pe.grid_hw = FastDiv(d.P * d.Q); pe.grid_w = FastDiv(d.Q);
     pe.M = d.K; pe.HWo = d.P * d.Q; pe.Wo = d.Q; pe.h0 = 0; pe.hs = 1; pe.w0 = 0; pe.ws = 1;
-    return launch_gemm<KLane0, DenseNLane, EpiNCHW, true>(pa, pb, pe, g, s);
+    return launch_gemm<L::template KLane0, DenseNLane, EpiNCHWT<E>, true>(pa, pb, pe, g, s);
 }
 
-hipError_t im2col_bwd_data(const Dims &d, int b, const float *dy, const float *w, float *dx, float *ws,
-                           hipStream_t s)
+hipError_t im2col_fwd(const Dims &d, int b, const void *x, const void *w, void *y, float *ws, hipStream_t s)
 {
+    return d.dtype == 1 ? im2col_fwd_t<bf16>(d, b, x, w, y, ws, s) : im2col_fwd_t<float>(d, b, x, w, y, ws, s);
+}
+
+template <class E>
+static hipError_t im2col_bwd_data_t(const Dims &d, int b, const void *dy, const void *w, void *dx, float *ws,
+                                    hipStream_t s)
+{
+    typedef Loaders<E> L;
     GemmShape g{d.crs(), b * d.P * d.Q, d.K};
     DenseParams pa{w, wbytes(d), d.crs()};
     GatherParams pb{};
@@ -122,10 +136,14 @@ hipError_t im2col_bwd_data(const Dims &d, int b, const float *dy, const float *w
     pb.n_tap_h = 1; pb.n_tap_w = 1; pb.shift_thread = 0; pb.shift_row = 0;
     EpiDenseParams pe{ws, col_ld(d, b)};
     hipError_t e;
-    if (d.crs() % 4 == 0)
-        e = launch_gemm<DenseNLane, GatherNLane, EpiDense>(pa, pb, pe, g, s);
-    else
-        e = launch_gemm<DenseNLaneS, GatherNLane, EpiDense>(pa, pb, pe, g, s);
+    bool done = false;
+    if constexpr (std::is_same<E, float>::value) {
+        if (d.crs() % 4 == 0) {  // 16-byte loads of the fp32 filter matrix
+            e = launch_gemm<DenseNLane, GatherNLane, EpiDense>(pa, pb, pe, g, s);
+            done = true;
+        }
+    }
+    if (!done) e = launch_gemm<L::template DenseNLaneS, L::template GatherNLane, EpiDense>(pa, pb, pe, g, s);
     if (e != hipSuccess) return e;
     const ColParams p = col_params(d, b);
     const int total = b * d.C * d.H * d.W;
@@ -133,16 +151,25 @@ hipError_t im2col_bwd_data(const Dims &d, int b, const float *dy, const float *w
         log->add("col2im_kernel");
         return hipSuccess;
     }
-    col2im_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(ws, dx, p, total);
+    col2im_kernel<E><<<(unsigned)((total + 255) / 256), 256, 0, s>>>(ws, dx, p, total);
     return hipGetLastError();
+}
+
+hipError_t im2col_bwd_data(const Dims &d, int b, const void *dy, const void *w, void *dx, float *ws,
+                           hipStream_t s)
+{
+    return d.dtype == 1 ? im2col_bwd_data_t<bf16>(d, b, dy, w, dx, ws, s)
+                        : im2col_bwd_data_t<float>(d, b, dy, w, dx, ws, s);
 }
 
 int filter_splits(int M, int N, int Kd);
 
-hipError_t im2col_bwd_filter(const Dims &d, int b, const float *x, const float *dy, float *dw, float beta,
-                             float *ws, hipStream_t s)
+template <class E>
+static hipError_t im2col_bwd_filter_t(const Dims &d, int b, const void *x, const void *dy, float *dw, float beta,
+                                      float *ws, hipStream_t s)
 {
-    hipError_t e = run_im2col(d, b, x, ws, s);
+    typedef Loaders<E> L;
+    hipError_t e = run_im2col<E>(d, b, x, ws, s);
     if (e != hipSuccess) return e;
     if (beta == 0.f && (e = fill_zero(dw, (size_t)d.K * d.crs(), s)) != hipSuccess) return e;
     GemmShape g{d.K, d.crs(), b * d.P * d.Q};
@@ -156,7 +183,14 @@ hipError_t im2col_bwd_filter(const Dims &d, int b, const float *x, const float *
     KLaneParams pb{};
     pb.t = ws; pb.bytes = (uint32_t)im2col_ws_bytes(d, b); pb.row_stride = 1; pb.col_stride = col_ld(d, b);
     EpiDenseParams pe{dw, d.crs()};
-    return launch_gemm<DyKLane, KLane0, EpiAtomic, true>(pa, pb, pe, g, s);
+    return launch_gemm<L::template DyKLane, KLane0, EpiAtomic, true>(pa, pb, pe, g, s);
+}
+
+hipError_t im2col_bwd_filter(const Dims &d, int b, const void *x, const void *dy, float *dw, float beta,
+                             float *ws, hipStream_t s)
+{
+    return d.dtype == 1 ? im2col_bwd_filter_t<bf16>(d, b, x, dy, dw, beta, ws, s)
+                        : im2col_bwd_filter_t<float>(d, b, x, dy, dw, beta, ws, s);
 }
 
 }  // namespace ucd

@@ -3,6 +3,8 @@
 //   Forward        Y[K x bPQ]   = W[K x CRS]      * im2col(X)[CRS x bPQ]
 //   BackwardData   dX[C x bHW]  = W^T[C x KRS]    * gather(dY)[KRS x bHW]   (one GEMM per stride phase)
 //   BackwardFilter dW[K x CRS] += dY[K x bPQ]     * im2col(X)^T[bPQ x CRS]  (split over bPQ, fp32 atomics)
+#include <type_traits>
+
 #include "gemm_launch.hpp"
 #include "kernels.h"
 
@@ -38,8 +40,9 @@ hipError_t fill_zero(float *p, size_t n, hipStream_t s)
 // reduction.  When the output has too few tiles to give every CU several workgroups (deep
 // layers: many channels, few pixels), the reduction is split as well and the partial results meet
 // through atomics in a zero-filled output.  Chunks keep at least 1024 reduction rows.
-static int output_splits(int M, int N, int Kd)
+static int output_splits(int M, int N, int Kd, bool fp32_out)
 {
+    if (!fp32_out) return 1;  // bf16 outputs cannot be accumulated with atomics
     const long tiles = pick_tile(M, N, true, 1 << 20).blocks(M, N, 1);  // tiles at the default shape
     if (tiles >= 768) return 1;  // three workgroups per CU already
     long want = (1536 + tiles - 1) / tiles;
@@ -48,10 +51,13 @@ static int output_splits(int M, int N, int Kd)
     return want < 2 ? 1 : (int)want;
 }
 
-hipError_t implicit_fwd(const Dims &d, int b, const float *x, const float *w, float *y, hipStream_t s)
+template <class E>
+static hipError_t implicit_fwd_t(const Dims &d, int b, const void *x, const void *w, void *y, hipStream_t s)
 {
+    typedef Loaders<E> L;
+    constexpr bool F32 = std::is_same<E, float>::value;
     GemmShape g{d.K, b * d.P * d.Q, d.crs()};
-    g.splits = output_splits(g.M, g.N, g.Kd);
+    g.splits = output_splits(g.M, g.N, g.Kd, F32);
     KLaneParams pa{};
     pa.t = w; pa.bytes = wbytes(d); pa.row_stride = 1; pa.col_stride = d.crs();
     GatherParams pb{};
@@ -64,21 +70,32 @@ hipError_t implicit_fwd(const Dims &d, int b, const float *x, const float *w, fl
     EpiNCHWParams pe{};
     pe.out = y; pe.grid_hw = pb.grid_hw; pe.grid_w = pb.grid_w;
     pe.M = d.K; pe.HWo = d.P * d.Q; pe.Wo = d.Q; pe.h0 = 0; pe.hs = 1; pe.w0 = 0; pe.ws = 1;
-    if (g.splits > 1) {
-        hipError_t e = fill_zero(y, (size_t)b * d.K * d.P * d.Q, s);
-        if (e != hipSuccess) return e;
-        if (d.R * d.S <= 31) return launch_gemm<KLane0, GatherNLane, EpiNCHWAtomic, true>(pa, pb, pe, g, s);
-        return launch_gemm<KLane0, GatherNLaneBig, EpiNCHWAtomic, true>(pa, pb, pe, g, s);
+    if constexpr (F32) {
+        if (g.splits > 1) {
+            hipError_t e = fill_zero((float *)y, (size_t)b * d.K * d.P * d.Q, s);
+            if (e != hipSuccess) return e;
+            if (d.R * d.S <= 31) return launch_gemm<KLane0, GatherNLane, EpiNCHWAtomic, true>(pa, pb, pe, g, s);
+            return launch_gemm<KLane0, GatherNLaneBig, EpiNCHWAtomic, true>(pa, pb, pe, g, s);
+        }
     }
-    if (d.R * d.S <= 31) return launch_gemm<KLane0, GatherNLane, EpiNCHW, true>(pa, pb, pe, g, s);
-    return launch_gemm<KLane0, GatherNLaneBig, EpiNCHW, true>(pa, pb, pe, g, s);
+    if (d.R * d.S <= 31)
+        return launch_gemm<L::template KLane0, L::template GatherNLane, EpiNCHWT<E>, true>(pa, pb, pe, g, s);
+    return launch_gemm<L::template KLane0, L::template GatherNLaneBig, EpiNCHWT<E>, true>(pa, pb, pe, g, s);
+}
+
+hipError_t implicit_fwd(const Dims &d, int b, const void *x, const void *w, void *y, hipStream_t s)
+{
+    return d.dtype == 1 ? implicit_fwd_t<bf16>(d, b, x, w, y, s) : implicit_fwd_t<float>(d, b, x, w, y, s);
 }
 
 // Stride phases: input pixels h with (h + ph) % sh == a are reached only by filter rows
 // r = a, a + sh, ...; within a phase the gather is a dense stride-1 correlation with the
 // sub-sampled, index-reversed filter.  Pixels of a phase with no tap get zeros (Kd = 0).
-hipError_t implicit_bwd_data(const Dims &d, int b, const float *dy, const float *w, float *dx, hipStream_t s)
+template <class E>
+static hipError_t implicit_bwd_data_t(const Dims &d, int b, const void *dy, const void *w, void *dx, hipStream_t s)
 {
+    typedef Loaders<E> L;
+    constexpr bool F32 = std::is_same<E, float>::value;
     // phases whose GEMM has too few tiles split their reduction (atomics); dx is zero-filled once
     // if any phase does
     auto phase_shape = [&](int a, int c, int &h0, int &w0, int &Hh, int &Ww, int &Ra, int &Sc) {
@@ -94,10 +111,10 @@ hipError_t implicit_bwd_data(const Dims &d, int b, const float *dy, const float 
         for (int c = 0; c < d.sw; ++c) {
             int h0, w0, Hh, Ww, Ra, Sc;
             phase_shape(a, c, h0, w0, Hh, Ww, Ra, Sc);
-            if (Hh && Ww && Ra && Sc && output_splits(d.C, b * Hh * Ww, d.K * Ra * Sc) > 1) any_split = true;
+            if (Hh && Ww && Ra && Sc && output_splits(d.C, b * Hh * Ww, d.K * Ra * Sc, F32) > 1) any_split = true;
         }
     if (any_split) {
-        hipError_t e = fill_zero(dx, (size_t)b * d.C * d.H * d.W, s);
+        hipError_t e = fill_zero((float *)dx, (size_t)b * d.C * d.H * d.W, s);
         if (e != hipSuccess) return e;
     }
     for (int a = 0; a < d.sh; ++a)
@@ -107,7 +124,7 @@ hipError_t implicit_bwd_data(const Dims &d, int b, const float *dy, const float 
             if (Hh == 0 || Ww == 0) continue;
             GemmShape g{d.C, b * Hh * Ww, d.K * Ra * Sc};
             if (any_split && g.Kd == 0) continue;  // dx is already zero there
-            g.splits = output_splits(g.M, g.N, g.Kd);
+            g.splits = output_splits(g.M, g.N, g.Kd, F32);
             const bool split = g.splits > 1;
             KLaneParams pa{};
             pa.t = w; pa.bytes = wbytes(d); pa.col_stride = d.R * d.S;
@@ -126,16 +143,28 @@ hipError_t implicit_bwd_data(const Dims &d, int b, const float *dy, const float 
             EpiNCHWParams pe{};
             pe.out = dx; pe.grid_hw = pb.grid_hw; pe.grid_w = pb.grid_w;
             pe.M = d.C; pe.HWo = d.H * d.W; pe.Wo = d.W; pe.h0 = h0; pe.hs = d.sh; pe.w0 = w0; pe.ws = d.sw;
-            hipError_t e;
-            if (split)
-                e = Ra * Sc <= 31 ? launch_gemm<FilterKLane, GatherNLane, EpiNCHWAtomic, true>(pa, pb, pe, g, s)
-                                  : launch_gemm<FilterKLane, GatherNLaneBig, EpiNCHWAtomic, true>(pa, pb, pe, g, s);
-            else
-                e = Ra * Sc <= 31 ? launch_gemm<FilterKLane, GatherNLane, EpiNCHW, true>(pa, pb, pe, g, s)
-                                  : launch_gemm<FilterKLane, GatherNLaneBig, EpiNCHW, true>(pa, pb, pe, g, s);
+            hipError_t e = hipSuccess;
+            bool done = false;
+            if constexpr (F32) {
+                if (split) {
+                    e = Ra * Sc <= 31
+                            ? launch_gemm<FilterKLane, GatherNLane, EpiNCHWAtomic, true>(pa, pb, pe, g, s)
+                            : launch_gemm<FilterKLane, GatherNLaneBig, EpiNCHWAtomic, true>(pa, pb, pe, g, s);
+                    done = true;
+                }
+            }
+            if (!done)
+                e = Ra * Sc <= 31
+                        ? launch_gemm<L::template FilterKLane, L::template GatherNLane, EpiNCHWT<E>, true>(pa, pb, pe, g, s)
+                        : launch_gemm<L::template FilterKLane, L::template GatherNLaneBig, EpiNCHWT<E>, true>(pa, pb, pe, g, s);
             if (e != hipSuccess) return e;
         }
     return hipSuccess;
+}
+
+hipError_t implicit_bwd_data(const Dims &d, int b, const void *dy, const void *w, void *dx, hipStream_t s)
+{
+    return d.dtype == 1 ? implicit_bwd_data_t<bf16>(d, b, dy, w, dx, s) : implicit_bwd_data_t<float>(d, b, dy, w, dx, s);
 }
 
 // Number of reduction splits so that tiles * splits covers the chip a few times over, with
@@ -151,9 +180,11 @@ int filter_splits(int M, int N, int Kd)
     return (int)want;
 }
 
-hipError_t implicit_bwd_filter(const Dims &d, int b, const float *x, const float *dy, float *dw, float beta,
-                               hipStream_t s)
+template <class E>
+static hipError_t implicit_bwd_filter_t(const Dims &d, int b, const void *x, const void *dy, float *dw, float beta,
+                                        hipStream_t s)
 {
+    typedef Loaders<E> L;
     hipError_t e;
     if (beta == 0.f && (e = fill_zero(dw, (size_t)d.K * d.crs(), s)) != hipSuccess) return e;
     GemmShape g{d.K, d.crs(), b * d.P * d.Q};
@@ -172,7 +203,14 @@ hipError_t implicit_bwd_filter(const Dims &d, int b, const float *x, const float
     pb.mul_h = d.sh; pb.add_h = -d.ph; pb.mul_w = d.sw; pb.add_w = -d.pw;
     pb.shift = d.ph * d.W + d.pw;
     EpiDenseParams pe{dw, d.crs()};
-    return launch_gemm<DyKLane, XKLane, EpiAtomic, true>(pa, pb, pe, g, s);
+    return launch_gemm<L::template DyKLane, L::template XKLane, EpiAtomic, true>(pa, pb, pe, g, s);
+}
+
+hipError_t implicit_bwd_filter(const Dims &d, int b, const void *x, const void *dy, float *dw, float beta,
+                               hipStream_t s)
+{
+    return d.dtype == 1 ? implicit_bwd_filter_t<bf16>(d, b, x, dy, dw, beta, s)
+                        : implicit_bwd_filter_t<float>(d, b, x, dy, dw, beta, s);
 }
 
 }  // namespace ucd

@@ -49,7 +49,8 @@ size_t winograd_ws_bytes(const Dims &d, int op, int b)
 }
 
 // U[xi][ci][co] = (G g G^T)[xi], one thread per (ci, co) filter; pads co up to Mo4 with zeros.
-__global__ __launch_bounds__(256) void wino_filter_kernel(const float *__restrict__ w, float *__restrict__ U, int Ci,
+template <class E>
+__global__ __launch_bounds__(256) void wino_filter_kernel(const void *__restrict__ w, float *__restrict__ U, int Ci,
                                                           int Co, int Mo4, int transposed)
 {
     const int i = blockIdx.x * 256 + threadIdx.x;
@@ -62,8 +63,8 @@ __global__ __launch_bounds__(256) void wino_filter_kernel(const float *__restric
         for (int s = 0; s < 3; ++s) {
             float v = 0.f;
             if (co < Co)
-                v = transposed ? w[((size_t)(ci * Co + co) * 3 + (2 - r)) * 3 + (2 - s)]
-                               : w[((size_t)(co * Ci + ci) * 3 + r) * 3 + s];
+                v = transposed ? Elem<E>::get(w, ((size_t)(ci * Co + co) * 3 + (2 - r)) * 3 + (2 - s))
+                               : Elem<E>::get(w, ((size_t)(co * Ci + ci) * 3 + r) * 3 + s);
             g[r][s] = v;
         }
     float t[4][3];  // G g
@@ -87,7 +88,8 @@ __global__ __launch_bounds__(256) void wino_filter_kernel(const float *__restric
 }
 
 // V[xi][ci][j] for tile j = n*T + th*TW + tw: lanes along j (coalesced plane writes).
-__global__ __launch_bounds__(256) void wino_input_kernel(const float *__restrict__ x, float *__restrict__ V,
+template <class E>
+__global__ __launch_bounds__(256) void wino_input_kernel(const void *__restrict__ x, float *__restrict__ V,
                                                          WinoGeom g, FastDiv divT, FastDiv divTW, int n_tiles)
 {
     const int j = blockIdx.x * 256 + threadIdx.x;
@@ -104,13 +106,13 @@ __global__ __launch_bounds__(256) void wino_input_kernel(const float *__restrict
             divT.divmod((uint32_t)j, n, t);
             divTW.divmod(t, th, tw);
             const int h0 = 2 * (int)th - g.pad_h, w0 = 2 * (int)tw - g.pad_w;
-            const float *src = x + ((size_t)n * g.Ci + ci) * g.Hi * g.Wi;
+            const size_t src = ((size_t)n * g.Ci + ci) * g.Hi * g.Wi;
 #pragma unroll
             for (int r = 0; r < 4; ++r)
 #pragma unroll
                 for (int s = 0; s < 4; ++s) {
                     const int h = h0 + r, ww = w0 + s;
-                    if ((unsigned)h < (unsigned)g.Hi && (unsigned)ww < (unsigned)g.Wi) d[r][s] = src[h * g.Wi + ww];
+                    if ((unsigned)h < (unsigned)g.Hi && (unsigned)ww < (unsigned)g.Wi) d[r][s] = Elem<E>::get(x, src + h * g.Wi + ww);
                 }
         }
         float t[4][4];  // B^T d
@@ -133,7 +135,8 @@ __global__ __launch_bounds__(256) void wino_input_kernel(const float *__restrict
 }
 
 // out[n, co, 2th + {0,1}, 2tw + {0,1}] = A^T z A, lanes along the tile index.
-__global__ __launch_bounds__(256) void wino_output_kernel(const float *__restrict__ Z, float *__restrict__ out,
+template <class E>
+__global__ __launch_bounds__(256) void wino_output_kernel(const float *__restrict__ Z, void *__restrict__ out,
                                                           WinoGeom g, FastDiv divT, FastDiv divTW, int n_tiles)
 {
     const int j = blockIdx.x * 256 + threadIdx.x;
@@ -156,19 +159,20 @@ __global__ __launch_bounds__(256) void wino_output_kernel(const float *__restric
             t[0][s] = z[0][s] + z[1][s] + z[2][s];
             t[1][s] = z[1][s] - z[2][s] - z[3][s];
         }
-        float *dst = out + ((size_t)n * g.Co + co) * g.Ho * g.Wo;
+        const size_t dst = ((size_t)n * g.Co + co) * g.Ho * g.Wo;
 #pragma unroll
         for (int r = 0; r < 2; ++r) {
             const int h = h0 + r;
             if (h >= g.Ho) continue;
             const float y0 = t[r][0] + t[r][1] + t[r][2], y1 = t[r][1] - t[r][2] - t[r][3];
-            dst[h * g.Wo + w0] = y0;
-            if (w0 + 1 < g.Wo) dst[h * g.Wo + w0 + 1] = y1;
+            Elem<E>::store(out, dst + h * g.Wo + w0, y0);
+            if (w0 + 1 < g.Wo) Elem<E>::store(out, dst + h * g.Wo + w0 + 1, y1);
         }
     }
 }
 
-static hipError_t winograd_run(const Dims &d, int op, int b, const float *in, const float *w, float *out,
+template <class E>
+static hipError_t winograd_run(const Dims &d, int op, int b, const void *in, const void *w, void *out,
                                float *ws, hipStream_t s)
 {
     const WinoGeom g = geom(d, op, b);
@@ -181,15 +185,15 @@ static hipError_t winograd_run(const Dims &d, int op, int b, const float *in, co
     LaunchLog *log = launch_log();
     if (log) log->add("wino_filter_kernel");
     else
-        wino_filter_kernel<<<(unsigned)((g.Ci * g.Mo4 + 255) / 256), 256, 0, s>>>(w, U, g.Ci, g.Co, g.Mo4,
-                                                                               g.transposed ? 1 : 0);
+        wino_filter_kernel<E><<<(unsigned)((g.Ci * g.Mo4 + 255) / 256), 256, 0, s>>>(w, U, g.Ci, g.Co, g.Mo4,
+                                                                                  g.transposed ? 1 : 0);
     hipError_t e = log ? hipSuccess : hipGetLastError();
     if (e != hipSuccess) return e;
 
     dim3 gi((unsigned)((g.ld + 255) / 256), (unsigned)(g.Ci < 4096 ? g.Ci : 4096));
     if (log) log->add("wino_input_kernel");
     else
-        wino_input_kernel<<<gi, 256, 0, s>>>(in, V, g, divT, divTW, n_tiles);
+        wino_input_kernel<E><<<gi, 256, 0, s>>>(in, V, g, divT, divTW, n_tiles);
     if (!log && (e = hipGetLastError()) != hipSuccess) return e;
 
     GemmShape gs{g.Co, n_tiles, g.Ci};
@@ -207,19 +211,20 @@ static hipError_t winograd_run(const Dims &d, int op, int b, const float *in, co
         log->add("wino_output_kernel");
         return hipSuccess;
     }
-    wino_output_kernel<<<go, 256, 0, s>>>(Z, out, g, divT, divTW, n_tiles);
+    wino_output_kernel<E><<<go, 256, 0, s>>>(Z, out, g, divT, divTW, n_tiles);
     return hipGetLastError();
 }
 
-hipError_t winograd_fwd(const Dims &d, int b, const float *x, const float *w, float *y, float *ws, hipStream_t s)
+hipError_t winograd_fwd(const Dims &d, int b, const void *x, const void *w, void *y, float *ws, hipStream_t s)
 {
-    return winograd_run(d, 0, b, x, w, y, ws, s);
+    return d.dtype == 1 ? winograd_run<bf16>(d, 0, b, x, w, y, ws, s) : winograd_run<float>(d, 0, b, x, w, y, ws, s);
 }
 
-hipError_t winograd_bwd_data(const Dims &d, int b, const float *dy, const float *w, float *dx, float *ws,
+hipError_t winograd_bwd_data(const Dims &d, int b, const void *dy, const void *w, void *dx, float *ws,
                              hipStream_t s)
 {
-    return winograd_run(d, 1, b, dy, w, dx, ws, s);
+    return d.dtype == 1 ? winograd_run<bf16>(d, 1, b, dy, w, dx, ws, s)
+                        : winograd_run<float>(d, 1, b, dy, w, dx, ws, s);
 }
 
 }  // namespace ucd

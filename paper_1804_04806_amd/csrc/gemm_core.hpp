@@ -16,6 +16,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <string>
+
 namespace ucd {
 
 constexpr int kThreads = 256;
@@ -113,6 +115,46 @@ __device__ __forceinline__ f32x4 buf_load4(__amdgpu_buffer_rsrc_t r, uint32_t by
     return v;
 }
 
+// Element types of tensor operands.  fp32, or bf16 storage: a bf16 value is widened on load by
+// placing its 16 bits in the upper half of a register (that is its exact fp32 value, so all
+// arithmetic downstream is the fp32 path's) and rounded to nearest-even when an output is stored.
+struct bf16 {};
+template <class E> struct Elem;
+template <> struct Elem<float> {
+    static constexpr uint32_t kBytes = 4;
+    static const char *tag() { return ""; }
+    static __device__ __forceinline__ float load(__amdgpu_buffer_rsrc_t r, uint32_t vo, uint32_t so)
+    {
+        return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, (int)vo, (int)so, 0));
+    }
+    static __device__ __forceinline__ void store(void *base, long idx, float v) { ((float *)base)[idx] = v; }
+    static __device__ __forceinline__ float get(const void *base, size_t idx) { return ((const float *)base)[idx]; }
+};
+template <> struct Elem<bf16> {
+    static constexpr uint32_t kBytes = 2;
+    static const char *tag() { return "/bf16"; }
+    static __device__ __forceinline__ float load(__amdgpu_buffer_rsrc_t r, uint32_t vo, uint32_t so)
+    {
+        const uint32_t h = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(r, (int)vo, (int)so, 0);
+        return __uint_as_float(h << 16);
+    }
+    static __device__ __forceinline__ uint16_t round(float v)
+    {
+        const uint32_t u = __float_as_uint(v);
+        const uint32_t r = u + 0x7fffu + ((u >> 16) & 1u);  // nearest, ties to even
+        return (uint16_t)((v != v ? 0x7fc00000u : r) >> 16);
+    }
+    static __device__ __forceinline__ void store(void *base, long idx, float v) { ((uint16_t *)base)[idx] = round(v); }
+    static __device__ __forceinline__ float get(const void *base, size_t idx)
+    {
+        return __uint_as_float((uint32_t)((const uint16_t *)base)[idx] << 16);
+    }
+};
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc_bytes(const void *p, long byte_shift, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc((void *)((const char *)p - byte_shift), 0, (int)bytes, 0x00020000);
+}
+
 // Gather from an NCHW tensor, lanes along the tile dimension.  Tile position j decodes to
 // (n, a, b) over a grid; reduction row kk decodes to (c, r, s); the element is
 // T[n, c, a*mul_h + add_h + dir*r, b*mul_w + add_w + dir*s] when in range.
@@ -127,7 +169,7 @@ __device__ __forceinline__ f32x4 buf_load4(__amdgpu_buffer_rsrc_t r, uint32_t by
 // Both address parts are kept non-negative by pointing the buffer resource `shift` elements
 // before the tensor (never dereferenced there: every in-range element lies inside the tensor).
 struct GatherParams {
-    const float *t;
+    const void *t;
     uint32_t bytes;
     int Ct, Ht, Wt;          // tensor channel count and plane size
     FastDiv grid_hw, grid_w; // tile-position decode
@@ -138,9 +180,10 @@ struct GatherParams {
 };
 
 // SMALL: at most 31 taps, one mask bit per (r, s); otherwise one mask per axis (R, S <= 31).
-template <int TD, bool SMALL>
+template <int TD, bool SMALL, class E = float>
 struct GatherNLaneT {
-    static const char *name() { return SMALL ? "GatherNLane<taps<=31>" : "GatherNLane<taps>31>"; }
+    static constexpr uint32_t EB = Elem<E>::kBytes;
+    static std::string name() { return std::string(SMALL ? "GatherNLane<taps<=31>" : "GatherNLane<taps>31>") + Elem<E>::tag(); }
     static_assert(TD >= 64, "a wave must cover one reduction row");
     static constexpr int RP = kThreads / TD;  // reduction rows per pass
     static constexpr int NE = kBK / RP;       // elements per thread per step
@@ -157,7 +200,7 @@ struct GatherNLaneT {
     {
         p = &prm;
         const int shift = prm.shift_thread + prm.shift_row;
-        rsrc = make_rsrc(prm.t - shift, prm.bytes + 4u * (uint32_t)shift);
+        rsrc = make_rsrc_bytes(prm.t, (long)EB * shift, prm.bytes + EB * (uint32_t)shift);
         const int tid = threadIdx.x;
         col = tid % TD;
         row0 = __builtin_amdgcn_readfirstlane(tid / TD);
@@ -169,7 +212,7 @@ struct GatherNLaneT {
             prm.grid_hw.divmod((uint32_t)j, n, rest);
             prm.grid_w.divmod(rest, a, b);
             const int hb = (int)a * prm.mul_h + prm.add_h, wb = (int)b * prm.mul_w + prm.add_w;
-            voff = 4u * (uint32_t)((int)n * prm.Ct * prm.Ht * prm.Wt + hb * prm.Wt + wb + prm.shift_thread);
+            voff = EB * (uint32_t)((int)n * prm.Ct * prm.Ht * prm.Wt + hb * prm.Wt + wb + prm.shift_thread);
             uint32_t okh = 0, okw = 0;
             for (int r = 0; r < prm.n_tap_h; ++r)
                 if ((unsigned)(hb + prm.dir * r) < (unsigned)prm.Ht) okh |= 1u << r;
@@ -200,7 +243,7 @@ struct GatherNLaneT {
         p->taps_w.divmod(tap, tr, ts);
         const uint32_t dead = (uint32_t)((k_end_ - 1 - kk) >> 31);  // all ones for rows past the end
         const uint32_t so =
-            ~dead & (4u * (uint32_t)(((int)c * p->Ht + p->dir * (int)tr) * p->Wt + p->dir * (int)ts + p->shift_row));
+            ~dead & (EB * (uint32_t)(((int)c * p->Ht + p->dir * (int)tr) * p->Wt + p->dir * (int)ts + p->shift_row));
         uint32_t vo;
         if (SMALL) {
             const uint32_t bit = tap | (dead & 31u);
@@ -209,7 +252,7 @@ struct GatherNLaneT {
             const uint32_t bit = tr | (dead & 31u);
             vo = (((nmask >> bit) | (nmask_w >> ts)) << 31) | voff;
         }
-        r[i] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc, (int)vo, (int)so, 0));
+        r[i] = Elem<E>::load(rsrc, vo, so);
     }
     __device__ __forceinline__ void store(float *lds, int i, const float (&r)[NE]) const
     {
@@ -230,7 +273,7 @@ template <int TD> using GatherNLaneBig = GatherNLaneT<TD, false>;
 // Rows past k_end get voffset 0x80000000.
 
 struct KLaneParams {
-    const float *t;
+    const void *t;
     uint32_t bytes;
     int row_stride, col_stride;                        // dense: element (kk, j) = t[kk*row_stride + j*col_stride]
     FastDiv taps, taps_w;                              // filter gather: kk -> (k, tap) -> (r, s)
@@ -251,9 +294,10 @@ struct KLaneParams {
 // Dense matrix, element (kk, j) = t[kk*row_stride + j*col_stride]  (operand limit 2 GiB).
 // One VGPR of address state: the thread's (kl, c0) offset; the step and the position index i enter
 // as scalar offsets.
-template <int TD>
-struct KLane0 {
-    static const char *name() { return "KLane0"; }
+template <int TD, class E = float>
+struct KLane0T {
+    static constexpr uint32_t EB = Elem<E>::kBytes;
+    static std::string name() { return std::string("KLane0") + Elem<E>::tag(); }
     static constexpr int CP = kThreads / kBK;  // tile positions per pass (16)
     static constexpr int NE = TD / CP;
     static constexpr int LD = TD + kPad;
@@ -268,10 +312,10 @@ struct KLane0 {
     __device__ __forceinline__ void init(const KLaneParams &prm, int origin, int)
     {
         p = &prm;
-        rsrc = make_rsrc(prm.t, prm.bytes);
+        rsrc = make_rsrc_bytes(prm.t, 0, prm.bytes);
         kl = threadIdx.x % kBK;
         c0 = threadIdx.x / kBK;
-        voff = 4u * (uint32_t)(kl * prm.row_stride + (origin + c0) * prm.col_stride);
+        voff = EB * (uint32_t)(kl * prm.row_stride + (origin + c0) * prm.col_stride);
     }
     template <class Peer>
     __device__ __forceinline__ void prep(int k0, int k_end, const Peer &)
@@ -281,8 +325,7 @@ struct KLane0 {
     }
     __device__ __forceinline__ void load(int i, float (&r)[NE]) const
     {
-        r[i] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(
-            rsrc, (int)vo_, (int)(4u * (uint32_t)(k0_ * p->row_stride + CP * i * p->col_stride)), 0));
+        r[i] = Elem<E>::load(rsrc, vo_, EB * (uint32_t)(k0_ * p->row_stride + CP * i * p->col_stride));
     }
     __device__ __forceinline__ void store(float *lds, int i, const float (&r)[NE]) const
     {
@@ -290,11 +333,14 @@ struct KLane0 {
     }
 };
 
+template <int TD> using KLane0 = KLane0T<TD, float>;
+
 // BackwardData's A operand: element (kk -> (k, r, s), j = c) = w[k, c, tap_add_h + tap_mul_h*r, tap_add_w + tap_mul_w*s]
 // (the filter taps of one stride phase).
-template <int TD>
-struct FilterKLane {
-    static const char *name() { return "FilterKLane"; }
+template <int TD, class E = float>
+struct FilterKLaneT {
+    static constexpr uint32_t EB = Elem<E>::kBytes;
+    static std::string name() { return std::string("FilterKLane") + Elem<E>::tag(); }
     static constexpr int CP = kThreads / kBK;
     static constexpr int NE = TD / CP;
     static constexpr int LD = TD + kPad;
@@ -308,10 +354,10 @@ struct FilterKLane {
     __device__ __forceinline__ void init(const KLaneParams &prm, int origin, int)
     {
         p = &prm;
-        rsrc = make_rsrc(prm.t, prm.bytes);
+        rsrc = make_rsrc_bytes(prm.t, 0, prm.bytes);
         kl = threadIdx.x % kBK;
         c0 = threadIdx.x / kBK;
-        coff0 = 4u * (uint32_t)((origin + c0) * prm.col_stride);
+        coff0 = EB * (uint32_t)((origin + c0) * prm.col_stride);
     }
     template <class Peer>
     __device__ __forceinline__ void prep(int k0, int k_end, const Peer &)
@@ -328,18 +374,19 @@ struct FilterKLane {
             roff = (int)k * p->k_stride + (p->tap_add_h + p->tap_mul_h * (int)tr) * p->s_mem + p->tap_add_w +
                    p->tap_mul_w * (int)ts;
         }
-        vo_ = kk < k_end ? 4u * (uint32_t)roff + coff0 : kOob;
+        vo_ = kk < k_end ? EB * (uint32_t)roff + coff0 : kOob;
     }
     __device__ __forceinline__ void load(int i, float (&r)[NE]) const
     {
-        r[i] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(
-            rsrc, (int)vo_, (int)(4u * (uint32_t)(CP * i * p->col_stride)), 0));
+        r[i] = Elem<E>::load(rsrc, vo_, EB * (uint32_t)(CP * i * p->col_stride));
     }
     __device__ __forceinline__ void store(float *lds, int i, const float (&r)[NE]) const
     {
         lds[kl * LD + c0 + CP * i] = r[i];
     }
 };
+
+template <int TD> using FilterKLane = FilterKLaneT<TD, float>;
 
 // BackwardFilter's operands: reduction row kk -> (n, a, b) over the output-pixel grid, tile
 // position j -> (c, r, s); element = T[n, c, a*mul_h + add_h + r, b*mul_w + add_w + s].
@@ -348,9 +395,10 @@ struct FilterKLane {
 //                   that fall outside the image; bit 31 of the row mask is always set and serves
 //                   out-of-extent tile positions (r = 31) and rows past the end (mask = all ones).
 // The x loader reuses the pixel decode its peer (the dy loader of the same step) has just done.
-template <int TD, bool WINDOW>
+template <int TD, bool WINDOW, class E = float>
 struct PixelKLane {
-    static const char *name() { return WINDOW ? "PixelKLane<x>" : "PixelKLane<dy>"; }
+    static constexpr uint32_t EB = Elem<E>::kBytes;
+    static std::string name() { return std::string(WINDOW ? "PixelKLane<x>" : "PixelKLane<dy>") + Elem<E>::tag(); }
     static constexpr int CP = kThreads / kBK;
     static constexpr int NE = TD / CP;
     static constexpr int LD = TD + kPad;
@@ -367,12 +415,12 @@ struct PixelKLane {
     __device__ __forceinline__ void init(const KLaneParams &prm, int origin, int extent)
     {
         p = &prm;
-        rsrc = make_rsrc(prm.t - prm.shift, prm.bytes + 4u * (uint32_t)prm.shift);
+        rsrc = make_rsrc_bytes(prm.t, (long)EB * prm.shift, prm.bytes + EB * (uint32_t)prm.shift);
         kl = threadIdx.x % kBK;
         c0 = threadIdx.x / kBK;
         n_ = rest_ = 0;
         if constexpr (!WINDOW) {
-            coffb[0] = 4u * (uint32_t)((origin + c0) * prm.Ht * prm.Wt);
+            coffb[0] = EB * (uint32_t)((origin + c0) * prm.Ht * prm.Wt);
             rs[0] = 0;
         } else {
 #pragma unroll
@@ -383,7 +431,7 @@ struct PixelKLane {
                     prm.col_taps.divmod((uint32_t)j, c, tap);
                     prm.col_taps_w.divmod(tap, r, s);
                     rs[i] = r | (s << 8);
-                    coffb[i] = 4u * (uint32_t)(((int)c * prm.Ht + (int)r) * prm.Wt + (int)s);
+                    coffb[i] = EB * (uint32_t)(((int)c * prm.Ht + (int)r) * prm.Wt + (int)s);
                 } else {
                     rs[i] = 31u;  // bit 31 of the row mask is always set
                     coffb[i] = 0u;
@@ -399,12 +447,12 @@ struct PixelKLane {
         if constexpr (!WINDOW) {
             p->grid_hw.divmod((uint32_t)kk, n_, rest_);
             // grid is the tensor's own plane here: (a, b) -> a*Wt + b == rest
-            vo_ = rowok ? 4u * (uint32_t)((int)n_ * p->n_stride + (int)rest_) + coffb[0] : kOob;
+            vo_ = rowok ? EB * (uint32_t)((int)n_ * p->n_stride + (int)rest_) + coffb[0] : kOob;
         } else {
             uint32_t a, b;
             p->grid_w.divmod(peer.rest_, a, b);
             const int hb = (int)a * p->mul_h + p->add_h, wb = (int)b * p->mul_w + p->add_w;
-            vo_ = 4u * (uint32_t)((int)peer.n_ * p->n_stride + hb * p->Wt + wb + p->shift);
+            vo_ = EB * (uint32_t)((int)peer.n_ * p->n_stride + hb * p->Wt + wb + p->shift);
             // taps r in [lo, hi) are inside the image; everything else (and bit 31) is masked
             const int lo_h = min(max(-hb, 0), 31), hi_h = max(min(p->Ht - hb, 31), lo_h);
             const int lo_w = min(max(-wb, 0), 31), hi_w = max(min(p->Wt - wb, 31), lo_w);
@@ -416,11 +464,11 @@ struct PixelKLane {
     __device__ __forceinline__ void load(int i, float (&r)[NE]) const
     {
         if constexpr (!WINDOW) {
-            const uint32_t step = 4u * (uint32_t)(CP * p->Ht * p->Wt);  // scalar: 16 channels further
-            r[i] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc, (int)vo_, (int)(step * (uint32_t)i), 0));
+            const uint32_t step = EB * (uint32_t)(CP * p->Ht * p->Wt);  // scalar: 16 channels further
+            r[i] = Elem<E>::load(rsrc, vo_, step * (uint32_t)i);
         } else {
             const uint32_t t = (nrow_ >> (rs[i] & 0xffu)) | (ncol_ >> (rs[i] >> 8));
-            r[i] = buf_load(rsrc, (t << 31) | (vo_ + coffb[i]));
+            r[i] = Elem<E>::load(rsrc, (t << 31) | (vo_ + coffb[i]), 0);
         }
     }
     __device__ __forceinline__ void store(float *lds, int i, const float (&r)[NE]) const
@@ -434,7 +482,7 @@ template <int TD> using XKLane = PixelKLane<TD, true>;
 // Dense matrix contiguous along the tile dimension:  element (kk, j) = t[kk*ld + j], float4 loads.
 // Requires ld % 4 == 0 and a 16-byte aligned base; columns in [extent, ld) may hold anything.
 struct DenseParams {
-    const float *t;
+    const void *t;
     uint32_t bytes;
     int ld;
 };
@@ -456,7 +504,7 @@ struct DenseNLane {
     __device__ __forceinline__ void init(const DenseParams &prm, int origin, int extent)
     {
         p = &prm;
-        rsrc = make_rsrc(prm.t, prm.bytes);
+        rsrc = make_rsrc_bytes(prm.t, 0, prm.bytes);
         const int tid = threadIdx.x;
         col = (tid % CQ) * 4;
         row0 = tid / CQ;
@@ -484,9 +532,10 @@ struct DenseNLane {
 };
 
 // Same matrix, any ld / alignment: scalar loads, one reduction row per pass.
-template <int TD>
-struct DenseNLaneS {
-    static const char *name() { return "DenseNLaneS"; }
+template <int TD, class E = float>
+struct DenseNLaneST {
+    static constexpr uint32_t EB = Elem<E>::kBytes;
+    static std::string name() { return std::string("DenseNLaneS") + Elem<E>::tag(); }
     static constexpr int RP = kThreads / TD;
     static constexpr int NE = kBK / RP;
     static constexpr int LD = TD + kPad;
@@ -500,7 +549,7 @@ struct DenseNLaneS {
     __device__ __forceinline__ void init(const DenseParams &prm, int origin, int extent)
     {
         p = &prm;
-        rsrc = make_rsrc(prm.t, prm.bytes);
+        rsrc = make_rsrc_bytes(prm.t, 0, prm.bytes);
         const int tid = threadIdx.x;
         col = tid % TD;
         row0 = TD >= 64 ? __builtin_amdgcn_readfirstlane(tid / TD) : tid / TD;  // wave-uniform only if TD >= 64
@@ -516,12 +565,26 @@ struct DenseNLaneS {
     __device__ __forceinline__ void load(int i, float (&r)[NE]) const
     {
         const int kk = k0_ + row0 + RP * i;
-        r[i] = buf_load(rsrc, (kk < k_end_ && ok_) ? (uint32_t)(kk * p->ld + j_) * 4u : kOob);
+        r[i] = Elem<E>::load(rsrc, (kk < k_end_ && ok_) ? (uint32_t)(kk * p->ld + j_) * EB : kOob, 0);
     }
     __device__ __forceinline__ void store(float *lds, int i, const float (&r)[NE]) const
     {
         lds[(row0 + RP * i) * LD + col] = r[i];
     }
+};
+
+template <int TD> using DenseNLaneS = DenseNLaneST<TD, float>;
+
+// The tensor-facing loaders for element type E, as templates of the tile extent alone.
+template <class E>
+struct Loaders {
+    template <int TD> using KLane0 = KLane0T<TD, E>;
+    template <int TD> using FilterKLane = FilterKLaneT<TD, E>;
+    template <int TD> using GatherNLane = GatherNLaneT<TD, true, E>;
+    template <int TD> using GatherNLaneBig = GatherNLaneT<TD, false, E>;
+    template <int TD> using DyKLane = PixelKLane<TD, false, E>;
+    template <int TD> using XKLane = PixelKLane<TD, true, E>;
+    template <int TD> using DenseNLaneS = DenseNLaneST<TD, E>;
 };
 
 // ---- epilogues ---------------------------------------------------------------------------------
@@ -531,12 +594,13 @@ struct DenseNLaneS {
 // out[n, m, h0 + hs*a, w0 + ws*b].  Forward writes y with the trivial grid; BackwardData writes
 // one stride phase of dx.
 struct EpiNCHWParams {
-    float *out;
+    void *out;
     FastDiv grid_hw, grid_w;
     int M, HWo, Wo, h0, hs, w0, ws;
 };
-struct EpiNCHW {
-    static const char *name() { return "EpiNCHW"; }
+template <class E>
+struct EpiNCHWT {
+    static std::string name() { return std::string("EpiNCHW") + Elem<E>::tag(); }
     typedef EpiNCHWParams Params;
     int off;
     __device__ __forceinline__ void prep(const Params &p, int j)
@@ -546,15 +610,19 @@ struct EpiNCHW {
         p.grid_w.divmod(rest, a, b);
         off = (int)n * p.M * p.HWo + (p.h0 + p.hs * (int)a) * p.Wo + p.w0 + p.ws * (int)b;
     }
-    __device__ __forceinline__ void store(const Params &p, int m, float v) const { p.out[off + m * p.HWo] = v; }
+    __device__ __forceinline__ void store(const Params &p, int m, float v) const
+    {
+        Elem<E>::store(p.out, off + m * p.HWo, v);
+    }
 };
+typedef EpiNCHWT<float> EpiNCHW;
 // The same scatter as an fp32 atomic add into a zero-filled tensor, for GEMMs whose reduction is
 // split over several workgroups because the output has too few tiles to fill the chip.
 struct EpiNCHWAtomic : EpiNCHW {
     static const char *name() { return "EpiNCHWAtomic"; }
     __device__ __forceinline__ void store(const Params &p, int m, float v) const
     {
-        unsafeAtomicAdd(p.out + off + m * p.HWo, v);
+        unsafeAtomicAdd((float *)p.out + off + m * p.HWo, v);
     }
 };
 
@@ -594,10 +662,10 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(AParams pa, BParams pb, 
 {
     __shared__ __attribute__((aligned(16))) float lds[2][T::LDS_FLOATS];
 
-    if (blockIdx.z) {
-        pa.t += a_batch * blockIdx.z;
-        pb.t += b_batch * blockIdx.z;
-        pe.out += c_batch * blockIdx.z;
+    if (blockIdx.z) {  // batched GEMMs run on fp32 matrices (strides in floats)
+        pa.t = (const float *)pa.t + a_batch * blockIdx.z;
+        pb.t = (const float *)pb.t + b_batch * blockIdx.z;
+        pe.out = (float *)pe.out + c_batch * blockIdx.z;
     }
     int tile_m, tile_n, split;
     xcd_tile(tiles_m, tiles_n, tile_m, tile_n, split);

@@ -8,35 +8,39 @@
 
 namespace ucd {
 
+// dtype 0: every tensor fp32.  dtype 1: x, w, dy, y, dx are bf16 (16-bit storage); dw and every
+// workspace matrix stay fp32, and all arithmetic is the fp32 path's.
 struct Dims {
     int C, H, W, K, R, S, sh, sw, ph, pw, P, Q;
+    int dtype;
     int crs() const { return C * R * S; }
+    size_t esize() const { return dtype == 1 ? 2 : 4; }
 };
 
 // operand sizes in bytes (each at most 2 GiB, checked before any launch)
-inline uint32_t wbytes(const Dims &d) { return (uint32_t)((size_t)4 * d.K * d.crs()); }
-inline uint32_t xbytes(const Dims &d, int b) { return (uint32_t)((size_t)4 * b * d.C * d.H * d.W); }
-inline uint32_t ybytes(const Dims &d, int b) { return (uint32_t)((size_t)4 * b * d.K * d.P * d.Q); }
+inline uint32_t wbytes(const Dims &d) { return (uint32_t)(d.esize() * d.K * d.crs()); }
+inline uint32_t xbytes(const Dims &d, int b) { return (uint32_t)(d.esize() * b * d.C * d.H * d.W); }
+inline uint32_t ybytes(const Dims &d, int b) { return (uint32_t)(d.esize() * b * d.K * d.P * d.Q); }
 
 // zero-workspace implicit GEMM
-hipError_t implicit_fwd(const Dims &d, int b, const float *x, const float *w, float *y, hipStream_t s);
-hipError_t implicit_bwd_data(const Dims &d, int b, const float *dy, const float *w, float *dx, hipStream_t s);
-hipError_t implicit_bwd_filter(const Dims &d, int b, const float *x, const float *dy, float *dw, float beta,
+hipError_t implicit_fwd(const Dims &d, int b, const void *x, const void *w, void *y, hipStream_t s);
+hipError_t implicit_bwd_data(const Dims &d, int b, const void *dy, const void *w, void *dx, hipStream_t s);
+hipError_t implicit_bwd_filter(const Dims &d, int b, const void *x, const void *dy, float *dw, float beta,
                                hipStream_t s);
 
 // im2col into workspace + GEMM
 size_t im2col_ws_bytes(const Dims &d, int b);
-hipError_t im2col_fwd(const Dims &d, int b, const float *x, const float *w, float *y, float *ws, hipStream_t s);
-hipError_t im2col_bwd_data(const Dims &d, int b, const float *dy, const float *w, float *dx, float *ws,
+hipError_t im2col_fwd(const Dims &d, int b, const void *x, const void *w, void *y, float *ws, hipStream_t s);
+hipError_t im2col_bwd_data(const Dims &d, int b, const void *dy, const void *w, void *dx, float *ws,
                            hipStream_t s);
-hipError_t im2col_bwd_filter(const Dims &d, int b, const float *x, const float *dy, float *dw, float beta,
+hipError_t im2col_bwd_filter(const Dims &d, int b, const void *x, const void *dy, float *dw, float beta,
                              float *ws, hipStream_t s);
 
 // Winograd F(2x2,3x3), 3x3 stride-1 layers, Forward and BackwardData
 bool winograd_applies(const Dims &d, int op);
 size_t winograd_ws_bytes(const Dims &d, int op, int b);
-hipError_t winograd_fwd(const Dims &d, int b, const float *x, const float *w, float *y, float *ws, hipStream_t s);
-hipError_t winograd_bwd_data(const Dims &d, int b, const float *dy, const float *w, float *dx, float *ws,
+hipError_t winograd_fwd(const Dims &d, int b, const void *x, const void *w, void *y, float *ws, hipStream_t s);
+hipError_t winograd_bwd_data(const Dims &d, int b, const void *dy, const void *w, void *dx, float *ws,
                              hipStream_t s);
 
 hipError_t fill_zero(float *p, size_t n, hipStream_t s);

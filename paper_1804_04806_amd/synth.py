@@ -79,6 +79,19 @@ def make_w(s, seed=0, layer_index=0):
     return (_gen(seed, layer_index, _W).standard_normal(size=s.w_shape) * std).astype(np.float32)
 
 
+def to_bf16_bits(a):
+    """bfloat16 storage of an fp32 array: round to nearest, ties to even; returns uint16 bits.
+    (Input preparation for the bf16 variant: the values the library is handed.)"""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+    r = u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))
+    return (r >> np.uint32(16)).astype(np.uint16)
+
+
+def from_bf16_bits(h):
+    """The exact fp32 value of bfloat16 bits."""
+    return (np.ascontiguousarray(h, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
 def sample_indices(total, count, seed=0):
     """``count`` distinct flat indices below ``total`` (all of them if total <= count), sorted."""
     if total <= count:

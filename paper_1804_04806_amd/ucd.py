@@ -123,11 +123,12 @@ def _stream(stream):
     return stream.cuda_stream
 
 
-def layer(shape=None, **kw):
-    """LayerDesc from a ``synth.Shape``-like object (N,C,H,W,K,R,S,stride,pad) or keywords."""
+def layer(shape=None, dtype=0, **kw):
+    """LayerDesc from a ``synth.Shape``-like object (N,C,H,W,K,R,S,stride,pad) or keywords.
+    dtype 0 = fp32 tensors; 1 = bf16 x, w, dy, y, dx with fp32 dw."""
     if shape is not None:
         return LayerDesc(shape.N, shape.C, shape.H, shape.W, shape.K, shape.R, shape.S,
-                         shape.stride, shape.stride, shape.pad, shape.pad, 0)
+                         shape.stride, shape.stride, shape.pad, shape.pad, dtype)
     d = dict(stride_h=1, stride_w=1, pad_h=0, pad_w=0, dtype=0)
     d.update(kw)
     return LayerDesc(**d)
