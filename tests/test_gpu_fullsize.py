@@ -33,16 +33,24 @@ SMALL = [(0, synth.config_small()[0], 64 * 1024, ucd.POLICY_ALL), (0, synth.conf
          (0, synth.config_small()[0], MIB, ucd.POLICY_ALL)]
 
 
-def check_layer(idx, s, limit, policy, n_samples=1500, n_filter_samples=150):
+def check_layer(idx, s, limit, policy, n_samples=1500, n_filter_samples=150, bf16=False):
+    """bf16: tensors stored as bfloat16 (dw fp32); the oracle then runs on the rounded inputs and
+    y / dx carry the output rounding (half an ulp = 2^-8 relative: 5e-3 in relative L2)."""
     import torch
     dev = torch.device("cuda:0")
-    desc = ucd.layer(s)
+    desc = ucd.layer(s, dtype=1 if bf16 else 0)
     L = oracle_layer(s)
     x, w, dy = synth.make_x(s, 1, idx), synth.make_w(s, 1, idx), synth.make_dy(s, 1, idx)
-    xd, wd, dyd = (torch.from_numpy(a).to(dev) for a in (x, w, dy))
+    tdt = torch.bfloat16 if bf16 else torch.float32
+    if bf16:
+        bits = [synth.to_bf16_bits(a) for a in (x, w, dy)]
+        x, w, dy = (synth.from_bf16_bits(b) for b in bits)
+        xd, wd, dyd = (torch.from_numpy(b.view(np.int16)).to(dev).view(torch.bfloat16) for b in bits)
+    else:
+        xd, wd, dyd = (torch.from_numpy(a).to(dev) for a in (x, w, dy))
     ws = torch.empty(max(limit, 4) // 4, dtype=torch.float32, device=dev)
-    out_y = torch.empty(s.y_shape, dtype=torch.float32, device=dev)
-    out_dx = torch.empty(s.x_shape, dtype=torch.float32, device=dev)
+    out_y = torch.empty(s.y_shape, dtype=tdt, device=dev)
+    out_dx = torch.empty(s.x_shape, dtype=tdt, device=dev)
     out_dw = torch.empty(s.w_shape, dtype=torch.float32, device=dev)
     pf = ucd.ucd_plan(desc, ucd.FWD, limit, policy, xd, wd, out_y, ws)
     pd = ucd.ucd_plan(desc, ucd.BWD_DATA, limit, policy, out_dx, wd, dyd, ws)
@@ -55,12 +63,14 @@ def check_layer(idx, s, limit, policy, n_samples=1500, n_filter_samples=150):
     ucd.ucd_conv_bwd_data(pd, dyd, wd, out_dx, ws)
     ucd.ucd_conv_bwd_filter(pw, xd, dyd, out_dw, 0.0, ws)
     torch.cuda.synchronize()
-    y, dx, dw = out_y.cpu().numpy(), out_dx.cpu().numpy(), out_dw.cpu().numpy()
+    y, dx, dw = out_y.float().cpu().numpy(), out_dx.float().cpu().numpy(), out_dw.cpu().numpy()
     del xd, dyd, out_y, out_dx, ws
     assert np.isfinite(y).all() and np.isfinite(dx).all() and np.isfinite(dw).all()
     x64, w64, dy64 = x.astype(np.float64), w.astype(np.float64), dy.astype(np.float64)
 
     def tol(p):
+        if bf16 and p is not pw:
+            return 5e-3
         return 1e-3 if any(a == ucd.ALGO_WINOGRAD for a, _ in p.micro) else 1e-5
 
     iy = synth.sample_indices(y.size, n_samples, seed=1)
@@ -92,3 +102,11 @@ def test_resnet18_full_batch_planned(idx, s, limit, policy):
 @pytest.mark.parametrize("idx,s,limit,policy", DENSENET + RESNET50, ids=lambda v: getattr(v, "name", None))
 def test_densenet_resnet50_layers_planned(idx, s, limit, policy):
     check_layer(idx, s, limit, policy, n_samples=800, n_filter_samples=60)
+
+
+BF16 = [t for t in ALEXNET if t[1].name in ("conv2", "conv4")] + [t for t in RESNET50 if t[1].name in ("s4b0.conv3x3", "s4b0.proj")]
+
+
+@pytest.mark.parametrize("idx,s,limit,policy", BF16, ids=lambda v: getattr(v, "name", None))
+def test_bf16_layers_planned(idx, s, limit, policy):
+    check_layer(idx, s, limit, ucd.POLICY_POW2, n_samples=800, n_filter_samples=60, bf16=True)
