@@ -50,6 +50,7 @@ MEASURED_TRAFFIC_BYTES = {
 WORKLOADS = {
     "alexnet": ("AlexNet-shaped 5-layer conv stack", "config_alexnet", 256, 64 << 20, "wr", "all"),
     "small": ("single small 3x3 layer", "config_small", 8, 64 << 10, "wr", "all"),
+    "alexnet-wd": ("AlexNet-shaped 5-layer conv stack", "config_alexnet", 256, 120 << 20, "wd", "all"),
     "resnet18": ("ResNet-18-shaped conv layers (20 layers)", "config_resnet18", 256, 64 << 20, "wr", "pow2"),
     "densenet": ("DenseNet-BC-style block (24 layers)", "config_densenet_block", 64, 8 << 20, "wr", "pow2"),
     "resnet50-wr": ("ResNet-50-shaped conv layers (53 layers)", "config_resnet50", 256, 64 << 20, "wr", "pow2"),
@@ -66,6 +67,8 @@ def parse():
     ap.add_argument("--workload", default="alexnet", choices=sorted(WORKLOADS))
     ap.add_argument("--policy", default=None, choices=["all", "pow2", "undivided"])
     ap.add_argument("--batch", type=int, default=None)
+    ap.add_argument("--ws-mib", type=float, default=None,
+                    help="override the workload's workspace limit (per layer for WR, total for WD), in MiB")
     ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"],
                     help="bf16: x, w, dy, y, dx stored as bfloat16 (dw and workspaces fp32, fp32 arithmetic)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -148,7 +151,11 @@ def plan_wd(ucd, states, pool, policy, ws, budget):
     # asks for; its own scratch tensors are then never launched on.
     for st in states:
         st.plan(ucd, policy, ws, budget)
-    plans, offs = ucd.ucd_plan_wd(descs, ops, budget, policy, pool.dx, pool.dw, pool.y, ws)
+    # scratch for the call's capacity checks: the largest output buffers (never launched on)
+    sx = max((st.dx for st in states), key=lambda t: t.numel())
+    sw = max((st.dw for st in states), key=lambda t: t.numel())
+    sy = max((st.y for st in states), key=lambda t: t.numel())
+    plans, offs = ucd.ucd_plan_wd(descs, ops, budget, policy, sx, sw, sy, ws)
     per_layer, per_off = [], []
     for i in range(len(states)):
         per_layer.append({ucd.FWD: plans[3 * i], ucd.BWD_DATA: plans[3 * i + 1], ucd.BWD_FILTER: plans[3 * i + 2]})
@@ -268,11 +275,13 @@ def main():
     dev = torch.device("cuda:0")
     title, table, batch0, limit, mode, policy0 = WORKLOADS[args.workload]
     batch = args.batch or batch0
+    if args.ws_mib is not None:
+        limit = int(args.ws_mib * (1 << 20))
     policy_name = args.policy or policy0
     policy = {"all": ucd.POLICY_ALL, "pow2": ucd.POLICY_POW2, "undivided": ucd.POLICY_UNDIVIDED}[policy_name]
     layers = getattr(synth, table)() if args.workload == "small" else getattr(synth, table)(batch)
     tdtype = torch.bfloat16 if args.dtype == "bf16" else torch.float32
-    pool = None if args.workload in ("alexnet", "small") else Pool(layers, torch, dev, tdtype)
+    pool = None if args.workload in ("alexnet", "alexnet-wd", "small") else Pool(layers, torch, dev, tdtype)
     states = [LayerState(s, i, torch, ucd, synth, dev, pool, tdtype) for i, s in enumerate(layers)]
     ws = torch.empty(max(limit, 4) // 4, dtype=torch.float32, device=dev)
     flops_per_step = 3 * sum(s.flops for s in layers)
