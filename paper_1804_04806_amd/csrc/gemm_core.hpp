@@ -731,9 +731,9 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(AParams pa, BParams pb, 
         // operands of the next k-pair are read from LDS before the MFMAs of the current one issue
         float a[2][T::WM], b[2][T::WN];
 #pragma unroll
-        for (int i = 0; i < T::WM; ++i) a[0][i] = As[lhi * T::LDA + wm0 + i * 32 + l32];
+        for (int i = 0; i < T::WM; ++i) a[0][i] = As[lhi * T::LDA + wm0 + T::WM * l32 + i];
 #pragma unroll
-        for (int j = 0; j < T::WN; ++j) b[0][j] = Bs[lhi * T::LDB + wn0 + j * 32 + l32];
+        for (int j = 0; j < T::WN; ++j) b[0][j] = Bs[lhi * T::LDB + wn0 + T::WN * l32 + j];
         __builtin_amdgcn_sched_barrier(0);
         __builtin_amdgcn_s_setprio(UCD_MFMA_PRIO);  // a wave inside its MFMA run keeps the pipe
 #pragma unroll
@@ -748,9 +748,9 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(AParams pa, BParams pb, 
                 __builtin_amdgcn_sched_barrier(0);
                 if (m == 0 && kk + 2 < kBK) {
 #pragma unroll
-                    for (int i = 0; i < T::WM; ++i) a[nxt][i] = As[(kk + 2 + lhi) * T::LDA + wm0 + i * 32 + l32];
+                    for (int i = 0; i < T::WM; ++i) a[nxt][i] = As[(kk + 2 + lhi) * T::LDA + wm0 + T::WM * l32 + i];
 #pragma unroll
-                    for (int j = 0; j < T::WN; ++j) b[nxt][j] = Bs[(kk + 2 + lhi) * T::LDB + wn0 + j * 32 + l32];
+                    for (int j = 0; j < T::WN; ++j) b[nxt][j] = Bs[(kk + 2 + lhi) * T::LDB + wn0 + T::WN * l32 + j];
                 }
                 if (m == 1 % NM) {
 #pragma unroll
@@ -776,18 +776,21 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(AParams pa, BParams pb, 
         buf ^= 1;
     }
 
-    // accumulator element v of a 32x32 tile: row 8*(v/4) + 4*(lane/32) + v%4, column lane%32
+    // accumulator element v of a 32x32 MFMA tile: row 8*(v/4) + 4*(lane/32) + v%4, column lane%32.
+    // A wave's WM x WN MFMA tiles are interleaved: MFMA row r of tile i is wave row WM*r + i (and
+    // likewise for columns), so that a lane's operands of one k-row are adjacent in LDS and come
+    // in one read with an immediate offset.
     Epi epi;
 #pragma unroll
     for (int j = 0; j < T::WN; ++j) {
-        const int col = n0 + wn0 + j * 32 + l32;
+        const int col = n0 + wn0 + T::WN * l32 + j;
         if (col >= N) continue;
         epi.prep(pe, col);
 #pragma unroll
         for (int i = 0; i < T::WM; ++i)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int row = m0 + wm0 + i * 32 + 8 * (v / 4) + 4 * lhi + (v % 4);
+                const int row = m0 + wm0 + T::WM * (8 * (v / 4) + 4 * lhi + (v % 4)) + i;
                 if (row < M) epi.store(pe, row, acc[i][j][v]);
             }
     }
