@@ -202,7 +202,14 @@ static hipError_t implicit_bwd_filter_t(const Dims &d, int b, const void *x, con
     pb.n_stride = d.C * d.H * d.W; pb.Ht = d.H; pb.Wt = d.W;
     pb.mul_h = d.sh; pb.add_h = -d.ph; pb.mul_w = d.sw; pb.add_w = -d.pw;
     pb.shift = d.ph * d.W + d.pw;
+    pb.n_tap_h = d.R; pb.n_tap_w = d.S;
     EpiDenseParams pe{dw, d.crs()};
+    if (d.R * d.S <= 31) {
+        // per-row state in an LDS table: the reduction chunk of a workgroup must fit it
+        const int need = (g.Kd + kTabRows - 1) / kTabRows;
+        if (g.splits < need) g.splits = need;
+        return launch_gemm<L::template DyTab, L::template XTab, EpiAtomic, true>(pa, pb, pe, g, s);
+    }
     return launch_gemm<L::template DyKLane, L::template XKLane, EpiAtomic, true>(pa, pb, pe, g, s);
 }
 

@@ -83,6 +83,16 @@ __device__ __forceinline__ void xcd_tile(int tiles_m, int tiles_n, int &tile_m, 
     tile_n = (int)(t / (uint32_t)tiles_m);
 }
 
+// Loaders may keep per-workgroup state in LDS (`Shared`, filled by `setup` before the main loop,
+// one barrier later everybody may read it); most have none.
+struct NoShared {};
+struct NoSetup {
+    typedef NoShared Shared;
+    static constexpr bool kHasShared = false;
+    template <class Peer>
+    __device__ __forceinline__ void setup(Shared &, int, int, const Peer &) {}
+};
+
 // ---- operand loaders ---------------------------------------------------------------------------
 // Common interface:  init(params, tile_origin, extent)  once per workgroup;
 //                    prep(k0, k_end, peer)   per-step state for reduction rows [k0, k0+BK);
@@ -181,7 +191,7 @@ struct GatherParams {
 
 // SMALL: at most 31 taps, one mask bit per (r, s); otherwise one mask per axis (R, S <= 31).
 template <int TD, bool SMALL, class E = float>
-struct GatherNLaneT {
+struct GatherNLaneT : NoSetup {
     static constexpr uint32_t EB = Elem<E>::kBytes;
     static std::string name() { return std::string(SMALL ? "GatherNLane<taps<=31>" : "GatherNLane<taps>31>") + Elem<E>::tag(); }
     static_assert(TD >= 64, "a wave must cover one reduction row");
@@ -280,6 +290,7 @@ struct KLaneParams {
     int k_stride, s_mem, tap_mul_h, tap_add_h, tap_mul_w, tap_add_w, unit_taps;
     FastDiv grid_hw, grid_w, col_taps, col_taps_w;     // pixel rows: kk -> (n, a, b); columns j -> (c, r, s)
     int n_stride, Ht, Wt, mul_h, add_h, mul_w, add_w, shift;
+    int n_tap_h, n_tap_w;                              // R, S of the column decode (table loaders)
 };
 
 // A note on tile positions outside the operand's extent (the ragged last tile): they only feed
@@ -295,7 +306,7 @@ struct KLaneParams {
 // One VGPR of address state: the thread's (kl, c0) offset; the step and the position index i enter
 // as scalar offsets.
 template <int TD, class E = float>
-struct KLane0T {
+struct KLane0T : NoSetup {
     static constexpr uint32_t EB = Elem<E>::kBytes;
     static std::string name() { return std::string("KLane0") + Elem<E>::tag(); }
     static constexpr int CP = kThreads / kBK;  // tile positions per pass (16)
@@ -338,7 +349,7 @@ template <int TD> using KLane0 = KLane0T<TD, float>;
 // BackwardData's A operand: element (kk -> (k, r, s), j = c) = w[k, c, tap_add_h + tap_mul_h*r, tap_add_w + tap_mul_w*s]
 // (the filter taps of one stride phase).
 template <int TD, class E = float>
-struct FilterKLaneT {
+struct FilterKLaneT : NoSetup {
     static constexpr uint32_t EB = Elem<E>::kBytes;
     static std::string name() { return std::string("FilterKLane") + Elem<E>::tag(); }
     static constexpr int CP = kThreads / kBK;
@@ -396,7 +407,7 @@ template <int TD> using FilterKLane = FilterKLaneT<TD, float>;
 //                   out-of-extent tile positions (r = 31) and rows past the end (mask = all ones).
 // The x loader reuses the pixel decode its peer (the dy loader of the same step) has just done.
 template <int TD, bool WINDOW, class E = float>
-struct PixelKLane {
+struct PixelKLane : NoSetup {
     static constexpr uint32_t EB = Elem<E>::kBytes;
     static std::string name() { return std::string(WINDOW ? "PixelKLane<x>" : "PixelKLane<dy>") + Elem<E>::tag(); }
     static constexpr int CP = kThreads / kBK;
@@ -479,6 +490,147 @@ struct PixelKLane {
 template <int TD> using DyKLane = PixelKLane<TD, false>;
 template <int TD> using XKLane = PixelKLane<TD, true>;
 
+// BackwardFilter's operands again, for filters of at most 31 taps and reduction chunks of at most
+// kTabRows rows: everything that depends on the reduction row alone (the pixel decode, the address
+// part of both tensors, and which taps of the window fall outside the image) is computed once per
+// workgroup into an LDS table, one entry per row of the chunk, instead of once per step per
+// thread.  Per step a thread then reads its entry (two LDS reads for x, one for dy) and spends three
+// vector instructions per x element (mask shift, address add, merge) and none per dy element.
+constexpr int kTabRows = 2048;
+constexpr int kTabCap = kTabRows + 2 * kBK;  // the pipeline looks two steps past the chunk's end
+
+struct PixelTable {
+    uint32_t dy_off[kTabCap];   // byte offset of (n, a, b) in dy, or kOob for rows past the end
+    uint32_t x_off[kTabCap];    // byte offset of the window origin in x (shifted resource)
+    uint32_t tapmask[kTabCap];  // bit r*S+s set = tap outside the image; bit 31 always set
+};
+
+template <int TD, class E = float>
+struct PixelTabX {
+    static constexpr uint32_t EB = Elem<E>::kBytes;
+    static std::string name() { return std::string("PixelTab<x>") + Elem<E>::tag(); }
+    static constexpr int CP = kThreads / kBK;
+    static constexpr int NE = TD / CP;
+    static constexpr int LD = TD + kPad;
+    typedef PixelTable Shared;
+    static constexpr bool kHasShared = true;
+    struct Regs { float r[NE]; };
+    const KLaneParams *p;
+    __amdgpu_buffer_rsrc_t rsrc;
+    const PixelTable *tab;
+    int kl, c0, k_begin_;
+    uint32_t coffb[NE];   // byte offset of each position's (c, r, s)
+    uint32_t tapbit[NE];  // r*S + s, or 31 for positions past the extent
+    uint32_t xo_, mask_;  // this step's table entry
+
+    __device__ __forceinline__ void init(const KLaneParams &prm, int origin, int extent)
+    {
+        p = &prm;
+        rsrc = make_rsrc_bytes(prm.t, (long)EB * prm.shift, prm.bytes + EB * (uint32_t)prm.shift);
+        kl = threadIdx.x % kBK;
+        c0 = threadIdx.x / kBK;
+        tab = nullptr;
+        k_begin_ = 0;
+        xo_ = 0;
+        mask_ = 0xFFFFFFFFu;
+#pragma unroll
+        for (int i = 0; i < NE; ++i) {
+            const int j = origin + c0 + CP * i;
+            if (j < extent) {
+                uint32_t c, tap, r, s;
+                prm.col_taps.divmod((uint32_t)j, c, tap);
+                prm.col_taps_w.divmod(tap, r, s);
+                tapbit[i] = tap;
+                coffb[i] = EB * (uint32_t)(((int)c * prm.Ht + (int)r) * prm.Wt + (int)s);
+            } else {
+                tapbit[i] = 31u;
+                coffb[i] = 0u;
+            }
+        }
+    }
+    // Fills the table for rows [k_begin, k_begin + kTabCap): the peer is the dy loader of the same
+    // GEMM (its parameters give dy's strides).
+    template <class Peer>
+    __device__ __forceinline__ void setup(PixelTable &sh, int k_begin, int k_end, const Peer &peer)
+    {
+        tab = &sh;
+        k_begin_ = k_begin;
+        const KLaneParams &q = *peer.p;
+        for (int e = threadIdx.x; e < kTabCap; e += kThreads) {
+            const int kk = k_begin + e;
+            uint32_t n, rest, a, b;
+            p->grid_hw.divmod((uint32_t)kk, n, rest);
+            p->grid_w.divmod(rest, a, b);
+            const int hb = (int)a * p->mul_h + p->add_h, wb = (int)b * p->mul_w + p->add_w;
+            uint32_t okw = 0, ok = 0;
+            for (int s = 0; s < p->n_tap_w; ++s)
+                if ((unsigned)(wb + s) < (unsigned)p->Wt) okw |= 1u << s;
+            for (int r = 0; r < p->n_tap_h; ++r)
+                if ((unsigned)(hb + r) < (unsigned)p->Ht) ok |= okw << (r * p->n_tap_w);
+            const bool live = kk < k_end;
+            sh.tapmask[e] = live ? (~ok | 0x80000000u) : 0xFFFFFFFFu;
+            sh.x_off[e] = EB * (uint32_t)((int)n * p->n_stride + hb * p->Wt + wb + p->shift);
+            sh.dy_off[e] = live ? Peer::EB * (uint32_t)((int)n * q.n_stride + (int)rest) : kOob;
+        }
+    }
+    template <class Peer>
+    __device__ __forceinline__ void prep(int k0, int, const Peer &)
+    {
+        const int e = k0 - k_begin_ + kl;
+        xo_ = tab->x_off[e];
+        mask_ = tab->tapmask[e];
+    }
+    __device__ __forceinline__ void load(int i, float (&r)[NE]) const
+    {
+        const uint32_t t = mask_ >> tapbit[i];
+        r[i] = Elem<E>::load(rsrc, (t << 31) | (xo_ + coffb[i]), 0);
+    }
+    __device__ __forceinline__ void store(float *lds, int i, const float (&r)[NE]) const
+    {
+        lds[kl * LD + c0 + CP * i] = r[i];
+    }
+};
+
+template <int TD, class E = float>
+struct PixelTabDy : NoSetup {
+    static constexpr uint32_t EB = Elem<E>::kBytes;
+    static std::string name() { return std::string("PixelTab<dy>") + Elem<E>::tag(); }
+    static constexpr int CP = kThreads / kBK;
+    static constexpr int NE = TD / CP;
+    static constexpr int LD = TD + kPad;
+    struct Regs { float r[NE]; };
+    const KLaneParams *p;
+    __amdgpu_buffer_rsrc_t rsrc;
+    int kl, c0;
+    uint32_t coff0;  // byte offset of position origin + c0 (a channel plane)
+    uint32_t vo_;
+
+    __device__ __forceinline__ void init(const KLaneParams &prm, int origin, int)
+    {
+        p = &prm;
+        rsrc = make_rsrc_bytes(prm.t, 0, prm.bytes);
+        kl = threadIdx.x % kBK;
+        c0 = threadIdx.x / kBK;
+        coff0 = EB * (uint32_t)((origin + c0) * prm.Ht * prm.Wt);
+        vo_ = kOob;
+    }
+    // the peer is the x loader, whose table holds dy's row offsets as well
+    template <class Peer>
+    __device__ __forceinline__ void prep(int k0, int, const Peer &peer)
+    {
+        vo_ = peer.tab->dy_off[k0 - peer.k_begin_ + kl] + coff0;  // kOob + coff0 stays out of range
+    }
+    __device__ __forceinline__ void load(int i, float (&r)[NE]) const
+    {
+        const uint32_t step = EB * (uint32_t)(CP * p->Ht * p->Wt);  // scalar: 16 channels further
+        r[i] = Elem<E>::load(rsrc, vo_, step * (uint32_t)i);
+    }
+    __device__ __forceinline__ void store(float *lds, int i, const float (&r)[NE]) const
+    {
+        lds[kl * LD + c0 + CP * i] = r[i];
+    }
+};
+
 // Dense matrix contiguous along the tile dimension:  element (kk, j) = t[kk*ld + j], float4 loads.
 // Requires ld % 4 == 0 and a 16-byte aligned base; columns in [extent, ld) may hold anything.
 struct DenseParams {
@@ -488,7 +640,7 @@ struct DenseParams {
 };
 
 template <int TD>
-struct DenseNLane {
+struct DenseNLane : NoSetup {
     static const char *name() { return "DenseNLane"; }
     static constexpr int CQ = TD / 4;          // float4 columns per row
     static constexpr int RP = kThreads / CQ;   // rows per pass
@@ -533,7 +685,7 @@ struct DenseNLane {
 
 // Same matrix, any ld / alignment: scalar loads, one reduction row per pass.
 template <int TD, class E = float>
-struct DenseNLaneST {
+struct DenseNLaneST : NoSetup {
     static constexpr uint32_t EB = Elem<E>::kBytes;
     static std::string name() { return std::string("DenseNLaneS") + Elem<E>::tag(); }
     static constexpr int RP = kThreads / TD;
@@ -584,6 +736,8 @@ struct Loaders {
     template <int TD> using GatherNLaneBig = GatherNLaneT<TD, false, E>;
     template <int TD> using DyKLane = PixelKLane<TD, false, E>;
     template <int TD> using XKLane = PixelKLane<TD, true, E>;
+    template <int TD> using DyTab = PixelTabDy<TD, E>;
+    template <int TD> using XTab = PixelTabX<TD, E>;
     template <int TD> using DenseNLaneS = DenseNLaneST<TD, E>;
 };
 
@@ -673,10 +827,15 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(AParams pa, BParams pb, 
     const int k_begin = split * k_chunk;
     const int k_end = min(Kd, k_begin + k_chunk);
 
+    __shared__ typename ALoader::Shared sha;
+    __shared__ typename BLoader::Shared shb;
     ALoader la;
     BLoader lb;
     la.init(pa, m0, M);
     lb.init(pb, n0, N);
+    la.setup(sha, k_begin, k_end, lb);
+    lb.setup(shb, k_begin, k_end, la);
+    if constexpr (ALoader::kHasShared || BLoader::kHasShared) __syncthreads();
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
