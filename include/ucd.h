@@ -207,7 +207,8 @@ int ucd_conv_bwd_filter(const ucd_plan_t *plan, const void *x, const void *dy, v
 
 /* Runs a single algorithm on one micro-batch of b samples starting at the given pointers
  * (already offset), bypassing plans: the unit the benchmark step times.  `a`, `bsrc`, `out`
- * are (x, w, y) for FWD, (dy, w, dx) for BWD_DATA, (x, dy, dw) for BWD_FILTER. */
+ * are (x, w, y) for FWD, (dy, w, dx) for BWD_DATA, (x, dy, dw) for BWD_FILTER.  1 <= b <= layer->N
+ * (UCD_E_INVALID otherwise): the buffers are taken to hold at least b samples. */
 int ucd_run_micro(const ucd_layer_t *layer, int op, int algo, int b, const void *a,
                   const void *bsrc, void *out, float beta, void *ws, size_t ws_bytes,
                   void *stream);

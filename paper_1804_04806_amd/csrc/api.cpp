@@ -672,9 +672,9 @@ int ucd_run_micro(const ucd_layer_t *layer, int op, int algo, int b, const void 
                   float beta, void *ws, size_t ws_bytes, void *stream)
 {
     if (!layer || !a || !bsrc || !out) return UCD_E_NULLPTR;
-    if (!layer_ok(layer) || op < 0 || op >= UCD_N_OP || b < 1) return UCD_E_INVALID;
+    // the descriptor's N is the extent of the caller's buffers: a micro-batch cannot exceed it
+    if (!layer_ok(layer) || op < 0 || op >= UCD_N_OP || b < 1 || b > layer->N) return UCD_E_INVALID;
     ucd_layer_t L = *layer;
-    L.N = std::max(L.N, b);
     const size_t need = ws_size(&L, op, algo, b);
     if (need == UCD_WS_NA) return UCD_E_UNSUPPORTED;
     if (need > 0 && !ws) return UCD_E_NULLPTR;

@@ -36,6 +36,29 @@ hipError_t fill_zero(float *p, size_t n, hipStream_t s)
     return hipGetLastError();
 }
 
+// Workgroups that are resident at once: 256 CUs x 2 (registers and LDS of the 128-row tiles allow two
+// per CU).  A launch whose workgroup count is just above a multiple of this leaves the chip nearly
+// idle for its last round, so split counts are chosen to fill whole rounds.
+constexpr long kSlots = 512;
+
+static double round_fill(long blocks) { return (double)blocks / (double)((blocks + kSlots - 1) / kSlots * kSlots); }
+
+// Among split counts in [lo, hi], the one whose workgroup count fills its rounds best (ties: the
+// one nearest to `want`).
+static int best_fill(long tiles, long want, long lo, long hi)
+{
+    if (lo < 1) lo = 1;
+    if (hi < lo) hi = lo;
+    long best = want < lo ? lo : (want > hi ? hi : want);
+    double best_f = round_fill(tiles * best);
+    for (long c = lo; c <= hi; ++c) {
+        const double f = round_fill(tiles * c);
+        const long dc = c > want ? c - want : want - c, db = best > want ? best - want : want - best;
+        if (f > best_f + 1e-9 || (f > best_f - 1e-9 && dc < db)) { best = c; best_f = f; }
+    }
+    return (int)best;
+}
+
 // Forward / BackwardData write each output once, so normally one workgroup owns a whole
 // reduction.  When the output has too few tiles to give every CU several workgroups (deep
 // layers: many channels, few pixels), the reduction is split as well and the partial results meet
@@ -48,7 +71,8 @@ static int output_splits(int M, int N, int Kd, bool fp32_out)
     long want = (1536 + tiles - 1) / tiles;
     const long cap = Kd / 1024;
     if (want > cap) want = cap;
-    return want < 2 ? 1 : (int)want;
+    if (want < 2) return 1;
+    return best_fill(tiles, want, want / 2 < 2 ? 2 : want / 2, want * 2 < cap ? want * 2 : cap);
 }
 
 template <class E>
@@ -177,7 +201,8 @@ int filter_splits(int M, int N, int Kd)
     if (cap < 1) cap = 1;
     if (want > cap) want = cap;
     if (want < 1) want = 1;
-    return (int)want;
+    if (tiles >= 4 * kSlots) return (int)want;  // many rounds anyway
+    return best_fill(tiles, want, (want + 1) / 2, want * 2 < cap ? want * 2 : cap);
 }
 
 template <class E>
@@ -204,12 +229,8 @@ static hipError_t implicit_bwd_filter_t(const Dims &d, int b, const void *x, con
     pb.shift = d.ph * d.W + d.pw;
     pb.n_tap_h = d.R; pb.n_tap_w = d.S;
     EpiDenseParams pe{dw, d.crs()};
-    if (d.R * d.S <= 31) {
-        // per-row state in an LDS table: the reduction chunk of a workgroup must fit it
-        const int need = (g.Kd + kTabRows - 1) / kTabRows;
-        if (g.splits < need) g.splits = need;
+    if (d.R * d.S <= 31)  // per-row state in an LDS table
         return launch_gemm<L::template DyTab, L::template XTab, EpiAtomic, true>(pa, pb, pe, g, s);
-    }
     return launch_gemm<L::template DyKLane, L::template XKLane, EpiAtomic, true>(pa, pb, pe, g, s);
 }
 

@@ -490,11 +490,11 @@ struct PixelKLane : NoSetup {
 template <int TD> using DyKLane = PixelKLane<TD, false>;
 template <int TD> using XKLane = PixelKLane<TD, true>;
 
-// BackwardFilter's operands again, for filters of at most 31 taps and reduction chunks of at most
-// kTabRows rows: everything that depends on the reduction row alone (the pixel decode, the address
+// BackwardFilter's operands again, for filters of at most 31 taps: everything that depends on
+// the reduction row alone (the pixel decode, the address
 // part of both tensors, and which taps of the window fall outside the image) is computed once per
-// workgroup into an LDS table, one entry per row of the chunk, instead of once per step per
-// thread.  Per step a thread then reads its entry (two LDS reads for x, one for dy) and spends three
+// workgroup into an LDS table, one entry per row for kTabRows rows at a time (the main loop has
+// it refilled when they are used up), instead of once per step per thread.  Per step a thread then reads its entry (two LDS reads for x, one for dy) and spends three
 // vector instructions per x element (mask shift, address add, merge) and none per dy element.
 constexpr int kTabRows = 2048;
 constexpr int kTabCap = kTabRows + 2 * kBK;  // the pipeline looks two steps past the chunk's end
@@ -548,8 +548,9 @@ struct PixelTabX {
             }
         }
     }
-    // Fills the table for rows [k_begin, k_begin + kTabCap): the peer is the dy loader of the same
-    // GEMM (its parameters give dy's strides).
+    // Fills the table for rows [k_begin, k_begin + kTabCap), k_begin being the start of the chunk
+    // or of a later refill: the peer is the dy loader of the same GEMM (its parameters give dy's
+    // strides).
     template <class Peer>
     __device__ __forceinline__ void setup(PixelTable &sh, int k_begin, int k_end, const Peer &peer)
     {
@@ -881,6 +882,16 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(AParams pa, BParams pb, 
 
     int buf = 0;
     for (int k0 = k_begin; k0 < k_end; k0 += kBK) {
+        if constexpr (ALoader::kHasShared || BLoader::kHasShared) {
+            // LDS tables hold kTabRows reduction rows (plus the two tiles of lookahead, already
+            // fetched from the old contents): refill them at every multiple of that
+            if (k0 != k_begin && ((k0 - k_begin) & (kTabRows - 1)) == 0) {
+                __syncthreads();
+                la.setup(sha, k0, k_end, lb);
+                lb.setup(shb, k0, k_end, la);
+                __syncthreads();
+            }
+        }
         la.prep(k0 + 2 * kBK, k_end, lb);
         lb.prep(k0 + 2 * kBK, k_end, la);
         const float *As = lds[buf];

@@ -24,9 +24,6 @@ hipError_t launch_tile(const AP &pa, const BP &pb, const typename Epi::Params &p
     int k_chunk = ((g.Kd + splits - 1) / splits + kBK - 1) / kBK * kBK;
     if (k_chunk < kBK) k_chunk = kBK;
     splits = g.Kd > 0 ? (g.Kd + k_chunk - 1) / k_chunk : 1;
-    if constexpr (AL<T::BM>::kHasShared || BL<T::BN>::kHasShared) {
-        if (k_chunk > kTabRows) return hipErrorInvalidValue;  // the per-row LDS table holds one chunk
-    }
     dim3 grid((unsigned)(tiles_m * tiles_n), (unsigned)splits, (unsigned)g.batch);
     if (LaunchLog *log = launch_log()) {
         log->add(std::string("gemm_kernel<Tile<") + std::to_string(T::BM) + "x" + std::to_string(T::BN) + ">," +

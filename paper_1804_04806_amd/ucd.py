@@ -129,7 +129,7 @@ def layer(shape=None, dtype=0, **kw):
     if shape is not None:
         return LayerDesc(shape.N, shape.C, shape.H, shape.W, shape.K, shape.R, shape.S,
                          shape.stride, shape.stride, shape.pad, shape.pad, dtype)
-    d = dict(stride_h=1, stride_w=1, pad_h=0, pad_w=0, dtype=0)
+    d = dict(stride_h=1, stride_w=1, pad_h=0, pad_w=0, dtype=dtype)
     d.update(kw)
     return LayerDesc(**d)
 

@@ -75,3 +75,20 @@ def test_execution_rejects_bad_calls_before_any_launch():
     t = [[ucd.TIME_INF, 5, 9]]
     pt = ucd.ucd_plan_from_table(2, 0, ucd.POLICY_ALL, t, [[ucd.WS_NA, 0, 0]])
     assert lib.ucd_conv_fwd(pt.handle, 4096, 4096, 4096, None, 0, None) == ucd.E_INVALID
+
+
+def test_run_micro_rejects_a_micro_batch_beyond_the_descriptor():
+    """The descriptor's N is the extent of the caller's buffers: b > N (or b < 1) is an error
+    before anything is launched, and so is a bf16 tensor pointer that is not 2-byte aligned."""
+    import ctypes as C
+    L = ucd.layer(N=8, C=16, H=16, W=16, K=32, R=3, S=3, pad_h=1, pad_w=1)
+    lib = ucd.lib()
+    for b in (0, 9, 1 << 20):
+        assert lib.ucd_run_micro(C.byref(L), ucd.FWD, ucd.ALGO_IMPLICIT, b, 4096, 4096, 4096, 0.0,
+                                 None, 0, None) == ucd.E_INVALID
+    Lh = ucd.layer(N=8, C=16, H=16, W=16, K=32, R=3, S=3, pad_h=1, pad_w=1, dtype=1)
+    assert lib.ucd_run_micro(C.byref(Lh), ucd.FWD, ucd.ALGO_IMPLICIT, 8, 4097, 4096, 4096, 0.0,
+                             None, 0, None) == ucd.E_INVALID
+    Lbad = ucd.layer(N=8, C=16, H=16, W=16, K=32, R=3, S=3, pad_h=1, pad_w=1, dtype=2)
+    assert lib.ucd_run_micro(C.byref(Lbad), ucd.FWD, ucd.ALGO_IMPLICIT, 8, 4096, 4096, 4096, 0.0,
+                             None, 0, None) == ucd.E_INVALID

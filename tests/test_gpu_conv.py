@@ -83,3 +83,29 @@ def test_unreached_pixels_are_written_as_zero():
     got = run_hip(s, ucd.BWD_DATA, [(ucd.ALGO_IMPLICIT, 2)], w=w, dy=dy)
     assert np.all(got[:, :, 1::2, :] == 0) and np.all(got[:, :, :, 1::2] == 0)
     assert rel_l2(got, run_oracle(s, ucd.BWD_DATA, w=w, dy=dy)) <= 1e-5
+
+
+def test_bwd_filter_chunks_longer_than_the_row_table():
+    """BackwardFilter keeps per-reduction-row state in an LDS table of 2048 rows that is refilled
+    inside the main loop: a layer whose workgroups each reduce more rows than that, checked on
+    sampled dw elements (each with its full exact reduction)."""
+    import torch
+    from oracle import conv as oc
+    from paper_1804_04806_amd import synth
+    from hip_helpers import oracle_layer
+    s = Shape(24, 512, 32, 32, 512, 3, 3, 1, 1, "long-chunks")
+    desc = ucd.layer(s)
+    text, _ = ucd.ucd_describe_micro(desc, ucd.BWD_FILTER, ucd.ALGO_IMPLICIT, s.N)
+    splits = int(text.split("splits=")[1].split()[0])
+    assert "PixelTab" in text and s.N * s.P * s.Q / splits > 2048, text
+    x, dy = synth.make_x(s, 2), synth.make_dy(s, 2)
+    dev = torch.device("cuda:0")
+    xd, dyd = torch.from_numpy(x).to(dev), torch.from_numpy(dy).to(dev)
+    dw = torch.full(s.w_shape, float("nan"), dtype=torch.float32, device=dev)
+    ucd.ucd_run_micro(desc, ucd.BWD_FILTER, ucd.ALGO_IMPLICIT, s.N, xd, dyd, dw, 0.0)
+    torch.cuda.synchronize()
+    got = dw.cpu().numpy()
+    assert np.isfinite(got).all()
+    idx = synth.sample_indices(got.size, 400, seed=9)
+    ref = oc.conv_bwd_filter_at(oracle_layer(s), x.astype(np.float64), dy.astype(np.float64), idx)
+    assert rel_l2(got.ravel()[idx], ref) <= 1e-5
