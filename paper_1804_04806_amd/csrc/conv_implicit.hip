@@ -36,23 +36,29 @@ hipError_t fill_zero(float *p, size_t n, hipStream_t s)
     return hipGetLastError();
 }
 
-// Workgroups that are resident at once: 256 CUs x 2 (registers and LDS of the 128-row tiles allow two
-// per CU).  A launch whose workgroup count is just above a multiple of this leaves the chip nearly
-// idle for its last round, so split counts are chosen to fill whole rounds.
-constexpr long kSlots = 512;
+// A CU holds several of these workgroups at once (four of the Forward / BackwardData kernels,
+// three of the BackwardFilter ones, by registers and LDS) and needs them all to keep its matrix
+// pipes busy; workgroups of one launch take equally long, so a launch proceeds in rounds of
+// 256 x resident workgroups, and a last round that is nearly empty costs as much as a full one
+// (measured: the time of a Forward launch is flat from 769 to 1024 tiles).  Split counts are
+// chosen so that the workgroup count fills its rounds.
+constexpr long kSlotsOutput = 256 * 4, kSlotsFilter = 256 * 3;
 
-static double round_fill(long blocks) { return (double)blocks / (double)((blocks + kSlots - 1) / kSlots * kSlots); }
+static double round_fill(long blocks, long slots)
+{
+    return (double)blocks / (double)((blocks + slots - 1) / slots * slots);
+}
 
 // Among split counts in [lo, hi], the one whose workgroup count fills its rounds best (ties: the
 // one nearest to `want`).
-static int best_fill(long tiles, long want, long lo, long hi)
+static int best_fill(long tiles, long want, long lo, long hi, long slots)
 {
     if (lo < 1) lo = 1;
     if (hi < lo) hi = lo;
     long best = want < lo ? lo : (want > hi ? hi : want);
-    double best_f = round_fill(tiles * best);
+    double best_f = round_fill(tiles * best, slots);
     for (long c = lo; c <= hi; ++c) {
-        const double f = round_fill(tiles * c);
+        const double f = round_fill(tiles * c, slots);
         const long dc = c > want ? c - want : want - c, db = best > want ? best - want : want - best;
         if (f > best_f + 1e-9 || (f > best_f - 1e-9 && dc < db)) { best = c; best_f = f; }
     }
@@ -72,7 +78,7 @@ static int output_splits(int M, int N, int Kd, bool fp32_out)
     const long cap = Kd / 1024;
     if (want > cap) want = cap;
     if (want < 2) return 1;
-    return best_fill(tiles, want, want / 2 < 2 ? 2 : want / 2, want * 2 < cap ? want * 2 : cap);
+    return best_fill(tiles, want, want / 2 < 2 ? 2 : want / 2, want * 2 < cap ? want * 2 : cap, kSlotsOutput);
 }
 
 template <class E>
@@ -201,8 +207,8 @@ int filter_splits(int M, int N, int Kd)
     if (cap < 1) cap = 1;
     if (want > cap) want = cap;
     if (want < 1) want = 1;
-    if (tiles >= 4 * kSlots) return (int)want;  // many rounds anyway
-    return best_fill(tiles, want, (want + 1) / 2, want * 2 < cap ? want * 2 : cap);
+    if (tiles >= 4 * kSlotsFilter) return (int)want;  // many rounds anyway
+    return best_fill(tiles, want, (want + 1) / 2, want * 2 < cap ? want * 2 : cap, kSlotsFilter);
 }
 
 template <class E>

@@ -496,7 +496,7 @@ template <int TD> using XKLane = PixelKLane<TD, true>;
 // workgroup into an LDS table, one entry per row for kTabRows rows at a time (the main loop has
 // it refilled when they are used up), instead of once per step per thread.  Per step a thread then reads its entry (two LDS reads for x, one for dy) and spends three
 // vector instructions per x element (mask shift, address add, merge) and none per dy element.
-constexpr int kTabRows = 2048;
+constexpr int kTabRows = 1024;
 constexpr int kTabCap = kTabRows + 2 * kBK;  // the pipeline looks two steps past the chunk's end
 
 struct PixelTable {
@@ -557,6 +557,7 @@ struct PixelTabX {
         tab = &sh;
         k_begin_ = k_begin;
         const KLaneParams &q = *peer.p;
+#pragma unroll 1
         for (int e = threadIdx.x; e < kTabCap; e += kThreads) {
             const int kk = k_begin + e;
             uint32_t n, rest, a, b;
@@ -564,8 +565,10 @@ struct PixelTabX {
             p->grid_w.divmod(rest, a, b);
             const int hb = (int)a * p->mul_h + p->add_h, wb = (int)b * p->mul_w + p->add_w;
             uint32_t okw = 0, ok = 0;
+#pragma unroll 1
             for (int s = 0; s < p->n_tap_w; ++s)
                 if ((unsigned)(wb + s) < (unsigned)p->Wt) okw |= 1u << s;
+#pragma unroll 1
             for (int r = 0; r < p->n_tap_h; ++r)
                 if ((unsigned)(hb + r) < (unsigned)p->Ht) ok |= okw << (r * p->n_tap_w);
             const bool live = kk < k_end;

@@ -86,7 +86,7 @@ def test_unreached_pixels_are_written_as_zero():
 
 
 def test_bwd_filter_chunks_longer_than_the_row_table():
-    """BackwardFilter keeps per-reduction-row state in an LDS table of 2048 rows that is refilled
+    """BackwardFilter keeps per-reduction-row state in an LDS table of 1024 rows that is refilled
     inside the main loop: a layer whose workgroups each reduce more rows than that, checked on
     sampled dw elements (each with its full exact reduction)."""
     import torch
@@ -97,7 +97,7 @@ def test_bwd_filter_chunks_longer_than_the_row_table():
     desc = ucd.layer(s)
     text, _ = ucd.ucd_describe_micro(desc, ucd.BWD_FILTER, ucd.ALGO_IMPLICIT, s.N)
     splits = int(text.split("splits=")[1].split()[0])
-    assert "PixelTab" in text and s.N * s.P * s.Q / splits > 2048, text
+    assert "PixelTab" in text and s.N * s.P * s.Q / splits > 1024, text   # the table holds 1024 rows
     x, dy = synth.make_x(s, 2), synth.make_dy(s, 2)
     dev = torch.device("cuda:0")
     xd, dyd = torch.from_numpy(x).to(dev), torch.from_numpy(dy).to(dev)
