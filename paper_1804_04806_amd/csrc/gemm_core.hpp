@@ -906,7 +906,7 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(AParams pa, BParams pb, 
 #pragma unroll
         for (int i = 0; i < T::WM; ++i) a[0][i] = As[lhi * T::LDA + wm0 + T::WM * l32 + i];
 #pragma unroll
-        for (int j = 0; j < T::WN; ++j) b[0][j] = Bs[lhi * T::LDB + wn0 + T::WN * l32 + j];
+        for (int j = 0; j < T::WN; ++j) b[0][j] = Bs[lhi * T::LDB + wn0 + j * 32 + l32];
         __builtin_amdgcn_sched_barrier(0);
         __builtin_amdgcn_s_setprio(UCD_MFMA_PRIO);  // a wave inside its MFMA run keeps the pipe
 #pragma unroll
@@ -923,7 +923,7 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(AParams pa, BParams pb, 
 #pragma unroll
                     for (int i = 0; i < T::WM; ++i) a[nxt][i] = As[(kk + 2 + lhi) * T::LDA + wm0 + T::WM * l32 + i];
 #pragma unroll
-                    for (int j = 0; j < T::WN; ++j) b[nxt][j] = Bs[(kk + 2 + lhi) * T::LDB + wn0 + T::WN * l32 + j];
+                    for (int j = 0; j < T::WN; ++j) b[nxt][j] = Bs[(kk + 2 + lhi) * T::LDB + wn0 + j * 32 + l32];
                 }
                 if (m == 1 % NM) {
 #pragma unroll
@@ -950,13 +950,15 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(AParams pa, BParams pb, 
     }
 
     // accumulator element v of a 32x32 MFMA tile: row 8*(v/4) + 4*(lane/32) + v%4, column lane%32.
-    // A wave's WM x WN MFMA tiles are interleaved: MFMA row r of tile i is wave row WM*r + i (and
-    // likewise for columns), so that a lane's operands of one k-row are adjacent in LDS and come
-    // in one read with an immediate offset.
+    // A wave's WM MFMA tiles along M are interleaved: MFMA row r of tile i is wave row WM*r + i, so
+    // that a lane's A operands of one k-row are adjacent in LDS and come in one read with an
+    // immediate offset.  Columns are not interleaved: consecutive lanes must keep consecutive
+    // output columns, or every store would touch only every other element of a cache line (that
+    // cost the bandwidth-bound 1x1 layers a quarter of their speed).
     Epi epi;
 #pragma unroll
     for (int j = 0; j < T::WN; ++j) {
-        const int col = n0 + wn0 + T::WN * l32 + j;
+        const int col = n0 + wn0 + j * 32 + l32;
         if (col >= N) continue;
         epi.prep(pe, col);
 #pragma unroll
