@@ -182,11 +182,11 @@ def kernel_class(ucd, desc, op, algo, b):
     text, n = ucd.ucd_describe_micro(desc, op, algo, b)
     parts = [p.strip() for p in text.split(";")]
     gemms = [p for p in parts if p.startswith("gemm_kernel<")]
-    others = [p for p in parts if not p.startswith("gemm_kernel<") and p != "fill_zero_kernel"]
+    others = [p for p in parts if not p.startswith("gemm_kernel<") and p not in ("fill_zero_kernel", "zero_tiles_kernel")]
     if len(gemms) != 1 or others:
         return None
     name = gemms[0].split("> tiles=")[0] + ">"
-    return name + (" (after fill_zero_kernel)" if len(parts) > 1 else "")
+    return name + (" (after " + parts[0] + ")" if len(parts) > 1 else "")
 
 
 def dominant_kernel_roofline(torch, ucd, states, plans, ws, reps, traffic_table=None):

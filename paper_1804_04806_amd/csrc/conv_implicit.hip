@@ -68,14 +68,14 @@ static int best_fill(long tiles, long want, long lo, long hi, long slots)
 // Forward / BackwardData write each output once, so normally one workgroup owns a whole
 // reduction.  When the output has too few tiles to give every CU several workgroups (deep
 // layers: many channels, few pixels), the reduction is split as well and the partial results meet
-// through atomics in a zero-filled output.  Chunks keep at least 1024 reduction rows.
+// through atomics in a zero-filled output.  Chunks keep at least 512 reduction rows.
 static int output_splits(int M, int N, int Kd, bool fp32_out)
 {
     if (!fp32_out) return 1;  // bf16 outputs cannot be accumulated with atomics
     const long tiles = pick_tile(M, N, true, 1 << 20).blocks(M, N, 1);  // tiles at the default shape
     if (tiles >= 768) return 1;  // three workgroups per CU already
     long want = (1536 + tiles - 1) / tiles;
-    const long cap = Kd / 1024;
+    const long cap = Kd / 512;
     if (want > cap) want = cap;
     if (want < 2) return 1;
     return best_fill(tiles, want, want / 2 < 2 ? 2 : want / 2, want * 2 < cap ? want * 2 : cap, kSlotsOutput);
@@ -108,6 +108,7 @@ static hipError_t implicit_fwd_t(const Dims &d, int b, const void *x, const void
             return launch_gemm<KLane0, GatherNLaneBig, EpiNCHWAtomic, true>(pa, pb, pe, g, s);
         }
     }
+    g.tail_split = true;
     if (d.R * d.S <= 31)
         return launch_gemm<L::template KLane0, L::template GatherNLane, EpiNCHWT<E>, true>(pa, pb, pe, g, s);
     return launch_gemm<L::template KLane0, L::template GatherNLaneBig, EpiNCHWT<E>, true>(pa, pb, pe, g, s);
@@ -183,6 +184,7 @@ static hipError_t implicit_bwd_data_t(const Dims &d, int b, const void *dy, cons
                     done = true;
                 }
             }
+            g.tail_split = true;
             if (!done)
                 e = Ra * Sc <= 31
                         ? launch_gemm<L::template FilterKLane, L::template GatherNLane, EpiNCHWT<E>, true>(pa, pb, pe, g, s)

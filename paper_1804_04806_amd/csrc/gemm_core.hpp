@@ -17,6 +17,7 @@
 #include <stdint.h>
 
 #include <string>
+#include <type_traits>
 
 namespace ucd {
 
@@ -69,19 +70,31 @@ struct Tile {
 // work items ordered split-major, then tile column, then tile row.  Tiles that re-read the same
 // B (activation) columns, and all tiles of one reduction chunk (which re-read the same slices of
 // both operands), therefore share an L2 instead of pulling the data into all eight.
+__device__ __forceinline__ uint32_t xcd_order(uint32_t id, uint32_t total)
+{
+    const uint32_t xcd = id & 7u, slot = id >> 3;
+    const uint32_t q = total >> 3, rem = total & 7u;
+    return xcd * q + (xcd < rem ? xcd : rem) + slot;
+}
 __device__ __forceinline__ void xcd_tile(int tiles_m, int tiles_n, int &tile_m, int &tile_n, int &split)
 {
     const uint32_t tiles = (uint32_t)tiles_m * (uint32_t)tiles_n;
-    const uint32_t total = tiles * gridDim.y;
-    const uint32_t id = blockIdx.x + gridDim.x * blockIdx.y;
-    const uint32_t xcd = id & 7u, slot = id >> 3;
-    const uint32_t q = total >> 3, rem = total & 7u;
-    const uint32_t v = xcd * q + (xcd < rem ? xcd : rem) + slot;
+    const uint32_t v = xcd_order(blockIdx.x + gridDim.x * blockIdx.y, tiles * gridDim.y);
     split = (int)(v / tiles);
     const uint32_t t = v - (uint32_t)split * tiles;
     tile_m = (int)(t % (uint32_t)tiles_m);
     tile_n = (int)(t / (uint32_t)tiles_m);
 }
+
+// Tail splitting.  A launch takes as long as the busiest CU, so a tile count a little above a
+// multiple of the CU count costs almost a whole extra round of workgroups.  With `tiles` > 0 the
+// last `tiles` tiles (in tile order) are each computed by `splits` workgroups, one per reduction
+// chunk of `chunk` rows, which add their partial results into a zero-filled output with atomics;
+// all other tiles are computed by one workgroup each as usual.  grid.x = (all tiles - tiles) +
+// tiles * splits, grid.y = 1.
+struct TailSplit {
+    int tiles, splits, chunk;
+};
 
 // Loaders may keep per-workgroup state in LDS (`Shared`, filled by `setup` before the main loop,
 // one barrier later everybody may read it); most have none.
@@ -772,11 +785,18 @@ struct EpiNCHWT {
     {
         Elem<E>::store(p.out, off + m * p.HWo, v);
     }
+    // accumulate instead of store (tail splitting; fp32 outputs only)
+    static constexpr bool kCanAdd = std::is_same<E, float>::value;
+    __device__ __forceinline__ void add(const Params &p, int m, float v) const
+    {
+        unsafeAtomicAdd((float *)p.out + off + m * p.HWo, v);
+    }
 };
 typedef EpiNCHWT<float> EpiNCHW;
 // The same scatter as an fp32 atomic add into a zero-filled tensor, for GEMMs whose reduction is
 // split over several workgroups because the output has too few tiles to fill the chip.
 struct EpiNCHWAtomic : EpiNCHW {
+    static constexpr bool kCanAdd = false;
     static const char *name() { return "EpiNCHWAtomic"; }
     __device__ __forceinline__ void store(const Params &p, int m, float v) const
     {
@@ -790,6 +810,7 @@ struct EpiDenseParams {
     int ld;
 };
 struct EpiDense {
+    static constexpr bool kCanAdd = false;
     static const char *name() { return "EpiDense"; }
     typedef EpiDenseParams Params;
     int j_;
@@ -799,6 +820,7 @@ struct EpiDense {
 
 // Dense row-major accumulate with hardware fp32 atomics (split-K partial sums of BackwardFilter).
 struct EpiAtomic {
+    static constexpr bool kCanAdd = false;
     static const char *name() { return "EpiAtomic"; }
     typedef EpiDenseParams Params;
     int j_;
@@ -816,7 +838,8 @@ struct EpiAtomic {
 template <class T, class ALoader, class BLoader, class Epi, class AParams, class BParams>
 __global__ __launch_bounds__(kThreads) void gemm_kernel(AParams pa, BParams pb, typename Epi::Params pe,
                                                          int M, int N, int Kd, int k_chunk, int tiles_m,
-                                                         int tiles_n, long a_batch, long b_batch, long c_batch)
+                                                         int tiles_n, long a_batch, long b_batch, long c_batch,
+                                                         TailSplit tail)
 {
     __shared__ __attribute__((aligned(16))) float lds[2][T::LDS_FLOATS];
 
@@ -826,7 +849,25 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(AParams pa, BParams pb, 
         pe.out = (float *)pe.out + c_batch * blockIdx.z;
     }
     int tile_m, tile_n, split;
-    xcd_tile(tiles_m, tiles_n, tile_m, tile_n, split);
+    bool accumulate = false;  // this workgroup adds a partial result (a chunk of a tail tile)
+    if (Epi::kCanAdd && tail.tiles > 0) {
+        const int whole = tiles_m * tiles_n - tail.tiles;
+        int t;
+        if ((int)blockIdx.x < whole) {
+            t = (int)xcd_order(blockIdx.x, (uint32_t)whole);
+            split = 0;
+        } else {
+            const int r = (int)blockIdx.x - whole;
+            t = whole + r / tail.splits;
+            split = r % tail.splits;
+            k_chunk = tail.chunk;
+            accumulate = true;
+        }
+        tile_m = t % tiles_m;
+        tile_n = t / tiles_m;
+    } else {
+        xcd_tile(tiles_m, tiles_n, tile_m, tile_n, split);
+    }
     const int m0 = tile_m * T::BM, n0 = tile_n * T::BN;
     const int k_begin = split * k_chunk;
     const int k_end = min(Kd, k_begin + k_chunk);
@@ -966,8 +1007,33 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(AParams pa, BParams pb, 
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int row = m0 + wm0 + T::WM * (8 * (v / 4) + 4 * lhi + (v % 4)) + i;
-                if (row < M) epi.store(pe, row, acc[i][j][v]);
+                if (row < M) {
+                    if constexpr (Epi::kCanAdd) {
+                        if (accumulate) epi.add(pe, row, acc[i][j][v]);
+                        else epi.store(pe, row, acc[i][j][v]);
+                    } else {
+                        epi.store(pe, row, acc[i][j][v]);
+                    }
+                }
             }
+    }
+}
+
+// Zero-fills the outputs of the last `tail_tiles` tiles through the epilogue's own index mapping.
+template <class T, class Epi>
+__global__ __launch_bounds__(kThreads) void zero_tiles_kernel(typename Epi::Params pe, int M, int N, int tiles_m,
+                                                              int tiles_n, int tail_tiles)
+{
+    const int t = tiles_m * tiles_n - tail_tiles + (int)blockIdx.x;
+    const int m0 = (t % tiles_m) * T::BM, n0 = (t / tiles_m) * T::BN;
+    static_assert(kThreads % T::BN == 0, "a row of the tile per thread group");
+    const int col = n0 + (int)threadIdx.x % T::BN;  // lanes along the columns: contiguous stores
+    if (col >= N) return;
+    Epi epi;
+    epi.prep(pe, col);
+    for (int r = threadIdx.x / T::BN; r < T::BM; r += kThreads / T::BN) {
+        const int row = m0 + r;
+        if (row < M) epi.store(pe, row, 0.f);
     }
 }
 

@@ -12,7 +12,11 @@ struct GemmShape {
     int splits = 1;   // reduction splits (epilogue must accumulate when > 1)
     int batch = 1;    // independent GEMMs, operands advanced by the strides below
     long a_batch = 0, b_batch = 0, c_batch = 0;
+    bool tail_split = false;  // the epilogue may split the tiles of a nearly empty last round
 };
+
+constexpr int kCUs = 256;          // compute units of the MI355X
+constexpr int kTailMinRows = 128;  // shortest reduction chunk of a split tail tile
 
 template <class T, template <int> class AL, template <int> class BL, class Epi, class AP, class BP>
 hipError_t launch_tile(const AP &pa, const BP &pb, const typename Epi::Params &pe, const GemmShape &g,
@@ -24,16 +28,43 @@ hipError_t launch_tile(const AP &pa, const BP &pb, const typename Epi::Params &p
     int k_chunk = ((g.Kd + splits - 1) / splits + kBK - 1) / kBK * kBK;
     if (k_chunk < kBK) k_chunk = kBK;
     splits = g.Kd > 0 ? (g.Kd + k_chunk - 1) / k_chunk : 1;
-    dim3 grid((unsigned)(tiles_m * tiles_n), (unsigned)splits, (unsigned)g.batch);
+    // Tail splitting (see TailSplit): when an unsplit GEMM has a few tiles more than a multiple of
+    // the CU count, those few are split along the reduction so that every CU gets the same work.
+    TailSplit tail{0, 1, 0};
+    if constexpr (Epi::kCanAdd) {
+        const long tiles = (long)tiles_m * tiles_n;
+        const int over = (int)(tiles % kCUs);
+        if (g.tail_split && splits == 1 && g.batch == 1 && tiles >= 3 * kCUs && over > 0 && over <= kCUs / 2 &&
+            g.Kd >= 2 * kTailMinRows) {
+            int f = kCUs / over;
+            if (f > g.Kd / kTailMinRows) f = g.Kd / kTailMinRows;
+            if (f > 16) f = 16;
+            if (f >= 2) {
+                tail.tiles = over;
+                tail.splits = f;
+                tail.chunk = ((g.Kd + f - 1) / f + kBK - 1) / kBK * kBK;
+                tail.splits = (g.Kd + tail.chunk - 1) / tail.chunk;
+            }
+        }
+    }
+    const unsigned gx = (unsigned)(tiles_m * tiles_n - tail.tiles + tail.tiles * tail.splits);
+    dim3 grid(gx, (unsigned)splits, (unsigned)g.batch);
     if (LaunchLog *log = launch_log()) {
+        if (tail.tiles) log->add("zero_tiles_kernel");
         log->add(std::string("gemm_kernel<Tile<") + std::to_string(T::BM) + "x" + std::to_string(T::BN) + ">," +
                  AL<T::BM>::name() + "," + BL<T::BN>::name() + "," + Epi::name() + "> tiles=" +
                  std::to_string(tiles_m * tiles_n) + " splits=" + std::to_string(splits) + " batch=" +
-                 std::to_string(g.batch));
+                 std::to_string(g.batch) +
+                 (tail.tiles ? " tail=" + std::to_string(tail.tiles) + "x" + std::to_string(tail.splits) : std::string()));
         return hipSuccess;
     }
+    if (tail.tiles) {
+        zero_tiles_kernel<T, Epi><<<(unsigned)tail.tiles, kThreads, 0, s>>>(pe, g.M, g.N, tiles_m, tiles_n, tail.tiles);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
     gemm_kernel<T, AL<T::BM>, BL<T::BN>, Epi, AP, BP><<<grid, kThreads, 0, s>>>(
-        pa, pb, pe, g.M, g.N, g.Kd, k_chunk, tiles_m, tiles_n, g.a_batch, g.b_batch, g.c_batch);
+        pa, pb, pe, g.M, g.N, g.Kd, k_chunk, tiles_m, tiles_n, g.a_batch, g.b_batch, g.c_batch, tail);
     return hipGetLastError();
 }
 

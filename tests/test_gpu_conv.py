@@ -109,3 +109,18 @@ def test_bwd_filter_chunks_longer_than_the_row_table():
     idx = synth.sample_indices(got.size, 400, seed=9)
     ref = oc.conv_bwd_filter_at(oracle_layer(s), x.astype(np.float64), dy.astype(np.float64), idx)
     assert rel_l2(got.ravel()[idx], ref) <= 1e-5
+
+
+def test_tail_tiles_split_along_the_reduction():
+    """A GEMM with a few tiles more than a multiple of the CU count computes those few tiles in
+    several workgroups that accumulate into a zero-filled output: 784 column tiles here, for
+    Forward (one row of tiles) and BackwardData, against the full oracle tensors."""
+    s = Shape(8, 32, 112, 112, 128, 3, 3, 1, 1, "tail-split")
+    desc = ucd.layer(s)
+    x, w, dy = inputs(s, seed=13)
+    for op in (ucd.FWD, ucd.BWD_DATA):
+        text, _ = ucd.ucd_describe_micro(desc, op, ucd.ALGO_IMPLICIT, s.N)
+        assert "zero_tiles_kernel" in text and "tail=16x" in text, text
+        got = run_hip(s, op, [(ucd.ALGO_IMPLICIT, s.N)], x=x, w=w, dy=dy)
+        assert np.isfinite(got).all()
+        assert rel_l2(got, run_oracle(s, op, x=x, w=w, dy=dy)) <= 1e-5
