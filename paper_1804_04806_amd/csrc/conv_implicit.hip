@@ -203,14 +203,17 @@ hipError_t implicit_bwd_data(const Dims &d, int b, const void *dy, const void *w
 // chunks of at least 256 reduction rows.
 int filter_splits(int M, int N, int Kd)
 {
-    const long tiles = pick_tile(M, N, true, 1 << 20).blocks(M, N, 1);  // tiles at the default shape
+    const TilePick shape = pick_tile(M, N, true, 1 << 20);  // the default shape
+    const long tiles = shape.blocks(M, N, 1);
     long want = (1024 + tiles - 1) / tiles;
     long cap = Kd / 256;
     if (cap < 1) cap = 1;
     if (want > cap) want = cap;
     if (want < 1) want = 1;
-    if (tiles >= 4 * kSlotsFilter) return (int)want;  // many rounds anyway
-    return best_fill(tiles, want, (want + 1) / 2, want * 2 < cap ? want * 2 : cap, kSlotsFilter);
+    // three workgroups of the 96- and 128-row BackwardFilter kernels fit a CU, four of the others
+    const long slots = shape.bm >= 96 ? kSlotsFilter : kSlotsOutput;
+    if (tiles >= 4 * slots) return (int)want;  // many rounds anyway
+    return best_fill(tiles, want, (want + 1) / 2, want * 2 < cap ? want * 2 : cap, slots);
 }
 
 template <class E>

@@ -96,7 +96,10 @@ struct TilePick {
 };
 inline TilePick pick_tile(int M, int N, bool rows96, long mult)
 {
-    TilePick t{pick_rows(M, rows96), N <= 64 ? 64 : 128};
+    // 64 columns when that wastes enough fewer padded columns to pay for the narrower tile's
+    // lower MFMA-per-load ratio (N = 147: 192 columns instead of 256)
+    const long pad128 = (long)(N + 127) / 128 * 128, pad64 = (long)(N + 63) / 64 * 64;
+    TilePick t{pick_rows(M, rows96), (double)pad64 * 1.10 < (double)pad128 ? 64 : 128};
     if (t.bm == 32 || t.bm == 96) return t;  // single shapes
     if (t.blocks(M, N, mult) < 256 && t.bn == 128) t.bn = 64;
     if (t.blocks(M, N, mult) < 256 && t.bm == 128) t.bm = 64;
