@@ -1,9 +1,9 @@
 // LDS-staged fp32 MFMA tile GEMM for gfx950, with pluggable operand loaders and epilogues.
 //
 // C[M x N] (+)= A[M x Kd] * B[Kd x N].  One 256-thread workgroup (4 wavefronts of 64) owns a
-// BM x BN tile of C and walks Kd in steps of BK = 16.  Each step both operand tiles are fetched
-// from global memory into registers (overlapping the MFMAs of the previous step), written to
-// one of two LDS buffers laid out [BK][tile + pad] and consumed by v_mfma_f32_32x32x2_f32.
+// BM x BN tile of C and walks Kd in steps of BK = 16.  The operand tiles travel global memory ->
+// registers -> one of two LDS buffers laid out [BK][tile + pad] -> v_mfma_f32_32x32x2_f32, as a
+// software pipeline two tiles deep whose memory instructions are dealt out behind the MFMAs.
 //
 // How an operand element (row kk of the reduction, position m in the tile) maps to memory is
 // the loader's business: dense matrices, an im2col-style gather from an NCHW tensor, a filter
@@ -121,14 +121,6 @@ struct NoSetup {
 
 constexpr uint32_t kOob = 0x80000000u;
 
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const float *p, uint32_t bytes)
-{
-    return __builtin_amdgcn_make_buffer_rsrc((void *)p, 0, (int)bytes, 0x00020000);
-}
-__device__ __forceinline__ float buf_load(__amdgpu_buffer_rsrc_t r, uint32_t byte_off)
-{
-    return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, (int)byte_off, 0, 0));
-}
 __device__ __forceinline__ f32x4 buf_load4(__amdgpu_buffer_rsrc_t r, uint32_t byte_off)
 {
     typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
@@ -936,8 +928,6 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(AParams pa, BParams pb, 
                 __syncthreads();
             }
         }
-        la.prep(k0 + 2 * kBK, k_end, lb);
-        lb.prep(k0 + 2 * kBK, k_end, la);
         const float *As = lds[buf];
         const float *Bs = lds[buf] + kBK * T::LDA;
         float *An = lds[buf ^ 1];
@@ -960,6 +950,10 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(AParams pa, BParams pb, 
                 const int mi = m / T::WN, mj = m % T::WN;
                 acc[mi][mj] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[cur][mi], b[cur][mj], acc[mi][mj], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
+                if (m == 0 && kk == 0) {  // per-step loader state, needed by the loads further down
+                    la.prep(k0 + 2 * kBK, k_end, lb);
+                    lb.prep(k0 + 2 * kBK, k_end, la);
+                }
                 if (m == 0 && kk + 2 < kBK) {
 #pragma unroll
                     for (int i = 0; i < T::WM; ++i) a[nxt][i] = As[(kk + 2 + lhi) * T::LDA + wm0 + T::WM * l32 + i];
