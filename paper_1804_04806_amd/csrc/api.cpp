@@ -90,7 +90,7 @@ int hip_status(hipError_t e) { return e == hipSuccess ? UCD_OK : UCD_E_HIP; }
 
 // One algorithm on one micro-batch.  (a, bsrc, out) = (x, w, y) | (dy, w, dx) | (x, dy, dw).
 int run_micro(const ucd_layer_t *L, int op, int algo, int b, const void *a, const void *bsrc, void *out,
-              float beta, float *ws, hipStream_t s)
+              float beta, float *ws, hipStream_t s, bool filter_ready = false)
 {
     const Dims d = dims_of(L);
     // tensors are read element by element (dw is always fp32); the workspace matrices with 16-byte loads
@@ -110,8 +110,8 @@ int run_micro(const ucd_layer_t *L, int op, int algo, int b, const void *a, cons
         else e = im2col_bwd_filter(d, b, a, bsrc, (float *)out, beta, ws, s);
         break;
     case UCD_ALGO_WINOGRAD:
-        if (op == UCD_FWD) e = winograd_fwd(d, b, a, bsrc, out, ws, s);
-        else if (op == UCD_BWD_DATA) e = winograd_bwd_data(d, b, a, bsrc, out, ws, s);
+        if (op == UCD_FWD) e = winograd_fwd(d, b, a, bsrc, out, ws, filter_ready, s);
+        else if (op == UCD_BWD_DATA) e = winograd_bwd_data(d, b, a, bsrc, out, ws, filter_ready, s);
         break;
     }
     return hip_status(e);
@@ -133,14 +133,18 @@ int run_plan(const ucd_plan_t *plan, int op, const void *a_, const void *bsrc_, 
     const size_t x_img = d.esize() * d.C * d.H * d.W, y_img = d.esize() * d.K * d.P * d.Q;
     size_t o = 0;
     bool first = true;
+    int prev_algo = -1;
     for (const Micro &m : plan->micro) {
         int rc;
+        // consecutive Winograd micro-batches of one call share the transformed filter in the workspace
+        const bool filter_ready = m.algo == UCD_ALGO_WINOGRAD && prev_algo == UCD_ALGO_WINOGRAD;
+        prev_algo = m.algo;
         if (op == UCD_FWD)
             rc = run_micro(L, op, m.algo, m.batch, a + o * x_img, bsrc, out + o * y_img, 0.f, (float *)ws,
-                           (hipStream_t)stream);
+                           (hipStream_t)stream, filter_ready);
         else if (op == UCD_BWD_DATA)
             rc = run_micro(L, op, m.algo, m.batch, a + o * y_img, bsrc, out + o * x_img, 0.f, (float *)ws,
-                           (hipStream_t)stream);
+                           (hipStream_t)stream, filter_ready);
         else  // the caller's beta for the first micro-batch, output scale 1 afterwards
             rc = run_micro(L, op, m.algo, m.batch, a + o * x_img, bsrc + o * y_img, out, first ? beta : 1.f,
                            (float *)ws, (hipStream_t)stream);

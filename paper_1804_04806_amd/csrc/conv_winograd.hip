@@ -173,7 +173,7 @@ __global__ __launch_bounds__(256) void wino_output_kernel(const float *__restric
 
 template <class E>
 static hipError_t winograd_run(const Dims &d, int op, int b, const void *in, const void *w, void *out,
-                               float *ws, hipStream_t s)
+                               float *ws, bool filter_ready, hipStream_t s)
 {
     const WinoGeom g = geom(d, op, b);
     const int n_tiles = b * g.T;
@@ -183,7 +183,9 @@ static hipError_t winograd_run(const Dims &d, int op, int b, const void *in, con
     const FastDiv divT(g.T), divTW(g.TW);
 
     LaunchLog *log = launch_log();
-    if (log) log->add("wino_filter_kernel");
+    if (filter_ready) {
+        // U of this filter is still at the head of the workspace from the previous micro-batch
+    } else if (log) log->add("wino_filter_kernel");
     else
         wino_filter_kernel<E><<<(unsigned)((g.Ci * g.Mo4 + 255) / 256), 256, 0, s>>>(w, U, g.Ci, g.Co, g.Mo4,
                                                                                   g.transposed ? 1 : 0);
@@ -215,16 +217,18 @@ static hipError_t winograd_run(const Dims &d, int op, int b, const void *in, con
     return hipGetLastError();
 }
 
-hipError_t winograd_fwd(const Dims &d, int b, const void *x, const void *w, void *y, float *ws, hipStream_t s)
+hipError_t winograd_fwd(const Dims &d, int b, const void *x, const void *w, void *y, float *ws, bool filter_ready,
+                        hipStream_t s)
 {
-    return d.dtype == 1 ? winograd_run<bf16>(d, 0, b, x, w, y, ws, s) : winograd_run<float>(d, 0, b, x, w, y, ws, s);
+    return d.dtype == 1 ? winograd_run<bf16>(d, 0, b, x, w, y, ws, filter_ready, s)
+                        : winograd_run<float>(d, 0, b, x, w, y, ws, filter_ready, s);
 }
 
 hipError_t winograd_bwd_data(const Dims &d, int b, const void *dy, const void *w, void *dx, float *ws,
-                             hipStream_t s)
+                             bool filter_ready, hipStream_t s)
 {
-    return d.dtype == 1 ? winograd_run<bf16>(d, 1, b, dy, w, dx, ws, s)
-                        : winograd_run<float>(d, 1, b, dy, w, dx, ws, s);
+    return d.dtype == 1 ? winograd_run<bf16>(d, 1, b, dy, w, dx, ws, filter_ready, s)
+                        : winograd_run<float>(d, 1, b, dy, w, dx, ws, filter_ready, s);
 }
 
 }  // namespace ucd
