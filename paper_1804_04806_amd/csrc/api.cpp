@@ -277,6 +277,19 @@ int solve_wd(const std::vector<std::vector<Config>> &fronts, size_t total_ws, st
     return UCD_OK;
 }
 
+// No C++ exception may cross the C boundary: allocation failures become UCD_E_NOMEM.
+template <class F>
+int guarded(F body) noexcept
+{
+    try {
+        return body();
+    } catch (const std::bad_alloc &) {
+        return UCD_E_NOMEM;
+    } catch (...) {
+        return UCD_E_INVALID;
+    }
+}
+
 }  // namespace
 
 // ---- exported ------------------------------------------------------------------------------
@@ -304,6 +317,7 @@ size_t ucd_workspace_size(const ucd_layer_t *layer, int op, int algo, int b) { r
 int ucd_plan_from_table(int B, size_t ws_limit, int policy, int n_algo, const uint64_t *t_ns, const size_t *ws,
                         ucd_plan_t **out)
 {
+    return guarded([&]() -> int {
     if (!t_ns || !ws || !out) return UCD_E_NULLPTR;
     if (B < 1 || n_algo < 1 || !policy_ok(policy)) return UCD_E_INVALID;
     Table tab{B, n_algo, t_ns, ws};
@@ -313,11 +327,13 @@ int ucd_plan_from_table(int B, size_t ws_limit, int policy, int n_algo, const ui
     if (!p) return UCD_E_NOMEM;
     *out = p;
     return UCD_OK;
+    });
 }
 
 int ucd_desirable_from_table(int B, size_t ws_limit, int policy, int n_algo, const uint64_t *t_ns,
                              const size_t *ws, uint64_t *front_t, size_t *front_ws, int cap, int *n)
 {
+    return guarded([&]() -> int {
     if (!t_ns || !ws || !n || (cap > 0 && (!front_t || !front_ws))) return UCD_E_NULLPTR;
     if (B < 1 || n_algo < 1 || !policy_ok(policy) || cap < 0) return UCD_E_INVALID;
     Table tab{B, n_algo, t_ns, ws};
@@ -329,11 +345,13 @@ int ucd_desirable_from_table(int B, size_t ws_limit, int policy, int n_algo, con
     }
     *n = (int)front.size();
     return UCD_OK;
+    });
 }
 
 int ucd_wd_solve(int n_kernels, const int *front_n, const uint64_t *front_t, const size_t *front_ws,
                  size_t budget, int *choice, uint64_t *total_t)
 {
+    return guarded([&]() -> int {
     if (!front_n || !front_t || !front_ws || !choice || !total_t) return UCD_E_NULLPTR;
     if (n_kernels < 1) return UCD_E_INVALID;
     std::vector<std::vector<FrontPoint>> pts(n_kernels);
@@ -348,11 +366,13 @@ int ucd_wd_solve(int n_kernels, const int *front_n, const uint64_t *front_t, con
     std::copy(ch.begin(), ch.end(), choice);
     *total_t = total;
     return UCD_OK;
+    });
 }
 
 int ucd_plan_wd_from_tables(int n_kernels, const int *B, int n_algo, const size_t *tab_off, const uint64_t *t_ns,
                             const size_t *ws, size_t total_ws, int policy, ucd_plan_t **plans, size_t *ws_offsets)
 {
+    return guarded([&]() -> int {
     if (!B || !tab_off || !t_ns || !ws || !plans || !ws_offsets) return UCD_E_NULLPTR;
     if (n_kernels < 1 || n_algo < 1 || !policy_ok(policy)) return UCD_E_INVALID;
     std::vector<std::vector<Config>> fronts(n_kernels);
@@ -380,10 +400,12 @@ int ucd_plan_wd_from_tables(int n_kernels, const int *B, int n_algo, const size_
         off += round256(made[k]->ws_bytes);
     }
     return UCD_OK;
+    });
 }
 
 int ucd_plan_fixed(const ucd_layer_t *layer, int op, const ucd_micro_t *micro, int n, ucd_plan_t **out)
 {
+    return guarded([&]() -> int {
     if (!layer || !micro || !out) return UCD_E_NULLPTR;
     if (!layer_ok(layer) || op < 0 || op >= UCD_N_OP || n < 1) return UCD_E_INVALID;
     Config cfg;
@@ -402,10 +424,12 @@ int ucd_plan_fixed(const ucd_layer_t *layer, int op, const ucd_micro_t *micro, i
     if (!p) return UCD_E_NOMEM;
     *out = p;
     return UCD_OK;
+    });
 }
 
 int ucd_plan_query(const ucd_plan_t *plan, ucd_micro_t *micro, int cap, int *n, uint64_t *cost_ns, size_t *ws_bytes)
 {
+    return guarded([&]() -> int {
     if (!plan) return UCD_E_NULLPTR;
     if (cap < 0 || (cap > 0 && !micro)) return UCD_E_INVALID;
     for (int i = 0; i < cap && i < (int)plan->micro.size(); ++i) {
@@ -416,6 +440,7 @@ int ucd_plan_query(const ucd_plan_t *plan, ucd_micro_t *micro, int cap, int *n, 
     if (cost_ns) *cost_ns = plan->cost_ns;
     if (ws_bytes) *ws_bytes = plan->ws_bytes;
     return UCD_OK;
+    });
 }
 
 void ucd_plan_destroy(ucd_plan_t *plan) { delete plan; }
@@ -423,6 +448,7 @@ void ucd_plan_destroy(ucd_plan_t *plan) { delete plan; }
 int ucd_plan(const ucd_layer_t *layer, int op, size_t ws_limit, int policy, void *x, void *w, void *y, void *ws,
              void *stream, ucd_plan_t **out)
 {
+    return guarded([&]() -> int {
     if (!layer || !x || !w || !y || !out) return UCD_E_NULLPTR;
     if (!layer_ok(layer) || op < 0 || op >= UCD_N_OP || !policy_ok(policy)) return UCD_E_INVALID;
     if (!fits_32bit(layer, layer->N)) return UCD_E_UNSUPPORTED;
@@ -439,12 +465,14 @@ int ucd_plan(const ucd_layer_t *layer, int op, size_t ws_limit, int policy, void
     if (!p) return UCD_E_NOMEM;
     *out = p;
     return UCD_OK;
+    });
 }
 
 int ucd_plan_wd(const ucd_layer_t *layers, const int *ops, int n_kernels, size_t total_ws, int policy, void *x,
                 size_t x_cap, void *w, size_t w_cap, void *y, size_t y_cap, void *ws, void *stream,
                 ucd_plan_t **plans, size_t *ws_offsets)
 {
+    return guarded([&]() -> int {
     if (!layers || !ops || !x || !w || !y || !plans || !ws_offsets) return UCD_E_NULLPTR;
     if (n_kernels < 1 || !policy_ok(policy)) return UCD_E_INVALID;
     if (total_ws > 0 && !ws) return UCD_E_NULLPTR;
@@ -487,10 +515,12 @@ int ucd_plan_wd(const ucd_layer_t *layers, const int *ops, int n_kernels, size_t
         off += round256(made[k]->ws_bytes);
     }
     return UCD_OK;
+    });
 }
 
 int ucd_bench_table(const ucd_layer_t *layer, int op, uint64_t *t_ns, size_t *ws, int cap_b)
 {
+    return guarded([&]() -> int {
     if (!layer || !t_ns || !ws) return UCD_E_NULLPTR;
     if (!layer_ok(layer) || op < 0 || op >= UCD_N_OP || cap_b < 1) return UCD_E_INVALID;
     ucd_layer_t L = *layer;
@@ -506,6 +536,7 @@ int ucd_bench_table(const ucd_layer_t *layer, int op, uint64_t *t_ns, size_t *ws
             if (cache_get(key_of(&L, op, a, b), ns)) t_ns[i] = ns;
         }
     return UCD_OK;
+    });
 }
 
 void ucd_bench_clear(void)
@@ -516,12 +547,14 @@ void ucd_bench_clear(void)
 
 int ucd_bench_put(const ucd_layer_t *layer, int op, int algo, int b, uint64_t t_ns)
 {
+    return guarded([&]() -> int {
     if (!layer) return UCD_E_NULLPTR;
     if (!layer_ok(layer) || op < 0 || op >= UCD_N_OP || algo < 0 || algo >= UCD_N_ALGO || b < 1 || t_ns == 0 ||
         t_ns == UCD_TIME_INF)
         return UCD_E_INVALID;
     cache_put(key_of(layer, op, algo, b), t_ns);
     return UCD_OK;
+    });
 }
 
 // File format: one header line "ucd-bench 1 <device>", then one line of 15 integers per timing:
@@ -542,6 +575,7 @@ static std::string device_tag()
 
 int ucd_bench_save(const char *path)
 {
+    return guarded([&]() -> int {
     if (!path) return UCD_E_NULLPTR;
     FILE *f = std::fopen(path, "w");
     if (!f) return UCD_E_INVALID;
@@ -556,10 +590,12 @@ int ucd_bench_save(const char *path)
     }
     const bool ok = std::fclose(f) == 0;
     return ok ? UCD_OK : UCD_E_INVALID;
+    });
 }
 
 int ucd_bench_load(const char *path, int *n_loaded)
 {
+    return guarded([&]() -> int {
     if (!path) return UCD_E_NULLPTR;
     FILE *f = std::fopen(path, "r");
     if (!f) return UCD_E_INVALID;
@@ -594,10 +630,12 @@ int ucd_bench_load(const char *path, int *n_loaded)
     for (const auto &r : rows) cache_put(r.first, r.second);
     if (n_loaded) *n_loaded = (int)rows.size();
     return UCD_OK;
+    });
 }
 
 int ucd_plan_cached(const ucd_layer_t *layer, int op, size_t ws_limit, int policy, ucd_plan_t **out)
 {
+    return guarded([&]() -> int {
     if (!layer || !out) return UCD_E_NULLPTR;
     if (!layer_ok(layer) || op < 0 || op >= UCD_N_OP || !policy_ok(policy)) return UCD_E_INVALID;
     if (!fits_32bit(layer, layer->N)) return UCD_E_UNSUPPORTED;
@@ -619,29 +657,37 @@ int ucd_plan_cached(const ucd_layer_t *layer, int op, size_t ws_limit, int polic
     if (!p) return UCD_E_NOMEM;
     *out = p;
     return UCD_OK;
+    });
 }
 
 int ucd_conv_fwd(const ucd_plan_t *plan, const void *x, const void *w, void *y, void *ws, size_t ws_bytes,
                  void *stream)
 {
+    return guarded([&]() -> int {
     return run_plan(plan, UCD_FWD, x, w, y, 0.f, ws, ws_bytes, stream);
+    });
 }
 
 int ucd_conv_bwd_data(const ucd_plan_t *plan, const void *dy, const void *w, void *dx, void *ws, size_t ws_bytes,
                       void *stream)
 {
+    return guarded([&]() -> int {
     return run_plan(plan, UCD_BWD_DATA, dy, w, dx, 0.f, ws, ws_bytes, stream);
+    });
 }
 
 int ucd_conv_bwd_filter(const ucd_plan_t *plan, const void *x, const void *dy, void *dw, float beta, void *ws,
                         size_t ws_bytes, void *stream)
 {
+    return guarded([&]() -> int {
     return run_plan(plan, UCD_BWD_FILTER, x, dy, dw, beta, ws, ws_bytes,
                     stream);
+    });
 }
 
 int ucd_describe_micro(const ucd_layer_t *layer, int op, int algo, int b, char *buf, size_t cap, int *n_launches)
 {
+    return guarded([&]() -> int {
     if (!layer || !buf) return UCD_E_NULLPTR;
     if (!layer_ok(layer) || op < 0 || op >= UCD_N_OP || b < 1 || cap < 1) return UCD_E_INVALID;
     ucd_layer_t L = *layer;
@@ -658,11 +704,13 @@ int ucd_describe_micro(const ucd_layer_t *layer, int op, int algo, int b, char *
     buf[n] = 0;
     if (n_launches) *n_launches = log.launches;
     return UCD_OK;
+    });
 }
 
 int ucd_mfma_probe(int valu_per_mfma, int blocks, int iters, void *scratch, size_t scratch_bytes, void *stream,
                    double *flops)
 {
+    return guarded([&]() -> int {
     if (!scratch || !flops) return UCD_E_NULLPTR;
     if (blocks < 1 || blocks > 65536 || iters < 1 || scratch_bytes < (size_t)blocks * 256 * 4) return UCD_E_INVALID;
     hipError_t e = mfma_probe(valu_per_mfma, blocks, iters, (float *)scratch, (hipStream_t)stream);
@@ -670,11 +718,13 @@ int ucd_mfma_probe(int valu_per_mfma, int blocks, int iters, void *scratch, size
     if (e != hipSuccess) return UCD_E_HIP;
     *flops = (double)blocks * 4.0 * iters * 16.0 * 4096.0;
     return UCD_OK;
+    });
 }
 
 int ucd_run_micro(const ucd_layer_t *layer, int op, int algo, int b, const void *a, const void *bsrc, void *out,
                   float beta, void *ws, size_t ws_bytes, void *stream)
 {
+    return guarded([&]() -> int {
     if (!layer || !a || !bsrc || !out) return UCD_E_NULLPTR;
     // the descriptor's N is the extent of the caller's buffers: a micro-batch cannot exceed it
     if (!layer_ok(layer) || op < 0 || op >= UCD_N_OP || b < 1 || b > layer->N) return UCD_E_INVALID;
@@ -686,6 +736,7 @@ int ucd_run_micro(const ucd_layer_t *layer, int op, int algo, int b, const void 
     if (op == UCD_BWD_FILTER && beta != 0.f && beta != 1.f) return UCD_E_INVALID;
     return run_micro(&L, op, algo, b, a, bsrc, out, beta, (float *)ws,
                      (hipStream_t)stream);
+    });
 }
 
 }  // extern "C"
