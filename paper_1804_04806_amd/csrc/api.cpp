@@ -318,15 +318,15 @@ int ucd_plan_from_table(int B, size_t ws_limit, int policy, int n_algo, const ui
                         ucd_plan_t **out)
 {
     return guarded([&]() -> int {
-    if (!t_ns || !ws || !out) return UCD_E_NULLPTR;
-    if (B < 1 || n_algo < 1 || !policy_ok(policy)) return UCD_E_INVALID;
-    Table tab{B, n_algo, t_ns, ws};
-    Config cfg;
-    if (!wr_plan(tab, ws_limit, policy, cfg)) return UCD_E_INFEASIBLE;
-    ucd_plan_t *p = make_plan(cfg, nullptr, 0);
-    if (!p) return UCD_E_NOMEM;
-    *out = p;
-    return UCD_OK;
+        if (!t_ns || !ws || !out) return UCD_E_NULLPTR;
+        if (B < 1 || n_algo < 1 || !policy_ok(policy)) return UCD_E_INVALID;
+        Table tab{B, n_algo, t_ns, ws};
+        Config cfg;
+        if (!wr_plan(tab, ws_limit, policy, cfg)) return UCD_E_INFEASIBLE;
+        ucd_plan_t *p = make_plan(cfg, nullptr, 0);
+        if (!p) return UCD_E_NOMEM;
+        *out = p;
+        return UCD_OK;
     });
 }
 
@@ -334,17 +334,17 @@ int ucd_desirable_from_table(int B, size_t ws_limit, int policy, int n_algo, con
                              const size_t *ws, uint64_t *front_t, size_t *front_ws, int cap, int *n)
 {
     return guarded([&]() -> int {
-    if (!t_ns || !ws || !n || (cap > 0 && (!front_t || !front_ws))) return UCD_E_NULLPTR;
-    if (B < 1 || n_algo < 1 || !policy_ok(policy) || cap < 0) return UCD_E_INVALID;
-    Table tab{B, n_algo, t_ns, ws};
-    std::vector<Config> front;
-    if (!desirable_set(tab, ws_limit, policy, front)) return UCD_E_INFEASIBLE;
-    for (int i = 0; i < (int)front.size() && i < cap; ++i) {
-        front_t[i] = front[i].cost;
-        front_ws[i] = front[i].ws;
-    }
-    *n = (int)front.size();
-    return UCD_OK;
+        if (!t_ns || !ws || !n || (cap > 0 && (!front_t || !front_ws))) return UCD_E_NULLPTR;
+        if (B < 1 || n_algo < 1 || !policy_ok(policy) || cap < 0) return UCD_E_INVALID;
+        Table tab{B, n_algo, t_ns, ws};
+        std::vector<Config> front;
+        if (!desirable_set(tab, ws_limit, policy, front)) return UCD_E_INFEASIBLE;
+        for (int i = 0; i < (int)front.size() && i < cap; ++i) {
+            front_t[i] = front[i].cost;
+            front_ws[i] = front[i].ws;
+        }
+        *n = (int)front.size();
+        return UCD_OK;
     });
 }
 
@@ -352,20 +352,20 @@ int ucd_wd_solve(int n_kernels, const int *front_n, const uint64_t *front_t, con
                  size_t budget, int *choice, uint64_t *total_t)
 {
     return guarded([&]() -> int {
-    if (!front_n || !front_t || !front_ws || !choice || !total_t) return UCD_E_NULLPTR;
-    if (n_kernels < 1) return UCD_E_INVALID;
-    std::vector<std::vector<FrontPoint>> pts(n_kernels);
-    size_t o = 0;
-    for (int k = 0; k < n_kernels; ++k) {
-        if (front_n[k] < 1) return UCD_E_INVALID;
-        for (int i = 0; i < front_n[k]; ++i, ++o) pts[k].push_back({front_t[o], front_ws[o]});
-    }
-    std::vector<int> ch;
-    uint64_t total;
-    if (!wd_solve(pts, budget, ch, total)) return UCD_E_INFEASIBLE;
-    std::copy(ch.begin(), ch.end(), choice);
-    *total_t = total;
-    return UCD_OK;
+        if (!front_n || !front_t || !front_ws || !choice || !total_t) return UCD_E_NULLPTR;
+        if (n_kernels < 1) return UCD_E_INVALID;
+        std::vector<std::vector<FrontPoint>> pts(n_kernels);
+        size_t o = 0;
+        for (int k = 0; k < n_kernels; ++k) {
+            if (front_n[k] < 1) return UCD_E_INVALID;
+            for (int i = 0; i < front_n[k]; ++i, ++o) pts[k].push_back({front_t[o], front_ws[o]});
+        }
+        std::vector<int> ch;
+        uint64_t total;
+        if (!wd_solve(pts, budget, ch, total)) return UCD_E_INFEASIBLE;
+        std::copy(ch.begin(), ch.end(), choice);
+        *total_t = total;
+        return UCD_OK;
     });
 }
 
@@ -373,73 +373,73 @@ int ucd_plan_wd_from_tables(int n_kernels, const int *B, int n_algo, const size_
                             const size_t *ws, size_t total_ws, int policy, ucd_plan_t **plans, size_t *ws_offsets)
 {
     return guarded([&]() -> int {
-    if (!B || !tab_off || !t_ns || !ws || !plans || !ws_offsets) return UCD_E_NULLPTR;
-    if (n_kernels < 1 || n_algo < 1 || !policy_ok(policy)) return UCD_E_INVALID;
-    std::vector<std::vector<Config>> fronts(n_kernels);
-    for (int k = 0; k < n_kernels; ++k) {
-        if (B[k] < 1) return UCD_E_INVALID;
-        Table tab{B[k], n_algo, t_ns + tab_off[k], ws + tab_off[k]};
-        if (!desirable_set(tab, total_ws, policy, fronts[k])) return UCD_E_INFEASIBLE;
-    }
-    std::vector<int> choice;
-    int rc = solve_wd(fronts, total_ws, choice);
-    if (rc != UCD_OK) return rc;
-    std::vector<ucd_plan_t *> made;
-    for (int k = 0; k < n_kernels; ++k) {
-        ucd_plan_t *p = make_plan(fronts[k][choice[k]], nullptr, 0);
-        if (!p) {
-            for (ucd_plan_t *q : made) delete q;
-            return UCD_E_NOMEM;
+        if (!B || !tab_off || !t_ns || !ws || !plans || !ws_offsets) return UCD_E_NULLPTR;
+        if (n_kernels < 1 || n_algo < 1 || !policy_ok(policy)) return UCD_E_INVALID;
+        std::vector<std::vector<Config>> fronts(n_kernels);
+        for (int k = 0; k < n_kernels; ++k) {
+            if (B[k] < 1) return UCD_E_INVALID;
+            Table tab{B[k], n_algo, t_ns + tab_off[k], ws + tab_off[k]};
+            if (!desirable_set(tab, total_ws, policy, fronts[k])) return UCD_E_INFEASIBLE;
         }
-        made.push_back(p);
-    }
-    size_t off = 0;
-    for (int k = 0; k < n_kernels; ++k) {
-        plans[k] = made[k];
-        ws_offsets[k] = off;
-        off += round256(made[k]->ws_bytes);
-    }
-    return UCD_OK;
+        std::vector<int> choice;
+        int rc = solve_wd(fronts, total_ws, choice);
+        if (rc != UCD_OK) return rc;
+        std::vector<ucd_plan_t *> made;
+        for (int k = 0; k < n_kernels; ++k) {
+            ucd_plan_t *p = make_plan(fronts[k][choice[k]], nullptr, 0);
+            if (!p) {
+                for (ucd_plan_t *q : made) delete q;
+                return UCD_E_NOMEM;
+            }
+            made.push_back(p);
+        }
+        size_t off = 0;
+        for (int k = 0; k < n_kernels; ++k) {
+            plans[k] = made[k];
+            ws_offsets[k] = off;
+            off += round256(made[k]->ws_bytes);
+        }
+        return UCD_OK;
     });
 }
 
 int ucd_plan_fixed(const ucd_layer_t *layer, int op, const ucd_micro_t *micro, int n, ucd_plan_t **out)
 {
     return guarded([&]() -> int {
-    if (!layer || !micro || !out) return UCD_E_NULLPTR;
-    if (!layer_ok(layer) || op < 0 || op >= UCD_N_OP || n < 1) return UCD_E_INVALID;
-    Config cfg;
-    long sum = 0;
-    for (int i = 0; i < n; ++i) {
-        if (micro[i].batch < 1 || micro[i].batch > layer->N) return UCD_E_INVALID;
-        if (micro[i].algo < 0 || micro[i].algo >= UCD_N_ALGO) return UCD_E_INVALID;
-        const size_t need = ws_size(layer, op, micro[i].algo, micro[i].batch);
-        if (need == UCD_WS_NA) return UCD_E_UNSUPPORTED;
-        cfg.ws = std::max(cfg.ws, need);
-        cfg.micro.push_back({micro[i].algo, micro[i].batch});
-        sum += micro[i].batch;
-    }
-    if (sum != layer->N) return UCD_E_INVALID;
-    ucd_plan_t *p = make_plan(cfg, layer, op);
-    if (!p) return UCD_E_NOMEM;
-    *out = p;
-    return UCD_OK;
+        if (!layer || !micro || !out) return UCD_E_NULLPTR;
+        if (!layer_ok(layer) || op < 0 || op >= UCD_N_OP || n < 1) return UCD_E_INVALID;
+        Config cfg;
+        long sum = 0;
+        for (int i = 0; i < n; ++i) {
+            if (micro[i].batch < 1 || micro[i].batch > layer->N) return UCD_E_INVALID;
+            if (micro[i].algo < 0 || micro[i].algo >= UCD_N_ALGO) return UCD_E_INVALID;
+            const size_t need = ws_size(layer, op, micro[i].algo, micro[i].batch);
+            if (need == UCD_WS_NA) return UCD_E_UNSUPPORTED;
+            cfg.ws = std::max(cfg.ws, need);
+            cfg.micro.push_back({micro[i].algo, micro[i].batch});
+            sum += micro[i].batch;
+        }
+        if (sum != layer->N) return UCD_E_INVALID;
+        ucd_plan_t *p = make_plan(cfg, layer, op);
+        if (!p) return UCD_E_NOMEM;
+        *out = p;
+        return UCD_OK;
     });
 }
 
 int ucd_plan_query(const ucd_plan_t *plan, ucd_micro_t *micro, int cap, int *n, uint64_t *cost_ns, size_t *ws_bytes)
 {
     return guarded([&]() -> int {
-    if (!plan) return UCD_E_NULLPTR;
-    if (cap < 0 || (cap > 0 && !micro)) return UCD_E_INVALID;
-    for (int i = 0; i < cap && i < (int)plan->micro.size(); ++i) {
-        micro[i].algo = plan->micro[i].algo;
-        micro[i].batch = plan->micro[i].batch;
-    }
-    if (n) *n = (int)plan->micro.size();
-    if (cost_ns) *cost_ns = plan->cost_ns;
-    if (ws_bytes) *ws_bytes = plan->ws_bytes;
-    return UCD_OK;
+        if (!plan) return UCD_E_NULLPTR;
+        if (cap < 0 || (cap > 0 && !micro)) return UCD_E_INVALID;
+        for (int i = 0; i < cap && i < (int)plan->micro.size(); ++i) {
+            micro[i].algo = plan->micro[i].algo;
+            micro[i].batch = plan->micro[i].batch;
+        }
+        if (n) *n = (int)plan->micro.size();
+        if (cost_ns) *cost_ns = plan->cost_ns;
+        if (ws_bytes) *ws_bytes = plan->ws_bytes;
+        return UCD_OK;
     });
 }
 
@@ -449,22 +449,22 @@ int ucd_plan(const ucd_layer_t *layer, int op, size_t ws_limit, int policy, void
              void *stream, ucd_plan_t **out)
 {
     return guarded([&]() -> int {
-    if (!layer || !x || !w || !y || !out) return UCD_E_NULLPTR;
-    if (!layer_ok(layer) || op < 0 || op >= UCD_N_OP || !policy_ok(policy)) return UCD_E_INVALID;
-    if (!fits_32bit(layer, layer->N)) return UCD_E_UNSUPPORTED;
-    if (ws_limit > 0 && !ws) return UCD_E_NULLPTR;
-    std::vector<uint64_t> t;
-    std::vector<size_t> m;
-    int rc = bench_kernel(layer, op, ws_limit, policy, x, w, y, (float *)ws,
-                          (hipStream_t)stream, t, m);
-    if (rc != UCD_OK) return rc;
-    Table tab{layer->N, UCD_N_ALGO, t.data(), m.data()};
-    Config cfg;
-    if (!wr_plan(tab, ws_limit, policy, cfg)) return UCD_E_INFEASIBLE;
-    ucd_plan_t *p = make_plan(cfg, layer, op);
-    if (!p) return UCD_E_NOMEM;
-    *out = p;
-    return UCD_OK;
+        if (!layer || !x || !w || !y || !out) return UCD_E_NULLPTR;
+        if (!layer_ok(layer) || op < 0 || op >= UCD_N_OP || !policy_ok(policy)) return UCD_E_INVALID;
+        if (!fits_32bit(layer, layer->N)) return UCD_E_UNSUPPORTED;
+        if (ws_limit > 0 && !ws) return UCD_E_NULLPTR;
+        std::vector<uint64_t> t;
+        std::vector<size_t> m;
+        int rc = bench_kernel(layer, op, ws_limit, policy, x, w, y, (float *)ws,
+                              (hipStream_t)stream, t, m);
+        if (rc != UCD_OK) return rc;
+        Table tab{layer->N, UCD_N_ALGO, t.data(), m.data()};
+        Config cfg;
+        if (!wr_plan(tab, ws_limit, policy, cfg)) return UCD_E_INFEASIBLE;
+        ucd_plan_t *p = make_plan(cfg, layer, op);
+        if (!p) return UCD_E_NOMEM;
+        *out = p;
+        return UCD_OK;
     });
 }
 
@@ -473,69 +473,69 @@ int ucd_plan_wd(const ucd_layer_t *layers, const int *ops, int n_kernels, size_t
                 ucd_plan_t **plans, size_t *ws_offsets)
 {
     return guarded([&]() -> int {
-    if (!layers || !ops || !x || !w || !y || !plans || !ws_offsets) return UCD_E_NULLPTR;
-    if (n_kernels < 1 || !policy_ok(policy)) return UCD_E_INVALID;
-    if (total_ws > 0 && !ws) return UCD_E_NULLPTR;
-    for (int k = 0; k < n_kernels; ++k) {
-        const ucd_layer_t *L = &layers[k];
-        if (!layer_ok(L) || ops[k] < 0 || ops[k] >= UCD_N_OP) return UCD_E_INVALID;
-        if (!fits_32bit(L, L->N)) return UCD_E_UNSUPPORTED;
-        const Dims d = dims_of(L);
-        // the w scratch doubles as the fp32 dw of BackwardFilter kernels
-        if ((size_t)L->N * d.C * d.H * d.W * d.esize() > x_cap || (size_t)d.K * d.crs() * 4 > w_cap ||
-            (size_t)L->N * d.K * d.P * d.Q * d.esize() > y_cap)
-            return UCD_E_INVALID;
-    }
-    std::vector<std::vector<Config>> fronts(n_kernels);
-    for (int k = 0; k < n_kernels; ++k) {
-        std::vector<uint64_t> t;
-        std::vector<size_t> m;
-        int rc = bench_kernel(&layers[k], ops[k], total_ws, policy, x, w, y, (float *)ws,
-                              (hipStream_t)stream, t, m);
-        if (rc != UCD_OK) return rc;
-        Table tab{layers[k].N, UCD_N_ALGO, t.data(), m.data()};
-        if (!desirable_set(tab, total_ws, policy, fronts[k])) return UCD_E_INFEASIBLE;
-    }
-    std::vector<int> choice;
-    int rc = solve_wd(fronts, total_ws, choice);
-    if (rc != UCD_OK) return rc;
-    std::vector<ucd_plan_t *> made;
-    for (int k = 0; k < n_kernels; ++k) {
-        ucd_plan_t *p = make_plan(fronts[k][choice[k]], &layers[k], ops[k]);
-        if (!p) {
-            for (ucd_plan_t *q : made) delete q;
-            return UCD_E_NOMEM;
+        if (!layers || !ops || !x || !w || !y || !plans || !ws_offsets) return UCD_E_NULLPTR;
+        if (n_kernels < 1 || !policy_ok(policy)) return UCD_E_INVALID;
+        if (total_ws > 0 && !ws) return UCD_E_NULLPTR;
+        for (int k = 0; k < n_kernels; ++k) {
+            const ucd_layer_t *L = &layers[k];
+            if (!layer_ok(L) || ops[k] < 0 || ops[k] >= UCD_N_OP) return UCD_E_INVALID;
+            if (!fits_32bit(L, L->N)) return UCD_E_UNSUPPORTED;
+            const Dims d = dims_of(L);
+            // the w scratch doubles as the fp32 dw of BackwardFilter kernels
+            if ((size_t)L->N * d.C * d.H * d.W * d.esize() > x_cap || (size_t)d.K * d.crs() * 4 > w_cap ||
+                (size_t)L->N * d.K * d.P * d.Q * d.esize() > y_cap)
+                return UCD_E_INVALID;
         }
-        made.push_back(p);
-    }
-    size_t off = 0;
-    for (int k = 0; k < n_kernels; ++k) {
-        plans[k] = made[k];
-        ws_offsets[k] = off;
-        off += round256(made[k]->ws_bytes);
-    }
-    return UCD_OK;
+        std::vector<std::vector<Config>> fronts(n_kernels);
+        for (int k = 0; k < n_kernels; ++k) {
+            std::vector<uint64_t> t;
+            std::vector<size_t> m;
+            int rc = bench_kernel(&layers[k], ops[k], total_ws, policy, x, w, y, (float *)ws,
+                                  (hipStream_t)stream, t, m);
+            if (rc != UCD_OK) return rc;
+            Table tab{layers[k].N, UCD_N_ALGO, t.data(), m.data()};
+            if (!desirable_set(tab, total_ws, policy, fronts[k])) return UCD_E_INFEASIBLE;
+        }
+        std::vector<int> choice;
+        int rc = solve_wd(fronts, total_ws, choice);
+        if (rc != UCD_OK) return rc;
+        std::vector<ucd_plan_t *> made;
+        for (int k = 0; k < n_kernels; ++k) {
+            ucd_plan_t *p = make_plan(fronts[k][choice[k]], &layers[k], ops[k]);
+            if (!p) {
+                for (ucd_plan_t *q : made) delete q;
+                return UCD_E_NOMEM;
+            }
+            made.push_back(p);
+        }
+        size_t off = 0;
+        for (int k = 0; k < n_kernels; ++k) {
+            plans[k] = made[k];
+            ws_offsets[k] = off;
+            off += round256(made[k]->ws_bytes);
+        }
+        return UCD_OK;
     });
 }
 
 int ucd_bench_table(const ucd_layer_t *layer, int op, uint64_t *t_ns, size_t *ws, int cap_b)
 {
     return guarded([&]() -> int {
-    if (!layer || !t_ns || !ws) return UCD_E_NULLPTR;
-    if (!layer_ok(layer) || op < 0 || op >= UCD_N_OP || cap_b < 1) return UCD_E_INVALID;
-    ucd_layer_t L = *layer;
-    for (int a = 0; a < UCD_N_ALGO; ++a)
-        for (int b = 0; b <= cap_b; ++b) {
-            const size_t i = (size_t)a * (cap_b + 1) + b;
-            t_ns[i] = UCD_TIME_INF;
-            ws[i] = UCD_WS_NA;
-            if (b < 1) continue;
-            L.N = std::max(L.N, b);
-            ws[i] = ws_size(&L, op, a, b);
-            uint64_t ns;
-            if (cache_get(key_of(&L, op, a, b), ns)) t_ns[i] = ns;
-        }
-    return UCD_OK;
+        if (!layer || !t_ns || !ws) return UCD_E_NULLPTR;
+        if (!layer_ok(layer) || op < 0 || op >= UCD_N_OP || cap_b < 1) return UCD_E_INVALID;
+        ucd_layer_t L = *layer;
+        for (int a = 0; a < UCD_N_ALGO; ++a)
+            for (int b = 0; b <= cap_b; ++b) {
+                const size_t i = (size_t)a * (cap_b + 1) + b;
+                t_ns[i] = UCD_TIME_INF;
+                ws[i] = UCD_WS_NA;
+                if (b < 1) continue;
+                L.N = std::max(L.N, b);
+                ws[i] = ws_size(&L, op, a, b);
+                uint64_t ns;
+                if (cache_get(key_of(&L, op, a, b), ns)) t_ns[i] = ns;
+            }
+        return UCD_OK;
     });
 }
 
@@ -548,12 +548,12 @@ void ucd_bench_clear(void)
 int ucd_bench_put(const ucd_layer_t *layer, int op, int algo, int b, uint64_t t_ns)
 {
     return guarded([&]() -> int {
-    if (!layer) return UCD_E_NULLPTR;
-    if (!layer_ok(layer) || op < 0 || op >= UCD_N_OP || algo < 0 || algo >= UCD_N_ALGO || b < 1 || t_ns == 0 ||
-        t_ns == UCD_TIME_INF)
-        return UCD_E_INVALID;
-    cache_put(key_of(layer, op, algo, b), t_ns);
-    return UCD_OK;
+        if (!layer) return UCD_E_NULLPTR;
+        if (!layer_ok(layer) || op < 0 || op >= UCD_N_OP || algo < 0 || algo >= UCD_N_ALGO || b < 1 || t_ns == 0 ||
+            t_ns == UCD_TIME_INF)
+            return UCD_E_INVALID;
+        cache_put(key_of(layer, op, algo, b), t_ns);
+        return UCD_OK;
     });
 }
 
@@ -576,87 +576,87 @@ static std::string device_tag()
 int ucd_bench_save(const char *path)
 {
     return guarded([&]() -> int {
-    if (!path) return UCD_E_NULLPTR;
-    FILE *f = std::fopen(path, "w");
-    if (!f) return UCD_E_INVALID;
-    std::fprintf(f, "ucd-bench 1 %s\n", device_tag().c_str());
-    std::lock_guard<std::mutex> g(g_cache_mu);
-    for (const auto &kv : g_cache) {
-        const BenchKey &k = kv.first;
-        std::fprintf(f, "%d %d %d %d %d %d %d %d %d %d %d %d %d %d %llu\n", std::get<0>(k), std::get<1>(k),
-                     std::get<2>(k), std::get<3>(k), std::get<4>(k), std::get<5>(k), std::get<6>(k), std::get<7>(k),
-                     std::get<8>(k), std::get<9>(k), std::get<10>(k), std::get<11>(k), std::get<12>(k), std::get<13>(k),
-                     (unsigned long long)kv.second);
-    }
-    const bool ok = std::fclose(f) == 0;
-    return ok ? UCD_OK : UCD_E_INVALID;
+        if (!path) return UCD_E_NULLPTR;
+        FILE *f = std::fopen(path, "w");
+        if (!f) return UCD_E_INVALID;
+        std::fprintf(f, "ucd-bench 1 %s\n", device_tag().c_str());
+        std::lock_guard<std::mutex> g(g_cache_mu);
+        for (const auto &kv : g_cache) {
+            const BenchKey &k = kv.first;
+            std::fprintf(f, "%d %d %d %d %d %d %d %d %d %d %d %d %d %d %llu\n", std::get<0>(k), std::get<1>(k),
+                         std::get<2>(k), std::get<3>(k), std::get<4>(k), std::get<5>(k), std::get<6>(k), std::get<7>(k),
+                         std::get<8>(k), std::get<9>(k), std::get<10>(k), std::get<11>(k), std::get<12>(k), std::get<13>(k),
+                         (unsigned long long)kv.second);
+        }
+        const bool ok = std::fclose(f) == 0;
+        return ok ? UCD_OK : UCD_E_INVALID;
     });
 }
 
 int ucd_bench_load(const char *path, int *n_loaded)
 {
     return guarded([&]() -> int {
-    if (!path) return UCD_E_NULLPTR;
-    FILE *f = std::fopen(path, "r");
-    if (!f) return UCD_E_INVALID;
-    char magic[32] = {0}, dev[128] = {0};
-    int ver = 0;
-    if (std::fscanf(f, "%31s %d %127s", magic, &ver, dev) != 3 || std::strcmp(magic, "ucd-bench") != 0 || ver != 1) {
-        std::fclose(f);
-        return UCD_E_INVALID;
-    }
-    // timings are only meaningful on the device they were taken on; a process without a GPU
-    // (offline planning) accepts any file
-    const std::string here = device_tag();
-    if (here != "none" && std::strcmp(dev, "none") != 0 && here != dev) {
-        std::fclose(f);
-        return UCD_E_UNSUPPORTED;
-    }
-    std::vector<std::pair<BenchKey, uint64_t>> rows;
-    int v[14];
-    unsigned long long ns;
-    for (;;) {
-        int got = 0;
-        for (int i = 0; i < 14; ++i) got += std::fscanf(f, "%d", &v[i]) == 1;
-        if (got == 0) break;
-        if (got != 14 || std::fscanf(f, "%llu", &ns) != 1 || ns == 0) {
+        if (!path) return UCD_E_NULLPTR;
+        FILE *f = std::fopen(path, "r");
+        if (!f) return UCD_E_INVALID;
+        char magic[32] = {0}, dev[128] = {0};
+        int ver = 0;
+        if (std::fscanf(f, "%31s %d %127s", magic, &ver, dev) != 3 || std::strcmp(magic, "ucd-bench") != 0 || ver != 1) {
             std::fclose(f);
             return UCD_E_INVALID;
         }
-        rows.push_back({BenchKey(v[0], v[1], v[2], v[3], v[4], v[5], v[6], v[7], v[8], v[9], v[10], v[11], v[12], v[13]),
-                        (uint64_t)ns});
-    }
-    std::fclose(f);
-    for (const auto &r : rows) cache_put(r.first, r.second);
-    if (n_loaded) *n_loaded = (int)rows.size();
-    return UCD_OK;
+        // timings are only meaningful on the device they were taken on; a process without a GPU
+        // (offline planning) accepts any file
+        const std::string here = device_tag();
+        if (here != "none" && std::strcmp(dev, "none") != 0 && here != dev) {
+            std::fclose(f);
+            return UCD_E_UNSUPPORTED;
+        }
+        std::vector<std::pair<BenchKey, uint64_t>> rows;
+        int v[14];
+        unsigned long long ns;
+        for (;;) {
+            int got = 0;
+            for (int i = 0; i < 14; ++i) got += std::fscanf(f, "%d", &v[i]) == 1;
+            if (got == 0) break;
+            if (got != 14 || std::fscanf(f, "%llu", &ns) != 1 || ns == 0) {
+                std::fclose(f);
+                return UCD_E_INVALID;
+            }
+            rows.push_back({BenchKey(v[0], v[1], v[2], v[3], v[4], v[5], v[6], v[7], v[8], v[9], v[10], v[11], v[12], v[13]),
+                            (uint64_t)ns});
+        }
+        std::fclose(f);
+        for (const auto &r : rows) cache_put(r.first, r.second);
+        if (n_loaded) *n_loaded = (int)rows.size();
+        return UCD_OK;
     });
 }
 
 int ucd_plan_cached(const ucd_layer_t *layer, int op, size_t ws_limit, int policy, ucd_plan_t **out)
 {
     return guarded([&]() -> int {
-    if (!layer || !out) return UCD_E_NULLPTR;
-    if (!layer_ok(layer) || op < 0 || op >= UCD_N_OP || !policy_ok(policy)) return UCD_E_INVALID;
-    if (!fits_32bit(layer, layer->N)) return UCD_E_UNSUPPORTED;
-    const int B = layer->N;
-    std::vector<uint64_t> t((size_t)UCD_N_ALGO * (B + 1), kTimeInf);
-    std::vector<size_t> m((size_t)UCD_N_ALGO * (B + 1), kWsNa);
-    for (int b : policy_sizes(policy, B))
-        for (int a = 0; a < UCD_N_ALGO; ++a) {
-            const size_t need = ws_size(layer, op, a, b);
-            if (need == UCD_WS_NA) continue;
-            m[(size_t)a * (B + 1) + b] = need;
-            uint64_t ns;
-            if (need <= ws_limit && cache_get(key_of(layer, op, a, b), ns)) t[(size_t)a * (B + 1) + b] = ns;
-        }
-    Table tab{B, UCD_N_ALGO, t.data(), m.data()};
-    Config cfg;
-    if (!wr_plan(tab, ws_limit, policy, cfg)) return UCD_E_INFEASIBLE;
-    ucd_plan_t *p = make_plan(cfg, layer, op);
-    if (!p) return UCD_E_NOMEM;
-    *out = p;
-    return UCD_OK;
+        if (!layer || !out) return UCD_E_NULLPTR;
+        if (!layer_ok(layer) || op < 0 || op >= UCD_N_OP || !policy_ok(policy)) return UCD_E_INVALID;
+        if (!fits_32bit(layer, layer->N)) return UCD_E_UNSUPPORTED;
+        const int B = layer->N;
+        std::vector<uint64_t> t((size_t)UCD_N_ALGO * (B + 1), kTimeInf);
+        std::vector<size_t> m((size_t)UCD_N_ALGO * (B + 1), kWsNa);
+        for (int b : policy_sizes(policy, B))
+            for (int a = 0; a < UCD_N_ALGO; ++a) {
+                const size_t need = ws_size(layer, op, a, b);
+                if (need == UCD_WS_NA) continue;
+                m[(size_t)a * (B + 1) + b] = need;
+                uint64_t ns;
+                if (need <= ws_limit && cache_get(key_of(layer, op, a, b), ns)) t[(size_t)a * (B + 1) + b] = ns;
+            }
+        Table tab{B, UCD_N_ALGO, t.data(), m.data()};
+        Config cfg;
+        if (!wr_plan(tab, ws_limit, policy, cfg)) return UCD_E_INFEASIBLE;
+        ucd_plan_t *p = make_plan(cfg, layer, op);
+        if (!p) return UCD_E_NOMEM;
+        *out = p;
+        return UCD_OK;
     });
 }
 
@@ -664,7 +664,7 @@ int ucd_conv_fwd(const ucd_plan_t *plan, const void *x, const void *w, void *y, 
                  void *stream)
 {
     return guarded([&]() -> int {
-    return run_plan(plan, UCD_FWD, x, w, y, 0.f, ws, ws_bytes, stream);
+        return run_plan(plan, UCD_FWD, x, w, y, 0.f, ws, ws_bytes, stream);
     });
 }
 
@@ -672,7 +672,7 @@ int ucd_conv_bwd_data(const ucd_plan_t *plan, const void *dy, const void *w, voi
                       void *stream)
 {
     return guarded([&]() -> int {
-    return run_plan(plan, UCD_BWD_DATA, dy, w, dx, 0.f, ws, ws_bytes, stream);
+        return run_plan(plan, UCD_BWD_DATA, dy, w, dx, 0.f, ws, ws_bytes, stream);
     });
 }
 
@@ -680,30 +680,30 @@ int ucd_conv_bwd_filter(const ucd_plan_t *plan, const void *x, const void *dy, v
                         size_t ws_bytes, void *stream)
 {
     return guarded([&]() -> int {
-    return run_plan(plan, UCD_BWD_FILTER, x, dy, dw, beta, ws, ws_bytes,
-                    stream);
+        return run_plan(plan, UCD_BWD_FILTER, x, dy, dw, beta, ws, ws_bytes,
+                        stream);
     });
 }
 
 int ucd_describe_micro(const ucd_layer_t *layer, int op, int algo, int b, char *buf, size_t cap, int *n_launches)
 {
     return guarded([&]() -> int {
-    if (!layer || !buf) return UCD_E_NULLPTR;
-    if (!layer_ok(layer) || op < 0 || op >= UCD_N_OP || b < 1 || cap < 1) return UCD_E_INVALID;
-    ucd_layer_t L = *layer;
-    L.N = std::max(L.N, b);
-    if (ws_size(&L, op, algo, b) == UCD_WS_NA) return UCD_E_UNSUPPORTED;
-    LaunchLog log;
-    launch_log() = &log;
-    // pointers are only passed through to the (suppressed) launches, never dereferenced on the host
-    int rc = run_micro(&L, op, algo, b, nullptr, nullptr, nullptr, op == UCD_BWD_FILTER ? 1.f : 0.f, nullptr, nullptr);
-    launch_log() = nullptr;
-    if (rc != UCD_OK) return rc;
-    const size_t n = std::min(cap - 1, log.text.size());
-    std::memcpy(buf, log.text.data(), n);
-    buf[n] = 0;
-    if (n_launches) *n_launches = log.launches;
-    return UCD_OK;
+        if (!layer || !buf) return UCD_E_NULLPTR;
+        if (!layer_ok(layer) || op < 0 || op >= UCD_N_OP || b < 1 || cap < 1) return UCD_E_INVALID;
+        ucd_layer_t L = *layer;
+        L.N = std::max(L.N, b);
+        if (ws_size(&L, op, algo, b) == UCD_WS_NA) return UCD_E_UNSUPPORTED;
+        LaunchLog log;
+        launch_log() = &log;
+        // pointers are only passed through to the (suppressed) launches, never dereferenced on the host
+        int rc = run_micro(&L, op, algo, b, nullptr, nullptr, nullptr, op == UCD_BWD_FILTER ? 1.f : 0.f, nullptr, nullptr);
+        launch_log() = nullptr;
+        if (rc != UCD_OK) return rc;
+        const size_t n = std::min(cap - 1, log.text.size());
+        std::memcpy(buf, log.text.data(), n);
+        buf[n] = 0;
+        if (n_launches) *n_launches = log.launches;
+        return UCD_OK;
     });
 }
 
@@ -711,13 +711,13 @@ int ucd_mfma_probe(int valu_per_mfma, int blocks, int iters, void *scratch, size
                    double *flops)
 {
     return guarded([&]() -> int {
-    if (!scratch || !flops) return UCD_E_NULLPTR;
-    if (blocks < 1 || blocks > 65536 || iters < 1 || scratch_bytes < (size_t)blocks * 256 * 4) return UCD_E_INVALID;
-    hipError_t e = mfma_probe(valu_per_mfma, blocks, iters, (float *)scratch, (hipStream_t)stream);
-    if (e == hipErrorInvalidValue) return UCD_E_INVALID;
-    if (e != hipSuccess) return UCD_E_HIP;
-    *flops = (double)blocks * 4.0 * iters * 16.0 * 4096.0;
-    return UCD_OK;
+        if (!scratch || !flops) return UCD_E_NULLPTR;
+        if (blocks < 1 || blocks > 65536 || iters < 1 || scratch_bytes < (size_t)blocks * 256 * 4) return UCD_E_INVALID;
+        hipError_t e = mfma_probe(valu_per_mfma, blocks, iters, (float *)scratch, (hipStream_t)stream);
+        if (e == hipErrorInvalidValue) return UCD_E_INVALID;
+        if (e != hipSuccess) return UCD_E_HIP;
+        *flops = (double)blocks * 4.0 * iters * 16.0 * 4096.0;
+        return UCD_OK;
     });
 }
 
@@ -725,17 +725,17 @@ int ucd_run_micro(const ucd_layer_t *layer, int op, int algo, int b, const void 
                   float beta, void *ws, size_t ws_bytes, void *stream)
 {
     return guarded([&]() -> int {
-    if (!layer || !a || !bsrc || !out) return UCD_E_NULLPTR;
-    // the descriptor's N is the extent of the caller's buffers: a micro-batch cannot exceed it
-    if (!layer_ok(layer) || op < 0 || op >= UCD_N_OP || b < 1 || b > layer->N) return UCD_E_INVALID;
-    ucd_layer_t L = *layer;
-    const size_t need = ws_size(&L, op, algo, b);
-    if (need == UCD_WS_NA) return UCD_E_UNSUPPORTED;
-    if (need > 0 && !ws) return UCD_E_NULLPTR;
-    if (need > ws_bytes) return UCD_E_WS_TOO_SMALL;
-    if (op == UCD_BWD_FILTER && beta != 0.f && beta != 1.f) return UCD_E_INVALID;
-    return run_micro(&L, op, algo, b, a, bsrc, out, beta, (float *)ws,
-                     (hipStream_t)stream);
+        if (!layer || !a || !bsrc || !out) return UCD_E_NULLPTR;
+        // the descriptor's N is the extent of the caller's buffers: a micro-batch cannot exceed it
+        if (!layer_ok(layer) || op < 0 || op >= UCD_N_OP || b < 1 || b > layer->N) return UCD_E_INVALID;
+        ucd_layer_t L = *layer;
+        const size_t need = ws_size(&L, op, algo, b);
+        if (need == UCD_WS_NA) return UCD_E_UNSUPPORTED;
+        if (need > 0 && !ws) return UCD_E_NULLPTR;
+        if (need > ws_bytes) return UCD_E_WS_TOO_SMALL;
+        if (op == UCD_BWD_FILTER && beta != 0.f && beta != 1.f) return UCD_E_INVALID;
+        return run_micro(&L, op, algo, b, a, bsrc, out, beta, (float *)ws,
+                         (hipStream_t)stream);
     });
 }
 
