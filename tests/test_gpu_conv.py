@@ -30,6 +30,8 @@ SHAPES = [
     Shape(2, 160, 6, 6, 160, 3, 3, 1, 1, "k160"),              # 96-row tiles with a ragged second tile
     Shape(3, 120, 7, 7, 136, 3, 3, 1, 1, "deep"),              # few output tiles, long reduction: split + atomics
     Shape(3, 130, 10, 10, 72, 3, 3, 2, 1, "deep-s2"),          # the same through BackwardData's stride phases
+    Shape(3, 24, 56, 56, 64, 3, 3, 1, 1, "k64-wide"),          # 64-row tiles over many column tiles
+    Shape(3, 96, 56, 56, 96, 3, 3, 1, 1, "c96-wide"),          # 96-row tiles, Forward and BackwardData, many column tiles
 ]
 
 DIVISIONS = {8: [[8], [1] * 8, [3, 5]], 5: [[5], [2, 3]], 4: [[4], [1, 3]], 3: [[3], [1, 2]],
