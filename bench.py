@@ -72,7 +72,7 @@ def parse():
     ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"],
                     help="bf16: x, w, dy, y, dx stored as bfloat16 (dw and workspaces fp32, fp32 arithmetic)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-samples", type=int, default=4)
+    ap.add_argument("--cpu-samples", type=int, default=24)
     ap.add_argument("--bench-db", default=None,
                     help="benchmark database file: loaded before planning if it exists, saved afterwards")
     return ap.parse_args()
