@@ -198,6 +198,7 @@ struct GatherParams {
 template <int TD, bool SMALL, class E = float>
 struct GatherNLaneT : NoSetup {
     static constexpr uint32_t EB = Elem<E>::kBytes;
+    static constexpr bool kBf16 = std::is_same<E, bf16>::value;
     static std::string name() { return std::string(SMALL ? "GatherNLane<taps<=31>" : "GatherNLane<taps>31>") + Elem<E>::tag(); }
     static_assert(TD >= 64, "a wave must cover one reduction row");
     static constexpr int RP = kThreads / TD;  // reduction rows per pass
@@ -269,6 +270,9 @@ struct GatherNLaneT : NoSetup {
         }
         r[i] = Elem<E>::load(rsrc, vo, so);
     }
+    // reduction row (within the step) and tile position of the thread's element i
+    __device__ __forceinline__ int erow(int i) const { return row0 + RP * i; }
+    __device__ __forceinline__ int ecol(int i) const { return col; }
     __device__ __forceinline__ void store(float *lds, int i, const float (&r)[NE]) const
     {
         lds[(row0 + RP * i) * LD + col] = r[i];
@@ -313,6 +317,7 @@ struct KLaneParams {
 template <int TD, class E = float>
 struct KLane0T : NoSetup {
     static constexpr uint32_t EB = Elem<E>::kBytes;
+    static constexpr bool kBf16 = std::is_same<E, bf16>::value;
     static std::string name() { return std::string("KLane0") + Elem<E>::tag(); }
     static constexpr int CP = kThreads / kBK;  // tile positions per pass (16)
     static constexpr int NE = TD / CP;
@@ -343,6 +348,9 @@ struct KLane0T : NoSetup {
     {
         r[i] = Elem<E>::load(rsrc, vo_, EB * (uint32_t)(k0_ * p->row_stride + CP * i * p->col_stride));
     }
+    // reduction row (within the step) and tile position of the thread's element i
+    __device__ __forceinline__ int erow(int i) const { return kl; }
+    __device__ __forceinline__ int ecol(int i) const { return c0 + CP * i; }
     __device__ __forceinline__ void store(float *lds, int i, const float (&r)[NE]) const
     {
         lds[kl * LD + c0 + CP * i] = r[i];
@@ -356,6 +364,7 @@ template <int TD> using KLane0 = KLane0T<TD, float>;
 template <int TD, class E = float>
 struct FilterKLaneT : NoSetup {
     static constexpr uint32_t EB = Elem<E>::kBytes;
+    static constexpr bool kBf16 = std::is_same<E, bf16>::value;
     static std::string name() { return std::string("FilterKLane") + Elem<E>::tag(); }
     static constexpr int CP = kThreads / kBK;
     static constexpr int NE = TD / CP;
@@ -396,6 +405,9 @@ struct FilterKLaneT : NoSetup {
     {
         r[i] = Elem<E>::load(rsrc, vo_, EB * (uint32_t)(CP * i * p->col_stride));
     }
+    // reduction row (within the step) and tile position of the thread's element i
+    __device__ __forceinline__ int erow(int i) const { return kl; }
+    __device__ __forceinline__ int ecol(int i) const { return c0 + CP * i; }
     __device__ __forceinline__ void store(float *lds, int i, const float (&r)[NE]) const
     {
         lds[kl * LD + c0 + CP * i] = r[i];
@@ -414,6 +426,7 @@ template <int TD> using FilterKLane = FilterKLaneT<TD, float>;
 template <int TD, bool WINDOW, class E = float>
 struct PixelKLane : NoSetup {
     static constexpr uint32_t EB = Elem<E>::kBytes;
+    static constexpr bool kBf16 = std::is_same<E, bf16>::value;
     static std::string name() { return std::string(WINDOW ? "PixelKLane<x>" : "PixelKLane<dy>") + Elem<E>::tag(); }
     static constexpr int CP = kThreads / kBK;
     static constexpr int NE = TD / CP;
@@ -487,6 +500,9 @@ struct PixelKLane : NoSetup {
             r[i] = Elem<E>::load(rsrc, (t << 31) | (vo_ + coffb[i]), 0);
         }
     }
+    // reduction row (within the step) and tile position of the thread's element i
+    __device__ __forceinline__ int erow(int i) const { return kl; }
+    __device__ __forceinline__ int ecol(int i) const { return c0 + CP * i; }
     __device__ __forceinline__ void store(float *lds, int i, const float (&r)[NE]) const
     {
         lds[kl * LD + c0 + CP * i] = r[i];
@@ -513,6 +529,7 @@ struct PixelTable {
 template <int TD, class E = float>
 struct PixelTabX {
     static constexpr uint32_t EB = Elem<E>::kBytes;
+    static constexpr bool kBf16 = std::is_same<E, bf16>::value;
     static std::string name() { return std::string("PixelTab<x>") + Elem<E>::tag(); }
     static constexpr int CP = kThreads / kBK;
     static constexpr int NE = TD / CP;
@@ -594,6 +611,9 @@ struct PixelTabX {
         const uint32_t t = mask_ >> tapbit[i];
         r[i] = Elem<E>::load(rsrc, (t << 31) | (xo_ + coffb[i]), 0);
     }
+    // reduction row (within the step) and tile position of the thread's element i
+    __device__ __forceinline__ int erow(int i) const { return kl; }
+    __device__ __forceinline__ int ecol(int i) const { return c0 + CP * i; }
     __device__ __forceinline__ void store(float *lds, int i, const float (&r)[NE]) const
     {
         lds[kl * LD + c0 + CP * i] = r[i];
@@ -603,6 +623,7 @@ struct PixelTabX {
 template <int TD, class E = float>
 struct PixelTabDy : NoSetup {
     static constexpr uint32_t EB = Elem<E>::kBytes;
+    static constexpr bool kBf16 = std::is_same<E, bf16>::value;
     static std::string name() { return std::string("PixelTab<dy>") + Elem<E>::tag(); }
     static constexpr int CP = kThreads / kBK;
     static constexpr int NE = TD / CP;
@@ -634,6 +655,9 @@ struct PixelTabDy : NoSetup {
         const uint32_t step = EB * (uint32_t)(CP * p->Ht * p->Wt);  // scalar: 16 channels further
         r[i] = Elem<E>::load(rsrc, vo_, step * (uint32_t)i);
     }
+    // reduction row (within the step) and tile position of the thread's element i
+    __device__ __forceinline__ int erow(int i) const { return kl; }
+    __device__ __forceinline__ int ecol(int i) const { return c0 + CP * i; }
     __device__ __forceinline__ void store(float *lds, int i, const float (&r)[NE]) const
     {
         lds[kl * LD + c0 + CP * i] = r[i];
@@ -650,6 +674,7 @@ struct DenseParams {
 
 template <int TD>
 struct DenseNLane : NoSetup {
+    static constexpr bool kBf16 = false;
     static const char *name() { return "DenseNLane"; }
     static constexpr int CQ = TD / 4;          // float4 columns per row
     static constexpr int RP = kThreads / CQ;   // rows per pass
@@ -696,6 +721,7 @@ struct DenseNLane : NoSetup {
 template <int TD, class E = float>
 struct DenseNLaneST : NoSetup {
     static constexpr uint32_t EB = Elem<E>::kBytes;
+    static constexpr bool kBf16 = std::is_same<E, bf16>::value;
     static std::string name() { return std::string("DenseNLaneS") + Elem<E>::tag(); }
     static constexpr int RP = kThreads / TD;
     static constexpr int NE = kBK / RP;
@@ -728,6 +754,9 @@ struct DenseNLaneST : NoSetup {
         const int kk = k0_ + row0 + RP * i;
         r[i] = Elem<E>::load(rsrc, (kk < k_end_ && ok_) ? (uint32_t)(kk * p->ld + j_) * EB : kOob, 0);
     }
+    // reduction row (within the step) and tile position of the thread's element i
+    __device__ __forceinline__ int erow(int i) const { return row0 + RP * i; }
+    __device__ __forceinline__ int ecol(int i) const { return col; }
     __device__ __forceinline__ void store(float *lds, int i, const float (&r)[NE]) const
     {
         lds[(row0 + RP * i) * LD + col] = r[i];
@@ -823,6 +852,77 @@ struct EpiAtomic {
     }
 };
 
+// What a workgroup computes: a tile and a range of reduction rows; `accumulate` = it adds a partial
+// result (one chunk of a tail tile) instead of storing.
+struct WorkItem {
+    int m0, n0, k_begin, k_end;
+    bool accumulate;
+};
+template <class T, class Epi>
+__device__ __forceinline__ WorkItem work_item(int Kd, int k_chunk, int tiles_m, int tiles_n, const TailSplit &tail)
+{
+    int tile_m, tile_n, split;
+    WorkItem w;
+    w.accumulate = false;
+    if (Epi::kCanAdd && tail.tiles > 0) {
+        const int whole = tiles_m * tiles_n - tail.tiles;
+        int t;
+        if ((int)blockIdx.x < whole) {
+            t = (int)xcd_order(blockIdx.x, (uint32_t)whole);
+            split = 0;
+        } else {
+            const int r = (int)blockIdx.x - whole;
+            t = whole + r / tail.splits;
+            split = r % tail.splits;
+            k_chunk = tail.chunk;
+            w.accumulate = true;
+        }
+        tile_m = t % tiles_m;
+        tile_n = t / tiles_m;
+    } else {
+        xcd_tile(tiles_m, tiles_n, tile_m, tile_n, split);
+    }
+    w.m0 = tile_m * T::BM;
+    w.n0 = tile_n * T::BN;
+    w.k_begin = split * k_chunk;
+    w.k_end = min(Kd, w.k_begin + k_chunk);
+    return w;
+}
+
+// Stores (or adds) a wave's accumulators.  Element v of a 32x32 MFMA tile: row
+// 8*(v/4) + 4*(lane/32) + v%4, column lane%32.  A wave's WM MFMA tiles along M are interleaved:
+// MFMA row r of tile i is wave row WM*r + i, so that a lane's A operands of one reduction row are
+// adjacent in LDS and come in one read with an immediate offset.  Columns are not interleaved:
+// consecutive lanes must keep consecutive output columns, or every store would touch only every
+// other element of a cache line (that cost the bandwidth-bound 1x1 layers a quarter of their speed).
+template <class T, class Epi>
+__device__ __forceinline__ void write_tile(const typename Epi::Params &pe, const f32x16 (&acc)[T::WM][T::WN], int M,
+                                           int N, int m0, int n0, int wm0, int wn0, int l32, int lhi,
+                                           bool accumulate)
+{
+    Epi epi;
+#pragma unroll
+    for (int j = 0; j < T::WN; ++j) {
+        const int col = n0 + wn0 + j * 32 + l32;
+        if (col >= N) continue;
+        epi.prep(pe, col);
+#pragma unroll
+        for (int i = 0; i < T::WM; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = m0 + wm0 + T::WM * (8 * (v / 4) + 4 * lhi + (v % 4)) + i;
+                if (row < M) {
+                    if constexpr (Epi::kCanAdd) {
+                        if (accumulate) epi.add(pe, row, acc[i][j][v]);
+                        else epi.store(pe, row, acc[i][j][v]);
+                    } else {
+                        epi.store(pe, row, acc[i][j][v]);
+                    }
+                }
+            }
+    }
+}
+
 // ---- the kernel --------------------------------------------------------------------------------
 // grid.x = tiles_m * tiles_n (XCD-remapped), grid.y = reduction splits (chunk `k_chunk`, a multiple
 // of BK), grid.z = batch of independent GEMMs (loaders/epilogue see pointers advanced by the
@@ -840,29 +940,9 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(AParams pa, BParams pb, 
         pb.t = (const float *)pb.t + b_batch * blockIdx.z;
         pe.out = (float *)pe.out + c_batch * blockIdx.z;
     }
-    int tile_m, tile_n, split;
-    bool accumulate = false;  // this workgroup adds a partial result (a chunk of a tail tile)
-    if (Epi::kCanAdd && tail.tiles > 0) {
-        const int whole = tiles_m * tiles_n - tail.tiles;
-        int t;
-        if ((int)blockIdx.x < whole) {
-            t = (int)xcd_order(blockIdx.x, (uint32_t)whole);
-            split = 0;
-        } else {
-            const int r = (int)blockIdx.x - whole;
-            t = whole + r / tail.splits;
-            split = r % tail.splits;
-            k_chunk = tail.chunk;
-            accumulate = true;
-        }
-        tile_m = t % tiles_m;
-        tile_n = t / tiles_m;
-    } else {
-        xcd_tile(tiles_m, tiles_n, tile_m, tile_n, split);
-    }
-    const int m0 = tile_m * T::BM, n0 = tile_n * T::BN;
-    const int k_begin = split * k_chunk;
-    const int k_end = min(Kd, k_begin + k_chunk);
+    const WorkItem wi = work_item<T, Epi>(Kd, k_chunk, tiles_m, tiles_n, tail);
+    const int m0 = wi.m0, n0 = wi.n0, k_begin = wi.k_begin, k_end = wi.k_end;
+    const bool accumulate = wi.accumulate;
 
     __shared__ typename ALoader::Shared sha;
     __shared__ typename BLoader::Shared shb;
@@ -984,33 +1064,147 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(AParams pa, BParams pb, 
         buf ^= 1;
     }
 
-    // accumulator element v of a 32x32 MFMA tile: row 8*(v/4) + 4*(lane/32) + v%4, column lane%32.
-    // A wave's WM MFMA tiles along M are interleaved: MFMA row r of tile i is wave row WM*r + i, so
-    // that a lane's A operands of one k-row are adjacent in LDS and come in one read with an
-    // immediate offset.  Columns are not interleaved: consecutive lanes must keep consecutive
-    // output columns, or every store would touch only every other element of a cache line (that
-    // cost the bandwidth-bound 1x1 layers a quarter of their speed).
-    Epi epi;
+    write_tile<T, Epi>(pe, acc, M, N, m0, n0, wm0, wn0, l32, lhi, accumulate);
+}
+
+// ---- the same GEMM on the bf16 matrix pipe -----------------------------------------------------
+// Both operands are bf16 tensors: the tiles are kept in LDS as bf16, eight consecutive reduction
+// rows of one tile position in one 16-byte cell ([BK/8][tile + pad][8]), which is exactly the
+// operand of v_mfma_f32_32x32x16_bf16 for the lane that owns that position (lanes 0-31 take rows
+// 0-7 of the step, lanes 32-63 rows 8-15, for A and B alike, so the products pair up whatever the
+// instruction's internal order).  One MFMA per 32x32 tile covers a whole step of BK = 16 rows,
+// 8 times the fp32 rate, so the loop is bound by its loads and LDS traffic rather than by the
+// matrix pipe; the pipeline is the fp32 kernel's (two tiles deep, one register set, memory work
+// dealt out behind the MFMAs).  The loaders hand over fp32-widened values; the LDS store writes
+// their upper 16 bits back, which costs no instruction.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+template <class T>
+struct HalfTile {
+    static constexpr int kCellPad = 4;  // cells of padding per 8-row plane (shifts the planes by 16 banks)
+    static constexpr int PA = T::BM + kCellPad, PB = T::BN + kCellPad;  // cells per plane
+    static constexpr int A_HALFS = (kBK / 8) * PA * 8, B_HALFS = (kBK / 8) * PB * 8;
+    static constexpr int HALFS = A_HALFS + B_HALFS;
+};
+
+template <class T, class ALoader, class BLoader, class Epi, class AParams, class BParams>
+__global__ __launch_bounds__(kThreads) void gemm_kernel_bf16(AParams pa, BParams pb, typename Epi::Params pe,
+                                                              int M, int N, int Kd, int k_chunk, int tiles_m,
+                                                              int tiles_n, TailSplit tail)
+{
+    typedef HalfTile<T> H;
+    __shared__ __attribute__((aligned(16))) uint16_t lds[2][H::HALFS];
+
+    const WorkItem wi = work_item<T, Epi>(Kd, k_chunk, tiles_m, tiles_n, tail);
+    const int m0 = wi.m0, n0 = wi.n0, k_begin = wi.k_begin, k_end = wi.k_end;
+
+    __shared__ typename ALoader::Shared sha;
+    __shared__ typename BLoader::Shared shb;
+    ALoader la;
+    BLoader lb;
+    la.init(pa, m0, M);
+    lb.init(pb, n0, N);
+    la.setup(sha, k_begin, k_end, lb);
+    lb.setup(shb, k_begin, k_end, la);
+    if constexpr (ALoader::kHasShared || BLoader::kHasShared) __syncthreads();
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm0 = (wave % T::WAVES_M) * (T::WM * 32);
+    const int wn0 = (wave / T::WAVES_M) * (T::WN * 32);
+    const int l32 = lane & 31, lhi = lane >> 5;
+
+    f32x16 acc[T::WM][T::WN];
 #pragma unroll
-    for (int j = 0; j < T::WN; ++j) {
-        const int col = n0 + wn0 + j * 32 + l32;
-        if (col >= N) continue;
-        epi.prep(pe, col);
+    for (int i = 0; i < T::WM; ++i)
+#pragma unroll
+        for (int j = 0; j < T::WN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    typename ALoader::Regs ra;
+    typename BLoader::Regs rb;
+    constexpr int NA = ALoader::NE, NB = BLoader::NE, NM = T::WM * T::WN;
+
+    // element (row, position) of a tile -> halfword index of its place in the [BK/8][P][8] layout
+    auto put_a = [&](uint16_t *buf, int i) {
+        const int row = la.erow(i), col = la.ecol(i);
+        buf[((row >> 3) * H::PA + col) * 8 + (row & 7)] = (uint16_t)(__float_as_uint(ra.r[i]) >> 16);
+    };
+    auto put_b = [&](uint16_t *buf, int i) {
+        const int row = lb.erow(i), col = lb.ecol(i);
+        buf[H::A_HALFS + ((row >> 3) * H::PB + col) * 8 + (row & 7)] = (uint16_t)(__float_as_uint(rb.r[i]) >> 16);
+    };
+
+    la.prep(k_begin, k_end, lb);
+    lb.prep(k_begin, k_end, la);
+#pragma unroll
+    for (int i = 0; i < NA; ++i) la.load(i, ra.r);
+#pragma unroll
+    for (int i = 0; i < NB; ++i) lb.load(i, rb.r);
+#pragma unroll
+    for (int i = 0; i < NA; ++i) put_a(lds[0], i);
+#pragma unroll
+    for (int i = 0; i < NB; ++i) put_b(lds[0], i);
+    la.prep(k_begin + kBK, k_end, lb);
+    lb.prep(k_begin + kBK, k_end, la);
+#pragma unroll
+    for (int i = 0; i < NA; ++i) la.load(i, ra.r);
+#pragma unroll
+    for (int i = 0; i < NB; ++i) lb.load(i, rb.r);
+    __syncthreads();
+
+    int buf = 0;
+    for (int k0 = k_begin; k0 < k_end; k0 += kBK) {
+        if constexpr (ALoader::kHasShared || BLoader::kHasShared) {
+            if (k0 != k_begin && ((k0 - k_begin) & (kTabRows - 1)) == 0) {
+                __syncthreads();
+                la.setup(sha, k0, k_end, lb);
+                lb.setup(shb, k0, k_end, la);
+                __syncthreads();
+            }
+        }
+        const uint16_t *cur = lds[buf];
+        uint16_t *nxt = lds[buf ^ 1];
+        // the step's operands: one 16-byte cell per MFMA tile and lane (rows 8*lhi .. 8*lhi+7)
+        bf16x8 a[T::WM], b[T::WN];
 #pragma unroll
         for (int i = 0; i < T::WM; ++i)
+            a[i] = __builtin_bit_cast(
+                bf16x8, *reinterpret_cast<const u32x4 *>(cur + (lhi * H::PA + wm0 + T::WM * l32 + i) * 8));
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = m0 + wm0 + T::WM * (8 * (v / 4) + 4 * lhi + (v % 4)) + i;
-                if (row < M) {
-                    if constexpr (Epi::kCanAdd) {
-                        if (accumulate) epi.add(pe, row, acc[i][j][v]);
-                        else epi.store(pe, row, acc[i][j][v]);
-                    } else {
-                        epi.store(pe, row, acc[i][j][v]);
-                    }
+        for (int j = 0; j < T::WN; ++j)
+            b[j] = __builtin_bit_cast(
+                bf16x8, *reinterpret_cast<const u32x4 *>(cur + H::A_HALFS + (lhi * H::PB + wn0 + j * 32 + l32) * 8));
+        la.prep(k0 + 2 * kBK, k_end, lb);
+        lb.prep(k0 + 2 * kBK, k_end, la);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int m = 0; m < NM; ++m) {
+            const int mi = m / T::WN, mj = m % T::WN;
+            acc[mi][mj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], b[mj], acc[mi][mj], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            // this MFMA's share of the memory work: tile s+1 registers -> LDS, then reloaded with tile s+2
+#pragma unroll
+            for (int i = 0; i < NA; ++i)
+                if (i * NM / NA == m) {
+                    put_a(nxt, i);
+                    la.load(i, ra.r);
                 }
-            }
+#pragma unroll
+            for (int i = 0; i < NB; ++i)
+                if (i * NM / NB == m) {
+                    put_b(nxt, i);
+                    lb.load(i, rb.r);
+                }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        __syncthreads();
+        buf ^= 1;
     }
+
+    write_tile<T, Epi>(pe, acc, M, N, m0, n0, wm0, wn0, l32, lhi, wi.accumulate);
 }
 
 // Zero-fills the outputs of the last `tail_tiles` tiles through the epilogue's own index mapping.

@@ -22,6 +22,9 @@ template <class T, template <int> class AL, template <int> class BL, class Epi, 
 hipError_t launch_tile(const AP &pa, const BP &pb, const typename Epi::Params &pe, const GemmShape &g,
                        hipStream_t s)
 {
+    // both operands bf16 tensors: the kernel on the bf16 matrix pipe (single GEMMs only)
+    constexpr bool kBf16Mfma = AL<T::BM>::kBf16 && BL<T::BN>::kBf16;
+    if (kBf16Mfma && g.batch != 1) return hipErrorInvalidValue;
     const int tiles_m = (g.M + T::BM - 1) / T::BM, tiles_n = (g.N + T::BN - 1) / T::BN;
     if (tiles_m <= 0 || tiles_n <= 0) return hipSuccess;
     int splits = g.splits < 1 ? 1 : g.splits;
@@ -51,7 +54,7 @@ hipError_t launch_tile(const AP &pa, const BP &pb, const typename Epi::Params &p
     dim3 grid(gx, (unsigned)splits, (unsigned)g.batch);
     if (LaunchLog *log = launch_log()) {
         if (tail.tiles) log->add("zero_tiles_kernel");
-        log->add(std::string("gemm_kernel<Tile<") + std::to_string(T::BM) + "x" + std::to_string(T::BN) + ">," +
+        log->add(std::string(kBf16Mfma ? "gemm_kernel_bf16<Tile<" : "gemm_kernel<Tile<") + std::to_string(T::BM) + "x" + std::to_string(T::BN) + ">," +
                  AL<T::BM>::name() + "," + BL<T::BN>::name() + "," + Epi::name() + "> tiles=" +
                  std::to_string(tiles_m * tiles_n) + " splits=" + std::to_string(splits) + " batch=" +
                  std::to_string(g.batch) +
@@ -63,8 +66,12 @@ hipError_t launch_tile(const AP &pa, const BP &pb, const typename Epi::Params &p
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    gemm_kernel<T, AL<T::BM>, BL<T::BN>, Epi, AP, BP><<<grid, kThreads, 0, s>>>(
-        pa, pb, pe, g.M, g.N, g.Kd, k_chunk, tiles_m, tiles_n, g.a_batch, g.b_batch, g.c_batch, tail);
+    if constexpr (kBf16Mfma)
+        gemm_kernel_bf16<T, AL<T::BM>, BL<T::BN>, Epi, AP, BP><<<grid, kThreads, 0, s>>>(
+            pa, pb, pe, g.M, g.N, g.Kd, k_chunk, tiles_m, tiles_n, tail);
+    else
+        gemm_kernel<T, AL<T::BM>, BL<T::BN>, Epi, AP, BP><<<grid, kThreads, 0, s>>>(
+            pa, pb, pe, g.M, g.N, g.Kd, k_chunk, tiles_m, tiles_n, g.a_batch, g.b_batch, g.c_batch, tail);
     return hipGetLastError();
 }
 
