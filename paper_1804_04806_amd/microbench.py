@@ -16,6 +16,8 @@ def main():
     ap.add_argument("--op", default="fwd", choices=["fwd", "bwd_data", "bwd_filter"])
     ap.add_argument("--algo", default="implicit", choices=["implicit", "im2col", "winograd"])
     ap.add_argument("--b", type=int, default=256)
+    ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"],
+                    help="bf16: x, w, dy, y, dx stored as bfloat16 (dw fp32)")
     ap.add_argument("--reps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--copy-mib", type=int, default=0,
@@ -68,13 +70,16 @@ def main():
     op = {"fwd": ucd.FWD, "bwd_data": ucd.BWD_DATA, "bwd_filter": ucd.BWD_FILTER}[args.op]
     algo = {"implicit": ucd.ALGO_IMPLICIT, "im2col": ucd.ALGO_IM2COL, "winograd": ucd.ALGO_WINOGRAD}[args.algo]
     dev = torch.device("cuda:0")
-    desc = ucd.layer(s)
+    desc = ucd.layer(s, dtype=1 if args.dtype == "bf16" else 0)
     need = ucd.ucd_workspace_size(desc, op, algo, args.b)
     if need == ucd.WS_NA:
         raise SystemExit("algorithm does not apply to this layer/operation")
-    x = torch.from_numpy(synth.make_x(s)).to(dev)
-    w = torch.from_numpy(synth.make_w(s)).to(dev)
-    y = torch.from_numpy(synth.make_dy(s)).to(dev)
+    td = torch.bfloat16 if args.dtype == "bf16" else torch.float32
+    x = torch.from_numpy(synth.make_x(s)).to(dev).to(td)
+    w = torch.from_numpy(synth.make_w(s)).to(dev).to(td)
+    y = torch.from_numpy(synth.make_dy(s)).to(dev).to(td)
+    if op == ucd.BWD_FILTER:
+        w = w.float()   # dw is fp32 for every dtype
     ws = torch.empty(max(need, 4) // 4, dtype=torch.float32, device=dev)
     a, bsrc, out = {ucd.FWD: (x, w, y), ucd.BWD_DATA: (y, w, x), ucd.BWD_FILTER: (x, y, w)}[op]
     beta = 1.0 if op == ucd.BWD_FILTER else 0.0
