@@ -102,6 +102,7 @@ struct NoShared {};
 struct NoSetup {
     typedef NoShared Shared;
     static constexpr bool kHasShared = false;
+    static constexpr bool kCellStore = false;  // see GatherNLaneT
     template <class Peer>
     __device__ __forceinline__ void setup(Shared &, int, int, const Peer &) {}
 };
@@ -109,7 +110,8 @@ struct NoSetup {
 // ---- operand loaders ---------------------------------------------------------------------------
 // Common interface:  init(params, tile_origin, extent)  once per workgroup;
 //                    prep(k0, k_end, peer)   per-step state for reduction rows [k0, k0+BK);
-//                    load(i, regs)           global -> register, element i of the thread's NE;
+//                    load(i, regs)           global -> register, element i of the thread's NE
+//                                            (called for i = 0 .. NE-1 in order, once per step);
 //                    store(lds_tile, i, regs) register -> LDS tile laid out [BK][LD].
 // Any k0 is legal: rows at or past k_end read as 0 (the main loop prefetches two tiles ahead and
 // does not special-case the end of the reduction).
@@ -204,6 +206,9 @@ struct GatherNLaneT : NoSetup {
     static constexpr int RP = kThreads / TD;  // reduction rows per pass
     static constexpr int NE = kBK / RP;       // elements per thread per step
     static constexpr int LD = TD + kPad;
+    // A thread takes a block of NE consecutive rows of the step (NE*row0 + i): their decode is
+    // incremental, and in the bf16 kernel the block is a whole run of an LDS cell, written in one piece.
+    static constexpr bool kCellStore = kBf16;
     struct Regs { float r[NE]; };
     const GatherParams *p;
     __amdgpu_buffer_rsrc_t rsrc;
@@ -211,12 +216,19 @@ struct GatherNLaneT : NoSetup {
     uint32_t nmask, nmask_w;  // bit set = tap outside the image (bit 31 always set)
     int col, row0;
     int k0_, k_end_;
+    uint32_t tap_, tr_, ts_, so_;   // (tap, r, s) and scalar byte offset of the row last loaded
+    uint32_t d_tap, e_row, e_chan;  // what that offset grows by per tap, and on top of it when the
+                                    // tap starts a new filter row / a new channel
 
     __device__ __forceinline__ void init(const GatherParams &prm, int origin, int extent)
     {
         p = &prm;
         const int shift = prm.shift_thread + prm.shift_row;
         rsrc = make_rsrc_bytes(prm.t, (long)EB * shift, prm.bytes + EB * (uint32_t)shift);
+        tap_ = tr_ = ts_ = so_ = 0;
+        d_tap = EB * (uint32_t)prm.dir;
+        e_row = EB * (uint32_t)(prm.dir * (prm.Wt - prm.n_tap_w));                  // (r, S-1) -> (r+1, 0)
+        e_chan = EB * (uint32_t)(prm.Ht * prm.Wt - prm.dir * prm.n_tap_h * prm.Wt);  // (c, R-1, .) -> (c+1, 0, .)
         const int tid = threadIdx.x;
         col = tid % TD;
         row0 = __builtin_amdgcn_readfirstlane(tid / TD);
@@ -251,31 +263,50 @@ struct GatherNLaneT : NoSetup {
         k0_ = k0;
         k_end_ = k_end;
     }
-    __device__ __forceinline__ void load(int i, float (&r)[NE]) const
+    // Must be called for i = 0, 1, ..., NE-1 in that order each step: the thread's rows are
+    // consecutive, so only the first is decoded by division and the others step the (c, r, s)
+    // counters.  Everything up to `so` is wave-uniform and runs on the scalar unit, which all waves
+    // of a CU share: with the bf16 matrix pipe the decode, not the MFMAs, sets the pace.
+    __device__ __forceinline__ void load(int i, float (&r)[NE])
     {
-        const int kk = k0_ + row0 + RP * i;  // wave-uniform: everything up to `so` is scalar
-        uint32_t c, tap, tr, ts;
-        p->taps.divmod((uint32_t)kk, c, tap);
-        p->taps_w.divmod(tap, tr, ts);
-        const uint32_t dead = (uint32_t)((k_end_ - 1 - kk) >> 31);  // all ones for rows past the end
-        const uint32_t so =
-            ~dead & (EB * (uint32_t)(((int)c * p->Ht + p->dir * (int)tr) * p->Wt + p->dir * (int)ts + p->shift_row));
+        const int kk = k0_ + erow(i);
+        if (i == 0) {
+            uint32_t c;
+            p->taps.divmod((uint32_t)kk, c, tap_);
+            p->taps_w.divmod(tap_, tr_, ts_);
+            so_ = EB * (uint32_t)(((int)c * p->Ht + p->dir * (int)tr_) * p->Wt + p->dir * (int)ts_ + p->shift_row);
+        } else {  // one row further: next tap, which may be the next filter row or the next channel
+            ++tap_;
+            ++ts_;
+            const bool row_wrap = ts_ == p->taps_w.d, chan_wrap = tap_ == p->taps.d;  // the second implies the first
+            so_ += d_tap + (row_wrap ? e_row : 0u) + (chan_wrap ? e_chan : 0u);
+            ts_ = row_wrap ? 0u : ts_;
+            tap_ = chan_wrap ? 0u : tap_;
+            if (!SMALL) tr_ = chan_wrap ? 0u : tr_ + (row_wrap ? 1u : 0u);
+        }
+        // wave-uniform by construction; saying so keeps the counters on the scalar unit
+        tap_ = (uint32_t)__builtin_amdgcn_readfirstlane((int)tap_);
+        ts_ = (uint32_t)__builtin_amdgcn_readfirstlane((int)ts_);
+        tr_ = (uint32_t)__builtin_amdgcn_readfirstlane((int)tr_);
+        so_ = (uint32_t)__builtin_amdgcn_readfirstlane((int)so_);
+        const bool dead = kk >= k_end_;  // rows past the end read as zero
+        const uint32_t so = dead ? 0u : so_;
         uint32_t vo;
         if (SMALL) {
-            const uint32_t bit = tap | (dead & 31u);
+            const uint32_t bit = dead ? 31u : tap_;
             vo = ((nmask >> bit) << 31) | voff;
         } else {
-            const uint32_t bit = tr | (dead & 31u);
-            vo = (((nmask >> bit) | (nmask_w >> ts)) << 31) | voff;
+            const uint32_t bit = dead ? 31u : tr_;
+            vo = (((nmask >> bit) | (nmask_w >> ts_)) << 31) | voff;
         }
         r[i] = Elem<E>::load(rsrc, vo, so);
     }
     // reduction row (within the step) and tile position of the thread's element i
-    __device__ __forceinline__ int erow(int i) const { return row0 + RP * i; }
+    __device__ __forceinline__ int erow(int i) const { return NE * row0 + i; }
     __device__ __forceinline__ int ecol(int i) const { return col; }
     __device__ __forceinline__ void store(float *lds, int i, const float (&r)[NE]) const
     {
-        lds[(row0 + RP * i) * LD + col] = r[i];
+        lds[erow(i) * LD + col] = r[i];
     }
 };
 template <int TD> using GatherNLane = GatherNLaneT<TD, true>;
@@ -536,6 +567,7 @@ struct PixelTabX {
     static constexpr int LD = TD + kPad;
     typedef PixelTable Shared;
     static constexpr bool kHasShared = true;
+    static constexpr bool kCellStore = false;
     struct Regs { float r[NE]; };
     const KLaneParams *p;
     __amdgpu_buffer_rsrc_t rsrc;
@@ -1136,6 +1168,22 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel_bf16(AParams pa, BParams
         const int row = lb.erow(i), col = lb.ecol(i);
         buf[H::A_HALFS + ((row >> 3) * H::PB + col) * 8 + (row & 7)] = (uint16_t)(__float_as_uint(rb.r[i]) >> 16);
     };
+    // a loader whose thread owns NB consecutive rows of one position writes them as one vector
+    auto put_b_cells = [&](uint16_t *buf) {
+        const int row = lb.erow(0), col = lb.ecol(0);
+        uint32_t *dst = reinterpret_cast<uint32_t *>(buf + H::A_HALFS + ((row >> 3) * H::PB + col) * 8 + (row & 7));
+        uint32_t w[NB / 2];
+#pragma unroll
+        for (int i = 0; i < NB / 2; ++i)
+            w[i] = (__float_as_uint(rb.r[2 * i]) >> 16) | (__float_as_uint(rb.r[2 * i + 1]) & 0xFFFF0000u);
+        if constexpr (NB == 8) {
+            u32x4 v = {w[0], w[1], w[2], w[3]};
+            *reinterpret_cast<u32x4 *>(dst) = v;
+        } else {
+#pragma unroll
+            for (int i = 0; i < NB / 2; ++i) dst[i] = w[i];
+        }
+    };
 
     la.prep(k_begin, k_end, lb);
     lb.prep(k_begin, k_end, la);
@@ -1145,8 +1193,12 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel_bf16(AParams pa, BParams
     for (int i = 0; i < NB; ++i) lb.load(i, rb.r);
 #pragma unroll
     for (int i = 0; i < NA; ++i) put_a(lds[0], i);
+    if constexpr (BLoader::kCellStore) {
+        put_b_cells(lds[0]);
+    } else {
 #pragma unroll
-    for (int i = 0; i < NB; ++i) put_b(lds[0], i);
+        for (int i = 0; i < NB; ++i) put_b(lds[0], i);
+    }
     la.prep(k_begin + kBK, k_end, lb);
     lb.prep(k_begin + kBK, k_end, la);
 #pragma unroll
@@ -1192,10 +1244,11 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel_bf16(AParams pa, BParams
                     put_a(nxt, i);
                     la.load(i, ra.r);
                 }
+            if (BLoader::kCellStore && m == 0) put_b_cells(nxt);  // all of tile s+1 at once, before any reload
 #pragma unroll
             for (int i = 0; i < NB; ++i)
                 if (i * NM / NB == m) {
-                    put_b(nxt, i);
+                    if constexpr (!BLoader::kCellStore) put_b(nxt, i);
                     lb.load(i, rb.r);
                 }
             __builtin_amdgcn_sched_barrier(0);
