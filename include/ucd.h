@@ -53,10 +53,12 @@ typedef enum {
 } ucd_status_t;
 
 /* dtype 0: every tensor fp32.
- * dtype 1: x, w, dy, y, dx hold bfloat16 (16-bit storage; outputs rounded to nearest-even), dw is
+ * dtype 1: x, w, dy, y, dx hold bfloat16 (outputs rounded to nearest-even), dw is
  *          fp32 (it accumulates over micro-batches with beta = 1) and so is every workspace
- *          matrix; the arithmetic is the fp32 path's (bf16 operands widen exactly), so only the
- *          memory traffic and the output rounding differ from dtype 0.
+ *          matrix.  Products of bf16 values are exact in fp32 and all accumulation is fp32
+ *          (on the bf16 matrix instructions where both operands of a GEMM are bf16 tensors),
+ *          so results differ from dtype 0 on the same values only by summation order and by
+ *          the rounding of y / dx.
  * Layout NCHW / KCRS, dense, groups = 1, dilation = 1. */
 typedef struct {
     int32_t N, C, H, W, K, R, S, stride_h, stride_w, pad_h, pad_w, dtype;

@@ -8,8 +8,8 @@
 
 namespace ucd {
 
-// dtype 0: every tensor fp32.  dtype 1: x, w, dy, y, dx are bf16 (16-bit storage); dw and every
-// workspace matrix stay fp32, and all arithmetic is the fp32 path's.
+// dtype 0: every tensor fp32.  dtype 1: x, w, dy, y, dx are bf16; dw and every workspace matrix
+// stay fp32, accumulation is fp32 everywhere.
 struct Dims {
     int C, H, W, K, R, S, sh, sw, ph, pw, P, Q;
     int dtype;
