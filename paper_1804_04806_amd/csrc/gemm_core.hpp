@@ -209,6 +209,11 @@ struct GatherNLaneT : NoSetup {
     // A thread takes a block of NE consecutive rows of the step (NE*row0 + i): their decode is
     // incremental, and in the bf16 kernel the block is a whole run of an LDS cell, written in one piece.
     static constexpr bool kCellStore = kBf16;
+    // Where the row decode runs.  With the fp32 matrix pipe every vector instruction costs matrix
+    // throughput and the scalar unit is idle: scalar.  With the bf16 pipe the MFMAs are short and
+    // the scalar unit, shared by all waves of a CU, becomes the bottleneck: vector lanes.
+    static constexpr bool kLaneDecode = kBf16;
+    static_assert((NE & (NE - 1)) == 0, "rows per thread: a power of two");
     struct Regs { float r[NE]; };
     const GatherParams *p;
     __amdgpu_buffer_rsrc_t rsrc;
@@ -216,6 +221,7 @@ struct GatherNLaneT : NoSetup {
     uint32_t nmask, nmask_w;  // bit set = tap outside the image (bit 31 always set)
     int col, row0;
     int k0_, k_end_;
+    uint32_t so_v, bit_v, ts_v;     // lane-decoded rows of the step (kLaneDecode)
     uint32_t tap_, tr_, ts_, so_;   // (tap, r, s) and scalar byte offset of the row last loaded
     uint32_t d_tap, e_row, e_chan;  // what that offset grows by per tap, and on top of it when the
                                     // tap starts a new filter row / a new channel
@@ -226,6 +232,8 @@ struct GatherNLaneT : NoSetup {
         const int shift = prm.shift_thread + prm.shift_row;
         rsrc = make_rsrc_bytes(prm.t, (long)EB * shift, prm.bytes + EB * (uint32_t)shift);
         tap_ = tr_ = ts_ = so_ = 0;
+        so_v = ts_v = 0;
+        bit_v = 31;
         d_tap = EB * (uint32_t)prm.dir;
         e_row = EB * (uint32_t)(prm.dir * (prm.Wt - prm.n_tap_w));                  // (r, S-1) -> (r+1, 0)
         e_chan = EB * (uint32_t)(prm.Ht * prm.Wt - prm.dir * prm.n_tap_h * prm.Wt);  // (c, R-1, .) -> (c+1, 0, .)
@@ -262,6 +270,20 @@ struct GatherNLaneT : NoSetup {
     {
         k0_ = k0;
         k_end_ = k_end;
+        if constexpr (kLaneDecode) {
+            // lane i (i < NE) decodes row i of this thread's block; load(i) fetches the result
+            // with a read-lane.  All on the vector unit, which has four times the issue slots of
+            // the scalar unit the waves of a CU share.
+            const int kk = k0 + NE * row0 + (int)(threadIdx.x & (NE - 1));
+            uint32_t c, tap, tr, ts;
+            p->taps.divmod((uint32_t)kk, c, tap);
+            p->taps_w.divmod(tap, tr, ts);
+            const bool dead = kk >= k_end;
+            so_v = dead ? 0u
+                        : EB * (uint32_t)(((int)c * p->Ht + p->dir * (int)tr) * p->Wt + p->dir * (int)ts + p->shift_row);
+            bit_v = dead ? 31u : (SMALL ? tap : tr);
+            ts_v = ts;
+        }
     }
     // Must be called for i = 0, 1, ..., NE-1 in that order each step: the thread's rows are
     // consecutive, so only the first is decoded by division and the others step the (c, r, s)
@@ -269,6 +291,19 @@ struct GatherNLaneT : NoSetup {
     // of a CU share: with the bf16 matrix pipe the decode, not the MFMAs, sets the pace.
     __device__ __forceinline__ void load(int i, float (&r)[NE])
     {
+        if constexpr (kLaneDecode) {
+            const uint32_t so = (uint32_t)__builtin_amdgcn_readlane((int)so_v, i);
+            const uint32_t bit = (uint32_t)__builtin_amdgcn_readlane((int)bit_v, i);
+            uint32_t vo;
+            if (SMALL) {
+                vo = ((nmask >> bit) << 31) | voff;
+            } else {
+                const uint32_t ts = (uint32_t)__builtin_amdgcn_readlane((int)ts_v, i);
+                vo = (((nmask >> bit) | (nmask_w >> ts)) << 31) | voff;
+            }
+            r[i] = Elem<E>::load(rsrc, vo, so);
+            return;
+        }
         const int kk = k0_ + erow(i);
         if (i == 0) {
             uint32_t c;
