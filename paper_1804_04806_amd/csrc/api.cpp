@@ -64,6 +64,10 @@ bool fits_32bit(const ucd_layer_t *L, int b)
            (long long)d.K * d.crs() <= kMaxOperandFloats;
 }
 
+// output tile edge of a Winograd algorithm id
+inline int wino_tile(int algo) { return algo == UCD_ALGO_WINOGRAD4 ? 4 : 2; }
+inline bool is_winograd(int algo) { return algo == UCD_ALGO_WINOGRAD || algo == UCD_ALGO_WINOGRAD4; }
+
 size_t ws_size(const ucd_layer_t *L, int op, int algo, int b)
 {
     if (!L || !layer_ok(L) || op < 0 || op >= UCD_N_OP || b < 1 || b > L->N) return UCD_WS_NA;
@@ -78,9 +82,13 @@ size_t ws_size(const ucd_layer_t *L, int op, int algo, int b)
         if ((long long)d.crs() * ((long long)b * d.P * d.Q + 4) > kMaxOperandFloats) return UCD_WS_NA;
         return im2col_ws_bytes(d, b);
     case UCD_ALGO_WINOGRAD:
+    case UCD_ALGO_WINOGRAD4: {
         if (!winograd_applies(d, op)) return UCD_WS_NA;
-        if (winograd_ws_bytes(d, op, b) / 64 > (size_t)kMaxOperandFloats) return UCD_WS_NA;
-        return winograd_ws_bytes(d, op, b);
+        // every transform plane is one GEMM operand
+        const int mt = wino_tile(algo), planes = (mt + 2) * (mt + 2);
+        if (winograd_ws_bytes(d, op, b, mt) / (4 * planes) > (size_t)kMaxOperandFloats) return UCD_WS_NA;
+        return winograd_ws_bytes(d, op, b, mt);
+    }
     default:
         return UCD_WS_NA;
     }
@@ -110,8 +118,9 @@ int run_micro(const ucd_layer_t *L, int op, int algo, int b, const void *a, cons
         else e = im2col_bwd_filter(d, b, a, bsrc, (float *)out, beta, ws, s);
         break;
     case UCD_ALGO_WINOGRAD:
-        if (op == UCD_FWD) e = winograd_fwd(d, b, a, bsrc, out, ws, filter_ready, s);
-        else if (op == UCD_BWD_DATA) e = winograd_bwd_data(d, b, a, bsrc, out, ws, filter_ready, s);
+    case UCD_ALGO_WINOGRAD4:
+        if (op == UCD_FWD) e = winograd_fwd(d, b, a, bsrc, out, ws, filter_ready, wino_tile(algo), s);
+        else if (op == UCD_BWD_DATA) e = winograd_bwd_data(d, b, a, bsrc, out, ws, filter_ready, wino_tile(algo), s);
         break;
     }
     return hip_status(e);
@@ -137,7 +146,7 @@ int run_plan(const ucd_plan_t *plan, int op, const void *a_, const void *bsrc_, 
     for (const Micro &m : plan->micro) {
         int rc;
         // consecutive Winograd micro-batches of one call share the transformed filter in the workspace
-        const bool filter_ready = m.algo == UCD_ALGO_WINOGRAD && prev_algo == UCD_ALGO_WINOGRAD;
+        const bool filter_ready = is_winograd(m.algo) && prev_algo == m.algo;
         prev_algo = m.algo;
         if (op == UCD_FWD)
             rc = run_micro(L, op, m.algo, m.batch, a + o * x_img, bsrc, out + o * y_img, 0.f, (float *)ws,

@@ -1,16 +1,80 @@
-// Winograd F(2x2,3x3) convolution (Lavin & Gray) for 3x3 stride-1 layers, Forward and
-// BackwardData, with every transform buffer in the caller's workspace:
-//   U[16][Ci][Mo4]   filter transform  U = G g G^T            (Mo4 = out channels rounded up to 4)
-//   V[16][Ci][ld]    input transform   V = B^T d B  per 4x4 input tile at stride 2
-//   Z[16][Mo][ld]    16 independent GEMMs  Z_xi = U_xi^T[Mo x Ci] * V_xi[Ci x b*T]   (MFMA)
-//   out              output transform  y = A^T z A  per 2x2 output tile
-// with T = ceil(Ho/2) * ceil(Wo/2) tiles per image and ld = b*T rounded up to 4.
+// Winograd convolution (Lavin & Gray) for 3x3 stride-1 layers, Forward and BackwardData, in two
+// sizes: F(2x2,3x3) (4x4 input tiles, 16 products per 2x2 outputs) and F(4x4,3x3) (6x6 input tiles,
+// 36 products per 4x4 outputs; interpolation points 0, +-1, +-2, infinity).  With m the output
+// tile edge and a = m + 2 the input tile edge, every transform buffer is in the caller's workspace:
+//   U[a*a][Ci][Mo4]   filter transform  U = G g G^T            (Mo4 = out channels rounded up to 4)
+//   V[a*a][Ci][ld]    input transform   V = B^T d B  per a x a input tile at stride m
+//   Z[a*a][Mo][ld]    a*a independent GEMMs  Z_xi = U_xi^T[Mo x Ci] * V_xi[Ci x b*T]   (MFMA)
+//   out               output transform  y = A^T z A  per m x m output tile
+// with T = ceil(Ho/m) * ceil(Wo/m) tiles per image and ld = b*T rounded up to 4.
 // BackwardData is the same pipeline on dy with the filter's two channel indices swapped and its
 // taps reversed, and padding 2 - pad.
 #include "gemm_launch.hpp"
 #include "kernels.h"
 
 namespace ucd {
+
+// The three one-dimensional transforms of F(m,3); the two-dimensional ones apply them to the
+// columns and then to the rows of a tile.
+template <int MT>
+struct Wino;
+
+template <>
+struct Wino<2> {
+    static constexpr int A = 4;
+    static __device__ __forceinline__ void filter(const float g[3], float u[4])  // G g
+    {
+        u[0] = g[0];
+        u[1] = 0.5f * (g[0] + g[1] + g[2]);
+        u[2] = 0.5f * (g[0] - g[1] + g[2]);
+        u[3] = g[2];
+    }
+    static __device__ __forceinline__ void input(const float d[4], float v[4])  // B^T d
+    {
+        v[0] = d[0] - d[2];
+        v[1] = d[1] + d[2];
+        v[2] = d[2] - d[1];
+        v[3] = d[1] - d[3];
+    }
+    static __device__ __forceinline__ void output(const float z[4], float y[2])  // A^T z
+    {
+        y[0] = z[0] + z[1] + z[2];
+        y[1] = z[1] - z[2] - z[3];
+    }
+};
+
+template <>
+struct Wino<4> {
+    static constexpr int A = 6;
+    static __device__ __forceinline__ void filter(const float g[3], float u[6])
+    {
+        const float e = g[0] + g[2], f = (1.f / 24.f) * g[0] + (1.f / 6.f) * g[2], h = (1.f / 12.f) * g[1];
+        u[0] = 0.25f * g[0];
+        u[1] = (-1.f / 6.f) * (e + g[1]);
+        u[2] = (-1.f / 6.f) * (e - g[1]);
+        u[3] = f + h;
+        u[4] = f - h;
+        u[5] = g[2];
+    }
+    static __device__ __forceinline__ void input(const float d[6], float v[6])
+    {
+        const float a = d[4] - 4.f * d[2], b = d[3] - 4.f * d[1], c = d[4] - d[2], e = 2.f * (d[3] - d[1]);
+        v[0] = 4.f * d[0] - 5.f * d[2] + d[4];
+        v[1] = a + b;
+        v[2] = a - b;
+        v[3] = c + e;
+        v[4] = c - e;
+        v[5] = 4.f * d[1] - 5.f * d[3] + d[5];
+    }
+    static __device__ __forceinline__ void output(const float z[6], float y[4])
+    {
+        const float s12 = z[1] + z[2], d12 = z[1] - z[2], s34 = z[3] + z[4], d34 = z[3] - z[4];
+        y[0] = z[0] + s12 + s34;
+        y[1] = d12 + 2.f * d34;
+        y[2] = s12 + 4.f * s34;
+        y[3] = d12 + 8.f * d34 + z[5];
+    }
+};
 
 struct WinoGeom {
     int Ci, Co, Hi, Wi, Ho, Wo, pad_h, pad_w;
@@ -19,7 +83,7 @@ struct WinoGeom {
     bool transposed;  // BackwardData: filter read as w[ci][co] with reversed taps
 };
 
-static WinoGeom geom(const Dims &d, int op, int b)
+static WinoGeom geom(const Dims &d, int op, int b, int mt)
 {
     WinoGeom g;
     if (op == 0) {
@@ -29,7 +93,7 @@ static WinoGeom geom(const Dims &d, int op, int b)
         g.Ci = d.K; g.Co = d.C; g.Hi = d.P; g.Wi = d.Q; g.Ho = d.H; g.Wo = d.W;
         g.pad_h = 2 - d.ph; g.pad_w = 2 - d.pw; g.transposed = true;
     }
-    g.TH = (g.Ho + 1) / 2; g.TW = (g.Wo + 1) / 2; g.T = g.TH * g.TW;
+    g.TH = (g.Ho + mt - 1) / mt; g.TW = (g.Wo + mt - 1) / mt; g.T = g.TH * g.TW;
     g.Mo4 = (g.Co + 3) / 4 * 4;
     g.ld = (b * g.T + 3) / 4 * 4;
     return g;
@@ -42,144 +106,140 @@ bool winograd_applies(const Dims &d, int op)
     return d.ph <= 2 && d.pw <= 2;
 }
 
-size_t winograd_ws_bytes(const Dims &d, int op, int b)
+size_t winograd_ws_bytes(const Dims &d, int op, int b, int mt)
 {
-    const WinoGeom g = geom(d, op, b);
-    return (size_t)64 * ((size_t)g.Ci * g.Mo4 + (size_t)g.ld * (g.Ci + g.Co));
+    const WinoGeom g = geom(d, op, b, mt);
+    return (size_t)4 * (mt + 2) * (mt + 2) * ((size_t)g.Ci * g.Mo4 + (size_t)g.ld * (g.Ci + g.Co));
 }
 
 // U[xi][ci][co] = (G g G^T)[xi], one thread per (ci, co) filter; pads co up to Mo4 with zeros.
-template <class E>
+template <class E, int MT>
 __global__ __launch_bounds__(256) void wino_filter_kernel(const void *__restrict__ w, float *__restrict__ U, int Ci,
                                                           int Co, int Mo4, int transposed)
 {
+    constexpr int A = Wino<MT>::A;
     const int i = blockIdx.x * 256 + threadIdx.x;
     if (i >= Ci * Mo4) return;
     const int ci = i / Mo4, co = i - ci * Mo4;
-    float g[3][3];
+    float t[A][3];  // G g, column by column
 #pragma unroll
-    for (int r = 0; r < 3; ++r)
+    for (int s = 0; s < 3; ++s) {
+        float g[3], u[A];
 #pragma unroll
-        for (int s = 0; s < 3; ++s) {
+        for (int r = 0; r < 3; ++r) {
             float v = 0.f;
             if (co < Co)
                 v = transposed ? Elem<E>::get(w, ((size_t)(ci * Co + co) * 3 + (2 - r)) * 3 + (2 - s))
                                : Elem<E>::get(w, ((size_t)(co * Ci + ci) * 3 + r) * 3 + s);
-            g[r][s] = v;
+            g[r] = v;
         }
-    float t[4][3];  // G g
+        Wino<MT>::filter(g, u);
 #pragma unroll
-    for (int s = 0; s < 3; ++s) {
-        t[0][s] = g[0][s];
-        t[1][s] = 0.5f * (g[0][s] + g[1][s] + g[2][s]);
-        t[2][s] = 0.5f * (g[0][s] - g[1][s] + g[2][s]);
-        t[3][s] = g[2][s];
+        for (int r = 0; r < A; ++r) t[r][s] = u[r];
     }
     const size_t plane = (size_t)Ci * Mo4;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const float u0 = t[r][0], u1 = 0.5f * (t[r][0] + t[r][1] + t[r][2]),
-                    u2 = 0.5f * (t[r][0] - t[r][1] + t[r][2]), u3 = t[r][2];
-        U[(size_t)(r * 4 + 0) * plane + i] = u0;
-        U[(size_t)(r * 4 + 1) * plane + i] = u1;
-        U[(size_t)(r * 4 + 2) * plane + i] = u2;
-        U[(size_t)(r * 4 + 3) * plane + i] = u3;
+    for (int r = 0; r < A; ++r) {
+        float u[A];
+        Wino<MT>::filter(t[r], u);
+#pragma unroll
+        for (int s = 0; s < A; ++s) U[(size_t)(r * A + s) * plane + i] = u[s];
     }
 }
 
 // V[xi][ci][j] for tile j = n*T + th*TW + tw: lanes along j (coalesced plane writes).
-template <class E>
+template <class E, int MT>
 __global__ __launch_bounds__(256) void wino_input_kernel(const void *__restrict__ x, float *__restrict__ V,
                                                          WinoGeom g, FastDiv divT, FastDiv divTW, int n_tiles)
 {
+    constexpr int A = Wino<MT>::A;
     const int j = blockIdx.x * 256 + threadIdx.x;
     if (j >= g.ld) return;
     const size_t plane = (size_t)g.Ci * g.ld;
+    uint32_t n = 0, t, th = 0, tw = 0;
+    if (j < n_tiles) {
+        divT.divmod((uint32_t)j, n, t);
+        divTW.divmod(t, th, tw);
+    }
+    const int h0 = MT * (int)th - g.pad_h, w0 = MT * (int)tw - g.pad_w;
     for (int ci = blockIdx.y; ci < g.Ci; ci += gridDim.y) {
-        float d[4][4];
+        const size_t src = ((size_t)n * g.Ci + ci) * g.Hi * g.Wi;
+        float tr[A][A];  // B^T d, column by column
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
+        for (int s = 0; s < A; ++s) {
+            float d[A], v[A];
+            const int ww = w0 + s;
 #pragma unroll
-            for (int s = 0; s < 4; ++s) d[r][s] = 0.f;
-        if (j < n_tiles) {
-            uint32_t n, t, th, tw;
-            divT.divmod((uint32_t)j, n, t);
-            divTW.divmod(t, th, tw);
-            const int h0 = 2 * (int)th - g.pad_h, w0 = 2 * (int)tw - g.pad_w;
-            const size_t src = ((size_t)n * g.Ci + ci) * g.Hi * g.Wi;
+            for (int r = 0; r < A; ++r) {
+                const int h = h0 + r;
+                d[r] = (j < n_tiles && (unsigned)h < (unsigned)g.Hi && (unsigned)ww < (unsigned)g.Wi)
+                           ? Elem<E>::get(x, src + h * g.Wi + ww)
+                           : 0.f;
+            }
+            Wino<MT>::input(d, v);
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-#pragma unroll
-                for (int s = 0; s < 4; ++s) {
-                    const int h = h0 + r, ww = w0 + s;
-                    if ((unsigned)h < (unsigned)g.Hi && (unsigned)ww < (unsigned)g.Wi) d[r][s] = Elem<E>::get(x, src + h * g.Wi + ww);
-                }
-        }
-        float t[4][4];  // B^T d
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            t[0][s] = d[0][s] - d[2][s];
-            t[1][s] = d[1][s] + d[2][s];
-            t[2][s] = d[2][s] - d[1][s];
-            t[3][s] = d[1][s] - d[3][s];
+            for (int r = 0; r < A; ++r) tr[r][s] = v[r];
         }
         float *dst = V + (size_t)ci * g.ld + j;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            dst[(size_t)(r * 4 + 0) * plane] = t[r][0] - t[r][2];
-            dst[(size_t)(r * 4 + 1) * plane] = t[r][1] + t[r][2];
-            dst[(size_t)(r * 4 + 2) * plane] = t[r][2] - t[r][1];
-            dst[(size_t)(r * 4 + 3) * plane] = t[r][1] - t[r][3];
+        for (int r = 0; r < A; ++r) {
+            float v[A];
+            Wino<MT>::input(tr[r], v);
+#pragma unroll
+            for (int s = 0; s < A; ++s) dst[(size_t)(r * A + s) * plane] = v[s];
         }
     }
 }
 
-// out[n, co, 2th + {0,1}, 2tw + {0,1}] = A^T z A, lanes along the tile index.
-template <class E>
+// out[n, co, m*th + {0..m-1}, m*tw + {0..m-1}] = A^T z A, lanes along the tile index.
+template <class E, int MT>
 __global__ __launch_bounds__(256) void wino_output_kernel(const float *__restrict__ Z, void *__restrict__ out,
                                                           WinoGeom g, FastDiv divT, FastDiv divTW, int n_tiles)
 {
+    constexpr int A = Wino<MT>::A;
     const int j = blockIdx.x * 256 + threadIdx.x;
     if (j >= n_tiles) return;
     uint32_t n, t, th, tw;
     divT.divmod((uint32_t)j, n, t);
     divTW.divmod(t, th, tw);
-    const int h0 = 2 * (int)th, w0 = 2 * (int)tw;
+    const int h0 = MT * (int)th, w0 = MT * (int)tw;
     const size_t plane = (size_t)g.Co * g.ld;
     for (int co = blockIdx.y; co < g.Co; co += gridDim.y) {
         const float *src = Z + (size_t)co * g.ld + j;
-        float z[4][4];
+        float tr[MT][A];  // A^T z, column by column
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
+        for (int s = 0; s < A; ++s) {
+            float z[A], y[MT];
 #pragma unroll
-            for (int s = 0; s < 4; ++s) z[r][s] = src[(size_t)(r * 4 + s) * plane];
-        float t[2][4];  // A^T z
+            for (int r = 0; r < A; ++r) z[r] = src[(size_t)(r * A + s) * plane];
+            Wino<MT>::output(z, y);
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            t[0][s] = z[0][s] + z[1][s] + z[2][s];
-            t[1][s] = z[1][s] - z[2][s] - z[3][s];
+            for (int r = 0; r < MT; ++r) tr[r][s] = y[r];
         }
         const size_t dst = ((size_t)n * g.Co + co) * g.Ho * g.Wo;
 #pragma unroll
-        for (int r = 0; r < 2; ++r) {
+        for (int r = 0; r < MT; ++r) {
             const int h = h0 + r;
             if (h >= g.Ho) continue;
-            const float y0 = t[r][0] + t[r][1] + t[r][2], y1 = t[r][1] - t[r][2] - t[r][3];
-            Elem<E>::store(out, dst + h * g.Wo + w0, y0);
-            if (w0 + 1 < g.Wo) Elem<E>::store(out, dst + h * g.Wo + w0 + 1, y1);
+            float y[MT];
+            Wino<MT>::output(tr[r], y);
+#pragma unroll
+            for (int s = 0; s < MT; ++s)
+                if (w0 + s < g.Wo) Elem<E>::store(out, dst + h * g.Wo + w0 + s, y[s]);
         }
     }
 }
 
-template <class E>
+template <class E, int MT>
 static hipError_t winograd_run(const Dims &d, int op, int b, const void *in, const void *w, void *out,
                                float *ws, bool filter_ready, hipStream_t s)
 {
-    const WinoGeom g = geom(d, op, b);
+    constexpr int AA = Wino<MT>::A * Wino<MT>::A;
+    const WinoGeom g = geom(d, op, b, MT);
     const int n_tiles = b * g.T;
     float *U = ws;
-    float *V = U + (size_t)16 * g.Ci * g.Mo4;
-    float *Z = V + (size_t)16 * g.Ci * g.ld;
+    float *V = U + (size_t)AA * g.Ci * g.Mo4;
+    float *Z = V + (size_t)AA * g.Ci * g.ld;
     const FastDiv divT(g.T), divTW(g.TW);
 
     LaunchLog *log = launch_log();
@@ -187,19 +247,19 @@ static hipError_t winograd_run(const Dims &d, int op, int b, const void *in, con
         // U of this filter is still at the head of the workspace from the previous micro-batch
     } else if (log) log->add("wino_filter_kernel");
     else
-        wino_filter_kernel<E><<<(unsigned)((g.Ci * g.Mo4 + 255) / 256), 256, 0, s>>>(w, U, g.Ci, g.Co, g.Mo4,
-                                                                                  g.transposed ? 1 : 0);
+        wino_filter_kernel<E, MT><<<(unsigned)((g.Ci * g.Mo4 + 255) / 256), 256, 0, s>>>(w, U, g.Ci, g.Co, g.Mo4,
+                                                                                      g.transposed ? 1 : 0);
     hipError_t e = log ? hipSuccess : hipGetLastError();
     if (e != hipSuccess) return e;
 
     dim3 gi((unsigned)((g.ld + 255) / 256), (unsigned)(g.Ci < 4096 ? g.Ci : 4096));
     if (log) log->add("wino_input_kernel");
     else
-        wino_input_kernel<E><<<gi, 256, 0, s>>>(in, V, g, divT, divTW, n_tiles);
+        wino_input_kernel<E, MT><<<gi, 256, 0, s>>>(in, V, g, divT, divTW, n_tiles);
     if (!log && (e = hipGetLastError()) != hipSuccess) return e;
 
     GemmShape gs{g.Co, n_tiles, g.Ci};
-    gs.batch = 16;
+    gs.batch = AA;
     gs.a_batch = (long)g.Ci * g.Mo4;
     gs.b_batch = (long)g.Ci * g.ld;
     gs.c_batch = (long)g.Co * g.ld;
@@ -213,22 +273,31 @@ static hipError_t winograd_run(const Dims &d, int op, int b, const void *in, con
         log->add("wino_output_kernel");
         return hipSuccess;
     }
-    wino_output_kernel<E><<<go, 256, 0, s>>>(Z, out, g, divT, divTW, n_tiles);
+    wino_output_kernel<E, MT><<<go, 256, 0, s>>>(Z, out, g, divT, divTW, n_tiles);
     return hipGetLastError();
 }
 
-hipError_t winograd_fwd(const Dims &d, int b, const void *x, const void *w, void *y, float *ws, bool filter_ready,
-                        hipStream_t s)
+template <class E>
+static hipError_t winograd_any(const Dims &d, int op, int b, const void *in, const void *w, void *out, float *ws,
+                               bool filter_ready, int mt, hipStream_t s)
 {
-    return d.dtype == 1 ? winograd_run<bf16>(d, 0, b, x, w, y, ws, filter_ready, s)
-                        : winograd_run<float>(d, 0, b, x, w, y, ws, filter_ready, s);
+    if (mt == 2) return winograd_run<E, 2>(d, op, b, in, w, out, ws, filter_ready, s);
+    if (mt == 4) return winograd_run<E, 4>(d, op, b, in, w, out, ws, filter_ready, s);
+    return hipErrorInvalidValue;
+}
+
+hipError_t winograd_fwd(const Dims &d, int b, const void *x, const void *w, void *y, float *ws, bool filter_ready,
+                        int mt, hipStream_t s)
+{
+    return d.dtype == 1 ? winograd_any<bf16>(d, 0, b, x, w, y, ws, filter_ready, mt, s)
+                        : winograd_any<float>(d, 0, b, x, w, y, ws, filter_ready, mt, s);
 }
 
 hipError_t winograd_bwd_data(const Dims &d, int b, const void *dy, const void *w, void *dx, float *ws,
-                             bool filter_ready, hipStream_t s)
+                             bool filter_ready, int mt, hipStream_t s)
 {
-    return d.dtype == 1 ? winograd_run<bf16>(d, 1, b, dy, w, dx, ws, filter_ready, s)
-                        : winograd_run<float>(d, 1, b, dy, w, dx, ws, filter_ready, s);
+    return d.dtype == 1 ? winograd_any<bf16>(d, 1, b, dy, w, dx, ws, filter_ready, mt, s)
+                        : winograd_any<float>(d, 1, b, dy, w, dx, ws, filter_ready, mt, s);
 }
 
 }  // namespace ucd

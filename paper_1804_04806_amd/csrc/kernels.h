@@ -36,16 +36,16 @@ hipError_t im2col_bwd_data(const Dims &d, int b, const void *dy, const void *w, 
 hipError_t im2col_bwd_filter(const Dims &d, int b, const void *x, const void *dy, float *dw, float beta,
                              float *ws, hipStream_t s);
 
-// Winograd F(2x2,3x3), 3x3 stride-1 layers, Forward and BackwardData.  The transformed filter sits
+// Winograd F(mt x mt, 3x3) with mt = 2 or 4, 3x3 stride-1 layers, Forward and BackwardData.  The transformed filter sits
 // at the head of the workspace and depends on the layer and the operation only: filter_ready = true
 // says that the previous launch on this workspace was the same operation on the same filter, so
 // the filter transform is skipped.
 bool winograd_applies(const Dims &d, int op);
-size_t winograd_ws_bytes(const Dims &d, int op, int b);
+size_t winograd_ws_bytes(const Dims &d, int op, int b, int mt);
 hipError_t winograd_fwd(const Dims &d, int b, const void *x, const void *w, void *y, float *ws, bool filter_ready,
-                        hipStream_t s);
+                        int mt, hipStream_t s);
 hipError_t winograd_bwd_data(const Dims &d, int b, const void *dy, const void *w, void *dx, float *ws,
-                             bool filter_ready, hipStream_t s);
+                             bool filter_ready, int mt, hipStream_t s);
 
 hipError_t fill_zero(float *p, size_t n, hipStream_t s);
 

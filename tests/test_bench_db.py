@@ -14,7 +14,7 @@ def fill(desc, op, B, seed):
         for b in range(1, B + 1):
             if ucd.ucd_workspace_size(desc, op, a, b) == ucd.WS_NA:
                 continue
-            t[a][b] = 1000 * (3 - a) * b + r.randint(0, 5000) + 20000
+            t[a][b] = 1000 * (4 - a) * b + r.randint(0, 5000) + 20000
             ucd.ucd_bench_put(desc, op, a, b, t[a][b])
     return t
 
@@ -31,8 +31,8 @@ def test_put_table_save_load_roundtrip_and_cached_plan(tmp_path):
     path = tmp_path / "bench.txt"
     ucd.ucd_bench_save(path)
     ucd.ucd_bench_clear()
-    assert ucd.ucd_bench_table(L, ucd.FWD, 12)[0] == [[ucd.TIME_INF] * 13 for _ in range(3)]
-    n_rows = sum(1 for a in range(3) for b in range(1, 13) if t_fwd[a][b] != ucd.TIME_INF)
+    assert ucd.ucd_bench_table(L, ucd.FWD, 12)[0] == [[ucd.TIME_INF] * 13 for _ in range(ucd.N_ALGO)]
+    n_rows = sum(1 for a in range(ucd.N_ALGO) for b in range(1, 13) if t_fwd[a][b] != ucd.TIME_INF)
     n = ucd.ucd_bench_load(path)
     assert n > n_rows and ucd.ucd_bench_table(L, ucd.FWD, 12)[0] == t_fwd
     assert ucd.ucd_bench_table(L, ucd.BWD_FILTER, 12)[0] == t_bf

@@ -9,7 +9,7 @@ from hip_helpers import inputs, rel_l2, run_hip, run_oracle
 
 pytestmark = pytest.mark.gpu
 
-TOL = {ucd.ALGO_IMPLICIT: 1e-5, ucd.ALGO_IM2COL: 1e-5, ucd.ALGO_WINOGRAD: 1e-3}
+TOL = {ucd.ALGO_IMPLICIT: 1e-5, ucd.ALGO_IM2COL: 1e-5, ucd.ALGO_WINOGRAD: 1e-3, ucd.ALGO_WINOGRAD4: 1e-3}
 
 # sizes span several tiles (128-wide) with ragged tails in M, N and the reduction
 SHAPES = [
@@ -30,6 +30,8 @@ SHAPES = [
     Shape(2, 160, 6, 6, 160, 3, 3, 1, 1, "k160"),              # 96-row tiles with a ragged second tile
     Shape(3, 120, 7, 7, 136, 3, 3, 1, 1, "deep"),              # few output tiles, long reduction: split + atomics
     Shape(3, 130, 10, 10, 72, 3, 3, 2, 1, "deep-s2"),          # the same through BackwardData's stride phases
+    Shape(2, 5, 11, 14, 7, 3, 3, 1, 0, "pad0-3x3"),             # Winograd tiles with no border; ragged 9 x 12 output
+    Shape(2, 5, 6, 9, 7, 3, 3, 1, 2, "pad2-3x3"),               # output larger than the input (8 x 11)
     Shape(3, 24, 56, 56, 64, 3, 3, 1, 1, "k64-wide"),          # 64-row tiles over many column tiles
     Shape(3, 96, 56, 56, 96, 3, 3, 1, 1, "c96-wide"),          # 96-row tiles, Forward and BackwardData, many column tiles
 ]
