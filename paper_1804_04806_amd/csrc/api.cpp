@@ -121,6 +121,7 @@ int run_micro(const ucd_layer_t *L, int op, int algo, int b, const void *a, cons
     case UCD_ALGO_WINOGRAD4:
         if (op == UCD_FWD) e = winograd_fwd(d, b, a, bsrc, out, ws, filter_ready, wino_tile(algo), s);
         else if (op == UCD_BWD_DATA) e = winograd_bwd_data(d, b, a, bsrc, out, ws, filter_ready, wino_tile(algo), s);
+        else e = winograd_bwd_filter(d, b, a, bsrc, (float *)out, beta, ws, wino_tile(algo), s);
         break;
     }
     return hip_status(e);

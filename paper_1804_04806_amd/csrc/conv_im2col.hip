@@ -162,8 +162,6 @@ hipError_t im2col_bwd_data(const Dims &d, int b, const void *dy, const void *w, 
                         : im2col_bwd_data_t<float>(d, b, dy, w, dx, ws, s);
 }
 
-int filter_splits(int M, int N, int Kd);
-
 template <class E>
 static hipError_t im2col_bwd_filter_t(const Dims &d, int b, const void *x, const void *dy, float *dw, float beta,
                                       float *ws, hipStream_t s)

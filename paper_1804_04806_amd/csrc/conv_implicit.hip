@@ -201,10 +201,10 @@ hipError_t implicit_bwd_data(const Dims &d, int b, const void *dy, const void *w
 
 // Number of reduction splits so that tiles * splits covers the chip a few times over, with
 // chunks of at least 256 reduction rows.
-int filter_splits(int M, int N, int Kd)
+int filter_splits(int M, int N, int Kd, int batch)
 {
     const TilePick shape = pick_tile(M, N, true, 1 << 20);  // the default shape
-    const long tiles = shape.blocks(M, N, 1);
+    const long tiles = shape.blocks(M, N, batch);
     long want = (1024 + tiles - 1) / tiles;
     long cap = Kd / 256;
     if (cap < 1) cap = 1;

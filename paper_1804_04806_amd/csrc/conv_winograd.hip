@@ -9,6 +9,15 @@
 // with T = ceil(Ho/m) * ceil(Wo/m) tiles per image and ld = b*T rounded up to 4.
 // BackwardData is the same pipeline on dy with the filter's two channel indices swapped and its
 // taps reversed, and padding 2 - pad.
+//
+// BackwardFilter is the transposed algorithm F(3x3, m x m): the 3x3 filter gradient of one tile is
+// the correlation of its a x a input tile with its m x m tile of dy, and swapping the roles of the
+// "filter" and the "output" in the bilinear form gives  dw_tile = G^T [(A dy A^T) . (B^T x B)] G
+// with the same three matrices.  The products are summed over all tiles of the micro-batch first:
+//   V[a*a][C][ld]     input transform of x, as above
+//   D[a*a][K][ld]     D = A dy A^T per m x m tile of dy
+//   Mw[a*a][K][C]     a*a GEMMs  Mw_xi = D_xi[K x b*T] * V_xi^T[b*T x C]  (reduction split, atomics)
+//   dw                = beta*dw + G^T Mw G per (k, c)
 #include "gemm_launch.hpp"
 #include "kernels.h"
 
@@ -40,6 +49,20 @@ struct Wino<2> {
     {
         y[0] = z[0] + z[1] + z[2];
         y[1] = z[1] - z[2] - z[3];
+    }
+    static __device__ __forceinline__ void grad(const float z[2], float u[4])  // A z
+    {
+        u[0] = z[0];
+        u[1] = z[0] + z[1];
+        u[2] = z[0] - z[1];
+        u[3] = -z[1];
+    }
+    static __device__ __forceinline__ void filter_t(const float m[4], float w[3])  // G^T m
+    {
+        const float s = 0.5f * (m[1] + m[2]);
+        w[0] = m[0] + s;
+        w[1] = 0.5f * (m[1] - m[2]);
+        w[2] = s + m[3];
     }
 };
 
@@ -74,6 +97,23 @@ struct Wino<4> {
         y[2] = s12 + 4.f * s34;
         y[3] = d12 + 8.f * d34 + z[5];
     }
+    static __device__ __forceinline__ void grad(const float z[4], float u[6])
+    {
+        const float e = z[0] + z[2], o = z[1] + z[3], e4 = z[0] + 4.f * z[2], o4 = 2.f * z[1] + 8.f * z[3];
+        u[0] = z[0];
+        u[1] = e + o;
+        u[2] = e - o;
+        u[3] = e4 + o4;
+        u[4] = e4 - o4;
+        u[5] = z[3];
+    }
+    static __device__ __forceinline__ void filter_t(const float m[6], float w[3])
+    {
+        const float s12 = m[1] + m[2], d12 = m[1] - m[2], s34 = m[3] + m[4], d34 = m[3] - m[4];
+        w[0] = 0.25f * m[0] - (1.f / 6.f) * s12 + (1.f / 24.f) * s34;
+        w[1] = (-1.f / 6.f) * d12 + (1.f / 12.f) * d34;
+        w[2] = (-1.f / 6.f) * s12 + (1.f / 6.f) * s34 + m[5];
+    }
 };
 
 struct WinoGeom {
@@ -101,15 +141,20 @@ static WinoGeom geom(const Dims &d, int op, int b, int mt)
 
 bool winograd_applies(const Dims &d, int op)
 {
-    if (op != 0 && op != 1) return false;
+    if (op < 0 || op > 2) return false;
     if (d.R != 3 || d.S != 3 || d.sh != 1 || d.sw != 1) return false;
     return d.ph <= 2 && d.pw <= 2;
 }
 
 size_t winograd_ws_bytes(const Dims &d, int op, int b, int mt)
 {
+    const size_t planes = (size_t)(mt + 2) * (mt + 2);
+    if (op == 2) {  // Mw, V, D
+        const WinoGeom g = geom(d, 0, b, mt);
+        return 4 * planes * ((size_t)d.K * d.C + (size_t)g.ld * (d.C + d.K));
+    }
     const WinoGeom g = geom(d, op, b, mt);
-    return (size_t)4 * (mt + 2) * (mt + 2) * ((size_t)g.Ci * g.Mo4 + (size_t)g.ld * (g.Ci + g.Co));
+    return 4 * planes * ((size_t)g.Ci * g.Mo4 + (size_t)g.ld * (g.Ci + g.Co));
 }
 
 // U[xi][ci][co] = (G g G^T)[xi], one thread per (ci, co) filter; pads co up to Mo4 with zeros.
@@ -275,6 +320,136 @@ static hipError_t winograd_run(const Dims &d, int op, int b, const void *in, con
     }
     wino_output_kernel<E, MT><<<go, 256, 0, s>>>(Z, out, g, divT, divTW, n_tiles);
     return hipGetLastError();
+}
+
+// D[xi][k][j] = (A dy A^T)[xi] for the m x m tile j of dy (zero outside the image), lanes along j.
+// g is the Forward geometry: Co = K, Ho x Wo = P x Q.
+template <class E, int MT>
+__global__ __launch_bounds__(256) void wino_grad_kernel(const void *__restrict__ dy, float *__restrict__ D,
+                                                        WinoGeom g, FastDiv divT, FastDiv divTW, int n_tiles)
+{
+    constexpr int A = Wino<MT>::A;
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= g.ld) return;
+    const size_t plane = (size_t)g.Co * g.ld;
+    uint32_t n = 0, t, th = 0, tw = 0;
+    if (j < n_tiles) {
+        divT.divmod((uint32_t)j, n, t);
+        divTW.divmod(t, th, tw);
+    }
+    const int h0 = MT * (int)th, w0 = MT * (int)tw;
+    for (int co = blockIdx.y; co < g.Co; co += gridDim.y) {
+        const size_t src = ((size_t)n * g.Co + co) * g.Ho * g.Wo;
+        float tr[A][MT];  // A dy, column by column
+#pragma unroll
+        for (int s = 0; s < MT; ++s) {
+            float z[MT], u[A];
+#pragma unroll
+            for (int r = 0; r < MT; ++r)
+                z[r] = (j < n_tiles && h0 + r < g.Ho && w0 + s < g.Wo) ? Elem<E>::get(dy, src + (h0 + r) * g.Wo + w0 + s)
+                                                                      : 0.f;
+            Wino<MT>::grad(z, u);
+#pragma unroll
+            for (int r = 0; r < A; ++r) tr[r][s] = u[r];
+        }
+        float *dst = D + (size_t)co * g.ld + j;
+#pragma unroll
+        for (int r = 0; r < A; ++r) {
+            float u[A];
+            Wino<MT>::grad(tr[r], u);
+#pragma unroll
+            for (int s = 0; s < A; ++s) dst[(size_t)(r * A + s) * plane] = u[s];
+        }
+    }
+}
+
+// dw[k, c] = beta * dw[k, c] + G^T Mw[., k, c] G, one thread per (k, c)
+template <int MT>
+__global__ __launch_bounds__(256) void wino_dw_kernel(const float *__restrict__ Mw, float *__restrict__ dw, int KC,
+                                                      float beta)
+{
+    constexpr int A = Wino<MT>::A;
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= KC) return;
+    float tr[3][A];  // G^T Mw, column by column
+#pragma unroll
+    for (int s = 0; s < A; ++s) {
+        float m[A], w3[3];
+#pragma unroll
+        for (int r = 0; r < A; ++r) m[r] = Mw[(size_t)(r * A + s) * KC + i];
+        Wino<MT>::filter_t(m, w3);
+#pragma unroll
+        for (int r = 0; r < 3; ++r) tr[r][s] = w3[r];
+    }
+    float *dst = dw + (size_t)i * 9;
+#pragma unroll
+    for (int r = 0; r < 3; ++r) {
+        float w3[3];
+        Wino<MT>::filter_t(tr[r], w3);
+#pragma unroll
+        for (int s = 0; s < 3; ++s) dst[r * 3 + s] = beta == 0.f ? w3[s] : beta * dst[r * 3 + s] + w3[s];
+    }
+}
+
+template <class E, int MT>
+static hipError_t winograd_filter_run(const Dims &d, int b, const void *x, const void *dy, float *dw, float beta,
+                                      float *ws, hipStream_t s)
+{
+    constexpr int AA = Wino<MT>::A * Wino<MT>::A;
+    const WinoGeom g = geom(d, 0, b, MT);
+    const int n_tiles = b * g.T, KC = d.K * d.C;
+    float *Mw = ws;
+    float *V = Mw + (size_t)AA * KC;
+    float *D = V + (size_t)AA * d.C * g.ld;
+    const FastDiv divT(g.T), divTW(g.TW);
+
+    LaunchLog *log = launch_log();
+    hipError_t e = fill_zero(Mw, (size_t)AA * KC, s);
+    if (e != hipSuccess) return e;
+    dim3 gi((unsigned)((g.ld + 255) / 256), (unsigned)(d.C < 4096 ? d.C : 4096));
+    dim3 gd((unsigned)((g.ld + 255) / 256), (unsigned)(d.K < 4096 ? d.K : 4096));
+    if (log) {
+        log->add("wino_input_kernel");
+        log->add("wino_grad_kernel");
+    } else {
+        wino_input_kernel<E, MT><<<gi, 256, 0, s>>>(x, V, g, divT, divTW, n_tiles);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        wino_grad_kernel<E, MT><<<gd, 256, 0, s>>>(dy, D, g, divT, divTW, n_tiles);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+
+    GemmShape gs{d.K, d.C, n_tiles};
+    gs.batch = AA;
+    gs.a_batch = (long)d.K * g.ld;
+    gs.b_batch = (long)d.C * g.ld;
+    gs.c_batch = KC;
+    gs.splits = filter_splits(gs.M, gs.N, gs.Kd, AA);
+    KLaneParams pa{};
+    pa.t = D; pa.bytes = (uint32_t)(gs.a_batch * 4); pa.row_stride = 1; pa.col_stride = g.ld;
+    KLaneParams pb{};
+    pb.t = V; pb.bytes = (uint32_t)(gs.b_batch * 4); pb.row_stride = 1; pb.col_stride = g.ld;
+    EpiDenseParams pe{Mw, d.C};
+    if ((e = launch_gemm<KLane0, KLane0, EpiAtomic, true>(pa, pb, pe, gs, s)) != hipSuccess) return e;
+
+    if (log) {
+        log->add("wino_dw_kernel");
+        return hipSuccess;
+    }
+    wino_dw_kernel<MT><<<(unsigned)((KC + 255) / 256), 256, 0, s>>>(Mw, dw, KC, beta);
+    return hipGetLastError();
+}
+
+hipError_t winograd_bwd_filter(const Dims &d, int b, const void *x, const void *dy, float *dw, float beta,
+                               float *ws, int mt, hipStream_t s)
+{
+    const bool h = d.dtype == 1;
+    if (mt == 2)
+        return h ? winograd_filter_run<bf16, 2>(d, b, x, dy, dw, beta, ws, s)
+                 : winograd_filter_run<float, 2>(d, b, x, dy, dw, beta, ws, s);
+    if (mt == 4)
+        return h ? winograd_filter_run<bf16, 4>(d, b, x, dy, dw, beta, ws, s)
+                 : winograd_filter_run<float, 4>(d, b, x, dy, dw, beta, ws, s);
+    return hipErrorInvalidValue;
 }
 
 template <class E>

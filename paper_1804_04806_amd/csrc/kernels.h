@@ -36,7 +36,8 @@ hipError_t im2col_bwd_data(const Dims &d, int b, const void *dy, const void *w, 
 hipError_t im2col_bwd_filter(const Dims &d, int b, const void *x, const void *dy, float *dw, float beta,
                              float *ws, hipStream_t s);
 
-// Winograd F(mt x mt, 3x3) with mt = 2 or 4, 3x3 stride-1 layers, Forward and BackwardData.  The transformed filter sits
+// Winograd with tiles of mt = 2 or 4, 3x3 stride-1 layers: F(mt x mt, 3x3) for Forward and
+// BackwardData, F(3x3, mt x mt) for BackwardFilter.  For the first two the transformed filter sits
 // at the head of the workspace and depends on the layer and the operation only: filter_ready = true
 // says that the previous launch on this workspace was the same operation on the same filter, so
 // the filter transform is skipped.
@@ -47,7 +48,13 @@ hipError_t winograd_fwd(const Dims &d, int b, const void *x, const void *w, void
 hipError_t winograd_bwd_data(const Dims &d, int b, const void *dy, const void *w, void *dx, float *ws,
                              bool filter_ready, int mt, hipStream_t s);
 
+hipError_t winograd_bwd_filter(const Dims &d, int b, const void *x, const void *dy, float *dw, float beta,
+                               float *ws, int mt, hipStream_t s);
+
 hipError_t fill_zero(float *p, size_t n, hipStream_t s);
+// reduction splits of a BackwardFilter-shaped GEMM (small output, long reduction), `batch` of which
+// run in one launch
+int filter_splits(int M, int N, int Kd, int batch = 1);
 
 // Dry-run support: while a log is installed (per host thread) every launcher appends a one-line
 // description of the kernel it would launch and launches nothing.

@@ -38,11 +38,13 @@ def test_workspace_formulas():
     # Winograd: 64 bytes x (C*K + b*T*(C+K)), T = 8*8 tiles: 32 + 64 + 128 KiB at b = 1
     assert ucd.ucd_workspace_size(L, ucd.FWD, ucd.ALGO_WINOGRAD, 1) == 64 * (16 * 32 + 64 * 48) == 224 * 1024
     assert ucd.ucd_workspace_size(L, ucd.BWD_DATA, ucd.ALGO_WINOGRAD, 2) == 64 * (16 * 32 + 128 * 48)
-    assert ucd.ucd_workspace_size(L, ucd.BWD_FILTER, ucd.ALGO_WINOGRAD, 1) == ucd.WS_NA
+    assert ucd.ucd_workspace_size(L, ucd.BWD_FILTER, ucd.ALGO_WINOGRAD, 1) == 64 * (16 * 32 + 64 * 48)
     # Winograd F(4x4,3x3): 36 planes of 4 bytes, T = 4*4 tiles
     assert ucd.ucd_workspace_size(L, ucd.FWD, ucd.ALGO_WINOGRAD4, 1) == 144 * (16 * 32 + 16 * 48)
     assert ucd.ucd_workspace_size(L, ucd.BWD_DATA, ucd.ALGO_WINOGRAD4, 3) == 144 * (16 * 32 + 48 * 48)
-    assert ucd.ucd_workspace_size(L, ucd.BWD_FILTER, ucd.ALGO_WINOGRAD4, 1) == ucd.WS_NA
+    assert ucd.ucd_workspace_size(L, ucd.BWD_FILTER, ucd.ALGO_WINOGRAD4, 2) == 144 * (16 * 32 + 32 * 48)
+    Ls2 = ucd.layer(N=8, C=16, H=16, W=16, K=32, R=3, S=3, pad_h=1, pad_w=1, stride_h=2, stride_w=2)
+    assert ucd.ucd_workspace_size(Ls2, ucd.BWD_FILTER, ucd.ALGO_WINOGRAD, 1) == ucd.WS_NA  # stride 2
     L11 = ucd.layer(N=4, C=8, H=7, W=7, K=8, R=1, S=1)
     assert ucd.ucd_workspace_size(L11, ucd.FWD, ucd.ALGO_IM2COL, 1) == ucd.WS_NA    # col == x
     assert ucd.ucd_workspace_size(L11, ucd.FWD, ucd.ALGO_WINOGRAD, 1) == ucd.WS_NA  # not 3x3

@@ -8,7 +8,7 @@ rounding an output to nearest moves it by at most half a unit in the last place,
 magnitude; over a tensor that is a relative L2 error of about 2^-8 / sqrt(3) = 2.3e-3, so 5e-3 is
 asserted for y and dx, together with the elementwise bound
 |got - ref| <= 2^-8 |ref| + 1e-5 rms(ref) (half an ulp plus the fp32 accumulation error).
-dw stays fp32 and keeps the fp32 path's 1e-5.
+dw stays fp32 and keeps the fp32 path's tolerances (1e-5; 1e-3 for Winograd).
 """
 import numpy as np
 import pytest
@@ -94,7 +94,8 @@ def test_bf16_parity_all_algorithms_and_divisions(s, op):
             got = run_hip_bf16(s, op, [(algo, b) for b in parts], bits)
             ctx = (s.name, ucd.OP_NAMES[op], ucd.ALGO_NAMES[algo], parts)
             if op == ucd.BWD_FILTER:
-                assert rel_l2(got, ref) <= 1e-5, (ctx, rel_l2(got, ref))
+                tol = 1e-3 if algo in ucd.WINOGRAD_ALGOS else 1e-5
+                assert rel_l2(got, ref) <= tol, (ctx, rel_l2(got, ref))
             else:
                 check_bf16_output(got, ref, ctx)
             ran += 1

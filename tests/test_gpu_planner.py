@@ -49,8 +49,7 @@ def test_small_config_plan_equals_brute_force_on_measured_table(limit):
         assert plans[ucd.POLICY_ALL].cost_ns <= plans[ucd.POLICY_POW2].cost_ns <= plans[ucd.POLICY_UNDIVIDED].cost_ns
         # feasibility of each algorithm at b=1 follows the workspace formulas
         assert (t[ucd.ALGO_IM2COL][1] != ucd.TIME_INF) == (limit >= 147456)
-        if op != ucd.BWD_FILTER:
-            assert (t[ucd.ALGO_WINOGRAD][1] != ucd.TIME_INF) == (limit >= 229376)
+        assert (t[ucd.ALGO_WINOGRAD][1] != ucd.TIME_INF) == (limit >= 229376)
         # and the planned configuration computes the right thing
         plan = plans[ucd.POLICY_ALL]
         if op == ucd.FWD:
