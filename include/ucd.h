@@ -69,9 +69,10 @@ enum { UCD_FWD = 0, UCD_BWD_DATA = 1, UCD_BWD_FILTER = 2, UCD_N_OP = 3 };
 
 /* Equivalent algorithms, differing in workspace need (the role cuDNN's algorithm list plays
  * in Section 1): implicit GEMM (no workspace), im2col into workspace + GEMM, Winograd F(2x2,3x3)
- * and Winograd F(4x4,3x3) with transform buffers in workspace (3x3 stride-1
- * Forward/BackwardData only; the larger tile does 36 products per 16 outputs instead of 16 per 4
- * and needs less workspace per sample, at a looser rounding error). */
+ * and Winograd F(4x4,3x3) with transform buffers in workspace (3x3 stride-1 layers only, all
+ * three operations, BackwardFilter as F(3x3,2x2) / F(3x3,4x4); the larger tile does 36 products
+ * per 16 outputs instead of 16 per 4 and needs less workspace per sample, at a looser rounding
+ * error). */
 enum { UCD_ALGO_IMPLICIT = 0, UCD_ALGO_IM2COL = 1, UCD_ALGO_WINOGRAD = 2, UCD_ALGO_WINOGRAD4 = 3, UCD_N_ALGO = 4 };
 
 /* Batch-size policies of Section 3.4: which micro-batch sizes get benchmarked. */
