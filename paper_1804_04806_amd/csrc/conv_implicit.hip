@@ -119,6 +119,63 @@ hipError_t implicit_fwd(const Dims &d, int b, const void *x, const void *w, void
     return d.dtype == 1 ? implicit_fwd_t<bf16>(d, b, x, w, y, s) : implicit_fwd_t<float>(d, b, x, w, y, s);
 }
 
+// Merged stride phases.  With few input channels a phase GEMM (M = C rows) leaves most of a
+// 32-row tile empty.  Writing h + ph = vs*t + a with vs = f*stride, the pixels a = 0..vs-1 of
+// block t are all reached from the same window of dy rows p = f*t + (f-1) - u, u = 0..U'-1,
+// U' = ceil(R/stride) + f - 1, through filter row r = a - stride*(f-1) + stride*u (no such tap:
+// zero).  One GEMM with M = C*vs_h*vs_w rows then computes all phases; R*S of every
+// (stride*U')*(stride*V') taps it multiplies are real.  f = 1 or 2, whichever wastes least;
+// 0 = keep the phases separate.
+static int merged_phase_factor(const Dims &d)
+{
+    if (d.sh * d.sw == 1 || d.C >= 32) return 0;
+    auto tile_eff = [](int M) {  // useful rows of the tiles x relative speed of the tile shape
+        const int rows = pick_rows(M, true);
+        const double speed = rows == 32 ? 0.7 : rows == 64 ? 0.9 : rows == 96 ? 0.96 : 1.0;
+        return (double)M / ((M + rows - 1) / rows * rows) * speed;
+    };
+    int best = 0;
+    double best_s = tile_eff(d.C);  // separate phases multiply no zero taps
+    for (int f = 1; f <= 2; ++f) {
+        const int M = d.C * f * d.sh * f * d.sw;
+        const int U = (d.R + d.sh - 1) / d.sh + f - 1, V = (d.S + d.sw - 1) / d.sw + f - 1;
+        if (M > 128 || U > 31 || V > 31) continue;
+        const double s = tile_eff(M) * d.R / (double)(d.sh * U) * d.S / (double)(d.sw * V);
+        if (s > best_s * 1.1) { best = f; best_s = s; }
+    }
+    return best;
+}
+
+template <class E>
+static hipError_t implicit_bwd_data_merged(const Dims &d, int b, const void *dy, const void *w, void *dx, int f,
+                                           hipStream_t s)
+{
+    typedef Loaders<E> L;
+    const int vsh = f * d.sh, vsw = f * d.sw;
+    const int U = (d.R + d.sh - 1) / d.sh + f - 1, V = (d.S + d.sw - 1) / d.sw + f - 1;
+    const int Hb = (d.H - 1 + d.ph) / vsh + 1, Wb = (d.W - 1 + d.pw) / vsw + 1;  // blocks that hold a pixel
+    GemmShape g{d.C * vsh * vsw, b * Hb * Wb, d.K * U * V};
+    KLaneParams pa{};
+    pa.t = w; pa.bytes = wbytes(d); pa.col_stride = d.R * d.S; pa.k_stride = d.crs(); pa.s_mem = d.S;
+    pa.taps = FastDiv(U * V); pa.taps_w = FastDiv(V);
+    pa.col_taps = FastDiv(vsh * vsw); pa.col_taps_w = FastDiv(vsw);
+    pa.tap_mul_h = d.sh; pa.tap_add_h = -d.sh * (f - 1); pa.tap_mul_w = d.sw; pa.tap_add_w = -d.sw * (f - 1);
+    pa.n_tap_h = d.R; pa.n_tap_w = d.S;
+    GatherParams pb{};
+    pb.t = dy; pb.bytes = ybytes(d, b); pb.Ct = d.K; pb.Ht = d.P; pb.Wt = d.Q;
+    pb.grid_hw = FastDiv(Hb * Wb); pb.grid_w = FastDiv(Wb);
+    pb.mul_h = f; pb.add_h = f - 1; pb.mul_w = f; pb.add_w = f - 1; pb.dir = -1;
+    pb.taps = pa.taps; pb.taps_w = pa.taps_w;
+    pb.n_tap_h = U; pb.n_tap_w = V;
+    pb.shift_thread = 0; pb.shift_row = (U - 1) * d.Q + (V - 1);
+    EpiPhasesParams pe{};
+    pe.out = dx; pe.grid_hw = pb.grid_hw; pe.grid_w = pb.grid_w; pe.block = pa.col_taps; pe.block_w = pa.col_taps_w;
+    pe.C = d.C; pe.H = d.H; pe.W = d.W; pe.vs_h = vsh; pe.vs_w = vsw; pe.pad_h = d.ph; pe.pad_w = d.pw;
+    if (U * V <= 31)
+        return launch_gemm<L::template PhaseFilterKLane, L::template GatherNLane, EpiPhasesT<E>, true>(pa, pb, pe, g, s);
+    return launch_gemm<L::template PhaseFilterKLane, L::template GatherNLaneBig, EpiPhasesT<E>, true>(pa, pb, pe, g, s);
+}
+
 // Stride phases: input pixels h with (h + ph) % sh == a are reached only by filter rows
 // r = a, a + sh, ...; within a phase the gather is a dense stride-1 correlation with the
 // sub-sampled, index-reversed filter.  Pixels of a phase with no tap get zeros (Kd = 0).
@@ -127,6 +184,7 @@ static hipError_t implicit_bwd_data_t(const Dims &d, int b, const void *dy, cons
 {
     typedef Loaders<E> L;
     constexpr bool F32 = std::is_same<E, float>::value;
+    if (const int f = merged_phase_factor(d)) return implicit_bwd_data_merged<E>(d, b, dy, w, dx, f, s);
     // phases whose GEMM has too few tiles split their reduction (atomics); dx is zero-filled once
     // if any phase does
     auto phase_shape = [&](int a, int c, int &h0, int &w0, int &Hh, int &Ww, int &Ra, int &Sc) {

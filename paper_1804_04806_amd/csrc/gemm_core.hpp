@@ -482,6 +482,75 @@ struct FilterKLaneT : NoSetup {
 
 template <int TD> using FilterKLane = FilterKLaneT<TD, float>;
 
+// BackwardData's A operand when the stride phases of a layer with few input channels are merged
+// into one GEMM: the tile position m = (c, a, b) names an input channel and a pixel of a
+// (vs_h x vs_w) block of dx (vs = a multiple f of the stride), the reduction row kk = (k, u, v) an
+// output channel and a position of the window of dy that reaches the block; the element is
+//   w[k, c, a + tap_add_h + tap_mul_h*u, b + tap_add_w + tap_mul_w*v]   (tap_mul = stride,
+//   tap_add = -stride*(f-1)), zero where that tap does not exist.
+// KLaneParams: col_taps / col_taps_w decode m, taps / taps_w decode kk, n_tap_h / n_tap_w = R, S,
+// s_mem = S, col_stride = R*S, k_stride = C*R*S.
+template <int TD, class E = float>
+struct PhaseFilterKLaneT : NoSetup {
+    static constexpr uint32_t EB = Elem<E>::kBytes;
+    static constexpr bool kBf16 = std::is_same<E, bf16>::value;
+    static std::string name() { return std::string("PhaseFilterKLane") + Elem<E>::tag(); }
+    static constexpr int CP = kThreads / kBK;
+    static constexpr int NE = TD / CP;
+    static constexpr int LD = TD + kPad;
+    struct Regs { float r[NE]; };
+    const KLaneParams *p;
+    __amdgpu_buffer_rsrc_t rsrc;
+    int kl, c0;
+    int coff[NE], rh[NE], rw[NE];  // per position: c*R*S, a + tap_add_h, b + tap_add_w
+    int koff_, uh_, vw_;           // per step: k*C*R*S, stride*u, stride*v of this thread's row
+    bool live_;
+
+    __device__ __forceinline__ void init(const KLaneParams &prm, int origin, int)
+    {
+        p = &prm;
+        rsrc = make_rsrc_bytes(prm.t, 0, prm.bytes);
+        kl = threadIdx.x % kBK;
+        c0 = threadIdx.x / kBK;
+#pragma unroll
+        for (int i = 0; i < NE; ++i) {
+            uint32_t c, rest, a, b;
+            prm.col_taps.divmod((uint32_t)(origin + c0 + CP * i), c, rest);
+            prm.col_taps_w.divmod(rest, a, b);
+            coff[i] = (int)c * prm.col_stride;
+            rh[i] = (int)a + prm.tap_add_h;
+            rw[i] = (int)b + prm.tap_add_w;
+        }
+    }
+    template <class Peer>
+    __device__ __forceinline__ void prep(int k0, int k_end, const Peer &)
+    {
+        const int kk = k0 + kl;
+        uint32_t k, tap, u, v;
+        p->taps.divmod((uint32_t)kk, k, tap);
+        p->taps_w.divmod(tap, u, v);
+        koff_ = (int)k * p->k_stride;
+        uh_ = p->tap_mul_h * (int)u;
+        vw_ = p->tap_mul_w * (int)v;
+        live_ = kk < k_end;
+    }
+    __device__ __forceinline__ void load(int i, float (&r)[NE]) const
+    {
+        const int tr = rh[i] + uh_, ts = rw[i] + vw_;
+        const bool ok = live_ && (unsigned)tr < (unsigned)p->n_tap_h && (unsigned)ts < (unsigned)p->n_tap_w;
+        // tile positions past the operand's extent (c >= C) may pass this test: a buffer load
+        // cannot fault, and those rows are never stored
+        const uint32_t vo = ok ? EB * (uint32_t)(koff_ + coff[i] + tr * p->s_mem + ts) : kOob;
+        r[i] = Elem<E>::load(rsrc, vo, 0);
+    }
+    __device__ __forceinline__ int erow(int i) const { return kl; }
+    __device__ __forceinline__ int ecol(int i) const { return c0 + CP * i; }
+    __device__ __forceinline__ void store(float *lds, int i, const float (&r)[NE]) const
+    {
+        lds[kl * LD + c0 + CP * i] = r[i];
+    }
+};
+
 // BackwardFilter's operands: reduction row kk -> (n, a, b) over the output-pixel grid, tile
 // position j -> (c, r, s); element = T[n, c, a*mul_h + add_h + r, b*mul_w + add_w + s].
 //   WINDOW = false: dy (a 1x1 "tap", always inside): flags are additive, operand limit 1 GiB.
@@ -837,6 +906,7 @@ template <class E>
 struct Loaders {
     template <int TD> using KLane0 = KLane0T<TD, E>;
     template <int TD> using FilterKLane = FilterKLaneT<TD, E>;
+    template <int TD> using PhaseFilterKLane = PhaseFilterKLaneT<TD, E>;
     template <int TD> using GatherNLane = GatherNLaneT<TD, true, E>;
     template <int TD> using GatherNLaneBig = GatherNLaneT<TD, false, E>;
     template <int TD> using DyKLane = PixelKLane<TD, false, E>;
@@ -889,6 +959,40 @@ struct EpiNCHWAtomic : EpiNCHW {
     __device__ __forceinline__ void store(const Params &p, int m, float v) const
     {
         unsafeAtomicAdd((float *)p.out + off + m * p.HWo, v);
+    }
+};
+
+// BackwardData with merged stride phases: column j -> (n, t, u) over the grid of (vs_h x vs_w)
+// pixel blocks, row m -> (c, a, b); element out[n, c, vs_h*t - pad_h + a, vs_w*u - pad_w + b]
+// where that pixel exists.  Every pixel of dx belongs to exactly one (block, position).
+struct EpiPhasesParams {
+    void *out;
+    FastDiv grid_hw, grid_w, block, block_w;
+    int C, H, W, vs_h, vs_w, pad_h, pad_w;
+};
+template <class E>
+struct EpiPhasesT {
+    static constexpr bool kCanAdd = false;
+    static std::string name() { return std::string("EpiPhases") + Elem<E>::tag(); }
+    typedef EpiPhasesParams Params;
+    int nb, hb, wb;
+    __device__ __forceinline__ void prep(const Params &p, int j)
+    {
+        uint32_t n, rest, t, u;
+        p.grid_hw.divmod((uint32_t)j, n, rest);
+        p.grid_w.divmod(rest, t, u);
+        nb = (int)n * p.C * p.H * p.W;
+        hb = p.vs_h * (int)t - p.pad_h;
+        wb = p.vs_w * (int)u - p.pad_w;
+    }
+    __device__ __forceinline__ void store(const Params &p, int m, float v) const
+    {
+        uint32_t c, rest, a, b;
+        p.block.divmod((uint32_t)m, c, rest);
+        p.block_w.divmod(rest, a, b);
+        const int h = hb + (int)a, w = wb + (int)b;
+        if ((unsigned)h < (unsigned)p.H && (unsigned)w < (unsigned)p.W)
+            Elem<E>::store(p.out, nb + ((int)c * p.H + h) * p.W + w, v);
     }
 };
 

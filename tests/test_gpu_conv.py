@@ -9,7 +9,9 @@ from hip_helpers import inputs, rel_l2, run_hip, run_oracle
 
 pytestmark = pytest.mark.gpu
 
-TOL = {ucd.ALGO_IMPLICIT: 1e-5, ucd.ALGO_IM2COL: 1e-5, ucd.ALGO_WINOGRAD: 1e-3, ucd.ALGO_WINOGRAD4: 1e-3}
+# The task's bounds are 1e-5 for the direct/GEMM paths and 1e-3 for Winograd; the Winograd kernels
+# measure 3e-7 (2x2 tiles) to 4e-6 (4x4 tiles), so they are held to 1e-4 here.
+TOL = {ucd.ALGO_IMPLICIT: 1e-5, ucd.ALGO_IM2COL: 1e-5, ucd.ALGO_WINOGRAD: 1e-4, ucd.ALGO_WINOGRAD4: 1e-4}
 
 # sizes span several tiles (128-wide) with ragged tails in M, N and the reduction
 SHAPES = [
@@ -32,6 +34,8 @@ SHAPES = [
     Shape(3, 130, 10, 10, 72, 3, 3, 2, 1, "deep-s2"),          # the same through BackwardData's stride phases
     Shape(2, 5, 11, 14, 7, 3, 3, 1, 0, "pad0-3x3"),             # Winograd tiles with no border; ragged 9 x 12 output
     Shape(2, 5, 6, 9, 7, 3, 3, 1, 2, "pad2-3x3"),               # output larger than the input (8 x 11)
+    Shape(2, 3, 30, 31, 16, 7, 7, 2, 3, "stem-c3"),             # BackwardData: stride phases merged in 4 x 4 pixel blocks
+    Shape(2, 2, 25, 25, 5, 11, 11, 2, 5, "bigwin-s2"),          # merged phases with a 6 x 6 window of dy (per-axis masks)
     Shape(3, 24, 56, 56, 64, 3, 3, 1, 1, "k64-wide"),          # 64-row tiles over many column tiles
     Shape(3, 96, 56, 56, 96, 3, 3, 1, 1, "c96-wide"),          # 96-row tiles, Forward and BackwardData, many column tiles
 ]
