@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <chrono>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -31,7 +32,9 @@ struct ucd_plan {
 
 namespace {
 
-constexpr int kTimedRuns = 3;
+constexpr int kMinTimedRuns = 2, kMaxTimedRuns = 8;
+constexpr float kTimedSpanMs = 0.4f;  // reps are chosen to cover about this much device time
+constexpr int kSpinUpMs = 10;         // device kept busy this long before the first timing of a call
 
 bool layer_ok(const ucd_layer_t *L)
 {
@@ -200,31 +203,44 @@ struct Events {
     }
 };
 
-// Device time of one (algo, b): one warm-up, then the minimum of kTimedRuns, in integer ns.
+// Device time of one (algo, b) as it will cost inside a configuration: after one warm-up run, a
+// few runs are launched back to back on consecutive micro-batches of the buffers (wrapping at N),
+// and the time per run between two events around the whole sequence is taken, in integer ns.
+// Timed like this a run includes the dispatch gap to its successor, reads activations that the
+// previous run has not just pulled into the caches, and sees the clock of a busy chip: the three
+// things a lone, repeated run on the same samples leaves out, all of which favour small
+// micro-batches and made configurations look faster than they then ran.
 int time_micro(const ucd_layer_t *L, int op, int algo, int b, void *x, void *w, void *y, float *ws,
                hipStream_t s, Events &ev, uint64_t &ns)
 {
-    const void *a = op == UCD_BWD_DATA ? y : x;
-    const void *bs = op == UCD_BWD_FILTER ? y : w;
-    void *out = op == UCD_FWD ? y : (op == UCD_BWD_DATA ? x : w);
+    const Dims d = dims_of(L);
+    const size_t x_img = d.esize() * d.C * d.H * d.W, y_img = d.esize() * d.K * d.P * d.Q;
     // BackwardFilter is timed as the accumulating call it is for every micro-batch but the first
     const float beta = op == UCD_BWD_FILTER ? 1.f : 0.f;
-    if (op == UCD_BWD_FILTER) {
-        const Dims d = dims_of(L);
-        if (fill_zero((float *)w, (size_t)d.K * d.crs(), s) != hipSuccess) return UCD_E_HIP;
+    if (op == UCD_BWD_FILTER && fill_zero((float *)w, (size_t)d.K * d.crs(), s) != hipSuccess) return UCD_E_HIP;
+    auto run_at = [&](int o) {  // the micro-batch of samples o .. o+b-1
+        char *xo = (char *)x + (size_t)o * x_img, *yo = (char *)y + (size_t)o * y_img;
+        if (op == UCD_FWD) return run_micro(L, op, algo, b, xo, w, yo, beta, ws, s);
+        if (op == UCD_BWD_DATA) return run_micro(L, op, algo, b, yo, w, xo, beta, ws, s);
+        return run_micro(L, op, algo, b, xo, yo, w, beta, ws, s);
+    };
+    auto elapsed = [&](float &ms) {
+        if (hipEventRecord(ev.b, s) != hipSuccess || hipEventSynchronize(ev.b) != hipSuccess) return UCD_E_HIP;
+        return hipEventElapsedTime(&ms, ev.a, ev.b) == hipSuccess ? UCD_OK : UCD_E_HIP;
+    };
+    float warm = 0.f, total = 0.f;
+    if (hipEventRecord(ev.a, s) != hipSuccess) return UCD_E_HIP;
+    int rc = run_at(0);
+    if (rc != UCD_OK || (rc = elapsed(warm)) != UCD_OK) return rc;
+    int reps = warm > 0.f ? (int)(kTimedSpanMs / warm) : kMaxTimedRuns;
+    reps = reps < kMinTimedRuns ? kMinTimedRuns : (reps > kMaxTimedRuns ? kMaxTimedRuns : reps);
+    if (hipEventRecord(ev.a, s) != hipSuccess) return UCD_E_HIP;
+    for (int it = 0, o = 0; it < reps; ++it) {
+        o = o + 2 * b <= L->N ? o + b : 0;  // the next micro-batch, starting after the warm-up's
+        if ((rc = run_at(o)) != UCD_OK) return rc;
     }
-    float best = INFINITY;
-    for (int it = 0; it <= kTimedRuns; ++it) {
-        if (hipEventRecord(ev.a, s) != hipSuccess) return UCD_E_HIP;
-        int rc = run_micro(L, op, algo, b, a, bs, out, beta, ws, s);
-        if (rc != UCD_OK) return rc;
-        if (hipEventRecord(ev.b, s) != hipSuccess) return UCD_E_HIP;
-        if (hipEventSynchronize(ev.b) != hipSuccess) return UCD_E_HIP;
-        float ms = 0.f;
-        if (hipEventElapsedTime(&ms, ev.a, ev.b) != hipSuccess) return UCD_E_HIP;
-        if (it > 0) best = std::min(best, ms);
-    }
-    ns = (uint64_t)std::llround((double)best * 1e6);
+    if ((rc = elapsed(total)) != UCD_OK) return rc;
+    ns = (uint64_t)std::llround((double)total / reps * 1e6);
     if (ns == 0) ns = 1;
     return UCD_OK;
 }
@@ -239,6 +255,7 @@ int bench_kernel(const ucd_layer_t *L, int op, size_t limit, int policy, void *x
     m.assign((size_t)UCD_N_ALGO * (B + 1), kWsNa);
     Events ev;
     if (hipEventCreate(&ev.a) != hipSuccess || hipEventCreate(&ev.b) != hipSuccess) return UCD_E_HIP;
+    bool spun = false;
     for (int b : policy_sizes(policy, B))
         for (int a = 0; a < UCD_N_ALGO; ++a) {
             const size_t need = ws_size(L, op, a, b);
@@ -248,6 +265,18 @@ int bench_kernel(const ucd_layer_t *L, int op, size_t limit, int policy, void *x
             const BenchKey k = key_of(L, op, a, b);
             uint64_t ns;
             if (!cache_get(k, ns)) {
+                if (!spun) {
+                    // A GPU that has sat idle (while the host prepared tensors, say) runs its first
+                    // kernels at a low clock: timings taken then came out 5-15 % too long, and since
+                    // they are cached, later plans compared fresh timings against stale slow ones.
+                    // Keep the device busy for a few milliseconds before the first measurement.
+                    const auto t0 = std::chrono::steady_clock::now();
+                    do {
+                        int rc = time_micro(L, op, a, b, x, w, y, ws, s, ev, ns);
+                        if (rc != UCD_OK) return rc;
+                    } while (std::chrono::steady_clock::now() - t0 < std::chrono::milliseconds(kSpinUpMs));
+                    spun = true;
+                }
                 int rc = time_micro(L, op, a, b, x, w, y, ws, s, ev, ns);
                 if (rc != UCD_OK) return rc;
                 cache_put(k, ns);
