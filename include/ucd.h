@@ -159,7 +159,10 @@ void ucd_plan_destroy(ucd_plan_t *plan);
  * The operation's output buffer is clobbered (FWD: y, BWD_DATA: x, BWD_FILTER: w); the other
  * two are only read.  For BWD_FILTER `w` stands in for dw and must hold K*C*R*S fp32 values
  * whatever the dtype.  Each timing is, after one warm-up run, the time per run of 2-8 runs
- * launched back to back on consecutive micro-batches of the buffers, in integer ns. */
+ * launched back to back on consecutive micro-batches of the buffers, in integer ns.  The
+ * planned configuration's micro-batches are stored grouped by algorithm and run in that order
+ * (consecutive Winograd micro-batches transform the filter once, so a configuration can run
+ * slightly faster than the sum of its standalone timings). */
 int ucd_plan(const ucd_layer_t *layer, int op, size_t ws_limit, int policy,
              void *x, void *w, void *y, void *ws, void *stream, ucd_plan_t **out);
 

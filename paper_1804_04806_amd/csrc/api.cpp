@@ -286,11 +286,16 @@ int bench_kernel(const ucd_layer_t *L, int op, size_t limit, int policy, void *x
     return UCD_OK;
 }
 
-ucd_plan_t *make_plan(const Config &cfg, const ucd_layer_t *L, int op)
+// group = true: a planner's configuration, whose micro-batches may run in any order, is stored with
+// those of one algorithm next to each other, so that consecutive Winograd micro-batches share
+// the transformed filter (see run_plan).  A caller's fixed configuration keeps its order.
+ucd_plan_t *make_plan(const Config &cfg, const ucd_layer_t *L, int op, bool group = true)
 {
     ucd_plan_t *p = new (std::nothrow) ucd_plan_t();
     if (!p) return nullptr;
     p->micro = cfg.micro;
+    if (group)
+        std::stable_sort(p->micro.begin(), p->micro.end(), [](const Micro &a, const Micro &b) { return a.algo < b.algo; });
     p->cost_ns = cfg.cost;
     p->ws_bytes = cfg.ws;
     p->op = op;
@@ -459,7 +464,7 @@ int ucd_plan_fixed(const ucd_layer_t *layer, int op, const ucd_micro_t *micro, i
             sum += micro[i].batch;
         }
         if (sum != layer->N) return UCD_E_INVALID;
-        ucd_plan_t *p = make_plan(cfg, layer, op);
+        ucd_plan_t *p = make_plan(cfg, layer, op, false);
         if (!p) return UCD_E_NOMEM;
         *out = p;
         return UCD_OK;
