@@ -110,3 +110,15 @@ BF16 = [t for t in ALEXNET if t[1].name in ("conv2", "conv4")] + [t for t in RES
 @pytest.mark.parametrize("idx,s,limit,policy", BF16, ids=lambda v: getattr(v, "name", None))
 def test_bf16_layers_planned(idx, s, limit, policy):
     check_layer(idx, s, limit, ucd.POLICY_POW2, n_samples=800, n_filter_samples=60, bf16=True)
+
+
+FIRST_LAYERS = [t for t in ALEXNET if t[1].name == "conv1"] + [t for t in RESNET18 if t[1].name == "stem"]
+
+
+@pytest.mark.parametrize("bf16", [False, True], ids=["f32", "bf16"])
+@pytest.mark.parametrize("idx,s,limit,policy", FIRST_LAYERS, ids=lambda v: getattr(v, "name", None))
+def test_first_layers_undivided_without_workspace(idx, s, limit, policy, bf16):
+    """No workspace, one micro-batch: the implicit GEMMs alone at their largest launch, among them
+    BackwardData with merged stride phases (C = 3: 4x4 blocks at stride 4, 4x4 blocks of two
+    strides at stride 2)."""
+    check_layer(idx, s, 0, ucd.POLICY_UNDIVIDED, n_samples=800, n_filter_samples=60, bf16=bf16)
