@@ -176,6 +176,16 @@ static hipError_t implicit_bwd_data_merged(const Dims &d, int b, const void *dy,
     return launch_gemm<L::template PhaseFilterKLane, L::template GatherNLaneBig, EpiPhasesT<E>, true>(pa, pb, pe, g, s);
 }
 
+// One phase GEMM with the gather loader that fits its tap count.
+template <template <int> class AL, template <int> class GatherSmall, template <int> class GatherBig, class Epi,
+          bool ROWS96>
+static hipError_t launch_phase(bool small, const KLaneParams &pa, const GatherParams &pb, const EpiNCHWParams &pe,
+                               const GemmShape &g, hipStream_t s)
+{
+    return small ? launch_gemm<AL, GatherSmall, Epi, ROWS96>(pa, pb, pe, g, s)
+                 : launch_gemm<AL, GatherBig, Epi, ROWS96>(pa, pb, pe, g, s);
+}
+
 // Stride phases: input pixels h with (h + ph) % sh == a are reached only by filter rows
 // r = a, a + sh, ...; within a phase the gather is a dense stride-1 correlation with the
 // sub-sampled, index-reversed filter.  Pixels of a phase with no tap get zeros (Kd = 0).
@@ -232,21 +242,29 @@ static hipError_t implicit_bwd_data_t(const Dims &d, int b, const void *dy, cons
             EpiNCHWParams pe{};
             pe.out = dx; pe.grid_hw = pb.grid_hw; pe.grid_w = pb.grid_w;
             pe.M = d.C; pe.HWo = d.H * d.W; pe.Wo = d.W; pe.h0 = h0; pe.hs = d.sh; pe.w0 = w0; pe.ws = d.sw;
+            // With 2-byte elements the filter operand is read with lanes along the input channels
+            // instead of the reduction rows (FilterNLaneT: fewer cache accesses per load; AlexNet
+            // conv4 at b = 256: 0.56 -> 0.44 ms), where the tile is not one that loader lacks (32
+            // and 96 rows) and the phase has at most 9 taps: its lanes are R*S elements apart, and
+            // on a 5x5 filter it is the slower one by far (conv2: 0.76 -> 1.46 ms).  In fp32, where
+            // vector and scalar instruction issue is the limit and not the memory pipeline, it
+            // measured 5-10 % slower even on 1x1 filters, whose channels are contiguous in memory.
+            const bool nlane = !F32 && d.C > 32 && pick_rows(d.C, true) != 96 && Ra * Sc <= 9;
+            const bool small = Ra * Sc <= 31;
             hipError_t e = hipSuccess;
             bool done = false;
             if constexpr (F32) {
                 if (split) {
-                    e = Ra * Sc <= 31
-                            ? launch_gemm<FilterKLane, GatherNLane, EpiNCHWAtomic, true>(pa, pb, pe, g, s)
-                            : launch_gemm<FilterKLane, GatherNLaneBig, EpiNCHWAtomic, true>(pa, pb, pe, g, s);
+                    e = launch_phase<FilterKLane, GatherNLane, GatherNLaneBig, EpiNCHWAtomic, true>(small, pa, pb, pe, g, s);
                     done = true;
                 }
             }
             g.tail_split = true;
             if (!done)
-                e = Ra * Sc <= 31
-                        ? launch_gemm<L::template FilterKLane, L::template GatherNLane, EpiNCHWT<E>, true>(pa, pb, pe, g, s)
-                        : launch_gemm<L::template FilterKLane, L::template GatherNLaneBig, EpiNCHWT<E>, true>(pa, pb, pe, g, s);
+                e = nlane ? launch_phase<L::template FilterNLane, L::template GatherNLane, L::template GatherNLaneBig,
+                                         EpiNCHWT<E>, false>(small, pa, pb, pe, g, s)
+                          : launch_phase<L::template FilterKLane, L::template GatherNLane, L::template GatherNLaneBig,
+                                         EpiNCHWT<E>, true>(small, pa, pb, pe, g, s);
             if (e != hipSuccess) return e;
         }
     return hipSuccess;

@@ -482,6 +482,85 @@ struct FilterKLaneT : NoSetup {
 
 template <int TD> using FilterKLane = FilterKLaneT<TD, float>;
 
+// The same operand with lanes along the tile positions (input channels c, `col_stride` = R*S
+// elements apart) and one reduction row per wave and pass: the row part k*k_stride + tap offset is
+// wave-uniform and enters as the load's scalar offset.  With 2-byte elements this order costs the
+// memory pipeline a third of the cache accesses per load of the reduction-lane loader above
+// (measured on 3x3 layers), which is what bounds the bf16 kernel; used for bf16 tensors only.
+// No 96-row tile (whole reduction rows per pass).
+template <int TD, class E = float>
+struct FilterNLaneT : NoSetup {
+    static constexpr uint32_t EB = Elem<E>::kBytes;
+    static constexpr bool kBf16 = std::is_same<E, bf16>::value;
+    static std::string name() { return std::string("FilterNLane") + Elem<E>::tag(); }
+    static_assert(kThreads % TD == 0, "whole reduction rows per pass");
+    static constexpr bool kUniformRows = TD >= 64;  // a wave stays inside one reduction row
+    static constexpr int RP = kThreads / TD;  // reduction rows per pass
+    static constexpr int NE = kBK / RP;       // elements per thread per step
+    static constexpr int LD = TD + kPad;
+    // where the row decode runs: see GatherNLaneT
+    static constexpr bool kLaneDecode = kBf16 && kUniformRows;
+    struct Regs { float r[NE]; };
+    const KLaneParams *p;
+    __amdgpu_buffer_rsrc_t rsrc;
+    int col, row0;
+    uint32_t voff;  // byte offset of the thread's tile position
+    uint32_t so_v;  // lane i: scalar byte offset of the thread's row i of this step (kLaneDecode)
+    int k0_, k_end_;
+
+    __device__ __forceinline__ void init(const KLaneParams &prm, int origin, int)
+    {
+        p = &prm;
+        rsrc = make_rsrc_bytes(prm.t, 0, prm.bytes);
+        col = threadIdx.x % TD;
+        row0 = kUniformRows ? __builtin_amdgcn_readfirstlane(threadIdx.x / TD) : threadIdx.x / TD;
+        // positions past the operand's extent read whatever lies there or zero: never stored
+        voff = EB * (uint32_t)((origin + col) * prm.col_stride);
+        so_v = kOob;
+    }
+    // byte offset of reduction row kk = (k, tap), or the "reads as zero" offset past the end
+    __device__ __forceinline__ uint32_t row_offset(int kk) const
+    {
+        uint32_t k, tap;
+        p->taps.divmod((uint32_t)kk, k, tap);
+        int roff;
+        if (p->unit_taps) {
+            roff = (int)k * p->k_stride + (int)tap;
+        } else {
+            uint32_t tr, ts;
+            p->taps_w.divmod(tap, tr, ts);
+            roff = (int)k * p->k_stride + (p->tap_add_h + p->tap_mul_h * (int)tr) * p->s_mem + p->tap_add_w +
+                   p->tap_mul_w * (int)ts;
+        }
+        return kk < k_end_ ? EB * (uint32_t)roff : kOob;
+    }
+    template <class Peer>
+    __device__ __forceinline__ void prep(int k0, int k_end, const Peer &)
+    {
+        k0_ = k0;
+        k_end_ = k_end;
+        if constexpr (kLaneDecode) so_v = row_offset(k0 + row0 + RP * (int)(threadIdx.x & (NE - 1)));
+    }
+    __device__ __forceinline__ void load(int i, float (&r)[NE]) const
+    {
+        if constexpr (!kUniformRows) {  // narrow tiles: the row differs within a wave
+            const uint32_t ro = row_offset(k0_ + row0 + RP * i);
+            r[i] = Elem<E>::load(rsrc, ro == kOob ? kOob : voff + ro, 0);
+            return;
+        }
+        uint32_t so;
+        if constexpr (kLaneDecode) so = (uint32_t)__builtin_amdgcn_readlane((int)so_v, i);
+        else so = row_offset(k0_ + row0 + RP * i);  // wave-uniform: scalar unit
+        r[i] = Elem<E>::load(rsrc, voff, so);
+    }
+    __device__ __forceinline__ int erow(int i) const { return row0 + RP * i; }
+    __device__ __forceinline__ int ecol(int i) const { return col; }
+    __device__ __forceinline__ void store(float *lds, int i, const float (&r)[NE]) const
+    {
+        lds[(row0 + RP * i) * LD + col] = r[i];
+    }
+};
+
 // BackwardData's A operand when the stride phases of a layer with few input channels are merged
 // into one GEMM: the tile position m = (c, a, b) names an input channel and a pixel of a
 // (vs_h x vs_w) block of dx (vs = a multiple f of the stride), the reduction row kk = (k, u, v) an
@@ -907,6 +986,7 @@ struct Loaders {
     template <int TD> using KLane0 = KLane0T<TD, E>;
     template <int TD> using FilterKLane = FilterKLaneT<TD, E>;
     template <int TD> using PhaseFilterKLane = PhaseFilterKLaneT<TD, E>;
+    template <int TD> using FilterNLane = FilterNLaneT<TD, E>;
     template <int TD> using GatherNLane = GatherNLaneT<TD, true, E>;
     template <int TD> using GatherNLaneBig = GatherNLaneT<TD, false, E>;
     template <int TD> using DyKLane = PixelKLane<TD, false, E>;

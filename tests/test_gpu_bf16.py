@@ -27,6 +27,7 @@ SHAPES = [
     Shape(3, 8, 30, 30, 16, 7, 7, 2, 3, "stem-like"),
     Shape(2, 3, 30, 31, 16, 7, 7, 2, 3, "stem-c3"),
     Shape(3, 20, 14, 14, 36, 3, 3, 2, 1, "down3x3"),
+    Shape(2, 64, 10, 10, 40, 3, 3, 2, 1, "c64-s2"),
     Shape(3, 20, 14, 14, 36, 1, 1, 2, 0, "proj1x1"),
     Shape(2, 40, 9, 9, 130, 1, 1, 1, 0, "1x1"),
     Shape(2, 6, 9, 12, 7, 2, 4, 1, 1, "evenfilter"),

@@ -36,6 +36,7 @@ SHAPES = [
     Shape(2, 5, 6, 9, 7, 3, 3, 1, 2, "pad2-3x3"),               # output larger than the input (8 x 11)
     Shape(2, 3, 30, 31, 16, 7, 7, 2, 3, "stem-c3"),             # BackwardData: stride phases merged in 4 x 4 pixel blocks
     Shape(2, 2, 25, 25, 5, 11, 11, 2, 5, "bigwin-s2"),          # merged phases with a 6 x 6 window of dy (per-axis masks)
+    Shape(2, 64, 10, 10, 40, 3, 3, 2, 1, "c64-s2"),             # BackwardData phases with 4, 2, 2 and 1 taps: both filter loaders
     Shape(3, 24, 56, 56, 64, 3, 3, 1, 1, "k64-wide"),          # 64-row tiles over many column tiles
     Shape(3, 96, 56, 56, 96, 3, 3, 1, 1, "c96-wide"),          # 96-row tiles, Forward and BackwardData, many column tiles
 ]
