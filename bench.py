@@ -32,21 +32,23 @@ FP32_MFMA_PEAK_TFLOPS = 157.3   # MI355X dense fp32 matrix peak: 256 CU x 2.4 GH
 BF16_MFMA_PEAK_TFLOPS = 2500.0  # dense bf16 matrix peak (16x the fp32 rate); kernels named gemm_kernel_bf16
 WS_LIMIT = 64 << 20
 
-# HBM bytes per launch (fetched + written) of the GEMM instantiations of the default workload's
-# planned step, from two rocprofv3 --pmc passes over this script (FETCH_SIZE, then WRITE_SIZE, each
-# scaled by what the counter reads for a plain device copy of known size: x2.00 and x1.00), mean
-# over the dispatches of a run whose benchmark cache came from a file, so that every dispatch has
-# a shape of the step.  Summary: profiles/bench_alexnet_b256_ws64MiB_kernel_stats.md.
-# A profiler cannot run inside the timed script, so these are recorded figures; they apply to
-# the AlexNet workload at batch 256 only and `traffic` is null for anything else.
-MEASURED_TRAFFIC_BYTES = {
-    "gemm_kernel<Tile<128x128>,PixelTab<dy>,PixelTab<x>,EpiAtomic>": 238.5e6,
-    "gemm_kernel<Tile<96x128>,PixelKLane<dy>,PixelKLane<x>,EpiAtomic>": 538.2e6,
-    "gemm_kernel<Tile<128x128>,KLane0,GatherNLane<taps<=31>,EpiNCHW>": 223.4e6,
-    "gemm_kernel<Tile<96x128>,FilterKLane,GatherNLane<taps<=31>,EpiNCHW>": 326.1e6,
-    "gemm_kernel<Tile<128x128>,FilterKLane,GatherNLane<taps<=31>,EpiNCHW>": 202.2e6,
-    "gemm_kernel<Tile<96x128>,KLane0,GatherNLane<taps>31>,EpiNCHW>": 273.6e6,
-    "gemm_kernel<Tile<64x128>,PhaseFilterKLane,GatherNLane<taps<=31>,EpiPhases>": 442.0e6,
+# HBM bytes (fetched + written) per algorithmic flop of the GEMM instantiations of the default
+# workload's planned step, from two rocprofv3 --pmc passes over this script (FETCH_SIZE, then
+# WRITE_SIZE, each scaled by what the counter reads for a plain device copy of known size: x2.00 and
+# x1.00): mean bytes per dispatch of a run whose benchmark cache came from a file (so that every
+# dispatch has a shape of the step), divided by the mean flops per launch of that run's step.
+# `traffic` = this figure x the flops per launch of the step being timed: the planner does not
+# pick the same micro-batch sizes every run, and a kernel's traffic follows its size.
+# Summary: profiles/bench_alexnet_b256_ws64MiB_kernel_stats.md.  A profiler cannot run inside the
+# timed script, so these are recorded figures; they apply to the AlexNet workload at batch 256
+# only and `traffic` is null for anything else.
+MEASURED_TRAFFIC_BYTES_PER_FLOP = {
+    "gemm_kernel<Tile<128x128>,PixelTab<dy>,PixelTab<x>,EpiAtomic>": 238.5e6 / 100.47e9,
+    "gemm_kernel<Tile<96x128>,PixelKLane<dy>,PixelKLane<x>,EpiAtomic>": 538.2e6 / 53.97e9,
+    "gemm_kernel<Tile<128x128>,KLane0,GatherNLane<taps<=31>,EpiNCHW>": 223.5e6 / 114.67e9,
+    "gemm_kernel<Tile<96x128>,FilterKLane,GatherNLane<taps<=31>,EpiNCHW>": 326.1e6 / 221.27e9,
+    "gemm_kernel<Tile<96x128>,KLane0,GatherNLane<taps>31>,EpiNCHW>": 274.0e6 / 26.99e9,
+    "gemm_kernel<Tile<64x128>,PhaseFilterKLane,GatherNLane<taps<=31>,EpiPhases>": 442.0e6 / 51.02e9,
 }
 
 # name -> (description, layer table, batch, per-layer limit or total budget, "wr" | "wd", default policy)
@@ -239,9 +241,12 @@ def dominant_kernel_roofline(torch, ucd, states, plans, ws, reps, traffic_table=
     peak = BF16_MFMA_PEAK_TFLOPS if name.startswith("gemm_kernel_bf16") else FP32_MFMA_PEAK_TFLOPS
     roof = {"bound": "mfma", "kernel": name, "achieved": round(achieved, 2), "peak": peak,
             "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
-            "traffic": (traffic_table or {}).get(name.split(" (after")[0]),
+            "traffic": None,
             "launches_per_step": g["launches"], "avg_launch_ms": round(g["ms"] / g["launches"], 4),
             "flops_per_launch": g["flops"] / g["launches"]}
+    per_flop = (traffic_table or {}).get(name.split(" (after")[0])
+    if per_flop is not None:
+        roof["traffic"] = round(per_flop * roof["flops_per_launch"])
     return roof, table
 
 
@@ -320,7 +325,7 @@ def main():
     tflops = flops_per_step / (ms * 1e-3) / 1e12
     roof, kernel_table = dominant_kernel_roofline(
         torch, ucd, states, plans, ws, reps=5,
-        traffic_table=MEASURED_TRAFFIC_BYTES if (args.workload, batch, args.dtype) == ("alexnet", 256, "f32") else None)
+        traffic_table=MEASURED_TRAFFIC_BYTES_PER_FLOP if (args.workload, batch, args.dtype) == ("alexnet", 256, "f32") else None)
 
     plan_report = []
     for st, p, u in zip(states, plans, undiv):
