@@ -38,17 +38,18 @@ WS_LIMIT = 64 << 20
 # x1.00): mean bytes per dispatch of a run whose benchmark cache came from a file (so that every
 # dispatch has a shape of the step), divided by the mean flops per launch of that run's step.
 # `traffic` = this figure x the flops per launch of the step being timed: the planner does not
-# pick the same micro-batch sizes every run, and a kernel's traffic follows its size.
+# pick the same micro-batch sizes every run, and a kernel's traffic follows its size (the ratio
+# itself differs by layer: 1.8e-3 to 2.7e-3 bytes per flop over the four BackwardFilter launches).
 # Summary: profiles/bench_alexnet_b256_ws64MiB_kernel_stats.md.  A profiler cannot run inside the
 # timed script, so these are recorded figures; they apply to the AlexNet workload at batch 256
 # only and `traffic` is null for anything else.
 MEASURED_TRAFFIC_BYTES_PER_FLOP = {
-    "gemm_kernel<Tile<128x128>,PixelTab<dy>,PixelTab<x>,EpiAtomic>": 238.5e6 / 100.47e9,
-    "gemm_kernel<Tile<96x128>,PixelKLane<dy>,PixelKLane<x>,EpiAtomic>": 538.2e6 / 53.97e9,
-    "gemm_kernel<Tile<128x128>,KLane0,GatherNLane<taps<=31>,EpiNCHW>": 223.5e6 / 114.67e9,
-    "gemm_kernel<Tile<96x128>,FilterKLane,GatherNLane<taps<=31>,EpiNCHW>": 326.1e6 / 221.27e9,
-    "gemm_kernel<Tile<96x128>,KLane0,GatherNLane<taps>31>,EpiNCHW>": 274.0e6 / 26.99e9,
-    "gemm_kernel<Tile<64x128>,PhaseFilterKLane,GatherNLane<taps<=31>,EpiPhases>": 442.0e6 / 51.02e9,
+    "gemm_kernel<Tile<128x128>,PixelTab<dy>,PixelTab<x>,EpiAtomic>": 283.0e6 / 133.56e9,
+    "gemm_kernel<Tile<96x128>,PixelKLane<dy>,PixelKLane<x>,EpiAtomic>": 538.3e6 / 53.97e9,
+    "gemm_kernel<Tile<128x128>,KLane0,GatherNLane<taps<=31>,EpiNCHW>": 326.3e6 / 229.32e9,
+    "gemm_kernel<Tile<96x128>,FilterKLane,GatherNLane<taps<=31>,EpiNCHW>": 322.2e6 / 214.09e9,
+    "gemm_kernel<Tile<96x128>,KLane0,GatherNLane<taps>31>,EpiNCHW>": 274.0e6 / 26.98e9,
+    "gemm_kernel<Tile<64x128>,PhaseFilterKLane,GatherNLane<taps<=31>,EpiPhases>": 451.9e6 / 52.71e9,
 }
 
 # name -> (description, layer table, batch, per-layer limit or total budget, "wr" | "wd", default policy)
