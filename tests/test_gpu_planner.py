@@ -189,3 +189,37 @@ def test_benchmark_db_roundtrip_on_device(tmp_path):
     assert again.query() == plan.query()
     ucd.ucd_conv_fwd(again, xd, wd, y, ws)
     torch.cuda.synchronize()
+
+
+def test_table_times_predict_a_configuration_run_in_sequence():
+    """The benchmark step times a micro-batch the way a configuration runs it (back to back, on
+    consecutive samples, after a clock spin-up), so the sum of table entries must predict the
+    time of the configuration executed in sequence.  Checked on forced divisions of a mid-size
+    3x3 layer; the bound is loose (25 %) because this is a timing, the measured agreement is
+    about 1 %."""
+    import torch
+    s = Shape(64, 256, 13, 13, 384, 3, 3, 1, 1, "conv3-b64")
+    desc = ucd.layer(s)
+    dev = torch.device("cuda:0")
+    x = torch.rand(s.x_shape, device=dev) * 2 - 1
+    w = torch.randn(s.w_shape, device=dev) * 0.05
+    y = torch.empty(s.y_shape, device=dev)
+    ws = torch.empty(4, device=dev)
+    ucd.ucd_bench_clear()
+    ucd.ucd_plan(desc, ucd.FWD, 0, ucd.POLICY_ALL, x, w, y, ws)
+    t, _ = ucd.ucd_bench_table(desc, ucd.FWD, s.N)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for parts in ([64], [32, 32], [48, 15, 1]):
+        plan = ucd.ucd_plan_fixed(desc, ucd.FWD, [(ucd.ALGO_IMPLICIT, b) for b in parts])
+        for _ in range(5):
+            ucd.ucd_conv_fwd(plan, x, w, y, ws)
+        torch.cuda.synchronize()
+        reps = 20
+        e0.record()
+        for _ in range(reps):
+            ucd.ucd_conv_fwd(plan, x, w, y, ws)
+        e1.record()
+        torch.cuda.synchronize()
+        measured = e0.elapsed_time(e1) / reps
+        predicted = sum(t[ucd.ALGO_IMPLICIT][b] for b in parts) / 1e6
+        assert 0.75 <= measured / predicted <= 1.25, (parts, measured, predicted)
