@@ -95,9 +95,10 @@ int ucd_version(void);
  * quantity compared with the limit M in step 1 of the WR algorithm, Section 3.2):
  *   implicit   0
  *   im2col     4 * C*R*S * ld,  ld = b*P*Q rounded up to 4
- *   Winograd   4 * a*a * (C*K4 + ld*(C + K)) with a = 4 (F(2x2,3x3)) or 6 (F(4x4,3x3)),
- *              ld = b * ceil(P/m) * ceil(Q/m) rounded up to 4 (m = a - 2), K4 = the operation's
- *              output channel count rounded up to 4 (BackwardFilter: K*C in place of C*K4)
+ *   Winograd   4 * a*a * (Ci*Co4 + ld*(C + K)) with a = 4 (F(2x2,3x3)) or 6 (F(4x4,3x3)),
+ *              ld = b * ceil(Ho/m) * ceil(Wo/m) rounded up to 4 (m = a - 2), where (Ci, Co, Ho, Wo)
+ *              = (C, K, P, Q) for Forward and (K, C, H, W) for BackwardData, Co4 = Co rounded up
+ *              to 4; BackwardFilter: K*C in place of Ci*Co4, tiles over (P, Q)
  * Returns UCD_WS_NA if the algorithm does not apply or an argument is invalid.  Host only. */
 size_t ucd_workspace_size(const ucd_layer_t *layer, int op, int algo, int b);
 
