@@ -244,12 +244,12 @@ static hipError_t implicit_bwd_data_t(const Dims &d, int b, const void *dy, cons
             pe.M = d.C; pe.HWo = d.H * d.W; pe.Wo = d.W; pe.h0 = h0; pe.hs = d.sh; pe.w0 = w0; pe.ws = d.sw;
             // With 2-byte elements the filter operand is read with lanes along the input channels
             // instead of the reduction rows (FilterNLaneT: fewer cache accesses per load; AlexNet
-            // conv4 at b = 256: 0.56 -> 0.44 ms), where the tile is not one that loader lacks (32
-            // and 96 rows) and the filter has at most 9 taps: its lanes are R*S elements apart, and
+            // conv4 at b = 256: 0.56 -> 0.44 ms), where the tile is not the one that loader lacks (96
+            // rows) and the filter has at most 9 taps: its lanes are R*S elements apart, and
             // on a 5x5 filter it is the slower one by far (conv2: 0.76 -> 1.46 ms).  In fp32, where
             // vector and scalar instruction issue is the limit and not the memory pipeline, it
             // measured 5-10 % slower even on 1x1 filters, whose channels are contiguous in memory.
-            const bool nlane = !F32 && d.C > 32 && pick_rows(d.C, true) != 96 && d.R * d.S <= 9;
+            const bool nlane = !F32 && pick_rows(d.C, true) != 96 && d.R * d.S <= 9;
             const bool small = Ra * Sc <= 31;
             hipError_t e = hipSuccess;
             bool done = false;
