@@ -260,11 +260,16 @@ static hipError_t implicit_bwd_data_t(const Dims &d, int b, const void *dy, cons
                 }
             }
             g.tail_split = true;
+            if constexpr (!F32) {
+                if (nlane) {
+                    e = launch_phase<L::template FilterNLane, L::template GatherNLane, L::template GatherNLaneBig,
+                                     EpiNCHWT<E>, false>(small, pa, pb, pe, g, s);
+                    done = true;
+                }
+            }
             if (!done)
-                e = nlane ? launch_phase<L::template FilterNLane, L::template GatherNLane, L::template GatherNLaneBig,
-                                         EpiNCHWT<E>, false>(small, pa, pb, pe, g, s)
-                          : launch_phase<L::template FilterKLane, L::template GatherNLane, L::template GatherNLaneBig,
-                                         EpiNCHWT<E>, true>(small, pa, pb, pe, g, s);
+                e = launch_phase<L::template FilterKLane, L::template GatherNLane, L::template GatherNLaneBig,
+                                 EpiNCHWT<E>, true>(small, pa, pb, pe, g, s);
             if (e != hipSuccess) return e;
         }
     return hipSuccess;
