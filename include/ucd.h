@@ -73,7 +73,12 @@ enum { UCD_FWD = 0, UCD_BWD_DATA = 1, UCD_BWD_FILTER = 2, UCD_N_OP = 3 };
  * three operations, BackwardFilter as F(3x3,2x2) / F(3x3,4x4); the larger tile does 36 products
  * per 16 outputs instead of 16 per 4 and needs less workspace per sample, at a looser rounding
  * error). */
-enum { UCD_ALGO_IMPLICIT = 0, UCD_ALGO_IM2COL = 1, UCD_ALGO_WINOGRAD = 2, UCD_ALGO_WINOGRAD4 = 3, UCD_N_ALGO = 4 };
+enum {
+    UCD_ALGO_IMPLICIT = 0, UCD_ALGO_IM2COL = 1, UCD_ALGO_WINOGRAD = 2, UCD_ALGO_WINOGRAD4 = 3,
+    UCD_ALGO_FFT = 4,  /* tiled FFT (16x16 tiles): stride-1 layers, filters up to 9x9, Forward and
+                        * BackwardData; the largest workspace of all (144 frequency planes) */
+    UCD_N_ALGO = 5
+};
 
 /* Batch-size policies of Section 3.4: which micro-batch sizes get benchmarked. */
 enum { UCD_POLICY_UNDIVIDED = 0, UCD_POLICY_POW2 = 1, UCD_POLICY_ALL = 2 };
@@ -99,6 +104,8 @@ int ucd_version(void);
  *              ld = b * ceil(Ho/m) * ceil(Wo/m) rounded up to 4 (m = a - 2), where (Ci, Co, Ho, Wo)
  *              = (C, K, P, Q) for Forward and (K, C, H, W) for BackwardData, Co4 = Co rounded up
  *              to 4; BackwardFilter: K*C in place of Ci*Co4, tiles over (P, Q)
+ *   FFT        4 * 144 * (2Ci*M4 + ld*(2Ci + 2Co)), M4 = 2Co rounded up to 4, ld = b *
+ *              ceil(Ho/(17-R)) * ceil(Wo/(17-S)) rounded up to 4, (Ci, Co, Ho, Wo) as for Winograd
  * Returns UCD_WS_NA if the algorithm does not apply or an argument is invalid.  Host only. */
 size_t ucd_workspace_size(const ucd_layer_t *layer, int op, int algo, int b);
 

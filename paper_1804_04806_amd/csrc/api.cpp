@@ -70,6 +70,8 @@ bool fits_32bit(const ucd_layer_t *L, int b)
 // output tile edge of a Winograd algorithm id
 inline int wino_tile(int algo) { return algo == UCD_ALGO_WINOGRAD4 ? 4 : 2; }
 inline bool is_winograd(int algo) { return algo == UCD_ALGO_WINOGRAD || algo == UCD_ALGO_WINOGRAD4; }
+// algorithms that keep a transformed filter at the head of the workspace
+inline bool keeps_filter(int algo) { return is_winograd(algo) || algo == UCD_ALGO_FFT; }
 
 size_t ws_size(const ucd_layer_t *L, int op, int algo, int b)
 {
@@ -92,6 +94,11 @@ size_t ws_size(const ucd_layer_t *L, int op, int algo, int b)
         if (winograd_ws_bytes(d, op, b, mt) / (4 * planes) > (size_t)kMaxOperandFloats) return UCD_WS_NA;
         return winograd_ws_bytes(d, op, b, mt);
     }
+    case UCD_ALGO_FFT:
+        if (!fft_applies(d, op)) return UCD_WS_NA;
+        // every frequency plane is one GEMM operand
+        if (fft_ws_bytes(d, op, b) / (4 * 144) > (size_t)kMaxOperandFloats) return UCD_WS_NA;
+        return fft_ws_bytes(d, op, b);
     default:
         return UCD_WS_NA;
     }
@@ -126,6 +133,10 @@ int run_micro(const ucd_layer_t *L, int op, int algo, int b, const void *a, cons
         else if (op == UCD_BWD_DATA) e = winograd_bwd_data(d, b, a, bsrc, out, ws, filter_ready, wino_tile(algo), s);
         else e = winograd_bwd_filter(d, b, a, bsrc, (float *)out, beta, ws, wino_tile(algo), s);
         break;
+    case UCD_ALGO_FFT:
+        if (op == UCD_FWD) e = fft_fwd(d, b, a, bsrc, out, ws, filter_ready, s);
+        else if (op == UCD_BWD_DATA) e = fft_bwd_data(d, b, a, bsrc, out, ws, filter_ready, s);
+        break;
     }
     return hip_status(e);
 }
@@ -150,7 +161,7 @@ int run_plan(const ucd_plan_t *plan, int op, const void *a_, const void *bsrc_, 
     for (const Micro &m : plan->micro) {
         int rc;
         // consecutive Winograd micro-batches of one call share the transformed filter in the workspace
-        const bool filter_ready = is_winograd(m.algo) && prev_algo == m.algo;
+        const bool filter_ready = keeps_filter(m.algo) && prev_algo == m.algo;
         prev_algo = m.algo;
         if (op == UCD_FWD)
             rc = run_micro(L, op, m.algo, m.batch, a + o * x_img, bsrc, out + o * y_img, 0.f, (float *)ws,

@@ -14,7 +14,7 @@ def main():
     ap.add_argument("--net", default="alexnet", choices=["small", "alexnet", "resnet18", "densenet", "resnet50"])
     ap.add_argument("--layer", default="conv4")
     ap.add_argument("--op", default="fwd", choices=["fwd", "bwd_data", "bwd_filter"])
-    ap.add_argument("--algo", default="implicit", choices=["implicit", "im2col", "winograd", "winograd4"])
+    ap.add_argument("--algo", default="implicit", choices=["implicit", "im2col", "winograd", "winograd4", "fft"])
     ap.add_argument("--b", type=int, default=256)
     ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"],
                     help="bf16: x, w, dy, y, dx stored as bfloat16 (dw fp32)")
@@ -69,7 +69,7 @@ def main():
     s = next(l for l in nets[args.net]() if l.name == args.layer).with_batch(args.b)
     op = {"fwd": ucd.FWD, "bwd_data": ucd.BWD_DATA, "bwd_filter": ucd.BWD_FILTER}[args.op]
     algo = {"implicit": ucd.ALGO_IMPLICIT, "im2col": ucd.ALGO_IM2COL, "winograd": ucd.ALGO_WINOGRAD,
-            "winograd4": ucd.ALGO_WINOGRAD4}[args.algo]
+            "winograd4": ucd.ALGO_WINOGRAD4, "fft": ucd.ALGO_FFT}[args.algo]
     dev = torch.device("cuda:0")
     desc = ucd.layer(s, dtype=1 if args.dtype == "bf16" else 0)
     need = ucd.ucd_workspace_size(desc, op, algo, args.b)

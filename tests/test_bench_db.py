@@ -14,7 +14,7 @@ def fill(desc, op, B, seed):
         for b in range(1, B + 1):
             if ucd.ucd_workspace_size(desc, op, a, b) == ucd.WS_NA:
                 continue
-            t[a][b] = 1000 * (4 - a) * b + r.randint(0, 5000) + 20000
+            t[a][b] = 1000 * (ucd.N_ALGO - a) * b + r.randint(0, 5000) + 20000
             ucd.ucd_bench_put(desc, op, a, b, t[a][b])
     return t
 

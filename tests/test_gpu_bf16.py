@@ -96,7 +96,7 @@ def test_bf16_parity_all_algorithms_and_divisions(s, op):
             got = run_hip_bf16(s, op, [(algo, b) for b in parts], bits)
             ctx = (s.name, ucd.OP_NAMES[op], ucd.ALGO_NAMES[algo], parts)
             if op == ucd.BWD_FILTER:
-                tol = 1e-3 if algo in ucd.WINOGRAD_ALGOS else 1e-5
+                tol = 1e-3 if algo in ucd.TRANSFORM_ALGOS else 1e-5
                 assert rel_l2(got, ref) <= tol, (ctx, rel_l2(got, ref))
             else:
                 check_bf16_output(got, ref, ctx)

@@ -71,7 +71,7 @@ def check_layer(idx, s, limit, policy, n_samples=1500, n_filter_samples=150, bf1
     def tol(p):
         if bf16 and p is not pw:
             return 5e-3
-        return 1e-3 if any(a in ucd.WINOGRAD_ALGOS for a, _ in p.micro) else 1e-5
+        return 1e-3 if any(a in ucd.TRANSFORM_ALGOS for a, _ in p.micro) else 1e-5
 
     iy = synth.sample_indices(y.size, n_samples, seed=1)
     e = rel_l2(y.ravel()[iy], oc.conv_fwd_at(L, x64, w64, iy))
