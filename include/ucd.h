@@ -75,8 +75,8 @@ enum { UCD_FWD = 0, UCD_BWD_DATA = 1, UCD_BWD_FILTER = 2, UCD_N_OP = 3 };
  * error). */
 enum {
     UCD_ALGO_IMPLICIT = 0, UCD_ALGO_IM2COL = 1, UCD_ALGO_WINOGRAD = 2, UCD_ALGO_WINOGRAD4 = 3,
-    UCD_ALGO_FFT = 4,  /* tiled FFT (16x16 tiles): stride-1 layers, filters up to 9x9, Forward and
-                        * BackwardData; the largest workspace of all (144 frequency planes) */
+    UCD_ALGO_FFT = 4,  /* tiled FFT (16x16 tiles): stride-1 layers, filters up to 9x9, all three
+                        * operations; the largest workspace of all (144 frequency planes) */
     UCD_N_ALGO = 5
 };
 
@@ -105,7 +105,8 @@ int ucd_version(void);
  *              = (C, K, P, Q) for Forward and (K, C, H, W) for BackwardData, Co4 = Co rounded up
  *              to 4; BackwardFilter: K*C in place of Ci*Co4, tiles over (P, Q)
  *   FFT        4 * 144 * (2Ci*M4 + ld*(2Ci + 2Co)), M4 = 2Co rounded up to 4, ld = b *
- *              ceil(Ho/(17-R)) * ceil(Wo/(17-S)) rounded up to 4, (Ci, Co, Ho, Wo) as for Winograd
+ *              ceil(Ho/(17-R)) * ceil(Wo/(17-S)) rounded up to 4, (Ci, Co, Ho, Wo) as for Winograd;
+ *              BackwardFilter: 4*K*C in place of 2Ci*M4, tiles over (P, Q)
  * Returns UCD_WS_NA if the algorithm does not apply or an argument is invalid.  Host only. */
 size_t ucd_workspace_size(const ucd_layer_t *layer, int op, int algo, int b);
 

@@ -136,6 +136,7 @@ int run_micro(const ucd_layer_t *L, int op, int algo, int b, const void *a, cons
     case UCD_ALGO_FFT:
         if (op == UCD_FWD) e = fft_fwd(d, b, a, bsrc, out, ws, filter_ready, s);
         else if (op == UCD_BWD_DATA) e = fft_bwd_data(d, b, a, bsrc, out, ws, filter_ready, s);
+        else e = fft_bwd_filter(d, b, a, bsrc, (float *)out, beta, ws, s);
         break;
     }
     return hip_status(e);

@@ -14,6 +14,14 @@
 // The transforms are separable 16-point FFTs in registers (fft16.hpp) with one pass through LDS.
 // BackwardData is the same pipeline on dy with the filter's two channel indices swapped and its
 // taps reversed, and padding (R-1-pad_h, S-1-pad_w).
+//
+// BackwardFilter: a tile's filter gradient is the correlation of its 16x16 tile of x with its
+// (17-R) x (17-S) tile of dy (zero-padded to 16x16), so in the frequency domain
+//   Mw_f[k][c] = sum over tiles j of V_f[c][j] conj(D_f[k][j]),    dw = beta*dw + IDFT(Mw)[0..R)[0..S)
+// with V and D the input transforms of x and dy.  One real GEMM per frequency, reduction over the
+// tiles (split, atomics), gives the four real products  P = [Dr; Di] [Vr; Vi]^T  (2K x 2C), which
+// the output kernel combines (Mr = Prr + Pii, Mi = Pri - Pir) before it inverts:
+//   Mw[144][2K][2C]    V[144][2C][ld]    D[144][2K][ld]
 #include "fft16.hpp"
 #include "gemm_launch.hpp"
 #include "kernels.h"
@@ -27,7 +35,8 @@ struct FftGeom {
     int Ci, Co, Hi, Wi, Ho, Wo, pad_h, pad_w, R, S;
     int Th, Tw, TH, TW, T;  // output tile, tiles per image
     int M4, ld;
-    bool transposed;  // BackwardData: filter read as w[ci][co] with reversed taps
+    int win_h, win_w;  // rows / columns of a tile that are read (the rest of the 16x16 tile is zero)
+    bool transposed;   // BackwardData: filter read as w[ci][co] with reversed taps
 };
 
 static FftGeom fft_geom(const Dims &d, int op, int b)
@@ -45,12 +54,13 @@ static FftGeom fft_geom(const Dims &d, int op, int b)
     g.TH = (g.Ho + g.Th - 1) / g.Th; g.TW = (g.Wo + g.Tw - 1) / g.Tw; g.T = g.TH * g.TW;
     g.M4 = (2 * g.Co + 3) / 4 * 4;
     g.ld = (b * g.T + 3) / 4 * 4;
+    g.win_h = g.win_w = kFftN;
     return g;
 }
 
 bool fft_applies(const Dims &d, int op)
 {
-    if (op != 0 && op != 1) return false;
+    if (op < 0 || op > 2) return false;
     if (d.sh != 1 || d.sw != 1) return false;
     if (d.R > 9 || d.S > 9 || d.R * d.S < 2) return false;  // output tiles of at least 8 x 8
     return d.ph <= d.R - 1 && d.pw <= d.S - 1;
@@ -58,6 +68,10 @@ bool fft_applies(const Dims &d, int op)
 
 size_t fft_ws_bytes(const Dims &d, int op, int b)
 {
+    if (op == 2) {  // Mw, V, D
+        const FftGeom g = fft_geom(d, 0, b);
+        return (size_t)4 * kFftFreqs * ((size_t)4 * d.K * d.C + (size_t)g.ld * (2 * d.C + 2 * d.K));
+    }
     const FftGeom g = fft_geom(d, op, b);
     return (size_t)4 * kFftFreqs * ((size_t)2 * g.Ci * g.M4 + (size_t)g.ld * (2 * g.Ci + 2 * g.Co));
 }
@@ -140,7 +154,7 @@ __global__ __launch_bounds__(256) void fft_input_kernel(const void *__restrict__
         divTW.divmod(t, th, tw);
     }
     const int h = (int)th * g.Th - g.pad_h + ia, w0 = (int)tw * g.Tw - g.pad_w;
-    const bool row_ok = live && (unsigned)h < (unsigned)g.Hi;
+    const bool row_ok = live && (unsigned)h < (unsigned)g.Hi && ia < g.win_h;
     // column phase: frequency column vb, tile tb (threads 0..143)
     const int vb = tid / kFftTilesPerBlock, tb = tid % kFftTilesPerBlock;
     const int jb = j0 + tb;
@@ -151,7 +165,7 @@ __global__ __launch_bounds__(256) void fft_input_kernel(const void *__restrict__
 #pragma unroll
         for (int c = 0; c < kFftN; ++c) {
             const int ww = w0 + c;
-            re[c] = (row_ok && (unsigned)ww < (unsigned)g.Wi) ? Elem<E>::get(x, src + ww) : 0.f;
+            re[c] = (row_ok && c < g.win_w && (unsigned)ww < (unsigned)g.Wi) ? Elem<E>::get(x, src + ww) : 0.f;
             im[c] = 0.f;
         }
         fft16<-1>(re, im);
@@ -290,6 +304,119 @@ static hipError_t fft_run(const Dims &d, int op, int b, const void *in, const vo
     fft_output_kernel<E><<<dim3(oblocks, (unsigned)(g.Co < 1024 ? g.Co : 1024)), 256, 0, s>>>(Z, out, g, divT, divTW,
                                                                                             n_tiles);
     return hipGetLastError();
+}
+
+// dw[k][c] = beta * dw[k][c] + the first R x S values of the inverse transform of
+// Mw[.][k][c] = (Prr + Pii) + i (Pri - Pir), P = the 2K x 2C product matrix of one frequency.
+// A workgroup handles 16 consecutive input channels of one output channel.
+__global__ __launch_bounds__(256) void fft_dw_kernel(const float *__restrict__ P, float *__restrict__ dw, int K, int C,
+                                                     int R, int S, float beta)
+{
+    __shared__ float sre[kFftTilesPerBlock * kFftN * kFftHalf], sim[kFftTilesPerBlock * kFftN * kFftHalf];
+    const int tid = threadIdx.x;
+    const int k = blockIdx.y, c0 = blockIdx.x * kFftTilesPerBlock;
+    const size_t plane = (size_t)4 * K * C, row = (size_t)2 * C;
+    float re[kFftN], im[kFftN];
+    {
+        const int va = tid / kFftTilesPerBlock, ca = tid % kFftTilesPerBlock;
+        const int c = c0 + ca;
+        if (va < kFftHalf) {
+            const bool ok = c < C;
+            const float *src = P + (ok ? c : 0);
+#pragma unroll
+            for (int u = 0; u < kFftN; ++u) {
+                const float *p = src + (size_t)(u * kFftHalf + va) * plane;
+                const float rr = ok ? p[(size_t)k * row] : 0.f, ri = ok ? p[(size_t)k * row + C] : 0.f;
+                const float ir = ok ? p[(size_t)(K + k) * row] : 0.f, ii = ok ? p[(size_t)(K + k) * row + C] : 0.f;
+                re[u] = rr + ii;
+                im[u] = ri - ir;
+            }
+            fft16<1>(re, im);
+#pragma unroll
+            for (int a = 0; a < kFftN; ++a) {
+                sre[(ca * kFftN + a) * kFftHalf + va] = re[a];
+                sim[(ca * kFftN + a) * kFftHalf + va] = im[a];
+            }
+        }
+    }
+    __syncthreads();
+    const int cb = tid / kFftN, ab = tid % kFftN;
+    const int c = c0 + cb;
+#pragma unroll
+    for (int v = 0; v < kFftHalf; ++v) {
+        re[v] = sre[(cb * kFftN + ab) * kFftHalf + v];
+        im[v] = sim[(cb * kFftN + ab) * kFftHalf + v];
+    }
+#pragma unroll
+    for (int v = kFftHalf; v < kFftN; ++v) {
+        re[v] = re[kFftN - v];
+        im[v] = -im[kFftN - v];
+    }
+    fft16<1>(re, im);
+    if (c < C && ab < R) {
+        float *dst = dw + (((size_t)k * C + c) * R + ab) * S;
+#pragma unroll
+        for (int s = 0; s < kFftN; ++s)
+            if (s < S) {
+                const float v = re[s] * (1.f / 256.f);
+                dst[s] = beta == 0.f ? v : beta * dst[s] + v;
+            }
+    }
+}
+
+template <class E>
+static hipError_t fft_filter_run(const Dims &d, int b, const void *x, const void *dy, float *dw, float beta, float *ws,
+                                 hipStream_t s)
+{
+    const FftGeom gx = fft_geom(d, 0, b);  // x: the Forward input tiles
+    FftGeom gd = gx;                        // dy: the output tiles, zero-padded to 16x16
+    gd.Ci = d.K; gd.Hi = d.P; gd.Wi = d.Q; gd.pad_h = 0; gd.pad_w = 0;
+    gd.win_h = gx.Th; gd.win_w = gx.Tw;
+    const int n_tiles = b * gx.T;
+    float *Mw = ws;
+    float *V = Mw + (size_t)kFftFreqs * 4 * d.K * d.C;
+    float *D = V + (size_t)kFftFreqs * 2 * d.C * gx.ld;
+    const FastDiv divT(gx.T), divTW(gx.TW);
+
+    LaunchLog *log = launch_log();
+    hipError_t e = fill_zero(Mw, (size_t)kFftFreqs * 4 * d.K * d.C, s);
+    if (e != hipSuccess) return e;
+    const unsigned blocks = (unsigned)((gx.ld + kFftTilesPerBlock - 1) / kFftTilesPerBlock);
+    if (log) {
+        log->add("fft_input_kernel");
+        log->add("fft_input_kernel");
+    } else {
+        fft_input_kernel<E><<<dim3(blocks, (unsigned)(d.C < 1024 ? d.C : 1024)), 256, 0, s>>>(x, V, gx, divT, divTW, n_tiles);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        fft_input_kernel<E><<<dim3(blocks, (unsigned)(d.K < 1024 ? d.K : 1024)), 256, 0, s>>>(dy, D, gd, divT, divTW, n_tiles);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    GemmShape gs{2 * d.K, 2 * d.C, n_tiles};
+    gs.batch = kFftFreqs;
+    gs.a_batch = (long)2 * d.K * gx.ld;
+    gs.b_batch = (long)2 * d.C * gx.ld;
+    gs.c_batch = (long)4 * d.K * d.C;
+    gs.splits = filter_splits(gs.M, gs.N, gs.Kd, kFftFreqs);
+    KLaneParams pa{};
+    pa.t = D; pa.bytes = (uint32_t)(gs.a_batch * 4); pa.row_stride = 1; pa.col_stride = gx.ld;
+    KLaneParams pb{};
+    pb.t = V; pb.bytes = (uint32_t)(gs.b_batch * 4); pb.row_stride = 1; pb.col_stride = gx.ld;
+    EpiDenseParams pe{Mw, 2 * d.C};
+    if ((e = launch_gemm<KLane0, KLane0, EpiAtomic, true>(pa, pb, pe, gs, s)) != hipSuccess) return e;
+    if (log) {
+        log->add("fft_dw_kernel");
+        return hipSuccess;
+    }
+    const dim3 go((unsigned)((d.C + kFftTilesPerBlock - 1) / kFftTilesPerBlock), (unsigned)d.K);
+    fft_dw_kernel<<<go, 256, 0, s>>>(Mw, dw, d.K, d.C, d.R, d.S, beta);
+    return hipGetLastError();
+}
+
+hipError_t fft_bwd_filter(const Dims &d, int b, const void *x, const void *dy, float *dw, float beta, float *ws,
+                          hipStream_t s)
+{
+    return d.dtype == 1 ? fft_filter_run<bf16>(d, b, x, dy, dw, beta, ws, s)
+                        : fft_filter_run<float>(d, b, x, dy, dw, beta, ws, s);
 }
 
 hipError_t fft_fwd(const Dims &d, int b, const void *x, const void *w, void *y, float *ws, bool filter_ready,

@@ -51,14 +51,16 @@ hipError_t winograd_bwd_data(const Dims &d, int b, const void *dy, const void *w
 hipError_t winograd_bwd_filter(const Dims &d, int b, const void *x, const void *dy, float *dw, float beta,
                                float *ws, int mt, hipStream_t s);
 
-// Tiled-FFT convolution (16x16 tiles), stride-1 layers with filters up to 9x9, Forward and
-// BackwardData; filter_ready as for Winograd.
+// Tiled-FFT convolution (16x16 tiles), stride-1 layers with filters up to 9x9; filter_ready as
+// for Winograd (Forward and BackwardData).
 bool fft_applies(const Dims &d, int op);
 size_t fft_ws_bytes(const Dims &d, int op, int b);
 hipError_t fft_fwd(const Dims &d, int b, const void *x, const void *w, void *y, float *ws, bool filter_ready,
                    hipStream_t s);
 hipError_t fft_bwd_data(const Dims &d, int b, const void *dy, const void *w, void *dx, float *ws, bool filter_ready,
                         hipStream_t s);
+hipError_t fft_bwd_filter(const Dims &d, int b, const void *x, const void *dy, float *dw, float beta, float *ws,
+                          hipStream_t s);
 
 hipError_t fill_zero(float *p, size_t n, hipStream_t s);
 // reduction splits of a BackwardFilter-shaped GEMM (small output, long reduction), `batch` of which

@@ -45,7 +45,7 @@ def test_workspace_formulas():
     assert ucd.ucd_workspace_size(L, ucd.BWD_FILTER, ucd.ALGO_WINOGRAD4, 2) == 144 * (16 * 32 + 32 * 48)
     # FFT: 144 planes of 4 bytes, 14 x 14 output tiles: T = 2*2, 2C*2K + ld*(2C + 2K)
     assert ucd.ucd_workspace_size(L, ucd.FWD, ucd.ALGO_FFT, 3) == 4 * 144 * (32 * 64 + 12 * 96)
-    assert ucd.ucd_workspace_size(L, ucd.BWD_FILTER, ucd.ALGO_FFT, 1) == ucd.WS_NA
+    assert ucd.ucd_workspace_size(L, ucd.BWD_FILTER, ucd.ALGO_FFT, 1) == 4 * 144 * (4 * 32 * 16 + 4 * 96)
     Ls2 = ucd.layer(N=8, C=16, H=16, W=16, K=32, R=3, S=3, pad_h=1, pad_w=1, stride_h=2, stride_w=2)
     assert ucd.ucd_workspace_size(Ls2, ucd.BWD_FILTER, ucd.ALGO_WINOGRAD, 1) == ucd.WS_NA  # stride 2
     L11 = ucd.layer(N=4, C=8, H=7, W=7, K=8, R=1, S=1)
