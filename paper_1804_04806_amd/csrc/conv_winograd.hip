@@ -23,8 +23,9 @@
 
 namespace ucd {
 
-// The three one-dimensional transforms of F(m,3); the two-dimensional ones apply them to the
-// columns and then to the rows of a tile.
+// The one-dimensional transforms of F(m,3) (filter, input, output) and of the transposed algorithm
+// F(3,m) BackwardFilter uses (grad = A z, filter_t = G^T m); the two-dimensional ones apply them to
+// the columns and then to the rows of a tile.
 template <int MT>
 struct Wino;
 
