@@ -29,7 +29,8 @@
 namespace ucd {
 
 constexpr int kFftN = 16, kFftHalf = 9, kFftFreqs = kFftN * kFftHalf;
-constexpr int kFftTilesPerBlock = 16;  // 16 tiles x 16 rows = one 256-thread workgroup
+constexpr int kFftTilesPerBlock = 32;  // tiles (filters, channel pairs) per workgroup: 128-byte rows of lanes
+constexpr int kFftThreads = kFftTilesPerBlock * kFftN;  // one thread per (tile, row)
 
 struct FftGeom {
     int Ci, Co, Hi, Wi, Ho, Wo, pad_h, pad_w, R, S;
@@ -77,12 +78,12 @@ size_t fft_ws_bytes(const Dims &d, int op, int b)
 }
 
 // AT[f][kk][m] for all 144 frequencies: U = the 2-D transform of the filter zero-padded to 16x16.
-// A workgroup transforms the filters of 16 consecutive output channels for one input channel:
+// A workgroup transforms the filters of 32 consecutive output channels for one input channel:
 // thread (filter, row) does the row FFT of the padded filter, the results cross through LDS,
 // thread (frequency column, filter) does the column FFT and writes the four entries of the block
 // matrix with lanes along the output channel.
 template <class E>
-__global__ __launch_bounds__(256) void fft_filter_kernel(const void *__restrict__ w, float *__restrict__ AT,
+__global__ __launch_bounds__(kFftThreads) void fft_filter_kernel(const void *__restrict__ w, float *__restrict__ AT,
                                                          FftGeom g)
 {
     __shared__ float sre[kFftTilesPerBlock * kFftHalf * kFftN], sim[kFftTilesPerBlock * kFftHalf * kFftN];
@@ -134,11 +135,11 @@ __global__ __launch_bounds__(256) void fft_filter_kernel(const void *__restrict_
 }
 
 // B[f][ci][j] (real part) and B[f][Ci + ci][j] (imaginary part) of the 16x16 input tile j.  A
-// workgroup transforms 16 tiles of one channel: thread (tile, row) does the row FFT, the results
+// workgroup transforms 32 tiles of one channel: thread (tile, row) does the row FFT, the results
 // cross through LDS, thread (frequency column, tile) does the column FFT and writes with lanes
 // along the tile index.
 template <class E>
-__global__ __launch_bounds__(256) void fft_input_kernel(const void *__restrict__ x, float *__restrict__ B, FftGeom g,
+__global__ __launch_bounds__(kFftThreads) void fft_input_kernel(const void *__restrict__ x, float *__restrict__ B, FftGeom g,
                                                         FastDiv divT, FastDiv divTW, int n_tiles)
 {
     __shared__ float sre[kFftTilesPerBlock * kFftHalf * kFftN], sim[kFftTilesPerBlock * kFftHalf * kFftN];
@@ -198,7 +199,7 @@ __global__ __launch_bounds__(256) void fft_input_kernel(const void *__restrict__
 // imaginary part).  Thread (frequency column, tile) inverts along u, the results cross through
 // LDS, thread (tile, row a) completes the Hermitian half along v, inverts and stores its row.
 template <class E>
-__global__ __launch_bounds__(256) void fft_output_kernel(const float *__restrict__ Z, void *__restrict__ out,
+__global__ __launch_bounds__(kFftThreads) void fft_output_kernel(const float *__restrict__ Z, void *__restrict__ out,
                                                          FftGeom g, FastDiv divT, FastDiv divTW, int n_tiles)
 {
     __shared__ float sre[kFftTilesPerBlock * kFftN * kFftHalf], sim[kFftTilesPerBlock * kFftN * kFftHalf];
@@ -276,14 +277,14 @@ static hipError_t fft_run(const Dims &d, int op, int b, const void *in, const vo
         log->add("fft_filter_kernel");
     } else {
         const dim3 gf((unsigned)((g.Co + kFftTilesPerBlock - 1) / kFftTilesPerBlock), (unsigned)g.Ci);
-        fft_filter_kernel<E><<<gf, 256, 0, s>>>(w, AT, g);
+        fft_filter_kernel<E><<<gf, kFftThreads, 0, s>>>(w, AT, g);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     const unsigned blocks = (unsigned)((g.ld + kFftTilesPerBlock - 1) / kFftTilesPerBlock);
     if (log) {
         log->add("fft_input_kernel");
     } else {
-        fft_input_kernel<E><<<dim3(blocks, (unsigned)(g.Ci < 1024 ? g.Ci : 1024)), 256, 0, s>>>(in, B, g, divT, divTW,
+        fft_input_kernel<E><<<dim3(blocks, (unsigned)(g.Ci < 1024 ? g.Ci : 1024)), kFftThreads, 0, s>>>(in, B, g, divT, divTW,
                                                                                               n_tiles);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
@@ -301,15 +302,15 @@ static hipError_t fft_run(const Dims &d, int op, int b, const void *in, const vo
         return hipSuccess;
     }
     const unsigned oblocks = (unsigned)((n_tiles + kFftTilesPerBlock - 1) / kFftTilesPerBlock);
-    fft_output_kernel<E><<<dim3(oblocks, (unsigned)(g.Co < 1024 ? g.Co : 1024)), 256, 0, s>>>(Z, out, g, divT, divTW,
+    fft_output_kernel<E><<<dim3(oblocks, (unsigned)(g.Co < 1024 ? g.Co : 1024)), kFftThreads, 0, s>>>(Z, out, g, divT, divTW,
                                                                                             n_tiles);
     return hipGetLastError();
 }
 
 // dw[k][c] = beta * dw[k][c] + the first R x S values of the inverse transform of
 // Mw[.][k][c] = (Prr + Pii) + i (Pri - Pir), P = the 2K x 2C product matrix of one frequency.
-// A workgroup handles 16 consecutive input channels of one output channel.
-__global__ __launch_bounds__(256) void fft_dw_kernel(const float *__restrict__ P, float *__restrict__ dw, int K, int C,
+// A workgroup handles 32 consecutive input channels of one output channel.
+__global__ __launch_bounds__(kFftThreads) void fft_dw_kernel(const float *__restrict__ P, float *__restrict__ dw, int K, int C,
                                                      int R, int S, float beta)
 {
     __shared__ float sre[kFftTilesPerBlock * kFftN * kFftHalf], sim[kFftTilesPerBlock * kFftN * kFftHalf];
@@ -386,9 +387,9 @@ static hipError_t fft_filter_run(const Dims &d, int b, const void *x, const void
         log->add("fft_input_kernel");
         log->add("fft_input_kernel");
     } else {
-        fft_input_kernel<E><<<dim3(blocks, (unsigned)(d.C < 1024 ? d.C : 1024)), 256, 0, s>>>(x, V, gx, divT, divTW, n_tiles);
+        fft_input_kernel<E><<<dim3(blocks, (unsigned)(d.C < 1024 ? d.C : 1024)), kFftThreads, 0, s>>>(x, V, gx, divT, divTW, n_tiles);
         if ((e = hipGetLastError()) != hipSuccess) return e;
-        fft_input_kernel<E><<<dim3(blocks, (unsigned)(d.K < 1024 ? d.K : 1024)), 256, 0, s>>>(dy, D, gd, divT, divTW, n_tiles);
+        fft_input_kernel<E><<<dim3(blocks, (unsigned)(d.K < 1024 ? d.K : 1024)), kFftThreads, 0, s>>>(dy, D, gd, divT, divTW, n_tiles);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     GemmShape gs{2 * d.K, 2 * d.C, n_tiles};
@@ -408,7 +409,7 @@ static hipError_t fft_filter_run(const Dims &d, int b, const void *x, const void
         return hipSuccess;
     }
     const dim3 go((unsigned)((d.C + kFftTilesPerBlock - 1) / kFftTilesPerBlock), (unsigned)d.K);
-    fft_dw_kernel<<<go, 256, 0, s>>>(Mw, dw, d.K, d.C, d.R, d.S, beta);
+    fft_dw_kernel<<<go, kFftThreads, 0, s>>>(Mw, dw, d.K, d.C, d.R, d.S, beta);
     return hipGetLastError();
 }
 
