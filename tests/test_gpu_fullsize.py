@@ -33,9 +33,10 @@ SMALL = [(0, synth.config_small()[0], 64 * 1024, ucd.POLICY_ALL), (0, synth.conf
          (0, synth.config_small()[0], MIB, ucd.POLICY_ALL)]
 
 
-def check_layer(idx, s, limit, policy, n_samples=1500, n_filter_samples=150, bf16=False):
+def check_layer(idx, s, limit, policy, n_samples=1500, n_filter_samples=150, bf16=False, forced=None):
     """bf16: tensors stored as bfloat16 (dw fp32); the oracle then runs on the rounded inputs and
-    y / dx carry the output rounding (half an ulp = 2^-8 relative: 5e-3 in relative L2)."""
+    y / dx carry the output rounding (half an ulp = 2^-8 relative: 5e-3 in relative L2).
+    forced: a configuration [(algo, b), ...] to run for all three operations instead of planning."""
     import torch
     dev = torch.device("cuda:0")
     desc = ucd.layer(s, dtype=1 if bf16 else 0)
@@ -52,9 +53,12 @@ def check_layer(idx, s, limit, policy, n_samples=1500, n_filter_samples=150, bf1
     out_y = torch.empty(s.y_shape, dtype=tdt, device=dev)
     out_dx = torch.empty(s.x_shape, dtype=tdt, device=dev)
     out_dw = torch.empty(s.w_shape, dtype=torch.float32, device=dev)
-    pf = ucd.ucd_plan(desc, ucd.FWD, limit, policy, xd, wd, out_y, ws)
-    pd = ucd.ucd_plan(desc, ucd.BWD_DATA, limit, policy, out_dx, wd, dyd, ws)
-    pw = ucd.ucd_plan(desc, ucd.BWD_FILTER, limit, policy, xd, out_dw, dyd, ws)
+    if forced is not None:
+        pf, pd, pw = (ucd.ucd_plan_fixed(desc, op, forced) for op in (ucd.FWD, ucd.BWD_DATA, ucd.BWD_FILTER))
+    else:
+        pf = ucd.ucd_plan(desc, ucd.FWD, limit, policy, xd, wd, out_y, ws)
+        pd = ucd.ucd_plan(desc, ucd.BWD_DATA, limit, policy, out_dx, wd, dyd, ws)
+        pw = ucd.ucd_plan(desc, ucd.BWD_FILTER, limit, policy, xd, out_dw, dyd, ws)
     for p in (pf, pd, pw):
         micro, _, need = p.query()
         assert sum(b for _, b in micro) == s.N and need <= limit
@@ -122,3 +126,16 @@ def test_first_layers_undivided_without_workspace(idx, s, limit, policy, bf16):
     BackwardData with merged stride phases (C = 3: 4x4 blocks at stride 4, 4x4 blocks of two
     strides at stride 2)."""
     check_layer(idx, s, 0, ucd.POLICY_UNDIVIDED, n_samples=800, n_filter_samples=60, bf16=bf16)
+
+
+def test_conv2_planned_with_512MiB_runs_the_tiled_fft_in_micro_batches():
+    """With 512 MiB the undivided tiled FFT of the 5x5 layer does not fit (991 MB) and its
+    micro-batches of 128 do: the situation of the paper's headline result, at full size."""
+    idx, s = [(i, s) for i, s, _, _ in ALEXNET if s.name == "conv2"][0]
+    desc = ucd.layer(s)
+    assert ucd.ucd_workspace_size(desc, ucd.FWD, ucd.ALGO_FFT, s.N) > 512 * MIB
+    assert ucd.ucd_workspace_size(desc, ucd.FWD, ucd.ALGO_FFT, 124) <= 512 * MIB
+    check_layer(idx, s, 512 * MIB, ucd.POLICY_POW2, n_samples=800, n_filter_samples=60)
+    # and that very configuration, whatever the planner preferred on this box
+    check_layer(idx, s, 512 * MIB, ucd.POLICY_POW2, n_samples=800, n_filter_samples=60,
+                forced=[(ucd.ALGO_FFT, 128), (ucd.ALGO_FFT, 128)])
