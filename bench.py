@@ -56,7 +56,9 @@ MEASURED_TRAFFIC_BYTES_PER_FLOP = {
 WORKLOADS = {
     "alexnet": ("AlexNet-shaped 5-layer conv stack", "config_alexnet", 256, 64 << 20, "wr", "all"),
     "small": ("single small 3x3 layer", "config_small", 8, 64 << 10, "wr", "all"),
-    "alexnet-wd": ("AlexNet-shaped 5-layer conv stack", "config_alexnet", 256, 120 << 20, "wd", "all"),
+    # one budget of 15 kernels x 64 MiB: the WD counterpart of the default workload (Section 4.4 pairs WR at M
+    # per kernel with WD at kernels x M in total)
+    "alexnet-wd": ("AlexNet-shaped 5-layer conv stack", "config_alexnet", 256, 960 << 20, "wd", "all"),
     "resnet18": ("ResNet-18-shaped conv layers (20 layers)", "config_resnet18", 256, 64 << 20, "wr", "all"),
     "densenet": ("DenseNet-BC-style block (24 layers)", "config_densenet_block", 64, 8 << 20, "wr", "all"),
     "resnet50-wr": ("ResNet-50-shaped conv layers (53 layers)", "config_resnet50", 256, 64 << 20, "wr", "pow2"),
