@@ -61,7 +61,7 @@ def test_plan_fixed_validation_and_query():
     p = ucd.ucd_plan_fixed(L, ucd.FWD, [(0, 3), (1, 5)])
     assert p.query() == ([(0, 3), (1, 5)], 0, 5 * 147456)
     for micro, status in (([(0, 3), (0, 4)], ucd.E_INVALID), ([(0, 0), (0, 8)], ucd.E_INVALID),
-                          ([(5, 8)], ucd.E_INVALID)):
+                          ([(ucd.N_ALGO, 8)], ucd.E_INVALID)):
         with pytest.raises(ucd.UcdError) as e:
             ucd.ucd_plan_fixed(L, ucd.FWD, micro)
         assert e.value.status == status
