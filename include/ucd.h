@@ -218,6 +218,18 @@ int ucd_plan_cached(const ucd_layer_t *layer, int op, size_t ws_limit, int polic
 int ucd_conv_fwd(const ucd_plan_t *plan, const void *x, const void *w, void *y,
                  void *ws, size_t ws_bytes, void *stream);
 
+/* ucd_conv_fwd for callers that cannot allocate device memory or pass a workspace (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the workspace is an
+ * array of UCD_STATIC_WS_BYTES that the library's code object holds on every GPU it is loaded on,
+ * from load to process end.  Allocates nothing (no hipMalloc / hipFree, no allocating library
+ * call); the array's address on the current device is looked up on the first call on that device.
+ * A plan that needs more than UCD_STATIC_WS_BYTES is refused with UCD_E_WS_TOO_SMALL before any
+ * launch.  Every call on one GPU uses the same array, which keeps the previous call's contents
+ * (every algorithm writes all it reads, nothing needs clearing): calls that overlap on one GPU
+ * (different streams, or threads) race; calls on one stream are ordered and safe. */
+#define UCD_STATIC_WS_BYTES ((size_t)64 << 20)
+int ucd_conv_fwd_static_ws(const ucd_plan_t *plan, const void *x, const void *w, void *y, void *stream);
+
 /* dx = adjoint of Forward with respect to x, applied to dy.  Overwrites all of dx (input pixels
  * no filter tap reaches become 0). */
 int ucd_conv_bwd_data(const ucd_plan_t *plan, const void *dy, const void *w, void *dx,

@@ -333,6 +333,34 @@ int solve_wd(const std::vector<std::vector<Config>> &fronts, size_t total_ws, st
     return UCD_OK;
 }
 
+// ---- workspace held by the library, for callers that cannot allocate ------------------------------
+// One array per GPU, in the code object's zero-initialised data: it exists from module load to
+// process end.  The name below is only the host-side handle of the symbol; its device address is
+// looked up once per device with that device current, and only that address is ever handed to a launch.
+constexpr size_t kStaticWsBytes = UCD_STATIC_WS_BYTES;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticWsBytes];
+void *g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mu;
+
+int static_workspace(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return UCD_E_HIP;
+    if (dev < 0 || dev >= kMaxDevices) return UCD_E_UNSUPPORTED;
+    std::lock_guard<std::mutex> g(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return UCD_E_HIP;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return UCD_OK;
+}
+
 // No C++ exception may cross the C boundary: allocation failures become UCD_E_NOMEM.
 template <class F>
 int guarded(F body) noexcept
@@ -721,6 +749,20 @@ int ucd_conv_fwd(const ucd_plan_t *plan, const void *x, const void *w, void *y, 
 {
     return guarded([&]() -> int {
         return run_plan(plan, UCD_FWD, x, w, y, 0.f, ws, ws_bytes, stream);
+    });
+}
+
+int ucd_conv_fwd_static_ws(const ucd_plan_t *plan, const void *x, const void *w, void *y, void *stream)
+{
+    return guarded([&]() -> int {
+        if (!plan) return UCD_E_NULLPTR;
+        if (plan->ws_bytes > kStaticWsBytes) return UCD_E_WS_TOO_SMALL;
+        void *ws = nullptr;
+        if (plan->ws_bytes > 0) {
+            const int rc = static_workspace(&ws);
+            if (rc != UCD_OK) return rc;
+        }
+        return run_plan(plan, UCD_FWD, x, w, y, 0.f, ws, kStaticWsBytes, stream);
     });
 }
 

@@ -30,7 +30,7 @@ EXPORTS = [
     "ucd_wd_solve", "ucd_plan_wd_from_tables", "ucd_plan_fixed", "ucd_plan_query", "ucd_plan_destroy",
     "ucd_plan", "ucd_plan_wd", "ucd_bench_table", "ucd_bench_clear", "ucd_conv_fwd", "ucd_conv_bwd_data",
     "ucd_conv_bwd_filter", "ucd_run_micro", "ucd_mfma_probe", "ucd_describe_micro",
-    "ucd_bench_save", "ucd_bench_load", "ucd_bench_put", "ucd_plan_cached",
+    "ucd_bench_save", "ucd_bench_load", "ucd_bench_put", "ucd_plan_cached", "ucd_conv_fwd_static_ws",
 ]
 
 
@@ -82,6 +82,7 @@ def lib():
         L.ucd_bench_table.argtypes = [lp, i, u64p, szp, i]
         L.ucd_bench_clear.restype = None
         L.ucd_conv_fwd.argtypes = [vp, vp, vp, vp, vp, sz, vp]
+        L.ucd_conv_fwd_static_ws.argtypes = [vp, vp, vp, vp, vp]
         L.ucd_conv_bwd_data.argtypes = [vp, vp, vp, vp, vp, sz, vp]
         L.ucd_conv_bwd_filter.argtypes = [vp, vp, vp, vp, ctypes.c_float, vp, sz, vp]
         L.ucd_run_micro.argtypes = [lp, i, i, i, vp, vp, vp, ctypes.c_float, vp, sz, vp]
@@ -292,6 +293,14 @@ def ucd_bench_clear():
 def ucd_conv_fwd(plan, x, w, y, ws=None, ws_bytes=None, stream=None):
     _check(lib().ucd_conv_fwd(plan.handle, _ptr(x), _ptr(w), _ptr(y), _ptr(ws),
                               _nbytes(ws) if ws_bytes is None else ws_bytes, _stream(stream)), "ucd_conv_fwd")
+
+
+STATIC_WS_BYTES = 64 << 20
+
+
+def ucd_conv_fwd_static_ws(plan, x, w, y, stream=None):
+    _check(lib().ucd_conv_fwd_static_ws(plan.handle, _ptr(x), _ptr(w), _ptr(y), _stream(stream)),
+           "ucd_conv_fwd_static_ws")
 
 
 def ucd_conv_bwd_data(plan, dy, w, dx, ws=None, ws_bytes=None, stream=None):
