@@ -8,14 +8,14 @@ rounding an output to nearest moves it by at most half a unit in the last place,
 magnitude; over a tensor that is a relative L2 error of about 2^-8 / sqrt(3) = 2.3e-3, so 5e-3 is
 asserted for y and dx, together with the elementwise bound
 |got - ref| <= 2^-8 |ref| + 1e-5 rms(ref) (half an ulp plus the fp32 accumulation error).
-dw stays fp32 and keeps the fp32 path's tolerances (1e-5; 1e-3 for Winograd).
+dw stays fp32 and keeps the fp32 path's tolerances (1e-5; 1e-4 for Winograd).
 """
 import numpy as np
 import pytest
 
 from paper_1804_04806_amd import synth, ucd
 from paper_1804_04806_amd.synth import Shape
-from hip_helpers import inputs, rel_l2, run_oracle
+from hip_helpers import GuardedWorkspace, inputs, l2_tol, rel_l2, run_oracle
 
 pytestmark = pytest.mark.gpu
 
@@ -55,19 +55,22 @@ def run_hip_bf16(s, op, micro, bits, beta=0.0, dw0=None):
     dev = torch.device("cuda:0")
     desc = ucd.layer(s, dtype=1)
     plan = ucd.ucd_plan_fixed(desc, op, micro)
-    ws = torch.full((max(plan.ws_bytes, 4) // 4 + 64,), float("nan"), dtype=torch.float32, device=dev)
+    need = plan.ws_bytes
+    guarded = GuardedWorkspace(need)   # exactly the plan's bytes, a guard region behind them
+    ws = guarded.tensor
     xb, wb, dyb = (dev_bf16(b) for b in bits)
     if op == ucd.FWD:
         out = torch.full(s.y_shape, float("nan"), dtype=torch.bfloat16, device=dev)
-        ucd.ucd_conv_fwd(plan, xb, wb, out, ws)
+        ucd.ucd_conv_fwd(plan, xb, wb, out, ws, need)
     elif op == ucd.BWD_DATA:
         out = torch.full(s.x_shape, float("nan"), dtype=torch.bfloat16, device=dev)
-        ucd.ucd_conv_bwd_data(plan, dyb, wb, out, ws)
+        ucd.ucd_conv_bwd_data(plan, dyb, wb, out, ws, need)
     else:
         out = (torch.from_numpy(dw0).to(dev).clone() if dw0 is not None
                else torch.full(s.w_shape, float("nan"), dtype=torch.float32, device=dev))
-        ucd.ucd_conv_bwd_filter(plan, xb, dyb, out, beta, ws)
+        ucd.ucd_conv_bwd_filter(plan, xb, dyb, out, beta, ws, need)
     torch.cuda.synchronize()
+    guarded.check_guard(need)
     return out.float().cpu().numpy()
 
 
@@ -96,8 +99,7 @@ def test_bf16_parity_all_algorithms_and_divisions(s, op):
             got = run_hip_bf16(s, op, [(algo, b) for b in parts], bits)
             ctx = (s.name, ucd.OP_NAMES[op], ucd.ALGO_NAMES[algo], parts)
             if op == ucd.BWD_FILTER:
-                tol = 1e-3 if algo in ucd.TRANSFORM_ALGOS else 1e-5
-                assert rel_l2(got, ref) <= tol, (ctx, rel_l2(got, ref))
+                assert rel_l2(got, ref) <= l2_tol([(algo, 0)]), (ctx, rel_l2(got, ref))
             else:
                 check_bf16_output(got, ref, ctx)
             ran += 1

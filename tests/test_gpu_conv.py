@@ -5,14 +5,15 @@ import pytest
 
 from paper_1804_04806_amd import ucd
 from paper_1804_04806_amd.synth import Shape
-from hip_helpers import inputs, rel_l2, run_hip, run_oracle
+from hip_helpers import inputs, l2_tol, rel_l2, run_hip, run_oracle
 
 pytestmark = pytest.mark.gpu
 
 # The task's bounds are 1e-5 for the direct/GEMM paths and 1e-3 for Winograd; the Winograd kernels
-# measure 3e-7 (2x2 tiles) to 4e-6 (4x4 tiles), so they are held to 1e-4 here.
+# measure 3e-7 (2x2 tiles) to 4e-6 (4x4 tiles), so they are held to 1e-4 here, and the tiled FFT
+# (1e-7 to 2e-7) to the GEMM paths' bound.
 TOL = {ucd.ALGO_IMPLICIT: 1e-5, ucd.ALGO_IM2COL: 1e-5, ucd.ALGO_WINOGRAD: 1e-4, ucd.ALGO_WINOGRAD4: 1e-4,
-       ucd.ALGO_FFT: 1e-4}
+       ucd.ALGO_FFT: 1e-5}
 
 # sizes span several tiles (128-wide) with ragged tails in M, N and the reduction
 SHAPES = [
@@ -74,7 +75,7 @@ def test_mixed_algorithms_in_one_configuration():
         ref = run_oracle(s, op, x=x, w=w, dy=dy)
         al = algos_for(desc, op, 2)
         micro = [(al[i % len(al)], b) for i, b in enumerate([2, 1, 3, 2])]
-        assert rel_l2(run_hip(s, op, micro, x=x, w=w, dy=dy), ref) <= 1e-3
+        assert rel_l2(run_hip(s, op, micro, x=x, w=w, dy=dy), ref) <= l2_tol(micro)
 
 
 @pytest.mark.parametrize("algo", range(ucd.N_ALGO), ids=lambda a: ucd.ALGO_NAMES[a])
