@@ -17,6 +17,12 @@ single-algorithm plan, a roofline object for the dominant kernel and a CPU-oracl
 Other workloads of the same shape family can be timed with --workload (not the contract line):
 small (N=8, 64 KiB), resnet18 (64 MiB/layer, WR), densenet (B=64, 8 MiB/layer, WR),
 resnet50-wr (64 MiB/layer) and resnet50-wd (one 512 MiB budget over all 159 kernels, WD).
+
+    python bench.py --micro --net alexnet --layer conv4 --op fwd --algo implicit --b 256
+
+times one (layer, operation, algorithm, micro-batch size) instead (or, with --copy-mib / --mfma-peak,
+a plain device copy of known traffic / the register-only MFMA loop): the unit to put under
+`rocprofv3 --kernel-trace --stats` or `--pmc` to look at a single kernel.
 """
 import argparse
 import json
@@ -52,6 +58,8 @@ MEASURED_TRAFFIC_BYTES_PER_FLOP = {
     "gemm_kernel<Tile<64x128>,PhaseFilterKLane,GatherNLane<taps<=31>,EpiPhases>": 451.9e6 / 52.71e9,
 }
 
+ALGO_IDS = {"implicit": 0, "im2col": 1, "winograd": 2, "winograd4": 3, "fft": 4}
+
 # name -> (description, layer table, batch, per-layer limit or total budget, "wr" | "wd", default policy)
 WORKLOADS = {
     "alexnet": ("AlexNet-shaped 5-layer conv stack", "config_alexnet", 256, 64 << 20, "wr", "all"),
@@ -84,6 +92,22 @@ def parse():
     ap.add_argument("--cpu-samples", type=int, default=24)
     ap.add_argument("--bench-db", default=None,
                     help="benchmark database file: loaded before planning if it exists, saved afterwards")
+    ap.add_argument("--memory-table", action="store_true",
+                    help="also print, as markdown on stderr, the per-kernel workspace of the planned configuration "
+                         "next to the undivided plan under a 512 MiB limit (the paper's Section 4.3 comparison)")
+    # single-kernel mode
+    ap.add_argument("--micro", action="store_true", help="time one algorithm on one micro-batch (see the docstring)")
+    ap.add_argument("--net", default="alexnet", choices=["small", "alexnet", "resnet18", "densenet", "resnet50"])
+    ap.add_argument("--layer", default="conv4")
+    ap.add_argument("--op", default="fwd", choices=["fwd", "bwd_data", "bwd_filter"])
+    ap.add_argument("--algo", default="implicit", choices=sorted(ALGO_IDS))
+    ap.add_argument("--b", type=int, default=256)
+    ap.add_argument("--reps", type=int, default=5)
+    ap.add_argument("--copy-mib", type=int, default=0,
+                    help="with --micro: a plain device copy of this many MiB (a kernel of known traffic, to "
+                         "calibrate the FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--mfma-peak", action="store_true",
+                    help="with --micro: the register-only MFMA loop with 0/2/4/8 vector FMAs per MFMA")
     return ap.parse_args()
 
 
@@ -91,15 +115,15 @@ class Pool:
     """One set of device buffers, sized for the largest layer, that every layer of a big
     workload takes views of (a resident ResNet-50 at batch 256 would need hundreds of GB)."""
 
-    def __init__(self, layers, torch, dev, tdtype):
+    def __init__(self, layers, torch, dev, tdtype, synth):
         nx = max(s.N * s.C * s.H * s.W for s in layers)
         ny = max(s.N * s.K * s.P * s.Q for s in layers)
         nw = max(s.K * s.C * s.R * s.S for s in layers)
-        g = torch.Generator(device=dev)
-        g.manual_seed(1234)
-        self.x = (torch.rand(nx, device=dev, generator=g) * 2 - 1).to(tdtype)
-        self.dy = (torch.rand(ny, device=dev, generator=g) * 2 - 1).to(tdtype)
-        self.w = (torch.randn(nw, device=dev, generator=g) * 0.03).to(tdtype)
+        # the same generator and distributions as the per-layer tensors (full-mantissa values: the
+        # chip's clock under matrix load depends on the operands' bit patterns)
+        self.x = torch.from_numpy(synth.make_flat(nx, "x")).to(dev).to(tdtype)
+        self.dy = torch.from_numpy(synth.make_flat(ny, "dy")).to(dev).to(tdtype)
+        self.w = torch.from_numpy(synth.make_flat(nw, "w", std=0.03)).to(dev).to(tdtype)
         self.y = torch.empty(ny, dtype=tdtype, device=dev)
         self.dx = torch.empty(nx, dtype=tdtype, device=dev)
         self.dw = torch.empty(nw, dtype=torch.float32, device=dev)
@@ -173,14 +197,65 @@ def plan_wd(ucd, states, pool, policy, ws, budget):
 
 
 def time_steps(torch, fn, steps, warmup):
+    """Times exactly `steps` calls of fn between two synchronisations (the contract's figure) and,
+    from events recorded on the launch stream between the calls, each step's own duration.
+    Returns (ms per step, median step ms, min step ms)."""
     for _ in range(warmup):
         fn()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(steps):
+    for i in range(steps):
+        ev[i].record()
         fn()
+    ev[steps].record()
     torch.cuda.synchronize()
-    return (time.perf_counter() - t0) * 1e3 / steps
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    each = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(steps))
+    return ms, each[len(each) // 2], each[0]
+
+
+def time_interleaved(torch, fn_a, fn_b, rounds, warmup):
+    """A/B/A/B timing with events: the two configurations see the same clock and cache history.
+    Returns (median ms of a, median ms of b, min of a, min of b)."""
+    for _ in range(warmup):
+        fn_a()
+        fn_b()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2 * rounds + 1)]
+    torch.cuda.synchronize()
+    for i in range(rounds):
+        ev[2 * i].record()
+        fn_a()
+        ev[2 * i + 1].record()
+        fn_b()
+    ev[2 * rounds].record()
+    torch.cuda.synchronize()
+    a = sorted(ev[2 * i].elapsed_time(ev[2 * i + 1]) for i in range(rounds))
+    b = sorted(ev[2 * i + 1].elapsed_time(ev[2 * i + 2]) for i in range(rounds))
+    return a[len(a) // 2], b[len(b) // 2], a[0], b[0]
+
+
+def gemm_flops(text):
+    """MFMA flops the GEMM launches of a micro-batch description issue: 2*M*N*K*batch each."""
+    total = 0.0
+    for part in text.split(";"):
+        part = part.strip()
+        if not part.startswith("gemm_kernel"):
+            continue
+        f = dict(kv.split("=") for kv in part.split("> ")[-1].split() if "=" in kv)
+        total += 2.0 * int(f["M"]) * int(f["N"]) * int(f["K"]) * int(f["batch"])
+    return total
+
+
+def executed_flops(ucd, states, plans):
+    """Matrix flops one step really issues (Winograd and FFT issue fewer than the direct count,
+    merged-phase BackwardData and padded Winograd tiles more)."""
+    total = 0.0
+    for st, pl in zip(states, plans):
+        for op in (ucd.FWD, ucd.BWD_DATA, ucd.BWD_FILTER):
+            for algo, b in pl[op].micro:
+                total += gemm_flops(ucd.ucd_describe_micro(st.desc, op, algo, b)[0])
+    return total
 
 
 def kernel_class(ucd, desc, op, algo, b):
@@ -274,8 +349,111 @@ def cpu_baseline(layers, n_samples):
             "ms_per_iter_scaled": round(secs * 1e3 * layers[0].N / n_samples, 1)}
 
 
+def memory_table(ucd, states, plans, ws, title, batch, limit):
+    """Markdown: per kernel, the workspace of the planned configuration under `limit` next to the
+    best undivided plan with 512 MiB (what a framework that hands the library a generous workspace
+    would hold), with each layer's tensor bytes (Section 4.3's per-layer memory comparison)."""
+    import torch
+    big = 512 << 20
+    ws_big = torch.empty(big // 4, dtype=torch.float32, device=ws.device)
+    lines = [f"### {title}, batch {batch}: workspace per kernel, planned at {limit >> 20} MiB vs undivided at 512 MiB", "",
+             "| layer | x + y + w MiB | op | planned configuration | planned ws MiB | planned ms | undivided@512MiB | ws MiB | ms |",
+             "|---|---|---|---|---|---|---|---|---|"]
+    tot = {"data": 0.0, "planned": 0.0, "big": 0.0, "planned_ms": 0.0, "big_ms": 0.0}
+    for st, pl in zip(states, plans):
+        s = st.s
+        u = st.plan(ucd, ucd.POLICY_UNDIVIDED, ws_big, big)
+        esz = st.x.element_size()
+        data = (s.N * s.C * s.H * s.W + s.N * s.K * s.P * s.Q + s.K * s.C * s.R * s.S) * esz / 2 ** 20
+        tot["data"] += data
+        peak_p = max(pl[op].ws_bytes for op in pl) / 2 ** 20
+        peak_u = max(u[op].ws_bytes for op in u) / 2 ** 20
+        tot["planned"] = max(tot["planned"], peak_p)   # WR: one workspace, reused by every kernel
+        tot["big"] = max(tot["big"], peak_u)
+        for op in (ucd.FWD, ucd.BWD_DATA, ucd.BWD_FILTER):
+            micro, cost, need = pl[op].query()
+            umicro, ucost, uneed = u[op].query()
+            cfg = ", ".join(f"{ucd.ALGO_NAMES[a]}x{b}" for a, b in micro[:4]) + (" ..." if len(micro) > 4 else "")
+            lines.append(f"| {s.name} | {data:.1f} | {ucd.OP_NAMES[op]} | {cfg} ({len(micro)} micro-batches) | "
+                         f"{need / 2 ** 20:.1f} | {cost / 1e6:.3f} | {ucd.ALGO_NAMES[umicro[0][0]]} | {uneed / 2 ** 20:.1f} | {ucost / 1e6:.3f} |")
+            tot["planned_ms"] += cost / 1e6
+            tot["big_ms"] += ucost / 1e6
+    lines += ["", f"Tensors of all layers: {tot['data']:.1f} MiB.  Workspace held (one buffer, reused by every kernel): "
+                  f"{tot['planned']:.1f} MiB planned against {tot['big']:.1f} MiB undivided at 512 MiB; predicted step "
+                  f"{tot['planned_ms']:.2f} ms against {tot['big_ms']:.2f} ms.", ""]
+    return "\n".join(lines)
+
+
+def micro_main(args):
+    """One (layer, operation, algorithm, micro-batch size) through ucd_run_micro, or a calibration kernel."""
+    import torch
+    from paper_1804_04806_amd import synth, ucd
+    dev = torch.device("cuda:0")
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def timed(fn):
+        times = []
+        for it in range(args.warmup + args.reps):
+            e0.record()
+            r = fn()
+            e1.record()
+            e1.synchronize()
+            if it >= args.warmup:
+                times.append(e0.elapsed_time(e1))
+        return times, r
+
+    if args.mfma_peak:
+        blocks, iters = 512, 2000
+        scratch = torch.empty(blocks * 256, dtype=torch.float32, device=dev)
+        out = {}
+        for valu in (0, 2, 4, 8):
+            times, flops = timed(lambda: ucd.ucd_mfma_probe(valu, blocks, iters, scratch))
+            out[f"tflops_with_{valu}_valu_per_mfma"] = round(flops / min(times) / 1e9, 1)
+        print(json.dumps(out))
+        return
+    if args.copy_mib:
+        n = args.copy_mib * (1 << 20) // 4
+        src = torch.rand(n, device=dev)
+        dst = torch.empty_like(src)
+        times, _ = timed(lambda: dst.copy_(src))
+        print(json.dumps({"copy_mib": args.copy_mib, "ms_min": round(min(times), 4),
+                          "GBps_read_plus_write": round(2 * n * 4 / min(times) / 1e6, 1)}))
+        return
+    nets = {"small": synth.config_small, "alexnet": synth.config_alexnet, "resnet18": synth.config_resnet18,
+            "densenet": synth.config_densenet_block, "resnet50": synth.config_resnet50}
+    s = next(l for l in nets[args.net]() if l.name == args.layer).with_batch(args.b)
+    op = {"fwd": ucd.FWD, "bwd_data": ucd.BWD_DATA, "bwd_filter": ucd.BWD_FILTER}[args.op]
+    algo = ALGO_IDS[args.algo]
+    desc = ucd.layer(s, dtype=1 if args.dtype == "bf16" else 0)
+    need = ucd.ucd_workspace_size(desc, op, algo, args.b)
+    if need == ucd.WS_NA:
+        raise SystemExit("algorithm does not apply to this layer/operation")
+    td = torch.bfloat16 if args.dtype == "bf16" else torch.float32
+    x = torch.from_numpy(synth.make_x(s)).to(dev).to(td)
+    w = torch.from_numpy(synth.make_w(s)).to(dev).to(td)
+    y = torch.from_numpy(synth.make_dy(s)).to(dev).to(td)
+    if op == ucd.BWD_FILTER:
+        w = w.float()   # dw is fp32 for every dtype
+    ws = torch.empty(max(need, 4) // 4, dtype=torch.float32, device=dev)
+    a, bsrc, out = {ucd.FWD: (x, w, y), ucd.BWD_DATA: (y, w, x), ucd.BWD_FILTER: (x, y, w)}[op]
+    beta = 1.0 if op == ucd.BWD_FILTER else 0.0
+    times, _ = timed(lambda: ucd.ucd_run_micro(desc, op, algo, args.b, a, bsrc, out, beta, ws))
+    ms = min(times)
+    text, _ = ucd.ucd_describe_micro(desc, op, algo, args.b)
+    print(json.dumps({"layer": s.name, "op": args.op, "algo": args.algo, "b": args.b, "dtype": args.dtype,
+                      "ms_min": round(ms, 4), "ms_avg": round(sum(times) / len(times), 4),
+                      "tflops": round(s.flops / ms / 1e9, 2),
+                      "executed_mfma_tflops": round(gemm_flops(text) / ms / 1e9, 2), "ws_bytes": need,
+                      "launches": text}))
+
+
 def main():
     args = parse()
+    if args.micro:
+        if args.gpus != 1:
+            sys.exit(2)
+        micro_main(args)
+        return
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
         sys.exit(2)
@@ -294,26 +472,41 @@ def main():
     policy = {"all": ucd.POLICY_ALL, "pow2": ucd.POLICY_POW2, "undivided": ucd.POLICY_UNDIVIDED}[policy_name]
     layers = getattr(synth, table)() if args.workload == "small" else getattr(synth, table)(batch)
     tdtype = torch.bfloat16 if args.dtype == "bf16" else torch.float32
-    pool = None if args.workload in ("alexnet", "alexnet-wd", "small") else Pool(layers, torch, dev, tdtype)
+    pool = None if args.workload in ("alexnet", "alexnet-wd", "small") else Pool(layers, torch, dev, tdtype, synth)
     states = [LayerState(s, i, torch, ucd, synth, dev, pool, tdtype) for i, s in enumerate(layers)]
     ws = torch.empty(max(limit, 4) // 4, dtype=torch.float32, device=dev)
     flops_per_step = 3 * sum(s.flops for s in layers)
 
-    if args.bench_db and os.path.exists(args.bench_db):
+    have_db = bool(args.bench_db and os.path.exists(args.bench_db))
+    if have_db:
         ucd.ucd_bench_load(args.bench_db)
     offsets = None
-    t0 = time.perf_counter()
     # baseline: the best single algorithm per kernel with no workspace beyond its own layer limit
     # (WR undivided); for the WD workload the same per-kernel share of the budget
     base_limit = limit if mode == "wr" else limit // (3 * len(layers))
-    undiv = [st.plan(ucd, ucd.POLICY_UNDIVIDED, ws, base_limit) for st in states]
-    t_plan_undiv = time.perf_counter() - t0
-    t0 = time.perf_counter()
+    plan_seconds = {}
+
+    def timed_plan(name, pol, lim):
+        """WR-plans every layer with one policy from an empty benchmark cache (unless a database
+        file supplied it), so that the time is that policy's own benchmarking cost."""
+        if not have_db:
+            ucd.ucd_bench_clear()
+        t0 = time.perf_counter()
+        pl = [st.plan(ucd, pol, ws, lim) for st in states]
+        plan_seconds[name] = round(time.perf_counter() - t0, 2)
+        return pl
+
+    undiv = timed_plan("undivided", ucd.POLICY_UNDIVIDED, base_limit)
     if mode == "wr":
-        plans = [st.plan(ucd, policy, ws, limit) for st in states]
+        if policy_name != "pow2" and (policy_name == "all" or not have_db):
+            timed_plan("pow2", ucd.POLICY_POW2, limit)   # reported for the comparison of Section 4.2 only
+        plans = undiv if policy_name == "undivided" else timed_plan(policy_name, policy, limit)
     else:
+        if not have_db:
+            ucd.ucd_bench_clear()
+        t0 = time.perf_counter()
         plans, offsets = plan_wd(ucd, states, pool, policy, ws, limit)
-    t_plan = time.perf_counter() - t0
+        plan_seconds[policy_name + "-wd"] = round(time.perf_counter() - t0, 2)
 
     if args.bench_db:
         ucd.ucd_bench_save(args.bench_db)
@@ -322,10 +515,15 @@ def main():
         for i, (st, p) in enumerate(zip(states, pl)):
             st.run(ucd, p, ws, None if offs is None else offs[i])
 
-    ms_undiv = time_steps(torch, lambda: step(undiv), args.steps, args.warmup)
-    ms = time_steps(torch, lambda: step(plans, offsets), args.steps, args.warmup)
+    # the contract's figure: exactly --steps planned steps between two synchronisations
+    ms, ms_median, ms_min = time_steps(torch, lambda: step(plans, offsets), args.steps, args.warmup)
+    # planned against undivided, interleaved step by step so that both see the same clock
+    u_med, p_med, u_min, p_min = time_interleaved(torch, lambda: step(undiv), lambda: step(plans, offsets),
+                                                  args.steps, args.warmup)
 
     tflops = flops_per_step / (ms * 1e-3) / 1e12
+    peak = FP32_MFMA_PEAK_TFLOPS if args.dtype == "f32" else BF16_MFMA_PEAK_TFLOPS
+    exec_flops = executed_flops(ucd, states, plans)
     roof, kernel_table = dominant_kernel_roofline(
         torch, ucd, states, plans, ws, reps=5,
         traffic_table=MEASURED_TRAFFIC_BYTES_PER_FLOP if (args.workload, batch, args.dtype) == ("alexnet", 256, "f32") else None)
@@ -358,11 +556,17 @@ def main():
                                   else f"{limit >> 10} KiB workspace per layer (WR)" if mode == "wr"
                                   else f"one {limit >> 20} MiB workspace budget over {3 * len(layers)} kernels (WD)"),
                    "policy": policy_name, "global_batch": batch, "ws_limit_bytes": limit, "mode": mode},
-        "ms_per_iter": round(ms, 4),
-        ("pct_fp32_mfma_peak" if args.dtype == "f32" else "pct_bf16_mfma_peak"):
-            round(100 * tflops / (FP32_MFMA_PEAK_TFLOPS if args.dtype == "f32" else BF16_MFMA_PEAK_TFLOPS), 2),
-        "undivided_ms_per_iter": round(ms_undiv, 4), "speedup_vs_undivided": round(ms_undiv / ms, 4),
-        "plan_seconds": round(t_plan, 2), "plan_seconds_undivided": round(t_plan_undiv, 2),
+        "ms_per_iter": round(ms, 4), "ms_median": round(ms_median, 4), "ms_min": round(ms_min, 4),
+        # algorithmic (direct-convolution) flops over time, as a share of the matrix peak ...
+        ("pct_fp32_mfma_peak" if args.dtype == "f32" else "pct_bf16_mfma_peak"): round(100 * tflops / peak, 2),
+        # ... and the matrix flops the step's GEMM launches really issue (fewer where Winograd / FFT run)
+        "executed_mfma_tflops": round(exec_flops / (ms * 1e-3) / 1e12, 3),
+        "pct_mfma_peak_executed": round(100 * exec_flops / (ms * 1e-3) / 1e12 / peak, 2),
+        "executed_gflop_per_step": round(exec_flops / 1e9, 1),
+        "undivided_ms_per_iter": round(u_med, 4), "planned_ms_interleaved": round(p_med, 4),
+        "undivided_ms_min": round(u_min, 4), "planned_ms_min_interleaved": round(p_min, 4),
+        "speedup_vs_undivided": round(u_med / p_med, 4),
+        "plan_seconds": plan_seconds,
         "gflop_per_step": round(flops_per_step / 1e9, 1),
         "roofline": roof,
         "kernels": kernel_table,
@@ -371,6 +575,8 @@ def main():
         "total_ws_MiB": round(sum(p[op].ws_bytes for p in plans for op in p) / 2 ** 20, 2),
         "plans": plan_report,
     }
+    if args.memory_table:
+        print(memory_table(ucd, states, plans, ws, title, batch, limit), file=sys.stderr)
     print(json.dumps(out))
 
 

@@ -30,11 +30,12 @@ def policy_sizes(B, policy):
     if policy == ALL:
         return list(range(1, B + 1))
     if policy == POW2:
+        # the set is printed as {2^0, 2^1, 2^2, ..., B}: the powers of two below B, and B itself
         out, b = [], 1
-        while b <= B:
+        while b < B:
             out.append(b)
             b *= 2
-        return out
+        return out + [B]
     if policy == UNDIVIDED:
         return [B]
     raise ValueError("unknown policy")

@@ -1,6 +1,8 @@
 // C-ABI of the library: validation, plan objects, the micro-batch executor, the on-device
-// benchmark cache and the glue to the host planners.  See include/ucd.h for the contract.
+// benchmark cache and the glue to the host planners.  See include/ucd.h for the contract
+// (include/ucd_calib.h for the single-micro-batch and calibration entry points).
 #include "ucd.h"
+#include "ucd_calib.h"
 
 #include <hip/hip_runtime.h>
 
@@ -230,26 +232,30 @@ int time_micro(const ucd_layer_t *L, int op, int algo, int b, void *x, void *w, 
     // BackwardFilter is timed as the accumulating call it is for every micro-batch but the first
     const float beta = op == UCD_BWD_FILTER ? 1.f : 0.f;
     if (op == UCD_BWD_FILTER && fill_zero((float *)w, (size_t)d.K * d.crs(), s) != hipSuccess) return UCD_E_HIP;
-    auto run_at = [&](int o) {  // the micro-batch of samples o .. o+b-1
+    auto run_at = [&](int o, bool filter_ready) {  // the micro-batch of samples o .. o+b-1
         char *xo = (char *)x + (size_t)o * x_img, *yo = (char *)y + (size_t)o * y_img;
-        if (op == UCD_FWD) return run_micro(L, op, algo, b, xo, w, yo, beta, ws, s);
-        if (op == UCD_BWD_DATA) return run_micro(L, op, algo, b, yo, w, xo, beta, ws, s);
+        if (op == UCD_FWD) return run_micro(L, op, algo, b, xo, w, yo, beta, ws, s, filter_ready);
+        if (op == UCD_BWD_DATA) return run_micro(L, op, algo, b, yo, w, xo, beta, ws, s, filter_ready);
         return run_micro(L, op, algo, b, xo, yo, w, beta, ws, s);
     };
+    // A configuration holds at most N / b micro-batches of this size, and the executor transforms
+    // the filter once per run of one algorithm: the timed sequence does the same, so that a
+    // transforming algorithm's entry carries the share of the filter transform it will really pay.
+    const int per_config = std::max(1, L->N / b);
     auto elapsed = [&](float &ms) {
         if (hipEventRecord(ev.b, s) != hipSuccess || hipEventSynchronize(ev.b) != hipSuccess) return UCD_E_HIP;
         return hipEventElapsedTime(&ms, ev.a, ev.b) == hipSuccess ? UCD_OK : UCD_E_HIP;
     };
     float warm = 0.f, total = 0.f;
     if (hipEventRecord(ev.a, s) != hipSuccess) return UCD_E_HIP;
-    int rc = run_at(0);
+    int rc = run_at(0, false);
     if (rc != UCD_OK || (rc = elapsed(warm)) != UCD_OK) return rc;
     int reps = warm > 0.f ? (int)(kTimedSpanMs / warm) : kMaxTimedRuns;
     reps = reps < kMinTimedRuns ? kMinTimedRuns : (reps > kMaxTimedRuns ? kMaxTimedRuns : reps);
     if (hipEventRecord(ev.a, s) != hipSuccess) return UCD_E_HIP;
     for (int it = 0, o = 0; it < reps; ++it) {
         o = o + 2 * b <= L->N ? o + b : 0;  // the next micro-batch, starting after the warm-up's
-        if ((rc = run_at(o)) != UCD_OK) return rc;
+        if ((rc = run_at(o, keeps_filter(algo) && it % per_config != 0)) != UCD_OK) return rc;
     }
     if ((rc = elapsed(total)) != UCD_OK) return rc;
     ns = (uint64_t)std::llround((double)total / reps * 1e6);

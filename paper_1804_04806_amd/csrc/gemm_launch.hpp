@@ -57,7 +57,8 @@ hipError_t launch_tile(const AP &pa, const BP &pb, const typename Epi::Params &p
         log->add(std::string(kBf16Mfma ? "gemm_kernel_bf16<Tile<" : "gemm_kernel<Tile<") + std::to_string(T::BM) + "x" + std::to_string(T::BN) + ">," +
                  AL<T::BM>::name() + "," + BL<T::BN>::name() + "," + Epi::name() + "> tiles=" +
                  std::to_string(tiles_m * tiles_n) + " splits=" + std::to_string(splits) + " batch=" +
-                 std::to_string(g.batch) +
+                 std::to_string(g.batch) + " M=" + std::to_string(g.M) + " N=" + std::to_string(g.N) + " K=" +
+                 std::to_string(g.Kd) +
                  (tail.tiles ? " tail=" + std::to_string(tail.tiles) + "x" + std::to_string(tail.splits) : std::string()));
         return hipSuccess;
     }

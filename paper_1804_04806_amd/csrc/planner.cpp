@@ -10,7 +10,7 @@ bool policy_allows(int policy, int B, int b)
     if (b < 1 || b > B) return false;
     switch (policy) {
     case 0: return b == B;                 // undivided
-    case 1: return (b & (b - 1)) == 0;     // powerOfTwo: {2^i <= B}
+    case 1: return (b & (b - 1)) == 0 || b == B;  // powerOfTwo: {2^0, 2^1, ..., B}: powers of two and B itself
     case 2: return true;                   // all
     default: return false;
     }

@@ -79,6 +79,15 @@ def make_w(s, seed=0, layer_index=0):
     return (_gen(seed, layer_index, _W).standard_normal(size=s.w_shape) * std).astype(np.float32)
 
 
+def make_flat(n, kind, seed=0, std=1.0):
+    """n values of one of the three distributions as a flat array (pooled benchmark buffers that
+    layers of different shapes take views of): kind "x" / "dy" ~ U[-1, 1], "w" ~ N(0, std^2)."""
+    g = _gen(seed, 0xFFFF, {"x": _X, "w": _W, "dy": _DY}[kind])
+    if kind == "w":
+        return (g.standard_normal(size=n) * std).astype(np.float32)
+    return g.uniform(-1.0, 1.0, size=n).astype(np.float32)
+
+
 def to_bf16_bits(a):
     """bfloat16 storage of an fp32 array: round to nearest, ties to even; returns uint16 bits.
     (Input preparation for the bf16 variant: the values the library is handed.)"""

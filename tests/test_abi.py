@@ -1,4 +1,4 @@
-"""The C-ABI library loads without a GPU and exports every symbol include/ucd.h declares."""
+"""The C-ABI library loads without a GPU and exports every symbol include/*.h declares."""
 import ctypes
 import os
 import re
@@ -9,7 +9,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "ucd.h")).read()
+    text = "".join(open(os.path.join(ROOT, "include", h)).read() for h in ("ucd.h", "ucd_calib.h"))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(ucd_[a-z_0-9]+)\s*\(", text)))
 

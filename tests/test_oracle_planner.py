@@ -30,7 +30,8 @@ def test_partition_counts_match_number_theory():
 
 def test_policy_sizes():
     assert P.policy_sizes(6, ALL) == [1, 2, 3, 4, 5, 6]
-    assert P.policy_sizes(12, POW2) == [1, 2, 4, 8]
+    assert P.policy_sizes(12, POW2) == [1, 2, 4, 8, 12]      # Section 3.4 writes the set as ending in B
+    assert P.policy_sizes(1, POW2) == [1] and P.policy_sizes(2, POW2) == [1, 2]
     assert P.policy_sizes(256, POW2) == [1, 2, 4, 8, 16, 32, 64, 128, 256]
     assert P.policy_sizes(12, UNDIVIDED) == [12]
 
@@ -102,7 +103,7 @@ def test_monotone_in_policy_and_limit():
     prev = None
     for M in range(0, 70, 5):
         u, p, a = (P.wr_optimum(B, M, pol, t, ws) for pol in (UNDIVIDED, POW2, ALL))
-        assert a <= p and a <= u
+        assert a <= p <= u       # undivided's set is inside powerOfTwo's, which is inside all's
         if prev is not None:
             assert a <= prev
         prev = a
