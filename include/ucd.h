@@ -97,9 +97,32 @@ typedef struct ucd_plan ucd_plan_t;
 const char *ucd_strerror(int status);
 int ucd_version(void);
 
+/* Run-to-run reproducibility.  By default some launches sum partial results with hardware fp32
+ * atomics, whose order of arrival differs from run to run, so these outputs are reproducible only
+ * up to rounding (and micro-batched == undivided likewise):
+ *   - BackwardFilter, every algorithm: the reduction over b*P*Q is split over workgroups whenever
+ *     it is long enough (always at the benchmark sizes), and micro-batches accumulate into dw;
+ *   - Forward / BackwardData, implicit GEMM, fp32 tensors only: when the output has fewer than 768
+ *     tiles the reduction over C*R*S is split the same way into a zero-filled output, and when the
+ *     tile count is not a multiple of 256 the last tiles' reductions are spread over several
+ *     workgroups.
+ * Everything else (im2col, Winograd and FFT Forward / BackwardData; implicit-GEMM Forward /
+ * BackwardData with bf16 tensors or without the splits above) adds each output once and is bit
+ * reproducible.
+ * ucd_set_deterministic(1) switches the library (process-wide) to reproducible execution: Forward /
+ * BackwardData never split a reduction, and BackwardFilter is offered by the implicit GEMM alone,
+ * which then writes each reduction chunk's partial result to workspace and sums the chunks in a
+ * fixed order (ucd_workspace_size reports those bytes, at most 32 MiB, so the planners price
+ * them; the other algorithms report UCD_WS_NA for BackwardFilter).  Results are then bit-identical
+ * from run to run for a given configuration.  Timings of the two modes are cached apart.  Plans
+ * made in one mode must be executed in that mode (a plan's workspace need differs).
+ * on < 0 only queries.  Returns the previous setting. */
+int ucd_set_deterministic(int on);
+
 /* Bytes of workspace algorithm `algo` needs for operation `op` at micro-batch size b (the
  * quantity compared with the limit M in step 1 of the WR algorithm, Section 3.2):
- *   implicit   0
+ *   implicit   0 (reproducible mode, BackwardFilter: 4*K*C*R*S bytes per reduction chunk, see
+ *              ucd_set_deterministic)
  *   im2col     4 * C*R*S * ld,  ld = b*P*Q rounded up to 4
  *   Winograd   4 * a*a * (Ci*Co4 + ld*(C + K)) with a = 4 (F(2x2,3x3)) or 6 (F(4x4,3x3)),
  *              ld = b * ceil(Ho/m) * ceil(Wo/m) rounded up to 4 (m = a - 2), where (Ci, Co, Ho, Wo)

@@ -7,6 +7,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <chrono>
 #include <cmath>
 #include <cstdio>
@@ -38,6 +39,8 @@ constexpr int kMinTimedRuns = 2, kMaxTimedRuns = 8;
 constexpr float kTimedSpanMs = 0.4f;  // reps are chosen to cover about this much device time
 constexpr int kSpinUpMs = 10;         // device kept busy this long before the first timing of a call
 
+std::atomic<int> g_deterministic{0};  // ucd_set_deterministic
+
 bool layer_ok(const ucd_layer_t *L)
 {
     if (L->N < 1 || L->C < 1 || L->H < 1 || L->W < 1 || L->K < 1 || L->R < 1 || L->S < 1) return false;
@@ -56,6 +59,7 @@ Dims dims_of(const ucd_layer_t *L)
     d.P = (L->H + 2 * L->pad_h - L->R) / L->stride_h + 1;
     d.Q = (L->W + 2 * L->pad_w - L->S) / L->stride_w + 1;
     d.dtype = L->dtype;
+    d.det = g_deterministic.load() != 0;
     return d;
 }
 
@@ -80,9 +84,11 @@ size_t ws_size(const ucd_layer_t *L, int op, int algo, int b)
     if (!L || !layer_ok(L) || op < 0 || op >= UCD_N_OP || b < 1 || b > L->N) return UCD_WS_NA;
     if (!fits_32bit(L, b)) return UCD_WS_NA;
     const Dims d = dims_of(L);
+    // reproducible mode: BackwardFilter is the implicit GEMM's alone (its partial sums in workspace)
+    if (d.det && op == UCD_BWD_FILTER && algo != UCD_ALGO_IMPLICIT) return UCD_WS_NA;
     switch (algo) {
     case UCD_ALGO_IMPLICIT:
-        return 0;
+        return d.det && op == UCD_BWD_FILTER ? implicit_det_ws_bytes(d, b) : 0;
     case UCD_ALGO_IM2COL:
         // a 1x1 stride-1 unpadded layer's column matrix is x itself: nothing to gain
         if (d.R == 1 && d.S == 1 && d.sh == 1 && d.sw == 1 && d.ph == 0 && d.pw == 0) return UCD_WS_NA;
@@ -116,13 +122,13 @@ int run_micro(const ucd_layer_t *L, int op, int algo, int b, const void *a, cons
     // tensors are read element by element (dw is always fp32); the workspace matrices with 16-byte loads
     const uintptr_t emask = d.esize() - 1, omask = op == UCD_BWD_FILTER ? 3u : emask;
     if ((((uintptr_t)a | (uintptr_t)bsrc) & emask) != 0 || ((uintptr_t)out & omask) != 0) return UCD_E_INVALID;
-    if (algo != UCD_ALGO_IMPLICIT && ((uintptr_t)ws & 15u) != 0) return UCD_E_INVALID;
+    if ((algo != UCD_ALGO_IMPLICIT || d.det) && ((uintptr_t)ws & 15u) != 0) return UCD_E_INVALID;
     hipError_t e = hipErrorInvalidValue;
     switch (algo) {
     case UCD_ALGO_IMPLICIT:
         if (op == UCD_FWD) e = implicit_fwd(d, b, a, bsrc, out, s);
         else if (op == UCD_BWD_DATA) e = implicit_bwd_data(d, b, a, bsrc, out, s);
-        else e = implicit_bwd_filter(d, b, a, bsrc, (float *)out, beta, s);
+        else e = implicit_bwd_filter(d, b, a, bsrc, (float *)out, beta, ws, s);
         break;
     case UCD_ALGO_IM2COL:
         if (op == UCD_FWD) e = im2col_fwd(d, b, a, bsrc, out, ws, s);
@@ -189,8 +195,9 @@ std::mutex g_cache_mu;
 
 BenchKey key_of(const ucd_layer_t *L, int op, int algo, int b)
 {
-    return BenchKey(L->C, L->H, L->W, L->K, L->R, L->S, L->stride_h, L->stride_w, L->pad_h, L->pad_w, L->dtype,
-                    op, algo, b);
+    // timings of the reproducible mode are kept apart (dtype field + 16)
+    return BenchKey(L->C, L->H, L->W, L->K, L->R, L->S, L->stride_h, L->stride_w, L->pad_h, L->pad_w,
+                    L->dtype + (g_deterministic.load() != 0 ? 16 : 0), op, algo, b);
 }
 
 bool cache_get(const BenchKey &k, uint64_t &t)
@@ -400,7 +407,13 @@ const char *ucd_strerror(int status)
     }
 }
 
-int ucd_version(void) { return 100; }
+int ucd_version(void) { return 101; }
+
+int ucd_set_deterministic(int on)
+{
+    if (on < 0) return g_deterministic.load();
+    return g_deterministic.exchange(on != 0 ? 1 : 0);
+}
 
 size_t ucd_workspace_size(const ucd_layer_t *layer, int op, int algo, int b) { return ws_size(layer, op, algo, b); }
 

@@ -71,7 +71,7 @@ static int best_fill(long tiles, long want, long lo, long hi, long slots)
 // through atomics in a zero-filled output.  Chunks keep at least 512 reduction rows.
 static int output_splits(int M, int N, int Kd, bool fp32_out)
 {
-    if (!fp32_out) return 1;  // bf16 outputs cannot be accumulated with atomics
+    if (!fp32_out) return 1;  // bf16 outputs cannot be accumulated with atomics (nor may reproducible runs)
     const long tiles = pick_tile(M, N, true, 1 << 20).blocks(M, N, 1);  // tiles at the default shape
     if (tiles >= 768) return 1;  // three workgroups per CU already
     long want = (1536 + tiles - 1) / tiles;
@@ -87,7 +87,7 @@ static hipError_t implicit_fwd_t(const Dims &d, int b, const void *x, const void
     typedef Loaders<E> L;
     constexpr bool F32 = std::is_same<E, float>::value;
     GemmShape g{d.K, b * d.P * d.Q, d.crs()};
-    g.splits = output_splits(g.M, g.N, g.Kd, F32);
+    g.splits = output_splits(g.M, g.N, g.Kd, F32 && !d.det);
     KLaneParams pa{};
     pa.t = w; pa.bytes = wbytes(d); pa.row_stride = 1; pa.col_stride = d.crs();
     GatherParams pb{};
@@ -108,7 +108,7 @@ static hipError_t implicit_fwd_t(const Dims &d, int b, const void *x, const void
             return launch_gemm<KLane0, GatherNLaneBig, EpiNCHWAtomic, true>(pa, pb, pe, g, s);
         }
     }
-    g.tail_split = true;
+    g.tail_split = !d.det;
     if (d.R * d.S <= 31)
         return launch_gemm<L::template KLane0, L::template GatherNLane, EpiNCHWT<E>, true>(pa, pb, pe, g, s);
     return launch_gemm<L::template KLane0, L::template GatherNLaneBig, EpiNCHWT<E>, true>(pa, pb, pe, g, s);
@@ -210,7 +210,7 @@ static hipError_t implicit_bwd_data_t(const Dims &d, int b, const void *dy, cons
         for (int c = 0; c < d.sw; ++c) {
             int h0, w0, Hh, Ww, Ra, Sc;
             phase_shape(a, c, h0, w0, Hh, Ww, Ra, Sc);
-            if (Hh && Ww && Ra && Sc && output_splits(d.C, b * Hh * Ww, d.K * Ra * Sc, F32) > 1) any_split = true;
+            if (Hh && Ww && Ra && Sc && output_splits(d.C, b * Hh * Ww, d.K * Ra * Sc, F32 && !d.det) > 1) any_split = true;
         }
     if (any_split) {
         hipError_t e = fill_zero((float *)dx, (size_t)b * d.C * d.H * d.W, s);
@@ -223,7 +223,7 @@ static hipError_t implicit_bwd_data_t(const Dims &d, int b, const void *dy, cons
             if (Hh == 0 || Ww == 0) continue;
             GemmShape g{d.C, b * Hh * Ww, d.K * Ra * Sc};
             if (any_split && g.Kd == 0) continue;  // dx is already zero there
-            g.splits = output_splits(g.M, g.N, g.Kd, F32);
+            g.splits = output_splits(g.M, g.N, g.Kd, F32 && !d.det);
             const bool split = g.splits > 1;
             KLaneParams pa{};
             pa.t = w; pa.bytes = wbytes(d); pa.col_stride = d.R * d.S;
@@ -259,7 +259,7 @@ static hipError_t implicit_bwd_data_t(const Dims &d, int b, const void *dy, cons
                     done = true;
                 }
             }
-            g.tail_split = true;
+            g.tail_split = !d.det;
             if constexpr (!F32) {
                 if (nlane) {
                     e = launch_phase<L::template FilterNLane, L::template GatherNLane, L::template GatherNLaneBig,
@@ -297,15 +297,48 @@ int filter_splits(int M, int N, int Kd, int batch)
     return best_fill(tiles, want, (want + 1) / 2, want * 2 < cap ? want * 2 : cap, slots);
 }
 
+// Reproducible BackwardFilter: at most this much workspace holds the reduction chunks' partial
+// results (one K x CRS plane per chunk); a filter too large for several planes gets fewer, longer chunks.
+constexpr size_t kDetPartialCap = (size_t)32 << 20;
+
+static int det_filter_splits(const Dims &d, int b)
+{
+    const int Kd = b * d.P * d.Q;
+    long want = filter_splits(d.K, d.crs(), Kd);
+    const long cap = (long)(kDetPartialCap / ((size_t)4 * d.K * d.crs()));
+    if (want > cap) want = cap;
+    int chunk;
+    return effective_splits(Kd, (int)(want < 1 ? 1 : want), chunk);
+}
+
+size_t implicit_det_ws_bytes(const Dims &d, int b)
+{
+    const int splits = det_filter_splits(d, b);
+    return splits > 1 ? (size_t)4 * splits * d.K * d.crs() : 0;  // one chunk: a single addition per element
+}
+
+// dw = beta * dw + part[0] + part[1] + ... in that order
+__global__ void reduce_partials_kernel(const float *part, int splits, size_t plane, float *dw, float beta, size_t n)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t step = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += step) {
+        float acc = beta == 0.f ? 0.f : dw[i];
+        for (int sp = 0; sp < splits; ++sp) acc += part[(size_t)sp * plane + i];
+        dw[i] = acc;
+    }
+}
+
 template <class E>
 static hipError_t implicit_bwd_filter_t(const Dims &d, int b, const void *x, const void *dy, float *dw, float beta,
-                                        hipStream_t s)
+                                        float *ws, hipStream_t s)
 {
     typedef Loaders<E> L;
     hipError_t e;
-    if (beta == 0.f && (e = fill_zero(dw, (size_t)d.K * d.crs(), s)) != hipSuccess) return e;
     GemmShape g{d.K, d.crs(), b * d.P * d.Q};
-    g.splits = filter_splits(g.M, g.N, g.Kd);
+    g.splits = d.det ? det_filter_splits(d, b) : filter_splits(g.M, g.N, g.Kd);
+    const bool partials = d.det && g.splits > 1;
+    if (!partials && beta == 0.f && (e = fill_zero(dw, (size_t)d.K * d.crs(), s)) != hipSuccess) return e;
     KLaneParams pa{};
     pa.t = dy; pa.bytes = ybytes(d, b);
     pa.grid_hw = FastDiv(d.P * d.Q); pa.grid_w = FastDiv(d.Q);
@@ -320,6 +353,21 @@ static hipError_t implicit_bwd_filter_t(const Dims &d, int b, const void *x, con
     pb.mul_h = d.sh; pb.add_h = -d.ph; pb.mul_w = d.sw; pb.add_w = -d.pw;
     pb.shift = d.ph * d.W + d.pw;
     pb.n_tap_h = d.R; pb.n_tap_w = d.S;
+    if (partials) {
+        const size_t plane = (size_t)d.K * d.crs();
+        EpiPartialParams pp{ws, d.crs(), (long)plane};
+        if (d.R * d.S <= 31) e = launch_gemm<L::template DyTab, L::template XTab, EpiPartial, true>(pa, pb, pp, g, s);
+        else e = launch_gemm<L::template DyKLane, L::template XKLane, EpiPartial, true>(pa, pb, pp, g, s);
+        if (e != hipSuccess) return e;
+        if (LaunchLog *log = launch_log()) {
+            log->add("reduce_partials_kernel");
+            return hipSuccess;
+        }
+        size_t blocks = (plane + 255) / 256;
+        if (blocks > 4096) blocks = 4096;
+        reduce_partials_kernel<<<(unsigned)blocks, 256, 0, s>>>(ws, g.splits, plane, dw, beta, plane);
+        return hipGetLastError();
+    }
     EpiDenseParams pe{dw, d.crs()};
     if (d.R * d.S <= 31)  // per-row state in an LDS table
         return launch_gemm<L::template DyTab, L::template XTab, EpiAtomic, true>(pa, pb, pe, g, s);
@@ -327,10 +375,10 @@ static hipError_t implicit_bwd_filter_t(const Dims &d, int b, const void *x, con
 }
 
 hipError_t implicit_bwd_filter(const Dims &d, int b, const void *x, const void *dy, float *dw, float beta,
-                               hipStream_t s)
+                               float *ws, hipStream_t s)
 {
-    return d.dtype == 1 ? implicit_bwd_filter_t<bf16>(d, b, x, dy, dw, beta, s)
-                        : implicit_bwd_filter_t<float>(d, b, x, dy, dw, beta, s);
+    return d.dtype == 1 ? implicit_bwd_filter_t<bf16>(d, b, x, dy, dw, beta, ws, s)
+                        : implicit_bwd_filter_t<float>(d, b, x, dy, dw, beta, ws, s);
 }
 
 }  // namespace ucd

@@ -86,14 +86,15 @@ __device__ __forceinline__ void xcd_tile(int tiles_m, int tiles_n, int &tile_m, 
     tile_n = (int)(t / (uint32_t)tiles_m);
 }
 
-// Tail splitting.  A launch takes as long as the busiest CU, so a tile count a little above a
+// Tail spreading.  A launch takes as long as the busiest CU, so a tile count a little above a
 // multiple of the CU count costs almost a whole extra round of workgroups.  With `tiles` > 0 the
-// last `tiles` tiles (in tile order) are each computed by `splits` workgroups, one per reduction
-// chunk of `chunk` rows, which add their partial results into a zero-filled output with atomics;
-// all other tiles are computed by one workgroup each as usual.  grid.x = (all tiles - tiles) +
-// tiles * splits, grid.y = 1.
+// reduction steps of the last `tiles` tiles (in tile order), tiles * ksteps of them, are dealt out
+// in equal contiguous runs to `wgs` workgroups: a run is a piece of one tile's reduction, or the end
+// of one tile's and the start of the next one's.  Each piece is added into a zero-filled output
+// with atomics; all other tiles are computed by one workgroup each as usual.
+// grid.x = (all tiles - tiles) + wgs, grid.y = 1.
 struct TailSplit {
-    int tiles, splits, chunk;
+    int tiles, wgs, ksteps;
 };
 
 // Loaders may keep per-workgroup state in LDS (`Shared`, filled by `setup` before the main loop,
@@ -1103,31 +1104,42 @@ struct EpiAtomic {
     }
 };
 
-// What a workgroup computes: a tile and a range of reduction rows; `accumulate` = it adds a partial
-// result (one chunk of a tail tile) instead of storing.
+// Dense row-major store of one reduction chunk's partial result into that chunk's own plane,
+// out + split * plane (the planes are summed in a fixed order by a second kernel: the
+// run-to-run reproducible alternative to EpiAtomic).
+struct EpiPartialParams {
+    float *out;
+    int ld;
+    long plane;
+};
+struct EpiPartial {
+    static constexpr bool kCanAdd = false;
+    static constexpr bool kPerSplit = true;
+    static const char *name() { return "EpiPartial"; }
+    typedef EpiPartialParams Params;
+    int j_;
+    __device__ __forceinline__ void prep(const Params &, int j) { j_ = j; }
+    __device__ __forceinline__ void store(const Params &p, int m, float v) const { p.out[(size_t)m * p.ld + j_] = v; }
+};
+template <class Epi>
+__host__ __device__ constexpr auto per_split(int) -> decltype(Epi::kPerSplit) { return Epi::kPerSplit; }
+template <class Epi>
+__host__ __device__ constexpr bool per_split(...) { return false; }
+
+// What a workgroup computes: a tile and a range of reduction rows (chunk `split`); `accumulate` = it
+// adds a partial result (a piece of a tail tile) instead of storing.
 struct WorkItem {
-    int m0, n0, k_begin, k_end;
+    int m0, n0, k_begin, k_end, split;
     bool accumulate;
 };
-template <class T, class Epi>
-__device__ __forceinline__ WorkItem work_item(int Kd, int k_chunk, int tiles_m, int tiles_n, const TailSplit &tail)
+template <class T>
+__device__ __forceinline__ WorkItem work_item(int Kd, int k_chunk, int tiles_m, int tiles_n, int whole_tiles)
 {
-    int tile_m, tile_n, split;
+    int tile_m, tile_n, split = 0;
     WorkItem w;
     w.accumulate = false;
-    if (Epi::kCanAdd && tail.tiles > 0) {
-        const int whole = tiles_m * tiles_n - tail.tiles;
-        int t;
-        if ((int)blockIdx.x < whole) {
-            t = (int)xcd_order(blockIdx.x, (uint32_t)whole);
-            split = 0;
-        } else {
-            const int r = (int)blockIdx.x - whole;
-            t = whole + r / tail.splits;
-            split = r % tail.splits;
-            k_chunk = tail.chunk;
-            w.accumulate = true;
-        }
+    if (whole_tiles > 0) {  // a launch with a spread tail: the tiles in front of it, one workgroup each
+        const int t = (int)xcd_order(blockIdx.x, (uint32_t)whole_tiles);
         tile_m = t % tiles_m;
         tile_n = t / tiles_m;
     } else {
@@ -1137,7 +1149,26 @@ __device__ __forceinline__ WorkItem work_item(int Kd, int k_chunk, int tiles_m, 
     w.n0 = tile_n * T::BN;
     w.k_begin = split * k_chunk;
     w.k_end = min(Kd, w.k_begin + k_chunk);
+    w.split = split;
     return w;
+}
+// The next piece of a tail workgroup's run [it, it_end) of reduction steps, numbered through the
+// tail tiles one after another (ksteps each); false when the run is used up.
+template <class T>
+__device__ __forceinline__ bool next_tail_item(WorkItem &w, int &it, int it_end, int whole_tiles, int ksteps,
+                                               int tiles_m, int Kd)
+{
+    if (it >= it_end) return false;
+    const int t = whole_tiles + it / ksteps, s0 = it % ksteps;
+    const int s1 = min(ksteps, s0 + (it_end - it));
+    w.m0 = (t % tiles_m) * T::BM;
+    w.n0 = (t / tiles_m) * T::BN;
+    w.k_begin = s0 * kBK;
+    w.k_end = min(Kd, s1 * kBK);
+    w.accumulate = true;
+    w.split = 0;
+    it += s1 - s0;
+    return true;
 }
 
 // Stores (or adds) a wave's accumulators.  Element v of a 32x32 MFMA tile: row
@@ -1191,19 +1222,8 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(AParams pa, BParams pb, 
         pb.t = (const float *)pb.t + b_batch * blockIdx.z;
         pe.out = (float *)pe.out + c_batch * blockIdx.z;
     }
-    const WorkItem wi = work_item<T, Epi>(Kd, k_chunk, tiles_m, tiles_n, tail);
-    const int m0 = wi.m0, n0 = wi.n0, k_begin = wi.k_begin, k_end = wi.k_end;
-    const bool accumulate = wi.accumulate;
-
     __shared__ typename ALoader::Shared sha;
     __shared__ typename BLoader::Shared shb;
-    ALoader la;
-    BLoader lb;
-    la.init(pa, m0, M);
-    lb.init(pb, n0, N);
-    la.setup(sha, k_begin, k_end, lb);
-    lb.setup(shb, k_begin, k_end, la);
-    if constexpr (ALoader::kHasShared || BLoader::kHasShared) __syncthreads();
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -1211,111 +1231,140 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(AParams pa, BParams pb, 
     const int wn0 = (wave / T::WAVES_M) * (T::WN * 32);
     const int l32 = lane & 31, lhi = lane >> 5;
 
-    f32x16 acc[T::WM][T::WN];
-#pragma unroll
-    for (int i = 0; i < T::WM; ++i)
-#pragma unroll
-        for (int j = 0; j < T::WN; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-    typename ALoader::Regs ra;
-    typename BLoader::Regs rb;
-
-    // Software pipeline, two tiles deep with one register set: during step s (MFMAs on tile s from
-    // one LDS buffer) the registers holding tile s+1, loaded during step s-1, are written to the
-    // other LDS buffer and immediately reloaded with tile s+2.  That work is dealt out over the 8
-    // k-pairs of the step, so that each wave always has MFMAs in flight while it issues its loads
-    // and LDS writes (a wave that issued them in one block would leave the matrix pipe idle unless
-    // another wave happened to be in its MFMA phase).
-    constexpr int NA = ALoader::NE, NB = BLoader::NE, kGroups = kBK / 2;
-    la.prep(k_begin, k_end, lb);
-    lb.prep(k_begin, k_end, la);
-#pragma unroll
-    for (int i = 0; i < NA; ++i) la.load(i, ra.r);
-#pragma unroll
-    for (int i = 0; i < NB; ++i) lb.load(i, rb.r);
-#pragma unroll
-    for (int i = 0; i < NA; ++i) la.store(lds[0], i, ra.r);
-#pragma unroll
-    for (int i = 0; i < NB; ++i) lb.store(lds[0] + kBK * T::LDA, i, rb.r);
-    la.prep(k_begin + kBK, k_end, lb);
-    lb.prep(k_begin + kBK, k_end, la);
-#pragma unroll
-    for (int i = 0; i < NA; ++i) la.load(i, ra.r);
-#pragma unroll
-    for (int i = 0; i < NB; ++i) lb.load(i, rb.r);
-    __syncthreads();
-
-    int buf = 0;
-    for (int k0 = k_begin; k0 < k_end; k0 += kBK) {
-        if constexpr (ALoader::kHasShared || BLoader::kHasShared) {
-            // LDS tables hold kTabRows reduction rows (plus the two tiles of lookahead, already
-            // fetched from the old contents): refill them at every multiple of that
-            if (k0 != k_begin && ((k0 - k_begin) & (kTabRows - 1)) == 0) {
-                __syncthreads();
-                la.setup(sha, k0, k_end, lb);
-                lb.setup(shb, k0, k_end, la);
-                __syncthreads();
-            }
-        }
-        const float *As = lds[buf];
-        const float *Bs = lds[buf] + kBK * T::LDA;
-        float *An = lds[buf ^ 1];
-        float *Bn = lds[buf ^ 1] + kBK * T::LDA;
-        // operands of the next k-pair are read from LDS before the MFMAs of the current one issue
-        float a[2][T::WM], b[2][T::WN];
-#pragma unroll
-        for (int i = 0; i < T::WM; ++i) a[0][i] = As[lhi * T::LDA + wm0 + T::WM * l32 + i];
-#pragma unroll
-        for (int j = 0; j < T::WN; ++j) b[0][j] = Bs[lhi * T::LDB + wn0 + j * 32 + l32];
-        __builtin_amdgcn_sched_barrier(0);
-        __builtin_amdgcn_s_setprio(UCD_MFMA_PRIO);  // a wave inside its MFMA run keeps the pipe
-#pragma unroll
-        for (int kk = 0; kk < kBK; kk += 2) {
-            const int g = kk >> 1, cur = g & 1, nxt = cur ^ 1;
-            constexpr int NM = T::WM * T::WN;
-            // each piece of memory work issues behind one MFMA, in the shadow of its 16 passes
-#pragma unroll
-            for (int m = 0; m < NM; ++m) {
-                const int mi = m / T::WN, mj = m % T::WN;
-                acc[mi][mj] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[cur][mi], b[cur][mj], acc[mi][mj], 0, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
-                if (m == 0 && kk == 0) {  // per-step loader state, needed by the loads further down
-                    la.prep(k0 + 2 * kBK, k_end, lb);
-                    lb.prep(k0 + 2 * kBK, k_end, la);
-                }
-                if (m == 0 && kk + 2 < kBK) {
-#pragma unroll
-                    for (int i = 0; i < T::WM; ++i) a[nxt][i] = As[(kk + 2 + lhi) * T::LDA + wm0 + T::WM * l32 + i];
-#pragma unroll
-                    for (int j = 0; j < T::WN; ++j) b[nxt][j] = Bs[(kk + 2 + lhi) * T::LDB + wn0 + j * 32 + l32];
-                }
-                if (m == 1 % NM) {
-#pragma unroll
-                    for (int i = 0; i < NA; ++i)
-                        if (i * kGroups / NA == g) {
-                            la.store(An, i, ra.r);
-                            la.load(i, ra.r);
-                        }
-                }
-                if (m == 2 % NM) {
-#pragma unroll
-                    for (int i = 0; i < NB; ++i)
-                        if (i * kGroups / NB == g) {
-                            lb.store(Bn, i, rb.r);
-                            lb.load(i, rb.r);
-                        }
-                }
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        }
-        __builtin_amdgcn_s_setprio(0);
-        __syncthreads();
-        buf ^= 1;
+    // What this workgroup computes: one tile (and reduction chunk), or, in the spread tail of a
+    // launch, a run of reduction steps that may end one tile and start the next.
+    WorkItem wi;
+    int tail_it = 0, tail_end = 0;
+    const int whole_tiles = (Epi::kCanAdd && tail.tiles > 0) ? tiles_m * tiles_n - tail.tiles : 0;
+    const bool tail_wg = Epi::kCanAdd && tail.tiles > 0 && (int)blockIdx.x >= whole_tiles;
+    if (tail_wg) {
+        const int r = (int)blockIdx.x - whole_tiles, steps = tail.tiles * tail.ksteps;
+        tail_it = (int)((long)r * steps / tail.wgs);
+        tail_end = (int)((long)(r + 1) * steps / tail.wgs);
+        if (!next_tail_item<T>(wi, tail_it, tail_end, whole_tiles, tail.ksteps, tiles_m, Kd)) return;
+    } else {
+        wi = work_item<T>(Kd, k_chunk, tiles_m, tiles_n, whole_tiles);
+        if constexpr (per_split<Epi>(0)) pe.out += (long)wi.split * pe.plane;
     }
+    for (;;) {
+        const int m0 = wi.m0, n0 = wi.n0, k_begin = wi.k_begin, k_end = wi.k_end;
+        const bool accumulate = wi.accumulate;
 
-    write_tile<T, Epi>(pe, acc, M, N, m0, n0, wm0, wn0, l32, lhi, accumulate);
+        ALoader la;
+        BLoader lb;
+        la.init(pa, m0, M);
+        lb.init(pb, n0, N);
+        la.setup(sha, k_begin, k_end, lb);
+        lb.setup(shb, k_begin, k_end, la);
+        if constexpr (ALoader::kHasShared || BLoader::kHasShared) __syncthreads();
+
+        f32x16 acc[T::WM][T::WN];
+#pragma unroll
+        for (int i = 0; i < T::WM; ++i)
+#pragma unroll
+            for (int j = 0; j < T::WN; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+        typename ALoader::Regs ra;
+        typename BLoader::Regs rb;
+
+        // Software pipeline, two tiles deep with one register set: during step s (MFMAs on tile s from
+        // one LDS buffer) the registers holding tile s+1, loaded during step s-1, are written to the
+        // other LDS buffer and immediately reloaded with tile s+2.  That work is dealt out over the 8
+        // k-pairs of the step, so that each wave always has MFMAs in flight while it issues its loads
+        // and LDS writes (a wave that issued them in one block would leave the matrix pipe idle unless
+        // another wave happened to be in its MFMA phase).
+        constexpr int NA = ALoader::NE, NB = BLoader::NE, kGroups = kBK / 2;
+        la.prep(k_begin, k_end, lb);
+        lb.prep(k_begin, k_end, la);
+#pragma unroll
+        for (int i = 0; i < NA; ++i) la.load(i, ra.r);
+#pragma unroll
+        for (int i = 0; i < NB; ++i) lb.load(i, rb.r);
+#pragma unroll
+        for (int i = 0; i < NA; ++i) la.store(lds[0], i, ra.r);
+#pragma unroll
+        for (int i = 0; i < NB; ++i) lb.store(lds[0] + kBK * T::LDA, i, rb.r);
+        la.prep(k_begin + kBK, k_end, lb);
+        lb.prep(k_begin + kBK, k_end, la);
+#pragma unroll
+        for (int i = 0; i < NA; ++i) la.load(i, ra.r);
+#pragma unroll
+        for (int i = 0; i < NB; ++i) lb.load(i, rb.r);
+        __syncthreads();
+
+        int buf = 0;
+        for (int k0 = k_begin; k0 < k_end; k0 += kBK) {
+            if constexpr (ALoader::kHasShared || BLoader::kHasShared) {
+                // LDS tables hold kTabRows reduction rows (plus the two tiles of lookahead, already
+                // fetched from the old contents): refill them at every multiple of that
+                if (k0 != k_begin && ((k0 - k_begin) & (kTabRows - 1)) == 0) {
+                    __syncthreads();
+                    la.setup(sha, k0, k_end, lb);
+                    lb.setup(shb, k0, k_end, la);
+                    __syncthreads();
+                }
+            }
+            const float *As = lds[buf];
+            const float *Bs = lds[buf] + kBK * T::LDA;
+            float *An = lds[buf ^ 1];
+            float *Bn = lds[buf ^ 1] + kBK * T::LDA;
+            // operands of the next k-pair are read from LDS before the MFMAs of the current one issue
+            float a[2][T::WM], b[2][T::WN];
+#pragma unroll
+            for (int i = 0; i < T::WM; ++i) a[0][i] = As[lhi * T::LDA + wm0 + T::WM * l32 + i];
+#pragma unroll
+            for (int j = 0; j < T::WN; ++j) b[0][j] = Bs[lhi * T::LDB + wn0 + j * 32 + l32];
+            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_setprio(UCD_MFMA_PRIO);  // a wave inside its MFMA run keeps the pipe
+#pragma unroll
+            for (int kk = 0; kk < kBK; kk += 2) {
+                const int g = kk >> 1, cur = g & 1, nxt = cur ^ 1;
+                constexpr int NM = T::WM * T::WN;
+                // each piece of memory work issues behind one MFMA, in the shadow of its 16 passes
+#pragma unroll
+                for (int m = 0; m < NM; ++m) {
+                    const int mi = m / T::WN, mj = m % T::WN;
+                    acc[mi][mj] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[cur][mi], b[cur][mj], acc[mi][mj], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (m == 0 && kk == 0) {  // per-step loader state, needed by the loads further down
+                        la.prep(k0 + 2 * kBK, k_end, lb);
+                        lb.prep(k0 + 2 * kBK, k_end, la);
+                    }
+                    if (m == 0 && kk + 2 < kBK) {
+#pragma unroll
+                        for (int i = 0; i < T::WM; ++i) a[nxt][i] = As[(kk + 2 + lhi) * T::LDA + wm0 + T::WM * l32 + i];
+#pragma unroll
+                        for (int j = 0; j < T::WN; ++j) b[nxt][j] = Bs[(kk + 2 + lhi) * T::LDB + wn0 + j * 32 + l32];
+                    }
+                    if (m == 1 % NM) {
+#pragma unroll
+                        for (int i = 0; i < NA; ++i)
+                            if (i * kGroups / NA == g) {
+                                la.store(An, i, ra.r);
+                                la.load(i, ra.r);
+                            }
+                    }
+                    if (m == 2 % NM) {
+#pragma unroll
+                        for (int i = 0; i < NB; ++i)
+                            if (i * kGroups / NB == g) {
+                                lb.store(Bn, i, rb.r);
+                                lb.load(i, rb.r);
+                            }
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            __builtin_amdgcn_s_setprio(0);
+            __syncthreads();
+            buf ^= 1;
+        }
+
+        write_tile<T, Epi>(pe, acc, M, N, m0, n0, wm0, wn0, l32, lhi, accumulate);
+        if (!tail_wg || !next_tail_item<T>(wi, tail_it, tail_end, whole_tiles, tail.ksteps, tiles_m, Kd)) break;
+    }
 }
 
 // ---- the same GEMM on the bf16 matrix pipe -----------------------------------------------------
@@ -1342,13 +1391,15 @@ struct HalfTile {
 template <class T, class ALoader, class BLoader, class Epi, class AParams, class BParams>
 __global__ __launch_bounds__(kThreads) void gemm_kernel_bf16(AParams pa, BParams pb, typename Epi::Params pe,
                                                               int M, int N, int Kd, int k_chunk, int tiles_m,
-                                                              int tiles_n, TailSplit tail)
+                                                              int tiles_n)
 {
     typedef HalfTile<T> H;
     __shared__ __attribute__((aligned(16))) uint16_t lds[2][H::HALFS];
 
-    const WorkItem wi = work_item<T, Epi>(Kd, k_chunk, tiles_m, tiles_n, tail);
+    // bf16 outputs cannot be accumulated: no spread tail here
+    const WorkItem wi = work_item<T>(Kd, k_chunk, tiles_m, tiles_n, 0);
     const int m0 = wi.m0, n0 = wi.n0, k_begin = wi.k_begin, k_end = wi.k_end;
+    if constexpr (per_split<Epi>(0)) pe.out += (long)wi.split * pe.plane;
 
     __shared__ typename ALoader::Shared sha;
     __shared__ typename BLoader::Shared shb;

@@ -16,7 +16,18 @@ struct GemmShape {
 };
 
 constexpr int kCUs = 256;          // compute units of the MI355X
-constexpr int kTailMinRows = 128;  // shortest reduction chunk of a split tail tile
+constexpr int kTailMinSteps = 8;    // a tail workgroup's run has at least this many reduction steps (of BK rows)
+constexpr int kTailMaxTiles = 224;  // a last round fuller than this is left alone
+
+// Reduction chunks are whole steps of BK rows: the chunk length for a requested split count, and the
+// number of chunks that really results.
+inline int effective_splits(int Kd, int want, int &k_chunk)
+{
+    if (want < 1) want = 1;
+    k_chunk = ((Kd + want - 1) / want + kBK - 1) / kBK * kBK;
+    if (k_chunk < kBK) k_chunk = kBK;
+    return Kd > 0 ? (Kd + k_chunk - 1) / k_chunk : 1;
+}
 
 template <class T, template <int> class AL, template <int> class BL, class Epi, class AP, class BP>
 hipError_t launch_tile(const AP &pa, const BP &pb, const typename Epi::Params &pe, const GemmShape &g,
@@ -27,30 +38,28 @@ hipError_t launch_tile(const AP &pa, const BP &pb, const typename Epi::Params &p
     if (kBf16Mfma && g.batch != 1) return hipErrorInvalidValue;
     const int tiles_m = (g.M + T::BM - 1) / T::BM, tiles_n = (g.N + T::BN - 1) / T::BN;
     if (tiles_m <= 0 || tiles_n <= 0) return hipSuccess;
-    int splits = g.splits < 1 ? 1 : g.splits;
-    int k_chunk = ((g.Kd + splits - 1) / splits + kBK - 1) / kBK * kBK;
-    if (k_chunk < kBK) k_chunk = kBK;
-    splits = g.Kd > 0 ? (g.Kd + k_chunk - 1) / k_chunk : 1;
-    // Tail splitting (see TailSplit): when an unsplit GEMM has a few tiles more than a multiple of
-    // the CU count, those few are split along the reduction so that every CU gets the same work.
+    int k_chunk;
+    const int splits = effective_splits(g.Kd, g.splits, k_chunk);
+    // Tail spreading (see TailSplit): when an unsplit GEMM's tile count is not a multiple of the CU
+    // count, the reduction steps of the tiles beyond the last multiple are dealt out evenly to (up to)
+    // one workgroup per CU, so that every CU gets the same work.
     TailSplit tail{0, 1, 0};
     if constexpr (Epi::kCanAdd) {
         const long tiles = (long)tiles_m * tiles_n;
         const int over = (int)(tiles % kCUs);
-        if (g.tail_split && splits == 1 && g.batch == 1 && tiles >= 3 * kCUs && over > 0 && over <= kCUs / 2 &&
-            g.Kd >= 2 * kTailMinRows) {
-            int f = kCUs / over;
-            if (f > g.Kd / kTailMinRows) f = g.Kd / kTailMinRows;
-            if (f > 16) f = 16;
-            if (f >= 2) {
+        if (g.tail_split && splits == 1 && g.batch == 1 && tiles >= 2 * kCUs && over > 0 && over <= kTailMaxTiles) {
+            const int ksteps = (g.Kd + kBK - 1) / kBK;
+            const long steps = (long)over * ksteps;
+            long wgs = steps / kTailMinSteps;
+            if (wgs > kCUs) wgs = kCUs;
+            if (wgs > over && steps < (1l << 30)) {   // more workgroups than tiles, or nothing is gained
                 tail.tiles = over;
-                tail.splits = f;
-                tail.chunk = ((g.Kd + f - 1) / f + kBK - 1) / kBK * kBK;
-                tail.splits = (g.Kd + tail.chunk - 1) / tail.chunk;
+                tail.wgs = (int)wgs;
+                tail.ksteps = ksteps;
             }
         }
     }
-    const unsigned gx = (unsigned)(tiles_m * tiles_n - tail.tiles + tail.tiles * tail.splits);
+    const unsigned gx = (unsigned)(tiles_m * tiles_n - tail.tiles + (tail.tiles ? tail.wgs : 0));
     dim3 grid(gx, (unsigned)splits, (unsigned)g.batch);
     if (LaunchLog *log = launch_log()) {
         if (tail.tiles) log->add("zero_tiles_kernel");
@@ -59,7 +68,7 @@ hipError_t launch_tile(const AP &pa, const BP &pb, const typename Epi::Params &p
                  std::to_string(tiles_m * tiles_n) + " splits=" + std::to_string(splits) + " batch=" +
                  std::to_string(g.batch) + " M=" + std::to_string(g.M) + " N=" + std::to_string(g.N) + " K=" +
                  std::to_string(g.Kd) +
-                 (tail.tiles ? " tail=" + std::to_string(tail.tiles) + "x" + std::to_string(tail.splits) : std::string()));
+                 (tail.tiles ? " tail=" + std::to_string(tail.tiles) + "/" + std::to_string(tail.wgs) : std::string()));
         return hipSuccess;
     }
     if (tail.tiles) {
@@ -69,7 +78,7 @@ hipError_t launch_tile(const AP &pa, const BP &pb, const typename Epi::Params &p
     }
     if constexpr (kBf16Mfma)
         gemm_kernel_bf16<T, AL<T::BM>, BL<T::BN>, Epi, AP, BP><<<grid, kThreads, 0, s>>>(
-            pa, pb, pe, g.M, g.N, g.Kd, k_chunk, tiles_m, tiles_n, tail);
+            pa, pb, pe, g.M, g.N, g.Kd, k_chunk, tiles_m, tiles_n);
     else
         gemm_kernel<T, AL<T::BM>, BL<T::BN>, Epi, AP, BP><<<grid, kThreads, 0, s>>>(
             pa, pb, pe, g.M, g.N, g.Kd, k_chunk, tiles_m, tiles_n, g.a_batch, g.b_batch, g.c_batch, tail);

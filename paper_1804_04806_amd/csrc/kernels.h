@@ -13,6 +13,10 @@ namespace ucd {
 struct Dims {
     int C, H, W, K, R, S, sh, sw, ph, pw, P, Q;
     int dtype;
+    // Reproducible mode: no launch accumulates with atomics in an order that can change from run to
+    // run.  Forward / BackwardData never split their reductions; BackwardFilter (implicit GEMM only)
+    // keeps its reduction chunks' partial results in workspace and sums them in a fixed order.
+    bool det;
     int crs() const { return C * R * S; }
     size_t esize() const { return dtype == 1 ? 2 : 4; }
 };
@@ -25,8 +29,10 @@ inline uint32_t ybytes(const Dims &d, int b) { return (uint32_t)(d.esize() * b *
 // zero-workspace implicit GEMM
 hipError_t implicit_fwd(const Dims &d, int b, const void *x, const void *w, void *y, hipStream_t s);
 hipError_t implicit_bwd_data(const Dims &d, int b, const void *dy, const void *w, void *dx, hipStream_t s);
+// ws: only read in reproducible mode (implicit_det_ws_bytes(d, b) bytes)
 hipError_t implicit_bwd_filter(const Dims &d, int b, const void *x, const void *dy, float *dw, float beta,
-                               hipStream_t s);
+                               float *ws, hipStream_t s);
+size_t implicit_det_ws_bytes(const Dims &d, int b);
 
 // im2col into workspace + GEMM
 size_t im2col_ws_bytes(const Dims &d, int b);

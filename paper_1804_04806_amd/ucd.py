@@ -31,6 +31,7 @@ EXPORTS = [
     "ucd_plan", "ucd_plan_wd", "ucd_bench_table", "ucd_bench_clear", "ucd_conv_fwd", "ucd_conv_bwd_data",
     "ucd_conv_bwd_filter", "ucd_run_micro", "ucd_mfma_probe", "ucd_describe_micro",
     "ucd_bench_save", "ucd_bench_load", "ucd_bench_put", "ucd_plan_cached", "ucd_conv_fwd_static_ws",
+    "ucd_set_deterministic",
 ]
 
 
@@ -67,6 +68,7 @@ def lib():
         L.ucd_strerror.restype = ctypes.c_char_p
         L.ucd_strerror.argtypes = [i]
         L.ucd_version.restype = i
+        L.ucd_set_deterministic.argtypes = [i]
         L.ucd_workspace_size.restype = sz
         L.ucd_workspace_size.argtypes = [lp, i, i, i]
         L.ucd_plan_from_table.argtypes = [i, sz, i, i, u64p, szp, pp]
@@ -175,6 +177,11 @@ class Plan:
 
 def ucd_version():
     return lib().ucd_version()
+
+
+def ucd_set_deterministic(on):
+    """Switches reproducible execution on / off (on < 0: query); returns the previous setting."""
+    return lib().ucd_set_deterministic(int(on))
 
 
 def ucd_workspace_size(desc, op, algo, b):

@@ -101,3 +101,23 @@ def test_run_micro_rejects_a_micro_batch_beyond_the_descriptor():
     Lbad = ucd.layer(N=8, C=16, H=16, W=16, K=32, R=3, S=3, pad_h=1, pad_w=1, dtype=2)
     assert lib.ucd_run_micro(C.byref(Lbad), ucd.FWD, ucd.ALGO_IMPLICIT, 8, 4096, 4096, 4096, 0.0,
                              None, 0, None) == ucd.E_INVALID
+
+
+def test_reproducible_mode_workspace_sizes():
+    """In the reproducible mode BackwardFilter is the implicit GEMM's alone and needs one K*C*R*S
+    plane per reduction chunk; Forward / BackwardData sizes do not change."""
+    L = ucd.layer(N=64, C=64, H=28, W=28, K=96, R=3, S=3, pad_h=1, pad_w=1)
+    before = [[ucd.ucd_workspace_size(L, op, a, 64) for a in range(ucd.N_ALGO)] for op in range(3)]
+    assert before[ucd.BWD_FILTER][ucd.ALGO_IMPLICIT] == 0
+    assert ucd.ucd_set_deterministic(1) == 0
+    try:
+        assert ucd.ucd_set_deterministic(-1) == 1
+        after = [[ucd.ucd_workspace_size(L, op, a, 64) for a in range(ucd.N_ALGO)] for op in range(3)]
+        assert after[ucd.FWD] == before[ucd.FWD] and after[ucd.BWD_DATA] == before[ucd.BWD_DATA]
+        need = after[ucd.BWD_FILTER][ucd.ALGO_IMPLICIT]
+        plane = 4 * 96 * 64 * 9
+        assert need % plane == 0 and 2 <= need // plane and need <= 32 << 20
+        assert all(after[ucd.BWD_FILTER][a] == ucd.WS_NA for a in range(1, ucd.N_ALGO))
+    finally:
+        assert ucd.ucd_set_deterministic(0) == 1
+    assert [[ucd.ucd_workspace_size(L, op, a, 64) for a in range(ucd.N_ALGO)] for op in range(3)] == before

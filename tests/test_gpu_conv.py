@@ -133,7 +133,7 @@ def test_tail_tiles_split_along_the_reduction():
     x, w, dy = inputs(s, seed=13)
     for op in (ucd.FWD, ucd.BWD_DATA):
         text, _ = ucd.ucd_describe_micro(desc, op, ucd.ALGO_IMPLICIT, s.N)
-        assert "zero_tiles_kernel" in text and "tail=16x" in text, text
+        assert "zero_tiles_kernel" in text and "tail=16/" in text, text
         got = run_hip(s, op, [(ucd.ALGO_IMPLICIT, s.N)], x=x, w=w, dy=dy)
         assert np.isfinite(got).all()
         assert rel_l2(got, run_oracle(s, op, x=x, w=w, dy=dy)) <= 1e-5
