@@ -3,6 +3,7 @@
 //   Forward        Y[K x bPQ]   = W[K x CRS]      * im2col(X)[CRS x bPQ]
 //   BackwardData   dX[C x bHW]  = W^T[C x KRS]    * gather(dY)[KRS x bHW]   (one GEMM per stride phase)
 //   BackwardFilter dW[K x CRS] += dY[K x bPQ]     * im2col(X)^T[bPQ x CRS]  (split over bPQ, fp32 atomics)
+#include <cstdlib>
 #include <type_traits>
 
 #include "gemm_launch.hpp"
@@ -81,11 +82,51 @@ static int output_splits(int M, int N, int Kd, bool fp32_out)
     return best_fill(tiles, want, want / 2 < 2 ? 2 : want / 2, want * 2 < cap ? want * 2 : cap, kSlotsOutput);
 }
 
+// bf16 tensors, stride-1 layers whose output rows are as wide as the input rows (so that, for every
+// tap, neighbouring pixels of an image are neighbours in memory), filters of at most 31 taps: the
+// activation operand is fetched four pixels per load (RunNLaneT).  Tile positions run over the
+// images with their pixel count rounded up to 4.
+static bool vector_gather_applies(const Dims &d, int grid_w, int tensor_w)
+{
+    // UCD_BF16_ELEMENTWISE=1 keeps the element-wise kernel (for comparisons)
+    static const bool off = [] { const char *e = std::getenv("UCD_BF16_ELEMENTWISE"); return e && e[0] == '1'; }();
+    return !off && d.dtype == 1 && d.sh == 1 && d.sw == 1 && grid_w == tensor_w && d.R * d.S <= 31;
+}
+
+static hipError_t implicit_fwd_bf16_vec(const Dims &d, int b, const void *x, const void *w, void *y, hipStream_t s)
+{
+    const int px = d.P * d.Q, px_pad = (px + 3) / 4 * 4;
+    GemmShape g{d.K, b * px_pad, d.crs()};
+    RunParams pb{};
+    pb.t = x; pb.bytes = xbytes(d, b); pb.Ct = d.C; pb.Ht = d.H; pb.Wt = d.W;
+    pb.plane_px = px; pb.grid_pad = FastDiv(px_pad); pb.grid_w = FastDiv(d.Q);
+    pb.add_h = -d.ph; pb.add_w = -d.pw; pb.dir = 1;
+    pb.taps = FastDiv(d.R * d.S); pb.taps_w = FastDiv(d.S);
+    pb.n_tap_h = d.R; pb.n_tap_w = d.S;
+    pb.shift_thread = d.ph * d.W + d.pw; pb.shift_row = 0;
+    EpiNCHWParams pe{};
+    pe.out = y; pe.grid_hw = pb.grid_pad; pe.grid_w = pb.grid_w;
+    pe.M = d.K; pe.HWo = px; pe.Wo = d.Q; pe.h0 = 0; pe.hs = 1; pe.w0 = 0; pe.ws = 1; pe.cols = px;
+    const bool plain = d.R * d.S == 1 && d.ph == 0 && d.pw == 0;  // every element exists: no border masks
+    if (d.crs() % 8 == 0) {  // filter rows are whole 16-byte cells
+        CellParams pa{w, wbytes(d), d.crs()};
+        return plain ? launch_gemm<CellKLaneT, RunNLane, EpiNCHWT<bf16>, true>(pa, pb, pe, g, s)
+                     : launch_gemm<CellKLaneT, RunNLaneMasked, EpiNCHWT<bf16>, true>(pa, pb, pe, g, s);
+    }
+    KLaneParams pa{};
+    pa.t = w; pa.bytes = wbytes(d); pa.row_stride = 1; pa.col_stride = d.crs();
+    return plain ? launch_gemm<Loaders<bf16>::KLane0, RunNLane, EpiNCHWT<bf16>, true>(pa, pb, pe, g, s)
+                 : launch_gemm<Loaders<bf16>::KLane0, RunNLaneMasked, EpiNCHWT<bf16>, true>(pa, pb, pe, g, s);
+}
+
 template <class E>
 static hipError_t implicit_fwd_t(const Dims &d, int b, const void *x, const void *w, void *y, hipStream_t s)
 {
     typedef Loaders<E> L;
     constexpr bool F32 = std::is_same<E, float>::value;
+    if constexpr (!F32) {
+        if (vector_gather_applies(d, d.Q, d.W)) return implicit_fwd_bf16_vec(d, b, x, w, y, s);
+    }
     GemmShape g{d.K, b * d.P * d.Q, d.crs()};
     g.splits = output_splits(g.M, g.N, g.Kd, F32 && !d.det);
     KLaneParams pa{};
@@ -186,6 +227,39 @@ static hipError_t launch_phase(bool small, const KLaneParams &pa, const GatherPa
                  : launch_gemm<AL, GatherBig, Epi, ROWS96>(pa, pb, pe, g, s);
 }
 
+// Stride-1 BackwardData with bf16 tensors and vector loads of dy (see vector_gather_applies): one
+// GEMM dX[C x bHW] = W^T[C x KRS] * gather(dY), the gather running backwards through the taps.
+static hipError_t implicit_bwd_data_bf16_vec(const Dims &d, int b, const void *dy, const void *w, void *dx,
+                                             hipStream_t s)
+{
+    typedef Loaders<bf16> L;
+    const int px = d.H * d.W, px_pad = (px + 3) / 4 * 4;
+    GemmShape g{d.C, b * px_pad, d.K * d.R * d.S};
+    KLaneParams pa{};
+    pa.t = w; pa.bytes = wbytes(d); pa.col_stride = d.R * d.S;
+    pa.taps = FastDiv(d.R * d.S); pa.taps_w = FastDiv(d.S);
+    pa.k_stride = d.crs(); pa.s_mem = d.S;
+    pa.tap_add_h = 0; pa.tap_mul_h = 1; pa.tap_add_w = 0; pa.tap_mul_w = 1;
+    pa.unit_taps = 1;
+    RunParams pb{};
+    pb.t = dy; pb.bytes = ybytes(d, b); pb.Ct = d.K; pb.Ht = d.P; pb.Wt = d.Q;
+    pb.plane_px = px; pb.grid_pad = FastDiv(px_pad); pb.grid_w = FastDiv(d.W);
+    pb.add_h = d.ph; pb.add_w = d.pw; pb.dir = -1;
+    pb.taps = pa.taps; pb.taps_w = pa.taps_w;
+    pb.n_tap_h = d.R; pb.n_tap_w = d.S;
+    pb.shift_thread = 0; pb.shift_row = (d.R - 1) * d.Q + (d.S - 1);
+    EpiNCHWParams pe{};
+    pe.out = dx; pe.grid_hw = pb.grid_pad; pe.grid_w = pb.grid_w;
+    pe.M = d.C; pe.HWo = px; pe.Wo = d.W; pe.h0 = 0; pe.hs = 1; pe.w0 = 0; pe.ws = 1; pe.cols = px;
+    const bool plain = d.R * d.S == 1 && d.ph == 0 && d.pw == 0;
+    // filter operand: lanes along the input channels for filters of at most 9 taps (see below)
+    if (pick_rows(d.C, true) != 96 && d.R * d.S <= 9)
+        return plain ? launch_gemm<L::template FilterNLane, RunNLane, EpiNCHWT<bf16>, false>(pa, pb, pe, g, s)
+                     : launch_gemm<L::template FilterNLane, RunNLaneMasked, EpiNCHWT<bf16>, false>(pa, pb, pe, g, s);
+    return plain ? launch_gemm<L::template FilterKLane, RunNLane, EpiNCHWT<bf16>, true>(pa, pb, pe, g, s)
+                 : launch_gemm<L::template FilterKLane, RunNLaneMasked, EpiNCHWT<bf16>, true>(pa, pb, pe, g, s);
+}
+
 // Stride phases: input pixels h with (h + ph) % sh == a are reached only by filter rows
 // r = a, a + sh, ...; within a phase the gather is a dense stride-1 correlation with the
 // sub-sampled, index-reversed filter.  Pixels of a phase with no tap get zeros (Kd = 0).
@@ -194,6 +268,12 @@ static hipError_t implicit_bwd_data_t(const Dims &d, int b, const void *dy, cons
 {
     typedef Loaders<E> L;
     constexpr bool F32 = std::is_same<E, float>::value;
+    if constexpr (!F32) {
+        // measured slower than the element-wise kernel (its filter operand cannot be fetched in cells
+        // and, run four times per step, costs the kernel its second workgroup per CU): opt-in only
+        static const bool on = [] { const char *e = std::getenv("UCD_BF16_VEC_BWD_DATA"); return e && e[0] == '1'; }();
+        if (on && vector_gather_applies(d, d.W, d.Q)) return implicit_bwd_data_bf16_vec(d, b, dy, w, dx, s);
+    }
     if (const int f = merged_phase_factor(d)) return implicit_bwd_data_merged<E>(d, b, dy, w, dx, f, s);
     // phases whose GEMM has too few tiles split their reduction (atomics); dx is zero-filled once
     // if any phase does

@@ -1007,18 +1007,21 @@ struct EpiNCHWParams {
     void *out;
     FastDiv grid_hw, grid_w;
     int M, HWo, Wo, h0, hs, w0, ws;
+    int cols;  // pixels per image of the column grid when grid_hw divides by a padded count; 0 = no padding
 };
 template <class E>
 struct EpiNCHWT {
     static std::string name() { return std::string("EpiNCHW") + Elem<E>::tag(); }
     typedef EpiNCHWParams Params;
     int off;
-    __device__ __forceinline__ void prep(const Params &p, int j)
+    // false: column j is padding (the grid's pixel count may be rounded up past `cols`, see RunNLaneT)
+    __device__ __forceinline__ bool prep(const Params &p, int j)
     {
         uint32_t n, rest, a, b;
         p.grid_hw.divmod((uint32_t)j, n, rest);
         p.grid_w.divmod(rest, a, b);
         off = (int)n * p.M * p.HWo + (p.h0 + p.hs * (int)a) * p.Wo + p.w0 + p.ws * (int)b;
+        return p.cols == 0 || (int)rest < p.cols;
     }
     __device__ __forceinline__ void store(const Params &p, int m, float v) const
     {
@@ -1057,7 +1060,7 @@ struct EpiPhasesT {
     static std::string name() { return std::string("EpiPhases") + Elem<E>::tag(); }
     typedef EpiPhasesParams Params;
     int nb, hb, wb;
-    __device__ __forceinline__ void prep(const Params &p, int j)
+    __device__ __forceinline__ bool prep(const Params &p, int j)
     {
         uint32_t n, rest, t, u;
         p.grid_hw.divmod((uint32_t)j, n, rest);
@@ -1065,6 +1068,7 @@ struct EpiPhasesT {
         nb = (int)n * p.C * p.H * p.W;
         hb = p.vs_h * (int)t - p.pad_h;
         wb = p.vs_w * (int)u - p.pad_w;
+        return true;
     }
     __device__ __forceinline__ void store(const Params &p, int m, float v) const
     {
@@ -1087,7 +1091,7 @@ struct EpiDense {
     static const char *name() { return "EpiDense"; }
     typedef EpiDenseParams Params;
     int j_;
-    __device__ __forceinline__ void prep(const Params &, int j) { j_ = j; }
+    __device__ __forceinline__ bool prep(const Params &, int j) { j_ = j; return true; }
     __device__ __forceinline__ void store(const Params &p, int m, float v) const { p.out[(size_t)m * p.ld + j_] = v; }
 };
 
@@ -1097,7 +1101,7 @@ struct EpiAtomic {
     static const char *name() { return "EpiAtomic"; }
     typedef EpiDenseParams Params;
     int j_;
-    __device__ __forceinline__ void prep(const Params &, int j) { j_ = j; }
+    __device__ __forceinline__ bool prep(const Params &, int j) { j_ = j; return true; }
     __device__ __forceinline__ void store(const Params &p, int m, float v) const
     {
         unsafeAtomicAdd(p.out + (size_t)m * p.ld + j_, v);
@@ -1118,7 +1122,7 @@ struct EpiPartial {
     static const char *name() { return "EpiPartial"; }
     typedef EpiPartialParams Params;
     int j_;
-    __device__ __forceinline__ void prep(const Params &, int j) { j_ = j; }
+    __device__ __forceinline__ bool prep(const Params &, int j) { j_ = j; return true; }
     __device__ __forceinline__ void store(const Params &p, int m, float v) const { p.out[(size_t)m * p.ld + j_] = v; }
 };
 template <class Epi>
@@ -1177,7 +1181,7 @@ __device__ __forceinline__ bool next_tail_item(WorkItem &w, int &it, int it_end,
 // adjacent in LDS and come in one read with an immediate offset.  Columns are not interleaved:
 // consecutive lanes must keep consecutive output columns, or every store would touch only every
 // other element of a cache line (that cost the bandwidth-bound 1x1 layers a quarter of their speed).
-template <class T, class Epi>
+template <class T, class Epi, bool INTERLEAVED = true>
 __device__ __forceinline__ void write_tile(const typename Epi::Params &pe, const f32x16 (&acc)[T::WM][T::WN], int M,
                                            int N, int m0, int n0, int wm0, int wn0, int l32, int lhi,
                                            bool accumulate)
@@ -1187,12 +1191,13 @@ __device__ __forceinline__ void write_tile(const typename Epi::Params &pe, const
     for (int j = 0; j < T::WN; ++j) {
         const int col = n0 + wn0 + j * 32 + l32;
         if (col >= N) continue;
-        epi.prep(pe, col);
+        if (!epi.prep(pe, col)) continue;
 #pragma unroll
         for (int i = 0; i < T::WM; ++i)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int row = m0 + wm0 + T::WM * (8 * (v / 4) + 4 * lhi + (v % 4)) + i;
+                const int r32 = 8 * (v / 4) + 4 * lhi + (v % 4);  // row within the 32x32 MFMA tile
+                const int row = m0 + wm0 + (INTERLEAVED ? T::WM * r32 + i : 32 * i + r32);
                 if (row < M) {
                     if constexpr (Epi::kCanAdd) {
                         if (accumulate) epi.add(pe, row, acc[i][j][v]);
@@ -1530,6 +1535,381 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel_bf16(AParams pa, BParams
     write_tile<T, Epi>(pe, acc, M, N, m0, n0, wm0, wn0, l32, lhi, wi.accumulate);
 }
 
+// ---- bf16 kernel with vector operand loads --------------------------------------------------------
+// The element-wise loaders above spend 10-24 vector instructions per bf16 MFMA (one 2-byte load, its
+// address and mask arithmetic and an LDS write per element) and synchronise the workgroup every 4
+// MFMAs, which is what bounds gemm_kernel_bf16.  gemm_kernel_bf16v walks the reduction in steps of
+// kDeepBK = 64 rows (16 MFMAs per wave between barriers) and, where the tensors' layout allows,
+// fetches several elements per load:
+//   * CellKLaneT: an operand contiguous along the reduction index (the filter matrix w[k][crs] of
+//     Forward): one 16-byte load is one LDS cell (8 consecutive reduction rows of one tile position).
+//   * RunNLaneT: the activation gather of a stride-1 layer whose output rows are as wide as its
+//     input rows (grid width == tensor width): for every tap, consecutive pixels of an image are
+//     consecutive in memory, so a thread fetches 4 neighbouring pixels of one reduction row with one
+//     8-byte load (2-byte aligned: the platform runs with unaligned vector memory access enabled),
+//     takes 8 rows, transposes them in registers into 4 cells and writes each cell in one piece.
+// Tile positions index (image, pixel) with the pixel count of an image rounded up to 4, so that a
+// thread's four pixels never straddle two images; the epilogue skips the padding positions.
+// An element-wise loader (BK = 16 interface) can still serve as the A operand: it is run four times
+// per step.
+
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+constexpr int kDeepBK = 64;          // reduction rows per step of gemm_kernel_bf16v
+constexpr int kDeepPlanes = kDeepBK / 8;
+
+// LDS layout of a step's tiles: 8 planes of 8 reduction rows; a plane holds one 16-byte cell per tile
+// position.  A: plane stride odd (in cells), so that the 8 cells one 128-byte global load run delivers
+// (8 planes of one position, 8 lanes) fall into 8 different 4-bank groups.  B: the four cells a thread
+// writes (4 neighbouring pixels) go to four sub-planes TD/4 + 2 cells apart (column n -> slot
+// (n % 4) * (TD/4 + 2) + n / 4): consecutive lanes then write consecutive cells, and consecutive
+// columns, as the MFMA lanes read them, still fall into different bank groups.
+template <class T>
+struct DeepTile {
+    static constexpr int PA = T::BM + 1;
+    static constexpr int SUB = T::BN / 4 + 2, PB = 4 * SUB;
+    static constexpr int A_HALFS = kDeepPlanes * PA * 8, B_HALFS = kDeepPlanes * PB * 8;
+    static constexpr int HALFS = A_HALFS + B_HALFS;
+    static __device__ __forceinline__ int b_slot(int n) { return (n & 3) * SUB + (n >> 2); }
+};
+
+struct CellParams {
+    const void *t;
+    uint32_t bytes;
+    int col_stride;  // elements between tile positions; reduction rows are contiguous
+};
+
+template <int TD>
+struct CellKLaneT : NoSetup {
+    static constexpr bool kBf16 = true;
+    static constexpr bool kVecCells = true;
+    static std::string name() { return "CellKLane/bf16"; }
+    static constexpr int kCells = kDeepPlanes * TD;                     // cells of a step's tile
+    static constexpr int NC = (kCells + kThreads - 1) / kThreads;      // per thread
+    static constexpr int NE = NC;
+    struct Regs { u32x4 c[NC]; };
+    __amdgpu_buffer_rsrc_t rsrc;
+    uint32_t voff[NC];  // byte offset of the thread's cells at reduction row 0 (kOob: no such cell)
+
+    __device__ __forceinline__ void init(const CellParams &prm, int origin, int)
+    {
+        rsrc = make_rsrc_bytes(prm.t, 0, prm.bytes);
+#pragma unroll
+        for (int i = 0; i < NC; ++i) {
+            const int id = (int)threadIdx.x + kThreads * i;
+            // positions past the operand's extent read whatever lies there or zero: never stored
+            // 8 consecutive threads take the 8 planes of one position: 128 contiguous bytes
+            voff[i] = id < kCells ? 2u * (uint32_t)((origin + id / kDeepPlanes) * prm.col_stride + 8 * (id % kDeepPlanes)) : kOob;
+        }
+    }
+    // rows [k0 + 8*plane, +8) of each cell's position; a cell at or past k_end reads as zero (chunks are
+    // multiples of 16 rows and the reduction length a multiple of 8, so a cell is all inside or all outside)
+    __device__ __forceinline__ void fetch(int k0, int k_end, Regs &r) const
+    {
+#pragma unroll
+        for (int i = 0; i < NC; ++i) {
+            const int plane = ((int)threadIdx.x + kThreads * i) % kDeepPlanes;
+            const bool live = k0 + 8 * plane < k_end;
+            r.c[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)(live ? voff[i] : kOob), 2 * k0, 0);
+        }
+    }
+    template <int P>
+    __device__ __forceinline__ void stage(uint16_t *tile, const Regs &r) const
+    {
+#pragma unroll
+        for (int i = 0; i < NC; ++i) {
+            const int id = (int)threadIdx.x + kThreads * i;
+            if (id < kCells) *reinterpret_cast<u32x4 *>(tile + ((id % kDeepPlanes) * P + id / kDeepPlanes) * 8) = r.c[i];
+        }
+    }
+};
+
+struct RunParams {
+    const void *t;
+    uint32_t bytes;
+    int Ct, Ht, Wt;       // tensor channel count and plane size; the grid has Wt columns too
+    int plane_px;         // pixels of the grid (its rows x Wt)
+    FastDiv grid_pad;     // tile position -> (image, pixel): divisor = plane_px rounded up to 4
+    FastDiv grid_w;       // pixel -> (row, column): divisor = Wt
+    int add_h, add_w, dir;
+    FastDiv taps, taps_w;
+    int n_tap_h, n_tap_w;
+    int shift_thread, shift_row;
+};
+
+// MASKS = false: 1x1 unpadded layers, every element exists.
+template <int TD, bool MASKS>
+struct RunNLaneT : NoSetup {
+    static constexpr bool kBf16 = true;
+    static constexpr bool kVecRun = true;
+    static std::string name() { return std::string(MASKS ? "RunNLane<masks>" : "RunNLane") + "/bf16"; }
+    static constexpr int kGroups = TD / 4;                 // 4-pixel groups per 8-row plane
+    static constexpr int kTasks = kDeepPlanes * kGroups;   // (8 rows x 4 pixels) pieces of a step's tile
+    static_assert(kTasks <= kThreads, "one piece per thread");
+    static constexpr int NE = 8;
+    struct Regs { u32x2 d[8]; uint32_t tap[MASKS ? 8 : 1]; };
+    const RunParams *p;
+    __amdgpu_buffer_rsrc_t rsrc;
+    uint32_t voff;       // byte offset of the thread's first pixel (shifted resource)
+    uint32_t ok[MASKS ? 4 : 1];  // per pixel: bit t set = tap t inside the image
+    uint32_t inside;     // bit e set = pixel e of the thread exists (is not image padding, nor past the extent)
+    int grp, plane;
+    bool has;
+    bool edge_lo, edge_hi;  // wave-uniform: some lane's windows can reach past the tensor's start / end
+
+    __device__ __forceinline__ void init(const RunParams &prm, int origin, int extent)
+    {
+        p = &prm;
+        const int shift = prm.shift_thread + prm.shift_row;
+        rsrc = make_rsrc_bytes(prm.t, 2l * shift, prm.bytes + 2u * (uint32_t)shift);
+        const int tid = threadIdx.x;
+        has = kTasks == kThreads || tid < kTasks;
+        grp = tid % kGroups;
+        plane = (tid / kGroups) % kDeepPlanes;
+        const int j0 = origin + 4 * grp;
+        uint32_t n, px;
+        prm.grid_pad.divmod((uint32_t)j0, n, px);
+        voff = 2u * (uint32_t)((int)n * prm.Ct * prm.Ht * prm.Wt + (int)px + prm.add_h * prm.Wt + prm.add_w +
+                               prm.shift_thread);
+        inside = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const bool exists = j0 + e < extent && (int)px + e < prm.plane_px;
+            inside |= exists ? 1u << e : 0u;
+            if constexpr (MASKS) {
+                uint32_t okm = 0;
+                if (exists) {
+                    uint32_t a, b;
+                    prm.grid_w.divmod(px + e, a, b);
+                    const int hb = (int)a + prm.add_h, wb = (int)b + prm.add_w;
+                    uint32_t okw = 0;
+                    for (int q = 0; q < prm.n_tap_w; ++q)
+                        if ((unsigned)(wb + prm.dir * q) < (unsigned)prm.Wt) okw |= 1u << q;
+                    for (int r = 0; r < prm.n_tap_h; ++r)
+                        if ((unsigned)(hb + prm.dir * r) < (unsigned)prm.Ht) okm |= okw << (r * prm.n_tap_w);
+                }
+                ok[e] = okm;
+            }
+        }
+        // A thread's 4-pixel window of tap (r, s) starts (r, s) rows / columns away from its pixels: in
+        // the first channel of the first image it can begin before the tensor, in the last channel of
+        // the last image end behind it.  Such windows are fetched element by element (see fetch).
+        const int reach = prm.n_tap_h * prm.Wt + prm.n_tap_w + 4;
+        const int last_image = (int)(prm.bytes / 2u) / (prm.Ct * prm.Ht * prm.Wt) - 1;
+        edge_lo = __builtin_amdgcn_ballot_w64(has && n == 0 && (int)px < reach) != 0;
+        edge_hi = __builtin_amdgcn_ballot_w64(has && (int)n >= last_image && (int)px + reach > prm.Ht * prm.Wt) != 0;
+    }
+    // The tile of reduction rows [k0, k0 + 64): lane l decodes row k0 + l, every thread then picks up
+    // its 8 rows' offsets through the LDS crossbar and issues its 8 loads.
+    __device__ __forceinline__ void fetch(int k0, int k_end, Regs &r) const
+    {
+        const int kk = k0 + (int)(threadIdx.x & 63);
+        uint32_t c, tap, tr, ts;
+        p->taps.divmod((uint32_t)kk, c, tap);
+        p->taps_w.divmod(tap, tr, ts);
+        // rows past the end get an offset that pushes every address out of range: they read as zero
+        const uint32_t so_v = kk < k_end ? 2u * (uint32_t)(((int)c * p->Ht + p->dir * (int)tr) * p->Wt +
+                                                            p->dir * (int)ts + p->shift_row)
+                                         : kOob;
+        // rows of the first / last channel, in a wave that holds pixels near the tensor's start / end
+        const int n_taps = (int)p->taps.d;
+        const bool careful = (edge_lo && k0 < n_taps) || (edge_hi && k0 + kDeepBK > (p->Ct - 1) * n_taps);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int src = 4 * (8 * plane + i);
+            const uint32_t so = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)so_v);
+            uint32_t tp = 0;
+            if constexpr (MASKS) tp = r.tap[i] = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)tap);
+            if (!careful) {
+                r.d[i] = __builtin_amdgcn_raw_buffer_load_b64(rsrc, (int)(has ? voff + so : kOob), 0, 0);
+            } else {  // only elements that exist are dereferenced
+                uint32_t h[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    bool live = has && ((inside >> e) & 1u);
+                    if constexpr (MASKS) live = live && ((ok[e] >> tp) & 1u);
+                    h[e] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rsrc, (int)(live ? voff + so + 2u * e : kOob), 0, 0);
+                }
+                r.d[i].x = h[0] | (h[1] << 16);
+                r.d[i].y = h[2] | (h[3] << 16);
+            }
+        }
+    }
+    // 8 rows x 4 pixels -> 4 cells of 8 rows, border taps zeroed, each cell written in one piece into
+    // sub-plane e (stride SUB cells) for pixel e
+    template <int P, int SUB>
+    __device__ __forceinline__ void stage(uint16_t *tile, const Regs &r) const
+    {
+        uint32_t lo[8], hi[8];  // pixels (0, 1) and (2, 3) of each row
+        uint32_t pair01 = 0, pair23 = 0;
+        const bool few_taps = p->taps.d <= 16;  // wave-uniform
+        if constexpr (MASKS) {
+            pair01 = ok[0] | (ok[1] << 16);
+            pair23 = ok[2] | (ok[3] << 16);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            lo[i] = r.d[i].x;
+            hi[i] = r.d[i].y;
+            if constexpr (MASKS) {
+                if (few_taps) {
+                    // bits `tap` of the two pixels' masks at bit 0 and bit 16; times 0xFFFF spreads each
+                    // over its half of the word (no carry between the halves)
+                    lo[i] &= __umul24((pair01 >> r.tap[i]) & 0x00010001u, 0xFFFFu);
+                    hi[i] &= __umul24((pair23 >> r.tap[i]) & 0x00010001u, 0xFFFFu);
+                } else {
+                    const int k0 = __builtin_amdgcn_sbfe(ok[0], r.tap[i], 1), k1 = __builtin_amdgcn_sbfe(ok[1], r.tap[i], 1);
+                    const int k2 = __builtin_amdgcn_sbfe(ok[2], r.tap[i], 1), k3 = __builtin_amdgcn_sbfe(ok[3], r.tap[i], 1);
+                    lo[i] &= ((uint32_t)k0 & 0xFFFFu) | ((uint32_t)k1 & 0xFFFF0000u);
+                    hi[i] &= ((uint32_t)k2 & 0xFFFFu) | ((uint32_t)k3 & 0xFFFF0000u);
+                }
+            }
+        }
+        if (!has) return;
+        u32x4 c0, c1, c2, c3;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            // rows 2q and 2q+1 of each pixel side by side
+            c0[q] = __builtin_amdgcn_perm(lo[2 * q + 1], lo[2 * q], 0x05040100u);
+            c1[q] = __builtin_amdgcn_perm(lo[2 * q + 1], lo[2 * q], 0x07060302u);
+            c2[q] = __builtin_amdgcn_perm(hi[2 * q + 1], hi[2 * q], 0x05040100u);
+            c3[q] = __builtin_amdgcn_perm(hi[2 * q + 1], hi[2 * q], 0x07060302u);
+        }
+        u32x4 *dst = reinterpret_cast<u32x4 *>(tile + (plane * P + grp) * 8);
+        dst[0] = c0;
+        dst[SUB] = c1;
+        dst[2 * SUB] = c2;
+        dst[3 * SUB] = c3;
+    }
+};
+template <int TD> using RunNLane = RunNLaneT<TD, false>;
+template <int TD> using RunNLaneMasked = RunNLaneT<TD, true>;
+
+template <class L>
+__host__ __device__ constexpr auto vec_cells(int) -> decltype(L::kVecCells) { return L::kVecCells; }
+template <class L>
+__host__ __device__ constexpr bool vec_cells(...) { return false; }
+template <class L>
+__host__ __device__ constexpr auto vec_run(int) -> decltype(L::kVecRun) { return L::kVecRun; }
+template <class L>
+__host__ __device__ constexpr bool vec_run(...) { return false; }
+
+// B operand: RunNLaneT.  A operand: CellKLaneT, or any element-wise bf16 loader (load / erow / ecol).
+// k_chunk must be a multiple of kDeepBK.
+template <class T, class ALoader, class BLoader, class Epi, class AParams, class BParams>
+__global__ __launch_bounds__(kThreads) void gemm_kernel_bf16v(AParams pa, BParams pb, typename Epi::Params pe,
+                                                               int M, int N, int Kd, int k_chunk, int tiles_m,
+                                                               int tiles_n)
+{
+    typedef DeepTile<T> H;
+    constexpr bool kACells = vec_cells<ALoader>(0);
+    constexpr int KS = kDeepBK / kBK;  // 16-row sub-steps (one MFMA per 32x32 tile each)
+    __shared__ __attribute__((aligned(16))) uint16_t lds[2][H::HALFS];
+
+    const WorkItem wi = work_item<T>(Kd, k_chunk, tiles_m, tiles_n, 0);
+    const int m0 = wi.m0, n0 = wi.n0, k_begin = wi.k_begin, k_end = wi.k_end;
+    if constexpr (per_split<Epi>(0)) pe.out += (long)wi.split * pe.plane;
+
+    ALoader la;
+    BLoader lb;
+    la.init(pa, m0, M);
+    lb.init(pb, n0, N);
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm0 = (wave % T::WAVES_M) * (T::WM * 32);
+    const int wn0 = (wave / T::WAVES_M) * (T::WN * 32);
+    const int l32 = lane & 31, lhi = lane >> 5;
+
+    f32x16 acc[T::WM][T::WN];
+#pragma unroll
+    for (int i = 0; i < T::WM; ++i)
+#pragma unroll
+        for (int j = 0; j < T::WN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    constexpr int NA = ALoader::NE, NM = T::WM * T::WN;
+    struct ElemRegs { float r[KS][kACells ? 1 : NA]; };
+    typename std::conditional<kACells, typename ALoader::Regs, ElemRegs>::type ra;
+    typename BLoader::Regs rb;
+
+    auto load_a = [&](int k0) {
+        if constexpr (kACells) {
+            la.fetch(k0, k_end, ra);
+        } else {
+#pragma unroll
+            for (int u = 0; u < KS; ++u) {
+                la.prep(k0 + u * kBK, k_end, lb);
+#pragma unroll
+                for (int i = 0; i < NA; ++i) la.load(i, ra.r[u]);
+            }
+        }
+    };
+    auto stage_a = [&](uint16_t *buf) {
+        if constexpr (kACells) {
+            la.template stage<H::PA>(buf, ra);
+        } else {
+#pragma unroll
+            for (int u = 0; u < KS; ++u)
+#pragma unroll
+                for (int i = 0; i < NA; ++i) {
+                    const int row = u * kBK + la.erow(i), col = la.ecol(i);
+                    buf[((row >> 3) * H::PA + col) * 8 + (row & 7)] = (uint16_t)(__float_as_uint(ra.r[u][i]) >> 16);
+                }
+        }
+    };
+
+    // two tiles deep on one register set, as in the kernels above
+    load_a(k_begin);
+    lb.fetch(k_begin, k_end, rb);
+    stage_a(lds[0]);
+    lb.template stage<H::PB, H::SUB>(lds[0] + H::A_HALFS, rb);
+    load_a(k_begin + kDeepBK);
+    lb.fetch(k_begin + kDeepBK, k_end, rb);
+    __syncthreads();
+
+    int buf = 0;
+    for (int k0 = k_begin; k0 < k_end; k0 += kDeepBK) {
+        const uint16_t *cur = lds[buf];
+        uint16_t *nxt = lds[buf ^ 1];
+        bf16x8 a[2][T::WM], b[2][T::WN];
+        auto read_ops = [&](int u, int slot) {  // the operands of sub-step u: planes 2u (lanes 0-31) and 2u+1
+#pragma unroll
+            for (int i = 0; i < T::WM; ++i)
+                a[slot][i] = __builtin_bit_cast(
+                    bf16x8, *reinterpret_cast<const u32x4 *>(cur + ((2 * u + lhi) * H::PA + wm0 + 32 * i + l32) * 8));
+#pragma unroll
+            for (int j = 0; j < T::WN; ++j)
+                b[slot][j] = __builtin_bit_cast(
+                    bf16x8, *reinterpret_cast<const u32x4 *>(cur + H::A_HALFS + ((2 * u + lhi) * H::PB + H::b_slot(wn0 + j * 32 + l32)) * 8));
+        };
+        read_ops(0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < KS; ++u) {
+            const int slot = u & 1;
+#pragma unroll
+            for (int m = 0; m < NM; ++m) {
+                const int mi = m / T::WN, mj = m % T::WN;
+                acc[mi][mj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[slot][mi], b[slot][mj], acc[mi][mj], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (m == 0 && u + 1 < KS) read_ops(u + 1, slot ^ 1);
+                // the step's memory work, dealt out behind the MFMAs: tile s+1 registers -> LDS, then
+                // reloaded with tile s+2
+                if (u == 0 && m == 1 % NM) stage_a(nxt);
+                if (u == 1 && m == 0) load_a(k0 + 2 * kDeepBK);
+                if (u == 2 && m == 0) lb.template stage<H::PB, H::SUB>(nxt + H::A_HALFS, rb);
+                if (u == 3 && m == 0) lb.fetch(k0 + 2 * kDeepBK, k_end, rb);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        __syncthreads();
+        buf ^= 1;
+    }
+
+    write_tile<T, Epi, false>(pe, acc, M, N, m0, n0, wm0, wn0, l32, lhi, false);
+}
+
 // Zero-fills the outputs of the last `tail_tiles` tiles through the epilogue's own index mapping.
 template <class T, class Epi>
 __global__ __launch_bounds__(kThreads) void zero_tiles_kernel(typename Epi::Params pe, int M, int N, int tiles_m,
@@ -1541,7 +1921,7 @@ __global__ __launch_bounds__(kThreads) void zero_tiles_kernel(typename Epi::Para
     const int col = n0 + (int)threadIdx.x % T::BN;  // lanes along the columns: contiguous stores
     if (col >= N) return;
     Epi epi;
-    epi.prep(pe, col);
+    if (!epi.prep(pe, col)) return;
     for (int r = threadIdx.x / T::BN; r < T::BM; r += kThreads / T::BN) {
         const int row = m0 + r;
         if (row < M) epi.store(pe, row, 0.f);

@@ -33,13 +33,18 @@ template <class T, template <int> class AL, template <int> class BL, class Epi, 
 hipError_t launch_tile(const AP &pa, const BP &pb, const typename Epi::Params &pe, const GemmShape &g,
                        hipStream_t s)
 {
+    constexpr bool kVecLoads = vec_run<BL<T::BN>>(0);  // the bf16 kernel with vector operand loads
     // both operands bf16 tensors: the kernel on the bf16 matrix pipe (single GEMMs only)
     constexpr bool kBf16Mfma = AL<T::BM>::kBf16 && BL<T::BN>::kBf16;
     if (kBf16Mfma && g.batch != 1) return hipErrorInvalidValue;
     const int tiles_m = (g.M + T::BM - 1) / T::BM, tiles_n = (g.N + T::BN - 1) / T::BN;
     if (tiles_m <= 0 || tiles_n <= 0) return hipSuccess;
     int k_chunk;
-    const int splits = effective_splits(g.Kd, g.splits, k_chunk);
+    int splits = effective_splits(g.Kd, g.splits, k_chunk);
+    if (kVecLoads) {  // that kernel's steps are kDeepBK rows
+        k_chunk = (k_chunk + kDeepBK - 1) / kDeepBK * kDeepBK;
+        splits = g.Kd > 0 ? (g.Kd + k_chunk - 1) / k_chunk : 1;
+    }
     // Tail spreading (see TailSplit): when an unsplit GEMM's tile count is not a multiple of the CU
     // count, the reduction steps of the tiles beyond the last multiple are dealt out evenly to (up to)
     // one workgroup per CU, so that every CU gets the same work.
@@ -63,7 +68,7 @@ hipError_t launch_tile(const AP &pa, const BP &pb, const typename Epi::Params &p
     dim3 grid(gx, (unsigned)splits, (unsigned)g.batch);
     if (LaunchLog *log = launch_log()) {
         if (tail.tiles) log->add("zero_tiles_kernel");
-        log->add(std::string(kBf16Mfma ? "gemm_kernel_bf16<Tile<" : "gemm_kernel<Tile<") + std::to_string(T::BM) + "x" + std::to_string(T::BN) + ">," +
+        log->add(std::string(kVecLoads ? "gemm_kernel_bf16v<Tile<" : kBf16Mfma ? "gemm_kernel_bf16<Tile<" : "gemm_kernel<Tile<") + std::to_string(T::BM) + "x" + std::to_string(T::BN) + ">," +
                  AL<T::BM>::name() + "," + BL<T::BN>::name() + "," + Epi::name() + "> tiles=" +
                  std::to_string(tiles_m * tiles_n) + " splits=" + std::to_string(splits) + " batch=" +
                  std::to_string(g.batch) + " M=" + std::to_string(g.M) + " N=" + std::to_string(g.N) + " K=" +
@@ -76,7 +81,10 @@ hipError_t launch_tile(const AP &pa, const BP &pb, const typename Epi::Params &p
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    if constexpr (kBf16Mfma)
+    if constexpr (kVecLoads)
+        gemm_kernel_bf16v<T, AL<T::BM>, BL<T::BN>, Epi, AP, BP><<<grid, kThreads, 0, s>>>(
+            pa, pb, pe, g.M, g.N, g.Kd, k_chunk, tiles_m, tiles_n);
+    else if constexpr (kBf16Mfma)
         gemm_kernel_bf16<T, AL<T::BM>, BL<T::BN>, Epi, AP, BP><<<grid, kThreads, 0, s>>>(
             pa, pb, pe, g.M, g.N, g.Kd, k_chunk, tiles_m, tiles_n);
     else
