@@ -107,16 +107,19 @@ static hipError_t implicit_fwd_bf16_vec(const Dims &d, int b, const void *x, con
     EpiNCHWParams pe{};
     pe.out = y; pe.grid_hw = pb.grid_pad; pe.grid_w = pb.grid_w;
     pe.M = d.K; pe.HWo = px; pe.Wo = d.Q; pe.h0 = 0; pe.hs = 1; pe.w0 = 0; pe.ws = 1; pe.cols = px;
-    const bool plain = d.R * d.S == 1 && d.ph == 0 && d.pw == 0;  // every element exists: no border masks
+    // 0: every element exists (no border masks); 1: masks, at most 16 taps; 2: masks, more taps
+    const int mode = d.R * d.S == 1 && d.ph == 0 && d.pw == 0 ? 0 : d.R * d.S <= 16 ? 1 : 2;
     if (d.crs() % 8 == 0) {  // filter rows are whole 16-byte cells
         CellParams pa{w, wbytes(d), d.crs()};
-        return plain ? launch_gemm<CellKLaneT, RunNLane, EpiNCHWT<bf16>, true>(pa, pb, pe, g, s)
-                     : launch_gemm<CellKLaneT, RunNLaneMasked, EpiNCHWT<bf16>, true>(pa, pb, pe, g, s);
+        if (mode == 0) return launch_gemm<CellKLaneT, RunNLane, EpiNCHWT<bf16>, true>(pa, pb, pe, g, s);
+        if (mode == 1) return launch_gemm<CellKLaneT, RunNLaneMasked, EpiNCHWT<bf16>, true>(pa, pb, pe, g, s);
+        return launch_gemm<CellKLaneT, RunNLaneMaskedBig, EpiNCHWT<bf16>, true>(pa, pb, pe, g, s);
     }
     KLaneParams pa{};
     pa.t = w; pa.bytes = wbytes(d); pa.row_stride = 1; pa.col_stride = d.crs();
-    return plain ? launch_gemm<Loaders<bf16>::KLane0, RunNLane, EpiNCHWT<bf16>, true>(pa, pb, pe, g, s)
-                 : launch_gemm<Loaders<bf16>::KLane0, RunNLaneMasked, EpiNCHWT<bf16>, true>(pa, pb, pe, g, s);
+    if (mode == 0) return launch_gemm<Loaders<bf16>::KLane0, RunNLane, EpiNCHWT<bf16>, true>(pa, pb, pe, g, s);
+    if (mode == 1) return launch_gemm<Loaders<bf16>::KLane0, RunNLaneMasked, EpiNCHWT<bf16>, true>(pa, pb, pe, g, s);
+    return launch_gemm<Loaders<bf16>::KLane0, RunNLaneMaskedBig, EpiNCHWT<bf16>, true>(pa, pb, pe, g, s);
 }
 
 template <class E>
@@ -257,7 +260,7 @@ static hipError_t implicit_bwd_data_bf16_vec(const Dims &d, int b, const void *d
         return plain ? launch_gemm<L::template FilterNLane, RunNLane, EpiNCHWT<bf16>, false>(pa, pb, pe, g, s)
                      : launch_gemm<L::template FilterNLane, RunNLaneMasked, EpiNCHWT<bf16>, false>(pa, pb, pe, g, s);
     return plain ? launch_gemm<L::template FilterKLane, RunNLane, EpiNCHWT<bf16>, true>(pa, pb, pe, g, s)
-                 : launch_gemm<L::template FilterKLane, RunNLaneMasked, EpiNCHWT<bf16>, true>(pa, pb, pe, g, s);
+                 : launch_gemm<L::template FilterKLane, RunNLaneMaskedBig, EpiNCHWT<bf16>, true>(pa, pb, pe, g, s);
 }
 
 // Stride phases: input pixels h with (h + ph) % sh == a are reached only by filter rows

@@ -1636,12 +1636,14 @@ struct RunParams {
     int shift_thread, shift_row;
 };
 
-// MASKS = false: 1x1 unpadded layers, every element exists.
-template <int TD, bool MASKS>
+// MODE 0: 1x1 unpadded layers, every element exists.  MODE 1: border masks, filters of at most 16
+// taps.  MODE 2: border masks, up to 31 taps.
+template <int TD, int MODE>
 struct RunNLaneT : NoSetup {
+    static constexpr bool MASKS = MODE != 0;
     static constexpr bool kBf16 = true;
     static constexpr bool kVecRun = true;
-    static std::string name() { return std::string(MASKS ? "RunNLane<masks>" : "RunNLane") + "/bf16"; }
+    static std::string name() { return std::string(MODE == 0 ? "RunNLane" : MODE == 1 ? "RunNLane<masks>" : "RunNLane<masks,taps>16>") + "/bf16"; }
     static constexpr int kGroups = TD / 4;                 // 4-pixel groups per 8-row plane
     static constexpr int kTasks = kDeepPlanes * kGroups;   // (8 rows x 4 pixels) pieces of a step's tile
     static_assert(kTasks <= kThreads, "one piece per thread");
@@ -1713,21 +1715,26 @@ struct RunNLaneT : NoSetup {
         // rows of the first / last channel, in a wave that holds pixels near the tensor's start / end
         const int n_taps = (int)p->taps.d;
         const bool careful = (edge_lo && k0 < n_taps) || (edge_hi && k0 + kDeepBK > (p->Ct - 1) * n_taps);
+        uint32_t off[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int src = 4 * (8 * plane + i);
-            const uint32_t so = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)so_v);
-            uint32_t tp = 0;
-            if constexpr (MASKS) tp = r.tap[i] = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)tap);
-            if (!careful) {
-                r.d[i] = __builtin_amdgcn_raw_buffer_load_b64(rsrc, (int)(has ? voff + so : kOob), 0, 0);
-            } else {  // only elements that exist are dereferenced
+            off[i] = voff + (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)so_v);
+            if constexpr (kTasks != kThreads) off[i] = has ? off[i] : kOob;
+            if constexpr (MASKS) r.tap[i] = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)tap);
+        }
+        if (__builtin_expect(!careful, 1)) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) r.d[i] = __builtin_amdgcn_raw_buffer_load_b64(rsrc, (int)off[i], 0, 0);
+        } else {  // only elements that exist are dereferenced (unrolled: registers cannot be indexed at run time)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
                 uint32_t h[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     bool live = has && ((inside >> e) & 1u);
-                    if constexpr (MASKS) live = live && ((ok[e] >> tp) & 1u);
-                    h[e] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rsrc, (int)(live ? voff + so + 2u * e : kOob), 0, 0);
+                    if constexpr (MASKS) live = live && ((ok[e] >> r.tap[i]) & 1u);
+                    h[e] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rsrc, (int)(live ? off[i] + 2u * e : kOob), 0, 0);
                 }
                 r.d[i].x = h[0] | (h[1] << 16);
                 r.d[i].y = h[2] | (h[3] << 16);
@@ -1741,7 +1748,7 @@ struct RunNLaneT : NoSetup {
     {
         uint32_t lo[8], hi[8];  // pixels (0, 1) and (2, 3) of each row
         uint32_t pair01 = 0, pair23 = 0;
-        const bool few_taps = p->taps.d <= 16;  // wave-uniform
+        constexpr bool few_taps = MODE == 1;
         if constexpr (MASKS) {
             pair01 = ok[0] | (ok[1] << 16);
             pair23 = ok[2] | (ok[3] << 16);
@@ -1751,7 +1758,7 @@ struct RunNLaneT : NoSetup {
             lo[i] = r.d[i].x;
             hi[i] = r.d[i].y;
             if constexpr (MASKS) {
-                if (few_taps) {
+                if constexpr (few_taps) {
                     // bits `tap` of the two pixels' masks at bit 0 and bit 16; times 0xFFFF spreads each
                     // over its half of the word (no carry between the halves)
                     lo[i] &= __umul24((pair01 >> r.tap[i]) & 0x00010001u, 0xFFFFu);
@@ -1781,8 +1788,9 @@ struct RunNLaneT : NoSetup {
         dst[3 * SUB] = c3;
     }
 };
-template <int TD> using RunNLane = RunNLaneT<TD, false>;
-template <int TD> using RunNLaneMasked = RunNLaneT<TD, true>;
+template <int TD> using RunNLane = RunNLaneT<TD, 0>;
+template <int TD> using RunNLaneMasked = RunNLaneT<TD, 1>;
+template <int TD> using RunNLaneMaskedBig = RunNLaneT<TD, 2>;
 
 template <class L>
 __host__ __device__ constexpr auto vec_cells(int) -> decltype(L::kVecCells) { return L::kVecCells; }
@@ -1830,10 +1838,14 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel_bf16v(AParams pa, BParam
 
     constexpr int NA = ALoader::NE, NM = T::WM * T::WN;
     struct ElemRegs { float r[KS][kACells ? 1 : NA]; };
-    typename std::conditional<kACells, typename ALoader::Regs, ElemRegs>::type ra;
-    typename BLoader::Regs rb;
+    typedef typename std::conditional<kACells, typename ALoader::Regs, ElemRegs>::type ARegs;
+    typedef typename BLoader::Regs BRegs;
+    // two register sets: global loads get two whole steps to land (a step of 16 bf16 MFMAs is far
+    // shorter than the memory latency, and only two of these workgroups fit a CU)
+    ARegs ra0, ra1;
+    BRegs rb0, rb1;
 
-    auto load_a = [&](int k0) {
+    auto load_a = [&](int k0, ARegs &ra) {
         if constexpr (kACells) {
             la.fetch(k0, k_end, ra);
         } else {
@@ -1845,7 +1857,7 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel_bf16v(AParams pa, BParam
             }
         }
     };
-    auto stage_a = [&](uint16_t *buf) {
+    auto stage_a = [&](uint16_t *buf, const ARegs &ra) {
         if constexpr (kACells) {
             la.template stage<H::PA>(buf, ra);
         } else {
@@ -1859,19 +1871,20 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel_bf16v(AParams pa, BParam
         }
     };
 
-    // two tiles deep on one register set, as in the kernels above
-    load_a(k_begin);
-    lb.fetch(k_begin, k_end, rb);
-    stage_a(lds[0]);
-    lb.template stage<H::PB, H::SUB>(lds[0] + H::A_HALFS, rb);
-    load_a(k_begin + kDeepBK);
-    lb.fetch(k_begin + kDeepBK, k_end, rb);
+    // tile 0 -> LDS; tile 1 -> set 1; tile 2 -> set 0
+    load_a(k_begin, ra0);
+    lb.fetch(k_begin, k_end, rb0);
+    load_a(k_begin + kDeepBK, ra1);
+    lb.fetch(k_begin + kDeepBK, k_end, rb1);
+    stage_a(lds[0], ra0);
+    lb.template stage<H::PB, H::SUB>(lds[0] + H::A_HALFS, rb0);
+    load_a(k_begin + 2 * kDeepBK, ra0);
+    lb.fetch(k_begin + 2 * kDeepBK, k_end, rb0);
     __syncthreads();
 
-    int buf = 0;
-    for (int k0 = k_begin; k0 < k_end; k0 += kDeepBK) {
-        const uint16_t *cur = lds[buf];
-        uint16_t *nxt = lds[buf ^ 1];
+    // One step: MFMAs on tile s from `cur`; the register set holding tile s+1 goes to `nxt` and is
+    // reloaded with tile s+3.  The memory work is dealt out behind the MFMAs.
+    auto step = [&](const uint16_t *cur, uint16_t *nxt, ARegs &ra, BRegs &rb, int k0) {
         bf16x8 a[2][T::WM], b[2][T::WN];
         auto read_ops = [&](int u, int slot) {  // the operands of sub-step u: planes 2u (lanes 0-31) and 2u+1
 #pragma unroll
@@ -1894,17 +1907,18 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel_bf16v(AParams pa, BParam
                 acc[mi][mj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[slot][mi], b[slot][mj], acc[mi][mj], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
                 if (m == 0 && u + 1 < KS) read_ops(u + 1, slot ^ 1);
-                // the step's memory work, dealt out behind the MFMAs: tile s+1 registers -> LDS, then
-                // reloaded with tile s+2
-                if (u == 0 && m == 1 % NM) stage_a(nxt);
-                if (u == 1 && m == 0) load_a(k0 + 2 * kDeepBK);
+                if (u == 0 && m == 1 % NM) stage_a(nxt, ra);
+                if (u == 1 && m == 0) load_a(k0 + 3 * kDeepBK, ra);
                 if (u == 2 && m == 0) lb.template stage<H::PB, H::SUB>(nxt + H::A_HALFS, rb);
-                if (u == 3 && m == 0) lb.fetch(k0 + 2 * kDeepBK, k_end, rb);
+                if (u == 3 && m == 0) lb.fetch(k0 + 3 * kDeepBK, k_end, rb);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
         __syncthreads();
-        buf ^= 1;
+    };
+    for (int k0 = k_begin; k0 < k_end; k0 += 2 * kDeepBK) {
+        step(lds[0], lds[1], ra1, rb1, k0);
+        if (k0 + kDeepBK < k_end) step(lds[1], lds[0], ra0, rb0, k0 + kDeepBK);
     }
 
     write_tile<T, Epi, false>(pe, acc, M, N, m0, n0, wm0, wn0, l32, lhi, false);
