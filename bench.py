@@ -58,7 +58,7 @@ MEASURED_TRAFFIC_BYTES_PER_FLOP = {
     "gemm_kernel<Tile<64x128>,PhaseFilterKLane,GatherNLane<taps<=31>,EpiPhases>": 451.9e6 / 52.71e9,
 }
 
-ALGO_IDS = {"implicit": 0, "im2col": 1, "winograd": 2, "winograd4": 3, "fft": 4}
+ALGO_IDS = {"implicit": 0, "im2col": 1, "winograd": 2, "winograd4": 3, "fft": 4, "winograd-fused": 5}
 
 # name -> (description, layer table, batch, per-layer limit or total budget, "wr" | "wd", default policy)
 WORKLOADS = {
@@ -240,6 +240,8 @@ def gemm_flops(text):
     total = 0.0
     for part in text.split(";"):
         part = part.strip()
+        if part.startswith("wino_fused_kernel"):
+            total += float(part.split("gemm_flops=")[1].split()[0])
         if not part.startswith("gemm_kernel"):
             continue
         f = dict(kv.split("=") for kv in part.split("> ")[-1].split() if "=" in kv)
@@ -409,6 +411,10 @@ def micro_main(args):
         for valu in (0, 2, 4, 8):
             times, flops = timed(lambda: ucd.ucd_mfma_probe(valu, blocks, iters, scratch))
             out[f"tflops_with_{valu}_valu_per_mfma"] = round(flops / min(times) / 1e9, 1)
+        # 16 accumulator tiles per wave (256 registers): one wave per SIMD, as in the fused Winograd kernel
+        for valu in (0, 2, 4):
+            times, flops = timed(lambda: ucd.ucd_mfma_probe(100 + valu, blocks, iters, scratch))
+            out[f"one_wave_per_simd_tflops_with_{valu}_valu_per_mfma"] = round(flops / min(times) / 1e9, 1)
         print(json.dumps(out))
         return
     if args.copy_mib:

@@ -77,7 +77,7 @@ bool fits_32bit(const ucd_layer_t *L, int b)
 inline int wino_tile(int algo) { return algo == UCD_ALGO_WINOGRAD4 ? 4 : 2; }
 inline bool is_winograd(int algo) { return algo == UCD_ALGO_WINOGRAD || algo == UCD_ALGO_WINOGRAD4; }
 // algorithms that keep a transformed filter at the head of the workspace
-inline bool keeps_filter(int algo) { return is_winograd(algo) || algo == UCD_ALGO_FFT; }
+inline bool keeps_filter(int algo) { return is_winograd(algo) || algo == UCD_ALGO_FFT || algo == UCD_ALGO_WINOGRAD_FUSED; }
 
 size_t ws_size(const ucd_layer_t *L, int op, int algo, int b)
 {
@@ -102,6 +102,9 @@ size_t ws_size(const ucd_layer_t *L, int op, int algo, int b)
         if (winograd_ws_bytes(d, op, b, mt) / (4 * planes) > (size_t)kMaxOperandFloats) return UCD_WS_NA;
         return winograd_ws_bytes(d, op, b, mt);
     }
+    case UCD_ALGO_WINOGRAD_FUSED:
+        if (op == UCD_BWD_FILTER || !winograd_applies(d, op)) return UCD_WS_NA;
+        return winograd_fused_ws_bytes(d, op);
     case UCD_ALGO_FFT:
         if (!fft_applies(d, op)) return UCD_WS_NA;
         // every frequency plane is one GEMM operand
@@ -140,6 +143,9 @@ int run_micro(const ucd_layer_t *L, int op, int algo, int b, const void *a, cons
         if (op == UCD_FWD) e = winograd_fwd(d, b, a, bsrc, out, ws, filter_ready, wino_tile(algo), s);
         else if (op == UCD_BWD_DATA) e = winograd_bwd_data(d, b, a, bsrc, out, ws, filter_ready, wino_tile(algo), s);
         else e = winograd_bwd_filter(d, b, a, bsrc, (float *)out, beta, ws, wino_tile(algo), s);
+        break;
+    case UCD_ALGO_WINOGRAD_FUSED:
+        if (op != UCD_BWD_FILTER) e = winograd_fused(d, op, b, a, bsrc, out, ws, filter_ready, s);
         break;
     case UCD_ALGO_FFT:
         if (op == UCD_FWD) e = fft_fwd(d, b, a, bsrc, out, ws, filter_ready, s);

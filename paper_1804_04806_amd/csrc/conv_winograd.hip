@@ -323,6 +323,269 @@ static hipError_t winograd_run(const Dims &d, int op, int b, const void *in, con
     return hipGetLastError();
 }
 
+// ---- F(2x2,3x3) with both data transforms fused into the GEMM kernel --------------------------------
+// The only workspace is the transformed filter U (64*Ci*Mo4 bytes, whatever the micro-batch), so the
+// whole mini-batch can run in one launch under a small workspace limit.  A workgroup owns a block of
+// 64 output channels x 64 tiles for all 16 transform points: each of its four waves keeps 16
+// accumulator tiles of 32 channels x 32 tiles (256 registers, one wave per SIMD).  Per step of 4
+// input channels every thread fetches the 4x4 input patch of one (tile, channel), transforms it in
+// registers (32 additions) and writes its 16 values to LDS; U's slice for the step is copied from
+// the workspace to LDS; then 32 MFMAs per wave (16 points x 2 channel pairs).  After the last
+// channel the 16 accumulators of an (output channel, tile) are combined by A^T . A in registers and
+// the 2x2 outputs stored.  Global loads run two steps ahead of the MFMAs (one register set, two LDS
+// buffers), and the step's memory and transform work is dealt out behind individual MFMAs.
+#ifndef UCD_FUSED_CHANNELS
+#define UCD_FUSED_CHANNELS 8
+#endif
+constexpr int kFuK = 64, kFuT = 64, kFuC = UCD_FUSED_CHANNELS;  // block: channels x tiles; input channels per step
+constexpr int kFuNP = kFuC / 4;   // input patches per thread and step (channel = wave + 4h)
+constexpr int kFuNU = kFuC;       // float4 pieces of the step's U slice per thread
+constexpr int kFuPairs = kFuC / 2;
+
+struct FusedParams {
+    const void *in;
+    const float *U;
+    void *out;
+    uint32_t in_bytes, u_bytes;
+    WinoGeom g;
+    FastDiv divT, divTW;
+    int n_tiles, k_blocks;
+};
+
+template <class E>
+__global__ __launch_bounds__(256) void wino_fused_kernel(FusedParams p)
+{
+    constexpr uint32_t EB = Elem<E>::kBytes;
+    __shared__ __attribute__((aligned(16))) float Us[2][16][kFuC][kFuK];
+    __shared__ __attribute__((aligned(16))) float Vs[2][16][kFuC][kFuT];
+    const WinoGeom &g = p.g;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, lhi = lane >> 5;
+    const int wk = wave & 1, wt = wave >> 1;
+
+    // consecutive work items of an XCD share a tile block (the input patches) and differ in the
+    // channel block
+    const uint32_t v = xcd_order(blockIdx.x, gridDim.x);
+    const int kb = (int)(v % (uint32_t)p.k_blocks), tb = (int)(v / (uint32_t)p.k_blocks);
+    const int k0 = kb * kFuK, t0 = tb * kFuT;
+
+    const __amdgpu_buffer_rsrc_t rin = make_rsrc_bytes(p.in, 0, p.in_bytes);
+    const __amdgpu_buffer_rsrc_t ru = make_rsrc_bytes(p.U, 0, p.u_bytes);
+
+    // producer role: the 4x4 patch of tile `lane` of the block, for channels wave, wave + 4, ... of the step
+    uint32_t voff[16];
+    {
+        const int j = t0 + lane;
+        uint32_t n = 0, t, th = 0, tw = 0;
+        const bool live = j < p.n_tiles;
+        if (live) {
+            p.divT.divmod((uint32_t)j, n, t);
+            p.divTW.divmod(t, th, tw);
+        }
+        const int h0 = 2 * (int)th - g.pad_h, w0 = 2 * (int)tw - g.pad_w;
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const int h = h0 + r, w = w0 + c;
+                const bool ok = live && (unsigned)h < (unsigned)g.Hi && (unsigned)w < (unsigned)g.Wi;
+                voff[4 * r + c] = ok ? EB * (uint32_t)(((int)n * g.Ci * g.Hi + h) * g.Wi + w) : kOob;
+            }
+    }
+    // U slice of a step: 16 points x kFuC channels x 64 output channels, as float4: piece id = tid + 256*i
+    // -> row = id / 16 = point * kFuC + channel, 4 output channels from 4 * (id % 16)
+    uint32_t uoff[kFuNU];
+#pragma unroll
+    for (int i = 0; i < kFuNU; ++i) {
+        const int id = tid + 256 * i, row = id >> 4, q = id & 15;
+        const int xi = row / kFuC, c = row % kFuC, k = k0 + 4 * q;
+        uoff[i] = k < g.Mo4 ? 4u * (uint32_t)((xi * g.Ci + c) * g.Mo4 + k) : kOob;
+    }
+
+    float d[kFuNP][16];  // the thread's input patches of the step after the one in LDS
+    f32x4 uq[kFuNU];     // and its share of that step's U slice
+    // a channel past the last one gets a scalar offset that pushes every address out of range
+    auto fetch_pixel = [&](int c0, int h, int i) {
+        const int c = c0 + wave + 4 * h;
+        const uint32_t so = c < g.Ci ? EB * (uint32_t)(c * g.Hi * g.Wi) : kOob;
+        d[h][i] = Elem<E>::load(rin, voff[i], so);
+    };
+    auto fetch_patch = [&](int c0, int h) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) fetch_pixel(c0, h, i);
+    };
+    auto fetch_u = [&](int c0, int i) {
+        const int c_in_step = ((tid + 256 * i) >> 4) % kFuC;
+        uq[i] = buf_load4(ru, c0 + c_in_step < g.Ci ? uoff[i] + 4u * (uint32_t)(c0 * g.Mo4) : kOob);
+    };
+    // B^T d B of patch h into LDS buffer `buf`: points 4r .. 4r+3 from row r of B^T d
+    auto store_v = [&](int buf, int h) {
+        float tr[16];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const float a0 = d[h][c], a1 = d[h][4 + c], a2 = d[h][8 + c], a3 = d[h][12 + c];
+            tr[c] = a0 - a2;
+            tr[4 + c] = a1 + a2;
+            tr[8 + c] = a2 - a1;
+            tr[12 + c] = a1 - a3;
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float a0 = tr[4 * r], a1 = tr[4 * r + 1], a2 = tr[4 * r + 2], a3 = tr[4 * r + 3];
+            Vs[buf][4 * r + 0][wave + 4 * h][lane] = a0 - a2;
+            Vs[buf][4 * r + 1][wave + 4 * h][lane] = a1 + a2;
+            Vs[buf][4 * r + 2][wave + 4 * h][lane] = a2 - a1;
+            Vs[buf][4 * r + 3][wave + 4 * h][lane] = a1 - a3;
+        }
+    };
+    auto store_u = [&](int buf, int i) {
+        const int id = tid + 256 * i, row = id >> 4, q = id & 15;
+        *reinterpret_cast<f32x4 *>(&Us[buf][row / kFuC][row % kFuC][4 * q]) = uq[i];
+    };
+
+    f32x16 acc[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+
+#pragma unroll
+    for (int h = 0; h < kFuNP; ++h) fetch_patch(0, h);
+#pragma unroll
+    for (int i = 0; i < kFuNU; ++i) fetch_u(0, i);
+#pragma unroll
+    for (int h = 0; h < kFuNP; ++h) store_v(0, h);
+#pragma unroll
+    for (int i = 0; i < kFuNU; ++i) store_u(0, i);
+#pragma unroll
+    for (int h = 0; h < kFuNP; ++h) fetch_patch(kFuC, h);
+#pragma unroll
+    for (int i = 0; i < kFuNU; ++i) fetch_u(kFuC, i);
+    __syncthreads();
+
+    int buf = 0;
+    for (int c0 = 0; c0 < g.Ci; c0 += kFuC) {
+        const float *ua = &Us[buf][0][lhi][wk * 32 + l32];
+        const float *vb = &Vs[buf][0][lhi][wt * 32 + l32];
+        // operands of (point xi, channel pair q): rows 2q + lhi of the point's slab; a point's operands
+        // are read while the previous point's MFMAs run
+        float a[2][kFuPairs], b[2][kFuPairs];
+        auto read_ops = [&](int xi) {
+#pragma unroll
+            for (int q = 0; q < kFuPairs; ++q) {
+                a[xi & 1][q] = ua[(xi * kFuC + 2 * q) * kFuK];
+                b[xi & 1][q] = vb[(xi * kFuC + 2 * q) * kFuT];
+            }
+        };
+        read_ops(0);
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_setprio(UCD_MFMA_PRIO);
+        constexpr int kMfmas = 16 * kFuPairs;
+#pragma unroll
+        for (int m = 0; m < kMfmas; ++m) {
+            const int xi = m / kFuPairs, q = m % kFuPairs;
+            acc[xi] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[xi & 1][q], b[xi & 1][q], acc[xi], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (q == 0 && xi + 1 < 16) read_ops(xi + 1);
+            // The registers hold step c0 + kFuC as loaded: it is transformed into the other LDS buffer
+            // and every register reloaded, as soon as it is free, with step c0 + 2 kFuC.  One piece of
+            // that work behind each MFMA, and never more than one global load: a burst of loads blocks
+            // the wave at the memory pipeline's queue, and with one wave per SIMD nothing else would
+            // feed the matrix pipe meanwhile.
+            constexpr int kPatchSlots = 17;  // 1 transform + 16 loads
+            if (m >= 1 && m < 1 + kPatchSlots * kFuNP) {
+                const int h = (m - 1) / kPatchSlots, i = (m - 1) % kPatchSlots;
+                if (i == 0) store_v(buf ^ 1, h);
+                else fetch_pixel(c0 + 2 * kFuC, h, i - 1);
+            }
+            constexpr int kUStart = 1 + kPatchSlots * kFuNP;
+            if (m >= kUStart && m < kUStart + 2 * kFuNU) {
+                const int i = (m - kUStart) / 2;
+                if ((m - kUStart) % 2 == 0) store_u(buf ^ 1, i);
+                else fetch_u(c0 + 2 * kFuC, i);
+            }
+            static_assert(kUStart + 2 * kFuNU <= 16 * kFuPairs, "the step's work fits behind its MFMAs");
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        __builtin_amdgcn_s_setprio(0);
+        __syncthreads();
+        buf ^= 1;
+    }
+
+    // output transform and store: lane = tile (column l32 of the wave's 32), register e = channel row
+    const int j = t0 + wt * 32 + l32;
+    if (j >= p.n_tiles) return;
+    uint32_t n, t, th, tw;
+    p.divT.divmod((uint32_t)j, n, t);
+    p.divTW.divmod(t, th, tw);
+    const int h0 = 2 * (int)th, w0 = 2 * (int)tw;
+    const bool h1 = h0 + 1 < g.Ho, w1 = w0 + 1 < g.Wo;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+        const int k = k0 + wk * 32 + 8 * (e / 4) + 4 * lhi + (e % 4);
+        if (k >= g.Co) continue;
+        float y[2][4];  // A^T m, column by column
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const float m0 = acc[c][e], m1 = acc[4 + c][e], m2 = acc[8 + c][e], m3 = acc[12 + c][e];
+            y[0][c] = m0 + m1 + m2;
+            y[1][c] = m1 - m2 - m3;
+        }
+        const long base = (((long)n * g.Co + k) * g.Ho + h0) * g.Wo + w0;
+        Elem<E>::store(p.out, base, y[0][0] + y[0][1] + y[0][2]);
+        if (w1) Elem<E>::store(p.out, base + 1, y[0][1] - y[0][2] - y[0][3]);
+        if (h1) {
+            Elem<E>::store(p.out, base + g.Wo, y[1][0] + y[1][1] + y[1][2]);
+            if (w1) Elem<E>::store(p.out, base + g.Wo + 1, y[1][1] - y[1][2] - y[1][3]);
+        }
+    }
+}
+
+size_t winograd_fused_ws_bytes(const Dims &d, int op)
+{
+    const WinoGeom g = geom(d, op, 1, 2);
+    return (size_t)64 * g.Ci * g.Mo4;
+}
+
+template <class E>
+static hipError_t winograd_fused_run(const Dims &d, int op, int b, const void *in, const void *w, void *out,
+                                     float *ws, bool filter_ready, hipStream_t s)
+{
+    const WinoGeom g = geom(d, op, b, 2);
+    LaunchLog *log = launch_log();
+    if (filter_ready) {
+        // U of this filter is still in the workspace from the previous micro-batch
+    } else if (log) log->add("wino_filter_kernel");
+    else
+        wino_filter_kernel<E, 2><<<(unsigned)((g.Ci * g.Mo4 + 255) / 256), 256, 0, s>>>(w, ws, g.Ci, g.Co, g.Mo4,
+                                                                                     g.transposed ? 1 : 0);
+    hipError_t e = log ? hipSuccess : hipGetLastError();
+    if (e != hipSuccess) return e;
+    FusedParams p{};
+    p.in = in; p.U = ws; p.out = out;
+    p.in_bytes = (uint32_t)(Elem<E>::kBytes * (size_t)b * g.Ci * g.Hi * g.Wi);
+    p.u_bytes = (uint32_t)((size_t)64 * g.Ci * g.Mo4);
+    p.g = g; p.divT = FastDiv(g.T); p.divTW = FastDiv(g.TW);
+    p.n_tiles = b * g.T;
+    p.k_blocks = (g.Co + kFuK - 1) / kFuK;
+    const unsigned blocks = (unsigned)(p.k_blocks * ((p.n_tiles + kFuT - 1) / kFuT));
+    if (log) {
+        log->add("wino_fused_kernel blocks=" + std::to_string(blocks) + " gemm_flops=" +
+                 std::to_string(2.0 * 16 * g.Co * (double)p.n_tiles * g.Ci));
+        return hipSuccess;
+    }
+    wino_fused_kernel<E><<<blocks, 256, 0, s>>>(p);
+    return hipGetLastError();
+}
+
+hipError_t winograd_fused(const Dims &d, int op, int b, const void *in, const void *w, void *out, float *ws,
+                          bool filter_ready, hipStream_t s)
+{
+    return d.dtype == 1 ? winograd_fused_run<bf16>(d, op, b, in, w, out, ws, filter_ready, s)
+                        : winograd_fused_run<float>(d, op, b, in, w, out, ws, filter_ready, s);
+}
+
 // D[xi][k][j] = (A dy A^T)[xi] for the m x m tile j of dy (zero outside the image), lanes along j.
 // g is the Forward geometry: Co = K, Ho x Wo = P x Q.
 template <class E, int MT>

@@ -57,6 +57,12 @@ hipError_t winograd_bwd_data(const Dims &d, int b, const void *dy, const void *w
 hipError_t winograd_bwd_filter(const Dims &d, int b, const void *x, const void *dy, float *dw, float beta,
                                float *ws, int mt, hipStream_t s);
 
+// F(2x2,3x3) with the input and output transforms fused into the GEMM kernel: Forward (op 0) and
+// BackwardData (op 1); the workspace holds the transformed filter only (independent of b).
+size_t winograd_fused_ws_bytes(const Dims &d, int op);
+hipError_t winograd_fused(const Dims &d, int op, int b, const void *in, const void *w, void *out, float *ws,
+                          bool filter_ready, hipStream_t s);
+
 // Tiled-FFT convolution (16x16 tiles), stride-1 layers with filters up to 9x9; filter_ready as
 // for Winograd (Forward and BackwardData).
 bool fft_applies(const Dims &d, int op);

@@ -10,40 +10,46 @@ namespace ucd {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-template <int VALU>
+// NACC accumulator tiles per wave: 4 (64 registers, several waves per SIMD) or 16 (256 registers,
+// one wave per SIMD: the situation of a kernel that keeps all 16 Winograd points of a tile resident).
+template <int VALU, int NACC>
 __global__ __launch_bounds__(256) void mfma_probe_kernel(float *out, int iters, float seed)
 {
-    f32x16 acc[4];
-    for (int i = 0; i < 4; ++i)
+    f32x16 acc[NACC];
+    for (int i = 0; i < NACC; ++i)
         for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
     const float a = seed + threadIdx.x, b = seed * 2 + threadIdx.x;
     float x[8];
     for (int i = 0; i < 8; ++i) x[i] = seed + i + threadIdx.x;
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < 16 / NACC; ++u)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
+            for (int i = 0; i < NACC; ++i) {
                 acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[i], 0, 0, 0);
 #pragma unroll
                 for (int v = 0; v < VALU; ++v) x[v] = x[v] * 1.0001f + 0.5f;
             }
     }
     float s = 0;
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < NACC; ++i)
         for (int v = 0; v < 16; ++v) s += acc[i][v];
     for (int i = 0; i < 8; ++i) s += x[i];
     out[blockIdx.x * 256 + threadIdx.x] = s;
 }
 
 // out must hold blocks * 256 floats.  flops counted: blocks * 4 waves * iters * 16 MFMAs * 4096.
+// valu_per_mfma: 0, 2, 4, 8 (4 accumulator tiles per wave), or 100 + those (16 tiles per wave).
 hipError_t mfma_probe(int valu_per_mfma, int blocks, int iters, float *out, hipStream_t s)
 {
     switch (valu_per_mfma) {
-    case 0: mfma_probe_kernel<0><<<blocks, 256, 0, s>>>(out, iters, 1.f); break;
-    case 2: mfma_probe_kernel<2><<<blocks, 256, 0, s>>>(out, iters, 1.f); break;
-    case 4: mfma_probe_kernel<4><<<blocks, 256, 0, s>>>(out, iters, 1.f); break;
-    case 8: mfma_probe_kernel<8><<<blocks, 256, 0, s>>>(out, iters, 1.f); break;
+    case 0: mfma_probe_kernel<0, 4><<<blocks, 256, 0, s>>>(out, iters, 1.f); break;
+    case 2: mfma_probe_kernel<2, 4><<<blocks, 256, 0, s>>>(out, iters, 1.f); break;
+    case 4: mfma_probe_kernel<4, 4><<<blocks, 256, 0, s>>>(out, iters, 1.f); break;
+    case 8: mfma_probe_kernel<8, 4><<<blocks, 256, 0, s>>>(out, iters, 1.f); break;
+    case 100: mfma_probe_kernel<0, 16><<<blocks, 256, 0, s>>>(out, iters, 1.f); break;
+    case 102: mfma_probe_kernel<2, 16><<<blocks, 256, 0, s>>>(out, iters, 1.f); break;
+    case 104: mfma_probe_kernel<4, 16><<<blocks, 256, 0, s>>>(out, iters, 1.f); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
