@@ -240,7 +240,7 @@ def gemm_flops(text):
     total = 0.0
     for part in text.split(";"):
         part = part.strip()
-        if part.startswith("wino_fused_kernel"):
+        if part.startswith("wino_fused"):
             total += float(part.split("gemm_flops=")[1].split()[0])
         if not part.startswith("gemm_kernel"):
             continue

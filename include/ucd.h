@@ -77,9 +77,9 @@ enum {
     UCD_ALGO_IMPLICIT = 0, UCD_ALGO_IM2COL = 1, UCD_ALGO_WINOGRAD = 2, UCD_ALGO_WINOGRAD4 = 3,
     UCD_ALGO_FFT = 4,  /* tiled FFT (16x16 tiles): stride-1 layers, filters up to 9x9, all three
                         * operations; the largest workspace of all (144 frequency planes) */
-    UCD_ALGO_WINOGRAD_FUSED = 5,  /* Winograd F(2x2,3x3), Forward and BackwardData, with the input and
-                        * output transforms inside the GEMM kernel: the workspace holds the transformed
-                        * filter only, whatever the micro-batch size */
+    UCD_ALGO_WINOGRAD_FUSED = 5,  /* Winograd F(2x2,3x3) (BackwardFilter: F(3x3,2x2)) with the data
+                        * transforms inside the GEMM kernel: the workspace holds the transformed filter
+                        * (BackwardFilter: the 16 K x C product planes) only, whatever the micro-batch size */
     UCD_N_ALGO = 6
 };
 
@@ -131,7 +131,7 @@ int ucd_set_deterministic(int on);
  *              ld = b * ceil(Ho/m) * ceil(Wo/m) rounded up to 4 (m = a - 2), where (Ci, Co, Ho, Wo)
  *              = (C, K, P, Q) for Forward and (K, C, H, W) for BackwardData, Co4 = Co rounded up
  *              to 4; BackwardFilter: K*C in place of Ci*Co4, tiles over (P, Q)
- *   Winograd, fused transforms   64 * Ci*Co4 (the transformed filter; no BackwardFilter)
+ *   Winograd, fused transforms   64 * Ci*Co4 (the transformed filter); BackwardFilter 64 * K*C
  *   FFT        4 * 144 * (2Ci*M4 + ld*(2Ci + 2Co)), M4 = 2Co rounded up to 4, ld = b *
  *              ceil(Ho/(17-R)) * ceil(Wo/(17-S)) rounded up to 4, (Ci, Co, Ho, Wo) as for Winograd;
  *              BackwardFilter: 4*K*C in place of 2Ci*M4, tiles over (P, Q)

@@ -103,8 +103,8 @@ size_t ws_size(const ucd_layer_t *L, int op, int algo, int b)
         return winograd_ws_bytes(d, op, b, mt);
     }
     case UCD_ALGO_WINOGRAD_FUSED:
-        if (op == UCD_BWD_FILTER || !winograd_applies(d, op)) return UCD_WS_NA;
-        return winograd_fused_ws_bytes(d, op);
+        if (!winograd_applies(d, op)) return UCD_WS_NA;
+        return op == UCD_BWD_FILTER ? winograd_fused_filter_ws_bytes(d) : winograd_fused_ws_bytes(d, op);
     case UCD_ALGO_FFT:
         if (!fft_applies(d, op)) return UCD_WS_NA;
         // every frequency plane is one GEMM operand
@@ -146,6 +146,7 @@ int run_micro(const ucd_layer_t *L, int op, int algo, int b, const void *a, cons
         break;
     case UCD_ALGO_WINOGRAD_FUSED:
         if (op != UCD_BWD_FILTER) e = winograd_fused(d, op, b, a, bsrc, out, ws, filter_ready, s);
+        else e = winograd_fused_filter(d, b, a, bsrc, (float *)out, beta, ws, s);
         break;
     case UCD_ALGO_FFT:
         if (op == UCD_FWD) e = fft_fwd(d, b, a, bsrc, out, ws, filter_ready, s);

@@ -655,6 +655,256 @@ __global__ __launch_bounds__(256) void wino_dw_kernel(const float *__restrict__ 
     }
 }
 
+// ---- BackwardFilter F(3x3,2x2) with both data transforms fused into the GEMM kernel -------------------
+// Mw[xi][k][c] = sum over tiles of D[xi][k][tile] * V[xi][c][tile] with D = A dy A^T and V = B^T x B
+// computed on the fly; the workspace holds Mw alone (64*K*C bytes).  A workgroup owns 64 output
+// channels x 64 input channels for all 16 points (16 accumulator tiles per wave, as in the kernel
+// above) and reduces over a chunk of the tiles: 8 tile positions of the image (fixed for the
+// workgroup, so that every thread's patch addresses and border masks are computed once) times a range
+// of images, one image per step.  Per step a thread fetches and transforms the x patches of two
+// (input channel, tile) pairs and the dy tiles of two (output channel, tile) pairs; 64 MFMAs per
+// wave (16 points x 4 tile pairs).  Chunks meet in Mw through fp32 atomics; dw = beta*dw + G^T Mw G
+// is wino_dw_kernel's.
+constexpr int kFwT = 8;                 // tile positions per step (the MFMAs' reduction rows)
+constexpr int kFwLd = 64 + 8;           // LDS row stride: 8 tiles x 8 channels of a wave's store hit every bank twice
+constexpr int kFwPairs = kFwT / 2;
+
+struct FusedFilterParams {
+    const void *x, *dy;
+    float *Mw;
+    uint32_t x_bytes, dy_bytes;
+    WinoGeom g;       // Forward geometry: Ci = C, Co = K, Hi x Wi = H x W, Ho x Wo = P x Q
+    int b, k_blocks, c_blocks, groups, n_split, images_per_chunk;
+};
+
+template <class E>
+__global__ __launch_bounds__(256) void wino_fused_filter_kernel(FusedFilterParams p)
+{
+    constexpr uint32_t EB = Elem<E>::kBytes;
+    __shared__ __attribute__((aligned(16))) float Ds[2][16][kFwT][kFwLd];
+    __shared__ __attribute__((aligned(16))) float Vs[2][16][kFwT][kFwLd];
+    const WinoGeom &g = p.g;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, lhi = lane >> 5;
+    const int wk = wave & 1, wc = wave >> 1;
+
+    // work item: (output-channel block, input-channel block, tile-position group, image chunk);
+    // neighbours on an XCD share the x patches (same input-channel block, group and chunk)
+    uint32_t v = xcd_order(blockIdx.x, gridDim.x);
+    const int kb = (int)(v % (uint32_t)p.k_blocks); v /= (uint32_t)p.k_blocks;
+    const int cb = (int)(v % (uint32_t)p.c_blocks); v /= (uint32_t)p.c_blocks;
+    const int grp = (int)(v % (uint32_t)p.groups);
+    const int chunk = (int)(v / (uint32_t)p.groups);
+    const int k0 = kb * 64, c0 = cb * 64;
+    const int n_begin = chunk * p.images_per_chunk, n_end = min(p.b, n_begin + p.images_per_chunk);
+
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc_bytes(p.x, 0, p.x_bytes);
+    const __amdgpu_buffer_rsrc_t rdy = make_rsrc_bytes(p.dy, 0, p.dy_bytes);
+
+    // producer role: tile position tid % 8 of the group, channel tid / 8 (and + 32) of both blocks;
+    // offsets within image 0 (kOob: outside the image, or no such tile / channel)
+    const int ptile = tid & 7, pch = tid >> 3;
+    uint32_t vx[2][16], vd[2][4];
+    {
+        const int t = grp * kFwT + ptile;
+        const bool live = t < g.T;
+        const int th = live ? t / g.TW : 0, tw = live ? t % g.TW : 0;
+        const int h0 = 2 * th - g.pad_h, w0 = 2 * tw - g.pad_w;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int c = c0 + pch + 32 * h, k = k0 + pch + 32 * h;
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int hh = h0 + r, ww = w0 + q;
+                    const bool ok = live && c < g.Ci && (unsigned)hh < (unsigned)g.Hi && (unsigned)ww < (unsigned)g.Wi;
+                    vx[h][4 * r + q] = ok ? EB * (uint32_t)((c * g.Hi + hh) * g.Wi + ww) : kOob;
+                }
+#pragma unroll
+            for (int r = 0; r < 2; ++r)
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    const int hh = 2 * th + r, ww = 2 * tw + q;
+                    const bool ok = live && k < g.Co && hh < g.Ho && ww < g.Wo;
+                    vd[h][2 * r + q] = ok ? EB * (uint32_t)((k * g.Ho + hh) * g.Wo + ww) : kOob;
+                }
+        }
+    }
+    const uint32_t x_image = EB * (uint32_t)(g.Ci * g.Hi * g.Wi), dy_image = EB * (uint32_t)(g.Co * g.Ho * g.Wo);
+
+    float dx[2][16], dz[2][4];  // the thread's patches of the image after the one in LDS
+    // an image past the chunk's end gets a scalar offset that pushes every address out of range
+    auto fetch_x = [&](int n, int h, int i) {
+        dx[h][i] = Elem<E>::load(rx, vx[h][i], n < n_end ? (uint32_t)n * x_image : kOob);
+    };
+    auto fetch_dy = [&](int n, int h, int i) {
+        dz[h][i] = Elem<E>::load(rdy, vd[h][i], n < n_end ? (uint32_t)n * dy_image : kOob);
+    };
+    auto store_v = [&](int buf, int h) {  // B^T x B of patch h
+        float tr[16];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const float a0 = dx[h][c], a1 = dx[h][4 + c], a2 = dx[h][8 + c], a3 = dx[h][12 + c];
+            tr[c] = a0 - a2;
+            tr[4 + c] = a1 + a2;
+            tr[8 + c] = a2 - a1;
+            tr[12 + c] = a1 - a3;
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float a0 = tr[4 * r], a1 = tr[4 * r + 1], a2 = tr[4 * r + 2], a3 = tr[4 * r + 3];
+            Vs[buf][4 * r + 0][ptile][pch + 32 * h] = a0 - a2;
+            Vs[buf][4 * r + 1][ptile][pch + 32 * h] = a1 + a2;
+            Vs[buf][4 * r + 2][ptile][pch + 32 * h] = a2 - a1;
+            Vs[buf][4 * r + 3][ptile][pch + 32 * h] = a1 - a3;
+        }
+    };
+    auto store_d = [&](int buf, int h) {  // A dy A^T of tile h: rows (z0, z0+z1, z0-z1, -z1) of A z, then the same on columns
+        const float z00 = dz[h][0], z01 = dz[h][1], z10 = dz[h][2], z11 = dz[h][3];
+        const float t[4][2] = {{z00, z01}, {z00 + z10, z01 + z11}, {z00 - z10, z01 - z11}, {-z10, -z11}};
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            Ds[buf][4 * r + 0][ptile][pch + 32 * h] = t[r][0];
+            Ds[buf][4 * r + 1][ptile][pch + 32 * h] = t[r][0] + t[r][1];
+            Ds[buf][4 * r + 2][ptile][pch + 32 * h] = t[r][0] - t[r][1];
+            Ds[buf][4 * r + 3][ptile][pch + 32 * h] = -t[r][1];
+        }
+    };
+
+    f32x16 acc[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) fetch_x(n_begin, h, i);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) fetch_dy(n_begin, h, i);
+    }
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        store_v(0, h);
+        store_d(0, h);
+    }
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) fetch_x(n_begin + 1, h, i);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) fetch_dy(n_begin + 1, h, i);
+    }
+    __syncthreads();
+
+    int buf = 0;
+    for (int n = n_begin; n < n_end; ++n) {
+        const float *da = &Ds[buf][0][lhi][wk * 32 + l32];
+        const float *vb = &Vs[buf][0][lhi][wc * 32 + l32];
+        // operands of (point xi, tile pair q): rows 2q + lhi of the point's slab, read one point ahead
+        float a[2][kFwPairs], b[2][kFwPairs];
+        auto read_ops = [&](int xi) {
+#pragma unroll
+            for (int q = 0; q < kFwPairs; ++q) {
+                a[xi & 1][q] = da[(xi * kFwT + 2 * q) * kFwLd];
+                b[xi & 1][q] = vb[(xi * kFwT + 2 * q) * kFwLd];
+            }
+        };
+        read_ops(0);
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_setprio(UCD_MFMA_PRIO);
+#pragma unroll
+        for (int m = 0; m < 16 * kFwPairs; ++m) {
+            const int xi = m / kFwPairs, q = m % kFwPairs;
+            acc[xi] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[xi & 1][q], b[xi & 1][q], acc[xi], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (q == 0 && xi + 1 < 16) read_ops(xi + 1);
+            // image n + 1 (in registers) is transformed into the other LDS buffer and every register
+            // reloaded with image n + 2 as soon as it is free: one piece, and at most one global load,
+            // behind each MFMA (a burst of loads would block this SIMD's only wave)
+            if (m >= 1 && m < 35) {          // x patches: 2 x (transform + 16 loads)
+                const int h = (m - 1) / 17, i = (m - 1) % 17;
+                if (i == 0) store_v(buf ^ 1, h);
+                else fetch_x(n + 2, h, i - 1);
+            }
+            if (m >= 35 && m < 45) {         // dy tiles: 2 x (transform + 4 loads)
+                const int h = (m - 35) / 5, i = (m - 35) % 5;
+                if (i == 0) store_d(buf ^ 1, h);
+                else fetch_dy(n + 2, h, i - 1);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        __builtin_amdgcn_s_setprio(0);
+        __syncthreads();
+        buf ^= 1;
+    }
+
+    // lane = input channel (column l32 of the wave's 32), register e = output-channel row
+    const int c = c0 + wc * 32 + l32;
+    if (c >= g.Ci) return;
+    const size_t plane = (size_t)g.Co * g.Ci;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+        const int k = k0 + wk * 32 + 8 * (e / 4) + 4 * lhi + (e % 4);
+        if (k >= g.Co) continue;
+#pragma unroll
+        for (int xi = 0; xi < 16; ++xi) unsafeAtomicAdd(p.Mw + xi * plane + (size_t)k * g.Ci + c, acc[xi][e]);
+    }
+}
+
+size_t winograd_fused_filter_ws_bytes(const Dims &d) { return (size_t)64 * d.K * d.C; }
+
+template <class E>
+static hipError_t winograd_fused_filter_run(const Dims &d, int b, const void *x, const void *dy, float *dw, float beta,
+                                            float *ws, hipStream_t s)
+{
+    const WinoGeom g = geom(d, 0, b, 2);
+    const int KC = d.K * d.C;
+    hipError_t e = fill_zero(ws, (size_t)16 * KC, s);
+    if (e != hipSuccess) return e;
+    FusedFilterParams p{};
+    p.x = x; p.dy = dy; p.Mw = ws;
+    p.x_bytes = xbytes(d, b); p.dy_bytes = ybytes(d, b);
+    p.g = g; p.b = b;
+    p.k_blocks = (d.K + 63) / 64; p.c_blocks = (d.C + 63) / 64; p.groups = (g.T + kFwT - 1) / kFwT;
+    // image chunks: about four rounds of one workgroup per CU, chunks of at least 4 images; among the
+    // counts near that, the one whose workgroup count fills its rounds of 256 best
+    const long items = (long)p.k_blocks * p.c_blocks * p.groups;
+    const long want = (1024 + items - 1) / items, cap = b / 4 < 1 ? 1 : b / 4;
+    long split = want > cap ? cap : want;
+    double best = -1.0;
+    for (long c = (want + 1) / 2; c <= 2 * want && c <= cap; ++c) {
+        const int per = (int)((b + c - 1) / c);
+        const long wgs = items * ((b + per - 1) / per);
+        const double fill = (double)wgs / (double)((wgs + 255) / 256 * 256);
+        if (fill > best + 1e-9) { best = fill; split = c; }
+    }
+    p.images_per_chunk = (int)((b + split - 1) / split);
+    p.n_split = (b + p.images_per_chunk - 1) / p.images_per_chunk;
+    const unsigned blocks = (unsigned)(items * p.n_split);
+    LaunchLog *log = launch_log();
+    if (log) {
+        log->add("wino_fused_filter_kernel blocks=" + std::to_string(blocks) + " gemm_flops=" +
+                 std::to_string(2.0 * 16 * d.K * (double)d.C * p.groups * kFwT * b));
+        log->add("wino_dw_kernel");
+        return hipSuccess;
+    }
+    wino_fused_filter_kernel<E><<<blocks, 256, 0, s>>>(p);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    wino_dw_kernel<2><<<(unsigned)((KC + 255) / 256), 256, 0, s>>>(ws, dw, KC, beta);
+    return hipGetLastError();
+}
+
+hipError_t winograd_fused_filter(const Dims &d, int b, const void *x, const void *dy, float *dw, float beta,
+                                 float *ws, hipStream_t s)
+{
+    return d.dtype == 1 ? winograd_fused_filter_run<bf16>(d, b, x, dy, dw, beta, ws, s)
+                        : winograd_fused_filter_run<float>(d, b, x, dy, dw, beta, ws, s);
+}
+
 template <class E, int MT>
 static hipError_t winograd_filter_run(const Dims &d, int b, const void *x, const void *dy, float *dw, float beta,
                                       float *ws, hipStream_t s)

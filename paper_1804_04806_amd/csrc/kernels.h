@@ -60,6 +60,10 @@ hipError_t winograd_bwd_filter(const Dims &d, int b, const void *x, const void *
 // F(2x2,3x3) with the input and output transforms fused into the GEMM kernel: Forward (op 0) and
 // BackwardData (op 1); the workspace holds the transformed filter only (independent of b).
 size_t winograd_fused_ws_bytes(const Dims &d, int op);
+// BackwardFilter F(3x3,2x2) with both transforms fused: the workspace holds the 16 K x C product planes
+size_t winograd_fused_filter_ws_bytes(const Dims &d);
+hipError_t winograd_fused_filter(const Dims &d, int b, const void *x, const void *dy, float *dw, float beta,
+                                 float *ws, hipStream_t s);
 hipError_t winograd_fused(const Dims &d, int op, int b, const void *in, const void *w, void *out, float *ws,
                           bool filter_ready, hipStream_t s);
 
