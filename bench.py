@@ -38,24 +38,22 @@ FP32_MFMA_PEAK_TFLOPS = 157.3   # MI355X dense fp32 matrix peak: 256 CU x 2.4 GH
 BF16_MFMA_PEAK_TFLOPS = 2500.0  # dense bf16 matrix peak (16x the fp32 rate); kernels named gemm_kernel_bf16
 WS_LIMIT = 64 << 20
 
-# HBM bytes (fetched + written) per algorithmic flop of the GEMM instantiations of the default
-# workload's planned step, from two rocprofv3 --pmc passes over this script (FETCH_SIZE, then
-# WRITE_SIZE, each scaled by what the counter reads for a plain device copy of known size: x2.00 and
-# x1.00): mean bytes per dispatch of a run whose benchmark cache came from a file (so that every
-# dispatch has a shape of the step), divided by the mean flops per launch of that run's step.
+# HBM bytes (fetched + written) per matrix flop of the kernels of the default workload's planned
+# step, from two rocprofv3 --pmc passes over this script (FETCH_SIZE, then WRITE_SIZE, each scaled by
+# what the counter reads for a plain device copy of known size: x2.00 and x1.00): mean bytes per
+# dispatch of a run whose benchmark cache came from a file (so that every dispatch has a shape of
+# the step), divided by the mean matrix flops per launch of that run's step.
 # `traffic` = this figure x the flops per launch of the step being timed: the planner does not
-# pick the same micro-batch sizes every run, and a kernel's traffic follows its size (the ratio
-# itself differs by layer: 1.8e-3 to 2.7e-3 bytes per flop over the four BackwardFilter launches).
-# Summary: profiles/bench_alexnet_b256_ws64MiB_kernel_stats.md.  A profiler cannot run inside the
-# timed script, so these are recorded figures; they apply to the AlexNet workload at batch 256
-# only and `traffic` is null for anything else.
+# pick the same micro-batch sizes every run, and a kernel's traffic follows its size.
 MEASURED_TRAFFIC_BYTES_PER_FLOP = {
-    "gemm_kernel<Tile<128x128>,PixelTab<dy>,PixelTab<x>,EpiAtomic>": 283.0e6 / 133.56e9,
-    "gemm_kernel<Tile<96x128>,PixelKLane<dy>,PixelKLane<x>,EpiAtomic>": 538.3e6 / 53.97e9,
-    "gemm_kernel<Tile<128x128>,KLane0,GatherNLane<taps<=31>,EpiNCHW>": 326.3e6 / 229.32e9,
-    "gemm_kernel<Tile<96x128>,FilterKLane,GatherNLane<taps<=31>,EpiNCHW>": 322.2e6 / 214.09e9,
-    "gemm_kernel<Tile<96x128>,KLane0,GatherNLane<taps>31>,EpiNCHW>": 274.0e6 / 26.98e9,
-    "gemm_kernel<Tile<64x128>,PhaseFilterKLane,GatherNLane<taps<=31>,EpiPhases>": 451.9e6 / 52.71e9,
+    "wino_fused_kernel": 334.6e6 / 41.23e9,
+    "wino_fused_filter_kernel": 727.0e6 / 67.64e9,
+    "gemm_kernel<Tile<128x128>,PixelTab<dy>,PixelTab<x>,EpiAtomic>": 295.3e6 / 148.6e9,
+    "gemm_kernel<Tile<96x128>,PixelKLane<dy>,PixelKLane<x>,EpiAtomic>": 537.2e6 / 53.97e9,
+    "gemm_kernel<Tile<128x128>,KLane0,GatherNLane<taps<=31>,EpiNCHW>": 447.8e6 / 229.32e9,
+    "gemm_kernel<Tile<96x128>,FilterKLane,GatherNLane<taps<=31>,EpiNCHW>": 386.8e6 / 229.32e9,
+    "gemm_kernel<Tile<96x128>,KLane0,GatherNLane<taps>31>,EpiNCHW>": 482.0e6 / 53.97e9,
+    "gemm_kernel<Tile<64x128>,PhaseFilterKLane,GatherNLane<taps<=31>,EpiPhases>": 459.2e6 / 68.99e9,
 }
 
 ALGO_IDS = {"implicit": 0, "im2col": 1, "winograd": 2, "winograd4": 3, "fft": 4, "winograd-fused": 5}
@@ -92,6 +90,9 @@ def parse():
     ap.add_argument("--cpu-samples", type=int, default=24)
     ap.add_argument("--bench-db", default=None,
                     help="benchmark database file: loaded before planning if it exists, saved afterwards")
+    ap.add_argument("--skip-undivided", action="store_true",
+                    help="do not time the undivided baseline (profiling runs: every launch of the process then "
+                         "belongs to the planned step)")
     ap.add_argument("--memory-table", action="store_true",
                     help="also print, as markdown on stderr, the per-kernel workspace of the planned configuration "
                          "next to the undivided plan under a 512 MiB limit (the paper's Section 4.3 comparison)")
@@ -101,7 +102,9 @@ def parse():
     ap.add_argument("--layer", default="conv4")
     ap.add_argument("--op", default="fwd", choices=["fwd", "bwd_data", "bwd_filter"])
     ap.add_argument("--algo", default="implicit", choices=sorted(ALGO_IDS))
-    ap.add_argument("--b", type=int, default=256)
+    ap.add_argument("--b", default="256", help="micro-batch size, or a comma-separated list (one JSON line each)")
+    ap.add_argument("--back-to-back", action="store_true",
+                    help="--micro: time --reps launches between one pair of events instead of one launch per pair")
     ap.add_argument("--reps", type=int, default=5)
     ap.add_argument("--copy-mib", type=int, default=0,
                     help="with --micro: a plain device copy of this many MiB (a kernel of known traffic, to "
@@ -235,6 +238,11 @@ def time_interleaved(torch, fn_a, fn_b, rounds, warmup):
     return a[len(a) // 2], b[len(b) // 2], a[0], b[0]
 
 
+def num(v):
+    """Rounded for the JSON line; None for a figure that was not measured."""
+    return None if v != v else round(v, 4)
+
+
 def gemm_flops(text):
     """MFMA flops the GEMM launches of a micro-batch description issue: 2*M*N*K*batch each."""
     total = 0.0
@@ -261,24 +269,32 @@ def executed_flops(ucd, states, plans):
 
 
 def kernel_class(ucd, desc, op, algo, b):
-    """The GEMM kernel instantiation a micro-batch run launches, as the library describes it
-    (the names rocprofv3 shows are these template instantiations), if the run is that one kernel
-    (a zero-fill kernel in front of it is tolerated: a few microseconds); otherwise None
-    (im2col, Winograd and strided BackwardData launch several kernels)."""
+    """The dominant kernel a micro-batch run launches, as the library describes it (the names
+    rocprofv3 shows are these template instantiations), if the run is that one kernel besides
+    helpers of a few microseconds (zero fills, the Winograd filter transform and the final
+    16 -> 9 reduction of the fused BackwardFilter); otherwise None (im2col, the unfused Winograd
+    variants, FFT and strided BackwardData launch several kernels of comparable weight).
+    Returns (name, matrix flops the kernel issues)."""
     text, n = ucd.ucd_describe_micro(desc, op, algo, b)
     parts = [p.strip() for p in text.split(";")]
-    gemms = [p for p in parts if p.startswith("gemm_kernel")]
-    others = [p for p in parts if not p.startswith("gemm_kernel") and p not in ("fill_zero_kernel", "zero_tiles_kernel")]
-    if len(gemms) != 1 or others:
+    helpers = ("fill_zero_kernel", "zero_tiles_kernel", "wino_filter_kernel", "wino_dw_kernel")
+    main = [p for p in parts if p.startswith(("gemm_kernel", "wino_fused"))]
+    others = [p for p in parts if p not in main and p not in helpers]
+    if len(main) != 1 or others:
         return None
-    name = gemms[0].split("> tiles=")[0] + ">"
-    return name + (" (after " + parts[0] + ")" if len(parts) > 1 else "")
+    if main[0].startswith("wino_fused"):
+        return main[0].split()[0], gemm_flops(main[0])
+    name = main[0].split("> tiles=")[0] + ">"
+    return name + (" (after " + parts[0] + ")" if len(parts) > 1 else ""), gemm_flops(main[0])
 
 
 def dominant_kernel_roofline(torch, ucd, states, plans, ws, reps, traffic_table=None):
-    """HIP-event timing (events recorded on the launch stream) of every single-kernel micro-batch
-    launch of the planned step, grouped by kernel instantiation; returns the roofline object of
-    the instantiation with the largest total time, and the per-instantiation table.
+    """HIP-event timing (events recorded on the launch stream, `reps` launches back to back between
+    them, as the launches of a step follow each other) of every single-kernel micro-batch launch of
+    the planned step, grouped by kernel instantiation; returns the roofline object of the
+    instantiation with the largest total time, and the per-instantiation table.  Flops are the
+    matrix flops the kernel issues (2*M*N*K of its GEMM; for the fused Winograd kernels the 16 tile
+    products), with the direct-convolution-equivalent rate beside them.
     BackwardFilter launches are timed as the accumulating (beta = 1) call, which is the GEMM
     kernel alone; with beta = 0 a small fill kernel precedes it."""
     groups = {}
@@ -289,8 +305,9 @@ def dominant_kernel_roofline(torch, ucd, states, plans, ws, reps, traffic_table=
         for op in (ucd.FWD, ucd.BWD_DATA, ucd.BWD_FILTER):
             o = 0
             for algo, b in pl[op].micro:
-                cls = kernel_class(ucd, st.desc, op, algo, b)
-                if cls is not None:
+                found = kernel_class(ucd, st.desc, op, algo, b)
+                if found is not None:
+                    cls, executed = found
                     xo = st.x.view(-1)[o * x_img:]
                     yo = st.y.view(-1)[o * y_img:]
                     dyo = st.dy.view(-1)[o * y_img:]
@@ -298,23 +315,25 @@ def dominant_kernel_roofline(torch, ucd, states, plans, ws, reps, traffic_table=
                     args = {ucd.FWD: (xo, st.w, yo), ucd.BWD_DATA: (dyo, st.w, dxo),
                             ucd.BWD_FILTER: (xo, dyo, st.dw)}[op]
                     beta = 1.0 if op == ucd.BWD_FILTER else 0.0
-                    tot = 0.0
+                    ucd.ucd_run_micro(st.desc, op, algo, b, *args, beta, ws)
+                    e0.record()
                     for _ in range(reps):
-                        e0.record()
                         ucd.ucd_run_micro(st.desc, op, algo, b, *args, beta, ws)
-                        e1.record()
-                        e1.synchronize()
-                        tot += e0.elapsed_time(e1)
-                    g = groups.setdefault(cls, {"ms": 0.0, "flops": 0.0, "launches": 0})
+                    e1.record()
+                    e1.synchronize()
+                    tot = e0.elapsed_time(e1)
+                    g = groups.setdefault(cls, {"ms": 0.0, "flops": 0.0, "direct": 0.0, "launches": 0})
                     g["ms"] += tot / reps
-                    g["flops"] += s.with_batch(b).flops
+                    g["flops"] += executed
+                    g["direct"] += s.with_batch(b).flops
                     g["launches"] += 1
                 o += b
     if not groups:
         return None, []
     table = [{"kernel": k, "launches_per_step": g["launches"], "ms_per_step": round(g["ms"], 4),
               "avg_launch_ms": round(g["ms"] / g["launches"], 4),
-              "tflops": round(g["flops"] / (g["ms"] * 1e-3) / 1e12, 2)}
+              "tflops": round(g["flops"] / (g["ms"] * 1e-3) / 1e12, 2),
+              "direct_equivalent_tflops": round(g["direct"] / (g["ms"] * 1e-3) / 1e12, 2)}
              for k, g in sorted(groups.items(), key=lambda kv: -kv[1]["ms"])]
     name, g = max(groups.items(), key=lambda kv: kv[1]["ms"])
     achieved = g["flops"] / (g["ms"] * 1e-3) / 1e12
@@ -323,7 +342,8 @@ def dominant_kernel_roofline(torch, ucd, states, plans, ws, reps, traffic_table=
             "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
             "traffic": None,
             "launches_per_step": g["launches"], "avg_launch_ms": round(g["ms"] / g["launches"], 4),
-            "flops_per_launch": g["flops"] / g["launches"]}
+            "flops_per_launch": g["flops"] / g["launches"],
+            "direct_equivalent_tflops": round(g["direct"] / (g["ms"] * 1e-3) / 1e12, 2)}
     per_flop = (traffic_table or {}).get(name.split(" (after")[0])
     if per_flop is not None:
         roof["traffic"] = round(per_flop * roof["flops_per_launch"])
@@ -427,30 +447,43 @@ def micro_main(args):
         return
     nets = {"small": synth.config_small, "alexnet": synth.config_alexnet, "resnet18": synth.config_resnet18,
             "densenet": synth.config_densenet_block, "resnet50": synth.config_resnet50}
-    s = next(l for l in nets[args.net]() if l.name == args.layer).with_batch(args.b)
     op = {"fwd": ucd.FWD, "bwd_data": ucd.BWD_DATA, "bwd_filter": ucd.BWD_FILTER}[args.op]
     algo = ALGO_IDS[args.algo]
-    desc = ucd.layer(s, dtype=1 if args.dtype == "bf16" else 0)
-    need = ucd.ucd_workspace_size(desc, op, algo, args.b)
-    if need == ucd.WS_NA:
-        raise SystemExit("algorithm does not apply to this layer/operation")
     td = torch.bfloat16 if args.dtype == "bf16" else torch.float32
-    x = torch.from_numpy(synth.make_x(s)).to(dev).to(td)
-    w = torch.from_numpy(synth.make_w(s)).to(dev).to(td)
-    y = torch.from_numpy(synth.make_dy(s)).to(dev).to(td)
-    if op == ucd.BWD_FILTER:
-        w = w.float()   # dw is fp32 for every dtype
-    ws = torch.empty(max(need, 4) // 4, dtype=torch.float32, device=dev)
-    a, bsrc, out = {ucd.FWD: (x, w, y), ucd.BWD_DATA: (y, w, x), ucd.BWD_FILTER: (x, y, w)}[op]
-    beta = 1.0 if op == ucd.BWD_FILTER else 0.0
-    times, _ = timed(lambda: ucd.ucd_run_micro(desc, op, algo, args.b, a, bsrc, out, beta, ws))
-    ms = min(times)
-    text, _ = ucd.ucd_describe_micro(desc, op, algo, args.b)
-    print(json.dumps({"layer": s.name, "op": args.op, "algo": args.algo, "b": args.b, "dtype": args.dtype,
-                      "ms_min": round(ms, 4), "ms_avg": round(sum(times) / len(times), 4),
-                      "tflops": round(s.flops / ms / 1e9, 2),
-                      "executed_mfma_tflops": round(gemm_flops(text) / ms / 1e9, 2), "ws_bytes": need,
-                      "launches": text}))
+    for b in [int(v) for v in str(args.b).split(",")]:
+        s = next(l for l in nets[args.net]() if l.name == args.layer).with_batch(b)
+        desc = ucd.layer(s, dtype=1 if args.dtype == "bf16" else 0)
+        need = ucd.ucd_workspace_size(desc, op, algo, b)
+        if need == ucd.WS_NA:
+            raise SystemExit("algorithm does not apply to this layer/operation")
+        x = torch.from_numpy(synth.make_x(s)).to(dev).to(td)
+        w = torch.from_numpy(synth.make_w(s)).to(dev).to(td)
+        y = torch.from_numpy(synth.make_dy(s)).to(dev).to(td)
+        if op == ucd.BWD_FILTER:
+            w = w.float()   # dw is fp32 for every dtype
+        ws = torch.empty(max(need, 4) // 4, dtype=torch.float32, device=dev)
+        a, bsrc, out = {ucd.FWD: (x, w, y), ucd.BWD_DATA: (y, w, x), ucd.BWD_FILTER: (x, y, w)}[op]
+        beta = 1.0 if op == ucd.BWD_FILTER else 0.0
+        run = lambda: ucd.ucd_run_micro(desc, op, algo, b, a, bsrc, out, beta, ws)
+        if args.back_to_back:
+            for _ in range(max(args.warmup, 1)):
+                run()
+            e0.record()
+            for _ in range(args.reps):
+                run()
+            e1.record()
+            e1.synchronize()
+            times = [e0.elapsed_time(e1) / args.reps]
+        else:
+            times, _ = timed(run)
+        ms = min(times)
+        text, _ = ucd.ucd_describe_micro(desc, op, algo, b)
+        print(json.dumps({"layer": s.name, "op": args.op, "algo": args.algo, "b": b, "dtype": args.dtype,
+                          "timing": "back-to-back" if args.back_to_back else "one launch per event pair",
+                          "ms_min": round(ms, 4), "ms_avg": round(sum(times) / len(times), 4),
+                          "tflops": round(s.flops / ms / 1e9, 2),
+                          "executed_mfma_tflops": round(gemm_flops(text) / ms / 1e9, 2), "ws_bytes": need,
+                          "launches": text}), flush=True)
 
 
 def main():
@@ -524,8 +557,11 @@ def main():
     # the contract's figure: exactly --steps planned steps between two synchronisations
     ms, ms_median, ms_min = time_steps(torch, lambda: step(plans, offsets), args.steps, args.warmup)
     # planned against undivided, interleaved step by step so that both see the same clock
-    u_med, p_med, u_min, p_min = time_interleaved(torch, lambda: step(undiv), lambda: step(plans, offsets),
-                                                  args.steps, args.warmup)
+    if args.skip_undivided:
+        u_med = p_med = u_min = p_min = float("nan")
+    else:
+        u_med, p_med, u_min, p_min = time_interleaved(torch, lambda: step(undiv), lambda: step(plans, offsets),
+                                                      args.steps, args.warmup)
 
     tflops = flops_per_step / (ms * 1e-3) / 1e12
     peak = FP32_MFMA_PEAK_TFLOPS if args.dtype == "f32" else BF16_MFMA_PEAK_TFLOPS
@@ -569,9 +605,9 @@ def main():
         "executed_mfma_tflops": round(exec_flops / (ms * 1e-3) / 1e12, 3),
         "pct_mfma_peak_executed": round(100 * exec_flops / (ms * 1e-3) / 1e12 / peak, 2),
         "executed_gflop_per_step": round(exec_flops / 1e9, 1),
-        "undivided_ms_per_iter": round(u_med, 4), "planned_ms_interleaved": round(p_med, 4),
-        "undivided_ms_min": round(u_min, 4), "planned_ms_min_interleaved": round(p_min, 4),
-        "speedup_vs_undivided": round(u_med / p_med, 4),
+        "undivided_ms_per_iter": num(u_med), "planned_ms_interleaved": num(p_med),
+        "undivided_ms_min": num(u_min), "planned_ms_min_interleaved": num(p_min),
+        "speedup_vs_undivided": num(u_med / p_med),
         "plan_seconds": plan_seconds,
         "gflop_per_step": round(flops_per_step / 1e9, 1),
         "roofline": roof,
