@@ -435,6 +435,10 @@ def micro_main(args):
         for valu in (0, 2, 4):
             times, flops = timed(lambda: ucd.ucd_mfma_probe(100 + valu, blocks, iters, scratch))
             out[f"one_wave_per_simd_tflops_with_{valu}_valu_per_mfma"] = round(flops / min(times) / 1e9, 1)
+        # the same, but every accumulator takes 4 dependent MFMAs in a row
+        for valu in (0, 2):
+            times, flops = timed(lambda: ucd.ucd_mfma_probe(200 + valu, blocks, iters, scratch))
+            out[f"one_wave_per_simd_4_in_a_row_tflops_with_{valu}_valu_per_mfma"] = round(flops / min(times) / 1e9, 1)
         print(json.dumps(out))
         return
     if args.copy_mib:

@@ -131,7 +131,8 @@ int ucd_set_deterministic(int on);
  *              ld = b * ceil(Ho/m) * ceil(Wo/m) rounded up to 4 (m = a - 2), where (Ci, Co, Ho, Wo)
  *              = (C, K, P, Q) for Forward and (K, C, H, W) for BackwardData, Co4 = Co rounded up
  *              to 4; BackwardFilter: K*C in place of Ci*Co4, tiles over (P, Q)
- *   Winograd, fused transforms   64 * Ci*Co4 (the transformed filter); BackwardFilter 64 * K*C
+ *   Winograd, fused transforms   64 * Ci8*Co4 (the transformed filter, Ci8 = Ci rounded up to 8);
+ *              BackwardFilter 64 * K*C
  *   FFT        4 * 144 * (2Ci*M4 + ld*(2Ci + 2Co)), M4 = 2Co rounded up to 4, ld = b *
  *              ceil(Ho/(17-R)) * ceil(Wo/(17-S)) rounded up to 4, (Ci, Co, Ho, Wo) as for Winograd;
  *              BackwardFilter: 4*K*C in place of 2Ci*M4, tiles over (P, Q)

@@ -36,7 +36,9 @@ int ucd_describe_micro(const ucd_layer_t *layer, int op, int algo, int b, char *
  * enqueues a register-only loop of independent v_mfma_f32_32x32x2_f32 with `valu_per_mfma`
  * (0, 2, 4 or 8) ordinary vector FMAs interleaved per MFMA, on `blocks` workgroups of 256
  * threads, `iters` iterations of 16 MFMAs per wave.  100 + {0, 2, 4} runs the loop on 16 accumulator
- * tiles per wave (256 registers, so that only one wave fits a SIMD) instead of 4.  `scratch` is device memory of at least
+ * tiles per wave (256 registers, so that only one wave fits a SIMD) instead of 4; 200 + {0, 2} does
+ * the same with 4 consecutive MFMAs into each tile, every one depending on the one before (`iters`
+ * must then be a multiple of 4; UCD_E_INVALID otherwise).  `scratch` is device memory of at least
  * blocks*1024 bytes (receives checksums).  *flops receives the MFMA flops one launch executes;
  * the caller times the launch. */
 int ucd_mfma_probe(int valu_per_mfma, int blocks, int iters, void *scratch, size_t scratch_bytes,

@@ -18,6 +18,10 @@
 //   D[a*a][K][ld]     D = A dy A^T per m x m tile of dy
 //   Mw[a*a][K][C]     a*a GEMMs  Mw_xi = D_xi[K x b*T] * V_xi^T[b*T x C]  (reduction split, atomics)
 //   dw                = beta*dw + G^T Mw G per (k, c)
+#include <cstdlib>
+#include <type_traits>
+#include <utility>
+
 #include "gemm_launch.hpp"
 #include "kernels.h"
 
@@ -161,11 +165,12 @@ size_t winograd_ws_bytes(const Dims &d, int op, int b, int mt)
 // U[xi][ci][co] = (G g G^T)[xi], one thread per (ci, co) filter; pads co up to Mo4 with zeros.
 template <class E, int MT>
 __global__ __launch_bounds__(256) void wino_filter_kernel(const void *__restrict__ w, float *__restrict__ U, int Ci,
-                                                          int Co, int Mo4, int transposed)
+                                                          int Co, int Mo4, int transposed, int Cpad)
 {
+    // a plane of U has Cpad >= Ci rows; rows past Ci are written as zeros
     constexpr int A = Wino<MT>::A;
     const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i >= Ci * Mo4) return;
+    if (i >= Cpad * Mo4) return;
     const int ci = i / Mo4, co = i - ci * Mo4;
     float t[A][3];  // G g, column by column
 #pragma unroll
@@ -174,7 +179,7 @@ __global__ __launch_bounds__(256) void wino_filter_kernel(const void *__restrict
 #pragma unroll
         for (int r = 0; r < 3; ++r) {
             float v = 0.f;
-            if (co < Co)
+            if (co < Co && ci < Ci)
                 v = transposed ? Elem<E>::get(w, ((size_t)(ci * Co + co) * 3 + (2 - r)) * 3 + (2 - s))
                                : Elem<E>::get(w, ((size_t)(co * Ci + ci) * 3 + r) * 3 + s);
             g[r] = v;
@@ -183,7 +188,7 @@ __global__ __launch_bounds__(256) void wino_filter_kernel(const void *__restrict
 #pragma unroll
         for (int r = 0; r < A; ++r) t[r][s] = u[r];
     }
-    const size_t plane = (size_t)Ci * Mo4;
+    const size_t plane = (size_t)Cpad * Mo4;
 #pragma unroll
     for (int r = 0; r < A; ++r) {
         float u[A];
@@ -294,7 +299,7 @@ static hipError_t winograd_run(const Dims &d, int op, int b, const void *in, con
     } else if (log) log->add("wino_filter_kernel");
     else
         wino_filter_kernel<E, MT><<<(unsigned)((g.Ci * g.Mo4 + 255) / 256), 256, 0, s>>>(w, U, g.Ci, g.Co, g.Mo4,
-                                                                                      g.transposed ? 1 : 0);
+                                                                                      g.transposed ? 1 : 0, g.Ci);
     hipError_t e = log ? hipSuccess : hipGetLastError();
     if (e != hipSuccess) return e;
 
@@ -324,16 +329,28 @@ static hipError_t winograd_run(const Dims &d, int op, int b, const void *in, con
 }
 
 // ---- F(2x2,3x3) with both data transforms fused into the GEMM kernel --------------------------------
-// The only workspace is the transformed filter U (64*Ci*Mo4 bytes, whatever the micro-batch), so the
-// whole mini-batch can run in one launch under a small workspace limit.  A workgroup owns a block of
-// 64 output channels x 64 tiles for all 16 transform points: each of its four waves keeps 16
-// accumulator tiles of 32 channels x 32 tiles (256 registers, one wave per SIMD).  Per step of 4
-// input channels every thread fetches the 4x4 input patch of one (tile, channel), transforms it in
-// registers (32 additions) and writes its 16 values to LDS; U's slice for the step is copied from
-// the workspace to LDS; then 32 MFMAs per wave (16 points x 2 channel pairs).  After the last
-// channel the 16 accumulators of an (output channel, tile) are combined by A^T . A in registers and
-// the 2x2 outputs stored.  Global loads run two steps ahead of the MFMAs (one register set, two LDS
-// buffers), and the step's memory and transform work is dealt out behind individual MFMAs.
+// The only workspace is the transformed filter U (64*Ci'*Mo4 bytes with Ci' = Ci rounded up to the
+// channel step, whatever the micro-batch), so the whole mini-batch can run in one launch under a
+// small workspace limit.  A workgroup owns a block of 64 output channels x 64 tiles for all 16
+// transform points: each of its four waves keeps 16 accumulator tiles of 32 channels x 32 tiles
+// (256 registers, one wave per SIMD).  Per step of kFuC input channels every thread fetches the 4x4
+// input patches of kFuC/4 (tile, channel) pairs, transforms them in registers (32 additions each)
+// and writes their 16 values to LDS; U's slice for the step is copied from the workspace to LDS
+// (rows of channels past Ci are zero there); then 16 points x kFuC/2 channel pairs of MFMAs per
+// wave.  After the last channel the 16 accumulators of an (output channel, tile) are combined by
+// A^T . A in registers and the 2x2 outputs stored.  Global loads run two steps ahead of the MFMAs
+// (one register set, two LDS buffers), and the step's memory and transform work is dealt out behind
+// individual MFMAs.
+//
+// Sixteen 4-byte loads per patch, lanes 8 bytes apart, cost the vector memory pipeline ~34 cache
+// accesses per wave instruction (the patch loads of AlexNet conv4 alone keep it busy for half of the
+// kernel's time).  PW >= 0 (fp32 tensors, horizontal padding PW = 0 or 1) fetches a patch row with
+// one 12- or 16-byte load instead (~21 accesses), starting at column 2*tw (never negative, so no
+// address before the tensor is formed): that window holds patch columns PW.. of the row; for PW = 1
+// the patch's first column is the second element of the window of the tile to the left, i.e. of
+// the lane below (one cross-lane move; lane 0 fetches it with a load of its own, tiles in the
+// first tile column take 0).  Window elements past the end of the row belong to the next row and
+// are replaced by 0.  PW = -1 is the element-wise form (any padding, bf16).
 #ifndef UCD_FUSED_CHANNELS
 #define UCD_FUSED_CHANNELS 8
 #endif
@@ -341,6 +358,18 @@ constexpr int kFuK = 64, kFuT = 64, kFuC = UCD_FUSED_CHANNELS;  // block: channe
 constexpr int kFuNP = kFuC / 4;   // input patches per thread and step (channel = wave + 4h)
 constexpr int kFuNU = kFuC;       // float4 pieces of the step's U slice per thread
 constexpr int kFuPairs = kFuC / 2;
+
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F &f, std::integer_sequence<int, I...>)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>), in order
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &f)
+{
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
 
 struct FusedParams {
     const void *in;
@@ -350,12 +379,15 @@ struct FusedParams {
     WinoGeom g;
     FastDiv divT, divTW;
     int n_tiles, k_blocks;
+    int ci_pad;   // rows of a plane of U: Ci rounded up to the channel step
 };
 
-template <class E>
+template <class E, int PW>
 __global__ __launch_bounds__(256) void wino_fused_kernel(FusedParams p)
 {
     constexpr uint32_t EB = Elem<E>::kBytes;
+    constexpr bool kRows = PW >= 0;   // row-vector patch loads
+    static_assert(!kRows || EB == 4, "row loads are written for fp32 tensors");
     __shared__ __attribute__((aligned(16))) float Us[2][16][kFuC][kFuK];
     __shared__ __attribute__((aligned(16))) float Vs[2][16][kFuC][kFuT];
     const WinoGeom &g = p.g;
@@ -374,7 +406,9 @@ __global__ __launch_bounds__(256) void wino_fused_kernel(FusedParams p)
     const __amdgpu_buffer_rsrc_t ru = make_rsrc_bytes(p.U, 0, p.u_bytes);
 
     // producer role: the 4x4 patch of tile `lane` of the block, for channels wave, wave + 4, ... of the step
-    uint32_t voff[16];
+    uint32_t voff[kRows ? 4 : 16];   // element-wise: one offset per pixel; rows: the window start of each row
+    uint32_t xoff[4];                // rows, PW = 1: the patch's first column, fetched by lane 0 only
+    bool first_col = false, ok1 = true, ok2 = true, ok3 = true;  // rows: tile column 0; window elements inside the row
     {
         const int j = t0 + lane;
         uint32_t n = 0, t, th = 0, tw = 0;
@@ -384,14 +418,28 @@ __global__ __launch_bounds__(256) void wino_fused_kernel(FusedParams p)
             p.divTW.divmod(t, th, tw);
         }
         const int h0 = 2 * (int)th - g.pad_h, w0 = 2 * (int)tw - g.pad_w;
+        if constexpr (kRows) {
+            const int ws = 2 * (int)tw;   // = w0 + PW
+            first_col = tw == 0;
+            ok1 = ws + 1 < g.Wi; ok2 = ws + 2 < g.Wi; ok3 = ws + 3 < g.Wi;
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const int h = h0 + r, w = w0 + c;
-                const bool ok = live && (unsigned)h < (unsigned)g.Hi && (unsigned)w < (unsigned)g.Wi;
-                voff[4 * r + c] = ok ? EB * (uint32_t)(((int)n * g.Ci * g.Hi + h) * g.Wi + w) : kOob;
+            for (int r = 0; r < 4; ++r) {
+                const int h = h0 + r;
+                const bool ok = live && (unsigned)h < (unsigned)g.Hi;
+                const uint32_t row = EB * (uint32_t)(((int)n * g.Ci * g.Hi + h) * g.Wi + ws);
+                voff[r] = ok ? row : kOob;
+                xoff[r] = ok && PW == 1 && lane == 0 && tw > 0 ? row - EB : kOob;
             }
+        } else {
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const int h = h0 + r, w = w0 + c;
+                    const bool ok = live && (unsigned)h < (unsigned)g.Hi && (unsigned)w < (unsigned)g.Wi;
+                    voff[4 * r + c] = ok ? EB * (uint32_t)(((int)n * g.Ci * g.Hi + h) * g.Wi + w) : kOob;
+                }
+        }
     }
     // U slice of a step: 16 points x kFuC channels x 64 output channels, as float4: piece id = tid + 256*i
     // -> row = id / 16 = point * kFuC + channel, 4 output channels from 4 * (id % 16)
@@ -400,27 +448,66 @@ __global__ __launch_bounds__(256) void wino_fused_kernel(FusedParams p)
     for (int i = 0; i < kFuNU; ++i) {
         const int id = tid + 256 * i, row = id >> 4, q = id & 15;
         const int xi = row / kFuC, c = row % kFuC, k = k0 + 4 * q;
-        uoff[i] = k < g.Mo4 ? 4u * (uint32_t)((xi * g.Ci + c) * g.Mo4 + k) : kOob;
+        uoff[i] = k < g.Mo4 ? 4u * (uint32_t)((xi * p.ci_pad + c) * g.Mo4 + k) : kOob;
     }
 
-    float d[kFuNP][16];  // the thread's input patches of the step after the one in LDS
+    // the thread's input patches of the step after the one in LDS: 16 pixels each, or per row a window
+    // of 3 (PW = 1) or 4 (PW = 0) pixels in d[h][4r..] and, for PW = 1, lane 0's first column in dx
+    float d[kFuNP][16];
+    float dx[kFuNP][4];
     f32x4 uq[kFuNU];     // and its share of that step's U slice
     // a channel past the last one gets a scalar offset that pushes every address out of range
-    auto fetch_pixel = [&](int c0, int h, int i) {
+    auto chan_off = [&](int c0, int h) {
         const int c = c0 + wave + 4 * h;
-        const uint32_t so = c < g.Ci ? EB * (uint32_t)(c * g.Hi * g.Wi) : kOob;
-        d[h][i] = Elem<E>::load(rin, voff[i], so);
+        return c < g.Ci ? EB * (uint32_t)(c * g.Hi * g.Wi) : kOob;
+    };
+    constexpr int kPatchLoads = !kRows ? 16 : PW == 1 ? 8 : 4;   // load instructions per patch
+    auto fetch_piece = [&](int c0, int h, int i) {   // i < kPatchLoads
+        const uint32_t so = chan_off(c0, h);
+        if constexpr (!kRows) {
+            d[h][i] = Elem<E>::load(rin, voff[i], so);
+        } else if constexpr (PW == 0) {
+            const f32x4 q = buf_load4(rin, voff[i], so);
+            d[h][4 * i] = q.x; d[h][4 * i + 1] = q.y; d[h][4 * i + 2] = q.z; d[h][4 * i + 3] = q.w;
+        } else if (i < 4) {
+            const auto q = __builtin_amdgcn_raw_buffer_load_b96(rin, (int)voff[i], (int)so, 0);
+#pragma unroll
+            for (int c = 0; c < 3; ++c) d[h][4 * i + 1 + c] = __uint_as_float(q[c]);
+        } else {
+            dx[h][i - 4] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rin, (int)xoff[i - 4], (int)so, 0));
+        }
     };
     auto fetch_patch = [&](int c0, int h) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) fetch_pixel(c0, h, i);
+        for (int i = 0; i < kPatchLoads; ++i) fetch_piece(c0, h, i);
     };
-    auto fetch_u = [&](int c0, int i) {
-        const int c_in_step = ((tid + 256 * i) >> 4) % kFuC;
-        uq[i] = buf_load4(ru, c0 + c_in_step < g.Ci ? uoff[i] + 4u * (uint32_t)(c0 * g.Mo4) : kOob);
+    // rows: the windows as loaded become the patch (first column from the lane below, zeros outside the row)
+    auto finish_patch = [&](int h) {
+        if constexpr (kRows) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                if constexpr (PW == 1) {
+                    // wave_shr:1: every lane takes the value of the lane below; lane 0 keeps `old`
+                    const int left = __builtin_amdgcn_update_dpp((int)__float_as_uint(dx[h][r]),
+                                                                 (int)__float_as_uint(d[h][4 * r + 2]), 0x138, 0xf, 0xf, false);
+                    d[h][4 * r] = first_col ? 0.f : __uint_as_float((uint32_t)left);
+                    d[h][4 * r + 2] = ok1 ? d[h][4 * r + 2] : 0.f;
+                    d[h][4 * r + 3] = ok2 ? d[h][4 * r + 3] : 0.f;
+                } else {
+                    d[h][4 * r + 1] = ok1 ? d[h][4 * r + 1] : 0.f;
+                    d[h][4 * r + 2] = ok2 ? d[h][4 * r + 2] : 0.f;
+                    d[h][4 * r + 3] = ok3 ? d[h][4 * r + 3] : 0.f;
+                }
+            }
+        }
     };
+    // U's planes have ci_pad rows (zero past Ci), so every step is whole and its part of the address is
+    // a scalar offset; a load for a step past the last one reads the next point's rows or out of range
+    // and is never used
+    auto fetch_u = [&](int c0, int i) { uq[i] = buf_load4(ru, uoff[i], 4u * (uint32_t)(c0 * g.Mo4)); };
     // B^T d B of patch h into LDS buffer `buf`: points 4r .. 4r+3 from row r of B^T d
     auto store_v = [&](int buf, int h) {
+        finish_patch(h);
         float tr[16];
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
@@ -439,9 +526,11 @@ __global__ __launch_bounds__(256) void wino_fused_kernel(FusedParams p)
             Vs[buf][4 * r + 3][wave + 4 * h][lane] = a1 - a3;
         }
     };
+    // piece i goes to row (tid >> 4) + 16 i of the buffer's [16 * kFuC][64] slab: one address per
+    // thread, the pieces 1024 floats apart (immediate offsets)
+    const int u_slot = (tid >> 4) * kFuK + 4 * (tid & 15);
     auto store_u = [&](int buf, int i) {
-        const int id = tid + 256 * i, row = id >> 4, q = id & 15;
-        *reinterpret_cast<f32x4 *>(&Us[buf][row / kFuC][row % kFuC][4 * q]) = uq[i];
+        *reinterpret_cast<f32x4 *>(&Us[buf][0][0][0] + u_slot + 1024 * i) = uq[i];
     };
 
     f32x16 acc[16];
@@ -482,32 +571,36 @@ __global__ __launch_bounds__(256) void wino_fused_kernel(FusedParams p)
         __builtin_amdgcn_sched_barrier(0);
         __builtin_amdgcn_s_setprio(UCD_MFMA_PRIO);
         constexpr int kMfmas = 16 * kFuPairs;
-#pragma unroll
-        for (int m = 0; m < kMfmas; ++m) {
-            const int xi = m / kFuPairs, q = m % kFuPairs;
+        // One MFMA and what is dealt out behind it; m is a compile-time constant so that every slot
+        // holds its own piece of work only (a loop left to the unroller keeps all pieces in every
+        // iteration until it has unrolled, and gives up on a body of that size).
+        auto slot = [&](auto M) {
+            constexpr int m = decltype(M)::value;
+            constexpr int xi = m / kFuPairs, q = m % kFuPairs;
             acc[xi] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[xi & 1][q], b[xi & 1][q], acc[xi], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
-            if (q == 0 && xi + 1 < 16) read_ops(xi + 1);
+            if constexpr (q == 0 && xi + 1 < 16) read_ops(xi + 1);
             // The registers hold step c0 + kFuC as loaded: it is transformed into the other LDS buffer
             // and every register reloaded, as soon as it is free, with step c0 + 2 kFuC.  One piece of
             // that work behind each MFMA, and never more than one global load: a burst of loads blocks
             // the wave at the memory pipeline's queue, and with one wave per SIMD nothing else would
             // feed the matrix pipe meanwhile.
-            constexpr int kPatchSlots = 17;  // 1 transform + 16 loads
-            if (m >= 1 && m < 1 + kPatchSlots * kFuNP) {
-                const int h = (m - 1) / kPatchSlots, i = (m - 1) % kPatchSlots;
-                if (i == 0) store_v(buf ^ 1, h);
-                else fetch_pixel(c0 + 2 * kFuC, h, i - 1);
+            constexpr int kPatchSlots = 1 + kPatchLoads;  // 1 transform + the patch's loads
+            if constexpr (m >= 1 && m < 1 + kPatchSlots * kFuNP) {
+                constexpr int h = (m - 1) / kPatchSlots, i = (m - 1) % kPatchSlots;
+                if constexpr (i == 0) store_v(buf ^ 1, h);
+                else fetch_piece(c0 + 2 * kFuC, h, i - 1);
             }
             constexpr int kUStart = 1 + kPatchSlots * kFuNP;
-            if (m >= kUStart && m < kUStart + 2 * kFuNU) {
-                const int i = (m - kUStart) / 2;
-                if ((m - kUStart) % 2 == 0) store_u(buf ^ 1, i);
+            if constexpr (m >= kUStart && m < kUStart + 2 * kFuNU) {
+                constexpr int i = (m - kUStart) / 2;
+                if constexpr ((m - kUStart) % 2 == 0) store_u(buf ^ 1, i);
                 else fetch_u(c0 + 2 * kFuC, i);
             }
             static_assert(kUStart + 2 * kFuNU <= 16 * kFuPairs, "the step's work fits behind its MFMAs");
             __builtin_amdgcn_sched_barrier(0);
-        }
+        };
+        static_for<kMfmas>(slot);
         __builtin_amdgcn_s_setprio(0);
         __syncthreads();
         buf ^= 1;
@@ -542,10 +635,12 @@ __global__ __launch_bounds__(256) void wino_fused_kernel(FusedParams p)
     }
 }
 
+static int fused_ci_pad(const WinoGeom &g) { return (g.Ci + kFuC - 1) / kFuC * kFuC; }
+
 size_t winograd_fused_ws_bytes(const Dims &d, int op)
 {
     const WinoGeom g = geom(d, op, 1, 2);
-    return (size_t)64 * g.Ci * g.Mo4;
+    return (size_t)64 * fused_ci_pad(g) * g.Mo4;
 }
 
 template <class E>
@@ -558,14 +653,15 @@ static hipError_t winograd_fused_run(const Dims &d, int op, int b, const void *i
         // U of this filter is still in the workspace from the previous micro-batch
     } else if (log) log->add("wino_filter_kernel");
     else
-        wino_filter_kernel<E, 2><<<(unsigned)((g.Ci * g.Mo4 + 255) / 256), 256, 0, s>>>(w, ws, g.Ci, g.Co, g.Mo4,
-                                                                                     g.transposed ? 1 : 0);
+        wino_filter_kernel<E, 2><<<(unsigned)((fused_ci_pad(g) * g.Mo4 + 255) / 256), 256, 0, s>>>(
+            w, ws, g.Ci, g.Co, g.Mo4, g.transposed ? 1 : 0, fused_ci_pad(g));
     hipError_t e = log ? hipSuccess : hipGetLastError();
     if (e != hipSuccess) return e;
     FusedParams p{};
     p.in = in; p.U = ws; p.out = out;
     p.in_bytes = (uint32_t)(Elem<E>::kBytes * (size_t)b * g.Ci * g.Hi * g.Wi);
-    p.u_bytes = (uint32_t)((size_t)64 * g.Ci * g.Mo4);
+    p.ci_pad = fused_ci_pad(g);
+    p.u_bytes = (uint32_t)((size_t)64 * p.ci_pad * g.Mo4);
     p.g = g; p.divT = FastDiv(g.T); p.divTW = FastDiv(g.TW);
     p.n_tiles = b * g.T;
     p.k_blocks = (g.Co + kFuK - 1) / kFuK;
@@ -575,7 +671,16 @@ static hipError_t winograd_fused_run(const Dims &d, int op, int b, const void *i
                  std::to_string(2.0 * 16 * g.Co * (double)p.n_tiles * g.Ci));
         return hipSuccess;
     }
-    wino_fused_kernel<E><<<blocks, 256, 0, s>>>(p);
+    // row-vector patch loads: fp32 tensors, horizontal padding 0 or 1 (UCD_FUSED_ELEMENTWISE=1 in the
+    // environment keeps the element-wise loads, for comparison)
+    static const bool elementwise = getenv("UCD_FUSED_ELEMENTWISE") != nullptr;
+    bool rows = false;
+    if constexpr (std::is_same_v<E, float>) {
+        rows = !elementwise && (g.pad_w == 0 || g.pad_w == 1);
+        if (rows && g.pad_w == 0) wino_fused_kernel<E, 0><<<blocks, 256, 0, s>>>(p);
+        else if (rows) wino_fused_kernel<E, 1><<<blocks, 256, 0, s>>>(p);
+    }
+    if (!rows) wino_fused_kernel<E, -1><<<blocks, 256, 0, s>>>(p);
     return hipGetLastError();
 }
 

@@ -124,10 +124,11 @@ struct NoSetup {
 
 constexpr uint32_t kOob = 0x80000000u;
 
-__device__ __forceinline__ f32x4 buf_load4(__amdgpu_buffer_rsrc_t r, uint32_t byte_off)
+// 16 bytes at byte_off + scalar_off (the range check covers the sum)
+__device__ __forceinline__ f32x4 buf_load4(__amdgpu_buffer_rsrc_t r, uint32_t byte_off, uint32_t scalar_off = 0)
 {
     typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-    const u32x4 q = __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, 0);
+    const u32x4 q = __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, (int)scalar_off, 0);
     f32x4 v;
     v.x = __uint_as_float(q.x); v.y = __uint_as_float(q.y); v.z = __uint_as_float(q.z); v.w = __uint_as_float(q.w);
     return v;
