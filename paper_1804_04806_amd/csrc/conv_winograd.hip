@@ -382,7 +382,7 @@ struct FusedParams {
     int ci_pad;   // rows of a plane of U: Ci rounded up to the channel step
 };
 
-template <class E, int PW>
+template <class E, int PW, bool ODD_W = false>
 __global__ __launch_bounds__(256) void wino_fused_kernel(FusedParams p)
 {
     constexpr uint32_t EB = Elem<E>::kBytes;
@@ -487,12 +487,16 @@ __global__ __launch_bounds__(256) void wino_fused_kernel(FusedParams p)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 if constexpr (PW == 1) {
+                    // Window = columns 2tw, 2tw+1, 2tw+2.  With an even width only the last one can lie
+                    // past the row (in the last tile column); with an odd width the last two can, and
+                    // the tile to the left of a first-column tile is then a last-column tile whose
+                    // second window element has just been zeroed: the cross-lane move delivers the 0.
+                    if constexpr (ODD_W) d[h][4 * r + 2] = ok1 ? d[h][4 * r + 2] : 0.f;
+                    d[h][4 * r + 3] = ok2 ? d[h][4 * r + 3] : 0.f;
                     // wave_shr:1: every lane takes the value of the lane below; lane 0 keeps `old`
                     const int left = __builtin_amdgcn_update_dpp((int)__float_as_uint(dx[h][r]),
                                                                  (int)__float_as_uint(d[h][4 * r + 2]), 0x138, 0xf, 0xf, false);
-                    d[h][4 * r] = first_col ? 0.f : __uint_as_float((uint32_t)left);
-                    d[h][4 * r + 2] = ok1 ? d[h][4 * r + 2] : 0.f;
-                    d[h][4 * r + 3] = ok2 ? d[h][4 * r + 3] : 0.f;
+                    d[h][4 * r] = ODD_W ? __uint_as_float((uint32_t)left) : first_col ? 0.f : __uint_as_float((uint32_t)left);
                 } else {
                     d[h][4 * r + 1] = ok1 ? d[h][4 * r + 1] : 0.f;
                     d[h][4 * r + 2] = ok2 ? d[h][4 * r + 2] : 0.f;
@@ -557,17 +561,21 @@ __global__ __launch_bounds__(256) void wino_fused_kernel(FusedParams p)
     for (int c0 = 0; c0 < g.Ci; c0 += kFuC) {
         const float *ua = &Us[buf][0][lhi][wk * 32 + l32];
         const float *vb = &Vs[buf][0][lhi][wt * 32 + l32];
-        // operands of (point xi, channel pair q): rows 2q + lhi of the point's slab; a point's operands
-        // are read while the previous point's MFMAs run
-        float a[2][kFuPairs], b[2][kFuPairs];
-        auto read_ops = [&](int xi) {
+        // Operands of (point xi, channel pair q): rows 2q + lhi of the point's slab.  They are read in
+        // units of two channel pairs (one two-address LDS read per operand), kAhead units before the
+        // unit's MFMAs: four units of registers, one in use, three on their way.
+        constexpr int kUnits = 16 * kFuPairs / 2, kAhead = 3;
+        float a[kAhead + 1][2], b[kAhead + 1][2];
+        auto read_unit = [&](int u) {
+            const int xi = u / (kFuPairs / 2), q0 = 2 * (u % (kFuPairs / 2));
 #pragma unroll
-            for (int q = 0; q < kFuPairs; ++q) {
-                a[xi & 1][q] = ua[(xi * kFuC + 2 * q) * kFuK];
-                b[xi & 1][q] = vb[(xi * kFuC + 2 * q) * kFuT];
+            for (int q = 0; q < 2; ++q) {
+                a[u % (kAhead + 1)][q] = ua[(xi * kFuC + 2 * (q0 + q)) * kFuK];
+                b[u % (kAhead + 1)][q] = vb[(xi * kFuC + 2 * (q0 + q)) * kFuT];
             }
         };
-        read_ops(0);
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) read_unit(u);
         __builtin_amdgcn_sched_barrier(0);
         __builtin_amdgcn_s_setprio(UCD_MFMA_PRIO);
         constexpr int kMfmas = 16 * kFuPairs;
@@ -576,10 +584,10 @@ __global__ __launch_bounds__(256) void wino_fused_kernel(FusedParams p)
         // iteration until it has unrolled, and gives up on a body of that size).
         auto slot = [&](auto M) {
             constexpr int m = decltype(M)::value;
-            constexpr int xi = m / kFuPairs, q = m % kFuPairs;
-            acc[xi] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[xi & 1][q], b[xi & 1][q], acc[xi], 0, 0, 0);
+            constexpr int xi = m / kFuPairs, u = m / 2;
+            acc[xi] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u % (kAhead + 1)][m % 2], b[u % (kAhead + 1)][m % 2], acc[xi], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
-            if constexpr (q == 0 && xi + 1 < 16) read_ops(xi + 1);
+            if constexpr (m % 2 == 0 && u + kAhead < kUnits) read_unit(u + kAhead);
             // The registers hold step c0 + kFuC as loaded: it is transformed into the other LDS buffer
             // and every register reloaded, as soon as it is free, with step c0 + 2 kFuC.  One piece of
             // that work behind each MFMA, and never more than one global load: a burst of loads blocks
@@ -678,7 +686,8 @@ static hipError_t winograd_fused_run(const Dims &d, int op, int b, const void *i
     if constexpr (std::is_same_v<E, float>) {
         rows = !elementwise && (g.pad_w == 0 || g.pad_w == 1);
         if (rows && g.pad_w == 0) wino_fused_kernel<E, 0><<<blocks, 256, 0, s>>>(p);
-        else if (rows) wino_fused_kernel<E, 1><<<blocks, 256, 0, s>>>(p);
+        else if (rows && g.Wi % 2) wino_fused_kernel<E, 1, true><<<blocks, 256, 0, s>>>(p);
+        else if (rows) wino_fused_kernel<E, 1, false><<<blocks, 256, 0, s>>>(p);
     }
     if (!rows) wino_fused_kernel<E, -1><<<blocks, 256, 0, s>>>(p);
     return hipGetLastError();
