@@ -780,7 +780,7 @@ __global__ __launch_bounds__(256) void wino_dw_kernel(const float *__restrict__ 
 // wave (16 points x 4 tile pairs).  Chunks meet in Mw through fp32 atomics; dw = beta*dw + G^T Mw G
 // is wino_dw_kernel's.
 constexpr int kFwT = 8;                 // tile positions per step (the MFMAs' reduction rows)
-constexpr int kFwLd = 64 + 8;           // LDS row stride: 8 tiles x 8 channels of a wave's store hit every bank twice
+constexpr int kFwLd = 64;               // LDS row stride; column c of tile position t sits at c ^ 4t (see kernel)
 constexpr int kFwPairs = kFwT / 2;
 
 struct FusedFilterParams {
@@ -817,8 +817,13 @@ __global__ __launch_bounds__(256) void wino_fused_filter_kernel(FusedFilterParam
     const __amdgpu_buffer_rsrc_t rdy = make_rsrc_bytes(p.dy, 0, p.dy_bytes);
 
     // producer role: tile position tid % 8 of the group, channel tid / 8 (and + 32) of both blocks;
-    // offsets within image 0 (kOob: outside the image, or no such tile / channel)
+    // offsets within image 0 (kOob: outside the image, or no such tile / channel).
+    // LDS slabs are [point][tile position][64 channels] with channel c of tile position t stored at
+    // column c ^ 4t: a wave's store (8 tile positions x 8 channels) then covers all banks evenly, and
+    // with a row stride of 64 every operand read is one base register (per tile pair) plus an
+    // immediate offset.
     const int ptile = tid & 7, pch = tid >> 3;
+    const int pcol = pch ^ (4 * ptile);   // + 32 h: bit 5 is not touched by the swizzle
     uint32_t vx[2][16], vd[2][4];
     {
         const int t = grp * kFwT + ptile;
@@ -869,10 +874,10 @@ __global__ __launch_bounds__(256) void wino_fused_filter_kernel(FusedFilterParam
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const float a0 = tr[4 * r], a1 = tr[4 * r + 1], a2 = tr[4 * r + 2], a3 = tr[4 * r + 3];
-            Vs[buf][4 * r + 0][ptile][pch + 32 * h] = a0 - a2;
-            Vs[buf][4 * r + 1][ptile][pch + 32 * h] = a1 + a2;
-            Vs[buf][4 * r + 2][ptile][pch + 32 * h] = a2 - a1;
-            Vs[buf][4 * r + 3][ptile][pch + 32 * h] = a1 - a3;
+            Vs[buf][4 * r + 0][ptile][pcol + 32 * h] = a0 - a2;
+            Vs[buf][4 * r + 1][ptile][pcol + 32 * h] = a1 + a2;
+            Vs[buf][4 * r + 2][ptile][pcol + 32 * h] = a2 - a1;
+            Vs[buf][4 * r + 3][ptile][pcol + 32 * h] = a1 - a3;
         }
     };
     auto store_d = [&](int buf, int h) {  // A dy A^T of tile h: rows (z0, z0+z1, z0-z1, -z1) of A z, then the same on columns
@@ -880,10 +885,10 @@ __global__ __launch_bounds__(256) void wino_fused_filter_kernel(FusedFilterParam
         const float t[4][2] = {{z00, z01}, {z00 + z10, z01 + z11}, {z00 - z10, z01 - z11}, {-z10, -z11}};
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            Ds[buf][4 * r + 0][ptile][pch + 32 * h] = t[r][0];
-            Ds[buf][4 * r + 1][ptile][pch + 32 * h] = t[r][0] + t[r][1];
-            Ds[buf][4 * r + 2][ptile][pch + 32 * h] = t[r][0] - t[r][1];
-            Ds[buf][4 * r + 3][ptile][pch + 32 * h] = -t[r][1];
+            Ds[buf][4 * r + 0][ptile][pcol + 32 * h] = t[r][0];
+            Ds[buf][4 * r + 1][ptile][pcol + 32 * h] = t[r][0] + t[r][1];
+            Ds[buf][4 * r + 2][ptile][pcol + 32 * h] = t[r][0] - t[r][1];
+            Ds[buf][4 * r + 3][ptile][pcol + 32 * h] = -t[r][1];
         }
     };
 
@@ -914,17 +919,22 @@ __global__ __launch_bounds__(256) void wino_fused_filter_kernel(FusedFilterParam
     }
     __syncthreads();
 
+    int col_q[kFwPairs];   // the lane's column within its wave's 32, as stored for tile position 2q + lhi
+#pragma unroll
+    for (int q = 0; q < kFwPairs; ++q) col_q[q] = l32 ^ (4 * (2 * q + lhi));
+
     int buf = 0;
     for (int n = n_begin; n < n_end; ++n) {
-        const float *da = &Ds[buf][0][lhi][wk * 32 + l32];
-        const float *vb = &Vs[buf][0][lhi][wc * 32 + l32];
-        // operands of (point xi, tile pair q): rows 2q + lhi of the point's slab, read one point ahead
+        // operands of (point xi, tile pair q): rows 2q + lhi of the point's slab (columns swizzled by
+        // 4 (2q + lhi)), read one point ahead
+        const float *da = &Ds[buf][0][lhi][wk * 32];
+        const float *vb = &Vs[buf][0][lhi][wc * 32];
         float a[2][kFwPairs], b[2][kFwPairs];
         auto read_ops = [&](int xi) {
 #pragma unroll
             for (int q = 0; q < kFwPairs; ++q) {
-                a[xi & 1][q] = da[(xi * kFwT + 2 * q) * kFwLd];
-                b[xi & 1][q] = vb[(xi * kFwT + 2 * q) * kFwLd];
+                a[xi & 1][q] = da[(xi * kFwT + 2 * q) * kFwLd + col_q[q]];
+                b[xi & 1][q] = vb[(xi * kFwT + 2 * q) * kFwLd + col_q[q]];
             }
         };
         read_ops(0);
