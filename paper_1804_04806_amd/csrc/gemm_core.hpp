@@ -1917,10 +1917,16 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel_bf16v(AParams pa, BParam
         }
         __syncthreads();
     };
-    for (int k0 = k_begin; k0 < k_end; k0 += 2 * kDeepBK) {
+    // steps in pairs (the two LDS buffers and register sets swap roles), an odd last one after the
+    // loop: a condition between the two steps of the loop body makes the register allocator move
+    // accumulators between register files in every iteration
+    const int n_steps = (k_end - k_begin + kDeepBK - 1) / kDeepBK;
+    int k0 = k_begin;
+    for (int s = 0; s + 2 <= n_steps; s += 2, k0 += 2 * kDeepBK) {
         step(lds[0], lds[1], ra1, rb1, k0);
-        if (k0 + kDeepBK < k_end) step(lds[1], lds[0], ra0, rb0, k0 + kDeepBK);
+        step(lds[1], lds[0], ra0, rb0, k0 + kDeepBK);
     }
+    if (n_steps & 1) step(lds[0], lds[1], ra1, rb1, k0);
 
     write_tile<T, Epi, false>(pe, acc, M, N, m0, n0, wm0, wn0, l32, lhi, false);
 }
