@@ -153,6 +153,10 @@ static hipError_t implicit_fwd_t(const Dims &d, int b, const void *x, const void
         }
     }
     g.tail_split = !d.det;
+    // without padding every tap of every output pixel lies inside x: the loader without border masks
+    // (filters of more than one tap: 1x1 layers are bound by memory, not by the loader)
+    if (d.ph == 0 && d.pw == 0 && d.R * d.S > 1)
+        return launch_gemm<L::template KLane0, L::template GatherNLaneFree, EpiNCHWT<E>, true>(pa, pb, pe, g, s);
     if (d.R * d.S <= 31)
         return launch_gemm<L::template KLane0, L::template GatherNLane, EpiNCHWT<E>, true>(pa, pb, pe, g, s);
     return launch_gemm<L::template KLane0, L::template GatherNLaneBig, EpiNCHWT<E>, true>(pa, pb, pe, g, s);
@@ -454,6 +458,8 @@ static hipError_t implicit_bwd_filter_t(const Dims &d, int b, const void *x, con
     EpiDenseParams pe{dw, d.crs()};
     if (d.R * d.S <= 31)  // per-row state in an LDS table
         return launch_gemm<L::template DyTab, L::template XTab, EpiAtomic, true>(pa, pb, pe, g, s);
+    if (d.ph == 0 && d.pw == 0)  // no padding: every tap of every pixel is inside x
+        return launch_gemm<L::template DyKLane, L::template XKLaneFree, EpiAtomic, true>(pa, pb, pe, g, s);
     return launch_gemm<L::template DyKLane, L::template XKLane, EpiAtomic, true>(pa, pb, pe, g, s);
 }
 

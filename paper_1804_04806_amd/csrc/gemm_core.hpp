@@ -199,11 +199,14 @@ struct GatherParams {
 };
 
 // SMALL: at most 31 taps, one mask bit per (r, s); otherwise one mask per axis (R, S <= 31).
-template <int TD, bool SMALL, class E = float>
+// NOMASK: every tap of every tile position lies inside the tensor (a layer without padding): the
+// per-thread offset is used as it is, and a row past the end of the reduction is pushed out of
+// range through the scalar offset: no vector instruction per element at all.
+template <int TD, bool SMALL, class E = float, bool NOMASK = false>
 struct GatherNLaneT : NoSetup {
     static constexpr uint32_t EB = Elem<E>::kBytes;
     static constexpr bool kBf16 = std::is_same<E, bf16>::value;
-    static std::string name() { return std::string(SMALL ? "GatherNLane<taps<=31>" : "GatherNLane<taps>31>") + Elem<E>::tag(); }
+    static std::string name() { return std::string(NOMASK ? "GatherNLane<no padding>" : SMALL ? "GatherNLane<taps<=31>" : "GatherNLane<taps>31>") + Elem<E>::tag(); }
     static_assert(TD >= 64, "a wave must cover one reduction row");
     static constexpr int RP = kThreads / TD;  // reduction rows per pass
     static constexpr int NE = kBK / RP;       // elements per thread per step
@@ -281,7 +284,7 @@ struct GatherNLaneT : NoSetup {
             p->taps.divmod((uint32_t)kk, c, tap);
             p->taps_w.divmod(tap, tr, ts);
             const bool dead = kk >= k_end;
-            so_v = dead ? 0u
+            so_v = dead ? (NOMASK ? kOob : 0u)
                         : EB * (uint32_t)(((int)c * p->Ht + p->dir * (int)tr) * p->Wt + p->dir * (int)ts + p->shift_row);
             bit_v = dead ? 31u : (SMALL ? tap : tr);
             ts_v = ts;
@@ -297,7 +300,9 @@ struct GatherNLaneT : NoSetup {
             const uint32_t so = (uint32_t)__builtin_amdgcn_readlane((int)so_v, i);
             const uint32_t bit = (uint32_t)__builtin_amdgcn_readlane((int)bit_v, i);
             uint32_t vo;
-            if (SMALL) {
+            if (NOMASK) {
+                vo = voff;
+            } else if (SMALL) {
                 vo = ((nmask >> bit) << 31) | voff;
             } else {
                 const uint32_t ts = (uint32_t)__builtin_amdgcn_readlane((int)ts_v, i);
@@ -327,9 +332,11 @@ struct GatherNLaneT : NoSetup {
         tr_ = (uint32_t)__builtin_amdgcn_readfirstlane((int)tr_);
         so_ = (uint32_t)__builtin_amdgcn_readfirstlane((int)so_);
         const bool dead = kk >= k_end_;  // rows past the end read as zero
-        const uint32_t so = dead ? 0u : so_;
+        const uint32_t so = dead ? (NOMASK ? kOob : 0u) : so_;
         uint32_t vo;
-        if (SMALL) {
+        if (NOMASK) {
+            vo = voff;
+        } else if (SMALL) {
             const uint32_t bit = dead ? 31u : tap_;
             vo = ((nmask >> bit) << 31) | voff;
         } else {
@@ -348,6 +355,7 @@ struct GatherNLaneT : NoSetup {
 };
 template <int TD> using GatherNLane = GatherNLaneT<TD, true>;
 template <int TD> using GatherNLaneBig = GatherNLaneT<TD, false>;
+template <int TD> using GatherNLaneFree = GatherNLaneT<TD, false, float, true>;
 
 // ---- loaders with lanes along the reduction dimension -------------------------------------------
 // 16 consecutive lanes take the 16 reduction rows of a step for one tile position; a thread owns
@@ -639,11 +647,13 @@ struct PhaseFilterKLaneT : NoSetup {
 //                   that fall outside the image; bit 31 of the row mask is always set and serves
 //                   out-of-extent tile positions (r = 31) and rows past the end (mask = all ones).
 // The x loader reuses the pixel decode its peer (the dy loader of the same step) has just done.
-template <int TD, bool WINDOW, class E = float>
+// NOMASK (x of a layer without padding: every tap of every pixel is inside the image): no masks, one
+// address addition per element.
+template <int TD, bool WINDOW, class E = float, bool NOMASK = false>
 struct PixelKLane : NoSetup {
     static constexpr uint32_t EB = Elem<E>::kBytes;
     static constexpr bool kBf16 = std::is_same<E, bf16>::value;
-    static std::string name() { return std::string(WINDOW ? "PixelKLane<x>" : "PixelKLane<dy>") + Elem<E>::tag(); }
+    static std::string name() { return std::string(!WINDOW ? "PixelKLane<dy>" : NOMASK ? "PixelKLane<x, no padding>" : "PixelKLane<x>") + Elem<E>::tag(); }
     static constexpr int CP = kThreads / kBK;
     static constexpr int NE = TD / CP;
     static constexpr int LD = TD + kPad;
@@ -698,6 +708,10 @@ struct PixelKLane : NoSetup {
             p->grid_w.divmod(peer.rest_, a, b);
             const int hb = (int)a * p->mul_h + p->add_h, wb = (int)b * p->mul_w + p->add_w;
             vo_ = EB * (uint32_t)((int)peer.n_ * p->n_stride + hb * p->Wt + wb + p->shift);
+            if constexpr (NOMASK) {
+                vo_ = rowok ? vo_ : kOob;   // + coffb (< 2^31) stays out of range
+                return;
+            }
             // taps r in [lo, hi) are inside the image; everything else (and bit 31) is masked
             const int lo_h = min(max(-hb, 0), 31), hi_h = max(min(p->Ht - hb, 31), lo_h);
             const int lo_w = min(max(-wb, 0), 31), hi_w = max(min(p->Wt - wb, 31), lo_w);
@@ -711,6 +725,8 @@ struct PixelKLane : NoSetup {
         if constexpr (!WINDOW) {
             const uint32_t step = EB * (uint32_t)(CP * p->Ht * p->Wt);  // scalar: 16 channels further
             r[i] = Elem<E>::load(rsrc, vo_, step * (uint32_t)i);
+        } else if constexpr (NOMASK) {
+            r[i] = Elem<E>::load(rsrc, vo_ + coffb[i], 0);
         } else {
             const uint32_t t = (nrow_ >> (rs[i] & 0xffu)) | (ncol_ >> (rs[i] >> 8));
             r[i] = Elem<E>::load(rsrc, (t << 31) | (vo_ + coffb[i]), 0);
@@ -726,6 +742,7 @@ struct PixelKLane : NoSetup {
 };
 template <int TD> using DyKLane = PixelKLane<TD, false>;
 template <int TD> using XKLane = PixelKLane<TD, true>;
+template <int TD> using XKLaneFree = PixelKLane<TD, true, float, true>;
 
 // BackwardFilter's operands again, for filters of at most 31 taps: everything that depends on
 // the reduction row alone (the pixel decode, the address
@@ -991,8 +1008,10 @@ struct Loaders {
     template <int TD> using FilterNLane = FilterNLaneT<TD, E>;
     template <int TD> using GatherNLane = GatherNLaneT<TD, true, E>;
     template <int TD> using GatherNLaneBig = GatherNLaneT<TD, false, E>;
+    template <int TD> using GatherNLaneFree = GatherNLaneT<TD, false, E, true>;
     template <int TD> using DyKLane = PixelKLane<TD, false, E>;
     template <int TD> using XKLane = PixelKLane<TD, true, E>;
+    template <int TD> using XKLaneFree = PixelKLane<TD, true, E, true>;
     template <int TD> using DyTab = PixelTabDy<TD, E>;
     template <int TD> using XTab = PixelTabX<TD, E>;
     template <int TD> using DenseNLaneS = DenseNLaneST<TD, E>;
