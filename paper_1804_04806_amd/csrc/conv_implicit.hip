@@ -43,7 +43,8 @@ hipError_t fill_zero(float *p, size_t n, hipStream_t s)
 // 256 x resident workgroups, and a last round that is nearly empty costs as much as a full one
 // (measured: the time of a Forward launch is flat from 769 to 1024 tiles).  Split counts are
 // chosen so that the workgroup count fills its rounds.
-constexpr long kSlotsOutput = 256 * 4, kSlotsFilter = 256 * 3;
+static long slots_output() { return 4l * device_cus(); }
+static long slots_filter() { return 3l * device_cus(); }
 
 static double round_fill(long blocks, long slots)
 {
@@ -79,7 +80,7 @@ static int output_splits(int M, int N, int Kd, bool fp32_out)
     const long cap = Kd / 512;
     if (want > cap) want = cap;
     if (want < 2) return 1;
-    return best_fill(tiles, want, want / 2 < 2 ? 2 : want / 2, want * 2 < cap ? want * 2 : cap, kSlotsOutput);
+    return best_fill(tiles, want, want / 2 < 2 ? 2 : want / 2, want * 2 < cap ? want * 2 : cap, slots_output());
 }
 
 // bf16 tensors, stride-1 layers whose output rows are as wide as the input rows (so that, for every
@@ -379,7 +380,7 @@ int filter_splits(int M, int N, int Kd, int batch)
     if (want > cap) want = cap;
     if (want < 1) want = 1;
     // three workgroups of the 96- and 128-row BackwardFilter kernels fit a CU, four of the others
-    const long slots = shape.bm >= 96 ? kSlotsFilter : kSlotsOutput;
+    const long slots = shape.bm >= 96 ? slots_filter() : slots_output();
     if (tiles >= 4 * slots) return (int)want;  // many rounds anyway
     return best_fill(tiles, want, (want + 1) / 2, want * 2 < cap ? want * 2 : cap, slots);
 }

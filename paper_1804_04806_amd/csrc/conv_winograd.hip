@@ -995,15 +995,15 @@ static hipError_t winograd_fused_filter_run(const Dims &d, int b, const void *x,
     p.g = g; p.b = b;
     p.k_blocks = (d.K + 63) / 64; p.c_blocks = (d.C + 63) / 64; p.groups = (g.T + kFwT - 1) / kFwT;
     // image chunks: about four rounds of one workgroup per CU, chunks of at least 4 images; among the
-    // counts near that, the one whose workgroup count fills its rounds of 256 best
-    const long items = (long)p.k_blocks * p.c_blocks * p.groups;
-    const long want = (1024 + items - 1) / items, cap = b / 4 < 1 ? 1 : b / 4;
+    // counts near that, the one whose workgroup count fills its rounds of one workgroup per CU best
+    const long items = (long)p.k_blocks * p.c_blocks * p.groups, cus = device_cus();
+    const long want = (4 * cus + items - 1) / items, cap = b / 4 < 1 ? 1 : b / 4;
     long split = want > cap ? cap : want;
     double best = -1.0;
     for (long c = (want + 1) / 2; c <= 2 * want && c <= cap; ++c) {
         const int per = (int)((b + c - 1) / c);
         const long wgs = items * ((b + per - 1) / per);
-        const double fill = (double)wgs / (double)((wgs + 255) / 256 * 256);
+        const double fill = (double)wgs / (double)((wgs + cus - 1) / cus * cus);
         if (fill > best + 1e-9) { best = fill; split = c; }
     }
     p.images_per_chunk = (int)((b + split - 1) / split);

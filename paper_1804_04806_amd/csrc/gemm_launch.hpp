@@ -15,7 +15,28 @@ struct GemmShape {
     bool tail_split = false;  // the epilogue may split the tiles of a nearly empty last round
 };
 
-constexpr int kCUs = 256;          // compute units of the MI355X
+// Compute units of the current device (256 on a whole MI355X; fewer in a partitioned mode).  The
+// launch heuristics fill rounds of this many workgroups.  Without a device (host-only planning,
+// launch descriptions) the MI355X's count is assumed.
+inline int device_cus()
+{
+    constexpr int kDefault = 256, kMaxDevices = 64;
+    static int cached[kMaxDevices];   // 0 = not asked yet; a racing first call writes the same value
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        return kDefault;
+    }
+    int v = cached[dev];
+    if (v == 0) {
+        v = kDefault;
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) v = n;
+        else (void)hipGetLastError();
+        cached[dev] = v;
+    }
+    return v;
+}
 constexpr int kTailMinSteps = 8;    // a tail workgroup's run has at least this many reduction steps (of BK rows)
 constexpr int kTailMaxTiles = 224;  // a last round fuller than this is left alone
 
@@ -51,8 +72,9 @@ hipError_t launch_tile(const AP &pa, const BP &pb, const typename Epi::Params &p
     TailSplit tail{0, 1, 0};
     if constexpr (Epi::kCanAdd) {
         const long tiles = (long)tiles_m * tiles_n;
+        const int kCUs = device_cus();
         const int over = (int)(tiles % kCUs);
-        if (g.tail_split && splits == 1 && g.batch == 1 && tiles >= 2 * kCUs && over > 0 && over <= kTailMaxTiles) {
+        if (g.tail_split && splits == 1 && g.batch == 1 && tiles >= 2 * kCUs && over > 0 && over <= kTailMaxTiles * kCUs / 256) {
             const int ksteps = (g.Kd + kBK - 1) / kBK;
             const long steps = (long)over * ksteps;
             long wgs = steps / kTailMinSteps;
