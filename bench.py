@@ -56,7 +56,8 @@ MEASURED_TRAFFIC_BYTES_PER_FLOP = {
     "gemm_kernel<Tile<64x128>,PhaseFilterKLane,GatherNLane<taps<=31>,EpiPhases>": 459.2e6 / 68.99e9,
 }
 
-ALGO_IDS = {"implicit": 0, "im2col": 1, "winograd": 2, "winograd4": 3, "fft": 4, "winograd-fused": 5}
+ALGO_IDS = {"implicit": 0, "im2col": 1, "winograd": 2, "winograd4": 3, "fft": 4, "winograd-fused": 5,
+            "implicit-mirror": 6}
 
 # name -> (description, layer table, batch, per-layer limit or total budget, "wr" | "wd", default policy)
 WORKLOADS = {
@@ -277,7 +278,7 @@ def kernel_class(ucd, desc, op, algo, b):
     Returns (name, matrix flops the kernel issues)."""
     text, n = ucd.ucd_describe_micro(desc, op, algo, b)
     parts = [p.strip() for p in text.split(";")]
-    helpers = ("fill_zero_kernel", "zero_tiles_kernel", "wino_filter_kernel", "wino_dw_kernel")
+    helpers = ("fill_zero_kernel", "zero_tiles_kernel", "wino_filter_kernel", "wino_dw_kernel", "mirror_filter_kernel")
     main = [p for p in parts if p.startswith(("gemm_kernel", "wino_fused"))]
     others = [p for p in parts if p not in main and p not in helpers]
     if len(main) != 1 or others:

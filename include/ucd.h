@@ -80,7 +80,11 @@ enum {
     UCD_ALGO_WINOGRAD_FUSED = 5,  /* Winograd F(2x2,3x3) (BackwardFilter: F(3x3,2x2)) with the data
                         * transforms inside the GEMM kernel: the workspace holds the transformed filter
                         * (BackwardFilter: the 16 K x C product planes) only, whatever the micro-batch size */
-    UCD_N_ALGO = 6
+    UCD_ALGO_IMPLICIT_MIRROR = 6, /* BackwardData of stride-1 layers (padding <= filter extent - 1) as the
+                                     Forward implicit GEMM of the mirrored layer on a copy of the
+                                     filter with channels transposed and taps reversed: workspace =
+                                     that copy, whatever the micro-batch size */
+    UCD_N_ALGO = 7
 };
 
 /* Batch-size policies of Section 3.4: which micro-batch sizes get benchmarked: only B; the powers
@@ -126,6 +130,8 @@ int ucd_set_deterministic(int on);
  * quantity compared with the limit M in step 1 of the WR algorithm, Section 3.2):
  *   implicit   0 (reproducible mode, BackwardFilter: 4*K*C*R*S bytes per reduction chunk, see
  *              ucd_set_deterministic)
+ *   implicit GEMM on a mirrored filter copy (BackwardData only)   e * K*C*R*S rounded up to 16,
+ *              e = 4 (fp32 tensors) or 2 (bf16)
  *   im2col     4 * C*R*S * ld,  ld = b*P*Q rounded up to 4
  *   Winograd   4 * a*a * (Ci*Co4 + ld*(C + K)) with a = 4 (F(2x2,3x3)) or 6 (F(4x4,3x3)),
  *              ld = b * ceil(Ho/m) * ceil(Wo/m) rounded up to 4 (m = a - 2), where (Ci, Co, Ho, Wo)

@@ -77,7 +77,10 @@ bool fits_32bit(const ucd_layer_t *L, int b)
 inline int wino_tile(int algo) { return algo == UCD_ALGO_WINOGRAD4 ? 4 : 2; }
 inline bool is_winograd(int algo) { return algo == UCD_ALGO_WINOGRAD || algo == UCD_ALGO_WINOGRAD4; }
 // algorithms that keep a transformed filter at the head of the workspace
-inline bool keeps_filter(int algo) { return is_winograd(algo) || algo == UCD_ALGO_FFT || algo == UCD_ALGO_WINOGRAD_FUSED; }
+inline bool keeps_filter(int algo)
+{
+    return is_winograd(algo) || algo == UCD_ALGO_FFT || algo == UCD_ALGO_WINOGRAD_FUSED || algo == UCD_ALGO_IMPLICIT_MIRROR;
+}
 
 size_t ws_size(const ucd_layer_t *L, int op, int algo, int b)
 {
@@ -105,6 +108,9 @@ size_t ws_size(const ucd_layer_t *L, int op, int algo, int b)
     case UCD_ALGO_WINOGRAD_FUSED:
         if (!winograd_applies(d, op)) return UCD_WS_NA;
         return op == UCD_BWD_FILTER ? winograd_fused_filter_ws_bytes(d) : winograd_fused_ws_bytes(d, op);
+    case UCD_ALGO_IMPLICIT_MIRROR:
+        if (!implicit_mirror_applies(d, op)) return UCD_WS_NA;
+        return implicit_mirror_ws_bytes(d);
     case UCD_ALGO_FFT:
         if (!fft_applies(d, op)) return UCD_WS_NA;
         // every frequency plane is one GEMM operand
@@ -147,6 +153,9 @@ int run_micro(const ucd_layer_t *L, int op, int algo, int b, const void *a, cons
     case UCD_ALGO_WINOGRAD_FUSED:
         if (op != UCD_BWD_FILTER) e = winograd_fused(d, op, b, a, bsrc, out, ws, filter_ready, s);
         else e = winograd_fused_filter(d, b, a, bsrc, (float *)out, beta, ws, s);
+        break;
+    case UCD_ALGO_IMPLICIT_MIRROR:
+        if (op == UCD_BWD_DATA) e = implicit_bwd_data_mirror(d, b, a, bsrc, out, ws, filter_ready, s);
         break;
     case UCD_ALGO_FFT:
         if (op == UCD_FWD) e = fft_fwd(d, b, a, bsrc, out, ws, filter_ready, s);

@@ -368,6 +368,58 @@ hipError_t implicit_bwd_data(const Dims &d, int b, const void *dy, const void *w
     return d.dtype == 1 ? implicit_bwd_data_t<bf16>(d, b, dy, w, dx, s) : implicit_bwd_data_t<float>(d, b, dy, w, dx, s);
 }
 
+// ---- BackwardData on a mirrored filter copy ---------------------------------------------------------
+// With stride 1, dx[n,c,h,w] = sum_{k,r,s} dy[n,k,h+pad-r,w+pad-s] w[k,c,r,s] is the Forward
+// convolution of dy (K channels, P x Q) with wt[c][k][r'][s'] = w[k][c][R-1-r'][S-1-s'] and padding
+// (R-1-pad, S-1-pad).  Once the filter is stored that way its rows are contiguous along the
+// reduction index, which is what the Forward kernels' filter loaders want (no per-element decode
+// in fp32; 16-byte cells for the bf16 vector-load kernel).  The copy costs K*C*R*S elements of
+// workspace and one small kernel per run of micro-batches.
+template <class E>
+__global__ __launch_bounds__(256) void mirror_filter_kernel(const E *__restrict__ w, E *__restrict__ wt, int K, int C,
+                                                            int RS)
+{
+    const long n = (long)K * C * RS;
+    for (long i = blockIdx.x * 256l + threadIdx.x; i < n; i += 256l * gridDim.x) {
+        const int t = (int)(i % RS);
+        const long ck = i / RS;
+        const int k = (int)(ck % K), c = (int)(ck / K);
+        wt[i] = w[((long)k * C + c) * RS + (RS - 1 - t)];   // (R-1-r)*S + (S-1-s) = RS-1 - (r*S+s)
+    }
+}
+
+bool implicit_mirror_applies(const Dims &d, int op)
+{
+    return op == 1 && d.sh == 1 && d.sw == 1 && d.ph <= d.R - 1 && d.pw <= d.S - 1;
+}
+
+size_t implicit_mirror_ws_bytes(const Dims &d) { return (d.esize() * d.K * d.crs() + 15) / 16 * 16; }
+
+hipError_t implicit_bwd_data_mirror(const Dims &d, int b, const void *dy, const void *w, void *dx, void *ws,
+                                    bool filter_ready, hipStream_t s)
+{
+    LaunchLog *log = launch_log();
+    if (filter_ready) {
+        // the copy is still in the workspace from the previous micro-batch
+    } else if (log) {
+        log->add("mirror_filter_kernel");
+    } else {
+        const long n = (long)d.K * d.crs();
+        const unsigned blocks = (unsigned)((n + 255) / 256 < 2048 ? (n + 255) / 256 : 2048);
+        if (d.dtype == 1)
+            mirror_filter_kernel<uint16_t><<<blocks, 256, 0, s>>>((const uint16_t *)w, (uint16_t *)ws, d.K, d.C, d.R * d.S);
+        else
+            mirror_filter_kernel<float><<<blocks, 256, 0, s>>>((const float *)w, (float *)ws, d.K, d.C, d.R * d.S);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    Dims m = d;   // the mirrored layer: dy is its input, dx its output
+    m.C = d.K; m.K = d.C;
+    m.H = d.P; m.W = d.Q; m.P = d.H; m.Q = d.W;
+    m.ph = d.R - 1 - d.ph; m.pw = d.S - 1 - d.pw;
+    return implicit_fwd(m, b, dy, ws, dx, s);
+}
+
 // Number of reduction splits so that tiles * splits covers the chip a few times over, with
 // chunks of at least 256 reduction rows.
 int filter_splits(int M, int N, int Kd, int batch)

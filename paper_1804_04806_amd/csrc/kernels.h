@@ -33,6 +33,13 @@ hipError_t implicit_bwd_data(const Dims &d, int b, const void *dy, const void *w
 hipError_t implicit_bwd_filter(const Dims &d, int b, const void *x, const void *dy, float *dw, float beta,
                                float *ws, hipStream_t s);
 size_t implicit_det_ws_bytes(const Dims &d, int b);
+// BackwardData of a stride-1 layer as the Forward implicit GEMM of the mirrored layer (channels
+// swapped, padding R-1-pad) on a copy of the filter with channels transposed and taps reversed; the
+// copy (implicit_mirror_ws_bytes) sits at the head of the workspace and is kept when filter_ready
+bool implicit_mirror_applies(const Dims &d, int op);
+size_t implicit_mirror_ws_bytes(const Dims &d);
+hipError_t implicit_bwd_data_mirror(const Dims &d, int b, const void *dy, const void *w, void *dx, void *ws,
+                                    bool filter_ready, hipStream_t s);
 
 // im2col into workspace + GEMM
 size_t im2col_ws_bytes(const Dims &d, int b);

@@ -13,7 +13,8 @@ LIB_PATH = os.path.join(_HERE, "libucd.so")
 
 FWD, BWD_DATA, BWD_FILTER = 0, 1, 2
 ALGO_IMPLICIT, ALGO_IM2COL, ALGO_WINOGRAD, ALGO_WINOGRAD4, ALGO_FFT, ALGO_WINOGRAD_FUSED = 0, 1, 2, 3, 4, 5
-N_ALGO = 6
+ALGO_IMPLICIT_MIRROR = 6
+N_ALGO = 7
 POLICY_UNDIVIDED, POLICY_POW2, POLICY_ALL = 0, 1, 2
 TIME_INF = (1 << 64) - 1
 WS_NA = (1 << 64) - 1
@@ -22,7 +23,8 @@ OK, E_INVALID, E_NULLPTR, E_UNSUPPORTED, E_WS_TOO_SMALL, E_HIP, E_NOMEM, E_INFEA
 WINOGRAD_ALGOS = (ALGO_WINOGRAD, ALGO_WINOGRAD4, ALGO_WINOGRAD_FUSED)
 # algorithms that reach the direct result through transforms (looser rounding bound than the GEMM paths)
 TRANSFORM_ALGOS = WINOGRAD_ALGOS + (ALGO_FFT,)
-ALGO_NAMES = {0: "implicit", 1: "im2col", 2: "winograd", 3: "winograd4", 4: "fft", 5: "winograd-fused"}
+ALGO_NAMES = {0: "implicit", 1: "im2col", 2: "winograd", 3: "winograd4", 4: "fft", 5: "winograd-fused",
+              6: "implicit-mirror"}
 OP_NAMES = {0: "fwd", 1: "bwd_data", 2: "bwd_filter"}
 
 EXPORTS = [

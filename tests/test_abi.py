@@ -46,8 +46,21 @@ def test_workspace_formulas():
     # FFT: 144 planes of 4 bytes, 14 x 14 output tiles: T = 2*2, 2C*2K + ld*(2C + 2K)
     assert ucd.ucd_workspace_size(L, ucd.FWD, ucd.ALGO_FFT, 3) == 4 * 144 * (32 * 64 + 12 * 96)
     assert ucd.ucd_workspace_size(L, ucd.BWD_FILTER, ucd.ALGO_FFT, 1) == 4 * 144 * (4 * 32 * 16 + 4 * 96)
+    # fused Winograd: the transformed filter, 64 bytes x Ci (rounded up to 8) x Co (rounded up to 4)
+    assert ucd.ucd_workspace_size(L, ucd.FWD, ucd.ALGO_WINOGRAD_FUSED, 8) == 64 * 16 * 32
+    assert ucd.ucd_workspace_size(L, ucd.BWD_FILTER, ucd.ALGO_WINOGRAD_FUSED, 8) == 64 * 16 * 32
+    Lc3 = ucd.layer(N=8, C=3, H=16, W=16, K=30, R=3, S=3, pad_h=1, pad_w=1)
+    assert ucd.ucd_workspace_size(Lc3, ucd.FWD, ucd.ALGO_WINOGRAD_FUSED, 1) == 64 * 8 * 32
+    assert ucd.ucd_workspace_size(Lc3, ucd.BWD_DATA, ucd.ALGO_WINOGRAD_FUSED, 1) == 64 * 32 * 4
+    # mirrored filter copy: BackwardData of stride-1 layers only, the filter's own size (16-byte multiple)
+    assert ucd.ucd_workspace_size(L, ucd.BWD_DATA, ucd.ALGO_IMPLICIT_MIRROR, 5) == 4 * 32 * 16 * 9
+    assert ucd.ucd_workspace_size(L, ucd.FWD, ucd.ALGO_IMPLICIT_MIRROR, 5) == ucd.WS_NA
+    assert ucd.ucd_workspace_size(L, ucd.BWD_FILTER, ucd.ALGO_IMPLICIT_MIRROR, 5) == ucd.WS_NA
+    Lb = ucd.layer(N=8, C=3, H=16, W=16, K=5, R=3, S=3, pad_h=1, pad_w=1, dtype=1)
+    assert ucd.ucd_workspace_size(Lb, ucd.BWD_DATA, ucd.ALGO_IMPLICIT_MIRROR, 1) == 272   # 2 x 135 -> 16-byte multiple
     Ls2 = ucd.layer(N=8, C=16, H=16, W=16, K=32, R=3, S=3, pad_h=1, pad_w=1, stride_h=2, stride_w=2)
     assert ucd.ucd_workspace_size(Ls2, ucd.BWD_FILTER, ucd.ALGO_WINOGRAD, 1) == ucd.WS_NA  # stride 2
+    assert ucd.ucd_workspace_size(Ls2, ucd.BWD_DATA, ucd.ALGO_IMPLICIT_MIRROR, 1) == ucd.WS_NA
     L11 = ucd.layer(N=4, C=8, H=7, W=7, K=8, R=1, S=1)
     assert ucd.ucd_workspace_size(L11, ucd.FWD, ucd.ALGO_IM2COL, 1) == ucd.WS_NA    # col == x
     assert ucd.ucd_workspace_size(L11, ucd.FWD, ucd.ALGO_WINOGRAD, 1) == ucd.WS_NA  # not 3x3

@@ -13,7 +13,7 @@ pytestmark = pytest.mark.gpu
 # measure 3e-7 (2x2 tiles) to 4e-6 (4x4 tiles), so they are held to 1e-4 here, and the tiled FFT
 # (1e-7 to 2e-7) to the GEMM paths' bound.
 TOL = {ucd.ALGO_IMPLICIT: 1e-5, ucd.ALGO_IM2COL: 1e-5, ucd.ALGO_WINOGRAD: 1e-4, ucd.ALGO_WINOGRAD4: 1e-4,
-       ucd.ALGO_FFT: 1e-5, ucd.ALGO_WINOGRAD_FUSED: 1e-4}
+       ucd.ALGO_FFT: 1e-5, ucd.ALGO_WINOGRAD_FUSED: 1e-4, ucd.ALGO_IMPLICIT_MIRROR: 1e-5}
 
 # sizes span several tiles (128-wide) with ragged tails in M, N and the reduction
 SHAPES = [
