@@ -791,10 +791,17 @@ struct FusedFilterParams {
     int b, k_blocks, c_blocks, groups, n_split, images_per_chunk;
 };
 
-template <class E>
+// PW >= 0 (fp32 tensors, horizontal padding PW = 0 or 1): patch rows of x and tile rows of dy are
+// fetched as 8-, 12- or 16-byte windows instead of element by element, as in wino_fused_kernel (the
+// element loads keep the texture path at 0.87 cache accesses per cycle, i.e. saturated): the window
+// of x starts at column 2*tw; with PW = 1 the patch's first column comes from the lane below (the
+// tile to the left, same channel), except for the first tile position of a group, which fetches it.
+template <class E, int PW, bool ODD_W = false>
 __global__ __launch_bounds__(256) void wino_fused_filter_kernel(FusedFilterParams p)
 {
     constexpr uint32_t EB = Elem<E>::kBytes;
+    constexpr bool kRows = PW >= 0;
+    static_assert(!kRows || EB == 4, "row loads are written for fp32 tensors");
     __shared__ __attribute__((aligned(16))) float Ds[2][16][kFwT][kFwLd];
     __shared__ __attribute__((aligned(16))) float Vs[2][16][kFwT][kFwLd];
     const WinoGeom &g = p.g;
@@ -824,44 +831,117 @@ __global__ __launch_bounds__(256) void wino_fused_filter_kernel(FusedFilterParam
     // immediate offset.
     const int ptile = tid & 7, pch = tid >> 3;
     const int pcol = pch ^ (4 * ptile);   // + 32 h: bit 5 is not touched by the swizzle
-    uint32_t vx[2][16], vd[2][4];
+    // element-wise: vx = the 16 pixels of the patch, vd = the 4 of the dy tile.  Rows: vx[h][r] = the
+    // window start of patch row r, vx[h][4 + r] = its first column where this lane fetches it itself;
+    // vd[h][r] = the start of tile row r.
+    uint32_t vx[2][kRows ? 8 : 16], vd[2][kRows ? 2 : 4];
+    bool own_col = false, ok1 = true, ok2 = true, ok3 = true, dy_ok1 = true;
     {
         const int t = grp * kFwT + ptile;
         const bool live = t < g.T;
         const int th = live ? t / g.TW : 0, tw = live ? t % g.TW : 0;
         const int h0 = 2 * th - g.pad_h, w0 = 2 * tw - g.pad_w;
+        if constexpr (kRows) {
+            const int ws = 2 * tw;   // = w0 + PW
+            // the first column is this lane's own load (or the padding's 0) for the first tile position
+            // of a group and for tiles in the first tile column; otherwise the lane below holds it
+            own_col = ptile == 0 || tw == 0;
+            ok1 = ws + 1 < g.Wi; ok2 = ws + 2 < g.Wi; ok3 = ws + 3 < g.Wi;
+            dy_ok1 = 2 * tw + 1 < g.Wo;
+        }
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const int c = c0 + pch + 32 * h, k = k0 + pch + 32 * h;
+            if constexpr (kRows) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int hh = h0 + r, ww = w0 + q;
-                    const bool ok = live && c < g.Ci && (unsigned)hh < (unsigned)g.Hi && (unsigned)ww < (unsigned)g.Wi;
-                    vx[h][4 * r + q] = ok ? EB * (uint32_t)((c * g.Hi + hh) * g.Wi + ww) : kOob;
+                for (int r = 0; r < 4; ++r) {
+                    const int hh = h0 + r;
+                    const bool ok = live && c < g.Ci && (unsigned)hh < (unsigned)g.Hi;
+                    const uint32_t row = EB * (uint32_t)((c * g.Hi + hh) * g.Wi + 2 * tw);
+                    vx[h][r] = ok ? row : kOob;
+                    vx[h][4 + r] = ok && PW == 1 && ptile == 0 && tw > 0 ? row - EB : kOob;
                 }
 #pragma unroll
-            for (int r = 0; r < 2; ++r)
-#pragma unroll
-                for (int q = 0; q < 2; ++q) {
-                    const int hh = 2 * th + r, ww = 2 * tw + q;
-                    const bool ok = live && k < g.Co && hh < g.Ho && ww < g.Wo;
-                    vd[h][2 * r + q] = ok ? EB * (uint32_t)((k * g.Ho + hh) * g.Wo + ww) : kOob;
+                for (int r = 0; r < 2; ++r) {
+                    const int hh = 2 * th + r;
+                    const bool ok = live && k < g.Co && hh < g.Ho;
+                    vd[h][r] = ok ? EB * (uint32_t)((k * g.Ho + hh) * g.Wo + 2 * tw) : kOob;
                 }
+            } else {
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const int hh = h0 + r, ww = w0 + q;
+                        const bool ok = live && c < g.Ci && (unsigned)hh < (unsigned)g.Hi && (unsigned)ww < (unsigned)g.Wi;
+                        vx[h][4 * r + q] = ok ? EB * (uint32_t)((c * g.Hi + hh) * g.Wi + ww) : kOob;
+                    }
+#pragma unroll
+                for (int r = 0; r < 2; ++r)
+#pragma unroll
+                    for (int q = 0; q < 2; ++q) {
+                        const int hh = 2 * th + r, ww = 2 * tw + q;
+                        const bool ok = live && k < g.Co && hh < g.Ho && ww < g.Wo;
+                        vd[h][2 * r + q] = ok ? EB * (uint32_t)((k * g.Ho + hh) * g.Wo + ww) : kOob;
+                    }
+            }
         }
     }
     const uint32_t x_image = EB * (uint32_t)(g.Ci * g.Hi * g.Wi), dy_image = EB * (uint32_t)(g.Co * g.Ho * g.Wo);
 
     float dx[2][16], dz[2][4];  // the thread's patches of the image after the one in LDS
+    float dl[2][4];             // rows, PW = 1: the first column where the lane fetches it itself
+    constexpr int kXLoads = !kRows ? 16 : PW == 1 ? 8 : 4, kDyLoads = kRows ? 2 : 4;   // load instructions per patch / tile
     // an image past the chunk's end gets a scalar offset that pushes every address out of range
-    auto fetch_x = [&](int n, int h, int i) {
-        dx[h][i] = Elem<E>::load(rx, vx[h][i], n < n_end ? (uint32_t)n * x_image : kOob);
+    auto fetch_x = [&](int n, int h, int i) {   // i < kXLoads
+        const uint32_t so = n < n_end ? (uint32_t)n * x_image : kOob;
+        if constexpr (!kRows) {
+            dx[h][i] = Elem<E>::load(rx, vx[h][i], so);
+        } else if constexpr (PW == 0) {
+            const f32x4 q = buf_load4(rx, vx[h][i], so);
+            dx[h][4 * i] = q.x; dx[h][4 * i + 1] = q.y; dx[h][4 * i + 2] = q.z; dx[h][4 * i + 3] = q.w;
+        } else if (i < 4) {
+            const auto q = __builtin_amdgcn_raw_buffer_load_b96(rx, (int)vx[h][i], (int)so, 0);
+#pragma unroll
+            for (int c = 0; c < 3; ++c) dx[h][4 * i + 1 + c] = __uint_as_float(q[c]);
+        } else {
+            dl[h][i - 4] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rx, (int)vx[h][i], (int)so, 0));
+        }
     };
-    auto fetch_dy = [&](int n, int h, int i) {
-        dz[h][i] = Elem<E>::load(rdy, vd[h][i], n < n_end ? (uint32_t)n * dy_image : kOob);
+    auto fetch_dy = [&](int n, int h, int i) {   // i < kDyLoads
+        const uint32_t so = n < n_end ? (uint32_t)n * dy_image : kOob;
+        if constexpr (!kRows) {
+            dz[h][i] = Elem<E>::load(rdy, vd[h][i], so);
+        } else {
+            const auto q = __builtin_amdgcn_raw_buffer_load_b64(rdy, (int)vd[h][i], (int)so, 0);
+            dz[h][2 * i] = __uint_as_float(q[0]);
+            dz[h][2 * i + 1] = __uint_as_float(q[1]);
+        }
+    };
+    // rows: the windows as loaded become the patch / tile (see wino_fused_kernel)
+    auto finish_x = [&](int h) {
+        if constexpr (kRows) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                if constexpr (PW == 1) {
+                    if constexpr (ODD_W) dx[h][4 * r + 2] = ok1 ? dx[h][4 * r + 2] : 0.f;
+                    dx[h][4 * r + 3] = ok2 ? dx[h][4 * r + 3] : 0.f;
+                    const int left = __builtin_amdgcn_update_dpp(0, (int)__float_as_uint(dx[h][4 * r + 2]), 0x138, 0xf, 0xf, false);
+                    dx[h][4 * r] = own_col ? dl[h][r] : __uint_as_float((uint32_t)left);
+                } else {
+                    if constexpr (ODD_W) dx[h][4 * r + 3] = ok3 ? dx[h][4 * r + 3] : 0.f;
+                }
+            }
+        }
+    };
+    auto finish_dy = [&](int h) {
+        if constexpr (kRows && ODD_W) {   // an odd width of x is an odd width of dy (3x3, stride 1, equal padding)
+            dz[h][1] = dy_ok1 ? dz[h][1] : 0.f;
+            dz[h][3] = dy_ok1 ? dz[h][3] : 0.f;
+        }
     };
     auto store_v = [&](int buf, int h) {  // B^T x B of patch h
+        finish_x(h);
         float tr[16];
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
@@ -881,6 +961,7 @@ __global__ __launch_bounds__(256) void wino_fused_filter_kernel(FusedFilterParam
         }
     };
     auto store_d = [&](int buf, int h) {  // A dy A^T of tile h: rows (z0, z0+z1, z0-z1, -z1) of A z, then the same on columns
+        finish_dy(h);
         const float z00 = dz[h][0], z01 = dz[h][1], z10 = dz[h][2], z11 = dz[h][3];
         const float t[4][2] = {{z00, z01}, {z00 + z10, z01 + z11}, {z00 - z10, z01 - z11}, {-z10, -z11}};
 #pragma unroll
@@ -901,9 +982,9 @@ __global__ __launch_bounds__(256) void wino_fused_filter_kernel(FusedFilterParam
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) fetch_x(n_begin, h, i);
+        for (int i = 0; i < kXLoads; ++i) fetch_x(n_begin, h, i);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) fetch_dy(n_begin, h, i);
+        for (int i = 0; i < kDyLoads; ++i) fetch_dy(n_begin, h, i);
     }
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
@@ -913,9 +994,9 @@ __global__ __launch_bounds__(256) void wino_fused_filter_kernel(FusedFilterParam
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) fetch_x(n_begin + 1, h, i);
+        for (int i = 0; i < kXLoads; ++i) fetch_x(n_begin + 1, h, i);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) fetch_dy(n_begin + 1, h, i);
+        for (int i = 0; i < kDyLoads; ++i) fetch_dy(n_begin + 1, h, i);
     }
     __syncthreads();
 
@@ -940,27 +1021,30 @@ __global__ __launch_bounds__(256) void wino_fused_filter_kernel(FusedFilterParam
         read_ops(0);
         __builtin_amdgcn_sched_barrier(0);
         __builtin_amdgcn_s_setprio(UCD_MFMA_PRIO);
-#pragma unroll
-        for (int m = 0; m < 16 * kFwPairs; ++m) {
-            const int xi = m / kFwPairs, q = m % kFwPairs;
+        auto slot = [&](auto M) {
+            constexpr int m = decltype(M)::value;
+            constexpr int xi = m / kFwPairs, q = m % kFwPairs;
             acc[xi] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[xi & 1][q], b[xi & 1][q], acc[xi], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
-            if (q == 0 && xi + 1 < 16) read_ops(xi + 1);
+            if constexpr (q == 0 && xi + 1 < 16) read_ops(xi + 1);
             // image n + 1 (in registers) is transformed into the other LDS buffer and every register
             // reloaded with image n + 2 as soon as it is free: one piece, and at most one global load,
             // behind each MFMA (a burst of loads would block this SIMD's only wave)
-            if (m >= 1 && m < 35) {          // x patches: 2 x (transform + 16 loads)
-                const int h = (m - 1) / 17, i = (m - 1) % 17;
-                if (i == 0) store_v(buf ^ 1, h);
+            constexpr int kXSlots = 1 + kXLoads, kDySlots = 1 + kDyLoads, kDyStart = 1 + 2 * kXSlots;
+            if constexpr (m >= 1 && m < kDyStart) {                      // x patches: 2 x (transform + loads)
+                constexpr int h = (m - 1) / kXSlots, i = (m - 1) % kXSlots;
+                if constexpr (i == 0) store_v(buf ^ 1, h);
                 else fetch_x(n + 2, h, i - 1);
             }
-            if (m >= 35 && m < 45) {         // dy tiles: 2 x (transform + 4 loads)
-                const int h = (m - 35) / 5, i = (m - 35) % 5;
-                if (i == 0) store_d(buf ^ 1, h);
+            if constexpr (m >= kDyStart && m < kDyStart + 2 * kDySlots) {  // dy tiles: 2 x (transform + loads)
+                constexpr int h = (m - kDyStart) / kDySlots, i = (m - kDyStart) % kDySlots;
+                if constexpr (i == 0) store_d(buf ^ 1, h);
                 else fetch_dy(n + 2, h, i - 1);
             }
+            static_assert(kDyStart + 2 * kDySlots <= 16 * kFwPairs, "the step's work fits behind its MFMAs");
             __builtin_amdgcn_sched_barrier(0);
-        }
+        };
+        static_for<16 * kFwPairs>(slot);
         __builtin_amdgcn_s_setprio(0);
         __syncthreads();
         buf ^= 1;
@@ -1016,7 +1100,19 @@ static hipError_t winograd_fused_filter_run(const Dims &d, int b, const void *x,
         log->add("wino_dw_kernel");
         return hipSuccess;
     }
-    wino_fused_filter_kernel<E><<<blocks, 256, 0, s>>>(p);
+    // row-vector loads: fp32 tensors, horizontal padding 0 or 1 (UCD_FUSED_ELEMENTWISE=1 keeps the
+    // element-wise loads, for comparison)
+    static const bool elementwise = getenv("UCD_FUSED_ELEMENTWISE") != nullptr;
+    bool rows = false;
+    if constexpr (std::is_same_v<E, float>) {
+        rows = !elementwise && (g.pad_w == 0 || g.pad_w == 1);
+        const bool odd = g.Wi % 2 != 0;
+        if (rows && g.pad_w == 0 && odd) wino_fused_filter_kernel<E, 0, true><<<blocks, 256, 0, s>>>(p);
+        else if (rows && g.pad_w == 0) wino_fused_filter_kernel<E, 0, false><<<blocks, 256, 0, s>>>(p);
+        else if (rows && odd) wino_fused_filter_kernel<E, 1, true><<<blocks, 256, 0, s>>>(p);
+        else if (rows) wino_fused_filter_kernel<E, 1, false><<<blocks, 256, 0, s>>>(p);
+    }
+    if (!rows) wino_fused_filter_kernel<E, -1><<<blocks, 256, 0, s>>>(p);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     wino_dw_kernel<2><<<(unsigned)((KC + 255) / 256), 256, 0, s>>>(ws, dw, KC, beta);
     return hipGetLastError();
