@@ -57,7 +57,7 @@ MEASURED_TRAFFIC_BYTES_PER_FLOP = {
 }
 
 ALGO_IDS = {"implicit": 0, "im2col": 1, "winograd": 2, "winograd4": 3, "fft": 4, "winograd-fused": 5,
-            "implicit-mirror": 6}
+            "implicit-mirror": 6, "winograd5x5-fused": 7}
 
 # name -> (description, layer table, batch, per-layer limit or total budget, "wr" | "wd", default policy)
 WORKLOADS = {
@@ -249,7 +249,7 @@ def gemm_flops(text):
     total = 0.0
     for part in text.split(";"):
         part = part.strip()
-        if part.startswith("wino_fused"):
+        if part.startswith(("wino_fused", "wino5_fused")):
             total += float(part.split("gemm_flops=")[1].split()[0])
         if not part.startswith("gemm_kernel"):
             continue
@@ -278,12 +278,13 @@ def kernel_class(ucd, desc, op, algo, b):
     Returns (name, matrix flops the kernel issues)."""
     text, n = ucd.ucd_describe_micro(desc, op, algo, b)
     parts = [p.strip() for p in text.split(";")]
-    helpers = ("fill_zero_kernel", "zero_tiles_kernel", "wino_filter_kernel", "wino_dw_kernel", "mirror_filter_kernel")
-    main = [p for p in parts if p.startswith(("gemm_kernel", "wino_fused"))]
+    helpers = ("fill_zero_kernel", "zero_tiles_kernel", "wino_filter_kernel", "wino_dw_kernel", "mirror_filter_kernel",
+               "wino5_filter_kernel")
+    main = [p for p in parts if p.startswith(("gemm_kernel", "wino_fused", "wino5_fused"))]
     others = [p for p in parts if p not in main and p not in helpers]
     if len(main) != 1 or others:
         return None
-    if main[0].startswith("wino_fused"):
+    if main[0].startswith(("wino_fused", "wino5_fused")):
         return main[0].split()[0], gemm_flops(main[0])
     name = main[0].split("> tiles=")[0] + ">"
     return name + (" (after " + parts[0] + ")" if len(parts) > 1 else ""), gemm_flops(main[0])

@@ -84,7 +84,10 @@ enum {
                                      Forward implicit GEMM of the mirrored layer on a copy of the
                                      filter with channels transposed and taps reversed: workspace =
                                      that copy, whatever the micro-batch size */
-    UCD_N_ALGO = 7
+    UCD_ALGO_WINOGRAD5_FUSED = 7, /* Winograd F(2x2,5x5) with the data transforms inside the GEMM kernel:
+                                     Forward and BackwardData of 5x5 stride-1 layers with horizontal padding
+                                     2, fp32 tensors; workspace = the transformed filter */
+    UCD_N_ALGO = 8
 };
 
 /* Batch-size policies of Section 3.4: which micro-batch sizes get benchmarked: only B; the powers
@@ -139,6 +142,7 @@ int ucd_set_deterministic(int on);
  *              to 4; BackwardFilter: K*C in place of Ci*Co4, tiles over (P, Q)
  *   Winograd, fused transforms   64 * Ci8*Co4 (the transformed filter, Ci8 = Ci rounded up to 8);
  *              BackwardFilter 64 * K*C
+ *   Winograd F(2x2,5x5), fused transforms   144 * Ci8*Co4
  *   FFT        4 * 144 * (2Ci*M4 + ld*(2Ci + 2Co)), M4 = 2Co rounded up to 4, ld = b *
  *              ceil(Ho/(17-R)) * ceil(Wo/(17-S)) rounded up to 4, (Ci, Co, Ho, Wo) as for Winograd;
  *              BackwardFilter: 4*K*C in place of 2Ci*M4, tiles over (P, Q)

@@ -17,7 +17,7 @@ INCLUDE = os.path.join(ROOT, "include")
 OUT = os.path.join(HERE, "libucd.so")
 OBJ_DIR = os.path.join(ROOT, "_build")
 
-SOURCES = ["api.cpp", "planner.cpp", "conv_implicit.hip", "conv_im2col.hip", "conv_winograd.hip", "conv_fft.hip", "mfma_probe.hip"]
+SOURCES = ["api.cpp", "planner.cpp", "conv_implicit.hip", "conv_im2col.hip", "conv_winograd.hip", "conv_winograd5.hip", "conv_fft.hip", "mfma_probe.hip"]
 
 # packed fp32 instructions are switched off on purpose (they have mis-computed on the test machines)
 HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-munsafe-fp-atomics",

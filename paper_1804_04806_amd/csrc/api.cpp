@@ -79,7 +79,8 @@ inline bool is_winograd(int algo) { return algo == UCD_ALGO_WINOGRAD || algo == 
 // algorithms that keep a transformed filter at the head of the workspace
 inline bool keeps_filter(int algo)
 {
-    return is_winograd(algo) || algo == UCD_ALGO_FFT || algo == UCD_ALGO_WINOGRAD_FUSED || algo == UCD_ALGO_IMPLICIT_MIRROR;
+    return is_winograd(algo) || algo == UCD_ALGO_FFT || algo == UCD_ALGO_WINOGRAD_FUSED ||
+           algo == UCD_ALGO_IMPLICIT_MIRROR || algo == UCD_ALGO_WINOGRAD5_FUSED;
 }
 
 size_t ws_size(const ucd_layer_t *L, int op, int algo, int b)
@@ -111,6 +112,9 @@ size_t ws_size(const ucd_layer_t *L, int op, int algo, int b)
     case UCD_ALGO_IMPLICIT_MIRROR:
         if (!implicit_mirror_applies(d, op)) return UCD_WS_NA;
         return implicit_mirror_ws_bytes(d);
+    case UCD_ALGO_WINOGRAD5_FUSED:
+        if (!winograd5_applies(d, op)) return UCD_WS_NA;
+        return winograd5_ws_bytes(d, op);
     case UCD_ALGO_FFT:
         if (!fft_applies(d, op)) return UCD_WS_NA;
         // every frequency plane is one GEMM operand
@@ -156,6 +160,9 @@ int run_micro(const ucd_layer_t *L, int op, int algo, int b, const void *a, cons
         break;
     case UCD_ALGO_IMPLICIT_MIRROR:
         if (op == UCD_BWD_DATA) e = implicit_bwd_data_mirror(d, b, a, bsrc, out, ws, filter_ready, s);
+        break;
+    case UCD_ALGO_WINOGRAD5_FUSED:
+        if (op != UCD_BWD_FILTER) e = winograd5_fused(d, op, b, a, bsrc, out, ws, filter_ready, s);
         break;
     case UCD_ALGO_FFT:
         if (op == UCD_FWD) e = fft_fwd(d, b, a, bsrc, out, ws, filter_ready, s);

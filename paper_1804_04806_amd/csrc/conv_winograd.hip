@@ -359,18 +359,6 @@ constexpr int kFuNP = kFuC / 4;   // input patches per thread and step (channel 
 constexpr int kFuNU = kFuC;       // float4 pieces of the step's U slice per thread
 constexpr int kFuPairs = kFuC / 2;
 
-template <class F, int... I>
-__device__ __forceinline__ void static_for_impl(F &f, std::integer_sequence<int, I...>)
-{
-    (f(std::integral_constant<int, I>{}), ...);
-}
-// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>), in order
-template <int N, class F>
-__device__ __forceinline__ void static_for(F &f)
-{
-    static_for_impl(f, std::make_integer_sequence<int, N>{});
-}
-
 struct FusedParams {
     const void *in;
     const float *U;

@@ -1,0 +1,436 @@
+// Winograd F(2x2,5x5) with the data transforms fused into the GEMM kernel: Forward and BackwardData
+// of 5x5 stride-1 layers with horizontal padding 2 (fp32 tensors).
+//
+// A 2x2 output tile of a 5x5 correlation is  A^T [ (G g G^T) (.) (B^T d B) ] A  over its 6x6 input
+// patch d, with the interpolation points 0, +-1, +-2 and infinity: 36 multiplications instead of 100
+// per tile and channel pair.  B^T is the input transform of any minimal algorithm on these six
+// points (it is the one F(4x4,3x3) uses), G (6x5) evaluates the filter polynomial at the points with
+// the usual normalisation 1/4, -1/6, -1/6, 1/24, 1/24, 1, and A^T (2x6) = [1 1 1 1 1 0; 0 1 -1 2 -2 1].
+//
+// The structure is that of wino_fused_kernel (F(2x2,3x3)): the only workspace is the transformed
+// filter U[36][Ci8][Co4]; a workgroup owns 64 output channels x 64 tiles, each wave 32 x 32.  36
+// accumulator tiles do not fit a wave's registers, so the workgroup makes three passes over the
+// input channels, one per pair of rows of the 6x6 point grid (12 points, 192 accumulator
+// registers): a pass fetches the patches again, computes the two rows of B^T d B it needs, and at
+// its end folds its 12 accumulators into the 2x2 outputs, which stay in registers until the last
+// pass (A^T M A is a sum over the rows of M, so the passes' contributions simply add).
+// Patch rows are fetched as 16-byte windows starting at column 2*tw (never before the tensor);
+// the patch's first two columns are the first two window elements of the tile to the left, taken
+// from the lane below with two cross-lane moves (lane 0 fetches them itself, tiles in the first
+// tile column take 0), and window elements past the end of the row are replaced by 0.
+#include <hip/hip_runtime.h>
+
+#include "gemm_launch.hpp"
+#include "kernels.h"
+
+namespace ucd {
+
+namespace {
+
+constexpr int kW5K = 64, kW5T = 64, kW5C = 8;   // block: output channels x tiles; input channels per step
+constexpr int kW5Rows = 2;                       // rows of the 6x6 point grid per pass
+constexpr int kW5Pts = 6 * kW5Rows;              // points (accumulator tiles) per pass
+constexpr int kW5Passes = 6 / kW5Rows;
+constexpr int kW5NP = kW5C / 4;                  // patches per thread and step (channel = wave + 4h)
+constexpr int kW5NU = kW5Pts * kW5C * kW5K / 4 / 256;   // float4 pieces of a step's U slice per thread
+constexpr int kW5Pairs = kW5C / 2;
+
+struct Wino5Params {
+    const float *in;
+    const float *U;
+    float *out;
+    uint32_t in_bytes, u_bytes;
+    int Ci, Co, Hi, Wi, Ho, Wo, pad_h;
+    int T, TW, Mo4, ci_pad;
+    FastDiv divT, divTW;
+    int n_tiles, k_blocks;
+};
+
+struct Geom5 {
+    int Ci, Co, Hi, Wi, Ho, Wo, pad_h, pad_w, TH, TW, T, Mo4, ci_pad;
+    bool transposed;
+};
+
+Geom5 geom5(const Dims &d, int op)
+{
+    Geom5 g;
+    if (op == 0) {
+        g.Ci = d.C; g.Co = d.K; g.Hi = d.H; g.Wi = d.W; g.Ho = d.P; g.Wo = d.Q;
+        g.pad_h = d.ph; g.pad_w = d.pw; g.transposed = false;
+    } else {
+        g.Ci = d.K; g.Co = d.C; g.Hi = d.P; g.Wi = d.Q; g.Ho = d.H; g.Wo = d.W;
+        g.pad_h = 4 - d.ph; g.pad_w = 4 - d.pw; g.transposed = true;
+    }
+    g.TH = (g.Ho + 1) / 2; g.TW = (g.Wo + 1) / 2; g.T = g.TH * g.TW;
+    g.Mo4 = (g.Co + 3) / 4 * 4;
+    g.ci_pad = (g.Ci + kW5C - 1) / kW5C * kW5C;
+    return g;
+}
+
+// one row of B^T applied to six values
+template <int I>
+__device__ __forceinline__ float bt_row(float d0, float d1, float d2, float d3, float d4, float d5)
+{
+    if constexpr (I == 0) return fmaf(-5.f, d2, fmaf(4.f, d0, d4));
+    if constexpr (I == 1) return fmaf(-4.f, d1 + d2, d3 + d4);
+    if constexpr (I == 2) return fmaf(4.f, d1 - d2, d4 - d3);
+    if constexpr (I == 3) return fmaf(2.f, d3 - d1, d4 - d2);
+    if constexpr (I == 4) return fmaf(-2.f, d3 - d1, d4 - d2);
+    return fmaf(-5.f, d3, fmaf(4.f, d1, d5));
+}
+
+// U[xi][ci][co] = (G g G^T)[xi] of the 5x5 filter of (co, ci); planes of Cpad rows (zero past Ci)
+__global__ __launch_bounds__(256) void wino5_filter_kernel(const float *__restrict__ w, float *__restrict__ U, int Ci,
+                                                           int Co, int Mo4, int transposed, int Cpad)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= Cpad * Mo4) return;
+    const int ci = i / Mo4, co = i - ci * Mo4;
+    const bool live = co < Co && ci < Ci;
+    // G = diag(1/4, -1/6, -1/6, 1/24, 1/24, 1) . [p^k], points 0, 1, -1, 2, -2, infinity
+    auto apply_g = [](const float (&g)[5], float (&u)[6]) {
+        const float e = g[0] + g[2] + g[4], o = g[1] + g[3];
+        const float e2 = g[0] + 4.f * g[2] + 16.f * g[4], o2 = 2.f * g[1] + 8.f * g[3];
+        u[0] = 0.25f * g[0];
+        u[1] = (-1.f / 6.f) * (e + o);
+        u[2] = (-1.f / 6.f) * (e - o);
+        u[3] = (1.f / 24.f) * (e2 + o2);
+        u[4] = (1.f / 24.f) * (e2 - o2);
+        u[5] = g[4];
+    };
+    float t[6][5];  // G g, column by column
+#pragma unroll
+    for (int s = 0; s < 5; ++s) {
+        float g[5], u[6];
+#pragma unroll
+        for (int r = 0; r < 5; ++r) {
+            float v = 0.f;
+            if (live)
+                v = transposed ? w[((size_t)(ci * Co + co) * 5 + (4 - r)) * 5 + (4 - s)]
+                               : w[((size_t)(co * Ci + ci) * 5 + r) * 5 + s];
+            g[r] = v;
+        }
+        apply_g(g, u);
+#pragma unroll
+        for (int r = 0; r < 6; ++r) t[r][s] = u[r];
+    }
+    const size_t plane = (size_t)Cpad * Mo4;
+#pragma unroll
+    for (int r = 0; r < 6; ++r) {
+        float u[6];
+        apply_g(t[r], u);
+#pragma unroll
+        for (int s = 0; s < 6; ++s) U[(size_t)(r * 6 + s) * plane + i] = u[s];
+    }
+}
+
+template <bool ODD_W>
+__global__ __launch_bounds__(256) void wino5_fused_kernel(Wino5Params p)
+{
+    __shared__ __attribute__((aligned(16))) float Us[2][kW5Pts][kW5C][kW5K];
+    __shared__ __attribute__((aligned(16))) float Vs[2][kW5Pts][kW5C][kW5T];
+    // the thread's 64 outputs (16 accumulator registers x 2x2) between the passes: value v of thread t at
+    // Ys[v][t], so that a wave's accesses are contiguous
+    __shared__ float Ys[64][256];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, lhi = lane >> 5;
+    const int wk = wave & 1, wt = wave >> 1;
+
+    // consecutive work items of an XCD share a tile block (the input patches) and differ in the channel block
+    const uint32_t v = xcd_order(blockIdx.x, gridDim.x);
+    const int kb = (int)(v % (uint32_t)p.k_blocks), tb = (int)(v / (uint32_t)p.k_blocks);
+    const int k0 = kb * kW5K, t0 = tb * kW5T;
+
+    const __amdgpu_buffer_rsrc_t rin = make_rsrc_bytes(p.in, 0, p.in_bytes);
+    const __amdgpu_buffer_rsrc_t ru = make_rsrc_bytes(p.U, 0, p.u_bytes);
+
+    // producer role: the 6x6 patch of tile `lane` of the block, for channels wave, wave + 4 of the step.
+    // voff[r]: the 16-byte window of patch row r (columns 2tw .. 2tw+3 = patch columns 2..5);
+    // xoff[r]: patch columns 0, 1 of that row, fetched by lane 0 only (the other lanes get them from
+    // the lane below)
+    uint32_t voff[6], xoff[6];
+    bool first_col, ok1, ok2, ok3;
+    {
+        const int j = t0 + lane;
+        uint32_t n = 0, t, th = 0, tw = 0;
+        const bool live = j < p.n_tiles;
+        if (live) {
+            p.divT.divmod((uint32_t)j, n, t);
+            p.divTW.divmod(t, th, tw);
+        }
+        const int h0 = 2 * (int)th - p.pad_h, ws = 2 * (int)tw;
+        first_col = tw == 0;
+        ok1 = ws + 1 < p.Wi; ok2 = ws + 2 < p.Wi; ok3 = ws + 3 < p.Wi;
+#pragma unroll
+        for (int r = 0; r < 6; ++r) {
+            const int h = h0 + r;
+            const bool ok = live && (unsigned)h < (unsigned)p.Hi;
+            const uint32_t row = 4u * (uint32_t)(((int)n * p.Ci * p.Hi + h) * p.Wi + ws);
+            voff[r] = ok ? row : kOob;
+            xoff[r] = ok && lane == 0 && tw > 0 ? row - 8u : kOob;
+        }
+    }
+    // U slice of a step and pass: kW5Pts points x kW5C channels x 64 output channels, as float4: piece id =
+    // tid + 256*i -> row = id / 16 = point * kW5C + channel, 4 output channels from 4 * (id % 16); the
+    // step's and the pass's parts of the address are a scalar offset
+    uint32_t uoff[kW5NU];
+#pragma unroll
+    for (int i = 0; i < kW5NU; ++i) {
+        const int id = tid + 256 * i, row = id >> 4, q = id & 15;
+        const int xi = row / kW5C, c = row % kW5C, k = k0 + 4 * q;
+        uoff[i] = k < p.Mo4 ? 4u * (uint32_t)((xi * p.ci_pad + c) * p.Mo4 + k) : kOob;
+    }
+    const int u_slot = (tid >> 4) * kW5K + 4 * (tid & 15);
+
+    float d[kW5NP][36];   // the thread's patches of the step after the one in LDS, as loaded
+    f32x4 uq[kW5NU];      // and its share of that step's U slice
+    auto chan_off = [&](int c0, int h) {
+        const int c = c0 + wave + 4 * h;
+        return c < p.Ci ? 4u * (uint32_t)(c * p.Hi * p.Wi) : kOob;   // past the last channel: out of range
+    };
+    constexpr int kPatchLoads = 12;   // per row: the window, and lane 0's first two columns
+    auto fetch_piece = [&](int c0, int h, int i) {
+        const uint32_t so = chan_off(c0, h);
+        if (i < 6) {
+            const f32x4 q = buf_load4(rin, voff[i], so);
+            d[h][6 * i + 2] = q.x; d[h][6 * i + 3] = q.y; d[h][6 * i + 4] = q.z; d[h][6 * i + 5] = q.w;
+        } else {
+            const auto q = __builtin_amdgcn_raw_buffer_load_b64(rin, (int)xoff[i - 6], (int)so, 0);
+            d[h][6 * (i - 6)] = __uint_as_float(q[0]);
+            d[h][6 * (i - 6) + 1] = __uint_as_float(q[1]);
+        }
+    };
+    auto fetch_u = [&](int c0, int pass, int i) {
+        uq[i] = buf_load4(ru, uoff[i], 4u * (uint32_t)((c0 + pass * kW5Pts * p.ci_pad) * p.Mo4));
+    };
+    // rows 2*pass, 2*pass + 1 of B^T d B of patch h into LDS buffer `buf`
+    auto store_v = [&](auto PASS, int buf, int h) {
+        constexpr int pass = decltype(PASS)::value;
+        float x[6][6];
+#pragma unroll
+        for (int r = 0; r < 6; ++r) {
+            // window elements past the end of the row belong to the next row: 0 instead.  With an even
+            // width the second element is always inside.
+            const float w2 = d[h][6 * r + 2];
+            const float w3 = ODD_W ? (ok1 ? d[h][6 * r + 3] : 0.f) : d[h][6 * r + 3];
+            x[r][2] = w2;
+            x[r][3] = w3;
+            x[r][4] = ok2 ? d[h][6 * r + 4] : 0.f;
+            x[r][5] = ok3 ? d[h][6 * r + 5] : 0.f;
+            // columns 0, 1 = the first two window elements of the tile to the left: wave_shr:1 takes them
+            // from the lane below (lane 0 keeps what it loaded).  Tiles in the first tile column take 0;
+            // with an odd width their left neighbour's second element has just been zeroed.
+            const int l0 = __builtin_amdgcn_update_dpp((int)__float_as_uint(d[h][6 * r]), (int)__float_as_uint(w2), 0x138, 0xf, 0xf, false);
+            const int l1 = __builtin_amdgcn_update_dpp((int)__float_as_uint(d[h][6 * r + 1]), (int)__float_as_uint(w3), 0x138, 0xf, 0xf, false);
+            x[r][0] = first_col ? 0.f : __uint_as_float((uint32_t)l0);
+            x[r][1] = ODD_W ? __uint_as_float((uint32_t)l1) : first_col ? 0.f : __uint_as_float((uint32_t)l1);
+        }
+        float tr[kW5Rows][6];   // rows 2*pass, 2*pass+1 of B^T d
+#pragma unroll
+        for (int c = 0; c < 6; ++c) {
+            tr[0][c] = bt_row<2 * pass>(x[0][c], x[1][c], x[2][c], x[3][c], x[4][c], x[5][c]);
+            tr[1][c] = bt_row<2 * pass + 1>(x[0][c], x[1][c], x[2][c], x[3][c], x[4][c], x[5][c]);
+        }
+#pragma unroll
+        for (int i = 0; i < kW5Rows; ++i) {
+            const float *t = tr[i];
+            Vs[buf][6 * i + 0][wave + 4 * h][lane] = bt_row<0>(t[0], t[1], t[2], t[3], t[4], t[5]);
+            Vs[buf][6 * i + 1][wave + 4 * h][lane] = bt_row<1>(t[0], t[1], t[2], t[3], t[4], t[5]);
+            Vs[buf][6 * i + 2][wave + 4 * h][lane] = bt_row<2>(t[0], t[1], t[2], t[3], t[4], t[5]);
+            Vs[buf][6 * i + 3][wave + 4 * h][lane] = bt_row<3>(t[0], t[1], t[2], t[3], t[4], t[5]);
+            Vs[buf][6 * i + 4][wave + 4 * h][lane] = bt_row<4>(t[0], t[1], t[2], t[3], t[4], t[5]);
+            Vs[buf][6 * i + 5][wave + 4 * h][lane] = bt_row<5>(t[0], t[1], t[2], t[3], t[4], t[5]);
+        }
+    };
+    auto store_u = [&](int buf, int i) {
+        *reinterpret_cast<f32x4 *>(&Us[buf][0][0][0] + u_slot + 1024 * i) = uq[i];
+    };
+
+    auto run_pass = [&](auto PASS) {
+        constexpr int pass = decltype(PASS)::value;
+        f32x16 acc[kW5Pts];
+#pragma unroll
+        for (int i = 0; i < kW5Pts; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+
+        // step 0 -> LDS buffer 0, step 1 -> registers
+#pragma unroll
+        for (int h = 0; h < kW5NP; ++h)
+#pragma unroll
+            for (int i = 0; i < kPatchLoads; ++i) fetch_piece(0, h, i);
+#pragma unroll
+        for (int i = 0; i < kW5NU; ++i) fetch_u(0, pass, i);
+#pragma unroll
+        for (int h = 0; h < kW5NP; ++h) store_v(PASS, 0, h);
+#pragma unroll
+        for (int i = 0; i < kW5NU; ++i) store_u(0, i);
+#pragma unroll
+        for (int h = 0; h < kW5NP; ++h)
+#pragma unroll
+            for (int i = 0; i < kPatchLoads; ++i) fetch_piece(kW5C, h, i);
+#pragma unroll
+        for (int i = 0; i < kW5NU; ++i) fetch_u(kW5C, pass, i);
+        __syncthreads();
+
+        int buf = 0;
+        for (int c0 = 0; c0 < p.Ci; c0 += kW5C) {
+            const float *ua = &Us[buf][0][lhi][wk * 32 + l32];
+            const float *vb = &Vs[buf][0][lhi][wt * 32 + l32];
+            // operands in units of two channel pairs, kAhead units before their MFMAs
+            constexpr int kUnits = kW5Pts * kW5Pairs / 2, kAhead = 3;
+            float a[kAhead + 1][2], b[kAhead + 1][2];
+            auto read_unit = [&](int u) {
+                const int xi = u / (kW5Pairs / 2), q0 = 2 * (u % (kW5Pairs / 2));
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    a[u % (kAhead + 1)][q] = ua[(xi * kW5C + 2 * (q0 + q)) * kW5K];
+                    b[u % (kAhead + 1)][q] = vb[(xi * kW5C + 2 * (q0 + q)) * kW5T];
+                }
+            };
+#pragma unroll
+            for (int u = 0; u < kAhead; ++u) read_unit(u);
+            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_setprio(UCD_MFMA_PRIO);
+            constexpr int kMfmas = kW5Pts * kW5Pairs;
+            // one MFMA and the piece of the step's memory and transform work dealt out behind it (at most
+            // one global load per MFMA: a burst would block this SIMD's only wave)
+            auto slot = [&](auto M) {
+                constexpr int m = decltype(M)::value;
+                constexpr int xi = m / kW5Pairs, u = m / 2;
+                acc[xi] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u % (kAhead + 1)][m % 2], b[u % (kAhead + 1)][m % 2], acc[xi], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                if constexpr (m % 2 == 0 && u + kAhead < kUnits) read_unit(u + kAhead);
+                constexpr int kPatchSlots = 1 + kPatchLoads;
+                if constexpr (m >= 1 && m < 1 + kPatchSlots * kW5NP) {
+                    constexpr int h = (m - 1) / kPatchSlots, i = (m - 1) % kPatchSlots;
+                    if constexpr (i == 0) store_v(PASS, buf ^ 1, h);
+                    else fetch_piece(c0 + 2 * kW5C, h, i - 1);
+                }
+                constexpr int kUStart = 1 + kPatchSlots * kW5NP;
+                if constexpr (m >= kUStart && m < kUStart + 2 * kW5NU) {
+                    constexpr int i = (m - kUStart) / 2;
+                    if constexpr ((m - kUStart) % 2 == 0) store_u(buf ^ 1, i);
+                    else fetch_u(c0 + 2 * kW5C, pass, i);
+                }
+                static_assert(kUStart + 2 * kW5NU <= kMfmas, "the step's work fits behind its MFMAs");
+                __builtin_amdgcn_sched_barrier(0);
+            };
+            static_for<kMfmas>(slot);
+            __builtin_amdgcn_s_setprio(0);
+            __syncthreads();
+            buf ^= 1;
+        }
+
+        // Y += A^T[:, i] (M[i][.] A) for the pass's rows i of M, A^T = [1 1 1 1 1 0; 0 1 -1 2 -2 1]; the
+        // running sums live in LDS between the passes, the last pass stores the tile
+        constexpr float at1[6] = {0.f, 1.f, -1.f, 2.f, -2.f, 1.f};
+        constexpr bool last = pass == kW5Passes - 1;
+        const int j = t0 + wt * 32 + l32;
+        uint32_t n = 0, t, th = 0, tw = 0;
+        if (last && j < p.n_tiles) {
+            p.divT.divmod((uint32_t)j, n, t);
+            p.divTW.divmod(t, th, tw);
+        }
+        const int ho = 2 * (int)th, wo = 2 * (int)tw;
+        const bool h1 = ho + 1 < p.Ho, w1 = wo + 1 < p.Wo;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            float y[4] = {0.f, 0.f, 0.f, 0.f};
+            if constexpr (pass > 0) {
+#pragma unroll
+                for (int o = 0; o < 4; ++o) y[o] = Ys[4 * e + o][tid];
+            }
+#pragma unroll
+            for (int ii = 0; ii < kW5Rows; ++ii) {
+                constexpr int unused = 0;
+                (void)unused;
+                const int i = kW5Rows * pass + ii;
+                const float m0 = acc[6 * ii][e], m1 = acc[6 * ii + 1][e], m2 = acc[6 * ii + 2][e];
+                const float m3 = acc[6 * ii + 3][e], m4 = acc[6 * ii + 4][e], m5 = acc[6 * ii + 5][e];
+                const float r0 = (m0 + m1) + (m2 + m3) + m4;
+                const float r1 = (m1 - m2) + 2.f * (m3 - m4) + m5;
+                if (i < 5) {
+                    y[0] += r0;
+                    y[1] += r1;
+                }
+                if (i > 0) {
+                    y[2] = fmaf(at1[i], r0, y[2]);
+                    y[3] = fmaf(at1[i], r1, y[3]);
+                }
+            }
+            if constexpr (!last) {
+#pragma unroll
+                for (int o = 0; o < 4; ++o) Ys[4 * e + o][tid] = y[o];
+            } else {
+                // lane = tile (column l32 of the wave's 32), register e = channel row
+                const int k = k0 + wk * 32 + 8 * (e / 4) + 4 * lhi + (e % 4);
+                if (j < p.n_tiles && k < p.Co) {
+                    float *dst = p.out + (((long)n * p.Co + k) * p.Ho + ho) * p.Wo + wo;
+                    dst[0] = y[0];
+                    if (w1) dst[1] = y[1];
+                    if (h1) {
+                        dst[p.Wo] = y[2];
+                        if (w1) dst[p.Wo + 1] = y[3];
+                    }
+                }
+            }
+        }
+    };
+    run_pass(std::integral_constant<int, 0>{});
+    run_pass(std::integral_constant<int, 1>{});
+    run_pass(std::integral_constant<int, 2>{});
+}
+
+}  // namespace
+
+bool winograd5_applies(const Dims &d, int op)
+{
+    if (op != 0 && op != 1) return false;
+    if (d.dtype != 0 || d.R != 5 || d.S != 5 || d.sh != 1 || d.sw != 1) return false;
+    return d.pw == 2 && d.ph <= 4;   // horizontal padding 2 in both directions (4 - 2 = 2)
+}
+
+size_t winograd5_ws_bytes(const Dims &d, int op)
+{
+    const Geom5 g = geom5(d, op);
+    return (size_t)144 * g.ci_pad * g.Mo4;
+}
+
+hipError_t winograd5_fused(const Dims &d, int op, int b, const void *in, const void *w, void *out, float *ws,
+                           bool filter_ready, hipStream_t s)
+{
+    const Geom5 g = geom5(d, op);
+    LaunchLog *log = launch_log();
+    if (filter_ready) {
+        // U of this filter is still in the workspace from the previous micro-batch
+    } else if (log) {
+        log->add("wino5_filter_kernel");
+    } else {
+        wino5_filter_kernel<<<(unsigned)((g.ci_pad * g.Mo4 + 255) / 256), 256, 0, s>>>((const float *)w, ws, g.Ci, g.Co, g.Mo4,
+                                                                                     g.transposed ? 1 : 0, g.ci_pad);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    Wino5Params p{};
+    p.in = (const float *)in; p.U = ws; p.out = (float *)out;
+    p.in_bytes = (uint32_t)(4 * (size_t)b * g.Ci * g.Hi * g.Wi);
+    p.u_bytes = (uint32_t)((size_t)144 * g.ci_pad * g.Mo4);
+    p.Ci = g.Ci; p.Co = g.Co; p.Hi = g.Hi; p.Wi = g.Wi; p.Ho = g.Ho; p.Wo = g.Wo; p.pad_h = g.pad_h;
+    p.T = g.T; p.TW = g.TW; p.Mo4 = g.Mo4; p.ci_pad = g.ci_pad;
+    p.divT = FastDiv(g.T); p.divTW = FastDiv(g.TW);
+    p.n_tiles = b * g.T;
+    p.k_blocks = (g.Co + kW5K - 1) / kW5K;
+    const unsigned blocks = (unsigned)(p.k_blocks * ((p.n_tiles + kW5T - 1) / kW5T));
+    if (log) {
+        log->add("wino5_fused_kernel blocks=" + std::to_string(blocks) + " gemm_flops=" +
+                 std::to_string(2.0 * 36 * g.Co * (double)p.n_tiles * g.Ci));
+        return hipSuccess;
+    }
+    if (g.Wi % 2) wino5_fused_kernel<true><<<blocks, 256, 0, s>>>(p);
+    else wino5_fused_kernel<false><<<blocks, 256, 0, s>>>(p);
+    return hipGetLastError();
+}
+
+}  // namespace ucd

@@ -18,6 +18,7 @@
 
 #include <string>
 #include <type_traits>
+#include <utility>
 
 namespace ucd {
 
@@ -121,6 +122,19 @@ struct NoSetup {
 // gets the byte offset kOob, which the hardware range check turns into 0 without touching
 // memory.  That keeps the loads branch-free so that they can be issued back to back.  Operands
 // are therefore limited to 2 GiB each (checked on the host).
+
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F &f, std::integer_sequence<int, I...>)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>), in order: a loop whose index is a
+// compile-time constant in every iteration
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &f)
+{
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
 
 constexpr uint32_t kOob = 0x80000000u;
 

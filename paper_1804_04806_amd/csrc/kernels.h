@@ -26,6 +26,13 @@ inline uint32_t wbytes(const Dims &d) { return (uint32_t)(d.esize() * d.K * d.cr
 inline uint32_t xbytes(const Dims &d, int b) { return (uint32_t)(d.esize() * b * d.C * d.H * d.W); }
 inline uint32_t ybytes(const Dims &d, int b) { return (uint32_t)(d.esize() * b * d.K * d.P * d.Q); }
 
+// Winograd F(2x2,5x5) with fused transforms: Forward / BackwardData of 5x5 stride-1 layers with
+// horizontal padding 2, fp32 tensors; workspace = the transformed filter (144 * Ci8 * Co4 bytes)
+bool winograd5_applies(const Dims &d, int op);
+size_t winograd5_ws_bytes(const Dims &d, int op);
+hipError_t winograd5_fused(const Dims &d, int op, int b, const void *in, const void *w, void *out, float *ws,
+                           bool filter_ready, hipStream_t s);
+
 // zero-workspace implicit GEMM
 hipError_t implicit_fwd(const Dims &d, int b, const void *x, const void *w, void *y, hipStream_t s);
 hipError_t implicit_bwd_data(const Dims &d, int b, const void *dy, const void *w, void *dx, hipStream_t s);

@@ -13,18 +13,18 @@ LIB_PATH = os.path.join(_HERE, "libucd.so")
 
 FWD, BWD_DATA, BWD_FILTER = 0, 1, 2
 ALGO_IMPLICIT, ALGO_IM2COL, ALGO_WINOGRAD, ALGO_WINOGRAD4, ALGO_FFT, ALGO_WINOGRAD_FUSED = 0, 1, 2, 3, 4, 5
-ALGO_IMPLICIT_MIRROR = 6
-N_ALGO = 7
+ALGO_IMPLICIT_MIRROR, ALGO_WINOGRAD5_FUSED = 6, 7
+N_ALGO = 8
 POLICY_UNDIVIDED, POLICY_POW2, POLICY_ALL = 0, 1, 2
 TIME_INF = (1 << 64) - 1
 WS_NA = (1 << 64) - 1
 OK, E_INVALID, E_NULLPTR, E_UNSUPPORTED, E_WS_TOO_SMALL, E_HIP, E_NOMEM, E_INFEASIBLE = 0, -1, -2, -3, -4, -5, -6, -7
 
-WINOGRAD_ALGOS = (ALGO_WINOGRAD, ALGO_WINOGRAD4, ALGO_WINOGRAD_FUSED)
+WINOGRAD_ALGOS = (ALGO_WINOGRAD, ALGO_WINOGRAD4, ALGO_WINOGRAD_FUSED, ALGO_WINOGRAD5_FUSED)
 # algorithms that reach the direct result through transforms (looser rounding bound than the GEMM paths)
 TRANSFORM_ALGOS = WINOGRAD_ALGOS + (ALGO_FFT,)
 ALGO_NAMES = {0: "implicit", 1: "im2col", 2: "winograd", 3: "winograd4", 4: "fft", 5: "winograd-fused",
-              6: "implicit-mirror"}
+              6: "implicit-mirror", 7: "winograd5x5-fused"}
 OP_NAMES = {0: "fwd", 1: "bwd_data", 2: "bwd_filter"}
 
 EXPORTS = [

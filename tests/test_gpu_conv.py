@@ -13,7 +13,8 @@ pytestmark = pytest.mark.gpu
 # measure 3e-7 (2x2 tiles) to 4e-6 (4x4 tiles), so they are held to 1e-4 here, and the tiled FFT
 # (1e-7 to 2e-7) to the GEMM paths' bound.
 TOL = {ucd.ALGO_IMPLICIT: 1e-5, ucd.ALGO_IM2COL: 1e-5, ucd.ALGO_WINOGRAD: 1e-4, ucd.ALGO_WINOGRAD4: 1e-4,
-       ucd.ALGO_FFT: 1e-5, ucd.ALGO_WINOGRAD_FUSED: 1e-4, ucd.ALGO_IMPLICIT_MIRROR: 1e-5}
+       ucd.ALGO_FFT: 1e-5, ucd.ALGO_WINOGRAD_FUSED: 1e-4, ucd.ALGO_IMPLICIT_MIRROR: 1e-5,
+       ucd.ALGO_WINOGRAD5_FUSED: 1e-4}
 
 # sizes span several tiles (128-wide) with ragged tails in M, N and the reduction
 SHAPES = [
@@ -41,6 +42,7 @@ SHAPES = [
     Shape(2, 64, 10, 10, 40, 3, 3, 2, 1, "c64-s2"),             # BackwardData phases with 4, 2, 2 and 1 taps: both filter loaders
     Shape(3, 24, 56, 56, 64, 3, 3, 1, 1, "k64-wide"),          # 64-row tiles over many column tiles
     Shape(3, 96, 56, 56, 96, 3, 3, 1, 1, "c96-wide"),          # 96-row tiles, Forward and BackwardData, many column tiles
+    Shape(2, 20, 10, 12, 70, 5, 5, 1, 2, "5x5-even"),          # F(2x2,5x5) tiles at an even width; K > 64 with a tail
 ]
 
 DIVISIONS = {8: [[8], [1] * 8, [3, 5]], 5: [[5], [2, 3]], 4: [[4], [1, 3]], 3: [[3], [1, 2]],
