@@ -75,6 +75,6 @@ def test_load_rejects_garbage(tmp_path):
 
 def test_put_validation():
     L = ucd.layer(N=4, C=8, H=9, W=9, K=8, R=3, S=3)
-    for args in ((ucd.FWD, 7, 1, 10), (5, 0, 1, 10), (ucd.FWD, 0, 0, 10), (ucd.FWD, 0, 1, 0)):
+    for args in ((ucd.FWD, ucd.N_ALGO, 1, 10), (5, 0, 1, 10), (ucd.FWD, 0, 0, 10), (ucd.FWD, 0, 1, 0)):
         with pytest.raises(ucd.UcdError):
             ucd.ucd_bench_put(L, *args)
