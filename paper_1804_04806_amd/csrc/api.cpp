@@ -163,6 +163,7 @@ int run_micro(const ucd_layer_t *L, int op, int algo, int b, const void *a, cons
         break;
     case UCD_ALGO_WINOGRAD5_FUSED:
         if (op != UCD_BWD_FILTER) e = winograd5_fused(d, op, b, a, bsrc, out, ws, filter_ready, s);
+        else e = winograd5_fused_filter(d, b, a, bsrc, (float *)out, beta, ws, s);
         break;
     case UCD_ALGO_FFT:
         if (op == UCD_FWD) e = fft_fwd(d, b, a, bsrc, out, ws, filter_ready, s);

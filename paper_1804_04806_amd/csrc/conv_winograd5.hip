@@ -383,17 +383,305 @@ __global__ __launch_bounds__(256) void wino5_fused_kernel(Wino5Params p)
     run_pass(std::integral_constant<int, 2>{});
 }
 
+
+// ---- BackwardFilter: F(5x5,2x2) with both data transforms fused ------------------------------------
+// dw (5x5) = G^T [ sum over tiles (A dy A^T) (.) (B^T x B) ] G with A = (A^T)^T (6x2): a 2x2 tile of
+// dy and its 6x6 patch of x give 36 products per channel pair.  The workspace holds the 36 K x C
+// planes Mw.  As in wino_fused_filter_kernel a workgroup owns 64 output channels x 64 input channels
+// and reduces over 8 tile positions of the image (fixed for the workgroup) times a range of images, one
+// image per step; here it also owns one pair of rows of the point grid (12 planes), so three workgroups
+// share every chunk.  Patch rows of x are fetched as 16-byte windows starting at column 2*tw, the
+// patch's first two columns come from the lane below (the tile to the left, same channel) or, for the
+// first tile position of a group, from a load of its own; tile rows of dy as 8-byte loads.
+constexpr int kF5T = 8, kF5Ld = 64, kF5Pairs = kF5T / 2;
+
+struct Wino5FilterParams {
+    const float *x, *dy;
+    float *Mw;
+    uint32_t x_bytes, dy_bytes;
+    int C, K, H, W, P, Q, pad_h, T, TW;
+    int b, k_blocks, c_blocks, groups, images_per_chunk;
+};
+
+template <bool ODD_W>
+__global__ __launch_bounds__(256) void wino5_fused_filter_kernel(Wino5FilterParams p)
+{
+    __shared__ __attribute__((aligned(16))) float Ds[2][kW5Pts][kF5T][kF5Ld];
+    __shared__ __attribute__((aligned(16))) float Vs[2][kW5Pts][kF5T][kF5Ld];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, lhi = lane >> 5;
+    const int wk = wave & 1, wc = wave >> 1;
+
+    // work item: (pass, output-channel block, input-channel block, tile-position group, image chunk);
+    // neighbours on an XCD share the x patches and dy tiles
+    uint32_t v = xcd_order(blockIdx.x, gridDim.x);
+    const int pass = __builtin_amdgcn_readfirstlane((int)(v % (uint32_t)kW5Passes)); v /= (uint32_t)kW5Passes;
+    const int kb = (int)(v % (uint32_t)p.k_blocks); v /= (uint32_t)p.k_blocks;
+    const int cb = (int)(v % (uint32_t)p.c_blocks); v /= (uint32_t)p.c_blocks;
+    const int grp = (int)(v % (uint32_t)p.groups);
+    const int chunk = (int)(v / (uint32_t)p.groups);
+    const int k0 = kb * 64, c0 = cb * 64;
+    const int n_begin = chunk * p.images_per_chunk, n_end = min(p.b, n_begin + p.images_per_chunk);
+
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc_bytes(p.x, 0, p.x_bytes);
+    const __amdgpu_buffer_rsrc_t rdy = make_rsrc_bytes(p.dy, 0, p.dy_bytes);
+
+    // producer role: tile position tid % 8 of the group, channel tid / 8 (and + 32) of both blocks; offsets
+    // within image 0.  LDS slabs are [point][tile position][64 channels] with channel c of tile position t
+    // at column c ^ 4t (conflict-free stores, operand reads with immediate offsets).
+    const int ptile = tid & 7, pch = tid >> 3;
+    const int pcol = pch ^ (4 * ptile);
+    uint32_t vx[2][12], vd[2][2];   // x: window starts of the 6 patch rows, then this lane's own first columns
+    bool own_col, ok1, ok2, ok3, dy_ok1;
+    {
+        const int t = grp * kF5T + ptile;
+        const bool live = t < p.T;
+        const int th = live ? t / p.TW : 0, tw = live ? t % p.TW : 0;
+        const int h0 = 2 * th - p.pad_h, ws = 2 * tw;
+        own_col = ptile == 0 || tw == 0;
+        ok1 = ws + 1 < p.W; ok2 = ws + 2 < p.W; ok3 = ws + 3 < p.W;
+        dy_ok1 = ws + 1 < p.Q;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int c = c0 + pch + 32 * h, k = k0 + pch + 32 * h;
+#pragma unroll
+            for (int r = 0; r < 6; ++r) {
+                const int hh = h0 + r;
+                const bool ok = live && c < p.C && (unsigned)hh < (unsigned)p.H;
+                const uint32_t row = 4u * (uint32_t)((c * p.H + hh) * p.W + ws);
+                vx[h][r] = ok ? row : kOob;
+                vx[h][6 + r] = ok && ptile == 0 && tw > 0 ? row - 8u : kOob;
+            }
+#pragma unroll
+            for (int r = 0; r < 2; ++r) {
+                const int hh = 2 * th + r;
+                const bool ok = live && k < p.K && hh < p.P;
+                vd[h][r] = ok ? 4u * (uint32_t)((k * p.P + hh) * p.Q + ws) : kOob;
+            }
+        }
+    }
+    const uint32_t x_image = 4u * (uint32_t)(p.C * p.H * p.W), dy_image = 4u * (uint32_t)(p.K * p.P * p.Q);
+
+    float dx[2][36], dz[2][4];   // the thread's patches / tiles of the image after the one in LDS, as loaded
+    constexpr int kXLoads = 12, kDyLoads = 2;
+    // an image past the chunk's end gets a scalar offset that pushes every address out of range
+    auto fetch_x = [&](int n, int h, int i) {
+        const uint32_t so = n < n_end ? (uint32_t)n * x_image : kOob;
+        if (i < 6) {
+            const f32x4 q = buf_load4(rx, vx[h][i], so);
+            dx[h][6 * i + 2] = q.x; dx[h][6 * i + 3] = q.y; dx[h][6 * i + 4] = q.z; dx[h][6 * i + 5] = q.w;
+        } else {
+            const auto q = __builtin_amdgcn_raw_buffer_load_b64(rx, (int)vx[h][i], (int)so, 0);
+            dx[h][6 * (i - 6)] = __uint_as_float(q[0]);
+            dx[h][6 * (i - 6) + 1] = __uint_as_float(q[1]);
+        }
+    };
+    auto fetch_dy = [&](int n, int h, int i) {
+        const uint32_t so = n < n_end ? (uint32_t)n * dy_image : kOob;
+        const auto q = __builtin_amdgcn_raw_buffer_load_b64(rdy, (int)vd[h][i], (int)so, 0);
+        dz[h][2 * i] = __uint_as_float(q[0]);
+        dz[h][2 * i + 1] = __uint_as_float(q[1]);
+    };
+    // rows 2*pass, 2*pass+1 of B^T x B of patch h
+    auto store_v = [&](auto PASS, int buf, int h) {
+        constexpr int ps = decltype(PASS)::value;
+        float x[6][6];
+#pragma unroll
+        for (int r = 0; r < 6; ++r) {
+            const float w2 = dx[h][6 * r + 2];
+            const float w3 = ODD_W ? (ok1 ? dx[h][6 * r + 3] : 0.f) : dx[h][6 * r + 3];
+            x[r][2] = w2;
+            x[r][3] = w3;
+            x[r][4] = ok2 ? dx[h][6 * r + 4] : 0.f;
+            x[r][5] = ok3 ? dx[h][6 * r + 5] : 0.f;
+            // the lane below holds the tile to the left (same channel) unless this is the first tile
+            // position of the group or of a tile row: then the lane's own load (0 in the first tile column)
+            const int l0 = __builtin_amdgcn_update_dpp(0, (int)__float_as_uint(w2), 0x138, 0xf, 0xf, false);
+            const int l1 = __builtin_amdgcn_update_dpp(0, (int)__float_as_uint(w3), 0x138, 0xf, 0xf, false);
+            x[r][0] = own_col ? dx[h][6 * r] : __uint_as_float((uint32_t)l0);
+            x[r][1] = own_col ? dx[h][6 * r + 1] : __uint_as_float((uint32_t)l1);
+        }
+        float tr[kW5Rows][6];
+#pragma unroll
+        for (int c = 0; c < 6; ++c) {
+            tr[0][c] = bt_row<2 * ps>(x[0][c], x[1][c], x[2][c], x[3][c], x[4][c], x[5][c]);
+            tr[1][c] = bt_row<2 * ps + 1>(x[0][c], x[1][c], x[2][c], x[3][c], x[4][c], x[5][c]);
+        }
+#pragma unroll
+        for (int i = 0; i < kW5Rows; ++i) {
+            const float *t = tr[i];
+            Vs[buf][6 * i + 0][ptile][pcol + 32 * h] = bt_row<0>(t[0], t[1], t[2], t[3], t[4], t[5]);
+            Vs[buf][6 * i + 1][ptile][pcol + 32 * h] = bt_row<1>(t[0], t[1], t[2], t[3], t[4], t[5]);
+            Vs[buf][6 * i + 2][ptile][pcol + 32 * h] = bt_row<2>(t[0], t[1], t[2], t[3], t[4], t[5]);
+            Vs[buf][6 * i + 3][ptile][pcol + 32 * h] = bt_row<3>(t[0], t[1], t[2], t[3], t[4], t[5]);
+            Vs[buf][6 * i + 4][ptile][pcol + 32 * h] = bt_row<4>(t[0], t[1], t[2], t[3], t[4], t[5]);
+            Vs[buf][6 * i + 5][ptile][pcol + 32 * h] = bt_row<5>(t[0], t[1], t[2], t[3], t[4], t[5]);
+        }
+    };
+    // rows 2*pass, 2*pass+1 of A z A^T of tile h, A = [1 0; 1 1; 1 -1; 1 2; 1 -2; 0 1]
+    auto store_d = [&](auto PASS, int buf, int h) {
+        constexpr int ps = decltype(PASS)::value;
+        constexpr float a0[6] = {1.f, 1.f, 1.f, 1.f, 1.f, 0.f}, a1[6] = {0.f, 1.f, -1.f, 2.f, -2.f, 1.f};
+        const float z00 = dz[h][0], z01 = ODD_W ? (dy_ok1 ? dz[h][1] : 0.f) : dz[h][1];
+        const float z10 = dz[h][2], z11 = ODD_W ? (dy_ok1 ? dz[h][3] : 0.f) : dz[h][3];
+#pragma unroll
+        for (int ii = 0; ii < kW5Rows; ++ii) {
+            constexpr int unused = 0;
+            (void)unused;
+            const int i = kW5Rows * ps + ii;
+            const float t0 = a0[i] * z00 + a1[i] * z10, t1 = a0[i] * z01 + a1[i] * z11;
+            Ds[buf][6 * ii + 0][ptile][pcol + 32 * h] = t0;
+            Ds[buf][6 * ii + 1][ptile][pcol + 32 * h] = t0 + t1;
+            Ds[buf][6 * ii + 2][ptile][pcol + 32 * h] = t0 - t1;
+            Ds[buf][6 * ii + 3][ptile][pcol + 32 * h] = fmaf(2.f, t1, t0);
+            Ds[buf][6 * ii + 4][ptile][pcol + 32 * h] = fmaf(-2.f, t1, t0);
+            Ds[buf][6 * ii + 5][ptile][pcol + 32 * h] = t1;
+        }
+    };
+
+    int col_q[kF5Pairs];   // the lane's column within its wave's 32, as stored for tile position 2q + lhi
+#pragma unroll
+    for (int q = 0; q < kF5Pairs; ++q) col_q[q] = l32 ^ (4 * (2 * q + lhi));
+
+    auto run = [&](auto PASS) {
+        f32x16 acc[kW5Pts];
+#pragma unroll
+        for (int i = 0; i < kW5Pts; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+#pragma unroll
+            for (int i = 0; i < kXLoads; ++i) fetch_x(n_begin, h, i);
+#pragma unroll
+            for (int i = 0; i < kDyLoads; ++i) fetch_dy(n_begin, h, i);
+        }
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            store_v(PASS, 0, h);
+            store_d(PASS, 0, h);
+        }
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+#pragma unroll
+            for (int i = 0; i < kXLoads; ++i) fetch_x(n_begin + 1, h, i);
+#pragma unroll
+            for (int i = 0; i < kDyLoads; ++i) fetch_dy(n_begin + 1, h, i);
+        }
+        __syncthreads();
+
+        int buf = 0;
+        for (int n = n_begin; n < n_end; ++n) {
+            const float *da = &Ds[buf][0][lhi][wk * 32];
+            const float *vb = &Vs[buf][0][lhi][wc * 32];
+            float a[2][kF5Pairs], b[2][kF5Pairs];
+            auto read_ops = [&](int xi) {
+#pragma unroll
+                for (int q = 0; q < kF5Pairs; ++q) {
+                    a[xi & 1][q] = da[(xi * kF5T + 2 * q) * kF5Ld + col_q[q]];
+                    b[xi & 1][q] = vb[(xi * kF5T + 2 * q) * kF5Ld + col_q[q]];
+                }
+            };
+            read_ops(0);
+            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_setprio(UCD_MFMA_PRIO);
+            constexpr int kMfmas = kW5Pts * kF5Pairs;
+            auto slot = [&](auto M) {
+                constexpr int m = decltype(M)::value;
+                constexpr int xi = m / kF5Pairs, q = m % kF5Pairs;
+                acc[xi] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[xi & 1][q], b[xi & 1][q], acc[xi], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                if constexpr (q == 0 && xi + 1 < kW5Pts) read_ops(xi + 1);
+                // image n + 1 (in registers) is transformed into the other LDS buffer and every register
+                // reloaded with image n + 2: one piece, at most one global load, behind each MFMA
+                constexpr int kXSlots = 1 + kXLoads, kDySlots = 1 + kDyLoads, kDyStart = 1 + 2 * kXSlots;
+                if constexpr (m >= 1 && m < kDyStart) {
+                    constexpr int h = (m - 1) / kXSlots, i = (m - 1) % kXSlots;
+                    if constexpr (i == 0) store_v(PASS, buf ^ 1, h);
+                    else fetch_x(n + 2, h, i - 1);
+                }
+                if constexpr (m >= kDyStart && m < kDyStart + 2 * kDySlots) {
+                    constexpr int h = (m - kDyStart) / kDySlots, i = (m - kDyStart) % kDySlots;
+                    if constexpr (i == 0) store_d(PASS, buf ^ 1, h);
+                    else fetch_dy(n + 2, h, i - 1);
+                }
+                static_assert(kDyStart + 2 * kDySlots <= kMfmas, "the step's work fits behind its MFMAs");
+                __builtin_amdgcn_sched_barrier(0);
+            };
+            static_for<kMfmas>(slot);
+            __builtin_amdgcn_s_setprio(0);
+            __syncthreads();
+            buf ^= 1;
+        }
+
+        // lane = input channel (column l32 of the wave's 32), register e = output-channel row
+        constexpr int ps = decltype(PASS)::value;
+        const int c = c0 + wc * 32 + l32;
+        if (c >= p.C) return;
+        const size_t plane = (size_t)p.K * p.C;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int k = k0 + wk * 32 + 8 * (e / 4) + 4 * lhi + (e % 4);
+            if (k >= p.K) continue;
+#pragma unroll
+            for (int xi = 0; xi < kW5Pts; ++xi)
+                unsafeAtomicAdd(p.Mw + (size_t)(kW5Pts * ps + xi) * plane + (size_t)k * p.C + c, acc[xi][e]);
+        }
+    };
+    if (pass == 0) run(std::integral_constant<int, 0>{});
+    else if (pass == 1) run(std::integral_constant<int, 1>{});
+    else run(std::integral_constant<int, 2>{});
+}
+
+// dw[k, c] (5x5) = beta * dw[k, c] + G^T Mw[., k, c] G, one thread per (k, c)
+__global__ __launch_bounds__(256) void wino5_dw_kernel(const float *__restrict__ Mw, float *__restrict__ dw, int KC, float beta)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= KC) return;
+    // G^T m for six values m at the points 0, 1, -1, 2, -2, infinity
+    auto apply_gt = [](const float (&m)[6], float (&w)[5]) {
+        const float s1 = (-1.f / 6.f) * (m[1] + m[2]), d1 = (-1.f / 6.f) * (m[1] - m[2]);
+        const float s2 = (1.f / 24.f) * (m[3] + m[4]), d2 = (1.f / 24.f) * (m[3] - m[4]);
+        w[0] = 0.25f * m[0] + s1 + s2;
+        w[1] = d1 + 2.f * d2;
+        w[2] = s1 + 4.f * s2;
+        w[3] = d1 + 8.f * d2;
+        w[4] = s1 + 16.f * s2 + m[5];
+    };
+    float tr[5][6];   // G^T Mw, column by column
+#pragma unroll
+    for (int s = 0; s < 6; ++s) {
+        float m[6], w5[5];
+#pragma unroll
+        for (int r = 0; r < 6; ++r) m[r] = Mw[(size_t)(r * 6 + s) * KC + i];
+        apply_gt(m, w5);
+#pragma unroll
+        for (int r = 0; r < 5; ++r) tr[r][s] = w5[r];
+    }
+    float *dst = dw + (size_t)i * 25;
+#pragma unroll
+    for (int r = 0; r < 5; ++r) {
+        float w5[5];
+        apply_gt(tr[r], w5);
+#pragma unroll
+        for (int s = 0; s < 5; ++s) dst[r * 5 + s] = beta == 0.f ? w5[s] : beta * dst[r * 5 + s] + w5[s];
+    }
+}
+
 }  // namespace
 
 bool winograd5_applies(const Dims &d, int op)
 {
-    if (op != 0 && op != 1) return false;
+    if (op < 0 || op > 2) return false;
     if (d.dtype != 0 || d.R != 5 || d.S != 5 || d.sh != 1 || d.sw != 1) return false;
     return d.pw == 2 && d.ph <= 4;   // horizontal padding 2 in both directions (4 - 2 = 2)
 }
 
 size_t winograd5_ws_bytes(const Dims &d, int op)
 {
+    if (op == 2) return (size_t)144 * d.K * d.C;   // the 36 product planes
     const Geom5 g = geom5(d, op);
     return (size_t)144 * g.ci_pad * g.Mo4;
 }
@@ -430,6 +718,48 @@ hipError_t winograd5_fused(const Dims &d, int op, int b, const void *in, const v
     }
     if (g.Wi % 2) wino5_fused_kernel<true><<<blocks, 256, 0, s>>>(p);
     else wino5_fused_kernel<false><<<blocks, 256, 0, s>>>(p);
+    return hipGetLastError();
+}
+
+hipError_t winograd5_fused_filter(const Dims &d, int b, const void *x, const void *dy, float *dw, float beta, float *ws,
+                                  hipStream_t s)
+{
+    const Geom5 g = geom5(d, 0);
+    const int KC = d.K * d.C;
+    hipError_t e = fill_zero(ws, (size_t)36 * KC, s);
+    if (e != hipSuccess) return e;
+    Wino5FilterParams p{};
+    p.x = (const float *)x; p.dy = (const float *)dy; p.Mw = ws;
+    p.x_bytes = xbytes(d, b); p.dy_bytes = ybytes(d, b);
+    p.C = d.C; p.K = d.K; p.H = d.H; p.W = d.W; p.P = d.P; p.Q = d.Q; p.pad_h = d.ph; p.T = g.T; p.TW = g.TW;
+    p.b = b;
+    p.k_blocks = (d.K + 63) / 64; p.c_blocks = (d.C + 63) / 64; p.groups = (g.T + kF5T - 1) / kF5T;
+    // image chunks: about four rounds of one workgroup per CU, chunks of at least 4 images; among the
+    // counts near that, the one whose workgroup count fills its rounds best
+    const long items = (long)kW5Passes * p.k_blocks * p.c_blocks * p.groups, cus = device_cus();
+    const long want = (4 * cus + items - 1) / items, cap = b / 4 < 1 ? 1 : b / 4;
+    long split = want > cap ? cap : want;
+    double best = -1.0;
+    for (long c = (want + 1) / 2; c <= 2 * want && c <= cap; ++c) {
+        const int per = (int)((b + c - 1) / c);
+        const long wgs = items * ((b + per - 1) / per);
+        const double fill = (double)wgs / (double)((wgs + cus - 1) / cus * cus);
+        if (fill > best + 1e-9) { best = fill; split = c; }
+    }
+    p.images_per_chunk = (int)((b + split - 1) / split);
+    const int n_split = (b + p.images_per_chunk - 1) / p.images_per_chunk;
+    const unsigned blocks = (unsigned)(items * n_split);
+    LaunchLog *log = launch_log();
+    if (log) {
+        log->add("wino5_fused_filter_kernel blocks=" + std::to_string(blocks) + " gemm_flops=" +
+                 std::to_string(2.0 * 36 * d.K * (double)d.C * p.groups * kF5T * b));
+        log->add("wino5_dw_kernel");
+        return hipSuccess;
+    }
+    if (d.W % 2) wino5_fused_filter_kernel<true><<<blocks, 256, 0, s>>>(p);
+    else wino5_fused_filter_kernel<false><<<blocks, 256, 0, s>>>(p);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    wino5_dw_kernel<<<(unsigned)((KC + 255) / 256), 256, 0, s>>>(ws, dw, KC, beta);
     return hipGetLastError();
 }
 

@@ -32,6 +32,9 @@ bool winograd5_applies(const Dims &d, int op);
 size_t winograd5_ws_bytes(const Dims &d, int op);
 hipError_t winograd5_fused(const Dims &d, int op, int b, const void *in, const void *w, void *out, float *ws,
                            bool filter_ready, hipStream_t s);
+// BackwardFilter as F(5x5,2x2): workspace = the 36 K x C product planes (144 * K * C bytes); fp32 atomics
+hipError_t winograd5_fused_filter(const Dims &d, int b, const void *x, const void *dy, float *dw, float beta, float *ws,
+                                  hipStream_t s);
 
 // zero-workspace implicit GEMM
 hipError_t implicit_fwd(const Dims &d, int b, const void *x, const void *w, void *y, hipStream_t s);
