@@ -84,9 +84,10 @@ enum {
                                      Forward implicit GEMM of the mirrored layer on a copy of the
                                      filter with channels transposed and taps reversed: workspace =
                                      that copy, whatever the micro-batch size */
-    UCD_ALGO_WINOGRAD5_FUSED = 7, /* Winograd F(2x2,5x5) with the data transforms inside the GEMM kernel:
-                                     Forward and BackwardData of 5x5 stride-1 layers with horizontal padding
-                                     2, fp32 tensors; workspace = the transformed filter */
+    UCD_ALGO_WINOGRAD5_FUSED = 7, /* Winograd F(2x2,5x5) (BackwardFilter: F(5x5,2x2)) with the data transforms
+                                     inside the GEMM kernel: 5x5 stride-1 layers with horizontal padding 2,
+                                     fp32 tensors; workspace = the transformed filter (BackwardFilter: the
+                                     36 K x C product planes) */
     UCD_N_ALGO = 8
 };
 
@@ -112,7 +113,7 @@ int ucd_version(void);
  * up to rounding (and micro-batched == undivided likewise):
  *   - BackwardFilter, every algorithm: the reduction over b*P*Q is split over workgroups whenever
  *     it is long enough (always at the benchmark sizes), and micro-batches accumulate into dw;
- *   - Forward / BackwardData, implicit GEMM, fp32 tensors only: when the output has fewer than 768
+ *   - Forward / BackwardData, implicit GEMM (also on the mirrored filter copy), fp32 tensors only: when the output has fewer than 768
  *     tiles the reduction over C*R*S is split the same way into a zero-filled output, and when the
  *     tile count is not a multiple of 256 the last tiles' reductions are spread over several
  *     workgroups.
@@ -142,7 +143,7 @@ int ucd_set_deterministic(int on);
  *              to 4; BackwardFilter: K*C in place of Ci*Co4, tiles over (P, Q)
  *   Winograd, fused transforms   64 * Ci8*Co4 (the transformed filter, Ci8 = Ci rounded up to 8);
  *              BackwardFilter 64 * K*C
- *   Winograd F(2x2,5x5), fused transforms   144 * Ci8*Co4
+ *   Winograd F(2x2,5x5), fused transforms   144 * Ci8*Co4; BackwardFilter 144 * K*C
  *   FFT        4 * 144 * (2Ci*M4 + ld*(2Ci + 2Co)), M4 = 2Co rounded up to 4, ld = b *
  *              ceil(Ho/(17-R)) * ceil(Wo/(17-S)) rounded up to 4, (Ci, Co, Ho, Wo) as for Winograd;
  *              BackwardFilter: 4*K*C in place of 2Ci*M4, tiles over (P, Q)

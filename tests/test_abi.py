@@ -58,6 +58,17 @@ def test_workspace_formulas():
     assert ucd.ucd_workspace_size(L, ucd.BWD_FILTER, ucd.ALGO_IMPLICIT_MIRROR, 5) == ucd.WS_NA
     Lb = ucd.layer(N=8, C=3, H=16, W=16, K=5, R=3, S=3, pad_h=1, pad_w=1, dtype=1)
     assert ucd.ucd_workspace_size(Lb, ucd.BWD_DATA, ucd.ALGO_IMPLICIT_MIRROR, 1) == 272   # 2 x 135 -> 16-byte multiple
+    # Winograd F(2x2,5x5), fused: 36 planes of the transformed filter (Ci rounded up to 8, Co to 4);
+    # BackwardFilter: the 36 K x C product planes; 5x5 stride-1 layers with horizontal padding 2, fp32
+    L5 = ucd.layer(N=8, C=20, H=16, W=16, K=30, R=5, S=5, pad_h=2, pad_w=2)
+    assert ucd.ucd_workspace_size(L5, ucd.FWD, ucd.ALGO_WINOGRAD5_FUSED, 8) == 144 * 24 * 32
+    assert ucd.ucd_workspace_size(L5, ucd.BWD_DATA, ucd.ALGO_WINOGRAD5_FUSED, 3) == 144 * 32 * 20
+    assert ucd.ucd_workspace_size(L5, ucd.BWD_FILTER, ucd.ALGO_WINOGRAD5_FUSED, 1) == 144 * 30 * 20
+    assert ucd.ucd_workspace_size(L, ucd.FWD, ucd.ALGO_WINOGRAD5_FUSED, 1) == ucd.WS_NA          # 3x3
+    assert ucd.ucd_workspace_size(ucd.layer(N=8, C=20, H=16, W=16, K=30, R=5, S=5, pad_h=2, pad_w=1),
+                                  ucd.FWD, ucd.ALGO_WINOGRAD5_FUSED, 1) == ucd.WS_NA             # padding 1
+    assert ucd.ucd_workspace_size(ucd.layer(N=8, C=20, H=16, W=16, K=30, R=5, S=5, pad_h=2, pad_w=2, dtype=1),
+                                  ucd.FWD, ucd.ALGO_WINOGRAD5_FUSED, 1) == ucd.WS_NA             # bf16
     Ls2 = ucd.layer(N=8, C=16, H=16, W=16, K=32, R=3, S=3, pad_h=1, pad_w=1, stride_h=2, stride_w=2)
     assert ucd.ucd_workspace_size(Ls2, ucd.BWD_FILTER, ucd.ALGO_WINOGRAD, 1) == ucd.WS_NA  # stride 2
     assert ucd.ucd_workspace_size(Ls2, ucd.BWD_DATA, ucd.ALGO_IMPLICIT_MIRROR, 1) == ucd.WS_NA
