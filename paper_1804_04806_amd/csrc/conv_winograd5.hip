@@ -207,30 +207,28 @@ __global__ __launch_bounds__(256) void wino5_fused_kernel(Wino5Params p)
     // rows 2*pass, 2*pass + 1 of B^T d B of patch h into LDS buffer `buf`
     auto store_v = [&](auto PASS, int buf, int h) {
         constexpr int pass = decltype(PASS)::value;
-        float x[6][6];
-#pragma unroll
-        for (int r = 0; r < 6; ++r) {
-            // window elements past the end of the row belong to the next row: 0 instead.  With an even
-            // width the second element is always inside.
-            const float w2 = d[h][6 * r + 2];
-            const float w3 = ODD_W ? (ok1 ? d[h][6 * r + 3] : 0.f) : d[h][6 * r + 3];
-            x[r][2] = w2;
-            x[r][3] = w3;
-            x[r][4] = ok2 ? d[h][6 * r + 4] : 0.f;
-            x[r][5] = ok3 ? d[h][6 * r + 5] : 0.f;
-            // columns 0, 1 = the first two window elements of the tile to the left: wave_shr:1 takes them
-            // from the lane below (lane 0 keeps what it loaded).  Tiles in the first tile column take 0;
-            // with an odd width their left neighbour's second element has just been zeroed.
-            const int l0 = __builtin_amdgcn_update_dpp((int)__float_as_uint(d[h][6 * r]), (int)__float_as_uint(w2), 0x138, 0xf, 0xf, false);
-            const int l1 = __builtin_amdgcn_update_dpp((int)__float_as_uint(d[h][6 * r + 1]), (int)__float_as_uint(w3), 0x138, 0xf, 0xf, false);
-            x[r][0] = first_col ? 0.f : __uint_as_float((uint32_t)l0);
-            x[r][1] = ODD_W ? __uint_as_float((uint32_t)l1) : first_col ? 0.f : __uint_as_float((uint32_t)l1);
-        }
-        float tr[kW5Rows][6];   // rows 2*pass, 2*pass+1 of B^T d
+        // B^T d first (the pass's two rows, column by column): the border handling then touches two
+        // values per column instead of six.  Columns 2..5 are the window as loaded.
+        float tr[kW5Rows][6];
 #pragma unroll
         for (int c = 0; c < 6; ++c) {
-            tr[0][c] = bt_row<2 * pass>(x[0][c], x[1][c], x[2][c], x[3][c], x[4][c], x[5][c]);
-            tr[1][c] = bt_row<2 * pass + 1>(x[0][c], x[1][c], x[2][c], x[3][c], x[4][c], x[5][c]);
+            tr[0][c] = bt_row<2 * pass>(d[h][c], d[h][6 + c], d[h][12 + c], d[h][18 + c], d[h][24 + c], d[h][30 + c]);
+            tr[1][c] = bt_row<2 * pass + 1>(d[h][c], d[h][6 + c], d[h][12 + c], d[h][18 + c], d[h][24 + c], d[h][30 + c]);
+        }
+#pragma unroll
+        for (int i = 0; i < kW5Rows; ++i) {
+            // window elements past the end of the row belong to the next row: their column counts as 0.
+            // With an even width the second element is always inside.
+            if constexpr (ODD_W) tr[i][3] = ok1 ? tr[i][3] : 0.f;
+            tr[i][4] = ok2 ? tr[i][4] : 0.f;
+            tr[i][5] = ok3 ? tr[i][5] : 0.f;
+            // columns 0, 1 = the first two window columns of the tile to the left: wave_shr:1 takes them
+            // from the lane below (lane 0 keeps what it computed from its own loads).  Tiles in the first
+            // tile column take 0; with an odd width their left neighbour's second column has just been zeroed.
+            const int l0 = __builtin_amdgcn_update_dpp((int)__float_as_uint(tr[i][0]), (int)__float_as_uint(tr[i][2]), 0x138, 0xf, 0xf, false);
+            const int l1 = __builtin_amdgcn_update_dpp((int)__float_as_uint(tr[i][1]), (int)__float_as_uint(tr[i][3]), 0x138, 0xf, 0xf, false);
+            tr[i][0] = first_col ? 0.f : __uint_as_float((uint32_t)l0);
+            tr[i][1] = ODD_W ? __uint_as_float((uint32_t)l1) : first_col ? 0.f : __uint_as_float((uint32_t)l1);
         }
 #pragma unroll
         for (int i = 0; i < kW5Rows; ++i) {
@@ -486,27 +484,26 @@ __global__ __launch_bounds__(256) void wino5_fused_filter_kernel(Wino5FilterPara
     // rows 2*pass, 2*pass+1 of B^T x B of patch h
     auto store_v = [&](auto PASS, int buf, int h) {
         constexpr int ps = decltype(PASS)::value;
-        float x[6][6];
-#pragma unroll
-        for (int r = 0; r < 6; ++r) {
-            const float w2 = dx[h][6 * r + 2];
-            const float w3 = ODD_W ? (ok1 ? dx[h][6 * r + 3] : 0.f) : dx[h][6 * r + 3];
-            x[r][2] = w2;
-            x[r][3] = w3;
-            x[r][4] = ok2 ? dx[h][6 * r + 4] : 0.f;
-            x[r][5] = ok3 ? dx[h][6 * r + 5] : 0.f;
-            // the lane below holds the tile to the left (same channel) unless this is the first tile
-            // position of the group or of a tile row: then the lane's own load (0 in the first tile column)
-            const int l0 = __builtin_amdgcn_update_dpp(0, (int)__float_as_uint(w2), 0x138, 0xf, 0xf, false);
-            const int l1 = __builtin_amdgcn_update_dpp(0, (int)__float_as_uint(w3), 0x138, 0xf, 0xf, false);
-            x[r][0] = own_col ? dx[h][6 * r] : __uint_as_float((uint32_t)l0);
-            x[r][1] = own_col ? dx[h][6 * r + 1] : __uint_as_float((uint32_t)l1);
-        }
+        // B^T x first (the pass's two rows, column by column), then the border handling on two values
+        // per column (see wino5_fused_kernel)
         float tr[kW5Rows][6];
 #pragma unroll
         for (int c = 0; c < 6; ++c) {
-            tr[0][c] = bt_row<2 * ps>(x[0][c], x[1][c], x[2][c], x[3][c], x[4][c], x[5][c]);
-            tr[1][c] = bt_row<2 * ps + 1>(x[0][c], x[1][c], x[2][c], x[3][c], x[4][c], x[5][c]);
+            tr[0][c] = bt_row<2 * ps>(dx[h][c], dx[h][6 + c], dx[h][12 + c], dx[h][18 + c], dx[h][24 + c], dx[h][30 + c]);
+            tr[1][c] = bt_row<2 * ps + 1>(dx[h][c], dx[h][6 + c], dx[h][12 + c], dx[h][18 + c], dx[h][24 + c], dx[h][30 + c]);
+        }
+#pragma unroll
+        for (int i = 0; i < kW5Rows; ++i) {
+            if constexpr (ODD_W) tr[i][3] = ok1 ? tr[i][3] : 0.f;
+            tr[i][4] = ok2 ? tr[i][4] : 0.f;
+            tr[i][5] = ok3 ? tr[i][5] : 0.f;
+            // the lane below holds the tile to the left (same channel) unless this is the first tile
+            // position of the group or of a tile row: then what the lane computed from its own load
+            // (0 in the first tile column)
+            const int l0 = __builtin_amdgcn_update_dpp(0, (int)__float_as_uint(tr[i][2]), 0x138, 0xf, 0xf, false);
+            const int l1 = __builtin_amdgcn_update_dpp(0, (int)__float_as_uint(tr[i][3]), 0x138, 0xf, 0xf, false);
+            tr[i][0] = own_col ? tr[i][0] : __uint_as_float((uint32_t)l0);
+            tr[i][1] = own_col ? tr[i][1] : __uint_as_float((uint32_t)l1);
         }
 #pragma unroll
         for (int i = 0; i < kW5Rows; ++i) {
