@@ -108,7 +108,8 @@ def test_bf16_parity_all_algorithms_and_divisions(s, op):
 
 def test_bf16_workspace_sizes_equal_fp32():
     """Workspace matrices stay fp32, so the workspace need does not depend on the dtype; the one
-    exception is the mirrored filter copy, which has the tensors' element type."""
+    exceptions are the mirrored filter copy, which has the tensors' element type, and the 5x5 Winograd
+    kernels, which exist for fp32 tensors only."""
     for s in SHAPES:
         for op in range(3):
             for algo in range(ucd.N_ALGO):
@@ -116,6 +117,8 @@ def test_bf16_workspace_sizes_equal_fp32():
                 if algo == ucd.ALGO_IMPLICIT_MIRROR and full != ucd.WS_NA:
                     n = s.K * s.C * s.R * s.S
                     assert (half, full) == ((2 * n + 15) // 16 * 16, (4 * n + 15) // 16 * 16)
+                elif algo == ucd.ALGO_WINOGRAD5_FUSED:
+                    assert half == ucd.WS_NA   # written for fp32 tensors only
                 else:
                     assert half == full
 
