@@ -385,13 +385,17 @@ __global__ __launch_bounds__(256) void wino5_fused_kernel(Wino5Params p)
 // ---- BackwardFilter: F(5x5,2x2) with both data transforms fused ------------------------------------
 // dw (5x5) = G^T [ sum over tiles (A dy A^T) (.) (B^T x B) ] G with A = (A^T)^T (6x2): a 2x2 tile of
 // dy and its 6x6 patch of x give 36 products per channel pair.  The workspace holds the 36 K x C
-// planes Mw.  As in wino_fused_filter_kernel a workgroup owns 64 output channels x 64 input channels
-// and reduces over 8 tile positions of the image (fixed for the workgroup) times a range of images, one
-// image per step; here it also owns one pair of rows of the point grid (12 planes), so three workgroups
-// share every chunk.  Patch rows of x are fetched as 16-byte windows starting at column 2*tw, the
-// patch's first two columns come from the lane below (the tile to the left, same channel) or, for the
-// first tile position of a group, from a load of its own; tile rows of dy as 8-byte loads.
-constexpr int kF5T = 8, kF5Ld = 64, kF5Pairs = kF5T / 2;
+// planes Mw.  As in wino_fused_filter_kernel a workgroup owns a block of output channels x input
+// channels and reduces over 8 tile positions of the image (fixed for the workgroup) times a range of
+// images, one image per step; here it also owns one pair of rows of the point grid (12 planes), so
+// three workgroups share every chunk.  The block is 64 x 64 channels (KW = 2: the waves 2 x 2) or 128
+// output x 32 input channels (KW = 4: the waves 4 x 1): transforming a patch of x costs five times
+// what a tile of dy costs, so the narrow block halves the vector work per MFMA, and it fits channel
+// counts such as 96 that fill one and a half 64-wide blocks.  Patch rows of x are fetched as 16-byte
+// windows starting at column 2*tw, the patch's first two columns come from the lane below (the tile
+// to the left, same channel) or, for the first tile position of a group, from a load of its own; tile
+// rows of dy as 8-byte loads.
+constexpr int kF5T = 8, kF5Pairs = kF5T / 2;
 
 struct Wino5FilterParams {
     const float *x, *dy;
@@ -401,15 +405,17 @@ struct Wino5FilterParams {
     int b, k_blocks, c_blocks, groups, images_per_chunk;
 };
 
-template <bool ODD_W>
+template <bool ODD_W, int KW>
 __global__ __launch_bounds__(256) void wino5_fused_filter_kernel(Wino5FilterParams p)
 {
-    __shared__ __attribute__((aligned(16))) float Ds[2][kW5Pts][kF5T][kF5Ld];
-    __shared__ __attribute__((aligned(16))) float Vs[2][kW5Pts][kF5T][kF5Ld];
+    constexpr int KB = 32 * KW, CB = 32 * (4 / KW);   // output / input channels of the block
+    constexpr int NX = CB / 32, NDY = KB / 32;        // patches of x / tiles of dy per thread and step
+    __shared__ __attribute__((aligned(16))) float Ds[2][kW5Pts][kF5T][KB];
+    __shared__ __attribute__((aligned(16))) float Vs[2][kW5Pts][kF5T][CB];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, lhi = lane >> 5;
-    const int wk = wave & 1, wc = wave >> 1;
+    const int wk = wave % KW, wc = wave / KW;
 
     // work item: (pass, output-channel block, input-channel block, tile-position group, image chunk);
     // neighbours on an XCD share the x patches and dy tiles
@@ -419,18 +425,18 @@ __global__ __launch_bounds__(256) void wino5_fused_filter_kernel(Wino5FilterPara
     const int cb = (int)(v % (uint32_t)p.c_blocks); v /= (uint32_t)p.c_blocks;
     const int grp = (int)(v % (uint32_t)p.groups);
     const int chunk = (int)(v / (uint32_t)p.groups);
-    const int k0 = kb * 64, c0 = cb * 64;
+    const int k0 = kb * KB, c0 = cb * CB;
     const int n_begin = chunk * p.images_per_chunk, n_end = min(p.b, n_begin + p.images_per_chunk);
 
     const __amdgpu_buffer_rsrc_t rx = make_rsrc_bytes(p.x, 0, p.x_bytes);
     const __amdgpu_buffer_rsrc_t rdy = make_rsrc_bytes(p.dy, 0, p.dy_bytes);
 
-    // producer role: tile position tid % 8 of the group, channel tid / 8 (and + 32) of both blocks; offsets
-    // within image 0.  LDS slabs are [point][tile position][64 channels] with channel c of tile position t
+    // producer role: tile position tid % 8 of the group, channel tid / 8 (+ 32 h) of either block; offsets
+    // within image 0.  LDS slabs are [point][tile position][channels] with channel c of tile position t
     // at column c ^ 4t (conflict-free stores, operand reads with immediate offsets).
     const int ptile = tid & 7, pch = tid >> 3;
     const int pcol = pch ^ (4 * ptile);
-    uint32_t vx[2][12], vd[2][2];   // x: window starts of the 6 patch rows, then this lane's own first columns
+    uint32_t vx[NX][12], vd[NDY][2];   // x: window starts of the 6 patch rows, then this lane's own first columns
     bool own_col, ok1, ok2, ok3, dy_ok1;
     {
         const int t = grp * kF5T + ptile;
@@ -441,8 +447,8 @@ __global__ __launch_bounds__(256) void wino5_fused_filter_kernel(Wino5FilterPara
         ok1 = ws + 1 < p.W; ok2 = ws + 2 < p.W; ok3 = ws + 3 < p.W;
         dy_ok1 = ws + 1 < p.Q;
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int c = c0 + pch + 32 * h, k = k0 + pch + 32 * h;
+        for (int h = 0; h < NX; ++h) {
+            const int c = c0 + pch + 32 * h;
 #pragma unroll
             for (int r = 0; r < 6; ++r) {
                 const int hh = h0 + r;
@@ -451,6 +457,10 @@ __global__ __launch_bounds__(256) void wino5_fused_filter_kernel(Wino5FilterPara
                 vx[h][r] = ok ? row : kOob;
                 vx[h][6 + r] = ok && ptile == 0 && tw > 0 ? row - 8u : kOob;
             }
+        }
+#pragma unroll
+        for (int h = 0; h < NDY; ++h) {
+            const int k = k0 + pch + 32 * h;
 #pragma unroll
             for (int r = 0; r < 2; ++r) {
                 const int hh = 2 * th + r;
@@ -461,7 +471,7 @@ __global__ __launch_bounds__(256) void wino5_fused_filter_kernel(Wino5FilterPara
     }
     const uint32_t x_image = 4u * (uint32_t)(p.C * p.H * p.W), dy_image = 4u * (uint32_t)(p.K * p.P * p.Q);
 
-    float dx[2][36], dz[2][4];   // the thread's patches / tiles of the image after the one in LDS, as loaded
+    float dx[NX][36], dz[NDY][4];   // the thread's patches / tiles of the image after the one in LDS, as loaded
     constexpr int kXLoads = 12, kDyLoads = 2;
     // an image past the chunk's end gets a scalar offset that pushes every address out of range
     auto fetch_x = [&](int n, int h, int i) {
@@ -524,8 +534,6 @@ __global__ __launch_bounds__(256) void wino5_fused_filter_kernel(Wino5FilterPara
         const float z10 = dz[h][2], z11 = ODD_W ? (dy_ok1 ? dz[h][3] : 0.f) : dz[h][3];
 #pragma unroll
         for (int ii = 0; ii < kW5Rows; ++ii) {
-            constexpr int unused = 0;
-            (void)unused;
             const int i = kW5Rows * ps + ii;
             const float t0 = a0[i] * z00 + a1[i] * z10, t1 = a0[i] * z01 + a1[i] * z11;
             Ds[buf][6 * ii + 0][ptile][pcol + 32 * h] = t0;
@@ -548,25 +556,22 @@ __global__ __launch_bounds__(256) void wino5_fused_filter_kernel(Wino5FilterPara
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
 
+        auto fetch_all = [&](int n) {
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
+            for (int h = 0; h < NX; ++h)
 #pragma unroll
-            for (int i = 0; i < kXLoads; ++i) fetch_x(n_begin, h, i);
+                for (int i = 0; i < kXLoads; ++i) fetch_x(n, h, i);
 #pragma unroll
-            for (int i = 0; i < kDyLoads; ++i) fetch_dy(n_begin, h, i);
-        }
+            for (int h = 0; h < NDY; ++h)
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            store_v(PASS, 0, h);
-            store_d(PASS, 0, h);
-        }
+                for (int i = 0; i < kDyLoads; ++i) fetch_dy(n, h, i);
+        };
+        fetch_all(n_begin);
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
+        for (int h = 0; h < NX; ++h) store_v(PASS, 0, h);
 #pragma unroll
-            for (int i = 0; i < kXLoads; ++i) fetch_x(n_begin + 1, h, i);
-#pragma unroll
-            for (int i = 0; i < kDyLoads; ++i) fetch_dy(n_begin + 1, h, i);
-        }
+        for (int h = 0; h < NDY; ++h) store_d(PASS, 0, h);
+        fetch_all(n_begin + 1);
         __syncthreads();
 
         int buf = 0;
@@ -577,8 +582,8 @@ __global__ __launch_bounds__(256) void wino5_fused_filter_kernel(Wino5FilterPara
             auto read_ops = [&](int xi) {
 #pragma unroll
                 for (int q = 0; q < kF5Pairs; ++q) {
-                    a[xi & 1][q] = da[(xi * kF5T + 2 * q) * kF5Ld + col_q[q]];
-                    b[xi & 1][q] = vb[(xi * kF5T + 2 * q) * kF5Ld + col_q[q]];
+                    a[xi & 1][q] = da[(xi * kF5T + 2 * q) * KB + col_q[q]];
+                    b[xi & 1][q] = vb[(xi * kF5T + 2 * q) * CB + col_q[q]];
                 }
             };
             read_ops(0);
@@ -593,18 +598,18 @@ __global__ __launch_bounds__(256) void wino5_fused_filter_kernel(Wino5FilterPara
                 if constexpr (q == 0 && xi + 1 < kW5Pts) read_ops(xi + 1);
                 // image n + 1 (in registers) is transformed into the other LDS buffer and every register
                 // reloaded with image n + 2: one piece, at most one global load, behind each MFMA
-                constexpr int kXSlots = 1 + kXLoads, kDySlots = 1 + kDyLoads, kDyStart = 1 + 2 * kXSlots;
+                constexpr int kXSlots = 1 + kXLoads, kDySlots = 1 + kDyLoads, kDyStart = 1 + NX * kXSlots;
                 if constexpr (m >= 1 && m < kDyStart) {
                     constexpr int h = (m - 1) / kXSlots, i = (m - 1) % kXSlots;
                     if constexpr (i == 0) store_v(PASS, buf ^ 1, h);
                     else fetch_x(n + 2, h, i - 1);
                 }
-                if constexpr (m >= kDyStart && m < kDyStart + 2 * kDySlots) {
+                if constexpr (m >= kDyStart && m < kDyStart + NDY * kDySlots) {
                     constexpr int h = (m - kDyStart) / kDySlots, i = (m - kDyStart) % kDySlots;
                     if constexpr (i == 0) store_d(PASS, buf ^ 1, h);
                     else fetch_dy(n + 2, h, i - 1);
                 }
-                static_assert(kDyStart + 2 * kDySlots <= kMfmas, "the step's work fits behind its MFMAs");
+                static_assert(kDyStart + NDY * kDySlots <= kMfmas, "the step's work fits behind its MFMAs");
                 __builtin_amdgcn_sched_barrier(0);
             };
             static_for<kMfmas>(slot);
@@ -730,7 +735,13 @@ hipError_t winograd5_fused_filter(const Dims &d, int b, const void *x, const voi
     p.x_bytes = xbytes(d, b); p.dy_bytes = ybytes(d, b);
     p.C = d.C; p.K = d.K; p.H = d.H; p.W = d.W; p.P = d.P; p.Q = d.Q; p.pad_h = d.ph; p.T = g.T; p.TW = g.TW;
     p.b = b;
-    p.k_blocks = (d.K + 63) / 64; p.c_blocks = (d.C + 63) / 64; p.groups = (g.T + kF5T - 1) / kF5T;
+    // block shape: 128 x 32 channels does less vector work per MFMA (one patch of x per thread instead
+    // of two); it is taken unless it needs clearly more blocks than 64 x 64
+    const long blocks_wide = (long)((d.K + 127) / 128) * ((d.C + 31) / 32), blocks_sq = (long)((d.K + 63) / 64) * ((d.C + 63) / 64);
+    const bool wide = blocks_wide * 9 <= blocks_sq * 10;
+    p.k_blocks = wide ? (d.K + 127) / 128 : (d.K + 63) / 64;
+    p.c_blocks = wide ? (d.C + 31) / 32 : (d.C + 63) / 64;
+    p.groups = (g.T + kF5T - 1) / kF5T;
     // image chunks: about four rounds of one workgroup per CU, chunks of at least 4 images; among the
     // counts near that, the one whose workgroup count fills its rounds best
     const long items = (long)kW5Passes * p.k_blocks * p.c_blocks * p.groups, cus = device_cus();
@@ -753,8 +764,13 @@ hipError_t winograd5_fused_filter(const Dims &d, int b, const void *x, const voi
         log->add("wino5_dw_kernel");
         return hipSuccess;
     }
-    if (d.W % 2) wino5_fused_filter_kernel<true><<<blocks, 256, 0, s>>>(p);
-    else wino5_fused_filter_kernel<false><<<blocks, 256, 0, s>>>(p);
+    if (wide) {
+        if (d.W % 2) wino5_fused_filter_kernel<true, 4><<<blocks, 256, 0, s>>>(p);
+        else wino5_fused_filter_kernel<false, 4><<<blocks, 256, 0, s>>>(p);
+    } else {
+        if (d.W % 2) wino5_fused_filter_kernel<true, 2><<<blocks, 256, 0, s>>>(p);
+        else wino5_fused_filter_kernel<false, 2><<<blocks, 256, 0, s>>>(p);
+    }
     if ((e = hipGetLastError()) != hipSuccess) return e;
     wino5_dw_kernel<<<(unsigned)((KC + 255) / 256), 256, 0, s>>>(ws, dw, KC, beta);
     return hipGetLastError();

@@ -43,6 +43,8 @@ SHAPES = [
     Shape(3, 24, 56, 56, 64, 3, 3, 1, 1, "k64-wide"),          # 64-row tiles over many column tiles
     Shape(3, 96, 56, 56, 96, 3, 3, 1, 1, "c96-wide"),          # 96-row tiles, Forward and BackwardData, many column tiles
     Shape(2, 20, 10, 12, 70, 5, 5, 1, 2, "5x5-even"),          # F(2x2,5x5) tiles at an even width; K > 64 with a tail
+    Shape(2, 40, 9, 9, 48, 5, 5, 1, 2, "5x5-square"),          # BackwardFilter in 64 x 64 channel blocks, odd width
+    Shape(2, 40, 8, 10, 48, 5, 5, 1, 1, "5x5-square-even"),    # the same at an even width, rows padded by 1
 ]
 
 DIVISIONS = {8: [[8], [1] * 8, [3, 5]], 5: [[5], [2, 3]], 4: [[4], [1, 3]], 3: [[3], [1, 2]],
