@@ -79,7 +79,10 @@ enum {
                         * operations; the largest workspace of all (144 frequency planes) */
     UCD_ALGO_WINOGRAD_FUSED = 5,  /* Winograd F(2x2,3x3) (BackwardFilter: F(3x3,2x2)) with the data
                         * transforms inside the GEMM kernel: the workspace holds the transformed filter
-                        * (BackwardFilter: the 16 K x C product planes) only, whatever the micro-batch size */
+                        * (BackwardFilter: the 16 K x C product planes) only, whatever the micro-batch size.
+                        * 3x3 stride-1 layers; also BackwardData of strided layers whose output phases
+                        * each see three filter taps per axis (11x11 stride 4, 5x5 stride 2, 7x7 stride 3):
+                        * all phases together are one 3x3 stride-1 convolution over dy */
     UCD_ALGO_IMPLICIT_MIRROR = 6, /* BackwardData of stride-1 layers (padding <= filter extent - 1) as the
                                      Forward implicit GEMM of the mirrored layer on a copy of the
                                      filter with channels transposed and taps reversed: workspace =
@@ -142,7 +145,9 @@ int ucd_set_deterministic(int on);
  *              = (C, K, P, Q) for Forward and (K, C, H, W) for BackwardData, Co4 = Co rounded up
  *              to 4; BackwardFilter: K*C in place of Ci*Co4, tiles over (P, Q)
  *   Winograd, fused transforms   64 * Ci8*Co4 (the transformed filter, Ci8 = Ci rounded up to 8);
- *              BackwardFilter 64 * K*C
+ *              BackwardFilter 64 * K*C; BackwardData of a strided layer with three filter taps per
+ *              output phase and axis (ceil(R/stride_h) = ceil(S/stride_w) = 3): Ci = K and
+ *              Co = C*stride_h*stride_w
  *   Winograd F(2x2,5x5), fused transforms   144 * Ci8*Co4; BackwardFilter 144 * K*C
  *   FFT        4 * 144 * (2Ci*M4 + ld*(2Ci + 2Co)), M4 = 2Co rounded up to 4, ld = b *
  *              ceil(Ho/(17-R)) * ceil(Wo/(17-S)) rounded up to 4, (Ci, Co, Ho, Wo) as for Winograd;

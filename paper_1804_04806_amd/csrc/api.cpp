@@ -107,7 +107,7 @@ size_t ws_size(const ucd_layer_t *L, int op, int algo, int b)
         return winograd_ws_bytes(d, op, b, mt);
     }
     case UCD_ALGO_WINOGRAD_FUSED:
-        if (!winograd_applies(d, op)) return UCD_WS_NA;
+        if (!winograd_fused_applies(d, op)) return UCD_WS_NA;
         return op == UCD_BWD_FILTER ? winograd_fused_filter_ws_bytes(d) : winograd_fused_ws_bytes(d, op);
     case UCD_ALGO_IMPLICIT_MIRROR:
         if (!implicit_mirror_applies(d, op)) return UCD_WS_NA;

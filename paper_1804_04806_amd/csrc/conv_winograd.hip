@@ -126,12 +126,34 @@ struct WinoGeom {
     int TH, TW, T;
     int Mo4, ld;
     bool transposed;  // BackwardData: filter read as w[ci][co] with reversed taps
+    // strided BackwardData as a stride-1 convolution over dy whose output channels are (c, row phase,
+    // column phase): the strides (1, 1 otherwise), and dx's channels, size and the layer's padding
+    int sh, sw, oc, oh, ow, oph, opw;
 };
+
+// BackwardData of a strided layer, one output phase at a time, is a stride-1 correlation of dy with the
+// taps r = phase + stride * i of the filter: with three such taps per axis (11x11 stride 4, 5x5 stride
+// 2, 7x7 stride 3, ...) all sh*sw phases together are one 3x3 stride-1 convolution from K channels to
+// C*sh*sw, which F(2x2,3x3) computes in 16/(3*3) of the multiplications, followed by a scatter of the
+// phases into dx.  (Two taps per axis would cost more than the direct sum, four do not fit 3x3.)
+static bool phased_applies(const Dims &d, int op)
+{
+    if (op != 1 || (d.sh == 1 && d.sw == 1)) return false;
+    return (d.R + d.sh - 1) / d.sh == 3 && (d.S + d.sw - 1) / d.sw == 3 && d.ph < d.R && d.pw < d.S;
+}
 
 static WinoGeom geom(const Dims &d, int op, int b, int mt)
 {
     WinoGeom g;
-    if (op == 0) {
+    g.sh = g.sw = 1; g.oc = g.oh = g.ow = g.oph = g.opw = 0;
+    if (phased_applies(d, op)) {
+        // dx[c, sh*a + pr - ph, sw*b + pc - pw] = sum_k sum_{i,j < 3} dy[k, a - i, b - j] w[k, c, pr + sh*i, pc + sw*j]:
+        // as a correlation over dy padded by 2, output (a, b) in [0, (H-1+ph)/sh] x [0, (W-1+pw)/sw]
+        g.Ci = d.K; g.Co = d.C * d.sh * d.sw; g.Hi = d.P; g.Wi = d.Q;
+        g.Ho = (d.H - 1 + d.ph) / d.sh + 1; g.Wo = (d.W - 1 + d.pw) / d.sw + 1;
+        g.pad_h = g.pad_w = 2; g.transposed = true;
+        g.sh = d.sh; g.sw = d.sw; g.oc = d.C; g.oh = d.H; g.ow = d.W; g.oph = d.ph; g.opw = d.pw;
+    } else if (op == 0) {
         g.Ci = d.C; g.Co = d.K; g.Hi = d.H; g.Wi = d.W; g.Ho = d.P; g.Wo = d.Q;
         g.pad_h = d.ph; g.pad_w = d.pw; g.transposed = false;
     } else {
@@ -143,6 +165,8 @@ static WinoGeom geom(const Dims &d, int op, int b, int mt)
     g.ld = (b * g.T + 3) / 4 * 4;
     return g;
 }
+
+bool winograd_fused_applies(const Dims &d, int op) { return winograd_applies(d, op) || phased_applies(d, op); }
 
 bool winograd_applies(const Dims &d, int op)
 {
@@ -195,6 +219,42 @@ __global__ __launch_bounds__(256) void wino_filter_kernel(const void *__restrict
         Wino<MT>::filter(t[r], u);
 #pragma unroll
         for (int s = 0; s < A; ++s) U[(size_t)(r * A + s) * plane + i] = u[s];
+    }
+}
+
+// The same for the phases of a strided BackwardData: input channel k, output channel co = (c*sh + pr)*sw + pc,
+// taps g[i'][j'] = w[k, c, pr + sh*(2 - i'), pc + sw*(2 - j')] (zero past the filter's end).
+template <class E>
+__global__ __launch_bounds__(256) void wino_phase_filter_kernel(const void *__restrict__ w, float *__restrict__ U,
+                                                                int K, int C, int R, int S, int sh, int sw, int Mo4,
+                                                                int Cpad)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= Cpad * Mo4) return;
+    const int k = i / Mo4, co = i - k * Mo4;
+    const int c = co / (sh * sw), pr = co / sw % sh, pc = co % sw;
+    const bool live = k < K && c < C;
+    float t[4][3];  // G g, column by column
+#pragma unroll
+    for (int jj = 0; jj < 3; ++jj) {
+        float g[3], u[4];
+        const int ss = pc + sw * (2 - jj);
+#pragma unroll
+        for (int ii = 0; ii < 3; ++ii) {
+            const int rr = pr + sh * (2 - ii);
+            g[ii] = live && rr < R && ss < S ? Elem<E>::get(w, ((size_t)(k * C + c) * R + rr) * S + ss) : 0.f;
+        }
+        Wino<2>::filter(g, u);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) t[r][jj] = u[r];
+    }
+    const size_t plane = (size_t)Cpad * Mo4;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        float u[4];
+        Wino<2>::filter(t[r], u);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) U[(size_t)(r * 4 + q) * plane + i] = u[q];
     }
 }
 
@@ -370,7 +430,7 @@ struct FusedParams {
     int ci_pad;   // rows of a plane of U: Ci rounded up to the channel step
 };
 
-template <class E, int PW, bool ODD_W = false>
+template <class E, int PW, bool ODD_W = false, bool PHASED = false>
 __global__ __launch_bounds__(256) void wino_fused_kernel(FusedParams p)
 {
     constexpr uint32_t EB = Elem<E>::kBytes;
@@ -395,8 +455,9 @@ __global__ __launch_bounds__(256) void wino_fused_kernel(FusedParams p)
 
     // producer role: the 4x4 patch of tile `lane` of the block, for channels wave, wave + 4, ... of the step
     uint32_t voff[kRows ? 4 : 16];   // element-wise: one offset per pixel; rows: the window start of each row
-    uint32_t xoff[4];                // rows, PW = 1: the patch's first column, fetched by lane 0 only
+    uint32_t xoff[4];                // rows, PW >= 1: the patch's first PW columns, fetched by lane 0 only
     bool first_col = false, ok1 = true, ok2 = true, ok3 = true;  // rows: tile column 0; window elements inside the row
+    bool ok0 = true, okm1 = true;    // PW = 2: the window's first element and the column before it
     {
         const int j = t0 + lane;
         uint32_t n = 0, t, th = 0, tw = 0;
@@ -410,13 +471,14 @@ __global__ __launch_bounds__(256) void wino_fused_kernel(FusedParams p)
             const int ws = 2 * (int)tw;   // = w0 + PW
             first_col = tw == 0;
             ok1 = ws + 1 < g.Wi; ok2 = ws + 2 < g.Wi; ok3 = ws + 3 < g.Wi;
+            ok0 = ws < g.Wi; okm1 = ws - 1 < g.Wi;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int h = h0 + r;
                 const bool ok = live && (unsigned)h < (unsigned)g.Hi;
                 const uint32_t row = EB * (uint32_t)(((int)n * g.Ci * g.Hi + h) * g.Wi + ws);
                 voff[r] = ok ? row : kOob;
-                xoff[r] = ok && PW == 1 && lane == 0 && tw > 0 ? row - EB : kOob;
+                xoff[r] = ok && PW >= 1 && lane == 0 && tw > 0 ? row - PW * EB : kOob;
             }
         } else {
 #pragma unroll
@@ -440,16 +502,17 @@ __global__ __launch_bounds__(256) void wino_fused_kernel(FusedParams p)
     }
 
     // the thread's input patches of the step after the one in LDS: 16 pixels each, or per row a window
-    // of 3 (PW = 1) or 4 (PW = 0) pixels in d[h][4r..] and, for PW = 1, lane 0's first column in dx
+    // of 2 (PW = 2), 3 (PW = 1) or 4 (PW = 0) pixels at the end of d[h][4r..] and, for PW >= 1, lane 0's
+    // first PW columns in dx
     float d[kFuNP][16];
-    float dx[kFuNP][4];
+    float dx[kFuNP][PW == 2 ? 8 : 4];
     f32x4 uq[kFuNU];     // and its share of that step's U slice
     // a channel past the last one gets a scalar offset that pushes every address out of range
     auto chan_off = [&](int c0, int h) {
         const int c = c0 + wave + 4 * h;
         return c < g.Ci ? EB * (uint32_t)(c * g.Hi * g.Wi) : kOob;
     };
-    constexpr int kPatchLoads = !kRows ? 16 : PW == 1 ? 8 : 4;   // load instructions per patch
+    constexpr int kPatchLoads = !kRows ? 16 : PW >= 1 ? 8 : 4;   // load instructions per patch
     auto fetch_piece = [&](int c0, int h, int i) {   // i < kPatchLoads
         const uint32_t so = chan_off(c0, h);
         if constexpr (!kRows) {
@@ -457,6 +520,14 @@ __global__ __launch_bounds__(256) void wino_fused_kernel(FusedParams p)
         } else if constexpr (PW == 0) {
             const f32x4 q = buf_load4(rin, voff[i], so);
             d[h][4 * i] = q.x; d[h][4 * i + 1] = q.y; d[h][4 * i + 2] = q.z; d[h][4 * i + 3] = q.w;
+        } else if constexpr (PW == 2) {
+            if (i < 4) {
+                const auto q = __builtin_amdgcn_raw_buffer_load_b64(rin, (int)voff[i], (int)so, 0);
+                d[h][4 * i + 2] = __uint_as_float(q[0]); d[h][4 * i + 3] = __uint_as_float(q[1]);
+            } else {
+                const auto q = __builtin_amdgcn_raw_buffer_load_b64(rin, (int)xoff[i - 4], (int)so, 0);
+                dx[h][2 * (i - 4)] = __uint_as_float(q[0]); dx[h][2 * (i - 4) + 1] = __uint_as_float(q[1]);
+            }
         } else if (i < 4) {
             const auto q = __builtin_amdgcn_raw_buffer_load_b96(rin, (int)voff[i], (int)so, 0);
 #pragma unroll
@@ -485,6 +556,20 @@ __global__ __launch_bounds__(256) void wino_fused_kernel(FusedParams p)
                     const int left = __builtin_amdgcn_update_dpp((int)__float_as_uint(dx[h][r]),
                                                                  (int)__float_as_uint(d[h][4 * r + 2]), 0x138, 0xf, 0xf, false);
                     d[h][4 * r] = ODD_W ? __uint_as_float((uint32_t)left) : first_col ? 0.f : __uint_as_float((uint32_t)left);
+                } else if constexpr (PW == 2) {
+                    // Window = columns 2tw, 2tw+1 = patch columns 2, 3; the last tile column's window can
+                    // lie past the row altogether.  Patch columns 0, 1 are the window of the tile to the
+                    // left, already masked there (lane 0: its own load, whose second element can be past
+                    // the row when the width is odd); zeros in the first tile column.
+                    d[h][4 * r + 2] = ok0 ? d[h][4 * r + 2] : 0.f;
+                    d[h][4 * r + 3] = ok1 ? d[h][4 * r + 3] : 0.f;
+                    const float own1 = okm1 ? dx[h][2 * r + 1] : 0.f;
+                    const int l0 = __builtin_amdgcn_update_dpp((int)__float_as_uint(dx[h][2 * r]),
+                                                               (int)__float_as_uint(d[h][4 * r + 2]), 0x138, 0xf, 0xf, false);
+                    const int l1 = __builtin_amdgcn_update_dpp((int)__float_as_uint(own1),
+                                                               (int)__float_as_uint(d[h][4 * r + 3]), 0x138, 0xf, 0xf, false);
+                    d[h][4 * r] = first_col ? 0.f : __uint_as_float((uint32_t)l0);
+                    d[h][4 * r + 1] = first_col ? 0.f : __uint_as_float((uint32_t)l1);
                 } else {
                     d[h][4 * r + 1] = ok1 ? d[h][4 * r + 1] : 0.f;
                     d[h][4 * r + 2] = ok2 ? d[h][4 * r + 2] : 0.f;
@@ -610,6 +695,72 @@ __global__ __launch_bounds__(256) void wino_fused_kernel(FusedParams p)
     p.divTW.divmod(t, th, tw);
     const int h0 = 2 * (int)th, w0 = 2 * (int)tw;
     const bool h1 = h0 + 1 < g.Ho, w1 = w0 + 1 < g.Wo;
+    if constexpr (PHASED) {
+        // channel k is (c, pr, pc) = ((k / sw) / sh, (k / sw) % sh, k % sw): position (a, b) of the tile goes
+        // to dx[c, sh*a + pr - ph, sw*b + pc - pw].  With a column stride of 4 the lane's registers
+        // 4q .. 4q+3 are the four column phases of one (c, pr), i.e. four adjacent pixels of dx: one
+        // 16-byte store (dword-aligned) unless the four straddle the row's ends.
+        typedef float f32x4_dw __attribute__((ext_vector_type(4), aligned(4)));
+        const bool quads = EB == 4 && g.sw == 4;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int kq = k0 + wk * 32 + 8 * q + 4 * lhi;
+            float o[4][2][2];   // [register of the quad][row of the tile][column of the tile]
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int e = 4 * q + i;
+                float y[2][4];  // A^T m, column by column
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const float m0 = acc[c][e], m1 = acc[4 + c][e], m2 = acc[8 + c][e], m3 = acc[12 + c][e];
+                    y[0][c] = m0 + m1 + m2;
+                    y[1][c] = m1 - m2 - m3;
+                }
+#pragma unroll
+                for (int dr = 0; dr < 2; ++dr) {
+                    o[i][dr][0] = y[dr][0] + y[dr][1] + y[dr][2];
+                    o[i][dr][1] = y[dr][1] - y[dr][2] - y[dr][3];
+                }
+            }
+            if (quads) {
+                if (kq >= g.Co) continue;
+                const int c = kq / (4 * g.sh), pr = kq / 4 % g.sh;
+#pragma unroll
+                for (int dr = 0; dr < 2; ++dr)
+#pragma unroll
+                    for (int dc = 0; dc < 2; ++dc) {
+                        const int h = g.sh * (h0 + dr) + pr - g.oph, w = 4 * (w0 + dc) - g.opw;
+                        if ((unsigned)h >= (unsigned)g.oh) continue;
+                        float *dst = (float *)p.out + (((long)n * g.oc + c) * g.oh + h) * g.ow + w;
+                        if (w >= 0 && w + 3 < g.ow) {
+                            f32x4_dw v4;
+                            v4.x = o[0][dr][dc]; v4.y = o[1][dr][dc]; v4.z = o[2][dr][dc]; v4.w = o[3][dr][dc];
+                            *reinterpret_cast<f32x4_dw *>(dst) = v4;
+                        } else {
+#pragma unroll
+                            for (int i = 0; i < 4; ++i)
+                                if ((unsigned)(w + i) < (unsigned)g.ow) dst[i] = o[i][dr][dc];
+                        }
+                    }
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int k = kq + i;
+                    if (k >= g.Co) continue;
+                    const int c = k / (g.sh * g.sw), pr = k / g.sw % g.sh, pc = k % g.sw;
+#pragma unroll
+                    for (int dr = 0; dr < 2; ++dr)
+#pragma unroll
+                        for (int dc = 0; dc < 2; ++dc) {
+                            const int h = g.sh * (h0 + dr) + pr - g.oph, w = g.sw * (w0 + dc) + pc - g.opw;
+                            if ((unsigned)h < (unsigned)g.oh && (unsigned)w < (unsigned)g.ow)
+                                Elem<E>::store(p.out, (((long)n * g.oc + c) * g.oh + h) * g.ow + w, o[i][dr][dc]);
+                        }
+                }
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
         const int k = k0 + wk * 32 + 8 * (e / 4) + 4 * lhi + (e % 4);
@@ -644,10 +795,14 @@ static hipError_t winograd_fused_run(const Dims &d, int op, int b, const void *i
                                      float *ws, bool filter_ready, hipStream_t s)
 {
     const WinoGeom g = geom(d, op, b, 2);
+    const bool phased = g.sh * g.sw > 1;
     LaunchLog *log = launch_log();
     if (filter_ready) {
         // U of this filter is still in the workspace from the previous micro-batch
-    } else if (log) log->add("wino_filter_kernel");
+    } else if (log) log->add(phased ? "wino_phase_filter_kernel" : "wino_filter_kernel");
+    else if (phased)
+        wino_phase_filter_kernel<E><<<(unsigned)((fused_ci_pad(g) * g.Mo4 + 255) / 256), 256, 0, s>>>(
+            w, ws, d.K, d.C, d.R, d.S, d.sh, d.sw, g.Mo4, fused_ci_pad(g));
     else
         wino_filter_kernel<E, 2><<<(unsigned)((fused_ci_pad(g) * g.Mo4 + 255) / 256), 256, 0, s>>>(
             w, ws, g.Ci, g.Co, g.Mo4, g.transposed ? 1 : 0, fused_ci_pad(g));
@@ -663,17 +818,23 @@ static hipError_t winograd_fused_run(const Dims &d, int op, int b, const void *i
     p.k_blocks = (g.Co + kFuK - 1) / kFuK;
     const unsigned blocks = (unsigned)(p.k_blocks * ((p.n_tiles + kFuT - 1) / kFuT));
     if (log) {
-        log->add("wino_fused_kernel blocks=" + std::to_string(blocks) + " gemm_flops=" +
-                 std::to_string(2.0 * 16 * g.Co * (double)p.n_tiles * g.Ci));
+        log->add(std::string(phased ? "wino_fused_kernel<phases>" : "wino_fused_kernel") + " blocks=" +
+                 std::to_string(blocks) + " gemm_flops=" + std::to_string(2.0 * 16 * g.Co * (double)p.n_tiles * g.Ci));
         return hipSuccess;
     }
-    // row-vector patch loads: fp32 tensors, horizontal padding 0 or 1 (UCD_FUSED_ELEMENTWISE=1 in the
-    // environment keeps the element-wise loads, for comparison)
+    // row-vector patch loads: fp32 tensors (UCD_FUSED_ELEMENTWISE=1 in the environment keeps the
+    // element-wise loads, for comparison)
     static const bool elementwise = getenv("UCD_FUSED_ELEMENTWISE") != nullptr;
+    if (phased) {
+        if (std::is_same_v<E, float> && !elementwise) wino_fused_kernel<float, 2, false, true><<<blocks, 256, 0, s>>>(p);
+        else wino_fused_kernel<E, -1, false, true><<<blocks, 256, 0, s>>>(p);
+        return hipGetLastError();
+    }
     bool rows = false;
     if constexpr (std::is_same_v<E, float>) {
-        rows = !elementwise && (g.pad_w == 0 || g.pad_w == 1);
+        rows = !elementwise && g.pad_w <= 2;
         if (rows && g.pad_w == 0) wino_fused_kernel<E, 0><<<blocks, 256, 0, s>>>(p);
+        else if (rows && g.pad_w == 2) wino_fused_kernel<E, 2><<<blocks, 256, 0, s>>>(p);
         else if (rows && g.Wi % 2) wino_fused_kernel<E, 1, true><<<blocks, 256, 0, s>>>(p);
         else if (rows) wino_fused_kernel<E, 1, false><<<blocks, 256, 0, s>>>(p);
     }

@@ -76,6 +76,7 @@ hipError_t winograd_bwd_filter(const Dims &d, int b, const void *x, const void *
 
 // F(2x2,3x3) with the input and output transforms fused into the GEMM kernel: Forward (op 0) and
 // BackwardData (op 1); the workspace holds the transformed filter only (independent of b).
+bool winograd_fused_applies(const Dims &d, int op);
 size_t winograd_fused_ws_bytes(const Dims &d, int op);
 // BackwardFilter F(3x3,2x2) with both transforms fused: the workspace holds the 16 K x C product planes
 size_t winograd_fused_filter_ws_bytes(const Dims &d);

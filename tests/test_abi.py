@@ -52,6 +52,11 @@ def test_workspace_formulas():
     Lc3 = ucd.layer(N=8, C=3, H=16, W=16, K=30, R=3, S=3, pad_h=1, pad_w=1)
     assert ucd.ucd_workspace_size(Lc3, ucd.FWD, ucd.ALGO_WINOGRAD_FUSED, 1) == 64 * 8 * 32
     assert ucd.ucd_workspace_size(Lc3, ucd.BWD_DATA, ucd.ALGO_WINOGRAD_FUSED, 1) == 64 * 32 * 4
+    # strided BackwardData with three taps per phase and axis: a 3x3 convolution from K to C * stride^2 channels
+    L11s4 = ucd.layer(N=4, C=3, H=35, W=35, K=20, R=11, S=11, pad_h=2, pad_w=2, stride_h=4, stride_w=4)
+    assert ucd.ucd_workspace_size(L11s4, ucd.BWD_DATA, ucd.ALGO_WINOGRAD_FUSED, 4) == 64 * 24 * 48
+    assert ucd.ucd_workspace_size(L11s4, ucd.FWD, ucd.ALGO_WINOGRAD_FUSED, 4) == ucd.WS_NA
+    assert ucd.ucd_workspace_size(L11s4, ucd.BWD_FILTER, ucd.ALGO_WINOGRAD_FUSED, 4) == ucd.WS_NA
     # mirrored filter copy: BackwardData of stride-1 layers only, the filter's own size (16-byte multiple)
     assert ucd.ucd_workspace_size(L, ucd.BWD_DATA, ucd.ALGO_IMPLICIT_MIRROR, 5) == 4 * 32 * 16 * 9
     assert ucd.ucd_workspace_size(L, ucd.FWD, ucd.ALGO_IMPLICIT_MIRROR, 5) == ucd.WS_NA
@@ -72,6 +77,7 @@ def test_workspace_formulas():
     Ls2 = ucd.layer(N=8, C=16, H=16, W=16, K=32, R=3, S=3, pad_h=1, pad_w=1, stride_h=2, stride_w=2)
     assert ucd.ucd_workspace_size(Ls2, ucd.BWD_FILTER, ucd.ALGO_WINOGRAD, 1) == ucd.WS_NA  # stride 2
     assert ucd.ucd_workspace_size(Ls2, ucd.BWD_DATA, ucd.ALGO_IMPLICIT_MIRROR, 1) == ucd.WS_NA
+    assert ucd.ucd_workspace_size(Ls2, ucd.BWD_DATA, ucd.ALGO_WINOGRAD_FUSED, 1) == ucd.WS_NA  # two taps per phase
     L11 = ucd.layer(N=4, C=8, H=7, W=7, K=8, R=1, S=1)
     assert ucd.ucd_workspace_size(L11, ucd.FWD, ucd.ALGO_IM2COL, 1) == ucd.WS_NA    # col == x
     assert ucd.ucd_workspace_size(L11, ucd.FWD, ucd.ALGO_WINOGRAD, 1) == ucd.WS_NA  # not 3x3
