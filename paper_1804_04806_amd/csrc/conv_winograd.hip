@@ -782,6 +782,316 @@ __global__ __launch_bounds__(256) void wino_fused_kernel(FusedParams p)
     }
 }
 
+// ---- the same on the bf16 matrix pipe (bf16 tensors) ---------------------------------------------
+// The transforms run in fp32 as above; U = G g G^T and V = B^T d B are then rounded to bf16 and
+// multiplied by v_mfma_f32_32x32x16_bf16 with fp32 accumulation: a step of 16 input channels is one
+// MFMA per point, an eighth of the fp32 kernel's matrix time, so the kernel lives on its loads, its
+// transforms and its LDS traffic.  LDS and the transformed filter in the workspace hold 16-byte cells
+// of eight consecutive input channels of one output channel (U) or tile (V), [point][half of the
+// step][64 rows][8]: exactly an MFMA operand of the lane that owns the row (lanes 0-31 the first
+// half's cell, lanes 32-63 the second's).
+// A patch row (4 pixels = 8 bytes at any 2-byte alignment) is fetched as the three aligned dwords that
+// cover it and shifted into place by the parity of its first element; pixels outside the row are
+// dropped by the byte selectors that widen bf16 to fp32.
+constexpr int kBfC = 16;   // input channels per step
+constexpr int kBfNU = 8;   // 16-byte cells of the step's U slice per thread: 16 points x 2 halves x 64 / 256
+
+struct FusedBf16Params {
+    const void *in;    // the input tensor's address rounded down to 4 bytes
+    const void *U;
+    void *out;
+    uint32_t in_bytes, u_bytes;
+    WinoGeom g;
+    FastDiv divT, divTW;
+    int n_tiles, k_blocks, ci_pad;
+    int lead;          // elements between `in` and the tensor's first element: 0 or 1
+};
+
+// U cells: [point][ci / 8][co (Mo4 rows)][ci % 8] as bf16, ci padded to Cpad (a multiple of 16) with zeros
+template <class E>
+__global__ __launch_bounds__(256) void wino_filter_bf16_kernel(const void *__restrict__ w, uint16_t *__restrict__ U,
+                                                               int Ci, int Co, int Mo4, int transposed, int Cpad)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= Cpad * Mo4) return;
+    const int ci = i / Mo4, co = i - ci * Mo4;
+    float t[4][3];  // G g, column by column
+#pragma unroll
+    for (int s = 0; s < 3; ++s) {
+        float g[3], u[4];
+#pragma unroll
+        for (int r = 0; r < 3; ++r) {
+            float v = 0.f;
+            if (co < Co && ci < Ci)
+                v = transposed ? Elem<E>::get(w, ((size_t)(ci * Co + co) * 3 + (2 - r)) * 3 + (2 - s))
+                               : Elem<E>::get(w, ((size_t)(co * Ci + ci) * 3 + r) * 3 + s);
+            g[r] = v;
+        }
+        Wino<2>::filter(g, u);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) t[r][s] = u[r];
+    }
+    const size_t plane = (size_t)Cpad * Mo4;   // elements per point
+    const size_t cell = ((size_t)(ci / 8) * Mo4 + co) * 8 + ci % 8;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        float u[4];
+        Wino<2>::filter(t[r], u);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) U[(size_t)(r * 4 + q) * plane + cell] = Elem<bf16>::round(u[q]);
+    }
+}
+
+__global__ __launch_bounds__(256) void wino_fused_bf16_kernel(FusedBf16Params p)
+{
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    typedef unsigned int u32x3 __attribute__((ext_vector_type(3)));
+    __shared__ __attribute__((aligned(16))) u32x4 Us[2][16][2][64];
+    __shared__ __attribute__((aligned(16))) u32x4 Vs[2][16][2][64];
+    const WinoGeom &g = p.g;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, lhi = lane >> 5;
+    const int wk = wave & 1, wt = wave >> 1;
+
+    const uint32_t v = xcd_order(blockIdx.x, gridDim.x);
+    const int kb = (int)(v % (uint32_t)p.k_blocks), tb = (int)(v / (uint32_t)p.k_blocks);
+    const int k0 = kb * kFuK, t0 = tb * kFuT;
+
+    const __amdgpu_buffer_rsrc_t rin = make_rsrc_bytes(p.in, 0, p.in_bytes);
+    const __amdgpu_buffer_rsrc_t ru = make_rsrc_bytes(p.U, 0, p.u_bytes);
+
+    // producer role: the 4x4 patch of tile `lane` of the block, for channels 4*wave .. 4*wave+3 of the step.
+    // Element index of a row's first pixel = lead + c*Hi*Wi + eo[r]; with q = parity of (lead + c*Hi*Wi)
+    // the row starts in the dword at element ((eo + q) & ~1) past the channel's dword-aligned base, at
+    // its upper half if (eo + q) is odd.  Offsets carry 4 bytes more than that (eo >= -2, so they are
+    // never negative) and the channel's scalar offset 4 bytes less.
+    uint32_t voffb0[4], voffb1[4];   // per row, for q = 0 and q = 1
+    uint32_t sh0[4];        // 16 * parity of eo[row]: the shift for q = 0; for q = 1 the other one
+    uint32_t sel[4];        // per patch column: selector that widens the pixel's half of a dword, or zeroes it
+    {
+        const int j = t0 + lane;
+        uint32_t n = 0, t, th = 0, tw = 0;
+        const bool live = j < p.n_tiles;
+        if (live) {
+            p.divT.divmod((uint32_t)j, n, t);
+            p.divTW.divmod(t, th, tw);
+        }
+        const int h0 = 2 * (int)th - g.pad_h, w0 = 2 * (int)tw - g.pad_w;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int h = h0 + r;
+            const bool ok = live && (unsigned)h < (unsigned)g.Hi;
+            const int eo = ((int)n * g.Ci * g.Hi + h) * g.Wi + w0;
+            voffb0[r] = ok ? (uint32_t)(2 * (eo & ~1) + 4) : kOob;
+            voffb1[r] = ok ? (uint32_t)(2 * ((eo + 1) & ~1) + 4) : kOob;
+            sh0[r] = (uint32_t)(eo & 1) << 4;
+        }
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            sel[c] = (unsigned)(w0 + c) < (unsigned)g.Wi ? (c & 1 ? 0x03020c0cu : 0x01000c0cu) : 0x0c0c0c0cu;
+    }
+    const int hw = g.Hi * g.Wi;
+    // channel c of the step at c0: the parity q and the scalar byte offset of its loads
+    auto chan_q = [&](int c) { return (p.lead + c * hw) & 1; };
+    auto chan_soff = [&](int c) {
+        if (c >= g.Ci) return kOob;   // past the last channel: every address out of range
+        const int base = p.lead + c * hw;
+        return (uint32_t)(2 * (base - (base & 1)));   // 4 less is taken off below, where it cannot go negative
+    };
+
+    // U slice of a step: cell id = tid + 256*i -> (point, half, output channel) = (id / 128, id / 64 % 2, id % 64)
+    uint32_t uoff[kBfNU];
+    const int cgroups = p.ci_pad / 8;
+#pragma unroll
+    for (int i = 0; i < kBfNU; ++i) {
+        const int id = tid + 256 * i, xi = id >> 7, half = (id >> 6) & 1, k = k0 + (id & 63);
+        uoff[i] = k < g.Mo4 ? 16u * (uint32_t)((xi * cgroups + half) * g.Mo4 + k) : kOob;
+    }
+
+    u32x3 raw[4][4];     // the thread's four patches of the step after the one in LDS, as loaded: [channel][row]
+    u32x4 uq[kBfNU];     // and its share of that step's U slice
+    auto fetch_row = [&](int c0, int i, int r) {
+        const int c = c0 + 4 * wave + i;
+        const int q = chan_q(c);
+        uint32_t vo = q ? voffb1[r] : voffb0[r];
+        uint32_t so = chan_soff(c);
+        if (c == 0) {
+            // the first channel has no room below its base for the 4 extra bytes: take them off the
+            // lane's offset instead; a row that starts before the tensor (first row, first tile column,
+            // padded) is fetched from the tensor's start and moved up one dword when it is unpacked
+            vo = vo < 4u ? 0u : vo - 4u;
+        } else if (so != kOob) {
+            so -= 4u;
+        }
+        raw[i][r] = __builtin_amdgcn_raw_buffer_load_b96(rin, (int)vo, (int)so, 0);
+    };
+    auto fetch_u = [&](int c0, int i) {
+        const auto q = __builtin_amdgcn_raw_buffer_load_b128(ru, (int)uoff[i], (int)(16u * (uint32_t)((c0 >> 3) * g.Mo4)), 0);
+        uq[i] = q;
+    };
+    auto store_u = [&](int buf, int i) { (&Us[buf][0][0][0])[tid + 256 * i] = uq[i]; };
+
+    // B^T d B of the four patches, rounded to bf16: pk[xi][0] = channels 0, 1; pk[xi][1] = channels 2, 3
+    uint32_t pk[16][2];
+    float vprev[16];   // the transformed patch of the even channel, waiting for its odd partner
+    auto transform = [&](int c0, int i) {
+        const int c = c0 + 4 * wave + i;
+        const uint32_t qs = (uint32_t)chan_q(c) << 4;
+        float d[16];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            uint32_t d0 = raw[i][r].x, d1 = raw[i][r].y, d2 = raw[i][r].z;
+            if (c == 0) {
+                const uint32_t vo = chan_q(0) ? voffb1[r] : voffb0[r];
+                if (vo < 4u) { d2 = d1; d1 = d0; d0 = 0u; }
+            }
+            const uint32_t sh = sh0[r] ^ qs;
+            const uint32_t w0 = __builtin_amdgcn_alignbit(d1, d0, sh), w1 = __builtin_amdgcn_alignbit(d2, d1, sh);
+            d[4 * r + 0] = __uint_as_float(__builtin_amdgcn_perm(0u, w0, sel[0]));
+            d[4 * r + 1] = __uint_as_float(__builtin_amdgcn_perm(0u, w0, sel[1]));
+            d[4 * r + 2] = __uint_as_float(__builtin_amdgcn_perm(0u, w1, sel[2]));
+            d[4 * r + 3] = __uint_as_float(__builtin_amdgcn_perm(0u, w1, sel[3]));
+        }
+        float tr[16], vv[16];
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc) {
+            const float a0 = d[cc], a1 = d[4 + cc], a2 = d[8 + cc], a3 = d[12 + cc];
+            tr[cc] = a0 - a2;
+            tr[4 + cc] = a1 + a2;
+            tr[8 + cc] = a2 - a1;
+            tr[12 + cc] = a1 - a3;
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float a0 = tr[4 * r], a1 = tr[4 * r + 1], a2 = tr[4 * r + 2], a3 = tr[4 * r + 3];
+            vv[4 * r + 0] = a0 - a2;
+            vv[4 * r + 1] = a1 + a2;
+            vv[4 * r + 2] = a2 - a1;
+            vv[4 * r + 3] = a1 - a3;
+        }
+        if (i % 2 == 0) {
+#pragma unroll
+            for (int xi = 0; xi < 16; ++xi) vprev[xi] = vv[xi];
+        } else {
+#pragma unroll
+            for (int xi = 0; xi < 16; ++xi) {
+                const f32x2 two = {vprev[xi], vv[xi]};
+                const bf16x2 h2 = __builtin_convertvector(two, bf16x2);
+                pk[xi][i / 2] = *reinterpret_cast<const uint32_t *>(&h2);
+            }
+        }
+    };
+    // the thread's four channels are half a cell: dwords 2*(wave & 1), +1 of cell [xi][wave >> 1][lane]
+    auto store_v = [&](int buf) {
+#pragma unroll
+        for (int xi = 0; xi < 16; ++xi) {
+            uint32_t *cell = reinterpret_cast<uint32_t *>(&Vs[buf][xi][wave >> 1][lane]) + 2 * (wave & 1);
+            *reinterpret_cast<u32x2 *>(cell) = u32x2{pk[xi][0], pk[xi][1]};
+        }
+    };
+
+    f32x16 acc[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+
+    // step 0 -> LDS buffer 0, step 1 -> registers
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) fetch_row(0, i, r);
+#pragma unroll
+    for (int i = 0; i < kBfNU; ++i) fetch_u(0, i);
+    auto first_transforms = [&](auto I) { transform(0, decltype(I)::value); };
+    static_for<4>(first_transforms);
+    store_v(0);
+#pragma unroll
+    for (int i = 0; i < kBfNU; ++i) store_u(0, i);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) fetch_row(kBfC, i, r);
+#pragma unroll
+    for (int i = 0; i < kBfNU; ++i) fetch_u(kBfC, i);
+    __syncthreads();
+
+    int buf = 0;
+    for (int c0 = 0; c0 < g.Ci; c0 += kBfC) {
+        const u32x4 *ua = &Us[buf][0][lhi][wk * 32 + l32];
+        const u32x4 *vb = &Vs[buf][0][lhi][wt * 32 + l32];
+        constexpr int kAhead = 2;
+        u32x4 a[kAhead + 1], b[kAhead + 1];
+        auto read_ops = [&](int xi) {
+            a[xi % (kAhead + 1)] = ua[xi * 128];
+            b[xi % (kAhead + 1)] = vb[xi * 128];
+        };
+#pragma unroll
+        for (int xi = 0; xi < kAhead; ++xi) read_ops(xi);
+        __builtin_amdgcn_sched_barrier(0);
+        // one MFMA per point and, behind it, a piece of the next step's work: the registers hold step
+        // c0 + 16 as loaded; each patch is transformed and its registers reloaded with step c0 + 32
+        auto slot = [&](auto M) {
+            constexpr int xi = decltype(M)::value;
+            acc[xi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[xi % (kAhead + 1)]),
+                                                              __builtin_bit_cast(bf16x8, b[xi % (kAhead + 1)]), acc[xi], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (xi + kAhead < 16) read_ops(xi + kAhead);
+            if constexpr (xi < 8) {
+                constexpr int i = xi / 2;
+                if constexpr (xi % 2 == 0) {
+                    transform(c0 + kBfC, i);
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) fetch_row(c0 + 2 * kBfC, i, r);
+                }
+            } else if constexpr (xi == 8) {
+                store_v(buf ^ 1);
+            } else if constexpr (xi < 13) {
+                constexpr int i0 = 2 * (xi - 9);
+                store_u(buf ^ 1, i0);
+                store_u(buf ^ 1, i0 + 1);
+                fetch_u(c0 + 2 * kBfC, i0);
+                fetch_u(c0 + 2 * kBfC, i0 + 1);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        static_for<16>(slot);
+        __syncthreads();
+        buf ^= 1;
+    }
+
+    // output transform and store: lane = tile (column l32 of the wave's 32), register e = channel row
+    const int j = t0 + wt * 32 + l32;
+    if (j >= p.n_tiles) return;
+    uint32_t n, t, th, tw;
+    p.divT.divmod((uint32_t)j, n, t);
+    p.divTW.divmod(t, th, tw);
+    const int h0 = 2 * (int)th, w0 = 2 * (int)tw;
+    const bool h1 = h0 + 1 < g.Ho, w1 = w0 + 1 < g.Wo;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+        const int k = k0 + wk * 32 + 8 * (e / 4) + 4 * lhi + (e % 4);
+        if (k >= g.Co) continue;
+        float y[2][4];  // A^T m, column by column
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const float m0 = acc[c][e], m1 = acc[4 + c][e], m2 = acc[8 + c][e], m3 = acc[12 + c][e];
+            y[0][c] = m0 + m1 + m2;
+            y[1][c] = m1 - m2 - m3;
+        }
+        const long base = (((long)n * g.Co + k) * g.Ho + h0) * g.Wo + w0;
+        Elem<bf16>::store(p.out, base, y[0][0] + y[0][1] + y[0][2]);
+        if (w1) Elem<bf16>::store(p.out, base + 1, y[0][1] - y[0][2] - y[0][3]);
+        if (h1) {
+            Elem<bf16>::store(p.out, base + g.Wo, y[1][0] + y[1][1] + y[1][2]);
+            if (w1) Elem<bf16>::store(p.out, base + g.Wo + 1, y[1][1] - y[1][2] - y[1][3]);
+        }
+    }
+}
+
 static int fused_ci_pad(const WinoGeom &g) { return (g.Ci + kFuC - 1) / kFuC * kFuC; }
 
 size_t winograd_fused_ws_bytes(const Dims &d, int op)
@@ -797,9 +1107,17 @@ static hipError_t winograd_fused_run(const Dims &d, int op, int b, const void *i
     const WinoGeom g = geom(d, op, b, 2);
     const bool phased = g.sh * g.sw > 1;
     LaunchLog *log = launch_log();
+    // bf16 tensors: the kernel on the bf16 matrix pipe (UCD_FUSED_BF16_FP32=1 in the environment keeps the
+    // fp32 products, for comparison); images of fewer than 4 pixels would break its address arithmetic
+    static const bool bf16_fp32 = getenv("UCD_FUSED_BF16_FP32") != nullptr;
+    const bool bf16_pipe = std::is_same_v<E, bf16> && !phased && !bf16_fp32 && g.Hi * g.Wi >= 4;
+    const int ci_pad16 = (g.Ci + kBfC - 1) / kBfC * kBfC;
     if (filter_ready) {
         // U of this filter is still in the workspace from the previous micro-batch
     } else if (log) log->add(phased ? "wino_phase_filter_kernel" : "wino_filter_kernel");
+    else if (bf16_pipe)
+        wino_filter_bf16_kernel<E><<<(unsigned)((ci_pad16 * g.Mo4 + 255) / 256), 256, 0, s>>>(
+            w, (uint16_t *)ws, g.Ci, g.Co, g.Mo4, g.transposed ? 1 : 0, ci_pad16);
     else if (phased)
         wino_phase_filter_kernel<E><<<(unsigned)((fused_ci_pad(g) * g.Mo4 + 255) / 256), 256, 0, s>>>(
             w, ws, d.K, d.C, d.R, d.S, d.sh, d.sw, g.Mo4, fused_ci_pad(g));
@@ -808,6 +1126,26 @@ static hipError_t winograd_fused_run(const Dims &d, int op, int b, const void *i
             w, ws, g.Ci, g.Co, g.Mo4, g.transposed ? 1 : 0, fused_ci_pad(g));
     hipError_t e = log ? hipSuccess : hipGetLastError();
     if (e != hipSuccess) return e;
+    if (bf16_pipe) {
+        const int ci_pad = ci_pad16;
+        FusedBf16Params q{};
+        q.lead = (int)(((uintptr_t)in >> 1) & 1);
+        q.in = (const char *)in - 2 * q.lead; q.U = ws; q.out = out;
+        q.in_bytes = (uint32_t)((2 * (size_t)q.lead + 2 * (size_t)b * g.Ci * g.Hi * g.Wi + 3) / 4 * 4);
+        q.ci_pad = ci_pad;
+        q.u_bytes = (uint32_t)((size_t)32 * ci_pad * g.Mo4);
+        q.g = g; q.divT = FastDiv(g.T); q.divTW = FastDiv(g.TW);
+        q.n_tiles = b * g.T;
+        q.k_blocks = (g.Co + kFuK - 1) / kFuK;
+        const unsigned nb = (unsigned)(q.k_blocks * ((q.n_tiles + kFuT - 1) / kFuT));
+        if (log) {
+            log->add("wino_fused_bf16_kernel blocks=" + std::to_string(nb) + " gemm_flops=" +
+                     std::to_string(2.0 * 16 * g.Co * (double)q.n_tiles * g.Ci));
+            return hipSuccess;
+        }
+        wino_fused_bf16_kernel<<<nb, 256, 0, s>>>(q);
+        return hipGetLastError();
+    }
     FusedParams p{};
     p.in = in; p.U = ws; p.out = out;
     p.in_bytes = (uint32_t)(Elem<E>::kBytes * (size_t)b * g.Ci * g.Hi * g.Wi);

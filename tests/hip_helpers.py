@@ -37,7 +37,12 @@ def l2_tol(micro):
 # An fp32 result of rms-sized terms is off by a few 1e-7 rms per element (1e-5 rms for 4x4 Winograd
 # tiles): one wrong term (a dropped tap, a neighbour's pixel) is off by about 1/sqrt(reduction
 # length) of an rms, i.e. 1e-2 or more.
-def elementwise_tol(micro):
+# With bf16 tensors the fused Winograd kernel multiplies on the bf16 matrix pipe: the transformed filter
+# and patches are rounded to bf16 (a relative 2^-9 each, 16 x Ci products per output), which in a numpy
+# model of the kernel leaves elements up to 1.8e-2 rms off (4.2e-3 relative L2): 3e-2 there.
+def elementwise_tol(micro, bf16=False):
+    if bf16 and any(a == ucd.ALGO_WINOGRAD_FUSED for a, _ in micro):
+        return 3e-2
     return 1e-3 if any(a in ucd.WINOGRAD_ALGOS for a, _ in micro) else 1e-4
 
 

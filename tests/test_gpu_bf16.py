@@ -33,6 +33,9 @@ SHAPES = [
     Shape(2, 6, 9, 12, 7, 2, 4, 1, 1, "evenfilter"),
     Shape(2, 96, 9, 9, 192, 3, 3, 1, 1, "c96k192"),
     Shape(3, 120, 7, 7, 136, 3, 3, 1, 1, "deep"),
+    Shape(3, 5, 7, 7, 9, 3, 3, 1, 1, "odd-chw"),               # second micro-batch starts at an odd element: 2-byte aligned tensors
+    Shape(2, 5, 11, 14, 7, 3, 3, 1, 0, "pad0-3x3"),
+    Shape(2, 5, 6, 9, 7, 3, 3, 1, 2, "pad2-3x3"),
 ]
 DIVISIONS = {8: [[8], [3, 5]], 5: [[5], [2, 3]], 4: [[4], [1, 3]], 3: [[3], [1, 2]], 2: [[2], [1, 1]]}
 
@@ -74,11 +77,16 @@ def run_hip_bf16(s, op, micro, bits, beta=0.0, dw0=None):
     return out.float().cpu().numpy()
 
 
-def check_bf16_output(got, ref, ctx):
+def check_bf16_output(got, ref, ctx, slack=1e-5):
+    """`slack` (in units of the tensor's rms) is what an element may be off beyond its own rounding to
+    bf16: 1e-5 where the products are exact (bf16 operands, fp32 sums); 3e-2 for the fused Winograd
+    kernel on the bf16 matrix pipe, which rounds the transformed filter and the transformed patches to
+    bf16 (a relative 2^-9 each on 16 x Ci products per output: 4.2e-3 relative L2 in a numpy model of
+    it, elements up to 1.8e-2 rms off)."""
     assert np.isfinite(got).all(), ctx
     assert rel_l2(got, ref) <= 5e-3, (ctx, rel_l2(got, ref))
     rms = float(np.sqrt(np.mean(np.square(ref)))) or 1.0
-    bound = np.abs(ref) * 2.0 ** -8 + 1e-5 * rms
+    bound = np.abs(ref) * 2.0 ** -8 + slack * rms
     worst = float(np.max(np.abs(got - ref) - bound))
     assert worst <= 0.0, (ctx, worst)
     # what is stored really is bf16: the low 16 bits of every value are clear
@@ -101,7 +109,7 @@ def test_bf16_parity_all_algorithms_and_divisions(s, op):
             if op == ucd.BWD_FILTER:
                 assert rel_l2(got, ref) <= l2_tol([(algo, 0)]), (ctx, rel_l2(got, ref))
             else:
-                check_bf16_output(got, ref, ctx)
+                check_bf16_output(got, ref, ctx, slack=3e-2 if algo == ucd.ALGO_WINOGRAD_FUSED else 1e-5)
             ran += 1
     assert ran >= 2
 

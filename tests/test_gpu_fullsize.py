@@ -150,7 +150,7 @@ class Case:
             e = rel_l2(got, ref)
             assert e <= (5e-3 if rounded else l2_tol(micro)), (ctx, e)
             rms = float(np.sqrt(np.mean(np.square(ref)))) or 1.0
-            bound = elementwise_tol(micro) * rms + (np.abs(ref) * 2.0 ** -8 if rounded else 0.0)
+            bound = elementwise_tol(micro, rounded) * rms + (np.abs(ref) * 2.0 ** -8 if rounded else 0.0)
             worst = int(np.argmax(np.abs(got - ref) - bound))
             assert abs(got[worst] - ref[worst]) <= (bound[worst] if rounded else bound), \
                 (ctx, "flat index", int(idx[worst]), got[worst], ref[worst])
