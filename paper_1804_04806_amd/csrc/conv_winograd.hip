@@ -785,16 +785,21 @@ __global__ __launch_bounds__(256) void wino_fused_kernel(FusedParams p)
 // ---- the same on the bf16 matrix pipe (bf16 tensors) ---------------------------------------------
 // The transforms run in fp32 as above; U = G g G^T and V = B^T d B are then rounded to bf16 and
 // multiplied by v_mfma_f32_32x32x16_bf16 with fp32 accumulation: a step of 16 input channels is one
-// MFMA per point, an eighth of the fp32 kernel's matrix time, so the kernel lives on its loads, its
-// transforms and its LDS traffic.  LDS and the transformed filter in the workspace hold 16-byte cells
-// of eight consecutive input channels of one output channel (U) or tile (V), [point][half of the
-// step][64 rows][8]: exactly an MFMA operand of the lane that owns the row (lanes 0-31 the first
-// half's cell, lanes 32-63 the second's).
+// MFMA per point and 32x32 tile, an eighth of the fp32 kernel's matrix time, so the kernel lives on
+// its vector instructions (unpacking, transforms, packing), its LDS traffic and its loads.  Those
+// overlap only between waves, so the workgroup has eight: wave (ph, wk, wt) accumulates the points
+// 8*ph .. 8*ph+7 (rows 2*ph, 2*ph+1 of the point grid) of the 32x32 tile (wk, wt) in 128 registers,
+// which leaves room for two waves per SIMD; the two halves of a tile's points meet in the output
+// transform through LDS.
+// LDS and the transformed filter in the workspace hold pairs of consecutive input channels as dwords,
+// [point][channel pair][64 rows]: the four pairs of a half-step are the MFMA operand of the lane that
+// owns the row (lanes 0-31 pairs 0-3 of the step, lanes 32-63 pairs 4-7), and a wave's accesses are
+// consecutive dwords.
 // A patch row (4 pixels = 8 bytes at any 2-byte alignment) is fetched as the three aligned dwords that
 // cover it and shifted into place by the parity of its first element; pixels outside the row are
 // dropped by the byte selectors that widen bf16 to fp32.
 constexpr int kBfC = 16;   // input channels per step
-constexpr int kBfNU = 8;   // 16-byte cells of the step's U slice per thread: 16 points x 2 halves x 64 / 256
+constexpr int kBfNU = 4;   // 16-byte pieces of the step's U slice per thread: 16 points x 8 pairs x 64 / 4 / 512
 
 struct FusedBf16Params {
     const void *in;    // the input tensor's address rounded down to 4 bytes
@@ -807,7 +812,7 @@ struct FusedBf16Params {
     int lead;          // elements between `in` and the tensor's first element: 0 or 1
 };
 
-// U cells: [point][ci / 8][co (Mo4 rows)][ci % 8] as bf16, ci padded to Cpad (a multiple of 16) with zeros
+// U as bf16: [point][ci / 2][co (Mo4 rows)][ci % 2], ci padded to Cpad (a multiple of 16) with zeros
 template <class E>
 __global__ __launch_bounds__(256) void wino_filter_bf16_kernel(const void *__restrict__ w, uint16_t *__restrict__ U,
                                                                int Ci, int Co, int Mo4, int transposed, int Cpad)
@@ -832,28 +837,29 @@ __global__ __launch_bounds__(256) void wino_filter_bf16_kernel(const void *__res
         for (int r = 0; r < 4; ++r) t[r][s] = u[r];
     }
     const size_t plane = (size_t)Cpad * Mo4;   // elements per point
-    const size_t cell = ((size_t)(ci / 8) * Mo4 + co) * 8 + ci % 8;
+    const size_t at = ((size_t)(ci / 2) * Mo4 + co) * 2 + ci % 2;
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         float u[4];
         Wino<2>::filter(t[r], u);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) U[(size_t)(r * 4 + q) * plane + cell] = Elem<bf16>::round(u[q]);
+        for (int q = 0; q < 4; ++q) U[(size_t)(r * 4 + q) * plane + at] = Elem<bf16>::round(u[q]);
     }
 }
 
-__global__ __launch_bounds__(256) void wino_fused_bf16_kernel(FusedBf16Params p)
+__global__ __launch_bounds__(512) void wino_fused_bf16_kernel(FusedBf16Params p)
 {
     typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
     typedef float f32x2 __attribute__((ext_vector_type(2)));
     typedef unsigned int u32x3 __attribute__((ext_vector_type(3)));
-    __shared__ __attribute__((aligned(16))) u32x4 Us[2][16][2][64];
-    __shared__ __attribute__((aligned(16))) u32x4 Vs[2][16][2][64];
+    // [buffer][point][channel pair of the step][row]: bf16 pairs
+    __shared__ __attribute__((aligned(16))) uint32_t Us[2][16][8][64];
+    __shared__ __attribute__((aligned(16))) uint32_t Vs[2][16][8][64];
     const WinoGeom &g = p.g;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, lhi = lane >> 5;
-    const int wk = wave & 1, wt = wave >> 1;
+    const int ph = wave >> 2, wk = wave & 1, wt = (wave >> 1) & 1;
 
     const uint32_t v = xcd_order(blockIdx.x, gridDim.x);
     const int kb = (int)(v % (uint32_t)p.k_blocks), tb = (int)(v / (uint32_t)p.k_blocks);
@@ -862,11 +868,11 @@ __global__ __launch_bounds__(256) void wino_fused_bf16_kernel(FusedBf16Params p)
     const __amdgpu_buffer_rsrc_t rin = make_rsrc_bytes(p.in, 0, p.in_bytes);
     const __amdgpu_buffer_rsrc_t ru = make_rsrc_bytes(p.U, 0, p.u_bytes);
 
-    // producer role: the 4x4 patch of tile `lane` of the block, for channels 4*wave .. 4*wave+3 of the step.
-    // Element index of a row's first pixel = lead + c*Hi*Wi + eo[r]; with q = parity of (lead + c*Hi*Wi)
-    // the row starts in the dword at element ((eo + q) & ~1) past the channel's dword-aligned base, at
-    // its upper half if (eo + q) is odd.  Offsets carry 4 bytes more than that (eo >= -2, so they are
-    // never negative) and the channel's scalar offset 4 bytes less.
+    // producer role: the 4x4 patch of tile `lane` of the block, for channels 2*wave, 2*wave+1 of the step
+    // (one channel pair).  Element index of a row's first pixel = lead + c*Hi*Wi + eo[r]; with q = parity
+    // of (lead + c*Hi*Wi) the row starts in the dword at element ((eo + q) & ~1) past the channel's
+    // dword-aligned base, at its upper half if (eo + q) is odd.  Offsets carry 4 bytes more than that
+    // (eo >= -2, so they are never negative) and the channel's scalar offset 4 bytes less.
     uint32_t voffb0[4], voffb1[4];   // per row, for q = 0 and q = 1
     uint32_t sh0[4];        // 16 * parity of eo[row]: the shift for q = 0; for q = 1 the other one
     uint32_t sel[4];        // per patch column: selector that widens the pixel's half of a dword, or zeroes it
@@ -893,7 +899,7 @@ __global__ __launch_bounds__(256) void wino_fused_bf16_kernel(FusedBf16Params p)
             sel[c] = (unsigned)(w0 + c) < (unsigned)g.Wi ? (c & 1 ? 0x03020c0cu : 0x01000c0cu) : 0x0c0c0c0cu;
     }
     const int hw = g.Hi * g.Wi;
-    // channel c of the step at c0: the parity q and the scalar byte offset of its loads
+    // channel c: the parity q and the scalar byte offset of its loads
     auto chan_q = [&](int c) { return (p.lead + c * hw) & 1; };
     auto chan_soff = [&](int c) {
         if (c >= g.Ci) return kOob;   // past the last channel: every address out of range
@@ -901,19 +907,20 @@ __global__ __launch_bounds__(256) void wino_fused_bf16_kernel(FusedBf16Params p)
         return (uint32_t)(2 * (base - (base & 1)));   // 4 less is taken off below, where it cannot go negative
     };
 
-    // U slice of a step: cell id = tid + 256*i -> (point, half, output channel) = (id / 128, id / 64 % 2, id % 64)
+    // U slice of a step: piece id = tid + 512*i -> row = id / 16 = point * 8 + pair, output channels 4 * (id % 16) ..+3
     uint32_t uoff[kBfNU];
-    const int cgroups = p.ci_pad / 8;
+    const int cpairs = p.ci_pad / 2;
 #pragma unroll
     for (int i = 0; i < kBfNU; ++i) {
-        const int id = tid + 256 * i, xi = id >> 7, half = (id >> 6) & 1, k = k0 + (id & 63);
-        uoff[i] = k < g.Mo4 ? 16u * (uint32_t)((xi * cgroups + half) * g.Mo4 + k) : kOob;
+        const int id = tid + 512 * i, row = id >> 4, k = k0 + 4 * (id & 15);
+        const int xi = row >> 3, pair = row & 7;
+        uoff[i] = k < g.Mo4 ? 4u * (uint32_t)((xi * cpairs + pair) * g.Mo4 + k) : kOob;
     }
 
-    u32x3 raw[4][4];     // the thread's four patches of the step after the one in LDS, as loaded: [channel][row]
+    u32x3 raw[2][4];     // the thread's two patches of the step after the one in LDS, as loaded: [channel][row]
     u32x4 uq[kBfNU];     // and its share of that step's U slice
     auto fetch_row = [&](int c0, int i, int r) {
-        const int c = c0 + 4 * wave + i;
+        const int c = c0 + 2 * wave + i;
         const int q = chan_q(c);
         uint32_t vo = q ? voffb1[r] : voffb0[r];
         uint32_t so = chan_soff(c);
@@ -928,16 +935,17 @@ __global__ __launch_bounds__(256) void wino_fused_bf16_kernel(FusedBf16Params p)
         raw[i][r] = __builtin_amdgcn_raw_buffer_load_b96(rin, (int)vo, (int)so, 0);
     };
     auto fetch_u = [&](int c0, int i) {
-        const auto q = __builtin_amdgcn_raw_buffer_load_b128(ru, (int)uoff[i], (int)(16u * (uint32_t)((c0 >> 3) * g.Mo4)), 0);
-        uq[i] = q;
+        uq[i] = __builtin_amdgcn_raw_buffer_load_b128(ru, (int)uoff[i], (int)(4u * (uint32_t)((c0 >> 1) * g.Mo4)), 0);
     };
-    auto store_u = [&](int buf, int i) { (&Us[buf][0][0][0])[tid + 256 * i] = uq[i]; };
+    auto store_u = [&](int buf, int i) {
+        *reinterpret_cast<u32x4 *>(&Us[buf][0][0][0] + 4 * (tid + 512 * i)) = uq[i];
+    };
 
-    // B^T d B of the four patches, rounded to bf16: pk[xi][0] = channels 0, 1; pk[xi][1] = channels 2, 3
-    uint32_t pk[16][2];
+    // B^T d B of the two patches, rounded to bf16 and paired
     float vprev[16];   // the transformed patch of the even channel, waiting for its odd partner
-    auto transform = [&](int c0, int i) {
-        const int c = c0 + 4 * wave + i;
+    auto transform = [&](int c0, auto I, int buf) {
+        constexpr int i = decltype(I)::value;
+        const int c = c0 + 2 * wave + i;
         const uint32_t qs = (uint32_t)chan_q(c) << 4;
         float d[16];
 #pragma unroll
@@ -971,47 +979,39 @@ __global__ __launch_bounds__(256) void wino_fused_bf16_kernel(FusedBf16Params p)
             vv[4 * r + 2] = a2 - a1;
             vv[4 * r + 3] = a1 - a3;
         }
-        if (i % 2 == 0) {
+        if constexpr (i == 0) {
 #pragma unroll
             for (int xi = 0; xi < 16; ++xi) vprev[xi] = vv[xi];
         } else {
+            // the thread's channel pair is dword [xi][wave][lane] of the step's slab
 #pragma unroll
             for (int xi = 0; xi < 16; ++xi) {
                 const f32x2 two = {vprev[xi], vv[xi]};
                 const bf16x2 h2 = __builtin_convertvector(two, bf16x2);
-                pk[xi][i / 2] = *reinterpret_cast<const uint32_t *>(&h2);
+                Vs[buf][xi][wave][lane] = *reinterpret_cast<const uint32_t *>(&h2);
             }
         }
     };
-    // the thread's four channels are half a cell: dwords 2*(wave & 1), +1 of cell [xi][wave >> 1][lane]
-    auto store_v = [&](int buf) {
-#pragma unroll
-        for (int xi = 0; xi < 16; ++xi) {
-            uint32_t *cell = reinterpret_cast<uint32_t *>(&Vs[buf][xi][wave >> 1][lane]) + 2 * (wave & 1);
-            *reinterpret_cast<u32x2 *>(cell) = u32x2{pk[xi][0], pk[xi][1]};
-        }
-    };
 
-    f32x16 acc[16];
+    f32x16 acc[8];
 #pragma unroll
-    for (int i = 0; i < 16; ++i)
+    for (int i = 0; i < 8; ++i)
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
 
     // step 0 -> LDS buffer 0, step 1 -> registers
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int r = 0; r < 4; ++r) fetch_row(0, i, r);
 #pragma unroll
     for (int i = 0; i < kBfNU; ++i) fetch_u(0, i);
-    auto first_transforms = [&](auto I) { transform(0, decltype(I)::value); };
-    static_for<4>(first_transforms);
-    store_v(0);
+    transform(0, std::integral_constant<int, 0>{}, 0);
+    transform(0, std::integral_constant<int, 1>{}, 0);
 #pragma unroll
     for (int i = 0; i < kBfNU; ++i) store_u(0, i);
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int r = 0; r < 4; ++r) fetch_row(kBfC, i, r);
 #pragma unroll
@@ -1020,75 +1020,81 @@ __global__ __launch_bounds__(256) void wino_fused_bf16_kernel(FusedBf16Params p)
 
     int buf = 0;
     for (int c0 = 0; c0 < g.Ci; c0 += kBfC) {
-        const u32x4 *ua = &Us[buf][0][lhi][wk * 32 + l32];
-        const u32x4 *vb = &Vs[buf][0][lhi][wt * 32 + l32];
-        constexpr int kAhead = 2;
-        u32x4 a[kAhead + 1], b[kAhead + 1];
-        auto read_ops = [&](int xi) {
-            a[xi % (kAhead + 1)] = ua[xi * 128];
-            b[xi % (kAhead + 1)] = vb[xi * 128];
-        };
+        // operands of point xi: the lane's row of pairs 4*lhi .. 4*lhi+3
+        const uint32_t *ua = &Us[buf][8 * ph][4 * lhi][wk * 32 + l32];
+        const uint32_t *vb = &Vs[buf][8 * ph][4 * lhi][wt * 32 + l32];
+        u32x4 a[2], b[2];
+        auto read_ops = [&](int m) {
 #pragma unroll
-        for (int xi = 0; xi < kAhead; ++xi) read_ops(xi);
-        __builtin_amdgcn_sched_barrier(0);
+            for (int q = 0; q < 4; ++q) {
+                a[m & 1][q] = ua[(m * 8 + q) * 64];
+                b[m & 1][q] = vb[(m * 8 + q) * 64];
+            }
+        };
+        read_ops(0);
         // one MFMA per point and, behind it, a piece of the next step's work: the registers hold step
         // c0 + 16 as loaded; each patch is transformed and its registers reloaded with step c0 + 32
         auto slot = [&](auto M) {
-            constexpr int xi = decltype(M)::value;
-            acc[xi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[xi % (kAhead + 1)]),
-                                                              __builtin_bit_cast(bf16x8, b[xi % (kAhead + 1)]), acc[xi], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            if constexpr (xi + kAhead < 16) read_ops(xi + kAhead);
-            if constexpr (xi < 8) {
-                constexpr int i = xi / 2;
-                if constexpr (xi % 2 == 0) {
-                    transform(c0 + kBfC, i);
-                } else {
+            constexpr int m = decltype(M)::value;
+            if constexpr (m + 1 < 8) read_ops(m + 1);
+            acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[m & 1]),
+                                                             __builtin_bit_cast(bf16x8, b[m & 1]), acc[m], 0, 0, 0);
+            if constexpr (m == 0 || m == 2) {
+                transform(c0 + kBfC, std::integral_constant<int, m / 2>{}, buf ^ 1);
+            } else if constexpr (m == 1 || m == 3) {
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) fetch_row(c0 + 2 * kBfC, i, r);
-                }
-            } else if constexpr (xi == 8) {
-                store_v(buf ^ 1);
-            } else if constexpr (xi < 13) {
-                constexpr int i0 = 2 * (xi - 9);
+                for (int r = 0; r < 4; ++r) fetch_row(c0 + 2 * kBfC, m / 2, r);
+            } else if constexpr (m < 6) {
+                constexpr int i0 = 2 * (m - 4);
                 store_u(buf ^ 1, i0);
                 store_u(buf ^ 1, i0 + 1);
                 fetch_u(c0 + 2 * kBfC, i0);
                 fetch_u(c0 + 2 * kBfC, i0 + 1);
             }
-            __builtin_amdgcn_sched_barrier(0);
         };
-        static_for<16>(slot);
+        static_for<8>(slot);
         __syncthreads();
         buf ^= 1;
     }
 
-    // output transform and store: lane = tile (column l32 of the wave's 32), register e = channel row
+    // Output transform Y = A^T M A, A^T = [1 1 1 0; 0 1 -1 -1]: this wave holds rows 2*ph, 2*ph+1 of M.
+    // Each half forms its share of both output rows; the share of the row it does not store goes to
+    // the other half through LDS (the operand buffers are free now), [value][wave][lane].
+    float *xch = reinterpret_cast<float *>(&Us[0][0][0][0]);   // 32 values x 8 waves x 64 lanes = 64 KB
+    float mine[16][2];   // the row this half stores: ph = 0 the tile's first row, ph = 1 its second
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+        // rows ra = M[2ph], rb = M[2ph+1], each times A: two values
+        const float a0 = acc[0][e], a1 = acc[1][e], a2 = acc[2][e], a3 = acc[3][e];
+        const float b0 = acc[4][e], b1 = acc[5][e], b2 = acc[6][e], b3 = acc[7][e];
+        const float ra0 = a0 + a1 + a2, ra1 = a1 - a2 - a3, rb0 = b0 + b1 + b2, rb1 = b1 - b2 - b3;
+        // ph = 0: rows 0, 1 of M: Y[0] += ra + rb, Y[1] += rb.   ph = 1: rows 2, 3: Y[0] += ra, Y[1] += -ra - rb
+        float keep0, keep1, give0, give1;
+        if (ph == 0) { keep0 = ra0 + rb0; keep1 = ra1 + rb1; give0 = rb0; give1 = rb1; }
+        else { keep0 = -ra0 - rb0; keep1 = -ra1 - rb1; give0 = ra0; give1 = ra1; }
+        mine[e][0] = keep0; mine[e][1] = keep1;
+        xch[((2 * e) * 8 + wave) * 64 + lane] = give0;
+        xch[((2 * e + 1) * 8 + wave) * 64 + lane] = give1;
+    }
+    __syncthreads();
     const int j = t0 + wt * 32 + l32;
     if (j >= p.n_tiles) return;
     uint32_t n, t, th, tw;
     p.divT.divmod((uint32_t)j, n, t);
     p.divTW.divmod(t, th, tw);
-    const int h0 = 2 * (int)th, w0 = 2 * (int)tw;
-    const bool h1 = h0 + 1 < g.Ho, w1 = w0 + 1 < g.Wo;
+    const int ho = 2 * (int)th + ph, wo = 2 * (int)tw;
+    if (ho >= g.Ho) return;
+    const bool w1 = wo + 1 < g.Wo;
+    const int other = wave ^ 4;
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
         const int k = k0 + wk * 32 + 8 * (e / 4) + 4 * lhi + (e % 4);
         if (k >= g.Co) continue;
-        float y[2][4];  // A^T m, column by column
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const float m0 = acc[c][e], m1 = acc[4 + c][e], m2 = acc[8 + c][e], m3 = acc[12 + c][e];
-            y[0][c] = m0 + m1 + m2;
-            y[1][c] = m1 - m2 - m3;
-        }
-        const long base = (((long)n * g.Co + k) * g.Ho + h0) * g.Wo + w0;
-        Elem<bf16>::store(p.out, base, y[0][0] + y[0][1] + y[0][2]);
-        if (w1) Elem<bf16>::store(p.out, base + 1, y[0][1] - y[0][2] - y[0][3]);
-        if (h1) {
-            Elem<bf16>::store(p.out, base + g.Wo, y[1][0] + y[1][1] + y[1][2]);
-            if (w1) Elem<bf16>::store(p.out, base + g.Wo + 1, y[1][1] - y[1][2] - y[1][3]);
-        }
+        const float y0 = mine[e][0] + xch[((2 * e) * 8 + other) * 64 + lane];
+        const float y1 = mine[e][1] + xch[((2 * e + 1) * 8 + other) * 64 + lane];
+        const long base = (((long)n * g.Co + k) * g.Ho + ho) * g.Wo + wo;
+        Elem<bf16>::store(p.out, base, y0);
+        if (w1) Elem<bf16>::store(p.out, base + 1, y1);
     }
 }
 
@@ -1143,7 +1149,7 @@ static hipError_t winograd_fused_run(const Dims &d, int op, int b, const void *i
                      std::to_string(2.0 * 16 * g.Co * (double)q.n_tiles * g.Ci));
             return hipSuccess;
         }
-        wino_fused_bf16_kernel<<<nb, 256, 0, s>>>(q);
+        wino_fused_bf16_kernel<<<nb, 512, 0, s>>>(q);
         return hipGetLastError();
     }
     FusedParams p{};
