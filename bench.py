@@ -278,7 +278,7 @@ def kernel_class(ucd, desc, op, algo, b):
     text, n = ucd.ucd_describe_micro(desc, op, algo, b)
     parts = [p.strip() for p in text.split(";")]
     helpers = ("fill_zero_kernel", "zero_tiles_kernel", "wino_filter_kernel", "wino_dw_kernel", "mirror_filter_kernel",
-               "wino5_filter_kernel", "wino5_dw_kernel", "wino_phase_filter_kernel")
+               "wino5_filter_kernel", "wino5_dw_kernel", "wino_phase_filter_kernel", "wino_filter_bf16_kernel")
     main = [p for p in parts if p.startswith(("gemm_kernel", "wino_fused", "wino5_fused"))]
     others = [p for p in parts if p not in main and p not in helpers]
     if len(main) != 1 or others:

@@ -1120,7 +1120,7 @@ static hipError_t winograd_fused_run(const Dims &d, int op, int b, const void *i
     const int ci_pad16 = (g.Ci + kBfC - 1) / kBfC * kBfC;
     if (filter_ready) {
         // U of this filter is still in the workspace from the previous micro-batch
-    } else if (log) log->add(phased ? "wino_phase_filter_kernel" : "wino_filter_kernel");
+    } else if (log) log->add(phased ? "wino_phase_filter_kernel" : bf16_pipe ? "wino_filter_bf16_kernel" : "wino_filter_kernel");
     else if (bf16_pipe)
         wino_filter_bf16_kernel<E><<<(unsigned)((ci_pad16 * g.Mo4 + 255) / 256), 256, 0, s>>>(
             w, (uint16_t *)ws, g.Ci, g.Co, g.Mo4, g.transposed ? 1 : 0, ci_pad16);
