@@ -46,13 +46,13 @@ WS_LIMIT = 64 << 20
 # `traffic` = this figure x the flops per launch of the step being timed: the planner does not
 # pick the same micro-batch sizes every run, and a kernel's traffic follows its size.
 MEASURED_TRAFFIC_BYTES_PER_FLOP = {
-    "wino_fused_kernel": 317.4e6 / 37.54e9,
-    "wino5_fused_kernel": 367.7e6 / 43.87e9,
-    "wino_fused_filter_kernel": 643.7e6 / 52.55e9,
-    "wino5_fused_filter_kernel": 1217.5e6 / 90.6e9,
-    "gemm_kernel<Tile<96x128>,PixelKLane<dy>,PixelKLane<x, no padding>,EpiAtomic>": 543.1e6 / 53.97e9,
-    "gemm_kernel<Tile<96x128>,KLane0,GatherNLane<no padding>,EpiNCHW>": 482.1e6 / 53.97e9,
-    "gemm_kernel<Tile<64x128>,PhaseFilterKLane,GatherNLane<taps<=31>,EpiPhases>": 434.5e6 / 68.98e9,
+    "wino_fused_kernel": 369.9e6 / 43.83e9,
+    "wino5_fused_kernel": 491.0e6 / 58.5e9,
+    "wino_fused_filter_kernel": 644.1e6 / 52.55e9,
+    "wino5_fused_filter_kernel": 1217.2e6 / 90.6e9,
+    "wino_fused_kernel<phases>": 242.1e6 / 15.88e9,
+    "gemm_kernel<Tile<96x128>,PixelKLane<dy>,PixelKLane<x, no padding>,EpiAtomic>": 547.9e6 / 53.97e9,
+    "gemm_kernel<Tile<96x128>,KLane0,GatherNLane<no padding>,EpiNCHW>": 242.4e6 / 26.99e9,
 }
 
 ALGO_IDS = {"implicit": 0, "im2col": 1, "winograd": 2, "winograd4": 3, "fft": 4, "winograd-fused": 5,
