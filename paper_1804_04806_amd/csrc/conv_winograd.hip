@@ -430,36 +430,48 @@ struct FusedParams {
     int ci_pad;   // rows of a plane of U: Ci rounded up to the channel step
 };
 
-template <class E, int PW, bool ODD_W = false, bool PHASED = false>
+template <class E, int PW, bool ODD_W = false, bool PHASED = false, bool WIDE = false>
 __global__ __launch_bounds__(256) void wino_fused_kernel(FusedParams p)
 {
     constexpr uint32_t EB = Elem<E>::kBytes;
     constexpr bool kRows = PW >= 0;   // row-vector patch loads
     static_assert(!kRows || EB == 4, "row loads are written for fp32 tensors");
-    __shared__ __attribute__((aligned(16))) float Us[2][16][kFuC][kFuK];
-    __shared__ __attribute__((aligned(16))) float Vs[2][16][kFuC][kFuT];
+    static_assert(!WIDE || kRows, "the wide block is written for row loads");
+    // block: 64 output channels x 64 tiles (waves 2 x 2), or WIDE: 128 x 32 (waves 4 x 1).  The wide block
+    // transforms one patch per thread and step instead of two (every patch serves twice as many output
+    // channels) and reads twice as much of U; LDS: 128 + 32 KB instead of 64 + 64.
+    constexpr int KB = WIDE ? 128 : kFuK, TB = WIDE ? 32 : kFuT;
+    constexpr int NP = WIDE ? 1 : kFuNP;             // input patches per thread and step
+    constexpr int NU = kFuC * 16 * KB / 4 / 256;     // float4 pieces of the step's U slice per thread
+    __shared__ __attribute__((aligned(16))) float Us[2][16][kFuC][KB];
+    __shared__ __attribute__((aligned(16))) float Vs[2][16][kFuC][TB];
     const WinoGeom &g = p.g;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, lhi = lane >> 5;
-    const int wk = wave & 1, wt = wave >> 1;
+    const int wk = WIDE ? wave : wave & 1, wt = WIDE ? 0 : wave >> 1;
 
     // consecutive work items of an XCD share a tile block (the input patches) and differ in the
     // channel block
     const uint32_t v = xcd_order(blockIdx.x, gridDim.x);
     const int kb = (int)(v % (uint32_t)p.k_blocks), tb = (int)(v / (uint32_t)p.k_blocks);
-    const int k0 = kb * kFuK, t0 = tb * kFuT;
+    const int k0 = kb * KB, t0 = tb * TB;
 
     const __amdgpu_buffer_rsrc_t rin = make_rsrc_bytes(p.in, 0, p.in_bytes);
     const __amdgpu_buffer_rsrc_t ru = make_rsrc_bytes(p.U, 0, p.u_bytes);
 
     // producer role: the 4x4 patch of tile `lane` of the block, for channels wave, wave + 4, ... of the step
+    // (WIDE: of tile lane % 32, for channel 2 * wave + lane / 32; the upper half's channel is part of its
+    // offsets).  The lanes that fetch their own first columns: lane 0, or WIDE the first of every 16
+    // (the cross-lane move then stays within rows of 16 lanes).
+    const int ptile = WIDE ? l32 : lane;
+    const bool own_lane = WIDE ? (lane & 15) == 0 : lane == 0;
     uint32_t voff[kRows ? 4 : 16];   // element-wise: one offset per pixel; rows: the window start of each row
     uint32_t xoff[4];                // rows, PW >= 1: the patch's first PW columns, fetched by lane 0 only
     bool first_col = false, ok1 = true, ok2 = true, ok3 = true;  // rows: tile column 0; window elements inside the row
     bool ok0 = true, okm1 = true;    // PW = 2: the window's first element and the column before it
     {
-        const int j = t0 + lane;
+        const int j = t0 + ptile;
         uint32_t n = 0, t, th = 0, tw = 0;
         const bool live = j < p.n_tiles;
         if (live) {
@@ -467,6 +479,7 @@ __global__ __launch_bounds__(256) void wino_fused_kernel(FusedParams p)
             p.divTW.divmod(t, th, tw);
         }
         const int h0 = 2 * (int)th - g.pad_h, w0 = 2 * (int)tw - g.pad_w;
+        const uint32_t half_chan = WIDE ? EB * (uint32_t)(lhi * g.Hi * g.Wi) : 0u;
         if constexpr (kRows) {
             const int ws = 2 * (int)tw;   // = w0 + PW
             first_col = tw == 0;
@@ -476,9 +489,9 @@ __global__ __launch_bounds__(256) void wino_fused_kernel(FusedParams p)
             for (int r = 0; r < 4; ++r) {
                 const int h = h0 + r;
                 const bool ok = live && (unsigned)h < (unsigned)g.Hi;
-                const uint32_t row = EB * (uint32_t)(((int)n * g.Ci * g.Hi + h) * g.Wi + ws);
+                const uint32_t row = EB * (uint32_t)(((int)n * g.Ci * g.Hi + h) * g.Wi + ws) + half_chan;
                 voff[r] = ok ? row : kOob;
-                xoff[r] = ok && PW >= 1 && lane == 0 && tw > 0 ? row - PW * EB : kOob;
+                xoff[r] = ok && PW >= 1 && own_lane && tw > 0 ? row - PW * EB : kOob;
             }
         } else {
 #pragma unroll
@@ -493,10 +506,10 @@ __global__ __launch_bounds__(256) void wino_fused_kernel(FusedParams p)
     }
     // U slice of a step: 16 points x kFuC channels x 64 output channels, as float4: piece id = tid + 256*i
     // -> row = id / 16 = point * kFuC + channel, 4 output channels from 4 * (id % 16)
-    uint32_t uoff[kFuNU];
+    uint32_t uoff[NU];
 #pragma unroll
-    for (int i = 0; i < kFuNU; ++i) {
-        const int id = tid + 256 * i, row = id >> 4, q = id & 15;
+    for (int i = 0; i < NU; ++i) {
+        const int id = tid + 256 * i, row = id / (KB / 4), q = id % (KB / 4);
         const int xi = row / kFuC, c = row % kFuC, k = k0 + 4 * q;
         uoff[i] = k < g.Mo4 ? 4u * (uint32_t)((xi * p.ci_pad + c) * g.Mo4 + k) : kOob;
     }
@@ -504,12 +517,14 @@ __global__ __launch_bounds__(256) void wino_fused_kernel(FusedParams p)
     // the thread's input patches of the step after the one in LDS: 16 pixels each, or per row a window
     // of 2 (PW = 2), 3 (PW = 1) or 4 (PW = 0) pixels at the end of d[h][4r..] and, for PW >= 1, lane 0's
     // first PW columns in dx
-    float d[kFuNP][16];
-    float dx[kFuNP][PW == 2 ? 8 : 4];
-    f32x4 uq[kFuNU];     // and its share of that step's U slice
+    float d[NP][16];
+    float dx[NP][PW == 2 ? 8 : 4];
+    f32x4 uq[NU];        // and its share of that step's U slice
     // a channel past the last one gets a scalar offset that pushes every address out of range
     auto chan_off = [&](int c0, int h) {
-        const int c = c0 + wave + 4 * h;
+        // WIDE: the lower half's channel; the upper half's, one further, may be the first one past the
+        // last: it then reads the next image's data (or nothing), and U's rows past Ci are zero
+        const int c = WIDE ? c0 + 2 * wave : c0 + wave + 4 * h;
         return c < g.Ci ? EB * (uint32_t)(c * g.Hi * g.Wi) : kOob;
     };
     constexpr int kPatchLoads = !kRows ? 16 : PW >= 1 ? 8 : 4;   // load instructions per patch
@@ -541,6 +556,7 @@ __global__ __launch_bounds__(256) void wino_fused_kernel(FusedParams p)
         for (int i = 0; i < kPatchLoads; ++i) fetch_piece(c0, h, i);
     };
     // rows: the windows as loaded become the patch (first column from the lane below, zeros outside the row)
+    constexpr int kShr = WIDE ? 0x111 : 0x138;   // row_shr:1 (rows of 16 lanes) | wave_shr:1
     auto finish_patch = [&](int h) {
         if constexpr (kRows) {
 #pragma unroll
@@ -552,9 +568,9 @@ __global__ __launch_bounds__(256) void wino_fused_kernel(FusedParams p)
                     // second window element has just been zeroed: the cross-lane move delivers the 0.
                     if constexpr (ODD_W) d[h][4 * r + 2] = ok1 ? d[h][4 * r + 2] : 0.f;
                     d[h][4 * r + 3] = ok2 ? d[h][4 * r + 3] : 0.f;
-                    // wave_shr:1: every lane takes the value of the lane below; lane 0 keeps `old`
+                    // every lane takes the value of the lane below; the lanes that loaded their own keep `old`
                     const int left = __builtin_amdgcn_update_dpp((int)__float_as_uint(dx[h][r]),
-                                                                 (int)__float_as_uint(d[h][4 * r + 2]), 0x138, 0xf, 0xf, false);
+                                                                 (int)__float_as_uint(d[h][4 * r + 2]), kShr, 0xf, 0xf, false);
                     d[h][4 * r] = ODD_W ? __uint_as_float((uint32_t)left) : first_col ? 0.f : __uint_as_float((uint32_t)left);
                 } else if constexpr (PW == 2) {
                     // Window = columns 2tw, 2tw+1 = patch columns 2, 3; the last tile column's window can
@@ -565,9 +581,9 @@ __global__ __launch_bounds__(256) void wino_fused_kernel(FusedParams p)
                     d[h][4 * r + 3] = ok1 ? d[h][4 * r + 3] : 0.f;
                     const float own1 = okm1 ? dx[h][2 * r + 1] : 0.f;
                     const int l0 = __builtin_amdgcn_update_dpp((int)__float_as_uint(dx[h][2 * r]),
-                                                               (int)__float_as_uint(d[h][4 * r + 2]), 0x138, 0xf, 0xf, false);
+                                                               (int)__float_as_uint(d[h][4 * r + 2]), kShr, 0xf, 0xf, false);
                     const int l1 = __builtin_amdgcn_update_dpp((int)__float_as_uint(own1),
-                                                               (int)__float_as_uint(d[h][4 * r + 3]), 0x138, 0xf, 0xf, false);
+                                                               (int)__float_as_uint(d[h][4 * r + 3]), kShr, 0xf, 0xf, false);
                     d[h][4 * r] = first_col ? 0.f : __uint_as_float((uint32_t)l0);
                     d[h][4 * r + 1] = first_col ? 0.f : __uint_as_float((uint32_t)l1);
                 } else {
@@ -583,6 +599,7 @@ __global__ __launch_bounds__(256) void wino_fused_kernel(FusedParams p)
     // and is never used
     auto fetch_u = [&](int c0, int i) { uq[i] = buf_load4(ru, uoff[i], 4u * (uint32_t)(c0 * g.Mo4)); };
     // B^T d B of patch h into LDS buffer `buf`: points 4r .. 4r+3 from row r of B^T d
+    auto vrow = [&](int h) { return WIDE ? 2 * wave + lhi : wave + 4 * h; };
     auto store_v = [&](int buf, int h) {
         finish_patch(h);
         float tr[16];
@@ -597,15 +614,15 @@ __global__ __launch_bounds__(256) void wino_fused_kernel(FusedParams p)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const float a0 = tr[4 * r], a1 = tr[4 * r + 1], a2 = tr[4 * r + 2], a3 = tr[4 * r + 3];
-            Vs[buf][4 * r + 0][wave + 4 * h][lane] = a0 - a2;
-            Vs[buf][4 * r + 1][wave + 4 * h][lane] = a1 + a2;
-            Vs[buf][4 * r + 2][wave + 4 * h][lane] = a2 - a1;
-            Vs[buf][4 * r + 3][wave + 4 * h][lane] = a1 - a3;
+            Vs[buf][4 * r + 0][vrow(h)][ptile] = a0 - a2;
+            Vs[buf][4 * r + 1][vrow(h)][ptile] = a1 + a2;
+            Vs[buf][4 * r + 2][vrow(h)][ptile] = a2 - a1;
+            Vs[buf][4 * r + 3][vrow(h)][ptile] = a1 - a3;
         }
     };
     // piece i goes to row (tid >> 4) + 16 i of the buffer's [16 * kFuC][64] slab: one address per
     // thread, the pieces 1024 floats apart (immediate offsets)
-    const int u_slot = (tid >> 4) * kFuK + 4 * (tid & 15);
+    const int u_slot = 4 * tid;
     auto store_u = [&](int buf, int i) {
         *reinterpret_cast<f32x4 *>(&Us[buf][0][0][0] + u_slot + 1024 * i) = uq[i];
     };
@@ -617,17 +634,17 @@ __global__ __launch_bounds__(256) void wino_fused_kernel(FusedParams p)
         for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
 
 #pragma unroll
-    for (int h = 0; h < kFuNP; ++h) fetch_patch(0, h);
+    for (int h = 0; h < NP; ++h) fetch_patch(0, h);
 #pragma unroll
-    for (int i = 0; i < kFuNU; ++i) fetch_u(0, i);
+    for (int i = 0; i < NU; ++i) fetch_u(0, i);
 #pragma unroll
-    for (int h = 0; h < kFuNP; ++h) store_v(0, h);
+    for (int h = 0; h < NP; ++h) store_v(0, h);
 #pragma unroll
-    for (int i = 0; i < kFuNU; ++i) store_u(0, i);
+    for (int i = 0; i < NU; ++i) store_u(0, i);
 #pragma unroll
-    for (int h = 0; h < kFuNP; ++h) fetch_patch(kFuC, h);
+    for (int h = 0; h < NP; ++h) fetch_patch(kFuC, h);
 #pragma unroll
-    for (int i = 0; i < kFuNU; ++i) fetch_u(kFuC, i);
+    for (int i = 0; i < NU; ++i) fetch_u(kFuC, i);
     __syncthreads();
 
     int buf = 0;
@@ -643,8 +660,8 @@ __global__ __launch_bounds__(256) void wino_fused_kernel(FusedParams p)
             const int xi = u / (kFuPairs / 2), q0 = 2 * (u % (kFuPairs / 2));
 #pragma unroll
             for (int q = 0; q < 2; ++q) {
-                a[u % (kAhead + 1)][q] = ua[(xi * kFuC + 2 * (q0 + q)) * kFuK];
-                b[u % (kAhead + 1)][q] = vb[(xi * kFuC + 2 * (q0 + q)) * kFuT];
+                a[u % (kAhead + 1)][q] = ua[(xi * kFuC + 2 * (q0 + q)) * KB];
+                b[u % (kAhead + 1)][q] = vb[(xi * kFuC + 2 * (q0 + q)) * TB];
             }
         };
 #pragma unroll
@@ -667,18 +684,18 @@ __global__ __launch_bounds__(256) void wino_fused_kernel(FusedParams p)
             // the wave at the memory pipeline's queue, and with one wave per SIMD nothing else would
             // feed the matrix pipe meanwhile.
             constexpr int kPatchSlots = 1 + kPatchLoads;  // 1 transform + the patch's loads
-            if constexpr (m >= 1 && m < 1 + kPatchSlots * kFuNP) {
+            if constexpr (m >= 1 && m < 1 + kPatchSlots * NP) {
                 constexpr int h = (m - 1) / kPatchSlots, i = (m - 1) % kPatchSlots;
                 if constexpr (i == 0) store_v(buf ^ 1, h);
                 else fetch_piece(c0 + 2 * kFuC, h, i - 1);
             }
-            constexpr int kUStart = 1 + kPatchSlots * kFuNP;
-            if constexpr (m >= kUStart && m < kUStart + 2 * kFuNU) {
+            constexpr int kUStart = 1 + kPatchSlots * NP;
+            if constexpr (m >= kUStart && m < kUStart + 2 * NU) {
                 constexpr int i = (m - kUStart) / 2;
                 if constexpr ((m - kUStart) % 2 == 0) store_u(buf ^ 1, i);
                 else fetch_u(c0 + 2 * kFuC, i);
             }
-            static_assert(kUStart + 2 * kFuNU <= 16 * kFuPairs, "the step's work fits behind its MFMAs");
+            static_assert(kUStart + 2 * NU <= 16 * kFuPairs, "the step's work fits behind its MFMAs");
             __builtin_amdgcn_sched_barrier(0);
         };
         static_for<kMfmas>(slot);
@@ -1159,28 +1176,39 @@ static hipError_t winograd_fused_run(const Dims &d, int op, int b, const void *i
     p.u_bytes = (uint32_t)((size_t)64 * p.ci_pad * g.Mo4);
     p.g = g; p.divT = FastDiv(g.T); p.divTW = FastDiv(g.TW);
     p.n_tiles = b * g.T;
-    p.k_blocks = (g.Co + kFuK - 1) / kFuK;
-    const unsigned blocks = (unsigned)(p.k_blocks * ((p.n_tiles + kFuT - 1) / kFuT));
+    // row-vector patch loads: fp32 tensors (UCD_FUSED_ELEMENTWISE=1 in the environment keeps the
+    // element-wise loads, for comparison).  With them, the 128 x 32 block wherever 128-channel blocks
+    // cover the output channels with no more padding than 64-channel ones (UCD_FUSED_NARROW=1: never).
+    static const bool elementwise = getenv("UCD_FUSED_ELEMENTWISE") != nullptr;
+    static const bool narrow = getenv("UCD_FUSED_NARROW") != nullptr;
+    const bool rows = std::is_same_v<E, float> && !elementwise && g.pad_w <= 2;
+    const bool wide = rows && !phased && !narrow && (g.Co + 127) / 128 * 2 <= (g.Co + 63) / 64;
+    const int kblock = wide ? 128 : kFuK, tblock = wide ? 32 : kFuT;
+    p.k_blocks = (g.Co + kblock - 1) / kblock;
+    const unsigned blocks = (unsigned)(p.k_blocks * ((p.n_tiles + tblock - 1) / tblock));
     if (log) {
         log->add(std::string(phased ? "wino_fused_kernel<phases>" : "wino_fused_kernel") + " blocks=" +
                  std::to_string(blocks) + " gemm_flops=" + std::to_string(2.0 * 16 * g.Co * (double)p.n_tiles * g.Ci));
         return hipSuccess;
     }
-    // row-vector patch loads: fp32 tensors (UCD_FUSED_ELEMENTWISE=1 in the environment keeps the
-    // element-wise loads, for comparison)
-    static const bool elementwise = getenv("UCD_FUSED_ELEMENTWISE") != nullptr;
     if (phased) {
-        if (std::is_same_v<E, float> && !elementwise) wino_fused_kernel<float, 2, false, true><<<blocks, 256, 0, s>>>(p);
+        if (rows) wino_fused_kernel<float, 2, false, true><<<blocks, 256, 0, s>>>(p);
         else wino_fused_kernel<E, -1, false, true><<<blocks, 256, 0, s>>>(p);
         return hipGetLastError();
     }
-    bool rows = false;
     if constexpr (std::is_same_v<E, float>) {
-        rows = !elementwise && g.pad_w <= 2;
-        if (rows && g.pad_w == 0) wino_fused_kernel<E, 0><<<blocks, 256, 0, s>>>(p);
-        else if (rows && g.pad_w == 2) wino_fused_kernel<E, 2><<<blocks, 256, 0, s>>>(p);
-        else if (rows && g.Wi % 2) wino_fused_kernel<E, 1, true><<<blocks, 256, 0, s>>>(p);
-        else if (rows) wino_fused_kernel<E, 1, false><<<blocks, 256, 0, s>>>(p);
+        const bool odd = g.Wi % 2 != 0;
+        if (wide) {
+            if (g.pad_w == 0) wino_fused_kernel<E, 0, false, false, true><<<blocks, 256, 0, s>>>(p);
+            else if (g.pad_w == 2) wino_fused_kernel<E, 2, false, false, true><<<blocks, 256, 0, s>>>(p);
+            else if (odd) wino_fused_kernel<E, 1, true, false, true><<<blocks, 256, 0, s>>>(p);
+            else wino_fused_kernel<E, 1, false, false, true><<<blocks, 256, 0, s>>>(p);
+        } else if (rows) {
+            if (g.pad_w == 0) wino_fused_kernel<E, 0><<<blocks, 256, 0, s>>>(p);
+            else if (g.pad_w == 2) wino_fused_kernel<E, 2><<<blocks, 256, 0, s>>>(p);
+            else if (odd) wino_fused_kernel<E, 1, true><<<blocks, 256, 0, s>>>(p);
+            else wino_fused_kernel<E, 1, false><<<blocks, 256, 0, s>>>(p);
+        }
     }
     if (!rows) wino_fused_kernel<E, -1><<<blocks, 256, 0, s>>>(p);
     return hipGetLastError();

@@ -45,6 +45,9 @@ SHAPES = [
     Shape(2, 20, 10, 12, 70, 5, 5, 1, 2, "5x5-even"),          # F(2x2,5x5) tiles at an even width; K > 64 with a tail
     Shape(2, 40, 9, 9, 48, 5, 5, 1, 2, "5x5-square"),          # BackwardFilter in 64 x 64 channel blocks, odd width
     Shape(2, 40, 8, 10, 48, 5, 5, 1, 1, "5x5-square-even"),    # the same at an even width, rows padded by 1
+    Shape(2, 6, 11, 14, 100, 3, 3, 1, 0, "pad0-k100"),         # fused Winograd Forward in 128 x 32 blocks, no padding
+    Shape(2, 6, 6, 9, 100, 3, 3, 1, 2, "pad2-k100"),           # the same with padding 2 (8-byte row windows)
+    Shape(2, 100, 11, 14, 6, 3, 3, 1, 0, "pad0-c100"),         # BackwardData in 128 x 32 blocks over dy padded by 2
     Shape(2, 3, 27, 29, 70, 11, 11, 4, 2, "conv1-pad2"),       # BackwardData as a 3x3 Winograd convolution over 16 phases
     Shape(3, 20, 15, 16, 24, 5, 5, 2, 2, "5x5-s2"),            # the same with 4 phases, 80 phase channels (two blocks)
     Shape(2, 4, 20, 22, 9, 7, 7, 3, 3, "7x7-s3"),              # 9 phases, the third tap past the filter's end in two of three
