@@ -1310,6 +1310,10 @@ struct FusedFilterParams {
     uint32_t x_bytes, dy_bytes;
     WinoGeom g;       // Forward geometry: Ci = C, Co = K, Hi x Wi = H x W, Ho x Wo = P x Q
     int b, k_blocks, c_blocks, groups, n_split, images_per_chunk;
+    // The last tile-position group when the image leaves it 1, 2 or 4 tiles (49 tiles: 1): instead of
+    // padding it to 8 positions, its 8 slots are those tiles of `spread` = 8, 4 or 2 consecutive images,
+    // and it takes `spread` images per step.  1: off (chunks are then multiples of 8 images otherwise).
+    int spread;
 };
 
 // PW >= 0 (fp32 tensors, horizontal padding PW = 0 or 1): patch rows of x and tile rows of dy are
@@ -1340,6 +1344,9 @@ __global__ __launch_bounds__(256) void wino_fused_filter_kernel(FusedFilterParam
     const int chunk = (int)(v / (uint32_t)p.groups);
     const int k0 = kb * 64, c0 = cb * 64;
     const int n_begin = chunk * p.images_per_chunk, n_end = min(p.b, n_begin + p.images_per_chunk);
+    // images per step: 1, or for the last group `spread` (slot s = tile s % L of image s / L, L = 8 / spread;
+    // slots of images past the batch read out of range, i.e. zeros)
+    const int n_step = p.spread > 1 && grp == p.groups - 1 ? p.spread : 1;
 
     const __amdgpu_buffer_rsrc_t rx = make_rsrc_bytes(p.x, 0, p.x_bytes);
     const __amdgpu_buffer_rsrc_t rdy = make_rsrc_bytes(p.dy, 0, p.dy_bytes);
@@ -1358,15 +1365,18 @@ __global__ __launch_bounds__(256) void wino_fused_filter_kernel(FusedFilterParam
     uint32_t vx[2][kRows ? 8 : 16], vd[2][kRows ? 2 : 4];
     bool own_col = false, ok1 = true, ok2 = true, ok3 = true, dy_ok1 = true;
     {
-        const int t = grp * kFwT + ptile;
+        const int per_image = kFwT / n_step;   // slots per image
+        const int t = grp * kFwT + ptile % per_image, image = ptile / per_image;
         const bool live = t < g.T;
         const int th = live ? t / g.TW : 0, tw = live ? t % g.TW : 0;
         const int h0 = 2 * th - g.pad_h, w0 = 2 * tw - g.pad_w;
+        const uint32_t x_slot = EB * (uint32_t)(image * g.Ci * g.Hi * g.Wi), dy_slot = EB * (uint32_t)(image * g.Co * g.Ho * g.Wo);
         if constexpr (kRows) {
             const int ws = 2 * tw;   // = w0 + PW
             // the first column is this lane's own load (or the padding's 0) for the first tile position
-            // of a group and for tiles in the first tile column; otherwise the lane below holds it
-            own_col = ptile == 0 || tw == 0;
+            // of a group (of each image's share of it) and for tiles in the first tile column; otherwise
+            // the lane below holds it
+            own_col = ptile % per_image == 0 || tw == 0;
             ok1 = ws + 1 < g.Wi; ok2 = ws + 2 < g.Wi; ok3 = ws + 3 < g.Wi;
             dy_ok1 = 2 * tw + 1 < g.Wo;
         }
@@ -1378,15 +1388,15 @@ __global__ __launch_bounds__(256) void wino_fused_filter_kernel(FusedFilterParam
                 for (int r = 0; r < 4; ++r) {
                     const int hh = h0 + r;
                     const bool ok = live && c < g.Ci && (unsigned)hh < (unsigned)g.Hi;
-                    const uint32_t row = EB * (uint32_t)((c * g.Hi + hh) * g.Wi + 2 * tw);
+                    const uint32_t row = EB * (uint32_t)((c * g.Hi + hh) * g.Wi + 2 * tw) + x_slot;
                     vx[h][r] = ok ? row : kOob;
-                    vx[h][4 + r] = ok && PW == 1 && ptile == 0 && tw > 0 ? row - EB : kOob;
+                    vx[h][4 + r] = ok && PW == 1 && ptile % per_image == 0 && tw > 0 ? row - EB : kOob;
                 }
 #pragma unroll
                 for (int r = 0; r < 2; ++r) {
                     const int hh = 2 * th + r;
                     const bool ok = live && k < g.Co && hh < g.Ho;
-                    vd[h][r] = ok ? EB * (uint32_t)((k * g.Ho + hh) * g.Wo + 2 * tw) : kOob;
+                    vd[h][r] = ok ? EB * (uint32_t)((k * g.Ho + hh) * g.Wo + 2 * tw) + dy_slot : kOob;
                 }
             } else {
 #pragma unroll
@@ -1395,7 +1405,7 @@ __global__ __launch_bounds__(256) void wino_fused_filter_kernel(FusedFilterParam
                     for (int q = 0; q < 4; ++q) {
                         const int hh = h0 + r, ww = w0 + q;
                         const bool ok = live && c < g.Ci && (unsigned)hh < (unsigned)g.Hi && (unsigned)ww < (unsigned)g.Wi;
-                        vx[h][4 * r + q] = ok ? EB * (uint32_t)((c * g.Hi + hh) * g.Wi + ww) : kOob;
+                        vx[h][4 * r + q] = ok ? EB * (uint32_t)((c * g.Hi + hh) * g.Wi + ww) + x_slot : kOob;
                     }
 #pragma unroll
                 for (int r = 0; r < 2; ++r)
@@ -1403,7 +1413,7 @@ __global__ __launch_bounds__(256) void wino_fused_filter_kernel(FusedFilterParam
                     for (int q = 0; q < 2; ++q) {
                         const int hh = 2 * th + r, ww = 2 * tw + q;
                         const bool ok = live && k < g.Co && hh < g.Ho && ww < g.Wo;
-                        vd[h][2 * r + q] = ok ? EB * (uint32_t)((k * g.Ho + hh) * g.Wo + ww) : kOob;
+                        vd[h][2 * r + q] = ok ? EB * (uint32_t)((k * g.Ho + hh) * g.Wo + ww) + dy_slot : kOob;
                     }
             }
         }
@@ -1515,9 +1525,9 @@ __global__ __launch_bounds__(256) void wino_fused_filter_kernel(FusedFilterParam
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
 #pragma unroll
-        for (int i = 0; i < kXLoads; ++i) fetch_x(n_begin + 1, h, i);
+        for (int i = 0; i < kXLoads; ++i) fetch_x(n_begin + n_step, h, i);
 #pragma unroll
-        for (int i = 0; i < kDyLoads; ++i) fetch_dy(n_begin + 1, h, i);
+        for (int i = 0; i < kDyLoads; ++i) fetch_dy(n_begin + n_step, h, i);
     }
     __syncthreads();
 
@@ -1526,7 +1536,7 @@ __global__ __launch_bounds__(256) void wino_fused_filter_kernel(FusedFilterParam
     for (int q = 0; q < kFwPairs; ++q) col_q[q] = l32 ^ (4 * (2 * q + lhi));
 
     int buf = 0;
-    for (int n = n_begin; n < n_end; ++n) {
+    for (int n = n_begin; n < n_end; n += n_step) {
         // operands of (point xi, tile pair q): rows 2q + lhi of the point's slab (columns swizzled by
         // 4 (2q + lhi)), read one point ahead
         const float *da = &Ds[buf][0][lhi][wk * 32];
@@ -1555,12 +1565,12 @@ __global__ __launch_bounds__(256) void wino_fused_filter_kernel(FusedFilterParam
             if constexpr (m >= 1 && m < kDyStart) {                      // x patches: 2 x (transform + loads)
                 constexpr int h = (m - 1) / kXSlots, i = (m - 1) % kXSlots;
                 if constexpr (i == 0) store_v(buf ^ 1, h);
-                else fetch_x(n + 2, h, i - 1);
+                else fetch_x(n + 2 * n_step, h, i - 1);
             }
             if constexpr (m >= kDyStart && m < kDyStart + 2 * kDySlots) {  // dy tiles: 2 x (transform + loads)
                 constexpr int h = (m - kDyStart) / kDySlots, i = (m - kDyStart) % kDySlots;
                 if constexpr (i == 0) store_d(buf ^ 1, h);
-                else fetch_dy(n + 2, h, i - 1);
+                else fetch_dy(n + 2 * n_step, h, i - 1);
             }
             static_assert(kDyStart + 2 * kDySlots <= 16 * kFwPairs, "the step's work fits behind its MFMAs");
             __builtin_amdgcn_sched_barrier(0);
@@ -1599,6 +1609,8 @@ static hipError_t winograd_fused_filter_run(const Dims &d, int b, const void *x,
     p.x_bytes = xbytes(d, b); p.dy_bytes = ybytes(d, b);
     p.g = g; p.b = b;
     p.k_blocks = (d.K + 63) / 64; p.c_blocks = (d.C + 63) / 64; p.groups = (g.T + kFwT - 1) / kFwT;
+    const int left = g.T % kFwT;   // tiles in the last group
+    p.spread = b >= 8 && (left == 1 || left == 2 || left == 4) ? kFwT / left : 1;
     // image chunks: about four rounds of one workgroup per CU, chunks of at least 4 images; among the
     // counts near that, the one whose workgroup count fills its rounds of one workgroup per CU best
     const long items = (long)p.k_blocks * p.c_blocks * p.groups, cus = device_cus();
@@ -1612,12 +1624,16 @@ static hipError_t winograd_fused_filter_run(const Dims &d, int b, const void *x,
         if (fill > best + 1e-9) { best = fill; split = c; }
     }
     p.images_per_chunk = (int)((b + split - 1) / split);
+    // a chunk of the spread group must start at a step of its own: whole multiples of 8 images
+    if (p.spread > 1) p.images_per_chunk = (p.images_per_chunk + 7) / 8 * 8;
     p.n_split = (b + p.images_per_chunk - 1) / p.images_per_chunk;
     const unsigned blocks = (unsigned)(items * p.n_split);
     LaunchLog *log = launch_log();
     if (log) {
+        // tile slots multiplied per image: whole groups of 8, the last one shared by `spread` images
+        const double slots = p.spread > 1 ? (double)(p.groups - 1) * kFwT + (double)kFwT / p.spread : (double)p.groups * kFwT;
         log->add("wino_fused_filter_kernel blocks=" + std::to_string(blocks) + " gemm_flops=" +
-                 std::to_string(2.0 * 16 * d.K * (double)d.C * p.groups * kFwT * b));
+                 std::to_string(2.0 * 16 * d.K * (double)d.C * slots * b));
         log->add("wino_dw_kernel");
         return hipSuccess;
     }

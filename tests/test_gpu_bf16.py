@@ -34,10 +34,11 @@ SHAPES = [
     Shape(2, 96, 9, 9, 192, 3, 3, 1, 1, "c96k192"),
     Shape(3, 120, 7, 7, 136, 3, 3, 1, 1, "deep"),
     Shape(3, 5, 7, 7, 9, 3, 3, 1, 1, "odd-chw"),               # second micro-batch starts at an odd element: 2-byte aligned tensors
+    Shape(9, 20, 13, 13, 24, 3, 3, 1, 1, "t49-n9"),            # fused BackwardFilter with the last tile group spread over 8 images
     Shape(2, 5, 11, 14, 7, 3, 3, 1, 0, "pad0-3x3"),
     Shape(2, 5, 6, 9, 7, 3, 3, 1, 2, "pad2-3x3"),
 ]
-DIVISIONS = {8: [[8], [3, 5]], 5: [[5], [2, 3]], 4: [[4], [1, 3]], 3: [[3], [1, 2]], 2: [[2], [1, 1]]}
+DIVISIONS = {9: [[9], [1, 8]], 8: [[8], [3, 5]], 5: [[5], [2, 3]], 4: [[4], [1, 3]], 3: [[3], [1, 2]], 2: [[2], [1, 1]]}
 
 
 def bf16_inputs(s, seed):
