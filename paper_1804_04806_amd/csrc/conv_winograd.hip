@@ -1312,7 +1312,8 @@ struct FusedFilterParams {
     int b, k_blocks, c_blocks, groups, n_split, images_per_chunk;
     // The last tile-position group when the image leaves it 1, 2 or 4 tiles (49 tiles: 1): instead of
     // padding it to 8 positions, its 8 slots are those tiles of `spread` = 8, 4 or 2 consecutive images,
-    // and it takes `spread` images per step.  1: off (chunks are then multiples of 8 images otherwise).
+    // and it takes `spread` images per step.  1: off.  The workgroups of that group come after all others
+    // and take the whole micro-batch each (b / spread steps: shorter than a chunk of the others).
     int spread;
 };
 
@@ -1340,13 +1341,16 @@ __global__ __launch_bounds__(256) void wino_fused_filter_kernel(FusedFilterParam
     uint32_t v = xcd_order(blockIdx.x, gridDim.x);
     const int kb = (int)(v % (uint32_t)p.k_blocks); v /= (uint32_t)p.k_blocks;
     const int cb = (int)(v % (uint32_t)p.c_blocks); v /= (uint32_t)p.c_blocks;
-    const int grp = (int)(v % (uint32_t)p.groups);
-    const int chunk = (int)(v / (uint32_t)p.groups);
+    // chunked groups first (group fastest, then chunk), then the spread group's whole-batch workgroups
+    const int chunked = p.groups - (p.spread > 1 ? 1 : 0);
+    const bool whole = (int)v >= chunked * p.n_split;
+    const int grp = whole ? p.groups - 1 : (int)(v % (uint32_t)chunked);
+    const int chunk = whole ? 0 : (int)(v / (uint32_t)chunked);
     const int k0 = kb * 64, c0 = cb * 64;
-    const int n_begin = chunk * p.images_per_chunk, n_end = min(p.b, n_begin + p.images_per_chunk);
+    const int n_begin = whole ? 0 : chunk * p.images_per_chunk, n_end = whole ? p.b : min(p.b, n_begin + p.images_per_chunk);
     // images per step: 1, or for the last group `spread` (slot s = tile s % L of image s / L, L = 8 / spread;
     // slots of images past the batch read out of range, i.e. zeros)
-    const int n_step = p.spread > 1 && grp == p.groups - 1 ? p.spread : 1;
+    const int n_step = whole ? p.spread : 1;
 
     const __amdgpu_buffer_rsrc_t rx = make_rsrc_bytes(p.x, 0, p.x_bytes);
     const __amdgpu_buffer_rsrc_t rdy = make_rsrc_bytes(p.dy, 0, p.dy_bytes);
@@ -1611,23 +1615,26 @@ static hipError_t winograd_fused_filter_run(const Dims &d, int b, const void *x,
     p.k_blocks = (d.K + 63) / 64; p.c_blocks = (d.C + 63) / 64; p.groups = (g.T + kFwT - 1) / kFwT;
     const int left = g.T % kFwT;   // tiles in the last group
     p.spread = b >= 8 && (left == 1 || left == 2 || left == 4) ? kFwT / left : 1;
-    // image chunks: about four rounds of one workgroup per CU, chunks of at least 4 images; among the
-    // counts near that, the one whose workgroup count fills its rounds of one workgroup per CU best
-    const long items = (long)p.k_blocks * p.c_blocks * p.groups, cus = device_cus();
-    const long want = (4 * cus + items - 1) / items, cap = b / 4 < 1 ? 1 : b / 4;
-    long split = want > cap ? cap : want;
-    double best = -1.0;
-    for (long c = (want + 1) / 2; c <= 2 * want && c <= cap; ++c) {
-        const int per = (int)((b + c - 1) / c);
-        const long wgs = items * ((b + per - 1) / per);
-        const double fill = (double)wgs / (double)((wgs + cus - 1) / cus * cus);
-        if (fill > best + 1e-9) { best = fill; split = c; }
+    // image chunks (of all groups but a spread one).  A workgroup costs its steps plus about 11 steps' worth
+    // of start-up and of adding its 16 accumulator tiles into Mw (measured on 13x13 layers at two chunk
+    // sizes); the launch costs the rounds of one workgroup per CU times that.  The chunk count with the
+    // lowest such cost, chunks of at least 4 images.
+    const long per_group = (long)p.k_blocks * p.c_blocks, cus = device_cus();
+    const long items = per_group * (p.groups - (p.spread > 1 ? 1 : 0));
+    long split = 1;
+    if (items > 0) {
+        const long cap = b / 4 < 1 ? 1 : b / 4;
+        double best = 1e30;
+        for (long c = 1; c <= cap && c <= 64; ++c) {
+            const int per = (int)((b + c - 1) / c);
+            const long wgs = items * ((b + per - 1) / per) + (p.spread > 1 ? per_group : 0);
+            const double cost = (double)((wgs + cus - 1) / cus) * (per + 11.0);
+            if (cost < best - 1e-9) { best = cost; split = c; }
+        }
     }
     p.images_per_chunk = (int)((b + split - 1) / split);
-    // a chunk of the spread group must start at a step of its own: whole multiples of 8 images
-    if (p.spread > 1) p.images_per_chunk = (p.images_per_chunk + 7) / 8 * 8;
     p.n_split = (b + p.images_per_chunk - 1) / p.images_per_chunk;
-    const unsigned blocks = (unsigned)(items * p.n_split);
+    const unsigned blocks = (unsigned)(items * p.n_split + (p.spread > 1 ? per_group : 0));
     LaunchLog *log = launch_log();
     if (log) {
         // tile slots multiplied per image: whole groups of 8, the last one shared by `spread` images

@@ -742,17 +742,18 @@ hipError_t winograd5_fused_filter(const Dims &d, int b, const void *x, const voi
     p.k_blocks = wide ? (d.K + 127) / 128 : (d.K + 63) / 64;
     p.c_blocks = wide ? (d.C + 31) / 32 : (d.C + 63) / 64;
     p.groups = (g.T + kF5T - 1) / kF5T;
-    // image chunks: about four rounds of one workgroup per CU, chunks of at least 4 images; among the
-    // counts near that, the one whose workgroup count fills its rounds best
+    // image chunks: a workgroup costs its steps plus about 11 steps' worth of start-up and of adding its
+    // accumulator tiles into Mw, the launch the rounds of one workgroup per CU times that; the chunk count
+    // with the lowest such cost, chunks of at least 4 images
     const long items = (long)kW5Passes * p.k_blocks * p.c_blocks * p.groups, cus = device_cus();
-    const long want = (4 * cus + items - 1) / items, cap = b / 4 < 1 ? 1 : b / 4;
-    long split = want > cap ? cap : want;
-    double best = -1.0;
-    for (long c = (want + 1) / 2; c <= 2 * want && c <= cap; ++c) {
+    const long cap = b / 4 < 1 ? 1 : b / 4;
+    long split = 1;
+    double best = 1e30;
+    for (long c = 1; c <= cap && c <= 64; ++c) {
         const int per = (int)((b + c - 1) / c);
         const long wgs = items * ((b + per - 1) / per);
-        const double fill = (double)wgs / (double)((wgs + cus - 1) / cus * cus);
-        if (fill > best + 1e-9) { best = fill; split = c; }
+        const double cost = (double)((wgs + cus - 1) / cus) * (per + 11.0);
+        if (cost < best - 1e-9) { best = cost; split = c; }
     }
     p.images_per_chunk = (int)((b + split - 1) / split);
     const int n_split = (b + p.images_per_chunk - 1) / p.images_per_chunk;
