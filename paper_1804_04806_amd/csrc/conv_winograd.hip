@@ -864,6 +864,44 @@ __global__ __launch_bounds__(256) void wino_filter_bf16_kernel(const void *__res
     }
 }
 
+// The same for the output phases of a strided BackwardData (see wino_phase_filter_kernel): input channel k,
+// output channel co = (c*sh + pr)*sw + pc, taps g[i'][j'] = w[k, c, pr + sh*(2 - i'), pc + sw*(2 - j')]
+template <class E>
+__global__ __launch_bounds__(256) void wino_phase_filter_bf16_kernel(const void *__restrict__ w, uint16_t *__restrict__ U,
+                                                                     int K, int C, int R, int S, int sh, int sw, int Mo4,
+                                                                     int Cpad)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= Cpad * Mo4) return;
+    const int k = i / Mo4, co = i - k * Mo4;
+    const int c = co / (sh * sw), pr = co / sw % sh, pc = co % sw;
+    const bool live = k < K && c < C;
+    float t[4][3];  // G g, column by column
+#pragma unroll
+    for (int jj = 0; jj < 3; ++jj) {
+        float g[3], u[4];
+        const int ss = pc + sw * (2 - jj);
+#pragma unroll
+        for (int ii = 0; ii < 3; ++ii) {
+            const int rr = pr + sh * (2 - ii);
+            g[ii] = live && rr < R && ss < S ? Elem<E>::get(w, ((size_t)(k * C + c) * R + rr) * S + ss) : 0.f;
+        }
+        Wino<2>::filter(g, u);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) t[r][jj] = u[r];
+    }
+    const size_t plane = (size_t)Cpad * Mo4;
+    const size_t at = ((size_t)(k / 2) * Mo4 + co) * 2 + k % 2;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        float u[4];
+        Wino<2>::filter(t[r], u);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) U[(size_t)(r * 4 + q) * plane + at] = Elem<bf16>::round(u[q]);
+    }
+}
+
+template <bool PHASED>
 __global__ __launch_bounds__(512) void wino_fused_bf16_kernel(FusedBf16Params p)
 {
     typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -1109,6 +1147,17 @@ __global__ __launch_bounds__(512) void wino_fused_bf16_kernel(FusedBf16Params p)
         if (k >= g.Co) continue;
         const float y0 = mine[e][0] + xch[((2 * e) * 8 + other) * 64 + lane];
         const float y1 = mine[e][1] + xch[((2 * e + 1) * 8 + other) * 64 + lane];
+        if constexpr (PHASED) {
+            // channel k is (c, pr, pc): position (a, b) of the tile goes to dx[c, sh*a + pr - ph, sw*b + pc - pw]
+            const int c = k / (g.sh * g.sw), pr = k / g.sw % g.sh, pc = k % g.sw;
+            const int h = g.sh * ho + pr - g.oph;
+            if ((unsigned)h >= (unsigned)g.oh) continue;
+            const long row = (((long)n * g.oc + c) * g.oh + h) * g.ow;
+            const int wa = g.sw * wo + pc - g.opw, wb = wa + g.sw;
+            if ((unsigned)wa < (unsigned)g.ow) Elem<bf16>::store(p.out, row + wa, y0);
+            if (w1 && (unsigned)wb < (unsigned)g.ow) Elem<bf16>::store(p.out, row + wb, y1);
+            continue;
+        }
         const long base = (((long)n * g.Co + k) * g.Ho + ho) * g.Wo + wo;
         Elem<bf16>::store(p.out, base, y0);
         if (w1) Elem<bf16>::store(p.out, base + 1, y1);
@@ -1133,11 +1182,14 @@ static hipError_t winograd_fused_run(const Dims &d, int op, int b, const void *i
     // bf16 tensors: the kernel on the bf16 matrix pipe (UCD_FUSED_BF16_FP32=1 in the environment keeps the
     // fp32 products, for comparison); images of fewer than 4 pixels would break its address arithmetic
     static const bool bf16_fp32 = getenv("UCD_FUSED_BF16_FP32") != nullptr;
-    const bool bf16_pipe = std::is_same_v<E, bf16> && !phased && !bf16_fp32 && g.Hi * g.Wi >= 4;
+    const bool bf16_pipe = std::is_same_v<E, bf16> && !bf16_fp32 && g.Hi * g.Wi >= 4;
     const int ci_pad16 = (g.Ci + kBfC - 1) / kBfC * kBfC;
     if (filter_ready) {
         // U of this filter is still in the workspace from the previous micro-batch
     } else if (log) log->add(phased ? "wino_phase_filter_kernel" : bf16_pipe ? "wino_filter_bf16_kernel" : "wino_filter_kernel");
+    else if (bf16_pipe && phased)
+        wino_phase_filter_bf16_kernel<E><<<(unsigned)((ci_pad16 * g.Mo4 + 255) / 256), 256, 0, s>>>(
+            w, (uint16_t *)ws, d.K, d.C, d.R, d.S, d.sh, d.sw, g.Mo4, ci_pad16);
     else if (bf16_pipe)
         wino_filter_bf16_kernel<E><<<(unsigned)((ci_pad16 * g.Mo4 + 255) / 256), 256, 0, s>>>(
             w, (uint16_t *)ws, g.Ci, g.Co, g.Mo4, g.transposed ? 1 : 0, ci_pad16);
@@ -1162,11 +1214,12 @@ static hipError_t winograd_fused_run(const Dims &d, int op, int b, const void *i
         q.k_blocks = (g.Co + kFuK - 1) / kFuK;
         const unsigned nb = (unsigned)(q.k_blocks * ((q.n_tiles + kFuT - 1) / kFuT));
         if (log) {
-            log->add("wino_fused_bf16_kernel blocks=" + std::to_string(nb) + " gemm_flops=" +
+            log->add(std::string(phased ? "wino_fused_bf16_kernel<phases>" : "wino_fused_bf16_kernel") + " blocks=" + std::to_string(nb) + " gemm_flops=" +
                      std::to_string(2.0 * 16 * g.Co * (double)q.n_tiles * g.Ci));
             return hipSuccess;
         }
-        wino_fused_bf16_kernel<<<nb, 512, 0, s>>>(q);
+        if (phased) wino_fused_bf16_kernel<true><<<nb, 512, 0, s>>>(q);
+        else wino_fused_bf16_kernel<false><<<nb, 512, 0, s>>>(q);
         return hipGetLastError();
     }
     FusedParams p{};
