@@ -125,7 +125,15 @@ size_t ws_size(const ucd_layer_t *L, int op, int algo, int b)
     }
 }
 
-int hip_status(hipError_t e) { return e == hipSuccess ? UCD_OK : UCD_E_HIP; }
+// UCD_E_HIP carries no detail: with UCD_VERBOSE_ERRORS set in the environment the runtime's own text
+// for the error goes to stderr
+int hip_status(hipError_t e)
+{
+    if (e == hipSuccess) return UCD_OK;
+    static const bool verbose = getenv("UCD_VERBOSE_ERRORS") != nullptr;
+    if (verbose) fprintf(stderr, "ucd: HIP error %d: %s\n", (int)e, hipGetErrorString(e));
+    return UCD_E_HIP;
+}
 
 // One algorithm on one micro-batch.  (a, bsrc, out) = (x, w, y) | (dy, w, dx) | (x, dy, dw).
 int run_micro(const ucd_layer_t *L, int op, int algo, int b, const void *a, const void *bsrc, void *out,
@@ -136,6 +144,9 @@ int run_micro(const ucd_layer_t *L, int op, int algo, int b, const void *a, cons
     const uintptr_t emask = d.esize() - 1, omask = op == UCD_BWD_FILTER ? 3u : emask;
     if ((((uintptr_t)a | (uintptr_t)bsrc) & emask) != 0 || ((uintptr_t)out & omask) != 0) return UCD_E_INVALID;
     if ((algo != UCD_ALGO_IMPLICIT || d.det) && ((uintptr_t)ws & 15u) != 0) return UCD_E_INVALID;
+    // The launches below report failure through hipGetLastError, which also returns what an earlier,
+    // unrelated call of this thread left behind (a framework probing a feature at start-up, say): drop that.
+    (void)hipGetLastError();
     hipError_t e = hipErrorInvalidValue;
     switch (algo) {
     case UCD_ALGO_IMPLICIT:

@@ -469,7 +469,7 @@ __global__ __launch_bounds__(256) void wino_fused_kernel(FusedParams p)
     uint32_t voff[kRows ? 4 : 16];   // element-wise: one offset per pixel; rows: the window start of each row
     uint32_t xoff[4];                // rows, PW >= 1: the patch's first PW columns, fetched by lane 0 only
     bool first_col = false, ok1 = true, ok2 = true, ok3 = true;  // rows: tile column 0; window elements inside the row
-    bool ok0 = true, okm1 = true;    // PW = 2: the window's first element and the column before it
+    bool ok0 = true, okm1 = true, okm2 = true;   // PW = 2: the window's first element and the two columns before it
     {
         const int j = t0 + ptile;
         uint32_t n = 0, t, th = 0, tw = 0;
@@ -484,7 +484,7 @@ __global__ __launch_bounds__(256) void wino_fused_kernel(FusedParams p)
             const int ws = 2 * (int)tw;   // = w0 + PW
             first_col = tw == 0;
             ok1 = ws + 1 < g.Wi; ok2 = ws + 2 < g.Wi; ok3 = ws + 3 < g.Wi;
-            ok0 = ws < g.Wi; okm1 = ws - 1 < g.Wi;
+            ok0 = ws < g.Wi; okm1 = ws - 1 < g.Wi; okm2 = ws - 2 < g.Wi;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int h = h0 + r;
@@ -576,11 +576,14 @@ __global__ __launch_bounds__(256) void wino_fused_kernel(FusedParams p)
                     // Window = columns 2tw, 2tw+1 = patch columns 2, 3; the last tile column's window can
                     // lie past the row altogether.  Patch columns 0, 1 are the window of the tile to the
                     // left, already masked there (lane 0: its own load, whose second element can be past
-                    // the row when the width is odd); zeros in the first tile column.
+                    // the row when the width is odd, and both when the output is more than two columns
+                    // wider than the input, as the phase form of a strided BackwardData can be); zeros in
+                    // the first tile column.
                     d[h][4 * r + 2] = ok0 ? d[h][4 * r + 2] : 0.f;
                     d[h][4 * r + 3] = ok1 ? d[h][4 * r + 3] : 0.f;
+                    const float own0 = okm2 ? dx[h][2 * r] : 0.f;
                     const float own1 = okm1 ? dx[h][2 * r + 1] : 0.f;
-                    const int l0 = __builtin_amdgcn_update_dpp((int)__float_as_uint(dx[h][2 * r]),
+                    const int l0 = __builtin_amdgcn_update_dpp((int)__float_as_uint(own0),
                                                                (int)__float_as_uint(d[h][4 * r + 2]), kShr, 0xf, 0xf, false);
                     const int l1 = __builtin_amdgcn_update_dpp((int)__float_as_uint(own1),
                                                                (int)__float_as_uint(d[h][4 * r + 3]), kShr, 0xf, 0xf, false);

@@ -62,6 +62,10 @@ def lib():
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_1804_04806_amd.build`")
+        # The callers' tensors come from PyTorch, which ships a HIP runtime of its own: it has to be in the
+        # process before this library's, or the library binds to the system's copy and its launches then
+        # fail with "no ROCm-capable device is detected" next to a working torch.
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
         vp, sz, i, u64p, szp, ip = (ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int,
                                     ctypes.POINTER(ctypes.c_uint64), ctypes.POINTER(ctypes.c_size_t),

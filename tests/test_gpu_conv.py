@@ -51,12 +51,13 @@ SHAPES = [
     Shape(9, 20, 13, 13, 24, 3, 3, 1, 1, "t49-n9"),            # fused BackwardFilter: 49 tiles, the 49th of 8 images per step; 9 images
     Shape(9, 6, 4, 10, 7, 3, 3, 1, 1, "t10-n9"),               # 10 tiles: the last two of 4 images per step
     Shape(9, 6, 6, 8, 7, 3, 3, 1, 1, "t12-n9"),                # 12 tiles: the last four of 2 images per step
-    Shape(2, 3, 27, 29, 70, 11, 11, 4, 2, "conv1-pad2"),       # BackwardData as a 3x3 Winograd convolution over 16 phases
+    Shape(2, 3, 27, 29, 70, 11, 11, 4, 2, "conv1-pad2"),
+    Shape(11, 6, 26, 17, 72, 11, 11, 4, 0, "s4-unreached"),    # (W - S) % stride = 2: the phase grid is three columns wider than dy       # BackwardData as a 3x3 Winograd convolution over 16 phases
     Shape(3, 20, 15, 16, 24, 5, 5, 2, 2, "5x5-s2"),            # the same with 4 phases, 80 phase channels (two blocks)
     Shape(2, 4, 20, 22, 9, 7, 7, 3, 3, "7x7-s3"),              # 9 phases, the third tap past the filter's end in two of three
 ]
 
-DIVISIONS = {9: [[9], [1, 8]], 8: [[8], [1] * 8, [3, 5]], 5: [[5], [2, 3]], 4: [[4], [1, 3]], 3: [[3], [1, 2]],
+DIVISIONS = {11: [[11], [4, 7]], 9: [[9], [1, 8]], 8: [[8], [1] * 8, [3, 5]], 5: [[5], [2, 3]], 4: [[4], [1, 3]], 3: [[3], [1, 2]],
              2: [[2], [1, 1]], 1: [[1]]}
 
 
