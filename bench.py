@@ -46,13 +46,13 @@ WS_LIMIT = 64 << 20
 # `traffic` = this figure x the flops per launch of the step being timed: the planner does not
 # pick the same micro-batch sizes every run, and a kernel's traffic follows its size.
 MEASURED_TRAFFIC_BYTES_PER_FLOP = {
-    "wino_fused_kernel": 364.7e6 / 43.80e9,
-    "wino5_fused_kernel": 488.8e6 / 58.51e9,
-    "wino_fused_filter_kernel": 569.9e6 / 46.06e9,
+    "wino_fused_kernel": 313.0e6 / 37.52e9,
+    "wino5_fused_kernel": 735.6e6 / 87.77e9,
+    "wino_fused_filter_kernel": 569.6e6 / 46.04e9,
     "wino5_fused_filter_kernel": 913.4e6 / 90.6e9,
-    "wino_fused_kernel<phases>": 242.1e6 / 15.86e9,
-    "gemm_kernel<Tile<96x128>,PixelKLane<dy>,PixelKLane<x, no padding>,EpiAtomic>": 543.9e6 / 53.97e9,
-    "gemm_kernel<Tile<96x128>,KLane0,GatherNLane<no padding>,EpiNCHW>": 482.0e6 / 53.97e9,
+    "wino_fused_kernel<phases>": 475.1e6 / 31.38e9,
+    "gemm_kernel<Tile<96x128>,PixelKLane<dy>,PixelKLane<x, no padding>,EpiAtomic>": 545.6e6 / 53.97e9,
+    "gemm_kernel<Tile<96x128>,KLane0,GatherNLane<no padding>,EpiNCHW>": 242.9e6 / 26.99e9,
 }
 
 ALGO_IDS = {"implicit": 0, "im2col": 1, "winograd": 2, "winograd4": 3, "fft": 4, "winograd-fused": 5,
